@@ -1,0 +1,204 @@
+/*
+ * igconv - implicit-GEMM convolution forward for AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  It follows the problem statement of the paper
+ * "cuDNN: Efficient Primitives for Deep Learning" (arXiv 1410.0759): a host-callable
+ * C interface whose data lives on the GPU in user-controlled buffers (Section 2,
+ * 2.1), opaque tensor / filter descriptors with arbitrary per-dimension strides for
+ * tensors (Section 2.1), one convolution descriptor holding pad and stride
+ * (Section 2.1.1, Table 1), and a forward convolution computed as a lowered matrix
+ * product whose lowered data matrix only ever exists in on-chip memory, so that no
+ * auxiliary memory is needed (Section 3.1, 3.2).
+ *
+ * Conventions that hold for every entry point
+ *  - Every call returns an igcStatus; nothing throws across the ABI.  Output
+ *    arguments are written only when the call returns IGC_STATUS_SUCCESS.
+ *  - Handles and descriptors are HOST objects created and destroyed by the caller.
+ *    Descriptors are read at call time only: they may be changed or destroyed as
+ *    soon as a call returns.
+ *  - x, w and y are DEVICE pointers owned by the caller.  The library never
+ *    allocates, frees or copies device memory and needs no workspace.
+ *  - alpha and beta are HOST pointers to float (the compute type is fp32 for every
+ *    supported data type); they are read before the call returns.
+ *  - igcConvolutionForward only enqueues work on the handle's stream and returns.
+ *  - All argument validation happens before the first GPU call, so every
+ *    BAD_PARAM / NOT_SUPPORTED path can be exercised on a machine without a GPU.
+ *  - No global mutable state: use one handle per host thread; descriptors may be
+ *    shared between threads while nobody is setting them (Section 2.1).
+ */
+#ifndef IGCONV_H_
+#define IGCONV_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    IGC_STATUS_SUCCESS = 0,
+    IGC_STATUS_BAD_PARAM = 1,        /* null pointer, non-positive size, inconsistent descriptors */
+    IGC_STATUS_NOT_SUPPORTED = 2,    /* valid problem outside what the kernels cover */
+    IGC_STATUS_NOT_INITIALIZED = 3,  /* descriptor used before it was set */
+    IGC_STATUS_ALLOC_FAILED = 4,     /* host allocation of a handle/descriptor failed */
+    IGC_STATUS_EXECUTION_FAILED = 5  /* the GPU runtime reported an error at launch */
+} igcStatus;
+
+typedef enum {
+    IGC_DATA_FLOAT = 0,   /* IEEE binary32 */
+    IGC_DATA_BFLOAT16 = 1 /* upper 16 bits of a binary32 */
+} igcDataType;
+
+typedef enum {
+    IGC_CONVOLUTION = 0,      /* eq. 2: tap r reads row p*u + R-1-r - pad_h (filter inverted) */
+    IGC_CROSS_CORRELATION = 1 /* tap r reads row p*u + r - pad_h (Section 2.1.1, last paragraph) */
+} igcConvolutionMode;
+
+typedef struct igcContext *igcHandle_t;
+typedef struct igcTensorStruct *igcTensorDescriptor_t;
+typedef struct igcFilterStruct *igcFilterDescriptor_t;
+typedef struct igcConvolutionStruct *igcConvolutionDescriptor_t;
+
+/* Human-readable name of a status; never NULL; static storage. */
+const char *igcGetErrorString(igcStatus status);
+
+/* ---- handle (Section 2.1: "Overview and Handles") --------------------------------
+ * igcCreate allocates a host context bound to the default stream (NULL).  It makes
+ * no GPU call.  igcSetStream stores a hipStream_t (passed as void*) on which later
+ * igcConvolutionForward calls are enqueued; the caller keeps ownership of it. */
+igcStatus igcCreate(igcHandle_t *handle);
+igcStatus igcDestroy(igcHandle_t handle);
+igcStatus igcSetStream(igcHandle_t handle, void *hipStream);
+igcStatus igcGetStream(igcHandle_t handle, void **hipStream);
+
+/* ---- tensor descriptor (Section 2.1; strides: Section 2.1.1) ----------------------
+ * A 4-D tensor with logical dimensions n, c, h, w and one element stride per
+ * dimension.  Strides are in ELEMENTS, not bytes, and must be >= 0.  NCHW packed is
+ * (c*h*w, h*w, w, 1); NHWC ("interleaved feature maps") is (h*w*c, 1, w*c, c);
+ * pitched rows, channel slices and other views are expressed the same way. */
+igcStatus igcCreateTensorDescriptor(igcTensorDescriptor_t *desc);
+igcStatus igcDestroyTensorDescriptor(igcTensorDescriptor_t desc);
+igcStatus igcSetTensor4dDescriptor(igcTensorDescriptor_t desc, igcDataType dataType,
+                                   int n, int c, int h, int w,
+                                   long long nStride, long long cStride,
+                                   long long hStride, long long wStride);
+igcStatus igcGetTensor4dDescriptor(igcTensorDescriptor_t desc, igcDataType *dataType,
+                                   int *n, int *c, int *h, int *w,
+                                   long long *nStride, long long *cStride,
+                                   long long *hStride, long long *wStride);
+
+/* ---- filter descriptor (Section 2.1.1: F in R^{KCRS}) -----------------------------
+ * k output feature maps, c input feature maps, r rows, s columns; the buffer is
+ * packed in that order, s fastest. */
+igcStatus igcCreateFilterDescriptor(igcFilterDescriptor_t *desc);
+igcStatus igcDestroyFilterDescriptor(igcFilterDescriptor_t desc);
+igcStatus igcSetFilter4dDescriptor(igcFilterDescriptor_t desc, igcDataType dataType,
+                                   int k, int c, int r, int s);
+igcStatus igcGetFilter4dDescriptor(igcFilterDescriptor_t desc, igcDataType *dataType,
+                                   int *k, int *c, int *r, int *s);
+
+/* ---- convolution descriptor (Table 1: pad_h, pad_w, u, v) -------------------------
+ * pad_h / pad_w rows / columns of zeros on EACH side; u / v vertical / horizontal
+ * stride; mode picks eq. 2 or its cross-correlation variant.  pad >= 0, u,v >= 1. */
+igcStatus igcCreateConvolutionDescriptor(igcConvolutionDescriptor_t *desc);
+igcStatus igcDestroyConvolutionDescriptor(igcConvolutionDescriptor_t desc);
+igcStatus igcSetConvolution2dDescriptor(igcConvolutionDescriptor_t desc,
+                                        int pad_h, int pad_w, int u, int v,
+                                        igcConvolutionMode mode);
+igcStatus igcGetConvolution2dDescriptor(igcConvolutionDescriptor_t desc,
+                                        int *pad_h, int *pad_w, int *u, int *v,
+                                        igcConvolutionMode *mode);
+
+/* ---- output size (eq. 1) ----------------------------------------------------------
+ * n = x.n, k = w.k, p = ceil((H - R + 1 + 2 pad_h)/u), q likewise with W, S, v,
+ * pad_w.  BAD_PARAM if x.c != w.c or if p or q would be < 1. */
+igcStatus igcGetConvolution2dForwardOutputDim(igcConvolutionDescriptor_t convDesc,
+                                              igcTensorDescriptor_t xDesc,
+                                              igcFilterDescriptor_t wDesc,
+                                              int *n, int *k, int *p, int *q);
+
+/* ---- workspace query (Section 3: "no auxiliary memory") ---------------------------
+ * Validates the problem exactly as igcConvolutionForward does and always reports
+ * *sizeInBytes = 0. */
+igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle,
+                                                igcTensorDescriptor_t xDesc,
+                                                igcFilterDescriptor_t wDesc,
+                                                igcConvolutionDescriptor_t convDesc,
+                                                igcTensorDescriptor_t yDesc,
+                                                size_t *sizeInBytes);
+
+/* ---- forward convolution (eq. 3, Section 2.1.1; algorithm of Section 3.1) ---------
+ *
+ *   y[n,k,p,q] = alpha * sum_{c,r,s} w[k,c,r,s] * x0[n,c,hh,ww] + beta * y[n,k,p,q]
+ *
+ * with x0 = x extended by zeros, (hh, ww) given by the descriptor's mode, pad and
+ * stride.  Data types: (x, w, y) = (float, float, float) or (bfloat16, bfloat16,
+ * float); products are accumulated in fp32.
+ *
+ *  - x (device, read): laid out by xDesc.  w (device, read): packed K,C,R,S.
+ *    y (device, written; read only when *beta != 0): laid out by yDesc, whose
+ *    dimensions must equal igcGetConvolution2dForwardOutputDim's result.
+ *  - *beta == 0 makes y write-only: NaN or Inf already in y does not propagate.
+ *  - y must not overlap x or w.  x may have zero or overlapping strides; y's strides
+ *    must address every output element at a distinct location (else BAD_PARAM).
+ *  - workSpace / workSpaceSizeInBytes are accepted for interface symmetry and
+ *    ignored; NULL / 0 is fine.
+ *  - NOT_SUPPORTED: any other data-type combination, or a tensor whose largest byte
+ *    offset reaches 2^31.
+ *  - EXECUTION_FAILED: the kernel launch was rejected by the runtime.
+ *  - Results are deterministic run to run (fixed summation order, no atomics).
+ */
+igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
+                                igcTensorDescriptor_t xDesc, const void *x,
+                                igcFilterDescriptor_t wDesc, const void *w,
+                                igcConvolutionDescriptor_t convDesc,
+                                void *workSpace, size_t workSpaceSizeInBytes,
+                                const void *beta,
+                                igcTensorDescriptor_t yDesc, void *y);
+
+/* ---- introspection and tuning (host only; no GPU call) ----------------------------
+ * The launch plan the library derives for a problem: the tile of the lowered
+ * product O_m (K x NPQ) = F_m (K x CRS) . D_m (CRS x NPQ) each workgroup computes,
+ * the grid, and the number of reduction steps (Section 3.1: fixed-size sub-matrices
+ * read successively into on-chip memory). */
+typedef struct {
+    int kernelId;    /* index into the library's kernel table */
+    int tileM;       /* rows of O_m (output feature maps) per workgroup */
+    int tileN;       /* columns of O_m (output pixels n,p,q) per workgroup */
+    int tileK;       /* reduction elements (c,r,s) per step */
+    int gridX;       /* workgroups launched */
+    int kSteps;      /* ceil(CRS / tileK) */
+    int threads;     /* threads per workgroup */
+    int ldsBytes;    /* LDS per workgroup */
+    int swapOperands;/* 1 when lanes run along k in the epilogue (y's c-stride is 1) */
+    int vecFilterLoads; /* 1 when filter rows are fetched with 16-byte loads */
+} igcConvolutionForwardPlan;
+
+igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle,
+                                       igcTensorDescriptor_t xDesc,
+                                       igcFilterDescriptor_t wDesc,
+                                       igcConvolutionDescriptor_t convDesc,
+                                       igcTensorDescriptor_t yDesc,
+                                       igcConvolutionForwardPlan *plan);
+
+/* Number of kernels in the table and a short description ("f32 128x128x32 ...") of
+ * one of them; NULL for an id out of range. */
+int igcGetKernelCount(void);
+const char *igcGetKernelName(int kernelId);
+
+/* Force a kernel for later calls on this handle (-1 restores the heuristic).  A
+ * kernel that cannot run the problem (wrong data type) makes the forward call
+ * return NOT_SUPPORTED. */
+igcStatus igcSetKernelOverride(igcHandle_t handle, int kernelId);
+
+/* Division by a launch-time constant as multiply + shift (Section 3.1, last
+ * paragraph).  igcMagicDivisor computes (mul, shift) for a divisor 1 <= d < 2^31;
+ * igcMagicDivide evaluates floor(n / d) for 0 <= n < 2^31 exactly the way the
+ * kernels do: (umulhi(n, mul) + n) >> shift. */
+igcStatus igcMagicDivisor(unsigned int d, unsigned int *mul, unsigned int *shift);
+unsigned int igcMagicDivide(unsigned int n, unsigned int mul, unsigned int shift);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IGCONV_H_ */

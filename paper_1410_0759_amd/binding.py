@@ -1,0 +1,237 @@
+"""ctypes binding of the C ABI in ``include/igconv.h`` - same names, same arguments.
+
+Argument marshalling only.  ``lib()`` loads the in-tree ``libigconv.so`` and raises
+if it is absent (run ``python -c "import __graft_entry__ as g; g.build()"`` or
+``python paper_1410_0759_amd/build.py`` first); nothing here computes anything.
+"""
+import ctypes
+import os
+
+__all__ = [
+    "lib", "IgcError", "check",
+    "IGC_STATUS_SUCCESS", "IGC_STATUS_BAD_PARAM", "IGC_STATUS_NOT_SUPPORTED",
+    "IGC_STATUS_NOT_INITIALIZED", "IGC_STATUS_ALLOC_FAILED", "IGC_STATUS_EXECUTION_FAILED",
+    "IGC_DATA_FLOAT", "IGC_DATA_BFLOAT16", "IGC_CONVOLUTION", "IGC_CROSS_CORRELATION",
+    "igcConvolutionForwardPlan", "DECLARED_SYMBOLS",
+    "Handle", "TensorDescriptor", "FilterDescriptor", "ConvolutionDescriptor",
+    "get_output_dim", "get_workspace_size", "get_plan", "convolution_forward",
+    "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
+]
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libigconv.so")
+
+(IGC_STATUS_SUCCESS, IGC_STATUS_BAD_PARAM, IGC_STATUS_NOT_SUPPORTED,
+ IGC_STATUS_NOT_INITIALIZED, IGC_STATUS_ALLOC_FAILED, IGC_STATUS_EXECUTION_FAILED) = range(6)
+IGC_DATA_FLOAT, IGC_DATA_BFLOAT16 = 0, 1
+IGC_CONVOLUTION, IGC_CROSS_CORRELATION = 0, 1
+
+
+class igcConvolutionForwardPlan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "kernelId", "tileM", "tileN", "tileK", "gridX", "kSteps", "threads", "ldsBytes",
+        "swapOperands", "vecFilterLoads")]
+
+
+_vp, _i, _ll, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t
+_P = ctypes.POINTER
+
+# name -> (restype, argtypes): every symbol include/igconv.h declares
+DECLARED_SYMBOLS = {
+    "igcGetErrorString": (ctypes.c_char_p, [_i]),
+    "igcCreate": (_i, [_P(_vp)]),
+    "igcDestroy": (_i, [_vp]),
+    "igcSetStream": (_i, [_vp, _vp]),
+    "igcGetStream": (_i, [_vp, _P(_vp)]),
+    "igcCreateTensorDescriptor": (_i, [_P(_vp)]),
+    "igcDestroyTensorDescriptor": (_i, [_vp]),
+    "igcSetTensor4dDescriptor": (_i, [_vp, _i, _i, _i, _i, _i, _ll, _ll, _ll, _ll]),
+    "igcGetTensor4dDescriptor": (_i, [_vp, _P(_i), _P(_i), _P(_i), _P(_i), _P(_i),
+                                      _P(_ll), _P(_ll), _P(_ll), _P(_ll)]),
+    "igcCreateFilterDescriptor": (_i, [_P(_vp)]),
+    "igcDestroyFilterDescriptor": (_i, [_vp]),
+    "igcSetFilter4dDescriptor": (_i, [_vp, _i, _i, _i, _i, _i]),
+    "igcGetFilter4dDescriptor": (_i, [_vp, _P(_i), _P(_i), _P(_i), _P(_i), _P(_i)]),
+    "igcCreateConvolutionDescriptor": (_i, [_P(_vp)]),
+    "igcDestroyConvolutionDescriptor": (_i, [_vp]),
+    "igcSetConvolution2dDescriptor": (_i, [_vp, _i, _i, _i, _i, _i]),
+    "igcGetConvolution2dDescriptor": (_i, [_vp, _P(_i), _P(_i), _P(_i), _P(_i), _P(_i)]),
+    "igcGetConvolution2dForwardOutputDim": (_i, [_vp, _vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
+    "igcGetConvolutionForwardWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
+    "igcConvolutionForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
+    "igcGetKernelCount": (_i, []),
+    "igcGetKernelName": (ctypes.c_char_p, [_i]),
+    "igcSetKernelOverride": (_i, [_vp, _i]),
+    "igcMagicDivisor": (_i, [ctypes.c_uint, _P(ctypes.c_uint), _P(ctypes.c_uint)]),
+    "igcMagicDivide": (ctypes.c_uint, [ctypes.c_uint, ctypes.c_uint, ctypes.c_uint]),
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library with argument types set; raises if it is not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libigconv.so is not built (%s); build it with paper_1410_0759_amd/build.py. "
+                "There is no fallback path." % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in DECLARED_SYMBOLS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+class IgcError(RuntimeError):
+    def __init__(self, status, where=""):
+        self.status = status
+        name = lib().igcGetErrorString(status).decode()
+        super().__init__("%s%s" % (name, " in " + where if where else ""))
+
+
+def check(status, where=""):
+    if status != IGC_STATUS_SUCCESS:
+        raise IgcError(status, where)
+
+
+class _Owned:
+    _create = _destroy = None
+
+    def __init__(self):
+        self.ptr = _vp()
+        check(getattr(lib(), self._create)(ctypes.byref(self.ptr)), self._create)
+
+    def close(self):
+        if self.ptr:
+            getattr(lib(), self._destroy)(self.ptr)
+            self.ptr = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Handle(_Owned):
+    _create, _destroy = "igcCreate", "igcDestroy"
+
+    def set_stream(self, stream_ptr):
+        """``stream_ptr``: integer value of a hipStream_t (e.g. torch's ``cuda_stream``), 0 = default."""
+        check(lib().igcSetStream(self.ptr, _vp(stream_ptr)), "igcSetStream")
+
+    def get_stream(self):
+        out = _vp()
+        check(lib().igcGetStream(self.ptr, ctypes.byref(out)), "igcGetStream")
+        return out.value or 0
+
+    def set_kernel_override(self, kernel_id):
+        check(lib().igcSetKernelOverride(self.ptr, kernel_id), "igcSetKernelOverride")
+
+
+class TensorDescriptor(_Owned):
+    _create, _destroy = "igcCreateTensorDescriptor", "igcDestroyTensorDescriptor"
+
+    def set(self, dtype, n, c, h, w, strides):
+        check(lib().igcSetTensor4dDescriptor(self.ptr, dtype, n, c, h, w, *[int(s) for s in strides]),
+              "igcSetTensor4dDescriptor")
+        return self
+
+    def get(self):
+        dt, d = _i(), [_i() for _ in range(4)]
+        s = [_ll() for _ in range(4)]
+        check(lib().igcGetTensor4dDescriptor(self.ptr, ctypes.byref(dt), *[ctypes.byref(v) for v in d + s]),
+              "igcGetTensor4dDescriptor")
+        return dt.value, tuple(v.value for v in d), tuple(v.value for v in s)
+
+
+class FilterDescriptor(_Owned):
+    _create, _destroy = "igcCreateFilterDescriptor", "igcDestroyFilterDescriptor"
+
+    def set(self, dtype, k, c, r, s):
+        check(lib().igcSetFilter4dDescriptor(self.ptr, dtype, k, c, r, s), "igcSetFilter4dDescriptor")
+        return self
+
+    def get(self):
+        v = [_i() for _ in range(5)]
+        check(lib().igcGetFilter4dDescriptor(self.ptr, *[ctypes.byref(a) for a in v]), "igcGetFilter4dDescriptor")
+        return tuple(a.value for a in v)
+
+
+class ConvolutionDescriptor(_Owned):
+    _create, _destroy = "igcCreateConvolutionDescriptor", "igcDestroyConvolutionDescriptor"
+
+    def set(self, pad_h, pad_w, u, v, mode):
+        check(lib().igcSetConvolution2dDescriptor(self.ptr, pad_h, pad_w, u, v, mode),
+              "igcSetConvolution2dDescriptor")
+        return self
+
+    def get(self):
+        v = [_i() for _ in range(5)]
+        check(lib().igcGetConvolution2dDescriptor(self.ptr, *[ctypes.byref(a) for a in v]),
+              "igcGetConvolution2dDescriptor")
+        return tuple(a.value for a in v)
+
+
+def get_output_dim(conv, xdesc, wdesc):
+    v = [_i() for _ in range(4)]
+    check(lib().igcGetConvolution2dForwardOutputDim(conv.ptr, xdesc.ptr, wdesc.ptr, *[ctypes.byref(a) for a in v]),
+          "igcGetConvolution2dForwardOutputDim")
+    return tuple(a.value for a in v)
+
+
+def get_workspace_size(handle, xdesc, wdesc, conv, ydesc):
+    out = _sz(12345)
+    check(lib().igcGetConvolutionForwardWorkspaceSize(handle.ptr, xdesc.ptr, wdesc.ptr, conv.ptr, ydesc.ptr,
+                                                      ctypes.byref(out)), "igcGetConvolutionForwardWorkspaceSize")
+    return out.value
+
+
+def get_plan(handle, xdesc, wdesc, conv, ydesc):
+    plan = igcConvolutionForwardPlan()
+    check(lib().igcGetConvolutionForwardPlan(handle.ptr, xdesc.ptr, wdesc.ptr, conv.ptr, ydesc.ptr,
+                                             ctypes.byref(plan)), "igcGetConvolutionForwardPlan")
+    return plan
+
+
+def convolution_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, ydesc, y_ptr,
+                        workspace_ptr=0, workspace_bytes=0):
+    """igcConvolutionForward with device pointers given as integers; returns the status."""
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcConvolutionForward(
+        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr,
+        _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
+
+
+def kernel_names():
+    L = lib()
+    return [L.igcGetKernelName(i).decode() for i in range(L.igcGetKernelCount())]
+
+
+def magic_divisor(d):
+    mul, shift = ctypes.c_uint(), ctypes.c_uint()
+    check(lib().igcMagicDivisor(d, ctypes.byref(mul), ctypes.byref(shift)), "igcMagicDivisor")
+    return mul.value, shift.value
+
+
+def magic_divide(n, mul, shift):
+    return lib().igcMagicDivide(n, mul, shift)
+
+
+def tensor_descriptor_for(t, dtype=None):
+    """Descriptor for a logically-NCHW 4-D torch tensor or numpy array, read from its
+    shape and strides (any memory order)."""
+    if hasattr(t, "element_size"):  # torch
+        strides = t.stride()
+        is_bf16 = "bfloat16" in str(t.dtype)
+    else:  # numpy
+        strides = [s // t.itemsize for s in t.strides]
+        is_bf16 = False
+    if dtype is None:
+        dtype = IGC_DATA_BFLOAT16 if is_bf16 else IGC_DATA_FLOAT
+    n, c, h, w = t.shape
+    return TensorDescriptor().set(dtype, n, c, h, w, strides)

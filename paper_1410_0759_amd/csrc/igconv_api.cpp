@@ -1,0 +1,473 @@
+// Host part of the library: descriptors, validation, launch plan, C ABI.
+// All validation runs before the first GPU call, so every error path works on a
+// machine without a GPU.  See include/igconv.h for the contract of each entry point.
+#include "../../include/igconv.h"
+
+#include <stdint.h>
+#include <algorithm>
+#include <new>
+
+#include "igconv_kernel_table.h"
+#include "igconv_params.h"
+
+struct igcContext {
+    void *stream = nullptr;
+    int kernelOverride = -1;
+};
+
+struct igcTensorStruct {
+    bool set = false;
+    igcDataType dtype = IGC_DATA_FLOAT;
+    int dim[4] = {0, 0, 0, 0};           // n, c, h, w
+    long long stride[4] = {0, 0, 0, 0};  // elements
+};
+
+struct igcFilterStruct {
+    bool set = false;
+    igcDataType dtype = IGC_DATA_FLOAT;
+    int k = 0, c = 0, r = 0, s = 0;
+};
+
+struct igcConvolutionStruct {
+    bool set = false;
+    int pad_h = 0, pad_w = 0, u = 1, v = 1;
+    igcConvolutionMode mode = IGC_CROSS_CORRELATION;
+};
+
+namespace igc {
+
+// MI355X: 256 compute units; the tile heuristic balances workgroups over them.
+constexpr int kComputeUnits = 256;
+constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
+
+int kernel_count() { return kNumKernelsF32 + kNumKernelsBF16; }
+
+const KernelInfo *kernel_info(int id) {
+    if (id < 0 || id >= kernel_count()) return nullptr;
+    return id < kNumKernelsF32 ? &kKernelsF32[id] : &kKernelsBF16[id - kNumKernelsF32];
+}
+
+static bool magic_for(uint32_t d, Magic *m) {
+    if (d < 1u || d >= (1u << 31)) return false;
+    uint32_t shift = 0;
+    while ((1ull << shift) < d) ++shift;  // ceil(log2 d)
+    const unsigned __int128 one = 1;
+    const unsigned __int128 num = one << (32 + shift);
+    const unsigned __int128 q = (num + d - 1) / d;  // ceil(2^(32+shift) / d), in [2^32, 2^33)
+    m->mul = (uint32_t)(q - (one << 32));
+    m->shift = shift;
+    return true;
+}
+
+static int elem_size(igcDataType t) { return t == IGC_DATA_BFLOAT16 ? 2 : 4; }
+
+// eq. 1: ceil((H - R + 1 + 2 pad) / u); <= 0 when there is no output.
+static long long out_dim(long long H, long long R, long long u, long long pad) {
+    const long long num = H - R + 1 + 2 * pad;
+    if (num <= 0) return 0;
+    return (num + u - 1) / u;
+}
+
+// Elements spanned by a strided 4-D tensor: 1 + sum (dim-1)*stride.
+static long long extent(const int dim[4], const long long stride[4]) {
+    long long e = 1;
+    for (int i = 0; i < 4; ++i) e += (long long)(dim[i] - 1) * stride[i];
+    return e;
+}
+
+// True when every index tuple lands on its own element.  Sufficient test: with the
+// dimensions of size > 1 sorted by stride, each stride must step over everything
+// the smaller-stride dimensions span.
+static bool non_aliasing(const int dim[4], const long long stride[4]) {
+    int idx[4], n = 0;
+    for (int i = 0; i < 4; ++i)
+        if (dim[i] > 1) idx[n++] = i;
+    std::sort(idx, idx + n, [&](int a, int b) { return stride[a] < stride[b]; });
+    long long span = 1;  // elements covered so far
+    for (int t = 0; t < n; ++t) {
+        const int i = idx[t];
+        if (stride[i] < span) return false;
+        span += (long long)(dim[i] - 1) * stride[i];
+    }
+    return true;
+}
+
+struct Problem {
+    ConvKernelParams kp;
+    bool bf16;
+    int vec;  // elements per 16 bytes of input
+};
+
+// Everything igcConvolutionForward checks that does not need the data pointers.
+static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
+                          igcConvolutionDescriptor_t cv, igcTensorDescriptor_t y, Problem *out) {
+    if (!x || !w || !cv || !y) return IGC_STATUS_BAD_PARAM;
+    if (!x->set || !w->set || !cv->set || !y->set) return IGC_STATUS_NOT_INITIALIZED;
+    if (x->dim[1] != w->c) return IGC_STATUS_BAD_PARAM;
+    const long long P = out_dim(x->dim[2], w->r, cv->u, cv->pad_h);
+    const long long Q = out_dim(x->dim[3], w->s, cv->v, cv->pad_w);
+    if (P < 1 || Q < 1) return IGC_STATUS_BAD_PARAM;
+    if (y->dim[0] != x->dim[0] || y->dim[1] != w->k || y->dim[2] != P || y->dim[3] != Q)
+        return IGC_STATUS_BAD_PARAM;
+    if (!non_aliasing(y->dim, y->stride)) return IGC_STATUS_BAD_PARAM;
+
+    const bool f32 = x->dtype == IGC_DATA_FLOAT && w->dtype == IGC_DATA_FLOAT;
+    const bool b16 = x->dtype == IGC_DATA_BFLOAT16 && w->dtype == IGC_DATA_BFLOAT16;
+    if (!(f32 || b16) || y->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+
+    const int es = elem_size(x->dtype);
+    const long long xb = extent(x->dim, x->stride) * es;
+    const long long yb = extent(y->dim, y->stride) * 4;
+    const long long CRS = (long long)w->c * w->r * w->s;
+    const long long wb = (long long)w->k * CRS * es;
+    const long long NPQ = (long long)x->dim[0] * P * Q;
+    if (xb >= kMaxBytes || yb >= kMaxBytes || wb >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
+    // Index ranges the kernels decode with 32-bit magic division, and the reach of
+    // the padded window in x measured in bytes (offsets of border taps are formed
+    // before they are discarded).
+    if (NPQ >= (1ll << 30) || CRS >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
+    if (cv->pad_h >= (1 << 20) || cv->pad_w >= (1 << 20) || cv->u >= (1 << 20) || cv->v >= (1 << 20))
+        return IGC_STATUS_NOT_SUPPORTED;
+
+    if (out) {
+        ConvKernelParams &k = out->kp;
+        k = ConvKernelParams{};
+        k.x_bytes = (uint32_t)xb;
+        k.w_bytes = (uint32_t)wb;
+        k.y_bytes = (uint32_t)yb;
+        k.N = x->dim[0]; k.C = x->dim[1]; k.H = x->dim[2]; k.W = x->dim[3];
+        k.K = w->k; k.R = w->r; k.S = w->s; k.P = (int)P; k.Q = (int)Q;
+        k.pad_h = cv->pad_h; k.pad_w = cv->pad_w; k.u = cv->u; k.v = cv->v;
+        k.flip = cv->mode == IGC_CONVOLUTION ? 1 : 0;
+        k.CRS = (int)CRS; k.NPQ = (int)NPQ; k.PQ = (int)(P * Q); k.RS = w->r * w->s;
+        if (!magic_for((uint32_t)k.PQ, &k.mPQ) || !magic_for((uint32_t)k.Q, &k.mQ) ||
+            !magic_for((uint32_t)k.RS, &k.mRS) || !magic_for((uint32_t)k.S, &k.mS))
+            return IGC_STATUS_NOT_SUPPORTED;
+        k.xsN = (int)x->stride[0]; k.xsC = (int)x->stride[1]; k.xsH = (int)x->stride[2]; k.xsW = (int)x->stride[3];
+        k.ysN = (int)y->stride[0]; k.ysK = (int)y->stride[1]; k.ysP = (int)y->stride[2]; k.ysQ = (int)y->stride[3];
+        out->bf16 = b16;
+        out->vec = 16 / es;
+    }
+    return IGC_STATUS_SUCCESS;
+}
+
+// Relative cost of running the problem with one kernel variant: MFMA work of the
+// busiest compute unit (tiles are padded to full size and dealt round-robin), plus a
+// term for the per-step tile traffic that favours larger tiles.
+static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
+    const long long tm = (k.K + ki.BM - 1) / ki.BM;
+    const long long tn = (k.NPQ + ki.BN - 1) / ki.BN;
+    const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
+    const long long tiles = tm * tn;
+    const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
+    const double mfma = (double)ki.BM * ki.BN * ki.BK;
+    const double traffic = 48.0 * (ki.BM + ki.BN) * ki.BK;
+    return (double)rounds * steps * (mfma + traffic);
+}
+
+static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, int *id_out) {
+    const ConvKernelParams &k = pr.kp;
+    const bool can_vec = w_aligned && (k.CRS % pr.vec == 0);
+    // Lanes should run along y's unit-stride dimension in the epilogue.
+    const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
+    if (h->kernelOverride >= 0) {
+        const KernelInfo *ki = kernel_info(h->kernelOverride);
+        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec)) return IGC_STATUS_NOT_SUPPORTED;
+        *id_out = h->kernelOverride;
+        return IGC_STATUS_SUCCESS;
+    }
+    int best = -1;
+    double best_cost = 0;
+    for (int id = 0; id < kernel_count(); ++id) {
+        const KernelInfo &ki = *kernel_info(id);
+        if (ki.bf16 != pr.bf16 || ki.veca != can_vec) continue;
+        // a swap variant exists only for some tiles; never use one when not wanted
+        if (ki.swap != want_swap) continue;
+        const double c = plan_cost(ki, k);
+        if (best < 0 || c < best_cost) {
+            best = id;
+            best_cost = c;
+        }
+    }
+    if (best < 0) return IGC_STATUS_NOT_SUPPORTED;
+    *id_out = best;
+    return IGC_STATUS_SUCCESS;
+}
+
+static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan) {
+    const KernelInfo &ki = *kernel_info(id);
+    ConvKernelParams &k = pr->kp;
+    k.tilesM = (k.K + ki.BM - 1) / ki.BM;
+    k.tilesN = (k.NPQ + ki.BN - 1) / ki.BN;
+    // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
+    if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
+    if (plan) {
+        plan->kernelId = id;
+        plan->tileM = ki.BM;
+        plan->tileN = ki.BN;
+        plan->tileK = ki.BK;
+        plan->gridX = k.tilesM * k.tilesN;
+        plan->kSteps = (k.CRS + ki.BK - 1) / ki.BK;
+        plan->threads = ki.threads;
+        plan->ldsBytes = ki.ldsBytes;
+        plan->swapOperands = ki.swap ? 1 : 0;
+        plan->vecFilterLoads = ki.veca ? 1 : 0;
+    }
+    return IGC_STATUS_SUCCESS;
+}
+
+}  // namespace igc
+
+using namespace igc;
+
+extern "C" {
+
+const char *igcGetErrorString(igcStatus status) {
+    switch (status) {
+        case IGC_STATUS_SUCCESS: return "IGC_STATUS_SUCCESS";
+        case IGC_STATUS_BAD_PARAM: return "IGC_STATUS_BAD_PARAM";
+        case IGC_STATUS_NOT_SUPPORTED: return "IGC_STATUS_NOT_SUPPORTED";
+        case IGC_STATUS_NOT_INITIALIZED: return "IGC_STATUS_NOT_INITIALIZED";
+        case IGC_STATUS_ALLOC_FAILED: return "IGC_STATUS_ALLOC_FAILED";
+        case IGC_STATUS_EXECUTION_FAILED: return "IGC_STATUS_EXECUTION_FAILED";
+    }
+    return "IGC_STATUS_UNKNOWN";
+}
+
+igcStatus igcCreate(igcHandle_t *handle) {
+    if (!handle) return IGC_STATUS_BAD_PARAM;
+    igcContext *c = new (std::nothrow) igcContext;
+    if (!c) return IGC_STATUS_ALLOC_FAILED;
+    *handle = c;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcDestroy(igcHandle_t handle) {
+    if (!handle) return IGC_STATUS_BAD_PARAM;
+    delete handle;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcSetStream(igcHandle_t handle, void *hipStream) {
+    if (!handle) return IGC_STATUS_BAD_PARAM;
+    handle->stream = hipStream;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetStream(igcHandle_t handle, void **hipStream) {
+    if (!handle || !hipStream) return IGC_STATUS_BAD_PARAM;
+    *hipStream = handle->stream;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcCreateTensorDescriptor(igcTensorDescriptor_t *desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    igcTensorStruct *d = new (std::nothrow) igcTensorStruct;
+    if (!d) return IGC_STATUS_ALLOC_FAILED;
+    *desc = d;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcDestroyTensorDescriptor(igcTensorDescriptor_t desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    delete desc;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcSetTensor4dDescriptor(igcTensorDescriptor_t desc, igcDataType dataType, int n, int c, int h,
+                                   int w, long long nStride, long long cStride, long long hStride,
+                                   long long wStride) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16) return IGC_STATUS_BAD_PARAM;
+    if (n < 1 || c < 1 || h < 1 || w < 1) return IGC_STATUS_BAD_PARAM;
+    if (nStride < 0 || cStride < 0 || hStride < 0 || wStride < 0) return IGC_STATUS_BAD_PARAM;
+    const int dim[4] = {n, c, h, w};
+    const long long stride[4] = {nStride, cStride, hStride, wStride};
+    // keep the extent computable without overflow
+    for (int i = 0; i < 4; ++i)
+        if (stride[i] >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
+    desc->dtype = dataType;
+    for (int i = 0; i < 4; ++i) {
+        desc->dim[i] = dim[i];
+        desc->stride[i] = stride[i];
+    }
+    desc->set = true;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetTensor4dDescriptor(igcTensorDescriptor_t desc, igcDataType *dataType, int *n, int *c, int *h,
+                                   int *w, long long *nStride, long long *cStride, long long *hStride,
+                                   long long *wStride) {
+    if (!desc || !dataType || !n || !c || !h || !w || !nStride || !cStride || !hStride || !wStride)
+        return IGC_STATUS_BAD_PARAM;
+    if (!desc->set) return IGC_STATUS_NOT_INITIALIZED;
+    *dataType = desc->dtype;
+    *n = desc->dim[0]; *c = desc->dim[1]; *h = desc->dim[2]; *w = desc->dim[3];
+    *nStride = desc->stride[0]; *cStride = desc->stride[1]; *hStride = desc->stride[2]; *wStride = desc->stride[3];
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcCreateFilterDescriptor(igcFilterDescriptor_t *desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    igcFilterStruct *d = new (std::nothrow) igcFilterStruct;
+    if (!d) return IGC_STATUS_ALLOC_FAILED;
+    *desc = d;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcDestroyFilterDescriptor(igcFilterDescriptor_t desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    delete desc;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcSetFilter4dDescriptor(igcFilterDescriptor_t desc, igcDataType dataType, int k, int c, int r, int s) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16) return IGC_STATUS_BAD_PARAM;
+    if (k < 1 || c < 1 || r < 1 || s < 1) return IGC_STATUS_BAD_PARAM;
+    desc->dtype = dataType;
+    desc->k = k; desc->c = c; desc->r = r; desc->s = s;
+    desc->set = true;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetFilter4dDescriptor(igcFilterDescriptor_t desc, igcDataType *dataType, int *k, int *c, int *r, int *s) {
+    if (!desc || !dataType || !k || !c || !r || !s) return IGC_STATUS_BAD_PARAM;
+    if (!desc->set) return IGC_STATUS_NOT_INITIALIZED;
+    *dataType = desc->dtype;
+    *k = desc->k; *c = desc->c; *r = desc->r; *s = desc->s;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcCreateConvolutionDescriptor(igcConvolutionDescriptor_t *desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    igcConvolutionStruct *d = new (std::nothrow) igcConvolutionStruct;
+    if (!d) return IGC_STATUS_ALLOC_FAILED;
+    *desc = d;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcDestroyConvolutionDescriptor(igcConvolutionDescriptor_t desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    delete desc;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcSetConvolution2dDescriptor(igcConvolutionDescriptor_t desc, int pad_h, int pad_w, int u, int v,
+                                        igcConvolutionMode mode) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    if (pad_h < 0 || pad_w < 0 || u < 1 || v < 1) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_CONVOLUTION && mode != IGC_CROSS_CORRELATION) return IGC_STATUS_BAD_PARAM;
+    desc->pad_h = pad_h; desc->pad_w = pad_w; desc->u = u; desc->v = v;
+    desc->mode = mode;
+    desc->set = true;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolution2dDescriptor(igcConvolutionDescriptor_t desc, int *pad_h, int *pad_w, int *u, int *v,
+                                        igcConvolutionMode *mode) {
+    if (!desc || !pad_h || !pad_w || !u || !v || !mode) return IGC_STATUS_BAD_PARAM;
+    if (!desc->set) return IGC_STATUS_NOT_INITIALIZED;
+    *pad_h = desc->pad_h; *pad_w = desc->pad_w; *u = desc->u; *v = desc->v;
+    *mode = desc->mode;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolution2dForwardOutputDim(igcConvolutionDescriptor_t convDesc, igcTensorDescriptor_t xDesc,
+                                              igcFilterDescriptor_t wDesc, int *n, int *k, int *p, int *q) {
+    if (!convDesc || !xDesc || !wDesc || !n || !k || !p || !q) return IGC_STATUS_BAD_PARAM;
+    if (!convDesc->set || !xDesc->set || !wDesc->set) return IGC_STATUS_NOT_INITIALIZED;
+    if (xDesc->dim[1] != wDesc->c) return IGC_STATUS_BAD_PARAM;
+    const long long P = out_dim(xDesc->dim[2], wDesc->r, convDesc->u, convDesc->pad_h);
+    const long long Q = out_dim(xDesc->dim[3], wDesc->s, convDesc->v, convDesc->pad_w);
+    if (P < 1 || Q < 1 || P > 0x7fffffff || Q > 0x7fffffff) return IGC_STATUS_BAD_PARAM;
+    *n = xDesc->dim[0];
+    *k = wDesc->k;
+    *p = (int)P;
+    *q = (int)Q;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle, igcTensorDescriptor_t xDesc,
+                                                igcFilterDescriptor_t wDesc, igcConvolutionDescriptor_t convDesc,
+                                                igcTensorDescriptor_t yDesc, size_t *sizeInBytes) {
+    if (!handle || !sizeInBytes) return IGC_STATUS_BAD_PARAM;
+    const igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, nullptr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    *sizeInBytes = 0;  // the lowered matrix only ever exists in LDS
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle, igcTensorDescriptor_t xDesc, igcFilterDescriptor_t wDesc,
+                                       igcConvolutionDescriptor_t convDesc, igcTensorDescriptor_t yDesc,
+                                       igcConvolutionForwardPlan *plan) {
+    if (!handle || !plan) return IGC_STATUS_BAD_PARAM;
+    Problem pr;
+    igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int id = -1;
+    st = choose(handle, pr, /*w_aligned=*/true, &id);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    igcConvolutionForwardPlan tmp;
+    st = fill_plan(id, &pr, &tmp);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    *plan = tmp;
+    return IGC_STATUS_SUCCESS;
+}
+
+int igcGetKernelCount(void) { return kernel_count(); }
+
+const char *igcGetKernelName(int kernelId) {
+    const KernelInfo *ki = kernel_info(kernelId);
+    return ki ? ki->name : nullptr;
+}
+
+igcStatus igcSetKernelOverride(igcHandle_t handle, int kernelId) {
+    if (!handle) return IGC_STATUS_BAD_PARAM;
+    if (kernelId < -1 || kernelId >= kernel_count()) return IGC_STATUS_BAD_PARAM;
+    handle->kernelOverride = kernelId;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcMagicDivisor(unsigned int d, unsigned int *mul, unsigned int *shift) {
+    if (!mul || !shift) return IGC_STATUS_BAD_PARAM;
+    Magic m;
+    if (!magic_for(d, &m)) return IGC_STATUS_BAD_PARAM;
+    *mul = m.mul;
+    *shift = m.shift;
+    return IGC_STATUS_SUCCESS;
+}
+
+unsigned int igcMagicDivide(unsigned int n, unsigned int mul, unsigned int shift) {
+    const uint32_t hi = (uint32_t)(((uint64_t)n * (uint64_t)mul) >> 32);
+    return (hi + n) >> shift;
+}
+
+igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha, igcTensorDescriptor_t xDesc, const void *x,
+                                igcFilterDescriptor_t wDesc, const void *w, igcConvolutionDescriptor_t convDesc,
+                                void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
+                                igcTensorDescriptor_t yDesc, void *y) {
+    (void)workSpace;
+    (void)workSpaceSizeInBytes;
+    if (!handle || !alpha || !beta || !x || !w || !y) return IGC_STATUS_BAD_PARAM;
+    Problem pr;
+    igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const int es = pr.bf16 ? 2 : 4;
+    if ((uintptr_t)x % es || (uintptr_t)w % es || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    int id = -1;
+    st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, &id);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    igcConvolutionForwardPlan plan;
+    st = fill_plan(id, &pr, &plan);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    pr.kp.x = x;
+    pr.kp.w = w;
+    pr.kp.y = y;
+    pr.kp.alpha = *static_cast<const float *>(alpha);
+    pr.kp.beta = *static_cast<const float *>(beta);
+    const int err = kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream);
+    return err == 0 ? IGC_STATUS_SUCCESS : IGC_STATUS_EXECUTION_FAILED;
+}
+
+}  // extern "C"

@@ -1,0 +1,332 @@
+// Implicit-GEMM convolution forward kernel for gfx950 (CDNA4), generic over tensor
+// strides.  Paper, Section 3.1: the convolution is the matrix product
+//   O_m (K x NPQ) = F_m (K x CRS) . D_m (CRS x NPQ)
+// where D_m, the lowered input, is never stored in off-chip memory: each workgroup
+// forms BK x BN tiles of it in LDS straight from the input tensor, using the map
+// column j -> (n,p,q), row i -> (c,r,s) and the accessing function of eq. 2, and
+// feeds them with BM x BK tiles of F_m to an MFMA microkernel.  The next tiles are
+// fetched from HBM while the current ones are multiplied (two LDS stages).  The
+// epilogue applies alpha/beta and stores through y's strides (the "transposition
+// to the user's layout").
+//
+// Work split inside a 256-thread workgroup (4 wavefronts of 64):
+//  * gather of the D_m tile: lane = column j (coalesced along q for NCHW inputs),
+//    each wavefront owns a run of KPT consecutive reduction indices, so the
+//    (c,r,s) decode and the tap offset live in scalar registers;
+//  * the F_m tile is a contiguous read of filter rows;
+//  * MFMA: wave (wm, wn) owns a (BM/WM) x (BN/WN) block of the output tile, made of
+//    32x32 MFMA blocks (v_mfma_f32_32x32x2_f32 or v_mfma_f32_32x32x16_bf16).
+// LDS tiles are stored [row][k] with k contiguous and a row stride of BK plus 16
+// bytes: a lane reads 16 bytes of k for its row, which is bank-conflict free because
+// the stride is an odd multiple of 16 bytes.  Which k a lane feeds to which MFMA is
+// a free choice as long as both operands agree (the sum over k commutes).
+//
+// Every global access goes through a buffer descriptor limited to the tensor's
+// extent; an element that must read as zero (zero border of eq. 3, tile tails) is
+// requested at an out-of-range offset, which the hardware returns as 0.
+#ifndef IGCONV_KERNEL_HPP_
+#define IGCONV_KERNEL_HPP_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "igconv_params.h"
+
+namespace igc {
+
+using f32x16 = float __attribute__((ext_vector_type(16)));
+using f32x4 = float __attribute__((ext_vector_type(4)));
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+
+constexpr uint32_t kBufferWord3 = 0x00020000u;  // raw buffer, 32-bit data format
+constexpr uint32_t kOutOfRange = 0x80000000u;   // >= any extent this library accepts
+
+__device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
+    return (__umulhi(n, m.mul) + n) >> m.shift;
+}
+
+template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_>
+struct KernelConfig {
+    static constexpr bool BF16 = BF16_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr bool SWAP = SWAP_;  // lanes run along output channels in the epilogue
+    static constexpr bool VECA = VECA_;  // filter rows fetched with 16-byte loads
+    static constexpr int THREADS = 256;
+    static constexpr int ESIZE = BF16 ? 2 : 4;
+    static constexpr int VEC = 16 / ESIZE;           // elements per 16-byte LDS access
+    static constexpr int KG = 2 * VEC;               // reduction elements per k-group
+    static constexpr int LD = BK + VEC;              // LDS row stride in elements
+    static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
+    static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE;
+    static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
+    static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
+    static constexpr int CG = BN / 64;               // column groups of 64 lanes
+    static constexpr int KPARTS = 4 / CG;            // wavefronts sharing one column group
+    static constexpr int KPT = BK / KPARTS;          // reduction indices gathered per thread
+    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave blocks are 32x32 multiples");
+    static_assert(BN == 64 || BN == 128 || BN == 256, "column tile is 1, 2 or 4 wavefronts wide");
+    static_assert(BK % KG == 0 && KPT % VEC == 0, "k tile granularity");
+    static_assert(VECA ? (BM * (BK / VEC)) % THREADS == 0 : (BM * BK) % THREADS == 0, "filter tile split");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams p) {
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LD = Cfg::LD;
+    constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
+    constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
+    using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
+
+    __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
+    elem_t *const ldsA = lds;                       // [2][BM][LD]
+    elem_t *const ldsB = lds + 2 * Cfg::A_ELEMS;    // [2][BN][LD]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5;   // which half of the k-group this lane feeds
+    const int l32 = lane & 31;
+
+    // M tiles are adjacent in launch order so that workgroups sharing the same
+    // columns of D_m run at the same time.
+    const int tile_m = blockIdx.x % p.tilesM;
+    const int tile_n = blockIdx.x / p.tilesM;
+    const int m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
+    const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
+
+    // ---- gather role: this lane's column j -> (n,p,q) (loop invariant) ------------
+    const int cg = wave % Cfg::CG;
+    const int kpart = wave / Cfg::CG;
+    const int jl = cg * 64 + lane;
+    int h0, w0;
+    uint32_t colbase;  // element offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
+    {
+        const int j = n0 + jl;
+        const bool cv = j < p.NPQ;
+        const uint32_t jj = cv ? (uint32_t)j : 0u;
+        const uint32_t n = magic_div(jj, p.mPQ);
+        const uint32_t rem = jj - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        h0 = (int)pp * p.u - p.pad_h;
+        w0 = (int)qq * p.v - p.pad_w;
+        colbase = n * (uint32_t)p.xsN + (uint32_t)h0 * (uint32_t)p.xsH + (uint32_t)w0 * (uint32_t)p.xsW;
+        if (!cv) h0 = -0x40000000;  // no tap of a column beyond NPQ is ever in range
+    }
+
+    // ---- filter-tile role ----------------------------------------------------------
+    constexpr int A_PASSES = Cfg::VECA ? (BM * (BK / VEC)) / 256 : (BM * BK) / 256;
+    constexpr int A_ROWS_PER_PASS = Cfg::VECA ? 256 / (BK / VEC) : 256 / BK;
+    const int a_row = Cfg::VECA ? tid / (BK / VEC) : tid / BK;
+    const int a_kk = Cfg::VECA ? (tid % (BK / VEC)) * VEC : tid % BK;
+
+    u32x4 a_vec[Cfg::VECA ? A_PASSES : 1];
+    elem_t a_sca[Cfg::VECA ? 1 : A_PASSES];
+    elem_t b_val[KPT];
+
+    auto fetch = [&](int k0) {
+        // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.
+        const int i = k0 + a_kk;
+        const bool kin = i < p.CRS;
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
+            const uint32_t off = ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)i) * ES;
+            const uint32_t voff = (kin && row < p.K) ? off : kOutOfRange;
+            if constexpr (Cfg::VECA) {
+                a_vec[ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voff, 0, 0);
+            } else if constexpr (Cfg::BF16) {
+                a_sca[ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voff, 0, 0);
+            } else {
+                a_sca[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voff, 0, 0));
+            }
+        }
+        // D_m tile: reduction indices i0..i0+KPT-1 of this lane's column.  The decode
+        // i -> (c,r,s) is uniform over the wavefront.
+        const uint32_t i0 = (uint32_t)(k0 + kpart * KPT);
+        uint32_t c = magic_div(i0, p.mRS);
+        const uint32_t rs = i0 - c * (uint32_t)p.RS;
+        uint32_t r = magic_div(rs, p.mS);
+        uint32_t s = rs - r * (uint32_t)p.S;
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) {
+            // tap position inside the filter window (eq. 2 inverts it)
+            uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - s : s;
+            tr = ((int)c < p.C) ? tr : 0x20000000u;  // i >= CRS: never in range
+            const int hh = h0 + (int)tr;
+            const int ww = w0 + (int)ts;
+            const bool ok = (uint32_t)hh < (uint32_t)p.H && (uint32_t)ww < (uint32_t)p.W;
+            const uint32_t delta = c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW;
+            const uint32_t voff = ok ? (colbase + delta) * ES : kOutOfRange;
+            if constexpr (Cfg::BF16) {
+                b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
+            } else {
+                b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
+            }
+            if (++s == (uint32_t)p.S) {
+                s = 0;
+                if (++r == (uint32_t)p.R) {
+                    r = 0;
+                    ++c;
+                }
+            }
+        }
+    };
+
+    auto stage = [&](int buf) {
+        elem_t *const A = ldsA + buf * Cfg::A_ELEMS;
+        elem_t *const B = ldsB + buf * Cfg::B_ELEMS;
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int row = a_row + ps * A_ROWS_PER_PASS;
+            if constexpr (Cfg::VECA) {
+                *reinterpret_cast<u32x4 *>(A + row * LD + a_kk) = a_vec[ps];
+            } else {
+                A[row * LD + a_kk] = a_sca[ps];
+            }
+        }
+        elem_t *const dst = B + jl * LD + kpart * KPT;
+#pragma unroll
+        for (int e = 0; e < KPT; e += VEC) {
+            u32x4 v;
+            if constexpr (Cfg::BF16) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+                    v[d] = (uint32_t)b_val[e + 2 * d] | ((uint32_t)b_val[e + 2 * d + 1] << 16);
+            } else {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) v[d] = __builtin_bit_cast(uint32_t, b_val[e + d]);
+            }
+            *reinterpret_cast<u32x4 *>(dst + e) = v;
+        }
+    };
+
+    // ---- MFMA role -------------------------------------------------------------------
+    const int wm = wave % Cfg::WM;
+    const int wn = wave / Cfg::WM;
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+
+    auto multiply = [&](int buf) {
+        const elem_t *const A = ldsA + buf * Cfg::A_ELEMS + (wm * Cfg::TM + l32) * LD + half * VEC;
+        const elem_t *const B = ldsB + buf * Cfg::B_ELEMS + (wn * Cfg::TN + l32) * LD + half * VEC;
+#pragma unroll
+        for (int g = 0; g < BK / KG; ++g) {
+            u32x4 af[MB], bfr[NB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                af[mb] = *reinterpret_cast<const u32x4 *>(A + mb * 32 * LD + g * KG);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                bfr[nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD + g * KG);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    if constexpr (Cfg::BF16) {
+                        const bf16x8 fa = __builtin_bit_cast(bf16x8, af[mb]);
+                        const bf16x8 fb = __builtin_bit_cast(bf16x8, bfr[nb]);
+                        if constexpr (Cfg::SWAP)
+                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[mb][nb], 0, 0, 0);
+                        else
+                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[mb][nb], 0, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float fa = __builtin_bit_cast(float, af[mb][e]);
+                            const float fb = __builtin_bit_cast(float, bfr[nb][e]);
+                            if constexpr (Cfg::SWAP)
+                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb, fa, acc[mb][nb], 0, 0, 0);
+                            else
+                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc[mb][nb], 0, 0, 0);
+                        }
+                    }
+                }
+        }
+    };
+
+    // ---- main loop: fetch step t+1 from HBM while step t is multiplied -----------------
+    const int ksteps = (p.CRS + BK - 1) / BK;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int t = 0; t < ksteps; ++t) {
+        const bool more = t + 1 < ksteps;
+        if (more) fetch((t + 1) * BK);
+        multiply(t & 1);
+        if (more) stage((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: alpha/beta, store through y's strides ---------------------------------
+    // A 32x32 MFMA result block keeps, in lane l, register v, the element
+    //   (row 8*(v/4) + 4*(l/32) + v%4, column l%32).
+    // Without SWAP rows are output channels and columns are pixels; with SWAP the
+    // operands were exchanged, so columns (lanes) are channels and rows are pixels.
+    const bool use_beta = p.beta != 0.f;
+    auto pixel_offset = [&](int j, bool &valid) -> uint32_t {
+        valid = j < p.NPQ;
+        const uint32_t jj = valid ? (uint32_t)j : 0u;
+        const uint32_t n = magic_div(jj, p.mPQ);
+        const uint32_t rem = jj - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        return n * (uint32_t)p.ysN + pp * (uint32_t)p.ysP + qq * (uint32_t)p.ysQ;
+    };
+    auto emit = [&](float a, uint32_t off, bool valid) {
+        const uint32_t voff = valid ? off * 4u : kOutOfRange;
+        float out = p.alpha * a;
+        if (use_beta) {
+            const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, voff, 0, 0));
+            out += p.beta * old;
+        }
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, voff, 0, 0);
+    };
+    if constexpr (!Cfg::SWAP) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            bool pv;
+            const uint32_t poff = pixel_offset(n0 + wn * Cfg::TN + nb * 32 + l32, pv);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = m0 + wm * Cfg::TM + mb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                    emit(acc[mb][nb][v], poff + (uint32_t)k * (uint32_t)p.ysK, pv && k < p.K);
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int k = m0 + wm * Cfg::TM + mb * 32 + l32;
+            const bool kv = k < p.K;
+            const uint32_t koff = (uint32_t)k * (uint32_t)p.ysK;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    bool pv;
+                    const uint32_t poff = pixel_offset(n0 + wn * Cfg::TN + nb * 32 + 8 * (v / 4) + 4 * half + (v % 4), pv);
+                    emit(acc[mb][nb][v], poff + koff, pv && kv);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace igc
+#endif

@@ -1,0 +1,31 @@
+// Table of compiled kernel variants and the host-side launcher.  Internal.
+#ifndef IGCONV_KERNEL_TABLE_H_
+#define IGCONV_KERNEL_TABLE_H_
+
+#include "igconv_params.h"
+
+namespace igc {
+
+struct KernelInfo {
+    const char *name;
+    bool bf16;      // input data type: bfloat16 (else float)
+    int BM, BN, BK; // tile of O_m per workgroup and reduction elements per step
+    bool swap;      // lanes run along output channels in the epilogue
+    bool veca;      // filter rows fetched with 16-byte loads (needs CRS % VEC == 0, aligned w)
+    int threads;
+    int ldsBytes;
+    // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
+    int (*launch)(const ConvKernelParams &, int grid, void *stream);
+};
+
+// Defined one per translation unit of kernel instantiations.
+extern const KernelInfo kKernelsF32[];
+extern const int kNumKernelsF32;
+extern const KernelInfo kKernelsBF16[];
+extern const int kNumKernelsBF16;
+
+int kernel_count();
+const KernelInfo *kernel_info(int id);  // nullptr when out of range
+
+}  // namespace igc
+#endif

@@ -1,0 +1,35 @@
+// Launch-time constants handed from the host part of the library to the kernels.
+// Internal to the library (not part of the C ABI).
+#ifndef IGCONV_PARAMS_H_
+#define IGCONV_PARAMS_H_
+
+#include <stdint.h>
+
+namespace igc {
+
+// floor(n / d) for 0 <= n < 2^31 as (umulhi(n, mul) + n) >> shift: division by a
+// launch-time constant turned into multiply + shift (paper, Section 3.1, last
+// paragraph).  shift = ceil(log2 d), mul = ceil(2^(32+shift) / d) - 2^32.
+struct Magic {
+    uint32_t mul;
+    uint32_t shift;
+};
+
+struct ConvKernelParams {
+    const void *x;   // input tensor D (device)
+    const void *w;   // filters F, packed K,C,R,S (device)
+    void *y;         // output tensor O (device)
+    uint32_t x_bytes, w_bytes, y_bytes;  // extents, used as buffer-descriptor limits
+    int32_t N, C, H, W, K, R, S, P, Q;
+    int32_t pad_h, pad_w, u, v;
+    int32_t flip;    // 1: eq. 2 (tap r reads row R-1-r), 0: cross-correlation
+    int32_t CRS, NPQ, PQ, RS;
+    Magic mPQ, mQ, mRS, mS;
+    int32_t xsN, xsC, xsH, xsW;  // element strides of x
+    int32_t ysN, ysK, ysP, ysQ;  // element strides of y
+    float alpha, beta;
+    int32_t tilesM, tilesN;
+};
+
+}  // namespace igc
+#endif

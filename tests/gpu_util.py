@@ -1,0 +1,117 @@
+"""Helpers for the GPU tests: run the HIP library on numpy inputs through its C ABI.
+
+PyTorch is used for device memory and streams only.  Output buffers are surrounded by
+guard bands so that a store outside y's extent is caught.
+"""
+import numpy as np
+import torch
+
+import paper_1410_0759_amd as ig
+
+GUARD = 4096          # elements of guard band before and after y
+GUARD_VALUE = 777.25
+
+
+def elem_strides(a):
+    return [s // a.itemsize for s in a.strides]
+
+
+def extent(shape, strides):
+    return 1 + sum((d - 1) * s for d, s in zip(shape, strides))
+
+
+def to_device_strided(a, dtype):
+    """Copy a (possibly strided) numpy array's memory span to the GPU; returns
+    (tensor holding the span, element strides).  bf16: values must be representable."""
+    strides = elem_strides(a)
+    n = extent(a.shape, strides)
+    flat = np.lib.stride_tricks.as_strided(a, shape=(n,), strides=(a.itemsize,))
+    t = torch.from_numpy(np.ascontiguousarray(flat))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+        assert torch.equal(t.float(), torch.from_numpy(np.ascontiguousarray(flat)))
+    return t.cuda(), strides
+
+
+class GpuConv:
+    """One problem set up on the GPU through the C ABI."""
+
+    def __init__(self, x, w, pad, stride, mode, dtype="f32", y_layout="NCHW", y_strides=None,
+                 y_extent=None, handle=None):
+        self.handle = handle or ig.Handle()
+        N, C, H, W = x.shape
+        K, _, R, S = w.shape
+        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        self.x_dev, xs = to_device_strided(x, dtype)
+        self.w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
+        self.xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
+        self.wdesc = ig.FilterDescriptor().set(dt, K, C, R, S)
+        self.conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+        n, k, p, q = ig.get_output_dim(self.conv, self.xdesc, self.wdesc)
+        self.yshape = (n, k, p, q)
+        if y_strides is None:
+            if y_layout == "NCHW":
+                y_strides = (k * p * q, p * q, q, 1)
+            elif y_layout == "NHWC":
+                y_strides = (p * q * k, 1, q * k, k)
+            else:
+                raise ValueError(y_layout)
+        self.ystrides = tuple(y_strides)
+        self.yext = y_extent or extent(self.yshape, self.ystrides)
+        self.ydesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, n, k, p, q, self.ystrides)
+        self.ybuf = torch.full((self.yext + 2 * GUARD,), GUARD_VALUE, dtype=torch.float32, device="cuda")
+        self.flops = 2 * n * k * p * q * C * R * S
+
+    @property
+    def y_ptr(self):
+        return self.ybuf.data_ptr() + 4 * GUARD
+
+    def y_view(self):
+        """Logical (N,K,P,Q) view of the device output."""
+        return torch.as_strided(self.ybuf, self.yshape, self.ystrides, storage_offset=GUARD)
+
+    def prefill(self, y0=None, value=None):
+        inner = self.ybuf[GUARD:GUARD + self.yext]
+        if y0 is not None:
+            inner.fill_(float("nan"))
+            self.y_view().copy_(torch.from_numpy(np.ascontiguousarray(y0)).cuda())
+        else:
+            inner.fill_(value)
+
+    def plan(self):
+        return ig.get_plan(self.handle, self.xdesc, self.wdesc, self.conv, self.ydesc)
+
+    def launch(self, alpha=1.0, beta=0.0):
+        self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
+        st = ig.convolution_forward(self.handle, alpha, self.xdesc, self.x_dev.data_ptr(), self.wdesc,
+                                    self.w_dev.data_ptr(), self.conv, beta, self.ydesc, self.y_ptr)
+        ig.check(st, "igcConvolutionForward")
+
+    def result(self):
+        torch.cuda.synchronize()
+        g = self.ybuf.cpu().numpy()
+        assert np.all(g[:GUARD] == GUARD_VALUE) and np.all(g[GUARD + self.yext:] == GUARD_VALUE), \
+            "store outside y's extent"
+        return self.y_view().cpu().numpy().astype(np.float64)
+
+
+def run(x, w, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0, y0=None,
+        dtype="f32", y_layout="NCHW", kernel=None):
+    """One forward call; returns (y as float64 logical NCHW, plan)."""
+    g = GpuConv(x, w, pad, stride, mode, dtype=dtype, y_layout=y_layout)
+    if kernel is not None:
+        g.handle.set_kernel_override(kernel)
+    if y0 is not None:
+        g.prefill(y0=y0)
+    else:
+        g.prefill(value=float("nan"))   # beta == 0 must overwrite, never read
+    g.launch(alpha, beta)
+    return g.result(), g.plan()
+
+
+def rel_err(got, want):
+    """The parity measure: max|got - want| / max|want|."""
+    return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
+
+
+TOL = {"f32": 2e-5, "bf16": 1e-2}

@@ -1,0 +1,201 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Bar: max|gpu - oracle| / max|oracle| <= 2e-5 for
+fp32 and <= 1e-2 for bf16 inputs (the oracle consumes the already-rounded bf16 values).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import workloads as wl
+from oracle import conv_oracle as oc
+
+
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _check(x, w, pad, stride, mode, dtype, alpha=1.0, beta=0.0, y0=None, y_layout="NCHW", kernel=None,
+           tag=""):
+    gu = _gpu()
+    print("case", tag, x.shape, w.shape, pad, stride, mode, dtype, alpha, beta, y_layout, "kernel", kernel,
+          flush=True)
+    got, plan = gu.run(x, w, pad, stride, mode, alpha, beta, y0, dtype, y_layout, kernel)
+    want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode, alpha=alpha, beta=beta, y_old=y0)
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got)), "non-finite output (NaN prefill leaked or garbage)"
+    err = gu.rel_err(got, want)
+    assert err <= gu.TOL[dtype], "rel err %.3g > %.3g (kernel %d)" % (err, gu.TOL[dtype], plan.kernelId)
+    return err, plan
+
+
+# ------------------------------------------------------------------ small sweep, heuristic kernel choice
+SWEEP = [
+    # N, C, H, W, K, R, S, pad, stride
+    (1, 1, 5, 5, 1, 1, 1, (0, 0), (1, 1)),
+    (2, 3, 9, 11, 5, 3, 3, (1, 1), (1, 1)),
+    (3, 5, 17, 19, 37, 3, 2, (1, 0), (1, 1)),
+    (2, 4, 23, 21, 70, 5, 5, (2, 2), (2, 2)),
+    (1, 3, 35, 35, 96, 11, 11, (0, 0), (4, 4)),
+    (2, 7, 12, 40, 33, 1, 7, (0, 3), (1, 3)),
+    (5, 9, 13, 13, 130, 3, 3, (1, 1), (1, 1)),
+    (2, 2, 8, 8, 4, 4, 4, (3, 3), (1, 1)),      # "full" padding
+    (1, 6, 30, 7, 20, 7, 1, (3, 0), (2, 1)),
+    (4, 16, 14, 14, 64, 3, 3, (1, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SWEEP, ids=[str(i) for i in range(len(SWEEP))])
+def test_small_sweep(shape, dtype, mode):
+    N, C, H, W, K, R, S, pad, stride = shape
+    x, w = wl.random_problem(1000 + hash(shape) % 1000, N, C, H, W, K, R, S, dtype=dtype)
+    _check(x, w, pad, stride, mode, dtype, tag="sweep")
+
+
+# ------------------------------------------------------------------ every kernel in the table
+def _kernel_cases():
+    # (dtype, needs CRS % vec == 0)
+    import paper_1410_0759_amd as ig
+    out = []
+    for kid, name in enumerate(ig.kernel_names()):
+        out.append((kid, name))
+    return out
+
+
+def test_every_kernel_variant():
+    """Each kernel of the table, forced, on problems with tails in every GEMM dimension
+    (K not a tile multiple, NPQ ragged, CRS not a multiple of the k tile)."""
+    import paper_1410_0759_amd as ig
+    for kid, name in _kernel_cases():
+        dtype = "bf16" if name.startswith("bf16") else "f32"
+        vec = "vecw" in name
+        swap = "swap" in name
+        vecn = 8 if dtype == "bf16" else 4
+        for (N, C, H, W, K, R, S, pad, stride) in [
+            (3, 8 if vec else 5, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
+            (2, 16 if vec else 3, 21, 9, 45, 2, 2 if vec else 3, (0, 1), (2, 1)),
+        ]:
+            if vec:
+                assert (C * R * S) % vecn == 0
+            x, w = wl.random_problem(7 + kid, N, C, H, W, K, R, S, dtype=dtype)
+            y0 = np.random.default_rng(kid).uniform(-1, 1, size=(N, K, (H + 2 * pad[0] - R) // stride[0] + 1,
+                                                                 (W + 2 * pad[1] - S) // stride[1] + 1)).astype(np.float32)
+            lay = "NHWC" if swap else "NCHW"
+            _, plan = _check(x, w, pad, stride, 1, dtype, kernel=kid, y_layout=lay, tag=name)
+            assert plan.kernelId == kid
+            _check(x, w, pad, stride, 0, dtype, alpha=0.5, beta=-1.5, y0=y0, kernel=kid, y_layout=lay, tag=name)
+
+
+# ------------------------------------------------------------------ layouts through strides
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("x_layout,y_layout", [("NCHW", "NCHW"), ("NHWC", "NHWC"), ("NHWC", "NCHW"),
+                                               ("NCHW", "NHWC")])
+def test_layouts(x_layout, y_layout, dtype):
+    x, w = wl.random_problem(31, 3, 24, 10, 9, 40, 3, 3, x_layout=x_layout, dtype=dtype)
+    _check(x, w, (1, 1), (1, 1), 1, dtype, y_layout=y_layout, tag="layout")
+
+
+def test_pitched_and_sliced_views():
+    """Sub-section indexing: x is a channel slice of a wider, row-padded buffer."""
+    rng = np.random.default_rng(5)
+    big = rng.uniform(-1, 1, size=(2, 9, 12, 20)).astype(np.float32)
+    x = big[:, 2:7, :, 3:16]      # channels 2..6, columns 3..15, pitch 20
+    w = rng.standard_normal((12, 5, 3, 3)).astype(np.float32) * 0.2
+    _check(x, w, (1, 1), (1, 1), 1, "f32", tag="view")
+    _check(x, w, (0, 2), (2, 1), 0, "f32", tag="view")
+
+
+def test_group_convolution_by_slices():
+    """Group convolution as several calls on channel slices (what the framework layer does)."""
+    gu = _gpu()
+    rng = np.random.default_rng(6)
+    x = rng.uniform(-1, 1, size=(2, 8, 10, 10)).astype(np.float32)
+    w = rng.standard_normal((6, 4, 3, 3)).astype(np.float32) * 0.2   # 2 groups of 4 channels -> 3 filters
+    for g in range(2):
+        xg = x[:, 4 * g:4 * g + 4]
+        wg = w[3 * g:3 * g + 3]
+        _check(xg, wg, (1, 1), (1, 1), 1, "f32", tag="group")
+
+
+def test_alpha_beta_and_nan_prefill():
+    x, w = wl.random_problem(41, 2, 6, 12, 12, 20, 3, 3)
+    y0 = np.random.default_rng(42).uniform(-1, 1, size=(2, 20, 12, 12)).astype(np.float32)
+    _check(x, w, (1, 1), (1, 1), 1, "f32", alpha=1.0, beta=1.0, y0=y0, tag="beta1")
+    _check(x, w, (1, 1), (1, 1), 1, "f32", alpha=0.0, beta=2.0, y0=y0, tag="alpha0")
+    _check(x, w, (1, 1), (1, 1), 1, "f32", alpha=-3.0, beta=0.0, tag="nan prefill")   # y prefilled with NaN
+
+
+def test_deterministic_run_to_run():
+    gu = _gpu()
+    x, w = wl.random_problem(43, 4, 32, 14, 14, 64, 3, 3)
+    a, _ = gu.run(x, w, (1, 1), (1, 1))
+    b, _ = gu.run(x, w, (1, 1), (1, 1))
+    assert np.array_equal(a, b)
+
+
+def test_workspace_is_zero_and_no_device_allocation():
+    import torch
+    import paper_1410_0759_amd as ig
+    gu = _gpu()
+    x, w = wl.random_problem(44, 2, 8, 16, 16, 32, 3, 3)
+    g = gu.GpuConv(x, w, (1, 1), (1, 1), 1)
+    assert ig.get_workspace_size(g.handle, g.xdesc, g.wdesc, g.conv, g.ydesc) == 0
+    g.prefill(value=0.0)
+    g.launch()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(10):
+        g.launch()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 == free0, "device memory changed across forward calls"
+
+
+def test_two_threads_two_handles():
+    """Section 2.1: the library is callable from different host threads."""
+    import threading
+    import torch
+    gu = _gpu()
+    x, w = wl.random_problem(45, 2, 8, 20, 20, 48, 3, 3)
+    want = oc.conv_forward(x, w, pad=(1, 1))
+    results = {}
+
+    def work(i):
+        torch.cuda.set_device(0)
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            g = gu.GpuConv(x, w, (1, 1), (1, 1), 1)
+            g.prefill(value=float("nan"))
+            for _ in range(20):
+                g.launch()
+            s.synchronize()
+            results[i] = g.result()
+
+    ts = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    for i in range(2):
+        assert gu.rel_err(results[i], want) <= gu.TOL["f32"]
+
+
+# ------------------------------------------------------------------ the five workloads at full size
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5])
+def test_workload_full_size(index):
+    """Full-size parity on the whole output, in the launch configuration the bench times."""
+    gu = _gpu()
+    w_ = wl.by_index(index)
+    x, w, y0 = wl.make_inputs(w_)
+    print("workload", w_.name, flush=True)
+    got, plan = gu.run(x, w, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, w_.alpha, w_.beta, y0, w_.dtype,
+                       w_.y_layout)
+    assert got.shape == (w_.N, w_.K, w_.P, w_.Q)
+    want = oc.conv_forward(x, w, pad=(w_.pad_h, w_.pad_w), stride=(w_.u, w_.v), mode=w_.mode,
+                           alpha=w_.alpha, beta=w_.beta, y_old=y0)
+    err = gu.rel_err(got, want)
+    print("workload", w_.name, "kernel", plan.kernelId, "rel err", err, flush=True)
+    assert err <= gu.TOL[w_.dtype]

@@ -1,0 +1,198 @@
+"""CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and
+its host logic (validation, output size, plan, magic division) behaves as the header
+says.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1410_0759_amd as ig
+from oracle import conv_oracle as oc
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "igconv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(igc[A-Z]\w*)\s*\(", header))
+    assert declared, "no declarations found"
+    L = ig.lib()
+    for name in declared:
+        assert hasattr(L, name), "library lacks %s" % name
+    assert declared == set(ig.DECLARED_SYMBOLS), declared ^ set(ig.DECLARED_SYMBOLS)
+
+
+def test_error_strings():
+    L = ig.lib()
+    names = {L.igcGetErrorString(i).decode() for i in range(6)}
+    assert len(names) == 6 and all(n.startswith("IGC_STATUS_") for n in names)
+    assert L.igcGetErrorString(99) is not None
+
+
+def _descs(N=2, C=3, H=8, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(1, 1), mode=1, dt=0,
+           xs=None, ys=None, ydims=None, ydt=0):
+    x = ig.TensorDescriptor().set(dt, N, C, H, W, xs or (C * H * W, H * W, W, 1))
+    w = ig.FilterDescriptor().set(dt, K, C, R, S)
+    c = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+    n, k, p, q = ydims or ig.get_output_dim(c, x, w)
+    y = ig.TensorDescriptor().set(ydt, n, k, p, q, ys or (k * p * q, p * q, q, 1))
+    return x, w, c, y
+
+
+def test_descriptor_roundtrip():
+    x, w, c, y = _descs()
+    assert x.get() == (0, (2, 3, 8, 8), (192, 64, 8, 1))
+    assert w.get() == (0, 4, 3, 3, 3)
+    assert c.get() == (1, 1, 1, 1, 1)
+
+
+def test_output_dim_matches_eq1():
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        H, W = int(rng.integers(1, 60)), int(rng.integers(1, 60))
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        pad = (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
+        st = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        x = ig.TensorDescriptor().set(0, 2, 3, H, W, (3 * H * W, H * W, W, 1))
+        w = ig.FilterDescriptor().set(0, 5, 3, R, S)
+        c = ig.ConvolutionDescriptor().set(pad[0], pad[1], st[0], st[1], 0)
+        P, Q = oc.output_dim(H, R, st[0], pad[0]), oc.output_dim(W, S, st[1], pad[1])
+        if P < 1 or Q < 1:
+            with pytest.raises(ig.IgcError) as e:
+                ig.get_output_dim(c, x, w)
+            assert e.value.status == ig.IGC_STATUS_BAD_PARAM
+        else:
+            assert ig.get_output_dim(c, x, w) == (2, 5, P, Q)
+
+
+def test_workload_dims_and_plans():
+    h = ig.Handle()
+    for w_ in wl.WORKLOADS:
+        dt = 1 if w_.dtype == "bf16" else 0
+        nchw = lambda n, c, hh, ww: (c * hh * ww, hh * ww, ww, 1)
+        nhwc = lambda n, c, hh, ww: (hh * ww * c, 1, ww * c, c)
+        xs = (nchw if w_.x_layout == "NCHW" else nhwc)(w_.N, w_.C, w_.H, w_.W)
+        ys = (nchw if w_.y_layout == "NCHW" else nhwc)(w_.N, w_.K, w_.P, w_.Q)
+        x, w, c, y = _descs(w_.N, w_.C, w_.H, w_.W, w_.K, w_.R, w_.S, (w_.pad_h, w_.pad_w), (w_.u, w_.v),
+                            w_.mode, dt, xs=xs, ys=ys)
+        assert ig.get_output_dim(c, x, w) == (w_.N, w_.K, w_.P, w_.Q)
+        assert ig.get_workspace_size(h, x, w, c, y) == 0
+        plan = ig.get_plan(h, x, w, c, y)
+        name = ig.kernel_names()[plan.kernelId]
+        assert name.startswith(w_.dtype)
+        assert plan.gridX == -(-w_.K // plan.tileM) * -(-(w_.N * w_.P * w_.Q) // plan.tileN)
+        assert plan.kSteps == -(-(w_.C * w_.R * w_.S) // plan.tileK)
+        assert plan.ldsBytes <= 160 * 1024
+        assert plan.swapOperands == (1 if w_.y_layout == "NHWC" else 0)
+
+
+def _fwd_status(x, w, c, y, xp=256, wp=256, yp=256, handle=None, alpha=True, beta=True):
+    """Call igcConvolutionForward with fake (never dereferenced) pointers: only legal
+    for argument sets that validation rejects before any GPU call."""
+    L = ig.lib()
+    h = handle or ig.Handle()
+    a, b = ctypes.c_float(1), ctypes.c_float(0)
+    return L.igcConvolutionForward(h.ptr, ctypes.byref(a) if alpha else None, x.ptr if x else None, xp,
+                                   w.ptr if w else None, wp, c.ptr if c else None, None, 0,
+                                   ctypes.byref(b) if beta else None, y.ptr if y else None, yp)
+
+
+def test_forward_rejects_bad_arguments_before_any_gpu_call():
+    x, w, c, y = _descs()
+    assert _fwd_status(None, w, c, y) == ig.IGC_STATUS_BAD_PARAM
+    assert _fwd_status(x, w, c, y, xp=None) == ig.IGC_STATUS_BAD_PARAM
+    assert _fwd_status(x, w, c, y, yp=None) == ig.IGC_STATUS_BAD_PARAM
+    assert _fwd_status(x, w, c, y, alpha=False) == ig.IGC_STATUS_BAD_PARAM
+    assert _fwd_status(x, w, c, y, beta=False) == ig.IGC_STATUS_BAD_PARAM
+    assert _fwd_status(x, w, c, y, xp=258 + 1) == ig.IGC_STATUS_BAD_PARAM        # misaligned x
+    # unset descriptor
+    assert _fwd_status(ig.TensorDescriptor(), w, c, y) == ig.IGC_STATUS_NOT_INITIALIZED
+    # channel mismatch
+    w2 = ig.FilterDescriptor().set(0, 4, 5, 3, 3)
+    assert _fwd_status(x, w2, c, y) == ig.IGC_STATUS_BAD_PARAM
+    # wrong y dims
+    ybad = ig.TensorDescriptor().set(0, 2, 4, 8, 7, (4 * 8 * 7, 56, 7, 1))
+    assert _fwd_status(x, w, c, ybad) == ig.IGC_STATUS_BAD_PARAM
+    # aliasing y strides
+    yal = ig.TensorDescriptor().set(0, 2, 4, 8, 8, (256, 64, 8, 0))
+    assert _fwd_status(x, w, c, yal) == ig.IGC_STATUS_BAD_PARAM
+    yal2 = ig.TensorDescriptor().set(0, 2, 4, 8, 8, (256, 60, 8, 1))            # planes overlap
+    assert _fwd_status(x, w, c, yal2) == ig.IGC_STATUS_BAD_PARAM
+    # data types
+    xb = ig.TensorDescriptor().set(1, 2, 3, 8, 8, (192, 64, 8, 1))
+    assert _fwd_status(xb, w, c, y) == ig.IGC_STATUS_NOT_SUPPORTED                # bf16 x, f32 w
+    yb = ig.TensorDescriptor().set(1, 2, 4, 8, 8, (256, 64, 8, 1))
+    assert _fwd_status(x, w, c, yb) == ig.IGC_STATUS_NOT_SUPPORTED                # bf16 y
+    # offsets reaching 2^31 bytes
+    xbig = ig.TensorDescriptor().set(0, 2, 3, 8, 8, (1 << 29, 64, 8, 1))
+    assert _fwd_status(xbig, w, c, y) == ig.IGC_STATUS_NOT_SUPPORTED
+    # kernel override of the wrong data type
+    h = ig.Handle()
+    h.set_kernel_override(len(ig.kernel_names()) - 1)       # a bf16 kernel
+    assert _fwd_status(x, w, c, y, handle=h) == ig.IGC_STATUS_NOT_SUPPORTED
+
+
+def test_setters_reject_bad_values():
+    L = ig.lib()
+    t = ig.TensorDescriptor()
+    assert L.igcSetTensor4dDescriptor(t.ptr, 0, 0, 1, 1, 1, 1, 1, 1, 1) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSetTensor4dDescriptor(t.ptr, 0, 1, 1, 1, 1, -1, 1, 1, 1) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSetTensor4dDescriptor(t.ptr, 7, 1, 1, 1, 1, 1, 1, 1, 1) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSetTensor4dDescriptor(None, 0, 1, 1, 1, 1, 1, 1, 1, 1) == ig.IGC_STATUS_BAD_PARAM
+    f = ig.FilterDescriptor()
+    assert L.igcSetFilter4dDescriptor(f.ptr, 0, 1, 1, 0, 1) == ig.IGC_STATUS_BAD_PARAM
+    c = ig.ConvolutionDescriptor()
+    assert L.igcSetConvolution2dDescriptor(c.ptr, -1, 0, 1, 1, 0) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSetConvolution2dDescriptor(c.ptr, 0, 0, 0, 1, 0) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSetConvolution2dDescriptor(c.ptr, 0, 0, 1, 1, 2) == ig.IGC_STATUS_BAD_PARAM
+    # out-params untouched on failure
+    n = ctypes.c_int(-5)
+    assert L.igcGetFilter4dDescriptor(f.ptr, ctypes.byref(n), ctypes.byref(n), ctypes.byref(n), ctypes.byref(n),
+                                      ctypes.byref(n)) == ig.IGC_STATUS_NOT_INITIALIZED
+    assert n.value == -5
+    assert L.igcCreate(None) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcDestroy(None) == ig.IGC_STATUS_BAD_PARAM
+
+
+def test_stream_roundtrip():
+    h = ig.Handle()
+    assert h.get_stream() == 0
+    h.set_stream(0x1234)
+    assert h.get_stream() == 0x1234
+
+
+def test_magic_division_exhaustive_small_and_sampled_large():
+    """Division by launch-time constants as multiply + shift (Section 3.1): brute force
+    against integer division for the divisors the workloads produce and for edge cases."""
+    divisors = {1, 2, 3, 5, 7, 9, 11, 13, 14, 55, 56, 121, 169, 196, 3025, 3136, 1 << 10, (1 << 10) + 1,
+                (1 << 16) - 1, 1 << 16, (1 << 20) + 7, (1 << 30) - 1, 1 << 30, (1 << 31) - 1}
+    rng = np.random.default_rng(3)
+    divisors |= {int(v) for v in rng.integers(1, 1 << 31, size=40)}
+    edge = np.array([0, 1, 2, (1 << 31) - 1, (1 << 31) - 2, 1 << 30], dtype=np.uint64)
+    for d in sorted(divisors):
+        mul, shift = ig.magic_divisor(d)
+        n = np.concatenate([np.arange(0, 70000, dtype=np.uint64),
+                            rng.integers(0, 1 << 31, size=20000).astype(np.uint64), edge,
+                            np.arange(1, 300, dtype=np.uint64) * np.uint64(d) % np.uint64(1 << 31),
+                            (np.arange(1, 300, dtype=np.uint64) * np.uint64(d) - np.uint64(1)) % np.uint64(1 << 31)])
+        q = (((n * np.uint64(mul)) >> np.uint64(32)) + n) >> np.uint64(shift)
+        assert np.array_equal(q, n // np.uint64(d)), d
+        # the library's own evaluator agrees with the formula
+        for v in (0, 1, d - 1, d, d + 1, (1 << 31) - 1):
+            assert ig.magic_divide(v, mul, shift) == v // d
+    with pytest.raises(ig.IgcError):
+        ig.magic_divisor(0)
+    with pytest.raises(ig.IgcError):
+        ig.magic_divisor(1 << 31)
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    import paper_1410_0759_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        b.lib()
