@@ -244,10 +244,14 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
                         else
                             acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[mb][nb], 0, 0, 0);
                     } else {
+                        // (whole-vector casts: a bit_cast applied to a single vector
+                        // element reads element 0 with this compiler)
+                        const f32x4 va = __builtin_bit_cast(f32x4, af[mb]);
+                        const f32x4 vb = __builtin_bit_cast(f32x4, bfr[nb]);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float fa = __builtin_bit_cast(float, af[mb][e]);
-                            const float fb = __builtin_bit_cast(float, bfr[nb][e]);
+                            const float fa = va[e];
+                            const float fb = vb[e];
                             if constexpr (Cfg::SWAP)
                                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb, fa, acc[mb][nb], 0, 0, 0);
                             else
