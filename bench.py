@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="headline workload (1-5)")
     ap.add_argument("--only", action="store_true", help="time the headline workload only")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a known-size reference "
+                         "for the profiler's HBM byte counters)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0, help="CPU budget of the headline oracle run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -99,6 +102,14 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
+
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     head = run_config(args.config, args.steps, args.warmup, args.oracle_seconds, args.kernel)
     per_config = []

@@ -39,6 +39,7 @@ using f32x16 = float __attribute__((ext_vector_type(16)));
 using f32x4 = float __attribute__((ext_vector_type(4)));
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+using u16x2 = uint16_t __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kBufferWord3 = 0x00020000u;  // raw buffer, 32-bit data format
 constexpr uint32_t kOutOfRange = 0x80000000u;   // >= any extent this library accepts
@@ -102,11 +103,16 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
 
     // ---- gather role: this lane's column j -> (n,p,q) (loop invariant) ------------
+    // hw0 packs (p*u - pad_h, q*v - pad_w) as two 16-bit fields (two's complement);
+    // adding a packed tap (tr, ts) gives the input coordinates of that tap, and the
+    // tap is inside the image iff both fields are <= (H-1, W-1) as unsigned 16-bit
+    // numbers (the host limits H, W and pad to 2^14, so a coordinate left of / above
+    // the image wraps to >= 0xC000 and nothing wraps back into range).
     const int cg = wave % Cfg::CG;
     const int kpart = wave / Cfg::CG;
     const int jl = cg * 64 + lane;
-    int h0, w0;
-    uint32_t colbase;  // element offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
+    u16x2 hw0;
+    uint32_t colbase_b;  // byte offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
     {
         const int j = n0 + jl;
         const bool cv = j < p.NPQ;
@@ -115,11 +121,19 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         const uint32_t rem = jj - n * (uint32_t)p.PQ;
         const uint32_t pp = magic_div(rem, p.mQ);
         const uint32_t qq = rem - pp * (uint32_t)p.Q;
-        h0 = (int)pp * p.u - p.pad_h;
-        w0 = (int)qq * p.v - p.pad_w;
-        colbase = n * (uint32_t)p.xsN + (uint32_t)h0 * (uint32_t)p.xsH + (uint32_t)w0 * (uint32_t)p.xsW;
-        if (!cv) h0 = -0x40000000;  // no tap of a column beyond NPQ is ever in range
+        const int h0 = (int)pp * p.u - p.pad_h;
+        const int w0 = (int)qq * p.v - p.pad_w;
+        colbase_b = (n * (uint32_t)p.xsN + (uint32_t)h0 * (uint32_t)p.xsH + (uint32_t)w0 * (uint32_t)p.xsW) * ES;
+        hw0[1] = (uint16_t)h0;
+        hw0[0] = (uint16_t)w0;
+        if (!cv) {
+            hw0[1] = 0x8000;           // no tap of a column beyond NPQ is ever in range
+            colbase_b = kOutOfRange;   // (used by the unpadded path)
+        }
     }
+    u16x2 hw_max;
+    hw_max[1] = (uint16_t)(p.H - 1);
+    hw_max[0] = (uint16_t)(p.W - 1);
 
     // ---- filter-tile role ----------------------------------------------------------
     constexpr int A_PASSES = Cfg::VECA ? (BM * (BK / VEC)) / 256 : (BM * BK) / 256;
@@ -148,34 +162,50 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
                 a_sca[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voff, 0, 0));
             }
         }
-        // D_m tile: reduction indices i0..i0+KPT-1 of this lane's column.  The decode
-        // i -> (c,r,s) is uniform over the wavefront.
-        const uint32_t i0 = (uint32_t)(k0 + kpart * KPT);
-        uint32_t c = magic_div(i0, p.mRS);
-        const uint32_t rs = i0 - c * (uint32_t)p.RS;
-        uint32_t r = magic_div(rs, p.mS);
-        uint32_t s = rs - r * (uint32_t)p.S;
+        // D_m tile: reduction indices i0..i0+KPT-1 of this lane's column.  Lane L of
+        // the wavefront decodes index i0+L -> (c,r,s) once for everybody (tap position
+        // inside the window, eq. 2 inverts it; byte offset of the tap relative to the
+        // window origin); element e then takes lane e's values as scalars.
+        const uint32_t il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
+        const uint32_t c = magic_div(il, p.mRS);
+        const uint32_t rs = il - c * (uint32_t)p.RS;
+        const uint32_t r = magic_div(rs, p.mS);
+        const uint32_t sx = rs - r * (uint32_t)p.S;
+        const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+        const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+        const bool iin = il < (uint32_t)p.CRS;
+        const uint32_t delta_l = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+        if (p.nopad) {
+            // Every tap of a valid column is inside the image: no window test.  An
+            // index beyond CRS or a column beyond NPQ contributes 2^31 to the offset,
+            // which puts it out of range (valid offsets are below 2^31).  When both are
+            // out of range the sum wraps to 0 and reads x[0]: that value only meets
+            // zero filter entries, in a column that is never stored.
+            const uint32_t dl = iin ? delta_l : kOutOfRange;
 #pragma unroll
-        for (int e = 0; e < KPT; ++e) {
-            // tap position inside the filter window (eq. 2 inverts it)
-            uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - s : s;
-            tr = ((int)c < p.C) ? tr : 0x20000000u;  // i >= CRS: never in range
-            const int hh = h0 + (int)tr;
-            const int ww = w0 + (int)ts;
-            const bool ok = (uint32_t)hh < (uint32_t)p.H && (uint32_t)ww < (uint32_t)p.W;
-            const uint32_t delta = c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW;
-            const uint32_t voff = ok ? (colbase + delta) * ES : kOutOfRange;
-            if constexpr (Cfg::BF16) {
-                b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
-            } else {
-                b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
+            for (int e = 0; e < KPT; ++e) {
+                const uint32_t d = __builtin_amdgcn_readlane(dl, e);
+                const uint32_t voff = colbase_b + d;
+                if constexpr (Cfg::BF16) {
+                    b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
+                } else {
+                    b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
+                }
             }
-            if (++s == (uint32_t)p.S) {
-                s = 0;
-                if (++r == (uint32_t)p.R) {
-                    r = 0;
-                    ++c;
+        } else {
+            const uint32_t tap_l = iin ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
+#pragma unroll
+            for (int e = 0; e < KPT; ++e) {
+                const uint32_t d = __builtin_amdgcn_readlane(delta_l, e);
+                const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(tap_l, e));
+                const u16x2 hw = hw0 + tap;
+                const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+                const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+                const uint32_t voff = ok ? colbase_b + d : kOutOfRange;
+                if constexpr (Cfg::BF16) {
+                    b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
+                } else {
+                    b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
                 }
             }
         }
@@ -232,33 +262,39 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
                 bfr[nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD + g * KG);
+            if constexpr (Cfg::BF16) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    if constexpr (Cfg::BF16) {
+                    for (int nb = 0; nb < NB; ++nb) {
                         const bf16x8 fa = __builtin_bit_cast(bf16x8, af[mb]);
                         const bf16x8 fb = __builtin_bit_cast(bf16x8, bfr[nb]);
                         if constexpr (Cfg::SWAP)
                             acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[mb][nb], 0, 0, 0);
                         else
                             acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[mb][nb], 0, 0, 0);
-                    } else {
-                        // (whole-vector casts: a bit_cast applied to a single vector
-                        // element reads element 0 with this compiler)
-                        const f32x4 va = __builtin_bit_cast(f32x4, af[mb]);
-                        const f32x4 vb = __builtin_bit_cast(f32x4, bfr[nb]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float fa = va[e];
-                            const float fb = vb[e];
-                            if constexpr (Cfg::SWAP)
-                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb, fa, acc[mb][nb], 0, 0, 0);
-                            else
-                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc[mb][nb], 0, 0, 0);
-                        }
                     }
-                }
+            } else {
+                // (whole-vector casts: a bit_cast applied to a single vector element
+                // reads element 0 with this compiler)
+                f32x4 va[MB], vb[NB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) va[mb] = __builtin_bit_cast(f32x4, af[mb]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) vb[nb] = __builtin_bit_cast(f32x4, bfr[nb]);
+                // consecutive MFMAs go to different accumulators
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            if constexpr (Cfg::SWAP)
+                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(vb[nb][e], va[mb][e], acc[mb][nb], 0, 0, 0);
+                            else
+                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[mb][e], vb[nb][e], acc[mb][nb], 0, 0, 0);
+                        }
+            }
         }
     };
 
