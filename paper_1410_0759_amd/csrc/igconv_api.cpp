@@ -140,7 +140,6 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
         k.K = w->k; k.R = w->r; k.S = w->s; k.P = (int)P; k.Q = (int)Q;
         k.pad_h = cv->pad_h; k.pad_w = cv->pad_w; k.u = cv->u; k.v = cv->v;
         k.flip = cv->mode == IGC_CONVOLUTION ? 1 : 0;
-        k.nopad = (cv->pad_h == 0 && cv->pad_w == 0) ? 1 : 0;
         k.CRS = (int)CRS; k.NPQ = (int)NPQ; k.PQ = (int)(P * Q); k.RS = w->r * w->s;
         if (!magic_for((uint32_t)k.PQ, &k.mPQ) || !magic_for((uint32_t)k.Q, &k.mQ) ||
             !magic_for((uint32_t)k.RS, &k.mRS) || !magic_for((uint32_t)k.S, &k.mS))

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
+#include <utility>
 
 #include "igconv_params.h"
 
@@ -43,6 +44,17 @@ using u16x2 = uint16_t __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kBufferWord3 = 0x00020000u;  // raw buffer, 32-bit data format
 constexpr uint32_t kOutOfRange = 0x80000000u;   // >= any extent this library accepts
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = 0..N-1, so that every
+// index below is a constant (register arrays stay in registers, schedule tests fold).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
     return (__umulhi(n, m.mul) + n) >> m.shift;
@@ -128,7 +140,6 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         hw0[0] = (uint16_t)w0;
         if (!cv) {
             hw0[1] = 0x8000;           // no tap of a column beyond NPQ is ever in range
-            colbase_b = kOutOfRange;   // (used by the unpadded path)
         }
     }
     u16x2 hw_max;
@@ -141,102 +152,97 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     const int a_row = Cfg::VECA ? tid / (BK / VEC) : tid / BK;
     const int a_kk = Cfg::VECA ? (tid % (BK / VEC)) * VEC : tid % BK;
 
-    u32x4 a_vec[Cfg::VECA ? A_PASSES : 1];
-    elem_t a_sca[Cfg::VECA ? 1 : A_PASSES];
-    elem_t b_val[KPT];
+    // Registers holding the tiles in flight between HBM and LDS: two sets, tile T uses
+    // set T&1, so that the loads of tile t+2 can be issued while tile t+1 still waits
+    // in the other set to be written to LDS.
+    u32x4 a_vec[2][Cfg::VECA ? A_PASSES : 1];
+    elem_t a_sca[2][Cfg::VECA ? 1 : A_PASSES];
+    elem_t b_val[2][KPT];
+    // Per-lane decode of reduction index (first index of this wavefront's run) + lane:
+    // byte offset of the tap relative to the window origin, and the packed tap (tr,ts).
+    uint32_t dec_il = 0, dec_c = 0, dec_rs = 0, dec_delta = 0, dec_tap = 0;
 
-    auto fetch = [&](int k0) {
-        // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.
-        const int i = k0 + a_kk;
-        const bool kin = i < p.CRS;
-#pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) {
-            const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
-            const uint32_t off = ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)i) * ES;
-            const uint32_t voff = (kin && row < p.K) ? off : kOutOfRange;
-            if constexpr (Cfg::VECA) {
-                a_vec[ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voff, 0, 0);
-            } else if constexpr (Cfg::BF16) {
-                a_sca[ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voff, 0, 0);
-            } else {
-                a_sca[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voff, 0, 0));
-            }
-        }
-        // D_m tile: reduction indices i0..i0+KPT-1 of this lane's column.  Lane L of
-        // the wavefront decodes index i0+L -> (c,r,s) once for everybody (tap position
-        // inside the window, eq. 2 inverts it; byte offset of the tap relative to the
-        // window origin); element e then takes lane e's values as scalars.
-        const uint32_t il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
-        const uint32_t c = magic_div(il, p.mRS);
-        const uint32_t rs = il - c * (uint32_t)p.RS;
-        const uint32_t r = magic_div(rs, p.mS);
-        const uint32_t sx = rs - r * (uint32_t)p.S;
+    // i -> (c,r,s) for the tile that starts at reduction index k0; lane L decodes index
+    // i0+L once for everybody (tap position inside the window: eq. 2 inverts it).  In
+    // two halves so that each fits between two MFMAs.
+    auto decode1 = [&](int k0) {
+        dec_il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
+        dec_c = magic_div(dec_il, p.mRS);
+        dec_rs = dec_il - dec_c * (uint32_t)p.RS;
+    };
+    auto decode2 = [&]() {
+        const uint32_t r = magic_div(dec_rs, p.mS);
+        const uint32_t sx = dec_rs - r * (uint32_t)p.S;
         const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
         const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-        const bool iin = il < (uint32_t)p.CRS;
-        const uint32_t delta_l = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
-        if (p.nopad) {
-            // Every tap of a valid column is inside the image: no window test.  An
-            // index beyond CRS or a column beyond NPQ contributes 2^31 to the offset,
-            // which puts it out of range (valid offsets are below 2^31).  When both are
-            // out of range the sum wraps to 0 and reads x[0]: that value only meets
-            // zero filter entries, in a column that is never stored.
-            const uint32_t dl = iin ? delta_l : kOutOfRange;
-#pragma unroll
-            for (int e = 0; e < KPT; ++e) {
-                const uint32_t d = __builtin_amdgcn_readlane(dl, e);
-                const uint32_t voff = colbase_b + d;
-                if constexpr (Cfg::BF16) {
-                    b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
-                } else {
-                    b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
-                }
-            }
+        dec_delta = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+        dec_tap = dec_il < (uint32_t)p.CRS ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
+    };
+    // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.
+    auto load_a = [&](int set, int k0, int ps) {
+        const int i = k0 + a_kk;
+        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
+        const uint32_t off = ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)i) * ES;
+        const uint32_t voff = (i < p.CRS && row < p.K) ? off : kOutOfRange;
+        if constexpr (Cfg::VECA) {
+            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voff, 0, 0);
+        } else if constexpr (Cfg::BF16) {
+            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voff, 0, 0);
         } else {
-            const uint32_t tap_l = iin ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
-#pragma unroll
-            for (int e = 0; e < KPT; ++e) {
-                const uint32_t d = __builtin_amdgcn_readlane(delta_l, e);
-                const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(tap_l, e));
-                const u16x2 hw = hw0 + tap;
-                const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
-                const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
-                const uint32_t voff = ok ? colbase_b + d : kOutOfRange;
-                if constexpr (Cfg::BF16) {
-                    b_val[e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
-                } else {
-                    b_val[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
-                }
-            }
+            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voff, 0, 0));
         }
     };
-
-    auto stage = [&](int buf) {
+    // D_m tile, element e of this lane's column: takes lane e's decode as scalars.
+    auto load_b = [&](int set, int e) {
+        const uint32_t d = __builtin_amdgcn_readlane(dec_delta, e);
+        const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
+        const u16x2 hw = hw0 + tap;
+        const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+        const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+        const uint32_t voff = ok ? colbase_b + d : kOutOfRange;
+        if constexpr (Cfg::BF16) {
+            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
+        } else {
+            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
+        }
+    };
+    auto write_a = [&](int set, int buf, int ps) {
         elem_t *const A = ldsA + buf * Cfg::A_ELEMS;
-        elem_t *const B = ldsB + buf * Cfg::B_ELEMS;
-#pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) {
-            const int row = a_row + ps * A_ROWS_PER_PASS;
-            if constexpr (Cfg::VECA) {
-                *reinterpret_cast<u32x4 *>(A + row * LD + a_kk) = a_vec[ps];
-            } else {
-                A[row * LD + a_kk] = a_sca[ps];
-            }
+        const int row = a_row + ps * A_ROWS_PER_PASS;
+        if constexpr (Cfg::VECA) {
+            *reinterpret_cast<u32x4 *>(A + row * LD + a_kk) = a_vec[set][ps];
+        } else {
+            A[row * LD + a_kk] = a_sca[set][ps];
         }
-        elem_t *const dst = B + jl * LD + kpart * KPT;
+    };
+    // 16-byte chunk q of this lane's run of the D_m tile.
+    auto write_b = [&](int set, int buf, int q) {
+        elem_t *const dst = ldsB + buf * Cfg::B_ELEMS + jl * LD + kpart * KPT + q * VEC;
+        u32x4 v;
+        if constexpr (Cfg::BF16) {
 #pragma unroll
-        for (int e = 0; e < KPT; e += VEC) {
-            u32x4 v;
-            if constexpr (Cfg::BF16) {
+            for (int d = 0; d < 4; ++d)
+                v[d] = (uint32_t)b_val[set][q * VEC + 2 * d] | ((uint32_t)b_val[set][q * VEC + 2 * d + 1] << 16);
+        } else {
 #pragma unroll
-                for (int d = 0; d < 4; ++d)
-                    v[d] = (uint32_t)b_val[e + 2 * d] | ((uint32_t)b_val[e + 2 * d + 1] << 16);
-            } else {
-#pragma unroll
-                for (int d = 0; d < 4; ++d) v[d] = __builtin_bit_cast(uint32_t, b_val[e + d]);
-            }
-            *reinterpret_cast<u32x4 *>(dst + e) = v;
+            for (int d = 0; d < 4; ++d) v[d] = __builtin_bit_cast(uint32_t, b_val[set][q * VEC + d]);
         }
+        *reinterpret_cast<u32x4 *>(dst) = v;
+    };
+
+    // Moving one tile is a list of small items: NL load items (decode halves, filter
+    // loads, gathered elements) and NW LDS-write items.
+    constexpr int NW_A = A_PASSES, NW_B = KPT / VEC, NW = NW_A + NW_B;
+    constexpr int NL = 2 + A_PASSES + KPT;
+    auto load_item = [&](int i, int set, int k0) {
+        if (i == 0) decode1(k0);
+        else if (i == 1) decode2();
+        else if (i < 2 + A_PASSES) load_a(set, k0, i - 2);
+        else load_b(set, i - 2 - A_PASSES);
+    };
+    auto write_item = [&](int i, int set, int buf) {
+        if (i < NW_A) write_a(set, buf, i);
+        else write_b(set, buf, i - NW_A);
     };
 
     // ---- MFMA role -------------------------------------------------------------------
@@ -250,65 +256,102 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    auto multiply = [&](int buf) {
-        const elem_t *const A = ldsA + buf * Cfg::A_ELEMS + (wm * Cfg::TM + l32) * LD + half * VEC;
-        const elem_t *const B = ldsB + buf * Cfg::B_ELEMS + (wn * Cfg::TN + l32) * LD + half * VEC;
+    constexpr int G = BK / KG;                          // k-groups per step
+    constexpr int EPG = Cfg::BF16 ? 1 : 4;              // MFMAs per (block, k-group)
+    constexpr int MPG = EPG * MB * NB;                  // MFMAs per k-group
+    constexpr int NM = G * MPG;                         // MFMAs per step
+    static_assert(G % 2 == 0, "operand fragments alternate between two register sets");
+    constexpr int SB = (G - 1) * MPG;                   // the step's barrier sits before MFMA number SB
+    // Operand fragments: 16 bytes of k per lane and 32-row block, two sets (k-group
+    // parity) so that the next group's fragments load while this group multiplies.
+    u32x4 fragA[2][MB], fragB[2][NB];
+    const int fa_off = (wm * Cfg::TM + l32) * LD + half * VEC;
+    const int fb_off = (wn * Cfg::TN + l32) * LD + half * VEC;
+    auto read_frags = [&](int buf, int g) {
+        const elem_t *const A = ldsA + buf * Cfg::A_ELEMS + fa_off + g * KG;
+        const elem_t *const B = ldsB + buf * Cfg::B_ELEMS + fb_off + g * KG;
 #pragma unroll
-        for (int g = 0; g < BK / KG; ++g) {
-            u32x4 af[MB], bfr[NB];
+        for (int mb = 0; mb < MB; ++mb) fragA[g & 1][mb] = *reinterpret_cast<const u32x4 *>(A + mb * 32 * LD);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                af[mb] = *reinterpret_cast<const u32x4 *>(A + mb * 32 * LD + g * KG);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                bfr[nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD + g * KG);
-            if constexpr (Cfg::BF16) {
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        const bf16x8 fa = __builtin_bit_cast(bf16x8, af[mb]);
-                        const bf16x8 fb = __builtin_bit_cast(bf16x8, bfr[nb]);
-                        if constexpr (Cfg::SWAP)
-                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[mb][nb], 0, 0, 0);
-                        else
-                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[mb][nb], 0, 0, 0);
-                    }
-            } else {
-                // (whole-vector casts: a bit_cast applied to a single vector element
-                // reads element 0 with this compiler)
-                f32x4 va[MB], vb[NB];
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) va[mb] = __builtin_bit_cast(f32x4, af[mb]);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) vb[nb] = __builtin_bit_cast(f32x4, bfr[nb]);
-                // consecutive MFMAs go to different accumulators
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            if constexpr (Cfg::SWAP)
-                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(vb[nb][e], va[mb][e], acc[mb][nb], 0, 0, 0);
-                            else
-                                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[mb][e], vb[nb][e], acc[mb][nb], 0, 0, 0);
-                        }
-            }
+        for (int nb = 0; nb < NB; ++nb) fragB[g & 1][nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD);
+    };
+    // MFMA number j of k-group g.  Consecutive MFMAs go to different accumulators.
+    auto mfma = [&](int g, int j) {
+        const int e = j / (MB * NB), mb = (j / NB) % MB, nb = j % NB;
+        if constexpr (Cfg::BF16) {
+            const bf16x8 fa = __builtin_bit_cast(bf16x8, fragA[g & 1][mb]);
+            const bf16x8 fb = __builtin_bit_cast(bf16x8, fragB[g & 1][nb]);
+            if constexpr (Cfg::SWAP)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[mb][nb], 0, 0, 0);
+            else
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[mb][nb], 0, 0, 0);
+        } else {
+            // (whole-vector casts: a bit_cast applied to a single vector element reads
+            // element 0 with this compiler)
+            const f32x4 va = __builtin_bit_cast(f32x4, fragA[g & 1][mb]);
+            const f32x4 vb = __builtin_bit_cast(f32x4, fragB[g & 1][nb]);
+            if constexpr (Cfg::SWAP)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(vb[e], va[e], acc[mb][nb], 0, 0, 0);
+            else
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], vb[e], acc[mb][nb], 0, 0, 0);
         }
     };
+    // Workgroup barrier that orders LDS traffic only: global loads stay in flight.
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
 
-    // ---- main loop: fetch step t+1 from HBM while step t is multiplied -----------------
+    // ---- main loop ----------------------------------------------------------------------
+    // Software pipeline over the reduction steps t = 0..T-1 (Section 3.1: compute on the
+    // current tiles while the next ones are fetched).  During step t, which multiplies
+    // LDS stage t&1:
+    //   * the loads of tile t+2 are issued into register set t&1, one item per MFMA;
+    //   * tile t+1, requested a whole step earlier into the other set, is written to
+    //     LDS stage (t+1)&1 in the slots just before the barrier;
+    //   * before the last k-group the workgroup synchronises and the first fragments of
+    //     step t+1 are read, so the MFMA pipe never waits for LDS.
+    // The order is pinned with scheduling barriers: one short burst of side work, one
+    // MFMA.  Tiles beyond the last step read as zeros (out-of-range requests), so no
+    // step is special; the loop is unrolled by two because the register set and the LDS
+    // stage alternate.
+    auto step = [&](auto parity, int t) {
+        constexpr int cur = decltype(parity)::value, nxt = cur ^ 1;
+        const int k2 = (t + 2) * BK;
+        static_for<NM>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            constexpr int g = m / MPG, j = m % MPG;
+            if constexpr (j == 0 && g + 1 < G) read_frags(cur, g + 1);
+            if constexpr (m == SB) {
+                lds_barrier();
+                read_frags(nxt, 0);
+            }
+            // load items i with floor(i * NM / NL) == m: tile t+2 -> set cur
+            constexpr int l0 = (m * NL + NM - 1) / NM, l1 = ((m + 1) * NL + NM - 1) / NM;
+            static_for<l1 - l0>([&](auto ic) { load_item(l0 + decltype(ic)::value, cur, k2); });
+            // write items, packed into the slots before the barrier: tile t+1, set nxt -> stage nxt
+            constexpr int WS = NW < SB ? NW : SB;   // slots used for writes
+            if constexpr (m >= SB - WS && m < SB) {
+                constexpr int q = m - (SB - WS);
+                constexpr int w0 = (q * NW + WS - 1) / WS, w1 = ((q + 1) * NW + WS - 1) / WS;
+                static_for<w1 - w0>([&](auto ic) { write_item(w0 + decltype(ic)::value, nxt, nxt); });
+            }
+            mfma(g, j);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
     const int ksteps = (p.CRS + BK - 1) / BK;
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    for (int t = 0; t < ksteps; ++t) {
-        const bool more = t + 1 < ksteps;
-        if (more) fetch((t + 1) * BK);
-        multiply(t & 1);
-        if (more) stage((t + 1) & 1);
-        __syncthreads();
+    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, 0); });
+    static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
+    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, BK); });
+    lds_barrier();
+    read_frags(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int t = 0; t < ksteps; t += 2) {
+        step(std::integral_constant<int, 0>{}, t);
+        if (t + 1 < ksteps) step(std::integral_constant<int, 1>{}, t + 1);
     }
 
     // ---- epilogue: alpha/beta, store through y's strides ---------------------------------

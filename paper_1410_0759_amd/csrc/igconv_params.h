@@ -23,7 +23,6 @@ struct ConvKernelParams {
     int32_t N, C, H, W, K, R, S, P, Q;
     int32_t pad_h, pad_w, u, v;
     int32_t flip;    // 1: eq. 2 (tap r reads row R-1-r), 0: cross-correlation
-    int32_t nopad;   // 1: pad_h == pad_w == 0, every tap of a valid column is inside the image
     int32_t CRS, NPQ, PQ, RS;
     Magic mPQ, mQ, mRS, mS;
     int32_t xsN, xsC, xsH, xsW;  // element strides of x
