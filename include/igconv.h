@@ -172,6 +172,7 @@ typedef struct {
     int ldsBytes;    /* LDS per workgroup */
     int swapOperands;/* 1 when lanes run along k in the epilogue (y's c-stride is 1) */
     int vecFilterLoads; /* 1 when filter rows are fetched with 16-byte loads */
+    int gatherMode;  /* 0 generic window test, 1 per-column tap table (R*S <= 9), 2 unpadded */
 } igcConvolutionForwardPlan;
 
 igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle,

@@ -30,7 +30,7 @@ IGC_CONVOLUTION, IGC_CROSS_CORRELATION = 0, 1
 class igcConvolutionForwardPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "kernelId", "tileM", "tileN", "tileK", "gridX", "kSteps", "threads", "ldsBytes",
-        "swapOperands", "vecFilterLoads")]
+        "swapOperands", "vecFilterLoads", "gatherMode")]
 
 
 _vp, _i, _ll, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t

@@ -40,11 +40,22 @@ namespace igc {
 constexpr int kComputeUnits = 256;
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
-int kernel_count() { return kNumKernelsF32 + kNumKernelsBF16; }
+static const KernelGroup *const kGroups[] = {&kGroupF32Taps, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
+                                            &kGroupBF16};
+
+int kernel_count() {
+    int n = 0;
+    for (const KernelGroup *g : kGroups) n += g->count;
+    return n;
+}
 
 const KernelInfo *kernel_info(int id) {
-    if (id < 0 || id >= kernel_count()) return nullptr;
-    return id < kNumKernelsF32 ? &kKernelsF32[id] : &kKernelsBF16[id - kNumKernelsF32];
+    if (id < 0) return nullptr;
+    for (const KernelGroup *g : kGroups) {
+        if (id < g->count) return &g->kernels[id];
+        id -= g->count;
+    }
+    return nullptr;
 }
 
 static bool magic_for(uint32_t d, Magic *m) {
@@ -166,6 +177,14 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     return (double)rounds * steps * (mfma + traffic);
 }
 
+// Gather modes a kernel may use for this problem (see the kernel source): the unpadded
+// mode needs pad 0, the tap table needs R*S <= 9, the generic mode always works.
+static bool gather_mode_ok(int gmode, const ConvKernelParams &k) {
+    if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
+    if (gmode == 1) return k.RS <= 9;
+    return true;
+}
+
 static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, int *id_out) {
     const ConvKernelParams &k = pr.kp;
     const bool can_vec = w_aligned && (k.CRS % pr.vec == 0);
@@ -173,18 +192,22 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
     if (h->kernelOverride >= 0) {
         const KernelInfo *ki = kernel_info(h->kernelOverride);
-        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec)) return IGC_STATUS_NOT_SUPPORTED;
+        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(ki->gmode, k))
+            return IGC_STATUS_NOT_SUPPORTED;
         *id_out = h->kernelOverride;
         return IGC_STATUS_SUCCESS;
     }
+    // Preference: a fast gather mode over the generic one, the wanted epilogue over the
+    // other one, then the cheapest tile.
     int best = -1;
     double best_cost = 0;
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
-        if (ki.bf16 != pr.bf16 || ki.veca != can_vec) continue;
-        // a swap variant exists only for some tiles; never use one when not wanted
-        if (ki.swap != want_swap) continue;
-        const double c = plan_cost(ki, k);
+        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki.gmode, k)) continue;
+        double c = plan_cost(ki, k);
+        if (ki.gmode == 0) c *= 1.5;
+        if (ki.swap != want_swap) c *= 1.5;
+        if (!ki.veca && can_vec) c *= 1.1;
         if (best < 0 || c < best_cost) {
             best = id;
             best_cost = c;
@@ -213,6 +236,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         plan->ldsBytes = ki.ldsBytes;
         plan->swapOperands = ki.swap ? 1 : 0;
         plan->vecFilterLoads = ki.veca ? 1 : 0;
+        plan->gatherMode = ki.gmode;
     }
     return IGC_STATUS_SUCCESS;
 }

@@ -1,7 +1,7 @@
 // Helper shared by the translation units that instantiate kernels.  A unit defines
-// IGC_KERNEL_LIST(X) as a list of X(name, bf16, BM, BN, BK, WM, WN, swap, veca) and
-// expands it twice: once to instantiate the device code, once (host pass only) to
-// fill its slice of the kernel table.
+// IGC_KERNEL_LIST(X) as a list of X(name, bf16, BM, BN, BK, WM, WN, swap, veca, gmode)
+// and expands it twice: once to instantiate the device code, once (host pass only) to
+// fill its group of the kernel table.
 #ifndef IGCONV_INSTANTIATE_HPP_
 #define IGCONV_INSTANTIATE_HPP_
 
@@ -17,13 +17,28 @@ int launch_kernel(const ConvKernelParams &p, int grid, void *stream) {
     return static_cast<int>(hipGetLastError());
 }
 
-#define IGC_INSTANTIATE(NAME, BF16, BM, BN, BK, WM, WN, SWAP, VECA) \
-    template __global__ void igconv_fwd_kernel<KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA>>(const ConvKernelParams);
+#define IGC_INSTANTIATE(NAME, BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE) \
+    template __global__ void igconv_fwd_kernel<KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE>>(const ConvKernelParams);
 
-#define IGC_TABLE_ROW(NAME, BF16, BM, BN, BK, WM, WN, SWAP, VECA)                               \
-    {NAME, BF16, BM, BN, BK, SWAP, VECA, 256,                                                   \
-     KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA>::LDS_BYTES,                             \
-     &launch_kernel<KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA>>},
+#define IGC_TABLE_ROW(NAME, BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE)                        \
+    {NAME, BF16, BM, BN, BK, SWAP, VECA, GMODE, 256,                                            \
+     KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE>::LDS_BYTES,                      \
+     &launch_kernel<KernelConfig<BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE>>},
+
+// Instantiates the kernels of IGC_KERNEL_LIST and defines the group GROUP.
+#if !defined(__HIP_DEVICE_COMPILE__)
+#define IGC_DEFINE_GROUP(GROUP)                                                     \
+    namespace igc {                                                                 \
+    IGC_KERNEL_LIST(IGC_INSTANTIATE)                                                \
+    static const KernelInfo GROUP##_rows[] = {IGC_KERNEL_LIST(IGC_TABLE_ROW)};      \
+    const KernelGroup GROUP = {GROUP##_rows, sizeof(GROUP##_rows) / sizeof(GROUP##_rows[0])}; \
+    }
+#else
+#define IGC_DEFINE_GROUP(GROUP) \
+    namespace igc {             \
+    IGC_KERNEL_LIST(IGC_INSTANTIATE) \
+    }
+#endif
 
 }  // namespace igc
 #endif

@@ -60,8 +60,20 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
     return (__umulhi(n, m.mul) + n) >> m.shift;
 }
 
-template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_>
+// How the gather of the D_m tile finds, for one element (column j, index i), the offset
+// of x[n, c, h, w] and whether the tap lies inside the image.  On this chip fp32 MFMA
+// and ordinary vector instructions cannot overlap, so every vector instruction in the
+// loop is taken from the MFMA rate: the two fast modes need ONE per gathered element.
+enum GatherMode {
+    GATHER_GENERIC = 0,  // any R,S,pad: window test per element on packed 16-bit coordinates
+    GATHER_TAPS = 1,     // R*S <= kMaxTaps: per-column table of tap offsets built once per tile
+    GATHER_NOPAD = 2     // pad_h == pad_w == 0: every tap of a valid column is inside the image
+};
+constexpr int kMaxTaps = 9;
+
+template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
 struct KernelConfig {
+    static constexpr int GMODE = GMODE_;
     static constexpr bool BF16 = BF16_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr bool SWAP = SWAP_;  // lanes run along output channels in the epilogue
@@ -145,6 +157,32 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     u16x2 hw_max;
     hw_max[1] = (uint16_t)(p.H - 1);
     hw_max[0] = (uint16_t)(p.W - 1);
+    // GATHER_TAPS: voff[t] = byte offset of tap t = r*S+s of this column in channel 0,
+    // or the out-of-range marker when the tap falls in the zero border; entry kMaxTaps
+    // is always out of range (used for indices beyond CRS).  GATHER_NOPAD: entry 0 is
+    // the window origin, entry 1 out of range.  The loop picks an entry with a
+    // wavefront-uniform index and adds the channel (resp. tap) offset as a scalar.
+    uint32_t voff[Cfg::GMODE == GATHER_TAPS ? kMaxTaps + 1 : 2];
+    if constexpr (Cfg::GMODE == GATHER_TAPS) {
+#pragma unroll
+        for (int t = 0; t < kMaxTaps; ++t) {
+            const uint32_t r = magic_div((uint32_t)t, p.mS);
+            const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
+            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            u16x2 tap;
+            tap[1] = (uint16_t)tr;
+            tap[0] = (uint16_t)ts;
+            const u16x2 hw = hw0 + tap;
+            const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+            const bool ok = t < p.RS && __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+            voff[t] = ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
+        }
+        voff[kMaxTaps] = kOutOfRange;
+    } else {
+        voff[0] = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
+        voff[1] = kOutOfRange;
+    }
 
     // ---- filter-tile role ----------------------------------------------------------
     constexpr int A_PASSES = Cfg::VECA ? (BM * (BK / VEC)) / 256 : (BM * BK) / 256;
@@ -158,52 +196,94 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     u32x4 a_vec[2][Cfg::VECA ? A_PASSES : 1];
     elem_t a_sca[2][Cfg::VECA ? 1 : A_PASSES];
     elem_t b_val[2][KPT];
-    // Per-lane decode of reduction index (first index of this wavefront's run) + lane:
-    // byte offset of the tap relative to the window origin, and the packed tap (tr,ts).
+    // GATHER_GENERIC: per-lane decode of reduction index (first index of this
+    // wavefront's run) + lane: byte offset of the tap relative to the window origin, and
+    // the packed tap (tr,ts).
     uint32_t dec_il = 0, dec_c = 0, dec_rs = 0, dec_delta = 0, dec_tap = 0;
+    // GATHER_TAPS / GATHER_NOPAD: reduction index of the next element to gather,
+    // wavefront-uniform, kept (with everything derived from it) in scalar registers.
+    uint32_t sc_i = 0;
 
-    // i -> (c,r,s) for the tile that starts at reduction index k0; lane L decodes index
-    // i0+L once for everybody (tap position inside the window: eq. 2 inverts it).  In
-    // two halves so that each fits between two MFMAs.
+    // i -> (c,r,s) for the tile that starts at reduction index k0.
     auto decode1 = [&](int k0) {
-        dec_il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
-        dec_c = magic_div(dec_il, p.mRS);
-        dec_rs = dec_il - dec_c * (uint32_t)p.RS;
-    };
-    auto decode2 = [&]() {
-        const uint32_t r = magic_div(dec_rs, p.mS);
-        const uint32_t sx = dec_rs - r * (uint32_t)p.S;
-        const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-        const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-        dec_delta = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
-        dec_tap = dec_il < (uint32_t)p.CRS ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
-    };
-    // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.
-    auto load_a = [&](int set, int k0, int ps) {
-        const int i = k0 + a_kk;
-        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
-        const uint32_t off = ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)i) * ES;
-        const uint32_t voff = (i < p.CRS && row < p.K) ? off : kOutOfRange;
-        if constexpr (Cfg::VECA) {
-            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voff, 0, 0);
-        } else if constexpr (Cfg::BF16) {
-            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voff, 0, 0);
+        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
+            // lane L decodes index i0+L once for everybody, in two halves so that each
+            // fits between two MFMAs
+            dec_il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
+            dec_c = magic_div(dec_il, p.mRS);
+            dec_rs = dec_il - dec_c * (uint32_t)p.RS;
         } else {
-            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voff, 0, 0));
+            // (readfirstlane states the wavefront-uniformity for the compiler)
+            sc_i = __builtin_amdgcn_readfirstlane((uint32_t)(k0 + kpart * KPT));
         }
     };
-    // D_m tile, element e of this lane's column: takes lane e's decode as scalars.
-    auto load_b = [&](int set, int e) {
-        const uint32_t d = __builtin_amdgcn_readlane(dec_delta, e);
-        const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
-        const u16x2 hw = hw0 + tap;
-        const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
-        const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
-        const uint32_t voff = ok ? colbase_b + d : kOutOfRange;
-        if constexpr (Cfg::BF16) {
-            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, voff, 0, 0);
+    auto decode2 = [&]() {
+        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
+            const uint32_t r = magic_div(dec_rs, p.mS);
+            const uint32_t sx = dec_rs - r * (uint32_t)p.S;
+            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            dec_delta = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+            dec_tap = dec_il < (uint32_t)p.CRS ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
+        }
+    };
+    // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.  The
+    // per-thread part of the offset is fixed; the step adds k0 as a scalar.  (The scalar
+    // offset takes part in the hardware range check as "limit - scalar", so it must
+    // never exceed the extent: tiles beyond the last step use 0.)
+    uint32_t a_voff[A_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) {
+        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
+        a_voff[ps] = row < p.K ? ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)a_kk) * ES : kOutOfRange;
+    }
+    auto load_a = [&](int set, int k0, int ps) {
+        const bool in = k0 + a_kk < p.CRS;
+        const uint32_t voffa = in ? a_voff[ps] : kOutOfRange;
+        const uint32_t soff = k0 < p.CRS ? (uint32_t)k0 * ES : 0u;
+        if constexpr (Cfg::VECA) {
+            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voffa, soff, 0);
+        } else if constexpr (Cfg::BF16) {
+            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voffa, soff, 0);
         } else {
-            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, voff, 0, 0));
+            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voffa, soff, 0));
+        }
+    };
+    // D_m tile, element e of this lane's column.
+    auto load_b = [&](int set, int e) {
+        uint32_t vo, so;
+        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
+            // takes lane e's decode as scalars
+            const uint32_t d = __builtin_amdgcn_readlane(dec_delta, e);
+            const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
+            const u16x2 hw = hw0 + tap;
+            const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+            const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+            vo = ok ? colbase_b + d : kOutOfRange;
+            so = 0;
+        } else {
+            // scalar decode of the running index; one register move picks the table
+            // entry; the rest of the offset is a scalar
+            const uint32_t c = magic_div(sc_i, p.mRS);
+            const uint32_t rs = sc_i - c * (uint32_t)p.RS;  // tap number r*S+s
+            const bool in = (int)c < p.C;
+            ++sc_i;
+            if constexpr (Cfg::GMODE == GATHER_TAPS) {
+                vo = voff[in ? rs : (uint32_t)kMaxTaps];
+                so = in ? c * (uint32_t)p.xsC * ES : 0u;
+            } else {
+                const uint32_t r = magic_div(rs, p.mS);
+                const uint32_t sx = rs - r * (uint32_t)p.S;
+                const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+                const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+                vo = voff[in ? 0 : 1];
+                so = in ? (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : 0u;
+            }
+        }
+        if constexpr (Cfg::BF16) {
+            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, vo, so, 0);
+        } else {
+            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, vo, so, 0));
         }
     };
     auto write_a = [&](int set, int buf, int ps) {
@@ -348,10 +428,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, BK); });
     lds_barrier();
     read_frags(0, 0);
+    // Enter the loop with no load outstanding: otherwise the compiler, merging this path
+    // with the loop's back edge, waits for every load at the top of each step.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __builtin_amdgcn_sched_barrier(0);
+    // (always whole pairs of steps - an odd count runs one extra step on zero tiles - so
+    // that the loop body stays a single basic block)
     for (int t = 0; t < ksteps; t += 2) {
         step(std::integral_constant<int, 0>{}, t);
-        if (t + 1 < ksteps) step(std::integral_constant<int, 1>{}, t + 1);
+        step(std::integral_constant<int, 1>{}, t + 1);
     }
 
     // ---- epilogue: alpha/beta, store through y's strides ---------------------------------

@@ -1,24 +1,19 @@
-// bf16-input kernel variants (v_mfma_f32_32x32x16_bf16, fp32 accumulate and output).
+// bf16-input kernels (v_mfma_f32_32x32x16_bf16, fp32 accumulate and output).
 #include "igconv_instantiate.hpp"
 
-//    name                         bf16  BM   BN  BK WM WN swap   veca
-#define IGC_KERNEL_LIST(X)                                              \
-    X("bf16 64x128x32",            true, 64, 128, 32, 2, 2, false, false) \
-    X("bf16 64x128x32 vecw",       true, 64, 128, 32, 2, 2, false, true)  \
-    X("bf16 128x128x32",           true, 128, 128, 32, 2, 2, false, false) \
-    X("bf16 128x128x32 vecw",      true, 128, 128, 32, 2, 2, false, true)  \
-    X("bf16 64x128x32 swap",       true, 64, 128, 32, 2, 2, true, false)  \
-    X("bf16 64x128x32 swap vecw",  true, 64, 128, 32, 2, 2, true, true)   \
-    X("bf16 128x128x32 swap",      true, 128, 128, 32, 2, 2, true, false) \
-    X("bf16 128x128x32 swap vecw", true, 128, 128, 32, 2, 2, true, true)
+//    name, bf16, BM, BN, BK, WM, WN, swap, veca, gather mode
+#define IGC_KERNEL_LIST(X) \
+    X("bf16 64x128x32 generic", true, 64, 128, 32, 2, 2, false, false, GATHER_GENERIC) \
+    X("bf16 64x128x32 generic vecw", true, 64, 128, 32, 2, 2, false, true, GATHER_GENERIC) \
+    X("bf16 128x128x32 generic", true, 128, 128, 32, 2, 2, false, false, GATHER_GENERIC) \
+    X("bf16 128x128x32 generic vecw", true, 128, 128, 32, 2, 2, false, true, GATHER_GENERIC) \
+    X("bf16 64x128x32 generic swap", true, 64, 128, 32, 2, 2, true, false, GATHER_GENERIC) \
+    X("bf16 64x128x32 generic swap vecw", true, 64, 128, 32, 2, 2, true, true, GATHER_GENERIC) \
+    X("bf16 128x128x32 generic swap", true, 128, 128, 32, 2, 2, true, false, GATHER_GENERIC) \
+    X("bf16 128x128x32 generic swap vecw", true, 128, 128, 32, 2, 2, true, true, GATHER_GENERIC) \
+    X("bf16 128x128x32 taps", true, 128, 128, 32, 2, 2, false, false, GATHER_TAPS) \
+    X("bf16 128x128x32 taps vecw", true, 128, 128, 32, 2, 2, false, true, GATHER_TAPS) \
+    X("bf16 128x128x32 taps swap", true, 128, 128, 32, 2, 2, true, false, GATHER_TAPS) \
+    X("bf16 128x128x32 taps swap vecw", true, 128, 128, 32, 2, 2, true, true, GATHER_TAPS)
 
-namespace igc {
-
-IGC_KERNEL_LIST(IGC_INSTANTIATE)
-
-#if !defined(__HIP_DEVICE_COMPILE__)
-const KernelInfo kKernelsBF16[] = {IGC_KERNEL_LIST(IGC_TABLE_ROW)};
-const int kNumKernelsBF16 = sizeof(kKernelsBF16) / sizeof(kKernelsBF16[0]);
-#endif
-
-}  // namespace igc
+IGC_DEFINE_GROUP(kGroupBF16)

@@ -1,0 +1,15 @@
+// fp32 kernels (v_mfma_f32_32x32x2_f32), unpadded gather, NCHW-style epilogue.
+#include "igconv_instantiate.hpp"
+
+//    name, bf16, BM, BN, BK, WM, WN, swap, veca, gather mode
+#define IGC_KERNEL_LIST(X) \
+    X("f32 32x128x32 nopad", false, 32, 128, 32, 1, 4, false, false, GATHER_NOPAD) \
+    X("f32 32x128x32 nopad vecw", false, 32, 128, 32, 1, 4, false, true, GATHER_NOPAD) \
+    X("f32 64x128x32 nopad", false, 64, 128, 32, 2, 2, false, false, GATHER_NOPAD) \
+    X("f32 64x128x32 nopad vecw", false, 64, 128, 32, 2, 2, false, true, GATHER_NOPAD) \
+    X("f32 96x128x32 nopad", false, 96, 128, 32, 1, 4, false, false, GATHER_NOPAD) \
+    X("f32 96x128x32 nopad vecw", false, 96, 128, 32, 1, 4, false, true, GATHER_NOPAD) \
+    X("f32 128x128x32 nopad", false, 128, 128, 32, 2, 2, false, false, GATHER_NOPAD) \
+    X("f32 128x128x32 nopad vecw", false, 128, 128, 32, 2, 2, false, true, GATHER_NOPAD)
+
+IGC_DEFINE_GROUP(kGroupF32Nopad)

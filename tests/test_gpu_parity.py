@@ -69,17 +69,22 @@ def _kernel_cases():
 
 def test_every_kernel_variant():
     """Each kernel of the table, forced, on problems with tails in every GEMM dimension
-    (K not a tile multiple, NPQ ragged, CRS not a multiple of the k tile)."""
+    (K not a tile multiple, NPQ ragged, CRS not a multiple of the k tile; odd and even
+    numbers of reduction steps)."""
     import paper_1410_0759_amd as ig
     for kid, name in _kernel_cases():
         dtype = "bf16" if name.startswith("bf16") else "f32"
         vec = "vecw" in name
         swap = "swap" in name
+        nopad = "nopad" in name
         vecn = 8 if dtype == "bf16" else 4
         for (N, C, H, W, K, R, S, pad, stride) in [
             (3, 8 if vec else 5, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
             (2, 16 if vec else 3, 21, 9, 45, 2, 2 if vec else 3, (0, 1), (2, 1)),
+            (2, 24 if vec else 13, 9, 11, 33, 1, 1, (0, 0), (1, 1)),
         ]:
+            if nopad:
+                pad = (0, 0)
             if vec:
                 assert (C * R * S) % vecn == 0
             x, w = wl.random_problem(7 + kid, N, C, H, W, K, R, S, dtype=dtype)
@@ -89,6 +94,24 @@ def test_every_kernel_variant():
             _, plan = _check(x, w, pad, stride, 1, dtype, kernel=kid, y_layout=lay, tag=name)
             assert plan.kernelId == kid
             _check(x, w, pad, stride, 0, dtype, alpha=0.5, beta=-1.5, y0=y0, kernel=kid, y_layout=lay, tag=name)
+
+
+def test_gather_modes_are_chosen():
+    """R*S <= 9 -> tap table (padded or not); larger unpadded -> unpadded gather; larger
+    padded -> generic."""
+    import paper_1410_0759_amd as ig
+    x, w = wl.random_problem(3, 2, 4, 12, 12, 8, 3, 3)
+    _, plan = _check(x, w, (0, 0), (1, 1), 1, "f32", tag="mode taps, pad 0")
+    assert plan.gatherMode == 1
+    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode taps")
+    assert plan.gatherMode == 1
+    x, w = wl.random_problem(4, 2, 4, 12, 12, 8, 5, 5)
+    _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad")
+    assert plan.gatherMode == 2
+    _, plan = _check(x, w, (2, 2), (1, 1), 0, "f32", tag="mode generic")
+    assert plan.gatherMode == 0
+    _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode generic swap")
+    assert plan.gatherMode == 0 and plan.swapOperands == 1
 
 
 # ------------------------------------------------------------------ layouts through strides
