@@ -40,7 +40,7 @@ namespace igc {
 constexpr int kComputeUnits = 256;
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
-static const KernelGroup *const kGroups[] = {&kGroupF32Taps, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
+static const KernelGroup *const kGroups[] = {&kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
                                             &kGroupBF16};
 
 int kernel_count() {
@@ -163,25 +163,33 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
     return IGC_STATUS_SUCCESS;
 }
 
+// Reduction steps a kernel needs: its order is either the filter's (c,r,s), cut into
+// chunks of BK, or tap-major: per tap, the channels in chunks of BK.
+static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
+    if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
+    return (k.CRS + ki.BK - 1) / ki.BK;
+}
+
 // Relative cost of running the problem with one kernel variant: MFMA work of the
 // busiest compute unit (tiles are padded to full size and dealt round-robin), plus a
-// term for the per-step tile traffic that favours larger tiles.
+// term for the per-step tile traffic that favours larger tiles, times what the gather
+// mode costs in vector instructions next to the MFMAs.
 static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long tm = (k.K + ki.BM - 1) / ki.BM;
     const long long tn = (k.NPQ + ki.BN - 1) / ki.BN;
-    const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
+    const long long steps = kernel_steps(ki, k);
     const long long tiles = tm * tn;
     const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
     const double mfma = (double)ki.BM * ki.BN * ki.BK;
     const double traffic = 48.0 * (ki.BM + ki.BN) * ki.BK;
-    return (double)rounds * steps * (mfma + traffic);
+    const double mode = ki.gmode == 0 ? 1.6 : (ki.gmode == 2 ? 1.1 : 1.0);
+    return (double)rounds * steps * (mfma + traffic) * mode;
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded
-// mode needs pad 0, the tap table needs R*S <= 9, the generic mode always works.
+// mode needs pad 0; the generic and the tap-major modes always work.
 static bool gather_mode_ok(int gmode, const ConvKernelParams &k) {
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
-    if (gmode == 1) return k.RS <= 9;
     return true;
 }
 
@@ -197,17 +205,14 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
         *id_out = h->kernelOverride;
         return IGC_STATUS_SUCCESS;
     }
-    // Preference: a fast gather mode over the generic one, the wanted epilogue over the
-    // other one, then the cheapest tile.
     int best = -1;
     double best_cost = 0;
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki.gmode, k)) continue;
         double c = plan_cost(ki, k);
-        if (ki.gmode == 0) c *= 1.5;
         if (ki.swap != want_swap) c *= 1.5;
-        if (!ki.veca && can_vec) c *= 1.1;
+        if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
         if (best < 0 || c < best_cost) {
             best = id;
             best_cost = c;
@@ -223,6 +228,10 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     ConvKernelParams &k = pr->kp;
     k.tilesM = (k.K + ki.BM - 1) / ki.BM;
     k.tilesN = (k.NPQ + ki.BN - 1) / ki.BN;
+    const long long steps = kernel_steps(ki, k);
+    if (steps >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
+    k.ksteps = (int)steps;
+    k.tail_step = (ki.gmode == 1 && k.C % ki.BK != 0) ? (int)((long long)(k.C / ki.BK) * k.RS) : -1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     if (plan) {
@@ -231,7 +240,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         plan->tileN = ki.BN;
         plan->tileK = ki.BK;
         plan->gridX = k.tilesM * k.tilesN;
-        plan->kSteps = (k.CRS + ki.BK - 1) / ki.BK;
+        plan->kSteps = k.ksteps;
         plan->threads = ki.threads;
         plan->ldsBytes = ki.ldsBytes;
         plan->swapOperands = ki.swap ? 1 : 0;

@@ -60,16 +60,26 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
     return (__umulhi(n, m.mul) + n) >> m.shift;
 }
 
-// How the gather of the D_m tile finds, for one element (column j, index i), the offset
-// of x[n, c, h, w] and whether the tap lies inside the image.  On this chip fp32 MFMA
-// and ordinary vector instructions cannot overlap, so every vector instruction in the
-// loop is taken from the MFMA rate: the two fast modes need ONE per gathered element.
+// How the reduction index is ordered and how the gather of the D_m tile finds, for one
+// element (column j, index i), the offset of x[n,c,h,w] and whether the tap lies inside
+// the image.  What was measured on this chip and shapes these modes: fp32 MFMA and
+// ordinary vector instructions do not overlap (every vector instruction in the loop is
+// taken from the MFMA rate), a register move through the GPR index costs about 40
+// cycles, while scalar instructions and buffer loads whose address is a fixed vector
+// register plus a scalar offset cost nothing next to the MFMAs.
 enum GatherMode {
-    GATHER_GENERIC = 0,  // any R,S,pad: window test per element on packed 16-bit coordinates
-    GATHER_TAPS = 1,     // R*S <= kMaxTaps: per-column table of tap offsets built once per tile
-    GATHER_NOPAD = 2     // pad_h == pad_w == 0: every tap of a valid column is inside the image
+    // i = (c,r,s) in filter order; window test per element on packed 16-bit coordinates
+    // (about 7 vector instructions per element).  Any R, S, pad.
+    GATHER_GENERIC = 0,
+    // i = (channel chunk, tap, channel in chunk): a step covers ONE tap and BK
+    // consecutive channels, so the per-column offset and window test are computed once
+    // per step and each element is one load with a scalar channel offset.  Any R, S,
+    // pad; steps = R*S*ceil(C/BK), so it wants C to fill a chunk.
+    GATHER_TAPMAJOR = 1,
+    // i = (c,r,s) in filter order, pad_h = pad_w = 0: every tap of a valid column is
+    // inside the image, the whole tap offset is a scalar.  For small C.
+    GATHER_NOPAD = 2
 };
-constexpr int kMaxTaps = 9;
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
 struct KernelConfig {
@@ -96,6 +106,7 @@ struct KernelConfig {
     static_assert(BK % KG == 0 && KPT % VEC == 0, "k tile granularity");
     static_assert(VECA ? (BM * (BK / VEC)) % THREADS == 0 : (BM * BK) % THREADS == 0, "filter tile split");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
 };
 
 template <class Cfg>
@@ -157,32 +168,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     u16x2 hw_max;
     hw_max[1] = (uint16_t)(p.H - 1);
     hw_max[0] = (uint16_t)(p.W - 1);
-    // GATHER_TAPS: voff[t] = byte offset of tap t = r*S+s of this column in channel 0,
-    // or the out-of-range marker when the tap falls in the zero border; entry kMaxTaps
-    // is always out of range (used for indices beyond CRS).  GATHER_NOPAD: entry 0 is
-    // the window origin, entry 1 out of range.  The loop picks an entry with a
-    // wavefront-uniform index and adds the channel (resp. tap) offset as a scalar.
-    uint32_t voff[Cfg::GMODE == GATHER_TAPS ? kMaxTaps + 1 : 2];
-    if constexpr (Cfg::GMODE == GATHER_TAPS) {
-#pragma unroll
-        for (int t = 0; t < kMaxTaps; ++t) {
-            const uint32_t r = magic_div((uint32_t)t, p.mS);
-            const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
-            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-            u16x2 tap;
-            tap[1] = (uint16_t)tr;
-            tap[0] = (uint16_t)ts;
-            const u16x2 hw = hw0 + tap;
-            const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
-            const bool ok = t < p.RS && __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
-            voff[t] = ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
-        }
-        voff[kMaxTaps] = kOutOfRange;
-    } else {
-        voff[0] = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
-        voff[1] = kOutOfRange;
-    }
+    // GATHER_NOPAD: the window origin of a valid column, else the out-of-range marker.
+    const uint32_t vcol = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
 
     // ---- filter-tile role ----------------------------------------------------------
     constexpr int A_PASSES = Cfg::VECA ? (BM * (BK / VEC)) / 256 : (BM * BK) / 256;
@@ -200,21 +187,50 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // wavefront's run) + lane: byte offset of the tap relative to the window origin, and
     // the packed tap (tr,ts).
     uint32_t dec_il = 0, dec_c = 0, dec_rs = 0, dec_delta = 0, dec_tap = 0;
-    // GATHER_TAPS / GATHER_NOPAD: reduction index of the next element to gather,
-    // wavefront-uniform, kept (with everything derived from it) in scalar registers.
-    uint32_t sc_i = 0;
+    // GATHER_NOPAD: reduction index of the next element to gather; GATHER_TAPMAJOR:
+    // first channel of the step's chunk, the step's tap, and whether the step exists.
+    // All wavefront-uniform, kept (with everything derived from them) in scalar registers.
+    uint32_t sc_i = 0, sc_c0 = 0, sc_tr = 0, sc_ts = 0, sc_asoff = 0;
+    bool sc_live = false;
+    int sc_tau = 0;
+    // GATHER_TAPMAJOR: this column's offset for the step's tap, or the out-of-range
+    // marker when the tap falls in the zero border.
+    uint32_t vtap = kOutOfRange;
 
-    // i -> (c,r,s) for the tile that starts at reduction index k0.
-    auto decode1 = [&](int k0) {
+    // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
+    // reduction range.  The per-thread part of the offset is fixed, the step's part is a
+    // scalar.  Natural order: index k0 + a_kk of row `row`.  Tap-major: channel
+    // c0 + a_kk, tap of the step, i.e. a read with stride R*S elements.
+    uint32_t a_voff[A_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) {
+        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
+        const uint32_t col = Cfg::GMODE == GATHER_TAPMAJOR ? (uint32_t)a_kk * (uint32_t)p.RS : (uint32_t)a_kk;
+        a_voff[ps] = row < p.K ? ((uint32_t)row * (uint32_t)p.CRS + col) * ES : kOutOfRange;
+    }
+    // Start of the load of tile number tau (reduction step tau).
+    auto decode1 = [&](int tau) {
         if constexpr (Cfg::GMODE == GATHER_GENERIC) {
-            // lane L decodes index i0+L once for everybody, in two halves so that each
-            // fits between two MFMAs
-            dec_il = (uint32_t)(k0 + kpart * KPT) + (uint32_t)lane;
+            // i -> (c,r,s): lane L decodes index i0+L once for everybody, in two halves
+            // so that each fits between two MFMAs
+            dec_il = (uint32_t)(tau * BK + kpart * KPT) + (uint32_t)lane;
             dec_c = magic_div(dec_il, p.mRS);
             dec_rs = dec_il - dec_c * (uint32_t)p.RS;
-        } else {
+        } else if constexpr (Cfg::GMODE == GATHER_NOPAD) {
             // (readfirstlane states the wavefront-uniformity for the compiler)
-            sc_i = __builtin_amdgcn_readfirstlane((uint32_t)(k0 + kpart * KPT));
+            sc_i = __builtin_amdgcn_readfirstlane((uint32_t)(tau * BK + kpart * KPT));
+        } else {
+            const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)tau);
+            sc_tau = (int)ut;
+            const uint32_t cc = magic_div(ut, p.mRS);     // channel chunk
+            const uint32_t tap = ut - cc * (uint32_t)p.RS;  // r*S+s
+            const uint32_t r = magic_div(tap, p.mS);
+            const uint32_t sx = tap - r * (uint32_t)p.S;
+            sc_tr = p.flip ? (uint32_t)p.R - 1u - r : r;   // eq. 2 inverts the filter
+            sc_ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            sc_c0 = cc * BK;
+            sc_live = tau < p.ksteps;
+            sc_asoff = sc_live ? (sc_c0 * (uint32_t)p.RS + tap) * ES : 0u;
         }
     };
     auto decode2 = [&]() {
@@ -225,33 +241,54 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
             dec_delta = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
             dec_tap = dec_il < (uint32_t)p.CRS ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
+        } else if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
+            const u16x2 tap = __builtin_bit_cast(u16x2, (sc_tr << 16) | sc_ts);
+            const u16x2 hw = hw0 + tap;
+            const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+            const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+            vtap = ok ? colbase_b + (sc_tr * (uint32_t)p.xsH + sc_ts * (uint32_t)p.xsW) * ES : kOutOfRange;
+            // When C is not a multiple of BK the last channel chunk is ragged: on
+            // entering it (once per tile; the chunks are the outer order) the filter
+            // offsets of the channels beyond C are replaced by the out-of-range marker.
+            if (sc_tau == p.tail_step) {
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_voff[ps] = sc_c0 + (uint32_t)a_kk < (uint32_t)p.C ? a_voff[ps] : kOutOfRange;
+            }
         }
     };
-    // F_m tile: rows m0.., reduction indices k0..k0+BK-1; zero beyond K and CRS.  The
-    // per-thread part of the offset is fixed; the step adds k0 as a scalar.  (The scalar
-    // offset takes part in the hardware range check as "limit - scalar", so it must
-    // never exceed the extent: tiles beyond the last step use 0.)
-    uint32_t a_voff[A_PASSES];
-#pragma unroll
-    for (int ps = 0; ps < A_PASSES; ++ps) {
-        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
-        a_voff[ps] = row < p.K ? ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)a_kk) * ES : kOutOfRange;
-    }
-    auto load_a = [&](int set, int k0, int ps) {
-        const bool in = k0 + a_kk < p.CRS;
-        const uint32_t voffa = in ? a_voff[ps] : kOutOfRange;
-        const uint32_t soff = k0 < p.CRS ? (uint32_t)k0 * ES : 0u;
-        if constexpr (Cfg::VECA) {
-            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voffa, soff, 0);
-        } else if constexpr (Cfg::BF16) {
-            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voffa, soff, 0);
+    // A buffer descriptor that reads as zeros everywhere when `live` is false.  (The
+    // scalar offset of a load takes part in the hardware range check as "limit - scalar",
+    // so a dead load must also use scalar offset 0, and a live one never exceeds the
+    // extent.)
+    auto rsrc_if = [&](const void *ptr, uint32_t bytes, bool live) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ptr), 0, live ? bytes : 0u, kBufferWord3);
+    };
+    auto load_a = [&](int set, int tau, int ps) {
+        uint32_t voffa, soff;
+        bool live = true;
+        if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
+            voffa = a_voff[ps];  // (channels beyond C: masked in place by decode2)
+            soff = sc_asoff;
+            live = sc_live;
         } else {
-            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voffa, soff, 0));
+            const int k0 = tau * BK;
+            voffa = k0 + a_kk < p.CRS ? a_voff[ps] : kOutOfRange;
+            soff = k0 < p.CRS ? (uint32_t)k0 * ES : 0u;
+        }
+        const __amdgpu_buffer_rsrc_t wb = Cfg::GMODE == GATHER_TAPMAJOR ? rsrc_if(p.w, p.w_bytes, live) : wbuf;
+        if constexpr (Cfg::VECA) {
+            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wb, voffa, soff, 0);
+        } else if constexpr (Cfg::BF16) {
+            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wb, voffa, soff, 0);
+        } else {
+            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wb, voffa, soff, 0));
         }
     };
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) {
         uint32_t vo, so;
+        bool live = true;
         if constexpr (Cfg::GMODE == GATHER_GENERIC) {
             // takes lane e's decode as scalars
             const uint32_t d = __builtin_amdgcn_readlane(dec_delta, e);
@@ -261,29 +298,30 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
             vo = ok ? colbase_b + d : kOutOfRange;
             so = 0;
+        } else if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
+            // fixed vector offset for the whole step, channel offset as a scalar
+            const uint32_t c = sc_c0 + (uint32_t)(kpart * KPT + e);
+            live = sc_live && (int)c < p.C;
+            vo = vtap;
+            so = live ? c * (uint32_t)p.xsC * ES : 0u;
         } else {
-            // scalar decode of the running index; one register move picks the table
-            // entry; the rest of the offset is a scalar
+            // scalar decode of the running index: the whole tap offset is a scalar
             const uint32_t c = magic_div(sc_i, p.mRS);
-            const uint32_t rs = sc_i - c * (uint32_t)p.RS;  // tap number r*S+s
-            const bool in = (int)c < p.C;
+            const uint32_t rs = sc_i - c * (uint32_t)p.RS;
+            const uint32_t r = magic_div(rs, p.mS);
+            const uint32_t sx = rs - r * (uint32_t)p.S;
+            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            live = (int)c < p.C;
             ++sc_i;
-            if constexpr (Cfg::GMODE == GATHER_TAPS) {
-                vo = voff[in ? rs : (uint32_t)kMaxTaps];
-                so = in ? c * (uint32_t)p.xsC * ES : 0u;
-            } else {
-                const uint32_t r = magic_div(rs, p.mS);
-                const uint32_t sx = rs - r * (uint32_t)p.S;
-                const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-                const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-                vo = voff[in ? 0 : 1];
-                so = in ? (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : 0u;
-            }
+            vo = vcol;
+            so = live ? (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : 0u;
         }
+        const __amdgpu_buffer_rsrc_t xb = Cfg::GMODE == GATHER_GENERIC ? xbuf : rsrc_if(p.x, p.x_bytes, live);
         if constexpr (Cfg::BF16) {
-            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, vo, so, 0);
+            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xb, vo, so, 0);
         } else {
-            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, vo, so, 0));
+            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xb, vo, so, 0));
         }
     };
     auto write_a = [&](int set, int buf, int ps) {
@@ -314,10 +352,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // loads, gathered elements) and NW LDS-write items.
     constexpr int NW_A = A_PASSES, NW_B = KPT / VEC, NW = NW_A + NW_B;
     constexpr int NL = 2 + A_PASSES + KPT;
-    auto load_item = [&](int i, int set, int k0) {
-        if (i == 0) decode1(k0);
+    auto load_item = [&](int i, int set, int tau) {
+        if (i == 0) decode1(tau);
         else if (i == 1) decode2();
-        else if (i < 2 + A_PASSES) load_a(set, k0, i - 2);
+        else if (i < 2 + A_PASSES) load_a(set, tau, i - 2);
         else load_b(set, i - 2 - A_PASSES);
     };
     auto write_item = [&](int i, int set, int buf) {
@@ -398,7 +436,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // stage alternate.
     auto step = [&](auto parity, int t) {
         constexpr int cur = decltype(parity)::value, nxt = cur ^ 1;
-        const int k2 = (t + 2) * BK;
+        const int k2 = t + 2;  // number of the tile requested during this step
         static_for<NM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             constexpr int g = m / MPG, j = m % MPG;
@@ -422,10 +460,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         });
     };
 
-    const int ksteps = (p.CRS + BK - 1) / BK;
+    const int ksteps = p.ksteps;
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, 0); });
     static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
-    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, BK); });
+    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, 1); });
     lds_barrier();
     read_frags(0, 0);
     // Enter the loop with no load outstanding: otherwise the compiler, merging this path

@@ -11,9 +11,9 @@
     X("bf16 64x128x32 generic swap vecw", true, 64, 128, 32, 2, 2, true, true, GATHER_GENERIC) \
     X("bf16 128x128x32 generic swap", true, 128, 128, 32, 2, 2, true, false, GATHER_GENERIC) \
     X("bf16 128x128x32 generic swap vecw", true, 128, 128, 32, 2, 2, true, true, GATHER_GENERIC) \
-    X("bf16 128x128x32 taps", true, 128, 128, 32, 2, 2, false, false, GATHER_TAPS) \
-    X("bf16 128x128x32 taps vecw", true, 128, 128, 32, 2, 2, false, true, GATHER_TAPS) \
-    X("bf16 128x128x32 taps swap", true, 128, 128, 32, 2, 2, true, false, GATHER_TAPS) \
-    X("bf16 128x128x32 taps swap vecw", true, 128, 128, 32, 2, 2, true, true, GATHER_TAPS)
+    X("bf16 64x128x32 tapmajor", true, 64, 128, 32, 2, 2, false, false, GATHER_TAPMAJOR) \
+    X("bf16 128x128x32 tapmajor", true, 128, 128, 32, 2, 2, false, false, GATHER_TAPMAJOR) \
+    X("bf16 64x128x32 tapmajor swap", true, 64, 128, 32, 2, 2, true, false, GATHER_TAPMAJOR) \
+    X("bf16 128x128x32 tapmajor swap", true, 128, 128, 32, 2, 2, true, false, GATHER_TAPMAJOR)
 
 IGC_DEFINE_GROUP(kGroupBF16)

@@ -1,4 +1,4 @@
-// fp32 kernels (v_mfma_f32_32x32x2_f32), unpadded gather, NCHW-style epilogue.
+// fp32 kernels (v_mfma_f32_32x32x2_f32), unpadded gather in filter order, NCHW-style epilogue.
 #include "igconv_instantiate.hpp"
 
 //    name, bf16, BM, BN, BK, WM, WN, swap, veca, gather mode

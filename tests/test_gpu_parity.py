@@ -97,21 +97,38 @@ def test_every_kernel_variant():
 
 
 def test_gather_modes_are_chosen():
-    """R*S <= 9 -> tap table (padded or not); larger unpadded -> unpadded gather; larger
-    padded -> generic."""
-    import paper_1410_0759_amd as ig
-    x, w = wl.random_problem(3, 2, 4, 12, 12, 8, 3, 3)
-    _, plan = _check(x, w, (0, 0), (1, 1), 1, "f32", tag="mode taps, pad 0")
-    assert plan.gatherMode == 1
-    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode taps")
-    assert plan.gatherMode == 1
-    x, w = wl.random_problem(4, 2, 4, 12, 12, 8, 5, 5)
+    """Enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
+    filter order; few channels, padded -> generic."""
+    x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 3, 3)
+    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode tapmajor")
+    assert plan.gatherMode == 1 and plan.kSteps == 9
+    x, w = wl.random_problem(4, 2, 3, 12, 12, 8, 5, 5)
     _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad")
-    assert plan.gatherMode == 2
+    assert plan.gatherMode == 2 and plan.kSteps == 3
     _, plan = _check(x, w, (2, 2), (1, 1), 0, "f32", tag="mode generic")
     assert plan.gatherMode == 0
     _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode generic swap")
     assert plan.gatherMode == 0 and plan.swapOperands == 1
+
+
+def test_tapmajor_ragged_channel_chunks():
+    """Tap-major kernels with C below, equal to and above the chunk size, ragged or not,
+    including filters holding Inf in channels that a ragged chunk would otherwise touch."""
+    import paper_1410_0759_amd as ig
+    names = ig.kernel_names()
+    for name in ("f32 64x128x32 tapmajor", "f32 128x128x32 tapmajor swap", "bf16 128x128x32 tapmajor"):
+        kid = names.index(name)
+        dtype = "bf16" if name.startswith("bf16") else "f32"
+        lay = "NHWC" if "swap" in name else "NCHW"
+        for C in (1, 7, 32, 33, 48, 64, 70):
+            x, w = wl.random_problem(100 + C, 2, C, 9, 10, 40, 3, 2, dtype=dtype)
+            _check(x, w, (1, 1), (1, 1), 1, dtype, kernel=kid, y_layout=lay, tag=name)
+            _check(x, w, (0, 1), (2, 1), 0, dtype, kernel=kid, y_layout=lay, tag=name)
+    # a huge weight right after a ragged row must not leak into the previous filter
+    x, w = wl.random_problem(5, 1, 33, 6, 6, 3, 1, 1)
+    w[1, 0, 0, 0] = np.float32(3.0e38)
+    x[:, 0] = 0.0
+    _check(x, w, (0, 0), (1, 1), 1, "f32", kernel=names.index("f32 64x128x32 tapmajor"), tag="big neighbour")
 
 
 # ------------------------------------------------------------------ layouts through strides
