@@ -167,12 +167,12 @@ typedef struct {
     int tileN;       /* columns of O_m (output pixels n,p,q) per workgroup */
     int tileK;       /* reduction elements (c,r,s) per step */
     int gridX;       /* workgroups launched */
-    int kSteps;      /* reduction steps: ceil(CRS / tileK), or R*S*ceil(C / tileK) in tap-major order */
+    int kSteps;      /* reduction steps: ceil(CRS / tileK); R*S*ceil(C / tileK) in tap-major order */
     int threads;     /* threads per workgroup */
     int ldsBytes;    /* LDS per workgroup */
     int swapOperands;/* 1 when lanes run along k in the epilogue (y's c-stride is 1) */
     int vecFilterLoads; /* 1 when filter rows are fetched with 16-byte loads */
-    int gatherMode;  /* 0 generic window test, 1 tap-major reduction order, 2 unpadded */
+    int gatherMode;  /* 0 generic window test, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table */
 } igcConvolutionForwardPlan;
 
 igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle,

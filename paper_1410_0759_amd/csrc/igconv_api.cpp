@@ -40,7 +40,7 @@ namespace igc {
 constexpr int kComputeUnits = 256;
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
-static const KernelGroup *const kGroups[] = {&kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
+static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
                                             &kGroupBF16};
 
 int kernel_count() {
@@ -167,6 +167,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 // chunks of BK, or tap-major: per tap, the channels in chunks of BK.
 static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
+    if (ki.gmode == 3) return k.C / (ki.BK / 9);
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
@@ -182,14 +183,16 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
     const double mfma = (double)ki.BM * ki.BN * ki.BK;
     const double traffic = 48.0 * (ki.BM + ki.BN) * ki.BK;
-    const double mode = ki.gmode == 0 ? 1.6 : (ki.gmode == 2 ? 1.1 : 1.0);
+    const double mode = ki.gmode == 0 ? 1.6 : (ki.gmode == 1 ? 1.15 : (ki.gmode == 2 ? 1.1 : 1.0));
     return (double)rounds * steps * (mfma + traffic) * mode;
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded
-// mode needs pad 0; the generic and the tap-major modes always work.
+// mode needs pad 0, the nine-tap table R*S = 9 and whole steps of four channels; the
+// generic and the tap-major modes always work.
 static bool gather_mode_ok(int gmode, const ConvKernelParams &k) {
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
+    if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
     return true;
 }
 

@@ -41,6 +41,7 @@ using f32x4 = float __attribute__((ext_vector_type(4)));
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
 using u16x2 = uint16_t __attribute__((ext_vector_type(2)));
+using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kBufferWord3 = 0x00020000u;  // raw buffer, 32-bit data format
 constexpr uint32_t kOutOfRange = 0x80000000u;   // >= any extent this library accepts
@@ -56,6 +57,15 @@ __device__ __forceinline__ void static_for(F &&f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// All-ones when a < b, else 0, for 0 <= a, b < 2^31, with integer arithmetic only.
+// Wavefront-uniform conditions of the loop are applied as such masks (x & mask) rather
+// than as c ? x : 0: a select may become a branch around the computation of x, and a
+// branch would split the loop body into blocks, while the pipelined schedule (and the
+// compiler's tracking of outstanding loads) relies on it being a single one.
+__device__ __forceinline__ uint32_t mask_lt(uint32_t a, uint32_t b) {
+    return (uint32_t)((int32_t)(a - b) >> 31);
+}
+
 __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
     return (__umulhi(n, m.mul) + n) >> m.shift;
 }
@@ -64,21 +74,30 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
 // element (column j, index i), the offset of x[n,c,h,w] and whether the tap lies inside
 // the image.  What was measured on this chip and shapes these modes: fp32 MFMA and
 // ordinary vector instructions do not overlap (every vector instruction in the loop is
-// taken from the MFMA rate), a register move through the GPR index costs about 40
-// cycles, while scalar instructions and buffer loads whose address is a fixed vector
-// register plus a scalar offset cost nothing next to the MFMAs.
+// taken from the MFMA rate); a register move through the GPR index costs about 40
+// cycles; a wavefront issues in order, so whatever sits between two MFMAs - scalar
+// instructions included - must fit in the 64 cycles one MFMA takes (about ten
+// instructions), or the MFMA pipe idles; a buffer load whose address is a fixed vector
+// register plus a scalar offset is one instruction.  So every fast mode gathers an
+// element with a load from a loop-invariant (or per-step) vector offset plus a scalar
+// offset, and zero-fills by making that sum fall outside the buffer.
 enum GatherMode {
     // i = (c,r,s) in filter order; window test per element on packed 16-bit coordinates
-    // (about 7 vector instructions per element).  Any R, S, pad.
+    // (about 7 vector instructions per element).  Any R, S, pad, C.
     GATHER_GENERIC = 0,
     // i = (channel chunk, tap, channel in chunk): a step covers ONE tap and BK
-    // consecutive channels, so the per-column offset and window test are computed once
-    // per step and each element is one load with a scalar channel offset.  Any R, S,
-    // pad; steps = R*S*ceil(C/BK), so it wants C to fill a chunk.
+    // consecutive channels; the per-column offset and window test are computed once per
+    // step.  Any R, S, pad; steps = R*S*ceil(C/BK), so it wants C to fill a chunk, and
+    // its filter reads are strided.
     GATHER_TAPMAJOR = 1,
     // i = (c,r,s) in filter order, pad_h = pad_w = 0: every tap of a valid column is
-    // inside the image, the whole tap offset is a scalar.  For small C.
-    GATHER_NOPAD = 2
+    // inside the image, the whole tap offset is a scalar.  Any R, S, C.
+    GATHER_NOPAD = 2,
+    // i = (c,r,s) in filter order with R*S = 9 and C a multiple of 4: a step is four
+    // whole channels (BK = 36), so which tap an element has never changes; the nine
+    // per-column tap offsets (window test folded in) are built once per tile and the
+    // loop holds no vector instruction at all.  Any pad, stride, mode.
+    GATHER_TAPS9 = 3
 };
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
@@ -91,8 +110,11 @@ struct KernelConfig {
     static constexpr int THREADS = 256;
     static constexpr int ESIZE = BF16 ? 2 : 4;
     static constexpr int VEC = 16 / ESIZE;           // elements per 16-byte LDS access
-    static constexpr int KG = 2 * VEC;               // reduction elements per k-group
-    static constexpr int LD = BK + VEC;              // LDS row stride in elements
+    static constexpr int KG = 2 * VEC;               // reduction elements per full k-group
+    // LDS row stride: at least BK plus 16 bytes, and an odd number of 16-byte units, so
+    // that 16-byte accesses of consecutive rows fall on distinct banks
+    static constexpr int LDV = (BK / VEC + 1) | 1;
+    static constexpr int LD = LDV * VEC;
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
     static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE;
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
@@ -100,13 +122,16 @@ struct KernelConfig {
     static constexpr int CG = BN / 64;               // column groups of 64 lanes
     static constexpr int KPARTS = 4 / CG;            // wavefronts sharing one column group
     static constexpr int KPT = BK / KPARTS;          // reduction indices gathered per thread
+    static constexpr int REM = BK % KG;              // elements of a last, partial k-group
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave blocks are 32x32 multiples");
     static_assert(BN == 64 || BN == 128 || BN == 256, "column tile is 1, 2 or 4 wavefronts wide");
-    static_assert(BK % KG == 0 && KPT % VEC == 0, "k tile granularity");
-    static_assert(VECA ? (BM * (BK / VEC)) % THREADS == 0 : (BM * BK) % THREADS == 0, "filter tile split");
+    static_assert(BK % VEC == 0 && BK % KPARTS == 0 && KPT % 2 == 0, "k tile granularity");
+    static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
+    static_assert(VECA || (BM * BK) % THREADS == 0, "scalar filter tile split");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
+    static_assert(GMODE != GATHER_TAPS9 || (VECA && BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
 template <class Cfg>
@@ -114,6 +139,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LD = Cfg::LD;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
+    constexpr int GM = Cfg::GMODE;
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
@@ -168,14 +194,43 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     u16x2 hw_max;
     hw_max[1] = (uint16_t)(p.H - 1);
     hw_max[0] = (uint16_t)(p.W - 1);
+    // Byte offset of tap (tr, ts) of this column in channel 0, or the out-of-range marker
+    // when the tap falls in the zero border (or the column is beyond NPQ).
+    auto tap_offset = [&](uint32_t tr, uint32_t ts) -> uint32_t {
+        const u16x2 tap = __builtin_bit_cast(u16x2, (tr << 16) | ts);
+        const u16x2 hw = hw0 + tap;
+        const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
+        const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
+        return ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
+    };
     // GATHER_NOPAD: the window origin of a valid column, else the out-of-range marker.
     const uint32_t vcol = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
+    // GATHER_TAPS9: the nine tap offsets of this column (tap t = r*3+s... in general
+    // r*S+s with R*S = 9), eq. 2's inversion applied.
+    uint32_t vtaps[GM == GATHER_TAPS9 ? 9 : 1];
+    if constexpr (GM == GATHER_TAPS9) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const uint32_t r = magic_div((uint32_t)t, p.mS);
+            const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
+            vtaps[t] = tap_offset(p.flip ? (uint32_t)p.R - 1u - r : r, p.flip ? (uint32_t)p.S - 1u - sx : sx);
+        }
+    }
 
     // ---- filter-tile role ----------------------------------------------------------
-    constexpr int A_PASSES = Cfg::VECA ? (BM * (BK / VEC)) / 256 : (BM * BK) / 256;
-    constexpr int A_ROWS_PER_PASS = Cfg::VECA ? 256 / (BK / VEC) : 256 / BK;
-    const int a_row = Cfg::VECA ? tid / (BK / VEC) : tid / BK;
-    const int a_kk = Cfg::VECA ? (tid % (BK / VEC)) * VEC : tid % BK;
+    // 16-byte path: the tile is BM rows of BK/VEC vectors, dealt to the threads in order;
+    // the last pass may be partial.  Scalar path: BM*BK elements, BK a power of two.
+    constexpr int A_VPR = BK / VEC;  // vectors per row
+    constexpr int A_TOTAL = Cfg::VECA ? BM * A_VPR : BM * BK;
+    constexpr int A_PASSES = (A_TOTAL + 255) / 256;
+    constexpr bool A_PARTIAL = A_TOTAL % 256 != 0;
+    int a_row[A_PASSES], a_kk[A_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) {
+        const int idx = tid + ps * 256;
+        a_row[ps] = Cfg::VECA ? idx / A_VPR : idx / BK;
+        a_kk[ps] = Cfg::VECA ? (idx % A_VPR) * VEC : idx % BK;
+    }
 
     // Registers holding the tiles in flight between HBM and LDS: two sets, tile T uses
     // set T&1, so that the loads of tile t+2 can be issued while tile t+1 still waits
@@ -183,174 +238,173 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     u32x4 a_vec[2][Cfg::VECA ? A_PASSES : 1];
     elem_t a_sca[2][Cfg::VECA ? 1 : A_PASSES];
     elem_t b_val[2][KPT];
-    // GATHER_GENERIC: per-lane decode of reduction index (first index of this
-    // wavefront's run) + lane: byte offset of the tap relative to the window origin, and
-    // the packed tap (tr,ts).
-    uint32_t dec_il = 0, dec_c = 0, dec_rs = 0, dec_delta = 0, dec_tap = 0;
-    // GATHER_NOPAD: reduction index of the next element to gather; GATHER_TAPMAJOR:
-    // first channel of the step's chunk, the step's tap, and whether the step exists.
-    // All wavefront-uniform, kept (with everything derived from them) in scalar registers.
-    uint32_t sc_i = 0, sc_c0 = 0, sc_tr = 0, sc_ts = 0, sc_asoff = 0;
-    bool sc_live = false;
+    // Per-lane decode, lane L standing for element L of this wavefront's run of the
+    // step.  GATHER_GENERIC: byte offset of the tap relative to the window origin
+    // (dec_so) and the packed tap (dec_tap).  GATHER_NOPAD / GATHER_TAPMAJOR: the
+    // element's scalar offset, or the buffer size if the element does not exist (the
+    // hardware compares the vector offset with "size - scalar offset": a scalar offset
+    // equal to the size puts every lane out of range, a larger one would wrap).
+    uint32_t dec_il = 0, dec_c = 0, dec_rs = 0, dec_so = 0, dec_tap = 0;
+    // GATHER_TAPMAJOR: the step's tap; this column's offset for it; the filter's scalar
+    // offset.  GATHER_TAPS9: the scalar offsets of the channels this thread gathers.
+    uint32_t sc_tr = 0, sc_ts = 0, sc_c0 = 0, sc_asoff = 0;
     int sc_tau = 0;
-    // GATHER_TAPMAJOR: this column's offset for the step's tap, or the out-of-range
-    // marker when the tap falls in the zero border.
     uint32_t vtap = kOutOfRange;
+    uint32_t sc_cso[GM == GATHER_TAPS9 ? KPT / 9 : 1];
 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
     // reduction range.  The per-thread part of the offset is fixed, the step's part is a
-    // scalar.  Natural order: index k0 + a_kk of row `row`.  Tap-major: channel
+    // scalar.  Filter order: index k0 + a_kk of row `row`.  Tap-major: channel
     // c0 + a_kk, tap of the step, i.e. a read with stride R*S elements.
     uint32_t a_voff[A_PASSES];
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps) {
-        const int row = m0 + a_row + ps * A_ROWS_PER_PASS;
-        const uint32_t col = Cfg::GMODE == GATHER_TAPMAJOR ? (uint32_t)a_kk * (uint32_t)p.RS : (uint32_t)a_kk;
-        a_voff[ps] = row < p.K ? ((uint32_t)row * (uint32_t)p.CRS + col) * ES : kOutOfRange;
+        const int row = m0 + a_row[ps];
+        const uint32_t col = GM == GATHER_TAPMAJOR ? (uint32_t)a_kk[ps] * (uint32_t)p.RS : (uint32_t)a_kk[ps];
+        const bool ok = row < p.K && a_row[ps] < BM;
+        a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.CRS + col) * ES : kOutOfRange;
     }
-    // Start of the load of tile number tau (reduction step tau).
+
+    // Start of the load of tile number tau (reduction step tau), in two halves so that
+    // each fits between two MFMAs.
     auto decode1 = [&](int tau) {
-        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
-            // i -> (c,r,s): lane L decodes index i0+L once for everybody, in two halves
-            // so that each fits between two MFMAs
+        if constexpr (GM == GATHER_GENERIC || GM == GATHER_NOPAD) {
+            // i -> (c, r*S+s) for i = first index of the run + lane
             dec_il = (uint32_t)(tau * BK + kpart * KPT) + (uint32_t)lane;
             dec_c = magic_div(dec_il, p.mRS);
             dec_rs = dec_il - dec_c * (uint32_t)p.RS;
-        } else if constexpr (Cfg::GMODE == GATHER_NOPAD) {
+        } else if constexpr (GM == GATHER_TAPMAJOR) {
             // (readfirstlane states the wavefront-uniformity for the compiler)
-            sc_i = __builtin_amdgcn_readfirstlane((uint32_t)(tau * BK + kpart * KPT));
-        } else {
             const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)tau);
             sc_tau = (int)ut;
-            const uint32_t cc = magic_div(ut, p.mRS);     // channel chunk
+            const uint32_t cc = magic_div(ut, p.mRS);       // channel chunk
             const uint32_t tap = ut - cc * (uint32_t)p.RS;  // r*S+s
             const uint32_t r = magic_div(tap, p.mS);
             const uint32_t sx = tap - r * (uint32_t)p.S;
-            sc_tr = p.flip ? (uint32_t)p.R - 1u - r : r;   // eq. 2 inverts the filter
+            sc_tr = p.flip ? (uint32_t)p.R - 1u - r : r;    // eq. 2 inverts the filter
             sc_ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
             sc_c0 = cc * BK;
-            sc_live = tau < p.ksteps;
-            sc_asoff = sc_live ? (sc_c0 * (uint32_t)p.RS + tap) * ES : 0u;
+            const uint32_t live = mask_lt(ut, (uint32_t)p.ksteps);
+            sc_asoff = (((sc_c0 * (uint32_t)p.RS + tap) * ES) & live) | (p.w_bytes & ~live);
+            const uint32_t c = sc_c0 + (uint32_t)(kpart * KPT) + (uint32_t)lane;
+            dec_so = (c < (uint32_t)p.C && live) ? c * (uint32_t)p.xsC * ES : p.x_bytes;
+        } else {
+            const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)tau);
+            const uint32_t live = mask_lt(ut, (uint32_t)p.ksteps);
+            sc_asoff = ((ut * BK * ES) & live) | (p.w_bytes & ~live);
+            const uint32_t c = ut * (BK / 9) + (uint32_t)(kpart * (KPT / 9));
+#pragma unroll
+            for (int q = 0; q < KPT / 9; ++q)
+                sc_cso[q] = (((c + q) * (uint32_t)p.xsC * ES) & live) | (p.x_bytes & ~live);
         }
     };
     auto decode2 = [&]() {
-        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
+        if constexpr (GM == GATHER_GENERIC || GM == GATHER_NOPAD) {
             const uint32_t r = magic_div(dec_rs, p.mS);
             const uint32_t sx = dec_rs - r * (uint32_t)p.S;
             const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
             const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-            dec_delta = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
-            dec_tap = dec_il < (uint32_t)p.CRS ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
-        } else if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
-            const u16x2 tap = __builtin_bit_cast(u16x2, (sc_tr << 16) | sc_ts);
-            const u16x2 hw = hw0 + tap;
-            const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
-            const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
-            vtap = ok ? colbase_b + (sc_tr * (uint32_t)p.xsH + sc_ts * (uint32_t)p.xsW) * ES : kOutOfRange;
+            const uint32_t so = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+            const bool live = dec_il < (uint32_t)p.CRS;
+            if constexpr (GM == GATHER_GENERIC) {
+                dec_so = so;
+                dec_tap = live ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
+            } else {
+                dec_so = live ? so : p.x_bytes;
+            }
+        } else if constexpr (GM == GATHER_TAPMAJOR) {
+            vtap = tap_offset(sc_tr, sc_ts);
             // When C is not a multiple of BK the last channel chunk is ragged: on
             // entering it (once per tile; the chunks are the outer order) the filter
             // offsets of the channels beyond C are replaced by the out-of-range marker.
             if (sc_tau == p.tail_step) {
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps)
-                    a_voff[ps] = sc_c0 + (uint32_t)a_kk < (uint32_t)p.C ? a_voff[ps] : kOutOfRange;
+                    a_voff[ps] = sc_c0 + (uint32_t)a_kk[ps] < (uint32_t)p.C ? a_voff[ps] : kOutOfRange;
             }
         }
     };
-    // A buffer descriptor that reads as zeros everywhere when `live` is false.  (The
-    // scalar offset of a load takes part in the hardware range check as "limit - scalar",
-    // so a dead load must also use scalar offset 0, and a live one never exceeds the
-    // extent.)
-    auto rsrc_if = [&](const void *ptr, uint32_t bytes, bool live) {
-        return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ptr), 0, live ? bytes : 0u, kBufferWord3);
-    };
     auto load_a = [&](int set, int tau, int ps) {
-        uint32_t voffa, soff;
-        bool live = true;
-        if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
-            voffa = a_voff[ps];  // (channels beyond C: masked in place by decode2)
-            soff = sc_asoff;
-            live = sc_live;
+        uint32_t voffa = a_voff[ps], soff;
+        if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
+            soff = sc_asoff;  // (TAPS9: C % 4 == 0, so a row never ends inside a step)
         } else {
             const int k0 = tau * BK;
-            voffa = k0 + a_kk < p.CRS ? a_voff[ps] : kOutOfRange;
-            soff = k0 < p.CRS ? (uint32_t)k0 * ES : 0u;
+            voffa = k0 + a_kk[ps] < p.CRS ? voffa : kOutOfRange;
+            soff = k0 < p.CRS ? (uint32_t)k0 * ES : p.w_bytes;
         }
-        const __amdgpu_buffer_rsrc_t wb = Cfg::GMODE == GATHER_TAPMAJOR ? rsrc_if(p.w, p.w_bytes, live) : wbuf;
         if constexpr (Cfg::VECA) {
-            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wb, voffa, soff, 0);
+            a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voffa, soff, 0);
         } else if constexpr (Cfg::BF16) {
-            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wb, voffa, soff, 0);
+            a_sca[set][ps] = __builtin_amdgcn_raw_buffer_load_b16(wbuf, voffa, soff, 0);
         } else {
-            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wb, voffa, soff, 0));
+            a_sca[set][ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wbuf, voffa, soff, 0));
         }
     };
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) {
         uint32_t vo, so;
-        bool live = true;
-        if constexpr (Cfg::GMODE == GATHER_GENERIC) {
-            // takes lane e's decode as scalars
-            const uint32_t d = __builtin_amdgcn_readlane(dec_delta, e);
+        if constexpr (GM == GATHER_GENERIC) {
+            // lane e's decode as scalars, then the window test
+            const uint32_t d = __builtin_amdgcn_readlane(dec_so, e);
             const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
             const u16x2 hw = hw0 + tap;
             const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
             const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
             vo = ok ? colbase_b + d : kOutOfRange;
             so = 0;
-        } else if constexpr (Cfg::GMODE == GATHER_TAPMAJOR) {
-            // fixed vector offset for the whole step, channel offset as a scalar
-            const uint32_t c = sc_c0 + (uint32_t)(kpart * KPT + e);
-            live = sc_live && (int)c < p.C;
+        } else if constexpr (GM == GATHER_TAPMAJOR) {
             vo = vtap;
-            so = live ? c * (uint32_t)p.xsC * ES : 0u;
-        } else {
-            // scalar decode of the running index: the whole tap offset is a scalar
-            const uint32_t c = magic_div(sc_i, p.mRS);
-            const uint32_t rs = sc_i - c * (uint32_t)p.RS;
-            const uint32_t r = magic_div(rs, p.mS);
-            const uint32_t sx = rs - r * (uint32_t)p.S;
-            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
-            live = (int)c < p.C;
-            ++sc_i;
+            so = __builtin_amdgcn_readlane(dec_so, e);
+        } else if constexpr (GM == GATHER_NOPAD) {
             vo = vcol;
-            so = live ? (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : 0u;
-        }
-        const __amdgpu_buffer_rsrc_t xb = Cfg::GMODE == GATHER_GENERIC ? xbuf : rsrc_if(p.x, p.x_bytes, live);
-        if constexpr (Cfg::BF16) {
-            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xb, vo, so, 0);
+            so = __builtin_amdgcn_readlane(dec_so, e);
         } else {
-            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xb, vo, so, 0));
+            vo = vtaps[e % 9];
+            so = sc_cso[e / 9];
+        }
+        if constexpr (Cfg::BF16) {
+            b_val[set][e] = __builtin_amdgcn_raw_buffer_load_b16(xbuf, vo, so, 0);
+        } else {
+            b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, vo, so, 0));
         }
     };
     auto write_a = [&](int set, int buf, int ps) {
-        elem_t *const A = ldsA + buf * Cfg::A_ELEMS;
-        const int row = a_row + ps * A_ROWS_PER_PASS;
+        elem_t *const A = ldsA + buf * Cfg::A_ELEMS + a_row[ps] * LD + a_kk[ps];
+        if (A_PARTIAL && ps == A_PASSES - 1 && a_row[ps] >= BM) return;  // threads beyond the tile
         if constexpr (Cfg::VECA) {
-            *reinterpret_cast<u32x4 *>(A + row * LD + a_kk) = a_vec[set][ps];
+            *reinterpret_cast<u32x4 *>(A) = a_vec[set][ps];
         } else {
-            A[row * LD + a_kk] = a_sca[set][ps];
+            *A = a_sca[set][ps];
         }
     };
-    // 16-byte chunk q of this lane's run of the D_m tile.
+    // Chunk q of this lane's run of the D_m tile: 16 bytes, or 8 where the run does not
+    // start on a 16-byte boundary.
+    constexpr bool B_W16 = (KPT * ES) % 16 == 0;
+    constexpr int B_WE = B_W16 ? VEC : VEC / 2;  // elements per write
     auto write_b = [&](int set, int buf, int q) {
-        elem_t *const dst = ldsB + buf * Cfg::B_ELEMS + jl * LD + kpart * KPT + q * VEC;
-        u32x4 v;
+        elem_t *const dst = ldsB + buf * Cfg::B_ELEMS + jl * LD + kpart * KPT + q * B_WE;
+        uint32_t v[4];
         if constexpr (Cfg::BF16) {
 #pragma unroll
-            for (int d = 0; d < 4; ++d)
-                v[d] = (uint32_t)b_val[set][q * VEC + 2 * d] | ((uint32_t)b_val[set][q * VEC + 2 * d + 1] << 16);
+            for (int d = 0; d < B_WE / 2; ++d)
+                v[d] = (uint32_t)b_val[set][q * B_WE + 2 * d] | ((uint32_t)b_val[set][q * B_WE + 2 * d + 1] << 16);
         } else {
 #pragma unroll
-            for (int d = 0; d < 4; ++d) v[d] = __builtin_bit_cast(uint32_t, b_val[set][q * VEC + d]);
+            for (int d = 0; d < B_WE; ++d) v[d] = __builtin_bit_cast(uint32_t, b_val[set][q * B_WE + d]);
         }
-        *reinterpret_cast<u32x4 *>(dst) = v;
+        if constexpr (B_W16) {
+            u32x4 o = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<u32x4 *>(dst) = o;
+        } else {
+            u32x2 o = {v[0], v[1]};
+            *reinterpret_cast<u32x2 *>(dst) = o;
+        }
     };
 
     // Moving one tile is a list of small items: NL load items (decode halves, filter
     // loads, gathered elements) and NW LDS-write items.
-    constexpr int NW_A = A_PASSES, NW_B = KPT / VEC, NW = NW_A + NW_B;
+    constexpr int NW_A = A_PASSES, NW_B = KPT / B_WE, NW = NW_A + NW_B;
     constexpr int NL = 2 + A_PASSES + KPT;
     auto load_item = [&](int i, int set, int tau) {
         if (i == 0) decode1(tau);
@@ -374,31 +428,54 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    constexpr int G = BK / KG;                          // k-groups per step
-    constexpr int EPG = Cfg::BF16 ? 1 : 4;              // MFMAs per (block, k-group)
-    constexpr int MPG = EPG * MB * NB;                  // MFMAs per k-group
-    constexpr int NM = G * MPG;                         // MFMAs per step
-    static_assert(G % 2 == 0, "operand fragments alternate between two register sets");
-    constexpr int SB = (G - 1) * MPG;                   // the step's barrier sits before MFMA number SB
-    // Operand fragments: 16 bytes of k per lane and 32-row block, two sets (k-group
-    // parity) so that the next group's fragments load while this group multiplies.
+    // A step's BK reduction elements are fed to the MFMAs in k-groups: a full group is
+    // 16 bytes of k per lane (the two halves of the wavefront hold different k), i.e. four
+    // fp32 MFMAs (one bf16 MFMA) per 32x32 block; a last group of half that size takes
+    // 8 bytes per lane.
+    constexpr int G_FULL = BK / KG, REM = Cfg::REM, G = G_FULL + (REM ? 1 : 0);
+    constexpr int EPG_FULL = Cfg::BF16 ? 1 : 4, EPG_LAST = REM ? REM / 2 : EPG_FULL;
+    constexpr int MPG_FULL = EPG_FULL * MB * NB, MPG_LAST = EPG_LAST * MB * NB;
+    constexpr int NM = G_FULL * MPG_FULL + (REM ? MPG_LAST : 0);  // MFMAs per step
+    constexpr int SB = NM - MPG_LAST;                             // first MFMA of the last group
+    // Operand fragments in two register sets, alternating from group to group (and on
+    // across steps when G is odd), so that the next group's fragments load while this
+    // group multiplies.
     u32x4 fragA[2][MB], fragB[2][NB];
-    const int fa_off = (wm * Cfg::TM + l32) * LD + half * VEC;
-    const int fb_off = (wn * Cfg::TN + l32) * LD + half * VEC;
-    auto read_frags = [&](int buf, int g) {
-        const elem_t *const A = ldsA + buf * Cfg::A_ELEMS + fa_off + g * KG;
-        const elem_t *const B = ldsB + buf * Cfg::B_ELEMS + fb_off + g * KG;
+    const int fa_off = (wm * Cfg::TM + l32) * LD;
+    const int fb_off = (wn * Cfg::TN + l32) * LD;
+    auto read_frags = [&](int buf, int g, int fs) {
+        const bool full = g < G_FULL;
+        const int koff = full ? g * KG + half * VEC : G_FULL * KG + half * (REM / 2);
+        const elem_t *const A = ldsA + buf * Cfg::A_ELEMS + fa_off + koff;
+        const elem_t *const B = ldsB + buf * Cfg::B_ELEMS + fb_off + koff;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) fragA[g & 1][mb] = *reinterpret_cast<const u32x4 *>(A + mb * 32 * LD);
+        for (int mb = 0; mb < MB; ++mb) {
+            if (full) {
+                fragA[fs][mb] = *reinterpret_cast<const u32x4 *>(A + mb * 32 * LD);
+            } else {
+                const u32x2 t2 = *reinterpret_cast<const u32x2 *>(A + mb * 32 * LD);
+                fragA[fs][mb][0] = t2[0];
+                fragA[fs][mb][1] = t2[1];
+            }
+        }
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) fragB[g & 1][nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD);
+        for (int nb = 0; nb < NB; ++nb) {
+            if (full) {
+                fragB[fs][nb] = *reinterpret_cast<const u32x4 *>(B + nb * 32 * LD);
+            } else {
+                const u32x2 t2 = *reinterpret_cast<const u32x2 *>(B + nb * 32 * LD);
+                fragB[fs][nb][0] = t2[0];
+                fragB[fs][nb][1] = t2[1];
+            }
+        }
     };
-    // MFMA number j of k-group g.  Consecutive MFMAs go to different accumulators.
-    auto mfma = [&](int g, int j) {
+    // MFMA number j of a k-group whose fragments sit in set fs.  Consecutive MFMAs go to
+    // different accumulators.
+    auto mfma = [&](int fs, int j) {
         const int e = j / (MB * NB), mb = (j / NB) % MB, nb = j % NB;
         if constexpr (Cfg::BF16) {
-            const bf16x8 fa = __builtin_bit_cast(bf16x8, fragA[g & 1][mb]);
-            const bf16x8 fb = __builtin_bit_cast(bf16x8, fragB[g & 1][nb]);
+            const bf16x8 fa = __builtin_bit_cast(bf16x8, fragA[fs][mb]);
+            const bf16x8 fb = __builtin_bit_cast(bf16x8, fragB[fs][nb]);
             if constexpr (Cfg::SWAP)
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[mb][nb], 0, 0, 0);
             else
@@ -406,8 +483,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         } else {
             // (whole-vector casts: a bit_cast applied to a single vector element reads
             // element 0 with this compiler)
-            const f32x4 va = __builtin_bit_cast(f32x4, fragA[g & 1][mb]);
-            const f32x4 vb = __builtin_bit_cast(f32x4, fragB[g & 1][nb]);
+            const f32x4 va = __builtin_bit_cast(f32x4, fragA[fs][mb]);
+            const f32x4 vb = __builtin_bit_cast(f32x4, fragB[fs][nb]);
             if constexpr (Cfg::SWAP)
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(vb[e], va[e], acc[mb][nb], 0, 0, 0);
             else
@@ -436,14 +513,17 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // stage alternate.
     auto step = [&](auto parity, int t) {
         constexpr int cur = decltype(parity)::value, nxt = cur ^ 1;
+        constexpr int fs0 = (G & 1) ? cur : 0;  // fragment set of this step's group 0
         const int k2 = t + 2;  // number of the tile requested during this step
         static_for<NM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
-            constexpr int g = m / MPG, j = m % MPG;
-            if constexpr (j == 0 && g + 1 < G) read_frags(cur, g + 1);
+            constexpr int g = m / MPG_FULL < G - 1 ? m / MPG_FULL : G - 1;
+            constexpr int j = m - g * MPG_FULL;
+            constexpr int fs = (fs0 + g) & 1;
+            if constexpr (j == 0 && g + 1 < G) read_frags(cur, g + 1, fs ^ 1);
             if constexpr (m == SB) {
                 lds_barrier();
-                read_frags(nxt, 0);
+                read_frags(nxt, 0, fs ^ 1);
             }
             // load items i with floor(i * NM / NL) == m: tile t+2 -> set cur
             constexpr int l0 = (m * NL + NM - 1) / NM, l1 = ((m + 1) * NL + NM - 1) / NM;
@@ -455,7 +535,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
                 constexpr int w0 = (q * NW + WS - 1) / WS, w1 = ((q + 1) * NW + WS - 1) / WS;
                 static_for<w1 - w0>([&](auto ic) { write_item(w0 + decltype(ic)::value, nxt, nxt); });
             }
-            mfma(g, j);
+            mfma(fs, j);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -465,7 +545,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, 1); });
     lds_barrier();
-    read_frags(0, 0);
+    read_frags(0, 0, 0);
     // Enter the loop with no load outstanding: otherwise the compiler, merging this path
     // with the loop's back edge, waits for every load at the top of each step.
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)

@@ -77,12 +77,22 @@ def test_every_kernel_variant():
         vec = "vecw" in name
         swap = "swap" in name
         nopad = "nopad" in name
+        taps9 = "taps9" in name
         vecn = 8 if dtype == "bf16" else 4
-        for (N, C, H, W, K, R, S, pad, stride) in [
+        problems = [
             (3, 8 if vec else 5, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
             (2, 16 if vec else 3, 21, 9, 45, 2, 2 if vec else 3, (0, 1), (2, 1)),
             (2, 24 if vec else 13, 9, 11, 33, 1, 1, (0, 0), (1, 1)),
-        ]:
+        ]
+        if taps9:   # nine taps, channels in fours; odd and even step counts
+            vec = True
+            problems = [
+                (3, 8, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
+                (2, 12, 21, 9, 45, 3, 3, (0, 2), (2, 1)),
+                (2, 4, 9, 30, 33, 1, 9, (0, 4), (1, 2)),
+                (1, 20, 12, 7, 70, 9, 1, (5, 0), (1, 1)),
+            ]
+        for (N, C, H, W, K, R, S, pad, stride) in problems:
             if nopad:
                 pad = (0, 0)
             if vec:
@@ -97,11 +107,14 @@ def test_every_kernel_variant():
 
 
 def test_gather_modes_are_chosen():
-    """Enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
+    """Nine taps and channels in fours -> tap table; otherwise enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
     filter order; few channels, padded -> generic."""
     x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 3, 3)
-    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode tapmajor")
-    assert plan.gatherMode == 1 and plan.kSteps == 9
+    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode taps9")
+    assert plan.gatherMode == 3 and plan.kSteps == 8
+    x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 5, 3)
+    _, plan = _check(x, w, (2, 1), (1, 1), 1, "f32", tag="mode tapmajor")
+    assert plan.gatherMode == 1 and plan.kSteps == 15
     x, w = wl.random_problem(4, 2, 3, 12, 12, 8, 5, 5)
     _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad")
     assert plan.gatherMode == 2 and plan.kSteps == 3
