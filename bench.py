@@ -82,8 +82,8 @@ def run_config(index, steps, warmup, oracle_seconds, kernel=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, help="headline workload (1-5)")
     ap.add_argument("--only", action="store_true", help="time the headline workload only")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
@@ -118,7 +118,7 @@ def main():
             if i == args.config:
                 per_config.append(head)
             else:
-                per_config.append(run_config(i, max(10, args.steps // 2), args.warmup, 3.0))
+                per_config.append(run_config(i, args.steps, args.warmup, 3.0))
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")

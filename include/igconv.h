@@ -166,7 +166,7 @@ typedef struct {
     int tileM;       /* rows of O_m (output feature maps) per workgroup */
     int tileN;       /* columns of O_m (output pixels n,p,q) per workgroup */
     int tileK;       /* reduction elements (c,r,s) per step */
-    int gridX;       /* workgroups launched */
+    int gridX;       /* workgroups launched: the tile count rounded up to a multiple of 8 (XCDs) */
     int kSteps;      /* reduction steps: ceil(CRS / tileK); R*S*ceil(C / tileK) in tap-major order */
     int threads;     /* threads per workgroup */
     int ldsBytes;    /* LDS per workgroup */

@@ -231,6 +231,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     ConvKernelParams &k = pr->kp;
     k.tilesM = (k.K + ki.BM - 1) / ki.BM;
     k.tilesN = (k.NPQ + ki.BN - 1) / ki.BN;
+    k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN + 7) / 8);
     const long long steps = kernel_steps(ki, k);
     if (steps >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
     k.ksteps = (int)steps;
@@ -242,7 +243,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         plan->tileM = ki.BM;
         plan->tileN = ki.BN;
         plan->tileK = ki.BK;
-        plan->gridX = k.tilesM * k.tilesN;
+        plan->gridX = 8 * k.tilesPerXcd;
         plan->kSteps = k.ksteps;
         plan->threads = ki.threads;
         plan->ldsBytes = ki.ldsBytes;

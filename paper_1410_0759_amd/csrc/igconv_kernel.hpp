@@ -152,10 +152,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     const int half = lane >> 5;   // which half of the k-group this lane feeds
     const int l32 = lane & 31;
 
-    // M tiles are adjacent in launch order so that workgroups sharing the same
-    // columns of D_m run at the same time.
-    const int tile_m = blockIdx.x % p.tilesM;
-    const int tile_n = blockIdx.x / p.tilesM;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The tiles
+    // are numbered with the M tiles of one column tile adjacent (they gather the same
+    // columns of D_m) and cut into 8 contiguous ranges, one per XCD, so that the
+    // workgroups which share input rows and columns also share an L2.  The grid is
+    // rounded up to 8 ranges of equal length; a workgroup past the last tile leaves.
+    const int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
+    if (tile >= p.tilesM * p.tilesN) return;
+    const int tile_m = tile % p.tilesM;
+    const int tile_n = tile / p.tilesM;
     const int m0 = tile_m * BM;
     const int n0 = tile_n * BN;
 
