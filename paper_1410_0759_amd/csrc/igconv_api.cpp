@@ -235,7 +235,11 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     const long long steps = kernel_steps(ki, k);
     if (steps >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
     k.ksteps = (int)steps;
-    k.tail_step = (ki.gmode == 1 && k.C % ki.BK != 0) ? (int)((long long)(k.C / ki.BK) * k.RS) : -1;
+    // first step of a ragged end of the reduction range (see the kernel): tap-major order,
+    // the last channel chunk; filter order, the last step; none when everything divides
+    k.tail_step = -1;
+    if (ki.gmode == 1 && k.C % ki.BK != 0) k.tail_step = (int)((long long)(k.C / ki.BK) * k.RS);
+    if ((ki.gmode == 0 || ki.gmode == 2) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     if (plan) {

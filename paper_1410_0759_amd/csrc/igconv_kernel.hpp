@@ -128,7 +128,6 @@ struct KernelConfig {
     static_assert(BN == 64 || BN == 128 || BN == 256, "column tile is 1, 2 or 4 wavefronts wide");
     static_assert(BK % VEC == 0 && BK % KPARTS == 0 && KPT % 2 == 0, "k tile granularity");
     static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
-    static_assert(VECA || (BM * BK) % THREADS == 0, "scalar filter tile split");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
     static_assert(GMODE != GATHER_TAPS9 || (VECA && BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
@@ -275,6 +274,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     auto decode1 = [&](int tau) {
         if constexpr (GM == GATHER_GENERIC || GM == GATHER_NOPAD) {
             // i -> (c, r*S+s) for i = first index of the run + lane
+            sc_tau = __builtin_amdgcn_readfirstlane(tau);
             dec_il = (uint32_t)(tau * BK + kpart * KPT) + (uint32_t)lane;
             dec_c = magic_div(dec_il, p.mRS);
             dec_rs = dec_il - dec_c * (uint32_t)p.RS;
@@ -317,6 +317,14 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             } else {
                 dec_so = live ? so : p.x_bytes;
             }
+            // When C*R*S is not a multiple of BK the last step is ragged: on entering it
+            // (once per tile) the filter offsets of the indices beyond the range are
+            // replaced by the out-of-range marker.
+            if (sc_tau == p.tail_step) {
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_voff[ps] = (uint32_t)(sc_tau * BK + a_kk[ps]) < (uint32_t)p.CRS ? a_voff[ps] : kOutOfRange;
+            }
         } else if constexpr (GM == GATHER_TAPMAJOR) {
             vtap = tap_offset(sc_tr, sc_ts);
             // When C is not a multiple of BK the last channel chunk is ragged: on
@@ -334,9 +342,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
             soff = sc_asoff;  // (TAPS9: C % 4 == 0, so a row never ends inside a step)
         } else {
-            const int k0 = tau * BK;
-            voffa = k0 + a_kk[ps] < p.CRS ? voffa : kOutOfRange;
-            soff = k0 < p.CRS ? (uint32_t)k0 * ES : p.w_bytes;
+            // (a reduction range that ends inside the last step: masked in place by decode2)
+            const uint32_t k0 = (uint32_t)tau * BK;
+            const uint32_t live = mask_lt(k0, (uint32_t)p.CRS);
+            soff = ((k0 * ES) & live) | (p.w_bytes & ~live);
         }
         if constexpr (Cfg::VECA) {
             a_vec[set][ps] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, voffa, soff, 0);
@@ -546,9 +555,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     };
 
     const int ksteps = p.ksteps;
+    // Prologue: request tiles 0 and 1 back to back, then write tile 0 to LDS stage 0 as
+    // it arrives (tile 1 stays in flight, it is written during step 0).
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, 0); });
-    static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, 1); });
+    static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
     lds_barrier();
     read_frags(0, 0, 0);
     // Enter the loop with no load outstanding: otherwise the compiler, merging this path

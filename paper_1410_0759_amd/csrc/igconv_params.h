@@ -31,7 +31,7 @@ struct ConvKernelParams {
     int32_t tilesM, tilesN;
     int32_t tilesPerXcd;  // ceil(tilesM * tilesN / 8): tiles are dealt to the 8 XCDs in contiguous ranges
     int32_t ksteps;  // reduction steps of the chosen kernel (depends on its reduction order)
-    int32_t tail_step;  // tap-major order: first step of a ragged last channel chunk, else -1
+    int32_t tail_step;  // first step in which the reduction range ends inside the step, else -1
 };
 
 }  // namespace igc
