@@ -33,14 +33,14 @@ def time_gpu(g, alpha, beta, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
-def run_config(index, steps, warmup, oracle_seconds, kernel=None):
+def run_config(index, steps, warmup, oracle_seconds, kernel=None, workload=None):
     import numpy as np
     import workloads as wl
     from oracle import conv_oracle as oc
     from tests import gpu_util as gu
     import paper_1410_0759_amd as ig
 
-    w_ = wl.by_index(index)
+    w_ = workload if workload is not None else wl.by_index(index)
     x, w, y0 = wl.make_inputs(w_)
     g = gu.GpuConv(x, w, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, dtype=w_.dtype, y_layout=w_.y_layout)
     if kernel is not None:
@@ -86,6 +86,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, help="headline workload (1-5)")
     ap.add_argument("--only", action="store_true", help="time the headline workload only")
+    ap.add_argument("--no-table2", action="store_true", help="skip the paper's Table-2 layer collection")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -120,6 +121,16 @@ def main():
             else:
                 per_config.append(run_config(i, args.steps, args.warmup, 3.0))
 
+    # The paper's own layer collection (its Table 2) with synthetic data, beside the numbers
+    # its Table 3 reports for 2014 hardware.
+    table2 = []
+    if not args.only and not args.no_table2:
+        import workloads as wl
+        for i, w_ in enumerate(wl.TABLE2_LAYERS):
+            r = run_config(None, max(20, args.steps // 10), max(10, args.warmup // 5), 1.0, workload=w_)
+            r["paper_tflops"] = {hw: v[i] for hw, v in wl.TABLE3_PAPER_TFLOPS.items()}
+            table2.append(r)
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -143,6 +154,7 @@ def main():
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
         "per_config": per_config,
+        "table2_layers": table2,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
                          "on GTX 980, fp32, its own Table-2 layers",
     }

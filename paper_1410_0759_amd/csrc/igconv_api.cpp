@@ -171,20 +171,25 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
-// Relative cost of running the problem with one kernel variant: MFMA work of the
-// busiest compute unit (tiles are padded to full size and dealt round-robin), plus a
-// term for the per-step tile traffic that favours larger tiles, times what the gather
+// Relative cost of running the problem with one kernel variant.  Tiles are padded to
+// full size; a compute unit holds up to `occ` workgroups at a time (LDS), which share its
+// MFMA pipes, so a full wave of 256*occ workgroups takes occ tile-times, and a last,
+// partial wave as many tile-times as its fullest compute unit holds workgroups.  A
+// tile-traffic term favours larger tiles, and a factor accounts for what the gather
 // mode costs in vector instructions next to the MFMAs.
 static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long tm = (k.K + ki.BM - 1) / ki.BM;
     const long long tn = (k.NPQ + ki.BN - 1) / ki.BN;
     const long long steps = kernel_steps(ki, k);
     const long long tiles = tm * tn;
-    const long long rounds = (tiles + kComputeUnits - 1) / kComputeUnits;
+    const long long occ = std::max(1, std::min(2, (160 * 1024) / ki.ldsBytes));
+    const long long wave = kComputeUnits * occ;
+    const long long rem = tiles % wave;
+    const double tile_times = (double)(tiles / wave) * occ + (double)((rem + kComputeUnits - 1) / kComputeUnits);
     const double mfma = (double)ki.BM * ki.BN * ki.BK;
-    const double traffic = 48.0 * (ki.BM + ki.BN) * ki.BK;
+    const double traffic = 8.0 * (ki.BM + ki.BN) * ki.BK;
     const double mode = ki.gmode == 0 ? 1.6 : (ki.gmode == 1 ? 1.15 : (ki.gmode == 2 ? 1.1 : 1.0));
-    return (double)rounds * steps * (mfma + traffic) * mode;
+    return tile_times * steps * (mfma + traffic) * mode;
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded

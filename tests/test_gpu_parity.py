@@ -252,3 +252,23 @@ def test_workload_full_size(index):
     err = gu.rel_err(got, want)
     print("workload", w_.name, "kernel", plan.kernelId, "rel err", err, flush=True)
     assert err <= gu.TOL[w_.dtype]
+
+
+# ------------------------------------------------------------------ the paper's Table-2 layers
+@pytest.mark.parametrize("layer", [1, 2, 3, 4, 5])
+def test_table2_layer_sampled(layer):
+    """The paper's layer collection at full size (N = 128) on the GPU; the oracle checks the
+    whole output of a sample of images (the first two and the last two - images are
+    independent, eq. 3)."""
+    gu = _gpu()
+    w_ = wl.TABLE2_LAYERS[layer - 1]
+    x, w, _ = wl.make_inputs(w_)
+    print("workload", w_.name, flush=True)
+    got, plan = gu.run(x, w, (0, 0), (1, 1), w_.mode)
+    assert got.shape == (w_.N, w_.K, w_.P, w_.Q)
+    assert np.all(np.isfinite(got))
+    for sl in (slice(0, 2), slice(w_.N - 2, w_.N)):
+        want = oc.conv_forward(x[sl], w, mode=w_.mode)
+        err = gu.rel_err(got[sl], want)
+        print("workload", w_.name, "kernel", plan.kernelId, "images", sl, "rel err", err, flush=True)
+        assert err <= gu.TOL["f32"]

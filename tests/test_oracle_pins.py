@@ -68,7 +68,7 @@ def test_output_dim_matlab_modes():
 
 def test_workload_output_dims():
     """P, Q stored with the workloads equal eq. 1."""
-    for w_ in wl.WORKLOADS:
+    for w_ in wl.WORKLOADS + wl.TABLE2_LAYERS:
         assert oc.output_dim(w_.H, w_.R, w_.u, w_.pad_h) == w_.P
         assert oc.output_dim(w_.W, w_.S, w_.v, w_.pad_w) == w_.Q
 

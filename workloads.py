@@ -79,6 +79,29 @@ WORKLOADS = (
 )
 
 
+# The paper's own layer collection (Table 2: "Convolutional layer collection"; N = 128, unit
+# stride, no padding), with synthetic data of the same recipe as the mid-layer workloads:
+# x uniform[-1,1], w normal(0, sqrt(2/(C*R*S))).  Indices 11..15 keep their seeds apart.
+def _table2(i, C, HW, K, RS):
+    P = HW - RS + 1
+    return ConvWorkload("table2_layer%d" % i, 10 + i, 128, C, HW, HW, K, RS, RS, 0, 0, 1, 1, P, P,
+                        "f32", "NCHW", "NCHW", ("uniform", -1.0, 1.0), _he(C, RS, RS))
+
+
+TABLE2_LAYERS = (
+    _table2(1, 3, 128, 96, 11),
+    _table2(2, 96, 64, 128, 9),
+    _table2(3, 128, 32, 128, 9),
+    _table2(4, 128, 16, 128, 7),
+    _table2(5, 128, 13, 384, 3),
+)
+# What the paper reports for them (Table 3, TFLOP/s; hardware of 2014, context only).
+TABLE3_PAPER_TFLOPS = {
+    "K40 (peak 4.29)": (0.99, 1.52, 1.51, 1.38, 1.01),
+    "GTX 980 (peak 4.95)": (1.46, 2.49, 2.42, 2.19, 1.87),
+}
+
+
 def by_index(i: int) -> ConvWorkload:
     return WORKLOADS[i - 1]
 
