@@ -174,9 +174,7 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
 // Relative cost of running the problem with one kernel variant.  Tiles are padded to
 // full size; a compute unit holds up to `occ` workgroups at a time (LDS), which share its
 // MFMA pipes, so a full wave of 256*occ workgroups takes occ tile-times, and a last,
-// partial wave as many tile-times as its fullest compute unit holds workgroups.  A
-// tile-traffic term favours larger tiles, and a factor accounts for what the gather
-// mode costs in vector instructions next to the MFMAs.
+// partial wave as many tile-times as its fullest compute unit holds workgroups.
 static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long tm = (k.K + ki.BM - 1) / ki.BM;
     const long long tn = (k.NPQ + ki.BN - 1) / ki.BN;
@@ -186,10 +184,11 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long wave = kComputeUnits * occ;
     const long long rem = tiles % wave;
     const double tile_times = (double)(tiles / wave) * occ + (double)((rem + kComputeUnits - 1) / kComputeUnits);
-    const double mfma = (double)ki.BM * ki.BN * ki.BK;
-    const double traffic = 8.0 * (ki.BM + ki.BN) * ki.BK;
-    const double mode = ki.gmode == 0 ? 1.6 : (ki.gmode == 1 ? 1.15 : (ki.gmode == 2 ? 1.1 : 1.0));
-    return tile_times * steps * (mfma + traffic) * mode;
+    // Per step a workgroup does BM*BN*BK multiply-adds and gathers BN*BK elements of
+    // D_m; measured on the box, gathering one element costs about as much MFMA time as
+    // `gather` multiply-add rows, depending on the mode.
+    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : 6.0));
+    return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded
