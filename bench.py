@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, help="headline workload (1-5)")
     ap.add_argument("--only", action="store_true", help="time the headline workload only")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time the Table-2 layers at mini-batches 16..256 (not part of the default run)")
     ap.add_argument("--no-table2", action="store_true", help="skip the paper's Table-2 layer collection")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -131,6 +133,21 @@ def main():
             r["paper_tflops"] = {hw: v[i] for hw, v in wl.TABLE3_PAPER_TFLOPS.items()}
             table2.append(r)
 
+    # Mini-batch sweep over the Table-2 layers (the paper reports 86 % of its maximum
+    # throughput at a mini-batch of 16): average TFLOP/s over the five layers per batch size.
+    batch_sweep = []
+    if args.batch_sweep:
+        import workloads as wl
+        for nb in (16, 32, 64, 128, 256):
+            rates = []
+            for w_ in wl.TABLE2_LAYERS:
+                r = run_config(None, 30, 15, 0.2, workload=wl.shrink(w_, nb))
+                rates.append(r["tflops"])
+            batch_sweep.append({"N": nb, "mean_tflops": sum(rates) / len(rates), "per_layer_tflops": rates})
+        top = max(b["mean_tflops"] for b in batch_sweep)
+        for b in batch_sweep:
+            b["fraction_of_best"] = b["mean_tflops"] / top
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -155,6 +172,7 @@ def main():
                    "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
         "per_config": per_config,
         "table2_layers": table2,
+        "table2_batch_sweep": batch_sweep,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
                          "on GTX 980, fp32, its own Table-2 layers",
     }

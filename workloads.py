@@ -107,7 +107,7 @@ def by_index(i: int) -> ConvWorkload:
 
 
 def shrink(wl: ConvWorkload, N: int) -> ConvWorkload:
-    """Same layer, fewer images (used to bound CPU time; every image is independent)."""
+    """Same layer with another number of images (every image is independent)."""
     return replace(wl, N=N, name="%s_N%d" % (wl.name, N))
 
 
