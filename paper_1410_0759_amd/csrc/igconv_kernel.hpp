@@ -70,6 +70,86 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
     return (__umulhi(n, m.mul) + n) >> m.shift;
 }
 
+// Epilogue shared by the kernels: out = alpha*acc (+ beta*y), stored through y's strides
+// (Section 3.1: the final transposition to the user's layout; Section 2.1.1: accumulate
+// mode).  `acc` holds MB x NB MFMA result blocks of 32x32; a block keeps, in lane l,
+// register v, the element (row 8*(v/4) + 4*(l/32) + v%4, column l%32).  Without SWAP rows
+// are output channels and columns are pixels (lanes run along pixels: contiguous for
+// NCHW); with SWAP the MFMA operands were exchanged, so lanes run along output channels
+// (contiguous for NHWC) and rows are pixels.  krow0 / col0: first output channel / first
+// column (n,p,q) of this wavefront's blocks.  Whatever does not depend on the lane goes
+// into the store's scalar offset; a wavefront whose blocks lie fully inside K x NPQ
+// needs no per-element test.
+template <bool SWAP, int MB, int NB>
+__device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_buffer_rsrc_t ybuf,
+                                           f32x16 (&acc)[MB][NB], int krow0, int col0, int half, int l32) {
+    const bool use_beta = p.beta != 0.f;
+    auto pixel_offset = [&](uint32_t j) -> uint32_t {  // element offset of column j = (n,p,q) in y
+        const uint32_t n = magic_div(j, p.mPQ);
+        const uint32_t rem = j - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        return n * (uint32_t)p.ysN + pp * (uint32_t)p.ysP + qq * (uint32_t)p.ysQ;
+    };
+    auto emit = [&](float a, uint32_t voff, uint32_t soff) {
+        float out = p.alpha * a;
+        if (use_beta) {
+            const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, voff, soff, 0));
+            out += p.beta * old;
+        }
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, voff, soff, 0);
+    };
+    const bool full = krow0 + MB * 32 <= p.K && col0 + NB * 32 <= p.NPQ;  // wavefront-uniform
+    if constexpr (!SWAP) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int j = col0 + nb * 32 + l32;
+            const bool pv = j < p.NPQ;
+            const uint32_t poff = pixel_offset(pv ? (uint32_t)j : 0u);
+            if (full) {
+                // lane part: pixel and the row half; scalar part: the register's row
+                const uint32_t vo = (poff + (uint32_t)(4 * half) * (uint32_t)p.ysK) * 4u;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        emit(acc[mb][nb][v], vo, (uint32_t)(krow0 + mb * 32 + 8 * (v / 4) + (v % 4)) * (uint32_t)p.ysK * 4u);
+            } else {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int k = krow0 + mb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                        emit(acc[mb][nb][v], pv && k < p.K ? (poff + (uint32_t)k * (uint32_t)p.ysK) * 4u : kOutOfRange, 0u);
+                    }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int k = krow0 + mb * 32 + l32;
+            const bool kv = k < p.K;
+            const uint32_t koff = (uint32_t)k * (uint32_t)p.ysK;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    // the two halves of the wavefront hold pixels j0 and j0 + 4: both
+                    // decoded on the scalar unit, the lane picks its own
+                    const int j0 = col0 + nb * 32 + 8 * (v / 4) + (v % 4);
+                    if (full) {
+                        const uint32_t d0 = pixel_offset((uint32_t)j0), d1 = pixel_offset((uint32_t)j0 + 4u);
+                        emit(acc[mb][nb][v], (koff + (half ? d1 : d0)) * 4u, 0u);
+                    } else {
+                        const int j = j0 + 4 * half;
+                        const bool ok = kv && j < p.NPQ;
+                        emit(acc[mb][nb][v], ok ? (koff + pixel_offset(ok ? (uint32_t)j : 0u)) * 4u : kOutOfRange, 0u);
+                    }
+                }
+        }
+    }
+}
+
 // How the reduction index is ordered and how the gather of the D_m tile finds, for one
 // element (column j, index i), the offset of x[n,c,h,w] and whether the tap lies inside
 // the image.  What was measured on this chip and shapes these modes: fp32 MFMA and
@@ -573,61 +653,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         step(std::integral_constant<int, 1>{}, t + 1);
     }
 
-    // ---- epilogue: alpha/beta, store through y's strides ---------------------------------
-    // A 32x32 MFMA result block keeps, in lane l, register v, the element
-    //   (row 8*(v/4) + 4*(l/32) + v%4, column l%32).
-    // Without SWAP rows are output channels and columns are pixels; with SWAP the
-    // operands were exchanged, so columns (lanes) are channels and rows are pixels.
-    const bool use_beta = p.beta != 0.f;
-    auto pixel_offset = [&](int j, bool &valid) -> uint32_t {
-        valid = j < p.NPQ;
-        const uint32_t jj = valid ? (uint32_t)j : 0u;
-        const uint32_t n = magic_div(jj, p.mPQ);
-        const uint32_t rem = jj - n * (uint32_t)p.PQ;
-        const uint32_t pp = magic_div(rem, p.mQ);
-        const uint32_t qq = rem - pp * (uint32_t)p.Q;
-        return n * (uint32_t)p.ysN + pp * (uint32_t)p.ysP + qq * (uint32_t)p.ysQ;
-    };
-    auto emit = [&](float a, uint32_t off, bool valid) {
-        const uint32_t voff = valid ? off * 4u : kOutOfRange;
-        float out = p.alpha * a;
-        if (use_beta) {
-            const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, voff, 0, 0));
-            out += p.beta * old;
-        }
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, voff, 0, 0);
-    };
-    if constexpr (!Cfg::SWAP) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            bool pv;
-            const uint32_t poff = pixel_offset(n0 + wn * Cfg::TN + nb * 32 + l32, pv);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int k = m0 + wm * Cfg::TM + mb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                    emit(acc[mb][nb][v], poff + (uint32_t)k * (uint32_t)p.ysK, pv && k < p.K);
-                }
-            }
-        }
-    } else {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int k = m0 + wm * Cfg::TM + mb * 32 + l32;
-            const bool kv = k < p.K;
-            const uint32_t koff = (uint32_t)k * (uint32_t)p.ysK;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    bool pv;
-                    const uint32_t poff = pixel_offset(n0 + wn * Cfg::TN + nb * 32 + 8 * (v / 4) + 4 * half + (v % 4), pv);
-                    emit(acc[mb][nb][v], poff + koff, pv && kv);
-                }
-            }
-        }
-    }
+    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, m0 + wm * Cfg::TM, n0 + wn * Cfg::TN, half, l32);
 }
 
 }  // namespace igc
