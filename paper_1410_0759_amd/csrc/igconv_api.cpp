@@ -41,7 +41,7 @@ constexpr int kComputeUnits = 256;
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16};
+                                            &kGroupBF16, &kGroupBF16Channels};
 
 int kernel_count() {
     int n = 0;
@@ -167,7 +167,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 // chunks of BK, or tap-major: per tap, the channels in chunks of BK.
 static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
-    if (ki.gmode == 3) return k.C / (ki.BK / 9);
+    if (ki.gmode == 3 || ki.gmode == 4) return k.C / (ki.BK / 9);
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
@@ -187,27 +187,35 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // Per step a workgroup does BM*BN*BK multiply-adds and gathers BN*BK elements of
     // D_m; measured on the box, gathering one element costs about as much MFMA time as
     // `gather` multiply-add rows, depending on the mode.
+    // The channel-vector bf16 kernel gathers 8 elements per load and is bound by the MFMA
+    // pipe alone; next to the element-wise bf16 kernels it is an order of magnitude cheaper.
+    if (ki.gmode == 4) return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + 6.0) * 0.1;
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : 6.0));
     return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded
 // mode needs pad 0, the nine-tap table R*S = 9 and whole steps of four channels; the
-// generic and the tap-major modes always work.
-static bool gather_mode_ok(int gmode, const ConvKernelParams &k) {
+// generic and the tap-major modes always work.  The channel-vector mode (bf16) reads 8
+// channels of one pixel with one 16-byte load: R*S = 9, whole steps of 16 channels, unit
+// channel stride, every other stride a multiple of 8 elements and x itself 16-byte aligned.
+static bool gather_mode_ok(int gmode, const ConvKernelParams &k, bool x_aligned) {
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
+    if (gmode == 4)
+        return x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
+               k.xsW % 8 == 0;
     return true;
 }
 
-static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, int *id_out) {
+static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, bool x_aligned, int *id_out) {
     const ConvKernelParams &k = pr.kp;
     const bool can_vec = w_aligned && (k.CRS % pr.vec == 0);
     // Lanes should run along y's unit-stride dimension in the epilogue.
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
     if (h->kernelOverride >= 0) {
         const KernelInfo *ki = kernel_info(h->kernelOverride);
-        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(ki->gmode, k))
+        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(ki->gmode, k, x_aligned))
             return IGC_STATUS_NOT_SUPPORTED;
         *id_out = h->kernelOverride;
         return IGC_STATUS_SUCCESS;
@@ -216,7 +224,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     double best_cost = 0;
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
-        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki.gmode, k)) continue;
+        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki.gmode, k, x_aligned)) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -452,7 +460,7 @@ igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle, igcTensorDescriptor_t
     igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
     if (st != IGC_STATUS_SUCCESS) return st;
     int id = -1;
-    st = choose(handle, pr, /*w_aligned=*/true, &id);
+    st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
     igcConvolutionForwardPlan tmp;
     st = fill_plan(id, &pr, &tmp);
@@ -502,7 +510,7 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha, igcTensor
     const int es = pr.bf16 ? 2 : 4;
     if ((uintptr_t)x % es || (uintptr_t)w % es || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
     int id = -1;
-    st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, &id);
+    st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, /*x_aligned=*/((uintptr_t)x % 16) == 0, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
     igcConvolutionForwardPlan plan;
     st = fill_plan(id, &pr, &plan);

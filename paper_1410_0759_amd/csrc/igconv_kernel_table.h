@@ -12,7 +12,8 @@ struct KernelInfo {
     int BM, BN, BK; // tile of O_m per workgroup and reduction elements per step
     bool swap;      // lanes run along output channels in the epilogue
     bool veca;      // filter rows fetched with 16-byte loads (needs CRS % VEC == 0, aligned w)
-    int gmode;      // gather mode: 0 generic, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table
+    int gmode;      // gather mode: 0 generic, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
+                    // 4 channel vectors (bf16, nine taps, unit channel stride)
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
@@ -25,7 +26,8 @@ struct KernelGroup {
 };
 
 // One group per translation unit of kernel instantiations.
-extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16;
+extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
+    kGroupBF16Channels;
 
 int kernel_count();
 const KernelInfo *kernel_info(int id);  // nullptr when out of range

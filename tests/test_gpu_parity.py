@@ -92,12 +92,23 @@ def test_every_kernel_variant():
                 (2, 4, 9, 30, 33, 1, 9, (0, 4), (1, 2)),
                 (1, 20, 12, 7, 70, 9, 1, (5, 0), (1, 1)),
             ]
+        channels = "channels" in name
+        if channels:   # nine taps, channels in sixteens and contiguous; odd and even step counts
+            vec = True
+            problems = [
+                (3, 16, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
+                (2, 48, 21, 9, 45, 3, 3, (0, 2), (2, 1)),
+                (2, 32, 9, 30, 33, 1, 9, (0, 4), (1, 2)),
+                (1, 80, 12, 7, 200, 9, 1, (5, 0), (1, 1)),
+            ]
         for (N, C, H, W, K, R, S, pad, stride) in problems:
             if nopad:
                 pad = (0, 0)
             if vec:
                 assert (C * R * S) % vecn == 0
             x, w = wl.random_problem(7 + kid, N, C, H, W, K, R, S, dtype=dtype)
+            if channels:
+                x = wl.with_layout(x, "NHWC")
             y0 = np.random.default_rng(kid).uniform(-1, 1, size=(N, K, (H + 2 * pad[0] - R) // stride[0] + 1,
                                                                  (W + 2 * pad[1] - S) // stride[1] + 1)).astype(np.float32)
             lay = "NHWC" if swap else "NCHW"
