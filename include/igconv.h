@@ -172,7 +172,8 @@ typedef struct {
     int ldsBytes;    /* LDS per workgroup */
     int swapOperands;/* 1 when lanes run along k in the epilogue (y's c-stride is 1) */
     int vecFilterLoads; /* 1 when filter rows are fetched with 16-byte loads */
-    int gatherMode;  /* 0 generic window test, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table */
+    int gatherMode;  /* 0 generic window test, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
+                        4 bf16 channel vectors, 5 bf16 channel vectors from a staged image patch */
 } igcConvolutionForwardPlan;
 
 igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle,

@@ -78,6 +78,14 @@ def lib():
             raise RuntimeError(
                 "libigconv.so is not built (%s); build it with paper_1410_0759_amd/build.py. "
                 "There is no fallback path." % LIB_PATH)
+        # A process may hold one HIP runtime only.  PyTorch-ROCm ships its own copy; when the
+        # caller is going to use PyTorch for device memory and streams, that copy has to be
+        # the one loaded first (libigconv.so then binds to it).  Loaded the other way round,
+        # the two runtimes conflict and every launch reports that no device is present.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in DECLARED_SYMBOLS.items():
             fn = getattr(L, name)

@@ -38,6 +38,7 @@ namespace igc {
 
 // MI355X: 256 compute units; the tile heuristic balances workgroups over them.
 constexpr int kComputeUnits = 256;
+constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels (Bf16cConfig::PATCH_PIX)
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
@@ -152,6 +153,10 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
         k.pad_h = cv->pad_h; k.pad_w = cv->pad_w; k.u = cv->u; k.v = cv->v;
         k.flip = cv->mode == IGC_CONVOLUTION ? 1 : 0;
         k.CRS = (int)CRS; k.NPQ = (int)NPQ; k.PQ = (int)(P * Q); k.RS = w->r * w->s;
+        k.Wp = k.W + 2 * k.pad_w;
+        // (only the patch-staging kernels use HpWp; they are not offered when it is clamped here)
+        k.HpWp = (int)std::min<long long>((long long)(k.H + 2 * k.pad_h) * k.Wp, 0x7fffffff);
+        if (!magic_for((uint32_t)k.Wp, &k.mWp) || !magic_for((uint32_t)k.HpWp, &k.mHpWp)) return IGC_STATUS_NOT_SUPPORTED;
         if (!magic_for((uint32_t)k.PQ, &k.mPQ) || !magic_for((uint32_t)k.Q, &k.mQ) ||
             !magic_for((uint32_t)k.RS, &k.mRS) || !magic_for((uint32_t)k.S, &k.mS))
             return IGC_STATUS_NOT_SUPPORTED;
@@ -167,7 +172,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 // chunks of BK, or tap-major: per tap, the channels in chunks of BK.
 static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
-    if (ki.gmode == 3 || ki.gmode == 4) return k.C / (ki.BK / 9);
+    if (ki.gmode >= 3) return k.C / (ki.BK / 9);
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
@@ -187,9 +192,11 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // Per step a workgroup does BM*BN*BK multiply-adds and gathers BN*BK elements of
     // D_m; measured on the box, gathering one element costs about as much MFMA time as
     // `gather` multiply-add rows, depending on the mode.
-    // The channel-vector bf16 kernel gathers 8 elements per load and is bound by the MFMA
-    // pipe alone; next to the element-wise bf16 kernels it is an order of magnitude cheaper.
-    if (ki.gmode == 4) return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + 6.0) * 0.1;
+    // The channel-vector bf16 kernels are bound by their loads, not by the MFMA pipe: measured,
+    // a step costs about 2.75 units per filter row and 1 (1.5 when gathered tap by tap) per
+    // column, plus a small MFMA term; the scale makes them comparable with the line below.
+    if (ki.gmode >= 4)
+        return tile_times * steps * 1000.0 * (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : 6.0));
     return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
 }
@@ -199,12 +206,37 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
 // generic and the tap-major modes always work.  The channel-vector mode (bf16) reads 8
 // channels of one pixel with one 16-byte load: R*S = 9, whole steps of 16 channels, unit
 // channel stride, every other stride a multiple of 8 elements and x itself 16-byte aligned.
-static bool gather_mode_ok(int gmode, const ConvKernelParams &k, bool x_aligned) {
+// Largest number of pixels of the zero-extended images (flat index over all images) between
+// the first pixel of a tile's first column window and the last pixel of its last column's,
+// for tiles of bn consecutive columns: an upper bound.  Going from one column to the next
+// advances the window start by v, by a row wrap or by an image wrap; within bn-1 such
+// moves at most `rows` are wraps and at most `imgs` of those image wraps.
+static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
+    const long long d = bn - 1;
+    const long long rows = (d + k.Q - 1) / k.Q, imgs = (d + k.PQ - 1) / k.PQ;
+    const long long row_wrap = std::max<long long>((long long)k.u * k.Wp - (long long)(k.Q - 1) * k.v, k.v);
+    const long long img_wrap =
+        std::max<long long>((long long)k.HpWp - (long long)(k.P - 1) * k.u * k.Wp - (long long)(k.Q - 1) * k.v, row_wrap);
+    return (d - rows) * k.v + (rows - imgs) * row_wrap + imgs * img_wrap + (long long)(k.R - 1) * k.Wp + k.S;
+}
+
+// Gather modes a kernel may use for this problem (see the kernel sources): the unpadded
+// mode needs pad 0, the nine-tap table R*S = 9 and whole steps of four channels; the
+// generic and the tap-major modes always work.  The channel-vector modes (bf16) read 8
+// channels of one pixel with one 16-byte load: R*S = 9, whole steps of 16 channels, unit
+// channel stride, every other stride a multiple of 8 elements and x itself 16-byte aligned;
+// staging a patch of the zero-extended image needs every tile's pixel range to fit it.
+static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
+    const int gmode = ki.gmode;
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
-    if (gmode == 4)
-        return x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
-               k.xsW % 8 == 0;
+    if (gmode >= 4) {
+        if (!(x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
+              k.xsW % 8 == 0))
+            return false;
+        if (gmode == 5)
+            return (long long)k.N * (k.H + 2 * k.pad_h) * k.Wp < (1ll << 31) && patch_pixels_bound(k, ki.BN) <= kPatchPixels;
+    }
     return true;
 }
 
@@ -215,7 +247,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
     if (h->kernelOverride >= 0) {
         const KernelInfo *ki = kernel_info(h->kernelOverride);
-        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(ki->gmode, k, x_aligned))
+        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(*ki, k, x_aligned))
             return IGC_STATUS_NOT_SUPPORTED;
         *id_out = h->kernelOverride;
         return IGC_STATUS_SUCCESS;
@@ -224,7 +256,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     double best_cost = 0;
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
-        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki.gmode, k, x_aligned)) continue;
+        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;

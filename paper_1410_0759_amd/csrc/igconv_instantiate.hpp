@@ -5,16 +5,32 @@
 #ifndef IGCONV_INSTANTIATE_HPP_
 #define IGCONV_INSTANTIATE_HPP_
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "igconv_kernel.hpp"
 #include "igconv_kernel_table.h"
 
 namespace igc {
 
+// Launches `kernel` and returns the runtime's verdict on this launch (0 = accepted): the
+// launch call's own return value, not the thread's last-error state, which other users of
+// the runtime in the same thread may have left set.  With IGCONV_DEBUG set in the
+// environment a rejected launch is also described on stderr.
+template <class Kernel>
+int launch_checked(Kernel kernel, const char *what, const ConvKernelParams &p, int grid, int threads, void *stream) {
+    ConvKernelParams args = p;
+    void *argv[] = {&args};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(grid), dim3(threads), argv, 0,
+                                         static_cast<hipStream_t>(stream));
+    if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
+        std::fprintf(stderr, "igconv: launch of %s failed: %s\n", what, hipGetErrorString(e));
+    return static_cast<int>(e);
+}
+
 template <class Cfg>
 int launch_kernel(const ConvKernelParams &p, int grid, void *stream) {
-    hipLaunchKernelGGL(igconv_fwd_kernel<Cfg>, dim3(grid), dim3(Cfg::THREADS), 0,
-                       static_cast<hipStream_t>(stream), p);
-    return static_cast<int>(hipGetLastError());
+    return launch_checked(&igconv_fwd_kernel<Cfg>, "igconv_fwd_kernel", p, grid, Cfg::THREADS, stream);
 }
 
 #define IGC_INSTANTIATE(NAME, BF16, BM, BN, BK, WM, WN, SWAP, VECA, GMODE) \

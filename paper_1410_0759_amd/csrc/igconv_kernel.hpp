@@ -78,8 +78,8 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
 // NCHW); with SWAP the MFMA operands were exchanged, so lanes run along output channels
 // (contiguous for NHWC) and rows are pixels.  krow0 / col0: first output channel / first
 // column (n,p,q) of this wavefront's blocks.  Whatever does not depend on the lane goes
-// into the store's scalar offset; a wavefront whose blocks lie fully inside K x NPQ
-// needs no per-element test.
+// into the store's scalar offset where that is possible; a wavefront whose blocks lie
+// fully inside K x NPQ needs no per-element test.
 template <bool SWAP, int MB, int NB>
 __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_buffer_rsrc_t ybuf,
                                            f32x16 (&acc)[MB][NB], int krow0, int col0, int half, int l32) {
@@ -99,8 +99,8 @@ __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_b
         }
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, voff, soff, 0);
     };
-    const bool full = krow0 + MB * 32 <= p.K && col0 + NB * 32 <= p.NPQ;  // wavefront-uniform
     if constexpr (!SWAP) {
+        const bool full = krow0 + MB * 32 <= p.K && col0 + NB * 32 <= p.NPQ;  // wavefront-uniform
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int j = col0 + nb * 32 + l32;
@@ -125,27 +125,27 @@ __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_b
             }
         }
     } else {
+        // Rows of a block are pixels here: 32 per block, decoded once, one per lane (both
+        // halves of the wavefront decode the same 32); register v of a lane then belongs
+        // to pixel 8*(v/4) + v%4 (+4 in the upper half), whose offset is fetched from the
+        // lane that decoded it.  A pixel past the end carries the out-of-range marker,
+        // which survives the addition of the channel offset (both stay below 2^31).
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int k = krow0 + mb * 32 + l32;
-            const bool kv = k < p.K;
-            const uint32_t koff = (uint32_t)k * (uint32_t)p.ysK;
+        for (int nb = 0; nb < NB; ++nb) {
+            const int jd = col0 + nb * 32 + l32;
+            const uint32_t pd = jd < p.NPQ ? pixel_offset((uint32_t)jd) * 4u : kOutOfRange;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int mb = 0; mb < MB; ++mb) {
+                const int k = krow0 + mb * 32 + l32;
+                const bool kv = k < p.K;
+                const uint32_t koff = (uint32_t)k * (uint32_t)p.ysK * 4u;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    // the two halves of the wavefront hold pixels j0 and j0 + 4: both
-                    // decoded on the scalar unit, the lane picks its own
-                    const int j0 = col0 + nb * 32 + 8 * (v / 4) + (v % 4);
-                    if (full) {
-                        const uint32_t d0 = pixel_offset((uint32_t)j0), d1 = pixel_offset((uint32_t)j0 + 4u);
-                        emit(acc[mb][nb][v], (koff + (half ? d1 : d0)) * 4u, 0u);
-                    } else {
-                        const int j = j0 + 4 * half;
-                        const bool ok = kv && j < p.NPQ;
-                        emit(acc[mb][nb][v], ok ? (koff + pixel_offset(ok ? (uint32_t)j : 0u)) * 4u : kOutOfRange, 0u);
-                    }
+                    const int r0 = 8 * (v / 4) + (v % 4);
+                    const uint32_t d0 = __builtin_amdgcn_readlane(pd, r0), d1 = __builtin_amdgcn_readlane(pd, r0 + 4);
+                    emit(acc[mb][nb][v], kv ? koff + (half ? d1 : d0) : kOutOfRange, 0u);
                 }
+            }
         }
     }
 }

@@ -18,6 +18,15 @@
 //  * LDS: [stage][tap][row][2 x 16 bytes]; the two 16-byte halves of a row are swapped on
 //    every other group of 8 rows, which makes the 16-byte reads of 16 consecutive rows
 //    bank-conflict free without padding.  Two stages of 9*(BM+BN)*32 bytes.
+// PATCH variant of the D_m side.  The nine taps of neighbouring columns read the same pixels:
+// in the zero-extended image (H+2pad_h rows of W+2pad_w pixels, all images in one flat
+// index g) column j = (n,p,q) starts at b(j) = n*Hp*Wp + p*u*Wp + q*v and tap (r,s) adds
+// r*Wp + s.  The pixels a tile needs are therefore the range [b(first column),
+// b(last column) + (R-1)*Wp + S-1] of g: a few hundred pixels instead of 9*BN.  That range
+// (16 channels of each pixel per step) is staged once per step; the MFMA operand of lane
+// (column, half) for tap t is the 16 bytes at patch[half][b(column) - b(first) + r*Wp + s],
+// read straight from the patch.  The host offers this variant only when the range of every
+// tile fits the patch.
 // The pipeline (two register sets, LDS-only barrier before the last k-group, one burst of
 // side work per MFMA, single-block loop) is the one of igconv_kernel.hpp.
 #ifndef IGCONV_KERNEL_BF16C_HPP_
@@ -27,8 +36,11 @@
 
 namespace igc {
 
-template <int BM_, int BN_, int WM_, int WN_, bool SWAP_>
+template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false>
 struct Bf16cConfig {
+    static constexpr bool PATCH = PATCH_;
+    static constexpr int PATCH_PIX = 512;                   // pixels of the zero-extended image per tile
+    static constexpr int PATCH_PLANE = PATCH_PIX * 16 + 128;  // one channel half; +128 B: halves on disjoint banks
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
     static constexpr bool SWAP = SWAP_;
     static constexpr int THREADS = 256;
@@ -38,13 +50,14 @@ struct Bf16cConfig {
     // Every thread stages filter rows, so that the main loop has no divergent code: the
     // F_m planes always hold THREADS/2 rows, of which the first BM are used.
     static constexpr int AR = THREADS / 2;
-    static constexpr int A_BYTES = TAPS * AR * ROW_BYTES, B_BYTES = TAPS * BN * ROW_BYTES;
+    static constexpr int A_BYTES = TAPS * AR * ROW_BYTES;
+    static constexpr int B_BYTES = PATCH ? 2 * PATCH_PLANE : TAPS * BN * ROW_BYTES;
     static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
     static constexpr int TM = BM / WM, TN = BN / WN;
     static constexpr int MB = TM / 32, NB = TN / 32;
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave blocks are 32x32 multiples");
-    static_assert(BM <= AR && 2 * BN == THREADS, "thread = (row or column, channel half)");
+    static_assert(BM <= AR && (PATCH || 2 * BN == THREADS), "thread = (row or column, channel half)");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -73,10 +86,51 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
     const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
 
-    // ---- D_m role: thread = (column j, channel half hb); nine tap offsets ----------
-    const int jl = tid >> 1, hb = tid & 1;  // neighbouring lanes read the two halves of one 32-byte run
-    uint32_t vtaps[TAPS];
-    {
+    // ---- D_m role -------------------------------------------------------------------
+    // Both variants: thread = (jl, hb) with the channel half hb in the lowest lane bit, so that
+    // neighbouring lanes read the two halves of one 32-byte run; NBL 16-byte loads per step
+    // whose per-thread offsets are built once per tile (validity folded in), the step's
+    // channel offset being added as a scalar.
+    constexpr bool PATCH = Cfg::PATCH;
+    constexpr int NBL = PATCH ? Cfg::PATCH_PIX / 128 : TAPS;
+    const int jl = tid >> 1, hb = tid & 1;
+    uint32_t b_voff[NBL];
+    // tap t of the reduction order -> (row, column) of the window, eq. 2 inverting the filter
+    auto tap_rs = [&](int t, uint32_t &tr, uint32_t &ts) {
+        const uint32_t r = magic_div((uint32_t)t, p.mS);
+        const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
+        tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+        ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+    };
+    // first pixel of column j's window as a flat index into the zero-extended images
+    auto window_start = [&](uint32_t j) {
+        const uint32_t n = magic_div(j, p.mPQ);
+        const uint32_t rem = j - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        return n * (uint32_t)p.HpWp + pp * (uint32_t)(p.u * p.Wp) + qq * (uint32_t)p.v;
+    };
+    uint32_t g_first = 0;  // PATCH: flat index of the tile's first pixel
+    if constexpr (PATCH) {
+        // thread stages pixels g_first + jl + 128*i, i < NBL
+        g_first = __builtin_amdgcn_readfirstlane(window_start((uint32_t)n0));
+        const int j_last = n0 + BN - 1 < p.NPQ ? n0 + BN - 1 : p.NPQ - 1;
+        const uint32_t g_end = __builtin_amdgcn_readfirstlane(window_start((uint32_t)j_last)) +
+                               (uint32_t)((p.R - 1) * p.Wp + p.S);   // one past the tile's last pixel
+#pragma unroll
+        for (int i = 0; i < NBL; ++i) {
+            const uint32_t g = g_first + (uint32_t)(jl + 128 * i);
+            const uint32_t n = magic_div(g, p.mHpWp);
+            const uint32_t rem = g - n * (uint32_t)p.HpWp;
+            const uint32_t hp = magic_div(rem, p.mWp);
+            const uint32_t wp = rem - hp * (uint32_t)p.Wp;
+            const uint32_t h = hp - (uint32_t)p.pad_h, w = wp - (uint32_t)p.pad_w;  // wrap below 0 -> huge
+            const bool ok = g < g_end && h < (uint32_t)p.H && w < (uint32_t)p.W;   // (g < g_end implies n < N)
+            b_voff[i] = ok ? (n * (uint32_t)p.xsN + h * (uint32_t)p.xsH + w * (uint32_t)p.xsW) * 2u + (uint32_t)hb * 16u
+                           : kOutOfRange;
+        }
+    } else {
+        // thread stages the nine taps of column n0 + jl
         const int j = n0 + jl;
         const bool cv = j < p.NPQ;
         const uint32_t jj = cv ? (uint32_t)j : 0u;
@@ -94,21 +148,19 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         hw_max[0] = (uint16_t)(p.W - 1);
 #pragma unroll
         for (int t = 0; t < TAPS; ++t) {
-            const uint32_t r = magic_div((uint32_t)t, p.mS);
-            const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
-            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;   // eq. 2 inverts the filter
-            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            uint32_t tr, ts;
+            tap_rs(t, tr, ts);
             const u16x2 tap = __builtin_bit_cast(u16x2, (tr << 16) | ts);
             const u16x2 hw = hw0 + tap;
             const u16x2 cl = __builtin_elementwise_min(hw, hw_max);
             const bool ok = __builtin_bit_cast(uint32_t, cl) == __builtin_bit_cast(uint32_t, hw);
-            vtaps[t] = ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * 2u + (uint32_t)hb * 16u : kOutOfRange;
+            b_voff[t] = ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * 2u + (uint32_t)hb * 16u : kOutOfRange;
         }
     }
     // LDS byte offset of (row, 16-byte half) inside one tap plane, halves swapped on every
     // other group of 8 rows
     auto plane_off = [](int row, int hf) { return row * 32 + ((hf ^ ((row >> 3) & 1)) << 4); };
-    const int b_woff = plane_off(jl, hb);
+    const int b_woff = PATCH ? hb * Cfg::PATCH_PLANE + jl * 16 : plane_off(jl, hb);
 
     // ---- F_m role: thread = (row, channel half ha) -----------------------------------
     const int a_row = tid >> 1, ha = tid & 1;
@@ -118,7 +170,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     const int a_woff = plane_off(a_row, ha);
 
     // registers holding the tiles in flight (two sets)
-    u32x4 a_reg[2][TAPS], b_reg[2][TAPS];
+    u32x4 a_reg[2][TAPS], b_reg[2][NBL];
     uint32_t sc_asoff = 0, sc_bsoff = 0;
 
     auto decode = [&](int tau) {
@@ -130,8 +182,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     auto load_a = [&](int set, int q) {   // q-th 16 bytes of this thread's 72 elements
         a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, sc_asoff, 0);
     };
-    auto load_b = [&](int set, int t) {
-        b_reg[set][t] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, vtaps[t], sc_bsoff, 0);
+    auto load_b = [&](int set, int i) {
+        b_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, b_voff[i], sc_bsoff, 0);
     };
     // Tap t of the thread's 8 channels: element (c, t) sits at position c*9 + t of the 72
     // loaded ones, i.e. 16-bit half (c*9+t)&1 of dword (c*9+t)>>1.
@@ -147,10 +199,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         }
         *reinterpret_cast<u32x4 *>(ldsA + buf * Cfg::A_BYTES + t * (Cfg::AR * 32) + a_woff) = o;
     };
-    auto write_b = [&](int set, int buf, int t) {
-        *reinterpret_cast<u32x4 *>(ldsB + buf * Cfg::B_BYTES + t * (BN * 32) + b_woff) = b_reg[set][t];
+    auto write_b = [&](int set, int buf, int i) {
+        constexpr int kStride = PATCH ? 128 * 16 : BN * 32;  // 128 pixels further / next tap plane
+        *reinterpret_cast<u32x4 *>(ldsB + buf * Cfg::B_BYTES + i * kStride + b_woff) = b_reg[set][i];
     };
-    constexpr int NL = 1 + 2 * TAPS, NW = 2 * TAPS;
+    constexpr int NL = 1 + TAPS + NBL, NW = TAPS + NBL;
     auto load_item = [&](int i, int set, int tau) {
         if (i == 0) decode(tau);
         else if (i <= TAPS) load_a(set, i - 1);
@@ -175,13 +228,33 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     // (wm*TM + mb*32 and wn*TN + nb*32 are multiples of 16, so the half swap depends on l32 only)
     const int fa_off = (wm * Cfg::TM) * 32 + plane_off(l32, half);
     const int fb_off = (wn * Cfg::TN) * 32 + plane_off(l32, half);
+    // PATCH: LDS offset of the lane's operand per column block and tap
+    int fb_patch[PATCH ? NB : 1][PATCH ? TAPS : 1];
+    if constexpr (PATCH) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int j = n0 + wn * Cfg::TN + nb * 32 + l32;
+            // columns past the end are never stored; let them read the last column's window
+            const uint32_t rel = window_start((uint32_t)(j < p.NPQ ? j : p.NPQ - 1)) - g_first;
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) {
+                uint32_t tr, ts;
+                tap_rs(t, tr, ts);
+                fb_patch[nb][t] = half * Cfg::PATCH_PLANE + (int)(rel + tr * (uint32_t)p.Wp + ts) * 16;
+            }
+        }
+    }
     auto read_frags = [&](int buf, int g, int fs) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
             fragA[fs][mb] = *reinterpret_cast<const u32x4 *>(ldsA + buf * Cfg::A_BYTES + g * (Cfg::AR * 32) + fa_off + mb * 1024);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            fragB[fs][nb] = *reinterpret_cast<const u32x4 *>(ldsB + buf * Cfg::B_BYTES + g * (BN * 32) + fb_off + nb * 1024);
+        for (int nb = 0; nb < NB; ++nb) {
+            if constexpr (PATCH)
+                fragB[fs][nb] = *reinterpret_cast<const u32x4 *>(ldsB + buf * Cfg::B_BYTES + fb_patch[nb][g]);
+            else
+                fragB[fs][nb] = *reinterpret_cast<const u32x4 *>(ldsB + buf * Cfg::B_BYTES + g * (BN * 32) + fb_off + nb * 1024);
+        }
     };
     auto mfma = [&](int fs, int j) {
         const int mb = j / NB, nb = j % NB;
@@ -212,8 +285,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
                 lds_barrier();
                 read_frags(nxt, 0, fs ^ 1);
             }
-            constexpr int l0 = (m * NL + NM - 1) / NM, l1 = ((m + 1) * NL + NM - 1) / NM;
-            static_for<l1 - l0>([&](auto ic) { load_item(l0 + decltype(ic)::value, cur, k2); });
+            // Loads go out in two bursts (filter rows, then pixels): a thread's loads hit the same
+            // few cache lines, which a 32 KB L1 only keeps if nothing else comes between them.
+            constexpr int l0 = m == 0 ? 0 : (m == 1 ? 1 + TAPS : NL), l1 = m == 0 ? 1 + TAPS : NL;
+            static_for<(l1 > l0 ? l1 - l0 : 0)>([&](auto ic) { load_item(l0 + decltype(ic)::value, cur, k2); });
             constexpr int WS = NW < SB ? NW : SB;
             if constexpr (m >= SB - WS && m < SB) {
                 constexpr int q = m - (SB - WS);

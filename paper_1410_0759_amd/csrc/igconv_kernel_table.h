@@ -13,7 +13,7 @@ struct KernelInfo {
     bool swap;      // lanes run along output channels in the epilogue
     bool veca;      // filter rows fetched with 16-byte loads (needs CRS % VEC == 0, aligned w)
     int gmode;      // gather mode: 0 generic, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
-                    // 4 channel vectors (bf16, nine taps, unit channel stride)
+                    // 4 channel vectors (bf16, nine taps, unit channel stride), 5 the same from a staged image patch
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).

@@ -32,6 +32,9 @@ struct ConvKernelParams {
     int32_t tilesPerXcd;  // ceil(tilesM * tilesN / 8): tiles are dealt to the 8 XCDs in contiguous ranges
     int32_t ksteps;  // reduction steps of the chosen kernel (depends on its reduction order)
     int32_t tail_step;  // first step in which the reduction range ends inside the step, else -1
+    // zero-extended image: Wp = W + 2 pad_w pixels per row, HpWp = (H + 2 pad_h) * Wp per image
+    int32_t Wp, HpWp;
+    Magic mWp, mHpWp;
 };
 
 }  // namespace igc

@@ -92,7 +92,7 @@ def test_every_kernel_variant():
                 (2, 4, 9, 30, 33, 1, 9, (0, 4), (1, 2)),
                 (1, 20, 12, 7, 70, 9, 1, (5, 0), (1, 1)),
             ]
-        channels = "channels" in name
+        channels = "channels" in name or "patch" in name
         if channels:   # nine taps, channels in sixteens and contiguous; odd and even step counts
             vec = True
             problems = [
@@ -101,6 +101,8 @@ def test_every_kernel_variant():
                 (2, 32, 9, 30, 33, 1, 9, (0, 4), (1, 2)),
                 (1, 80, 12, 7, 200, 9, 1, (5, 0), (1, 1)),
             ]
+            if "x256x" in name:   # 256 strided columns would not fit the staged image patch
+                problems = [pr[:8] + ((1, 1),) for pr in problems]
         for (N, C, H, W, K, R, S, pad, stride) in problems:
             if nopad:
                 pad = (0, 0)
@@ -133,6 +135,14 @@ def test_gather_modes_are_chosen():
     assert plan.gatherMode == 0
     _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode generic swap")
     assert plan.gatherMode == 0 and plan.swapOperands == 1
+    # bf16, nine taps, contiguous channels in sixteens: channel vectors from a staged image patch;
+    # an image too wide for the patch: channel vectors gathered tap by tap
+    x, w = wl.random_problem(5, 3, 48, 13, 11, 40, 3, 3, dtype="bf16")
+    _, plan = _check(wl.with_layout(x, "NHWC"), w, (1, 1), (1, 1), 0, "bf16", y_layout="NHWC", tag="mode patch")
+    assert plan.gatherMode == 5 and plan.kSteps == 3 and plan.swapOperands == 1
+    x, w = wl.random_problem(6, 1, 16, 5, 300, 24, 3, 3, dtype="bf16")
+    _, plan = _check(wl.with_layout(x, "NHWC"), w, (1, 1), (1, 1), 1, "bf16", tag="mode channels")
+    assert plan.gatherMode == 4 and plan.kSteps == 1
 
 
 def test_tapmajor_ragged_channel_chunks():

@@ -91,6 +91,30 @@ def test_workload_dims_and_plans():
         assert plan.swapOperands == (1 if w_.y_layout == "NHWC" else 0)
 
 
+def test_bf16_channel_vector_modes_are_offered_only_where_they_apply():
+    """bf16, nine taps, channels contiguous and in sixteens: 16-byte channel vectors, read from
+    a staged patch of the zero-extended image while every tile's pixel range fits it (512
+    pixels), else gathered tap by tap; any other layout falls back to the element-wise kernels."""
+    h = ig.Handle()
+    nhwc = lambda c, hh, ww: (hh * ww * c, 1, ww * c, c)
+
+    def mode(N, C, H, W, K, R=3, S=3, pad=(1, 1), stride=(1, 1), xs=None):
+        x, w, c, y = _descs(N, C, H, W, K, R, S, pad, stride, 1, 1, xs=xs or nhwc(C, H, W))
+        return ig.get_plan(h, x, w, c, y)
+
+    p5 = mode(32, 512, 14, 14, 512)
+    assert p5.gatherMode == 5 and p5.kSteps == 512 // 16 and p5.tileK == 144
+    assert mode(2, 32, 10, 12, 8, 1, 9, (0, 4)).gatherMode == 5          # nine taps in a row
+    # a 128-column tile of a 300-pixel-wide image spans 3 rows of 302 pixels: too long for the patch
+    assert mode(1, 32, 20, 300, 8).gatherMode == 4
+    # its pixel range grows with the stride
+    assert mode(2, 32, 40, 40, 8, stride=(4, 4)).gatherMode == 4
+    assert mode(2, 24, 14, 14, 8).gatherMode in (0, 1)                    # channels not in sixteens
+    assert mode(2, 32, 14, 14, 8, 5, 5, (2, 2)).gatherMode in (0, 1)      # not nine taps
+    assert mode(2, 32, 14, 14, 8, xs=(32 * 196, 196, 14, 1)).gatherMode in (0, 1)   # NCHW
+    assert mode(2, 32, 14, 14, 8, xs=(14 * 14 * 32 + 4, 1, 14 * 32, 32)).gatherMode in (0, 1)  # image pitch not 16-byte
+
+
 def _fwd_status(x, w, c, y, xp=256, wp=256, yp=256, handle=None, alpha=True, beta=True):
     """Call igcConvolutionForward with fake (never dereferenced) pointers: only legal
     for argument sets that validation rejects before any GPU call."""
