@@ -156,6 +156,41 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
                                 const void *beta,
                                 igcTensorDescriptor_t yDesc, void *y);
 
+/* ---- backward data (Section 2.1.1: the forms needed for back-propagation are closely
+ * related to the forward one; Section 2.1: the same convolution descriptor serves the
+ * forward and the backward passes; results are returned raw or accumulated) -----------
+ *
+ *   dx[n,c,h,w] = alpha * sum over all (k,p,q,r,s) whose forward read lands on (h,w)
+ *                           of w[k,c,r,s] * dy[n,k,p,q]      + beta * dx[n,c,h,w]
+ *
+ * i.e. the transpose of igcConvolutionForward with respect to x, for the same filter and
+ * convolution descriptors.  It runs as an implicit GEMM as well (rows c, columns (n,h,w),
+ * reduction (k,r,s)): the gathered operand is dy, no lowered matrix is stored and no
+ * workspace is needed; with strides u, v above 1 one launch is made per residue class of
+ * (h mod u, w mod v), each reducing over exactly the taps that reach it.
+ *
+ *  - w (device, read): packed K,C,R,S.  dy (device, read): laid out by dyDesc, dimensions
+ *    (N, K, P, Q) with P, Q = eq. 1 of dxDesc's H, W.  dx (device, written; read only when
+ *    *beta != 0): laid out by dxDesc, dimensions (N, C, H, W); input rows or columns the
+ *    forward pass never reads receive beta * dx.
+ *  - Data types: (w, dy, dx) = (float, float, float) or (bfloat16, bfloat16, float).
+ *  - dx must not overlap w or dy and its strides must not alias (else BAD_PARAM).
+ *  - Errors as for igcConvolutionForward; all validation precedes the first launch.
+ *  - igcSetKernelOverride does not apply; results are deterministic. */
+igcStatus igcGetConvolutionBackwardDataWorkspaceSize(igcHandle_t handle,
+                                                     igcFilterDescriptor_t wDesc,
+                                                     igcTensorDescriptor_t dyDesc,
+                                                     igcConvolutionDescriptor_t convDesc,
+                                                     igcTensorDescriptor_t dxDesc,
+                                                     size_t *sizeInBytes);
+igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha,
+                                     igcFilterDescriptor_t wDesc, const void *w,
+                                     igcTensorDescriptor_t dyDesc, const void *dy,
+                                     igcConvolutionDescriptor_t convDesc,
+                                     void *workSpace, size_t workSpaceSizeInBytes,
+                                     const void *beta,
+                                     igcTensorDescriptor_t dxDesc, void *dx);
+
 /* ---- introspection and tuning (host only; no GPU call) ----------------------------
  * The launch plan the library derives for a problem: the tile of the lowered
  * product O_m (K x NPQ) = F_m (K x CRS) . D_m (CRS x NPQ) each workgroup computes,

@@ -15,6 +15,7 @@ __all__ = [
     "igcConvolutionForwardPlan", "DECLARED_SYMBOLS",
     "Handle", "TensorDescriptor", "FilterDescriptor", "ConvolutionDescriptor",
     "get_output_dim", "get_workspace_size", "get_plan", "convolution_forward",
+    "get_backward_data_workspace_size", "convolution_backward_data",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
 ]
 
@@ -59,6 +60,8 @@ DECLARED_SYMBOLS = {
     "igcGetConvolution2dForwardOutputDim": (_i, [_vp, _vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
     "igcGetConvolutionForwardWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
     "igcConvolutionForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "igcGetConvolutionBackwardDataWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
+    "igcConvolutionBackwardData": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
     "igcGetKernelCount": (_i, []),
     "igcGetKernelName": (ctypes.c_char_p, [_i]),
@@ -213,6 +216,23 @@ def convolution_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, y
     return lib().igcConvolutionForward(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
+
+
+def get_backward_data_workspace_size(handle, wdesc, dydesc, conv, dxdesc):
+    out = _sz(12345)
+    check(lib().igcGetConvolutionBackwardDataWorkspaceSize(handle.ptr, wdesc.ptr, dydesc.ptr, conv.ptr, dxdesc.ptr,
+                                                           ctypes.byref(out)),
+          "igcGetConvolutionBackwardDataWorkspaceSize")
+    return out.value
+
+
+def convolution_backward_data(handle, alpha, wdesc, w_ptr, dydesc, dy_ptr, conv, beta, dxdesc, dx_ptr,
+                              workspace_ptr=0, workspace_bytes=0):
+    """igcConvolutionBackwardData with device pointers given as integers; returns the status."""
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcConvolutionBackwardData(
+        handle.ptr, ctypes.byref(a), wdesc.ptr, _vp(w_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
+        _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
 
 
 def kernel_names():

@@ -5,6 +5,7 @@
 
 #include <stdint.h>
 #include <algorithm>
+#include <vector>
 #include <new>
 
 #include "igconv_kernel_table.h"
@@ -108,6 +109,8 @@ struct Problem {
     ConvKernelParams kp;
     bool bf16;
     int vec;  // elements per 16 bytes of input
+    int only_gmode = -1;      // >= 0: the one gather mode that can run this problem
+    bool zero_steps = false;  // nothing to accumulate: the kernel only scales the old output
 };
 
 // Everything igcConvolutionForward checks that does not need the data pointers.
@@ -160,6 +163,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
         if (!magic_for((uint32_t)k.PQ, &k.mPQ) || !magic_for((uint32_t)k.Q, &k.mQ) ||
             !magic_for((uint32_t)k.RS, &k.mRS) || !magic_for((uint32_t)k.S, &k.mS))
             return IGC_STATUS_NOT_SUPPORTED;
+        k.wsRow = k.CRS; k.wsRed = k.RS; k.wTap0 = 0; k.wsTapR = k.S; k.wsTapS = 1;
         k.xsN = (int)x->stride[0]; k.xsC = (int)x->stride[1]; k.xsH = (int)x->stride[2]; k.xsW = (int)x->stride[3];
         k.ysN = (int)y->stride[0]; k.ysK = (int)y->stride[1]; k.ysP = (int)y->stride[2]; k.ysQ = (int)y->stride[3];
         out->bf16 = b16;
@@ -245,7 +249,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     const bool can_vec = w_aligned && (k.CRS % pr.vec == 0);
     // Lanes should run along y's unit-stride dimension in the epilogue.
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
-    if (h->kernelOverride >= 0) {
+    if (h->kernelOverride >= 0 && pr.only_gmode < 0) {   // (the override is for the forward pass)
         const KernelInfo *ki = kernel_info(h->kernelOverride);
         if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(*ki, k, x_aligned))
             return IGC_STATUS_NOT_SUPPORTED;
@@ -257,6 +261,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
+        if (pr.only_gmode >= 0 && ki.gmode != pr.only_gmode) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -276,7 +281,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     k.tilesM = (k.K + ki.BM - 1) / ki.BM;
     k.tilesN = (k.NPQ + ki.BN - 1) / ki.BN;
     k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN + 7) / 8);
-    const long long steps = kernel_steps(ki, k);
+    const long long steps = pr->zero_steps ? 0 : kernel_steps(ki, k);
     if (steps >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
     k.ksteps = (int)steps;
     // first step of a ragged end of the reduction range (see the kernel): tap-major order,
@@ -300,6 +305,115 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         plan->gatherMode = ki.gmode;
     }
     return IGC_STATUS_SUCCESS;
+}
+
+
+// ---- backward data ------------------------------------------------------------------
+// dx[n,c,h,w] = sum over (k,p,q,r,s) whose forward read lands on (h,w) of w[k,c,r,s] * dy[n,k,p,q].
+// Per axis, with e the tap counted in reading direction (e = r for cross-correlation,
+// R-1-r for eq. 2), the forward pass reads row p*u + e - pad.  The rows h = ph (mod u) of dx
+// therefore only meet the taps e = a (mod u), a = (ph + pad) mod u: writing h = ph + u*i and
+// e = a + u*t gives p = i + b - t with b = (ph + pad - a)/u.  That is a stride-1 gather over
+// dy with R' = ceil((R - a)/u) taps: with tap index g = R'-1-t it reads row i + g - (R'-1-b),
+// i.e. the forward kernel's own addressing with pad R'-1-b, taps walked backwards through
+// the filter, and the roles of k and c exchanged.  One launch per phase (ph, pw), each
+// writing its own rows and columns of dx through strides multiplied by (u, v); for u = v = 1
+// there is a single phase.  A phase that meets no tap still runs, with zero reduction
+// steps, so that its part of dx becomes beta * dx.
+struct PhaseAxis {
+    int count;   // outputs of this phase along the axis
+    int taps;    // R' (0: none)
+    int pad;     // pad of the equivalent stride-1 gather (may be negative)
+    int tap0;    // filter index of gather tap g = 0
+    int tap_step;  // filter index step per gather tap
+};
+
+static PhaseAxis phase_axis(int H, int R, int pad, int u, bool flip, int ph) {
+    PhaseAxis a{};
+    a.count = ph < H ? (H - ph + u - 1) / u : 0;
+    const int r0 = (ph + pad) % u, b = (ph + pad) / u;
+    a.taps = r0 < R ? (R - r0 + u - 1) / u : 0;
+    a.pad = a.taps - 1 - b;
+    const int e0 = r0 + u * (a.taps - 1);   // reading-direction tap of g = 0; g steps it by -u
+    a.tap0 = flip ? R - 1 - e0 : e0;
+    a.tap_step = flip ? u : -u;
+    return a;
+}
+
+struct BackwardDataProblem {
+    // validated sizes, forward naming
+    int N, C, H, W, K, R, S, P, Q, pad_h, pad_w, u, v;
+    bool flip, bf16;
+    long long dys[4], dxs[4];
+    long long dy_bytes, w_bytes, dx_bytes;
+};
+
+static igcStatus validate_backward_data(igcFilterDescriptor_t w, igcTensorDescriptor_t dy, igcConvolutionDescriptor_t cv,
+                                        igcTensorDescriptor_t dx, BackwardDataProblem *out) {
+    if (!w || !dy || !cv || !dx) return IGC_STATUS_BAD_PARAM;
+    if (!w->set || !dy->set || !cv->set || !dx->set) return IGC_STATUS_NOT_INITIALIZED;
+    if (dx->dim[1] != w->c || dy->dim[1] != w->k || dy->dim[0] != dx->dim[0]) return IGC_STATUS_BAD_PARAM;
+    const long long P = out_dim(dx->dim[2], w->r, cv->u, cv->pad_h);
+    const long long Q = out_dim(dx->dim[3], w->s, cv->v, cv->pad_w);
+    if (P < 1 || Q < 1 || dy->dim[2] != P || dy->dim[3] != Q) return IGC_STATUS_BAD_PARAM;
+    if (!non_aliasing(dx->dim, dx->stride)) return IGC_STATUS_BAD_PARAM;
+    const bool f32 = dy->dtype == IGC_DATA_FLOAT && w->dtype == IGC_DATA_FLOAT;
+    const bool b16 = dy->dtype == IGC_DATA_BFLOAT16 && w->dtype == IGC_DATA_BFLOAT16;
+    if (!(f32 || b16) || dx->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    const int es = elem_size(dy->dtype);
+    BackwardDataProblem b{};
+    b.dy_bytes = extent(dy->dim, dy->stride) * es;
+    b.dx_bytes = extent(dx->dim, dx->stride) * 4;
+    b.w_bytes = (long long)w->k * w->c * w->r * w->s * es;
+    if (b.dy_bytes >= kMaxBytes || b.dx_bytes >= kMaxBytes || b.w_bytes >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
+    if ((long long)dx->dim[0] * dx->dim[2] * dx->dim[3] >= (1ll << 30) || (long long)w->k * w->r * w->s >= (1ll << 30))
+        return IGC_STATUS_NOT_SUPPORTED;
+    // packed 16-bit window coordinates: sizes, pads and tap counts stay below 2^14
+    if (dx->dim[2] > (1 << 14) || dx->dim[3] > (1 << 14) || cv->pad_h >= (1 << 14) || cv->pad_w >= (1 << 14) ||
+        w->r > (1 << 14) || w->s > (1 << 14) || P > (1 << 14) || Q > (1 << 14))
+        return IGC_STATUS_NOT_SUPPORTED;
+    b.N = dx->dim[0]; b.C = dx->dim[1]; b.H = dx->dim[2]; b.W = dx->dim[3];
+    b.K = w->k; b.R = w->r; b.S = w->s; b.P = (int)P; b.Q = (int)Q;
+    b.pad_h = cv->pad_h; b.pad_w = cv->pad_w; b.u = cv->u; b.v = cv->v;
+    b.flip = cv->mode == IGC_CONVOLUTION;
+    b.bf16 = b16;
+    for (int i = 0; i < 4; ++i) { b.dys[i] = dy->stride[i]; b.dxs[i] = dx->stride[i]; }
+    if (out) *out = b;
+    return IGC_STATUS_SUCCESS;
+}
+
+// The launch parameters of phase (ph, pw); false when the phase has no output element.
+static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Problem *pr, long long *dx_offset) {
+    const PhaseAxis ah = phase_axis(b.H, b.R, b.pad_h, b.u, b.flip, ph);
+    const PhaseAxis aw = phase_axis(b.W, b.S, b.pad_w, b.v, b.flip, pw);
+    if (ah.count <= 0 || aw.count <= 0) return false;
+    *pr = Problem{};
+    pr->bf16 = b.bf16;
+    pr->vec = b.bf16 ? 8 : 4;
+    pr->only_gmode = 1;
+    pr->zero_steps = ah.taps == 0 || aw.taps == 0;
+    ConvKernelParams &k = pr->kp;
+    const int es = b.bf16 ? 2 : 4;
+    const int Rp = std::max(ah.taps, 1), Sp = std::max(aw.taps, 1);
+    *dx_offset = (long long)ph * b.dxs[2] + (long long)pw * b.dxs[3];
+    k.x_bytes = (uint32_t)b.dy_bytes;
+    k.w_bytes = (uint32_t)b.w_bytes;
+    k.y_bytes = (uint32_t)(b.dx_bytes - *dx_offset * 4);
+    // the gather runs over dy: its channels are the reduction, its rows and columns the image
+    k.N = b.N; k.C = b.K; k.H = b.P; k.W = b.Q;
+    k.K = b.C; k.R = Rp; k.S = Sp; k.P = ah.count; k.Q = aw.count;
+    k.pad_h = ah.pad; k.pad_w = aw.pad; k.u = 1; k.v = 1; k.flip = 0;
+    k.RS = Rp * Sp; k.CRS = b.K * k.RS; k.PQ = ah.count * aw.count; k.NPQ = b.N * k.PQ;
+    k.Wp = 1; k.HpWp = 1;   // (patch staging is never used here)
+    magic_for(1, &k.mWp); magic_for(1, &k.mHpWp);
+    magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
+    magic_for((uint32_t)k.RS, &k.mRS); magic_for((uint32_t)k.S, &k.mS);
+    k.wsRow = b.R * b.S; k.wsRed = b.C * b.R * b.S;
+    k.wTap0 = ah.tap0 * b.S + aw.tap0; k.wsTapR = ah.tap_step * b.S; k.wsTapS = aw.tap_step;
+    k.xsN = (int)b.dys[0]; k.xsC = (int)b.dys[1]; k.xsH = (int)b.dys[2]; k.xsW = (int)b.dys[3];
+    k.ysN = (int)b.dxs[0]; k.ysK = (int)b.dxs[1]; k.ysP = (int)(b.dxs[2] * b.u); k.ysQ = (int)(b.dxs[3] * b.v);
+    (void)es;
+    return true;
 }
 
 }  // namespace igc
@@ -554,6 +668,54 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha, igcTensor
     pr.kp.beta = *static_cast<const float *>(beta);
     const int err = kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream);
     return err == 0 ? IGC_STATUS_SUCCESS : IGC_STATUS_EXECUTION_FAILED;
+}
+
+igcStatus igcGetConvolutionBackwardDataWorkspaceSize(igcHandle_t handle, igcFilterDescriptor_t wDesc,
+                                                     igcTensorDescriptor_t dyDesc, igcConvolutionDescriptor_t convDesc,
+                                                     igcTensorDescriptor_t dxDesc, size_t *sizeInBytes) {
+    if (!handle || !sizeInBytes) return IGC_STATUS_BAD_PARAM;
+    const igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, nullptr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    *sizeInBytes = 0;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcFilterDescriptor_t wDesc, const void *w,
+                                     igcTensorDescriptor_t dyDesc, const void *dy, igcConvolutionDescriptor_t convDesc,
+                                     void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
+                                     igcTensorDescriptor_t dxDesc, void *dx) {
+    (void)workSpace;
+    (void)workSpaceSizeInBytes;
+    if (!handle || !alpha || !beta || !w || !dy || !dx) return IGC_STATUS_BAD_PARAM;
+    BackwardDataProblem b;
+    igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const int es = b.bf16 ? 2 : 4;
+    if ((uintptr_t)dy % es || (uintptr_t)w % es || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    // plan every phase before the first launch, so that a rejected problem launches nothing
+    struct Launch { Problem pr; int id; int grid; };
+    std::vector<Launch> launches;
+    for (int ph = 0; ph < b.u; ++ph)
+        for (int pw = 0; pw < b.v; ++pw) {
+            Launch l;
+            long long off = 0;
+            if (!backward_data_phase(b, ph, pw, &l.pr, &off)) continue;
+            st = choose(handle, l.pr, /*w_aligned=*/false, /*x_aligned=*/false, &l.id);
+            if (st != IGC_STATUS_SUCCESS) return st;
+            igcConvolutionForwardPlan plan;
+            st = fill_plan(l.id, &l.pr, &plan);
+            if (st != IGC_STATUS_SUCCESS) return st;
+            l.grid = plan.gridX;
+            l.pr.kp.x = dy;
+            l.pr.kp.w = w;
+            l.pr.kp.y = static_cast<float *>(dx) + off;
+            l.pr.kp.alpha = *static_cast<const float *>(alpha);
+            l.pr.kp.beta = *static_cast<const float *>(beta);
+            launches.push_back(l);
+        }
+    for (const Launch &l : launches)
+        if (kernel_info(l.id)->launch(l.pr.kp, l.grid, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    return IGC_STATUS_SUCCESS;
 }
 
 }  // extern "C"

@@ -339,14 +339,17 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
     // reduction range.  The per-thread part of the offset is fixed, the step's part is a
     // scalar.  Filter order: index k0 + a_kk of row `row`.  Tap-major: channel
-    // c0 + a_kk, tap of the step, i.e. a read with stride R*S elements.
+    // c0 + a_kk, tap of the step, i.e. a strided read (stride R*S elements in the
+    // forward pass); row, channel and tap strides come from the launch parameters.
     uint32_t a_voff[A_PASSES];
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps) {
         const int row = m0 + a_row[ps];
-        const uint32_t col = GM == GATHER_TAPMAJOR ? (uint32_t)a_kk[ps] * (uint32_t)p.RS : (uint32_t)a_kk[ps];
         const bool ok = row < p.K && a_row[ps] < BM;
-        a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.CRS + col) * ES : kOutOfRange;
+        if constexpr (GM == GATHER_TAPMAJOR)
+            a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.wsRow + (uint32_t)a_kk[ps] * (uint32_t)p.wsRed) * ES : kOutOfRange;
+        else
+            a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)a_kk[ps]) * ES : kOutOfRange;
     }
 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
@@ -370,7 +373,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             sc_ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
             sc_c0 = cc * BK;
             const uint32_t live = mask_lt(ut, (uint32_t)p.ksteps);
-            sc_asoff = (((sc_c0 * (uint32_t)p.RS + tap) * ES) & live) | (p.w_bytes & ~live);
+            // (wrap-around arithmetic: a tap stride may be negative, the sum never is)
+            const uint32_t woff = sc_c0 * (uint32_t)p.wsRed + (uint32_t)p.wTap0 + r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS;
+            sc_asoff = ((woff * ES) & live) | (p.w_bytes & ~live);
             const uint32_t c = sc_c0 + (uint32_t)(kpart * KPT) + (uint32_t)lane;
             dec_so = (c < (uint32_t)p.C && live) ? c * (uint32_t)p.xsC * ES : p.x_bytes;
         } else {

@@ -32,6 +32,11 @@ struct ConvKernelParams {
     int32_t tilesPerXcd;  // ceil(tilesM * tilesN / 8): tiles are dealt to the 8 XCDs in contiguous ranges
     int32_t ksteps;  // reduction steps of the chosen kernel (depends on its reduction order)
     int32_t tail_step;  // first step in which the reduction range ends inside the step, else -1
+    // Where the filter element (row m, reduction channel c, tap (r,s)) lives, in elements:
+    // m*wsRow + c*wsRed + wTap0 + r*wsTapR + s*wsTapS (tap-major kernels only; the others
+    // read the packed K,C,R,S order directly).  Forward: (C*R*S, R*S, 0, S, 1).  Backward-data
+    // exchanges the roles of k and c and walks a subset of the taps backwards.
+    int32_t wsRow, wsRed, wTap0, wsTapR, wsTapS;
     // zero-extended image: Wp = W + 2 pad_w pixels per row, HpWp = (H + 2 pad_h) * Wp per image
     int32_t Wp, HpWp;
     Magic mWp, mHpWp;

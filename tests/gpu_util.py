@@ -115,3 +115,75 @@ def rel_err(got, want):
 
 
 TOL = {"f32": 2e-5, "bf16": 1e-2}
+
+
+def _device_tensor(a, dtype):
+    """(device tensor holding a's memory span, element strides, byte offset 0)."""
+    return to_device_strided(a, dtype)
+
+
+class GuardedOutput:
+    """A float32 device buffer for a strided logical 4-D tensor, with guard bands."""
+
+    def __init__(self, shape, strides):
+        self.shape, self.strides = tuple(shape), tuple(strides)
+        self.ext = extent(self.shape, self.strides)
+        self.buf = torch.full((self.ext + 2 * GUARD,), GUARD_VALUE, dtype=torch.float32, device="cuda")
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr() + 4 * GUARD
+
+    def view(self):
+        return torch.as_strided(self.buf, self.shape, self.strides, storage_offset=GUARD)
+
+    def prefill(self, old=None, value=None):
+        inner = self.buf[GUARD:GUARD + self.ext]
+        if old is not None:
+            inner.fill_(float("nan"))
+            self.view().copy_(torch.from_numpy(np.ascontiguousarray(old)).cuda())
+        else:
+            inner.fill_(value)
+
+    def result(self):
+        torch.cuda.synchronize()
+        g = self.buf.cpu().numpy()
+        assert np.all(g[:GUARD] == GUARD_VALUE) and np.all(g[GUARD + self.ext:] == GUARD_VALUE), \
+            "store outside the output's extent"
+        return self.view().cpu().numpy().astype(np.float64)
+
+
+def layout_strides(shape, layout):
+    n, c, h, w = shape
+    if layout == "NCHW":
+        return (c * h * w, h * w, w, 1)
+    if layout == "NHWC":
+        return (h * w * c, 1, w * c, c)
+    raise ValueError(layout)
+
+
+def run_backward_data(dy, w, hw, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0,
+                      dx_old=None, dtype="f32", dx_layout="NCHW"):
+    """One igcConvolutionBackwardData call; returns dx as float64, logical (N,C,H,W)."""
+    handle = ig.Handle()
+    handle.set_stream(torch.cuda.current_stream().cuda_stream)
+    N, K, P, Q = dy.shape
+    _, C, R, S = w.shape
+    dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+    dy_dev, dys = to_device_strided(dy, dtype)
+    w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
+    dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
+    wdesc = ig.FilterDescriptor().set(dt, K, C, R, S)
+    conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+    shape = (N, C, hw[0], hw[1])
+    out = GuardedOutput(shape, layout_strides(shape, dx_layout))
+    dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, out.strides)
+    assert ig.get_backward_data_workspace_size(handle, wdesc, dydesc, conv, dxdesc) == 0
+    if dx_old is not None:
+        out.prefill(old=dx_old)
+    else:
+        out.prefill(value=float("nan"))
+    st = ig.convolution_backward_data(handle, alpha, wdesc, w_dev.data_ptr(), dydesc, dy_dev.data_ptr(), conv, beta,
+                                      dxdesc, out.ptr)
+    ig.check(st, "igcConvolutionBackwardData")
+    return out.result()

@@ -1,0 +1,85 @@
+"""GPU parity of the backward passes: the HIP library (through its C ABI) against the CPU
+oracle's backward forms, element by element on the same seeded inputs.  Bar as for the
+forward pass: max|gpu - oracle| / max|oracle| <= 2e-5 (fp32), <= 1e-2 (bf16 inputs)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import workloads as wl
+from oracle import conv_oracle as oc
+
+
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _rnd(seed, shape, dtype):
+    a = np.random.default_rng(seed).uniform(-1, 1, size=shape).astype(np.float32)
+    return wl.round_to_bf16(a) if dtype == "bf16" else a
+
+
+# N, C, H, W, K, R, S, pad, stride
+BWD_PROBLEMS = [
+    (2, 5, 9, 11, 7, 3, 3, (1, 1), (1, 1)),
+    (3, 40, 14, 13, 150, 3, 3, (1, 1), (1, 1)),       # several tiles, ragged channel chunks
+    (2, 3, 23, 21, 70, 5, 5, (2, 2), (2, 2)),         # four phases
+    (1, 6, 30, 17, 20, 7, 1, (3, 0), (3, 1)),         # a phase with fewer taps
+    (2, 4, 12, 12, 9, 1, 1, (0, 0), (2, 2)),          # 1x1, stride 2: three phases meet no tap
+    (1, 3, 35, 35, 96, 11, 11, (0, 0), (4, 4)),       # first-layer shape, 16 phases
+    (2, 7, 12, 40, 33, 1, 7, (0, 3), (1, 3)),
+    (2, 2, 8, 8, 4, 4, 4, (3, 3), (1, 1)),            # "full" padding
+    (2, 8, 10, 11, 5, 3, 3, (0, 0), (3, 3)),          # stride leaves rows and columns unread
+]
+
+
+def _check_bd(prob, dtype, mode, alpha=1.0, beta=0.0, dx_layout="NCHW", dy_layout="NCHW", seed=0):
+    gu = _gpu()
+    N, C, H, W, K, R, S, pad, stride = prob
+    P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
+    dy = wl.with_layout(_rnd(seed + 1, (N, K, P, Q), dtype), dy_layout)
+    w = _rnd(seed + 2, (K, C, R, S), dtype)
+    dx_old = _rnd(seed + 3, (N, C, H, W), "f32") if beta != 0.0 else None
+    print("backward data", prob, dtype, mode, alpha, beta, dx_layout, dy_layout, flush=True)
+    got = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, alpha, beta, dx_old, dtype, dx_layout)
+    want = oc.conv_backward_data(dy, w, (H, W), pad=pad, stride=stride, mode=mode, alpha=alpha, beta=beta, dx_old=dx_old)
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got)), "non-finite output (NaN prefill leaked or garbage)"
+    err = gu.rel_err(got, want)
+    assert err <= gu.TOL[dtype], "rel err %.3g > %.3g" % (err, gu.TOL[dtype])
+    return err
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("prob", BWD_PROBLEMS, ids=[str(i) for i in range(len(BWD_PROBLEMS))])
+def test_backward_data_sweep(prob, dtype, mode):
+    _check_bd(prob, dtype, mode, seed=10 * BWD_PROBLEMS.index(prob))
+
+
+@pytest.mark.parametrize("dx_layout,dy_layout", [("NHWC", "NHWC"), ("NHWC", "NCHW"), ("NCHW", "NHWC")])
+def test_backward_data_layouts(dx_layout, dy_layout):
+    _check_bd(BWD_PROBLEMS[1], "f32", 1, dx_layout=dx_layout, dy_layout=dy_layout)
+    _check_bd(BWD_PROBLEMS[2], "bf16", 0, dx_layout=dx_layout, dy_layout=dy_layout)
+
+
+def test_backward_data_accumulates():
+    """out = alpha * raw + beta * old; rows the forward pass never reads keep beta * old."""
+    for prob in (BWD_PROBLEMS[1], BWD_PROBLEMS[4], BWD_PROBLEMS[8]):
+        _check_bd(prob, "f32", 1, alpha=0.5, beta=-1.5)
+        _check_bd(prob, "f32", 0, alpha=2.0, beta=1.0, dx_layout="NHWC")
+
+
+def test_backward_data_is_the_transpose_of_forward_on_the_gpu():
+    """<forward(x,w), dy> == <x, backward_data(dy,w)> with both sides from the library."""
+    gu = _gpu()
+    N, C, H, W, K, R, S, pad, stride = BWD_PROBLEMS[2]
+    x, w = _rnd(1, (N, C, H, W), "f32"), _rnd(2, (K, C, R, S), "f32")
+    y, _ = gu.run(x, w, pad, stride, 1)
+    dy = _rnd(3, y.shape, "f32")
+    dx = gu.run_backward_data(dy, w, (H, W), pad, stride, 1)
+    lhs, rhs = float(np.sum(y * dy)), float(np.sum(dx * x))
+    assert abs(lhs - rhs) <= 1e-4 * max(1.0, abs(lhs))
