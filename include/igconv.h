@@ -1,5 +1,6 @@
 /*
- * igconv - implicit-GEMM convolution forward for AMD MI355X (gfx950).
+ * igconv - implicit-GEMM convolution (forward, backward data, backward filter) for AMD
+ * MI355X (gfx950).
  *
  * C ABI of the library.  It follows the problem statement of the paper
  * "cuDNN: Efficient Primitives for Deep Learning" (arXiv 1410.0759): a host-callable
@@ -17,7 +18,8 @@
  *    Descriptors are read at call time only: they may be changed or destroyed as
  *    soon as a call returns.
  *  - x, w and y are DEVICE pointers owned by the caller.  The library never
- *    allocates, frees or copies device memory and needs no workspace.
+ *    allocates, frees or copies device memory; only igcConvolutionBackwardFilter can
+ *    make use of a workspace, which the caller provides.
  *  - alpha and beta are HOST pointers to float (the compute type is fp32 for every
  *    supported data type); they are read before the call returns.
  *  - igcConvolutionForward only enqueues work on the handle's stream and returns.
@@ -190,6 +192,44 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha,
                                      void *workSpace, size_t workSpaceSizeInBytes,
                                      const void *beta,
                                      igcTensorDescriptor_t dxDesc, void *dx);
+
+/* ---- backward filter (same passages as backward data) ------------------------------
+ *
+ *   dw[k,c,r,s] = alpha * sum_{n,p,q} dy[n,k,p,q] * x0[n,c,hh,ww] + beta * dw[k,c,r,s]
+ *
+ * with x0, hh, ww as in igcConvolutionForward: the transpose of the forward pass with
+ * respect to w.  An implicit GEMM as well (rows k, columns (c,r,s), reduction (n,p,q));
+ * the lowered matrix is never stored.  The output is small and the reduction long, so the
+ * reduction is cut into ranges computed side by side, each leaving a partial K*C*R*S
+ * result in the workspace, which a second kernel adds up in a fixed order (results are
+ * deterministic) while applying alpha and beta.
+ *
+ *  - x (device, read): laid out by xDesc.  dy (device, read): laid out by dyDesc,
+ *    dimensions (N, K, P, Q) from eq. 1.  dw (device, written; read only when *beta != 0):
+ *    packed K,C,R,S floats, described by dwDesc (data type float).
+ *  - Data types: (x, dy, dw) = (float, float, float) or (bfloat16, bfloat16, float).
+ *  - workSpace (device, scratch, 4-byte aligned, owned by the caller, may be reused as
+ *    soon as the stream has run the call): igcGetConvolutionBackwardFilterWorkspaceSize
+ *    reports the size that lets the reduction be cut as finely as the library would like.
+ *    Any smaller size is accepted, NULL / 0 included: the reduction is then cut into as
+ *    many ranges as fit (a multiple of K*C*R*S*4 bytes each), down to a single range that
+ *    writes dw directly - same result up to summation order, less parallelism.
+ *  - dw and workSpace must not overlap x, dy or each other.
+ *  - NOT_SUPPORTED also when H + 2*pad_h or W + 2*pad_w exceeds 2^14.
+ *  - Other errors as for igcConvolutionForward; igcSetKernelOverride does not apply. */
+igcStatus igcGetConvolutionBackwardFilterWorkspaceSize(igcHandle_t handle,
+                                                       igcTensorDescriptor_t xDesc,
+                                                       igcTensorDescriptor_t dyDesc,
+                                                       igcConvolutionDescriptor_t convDesc,
+                                                       igcFilterDescriptor_t dwDesc,
+                                                       size_t *sizeInBytes);
+igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha,
+                                       igcTensorDescriptor_t xDesc, const void *x,
+                                       igcTensorDescriptor_t dyDesc, const void *dy,
+                                       igcConvolutionDescriptor_t convDesc,
+                                       void *workSpace, size_t workSpaceSizeInBytes,
+                                       const void *beta,
+                                       igcFilterDescriptor_t dwDesc, void *dw);
 
 /* ---- introspection and tuning (host only; no GPU call) ----------------------------
  * The launch plan the library derives for a problem: the tile of the lowered

@@ -16,6 +16,7 @@ __all__ = [
     "Handle", "TensorDescriptor", "FilterDescriptor", "ConvolutionDescriptor",
     "get_output_dim", "get_workspace_size", "get_plan", "convolution_forward",
     "get_backward_data_workspace_size", "convolution_backward_data",
+    "get_backward_filter_workspace_size", "convolution_backward_filter",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
 ]
 
@@ -62,6 +63,8 @@ DECLARED_SYMBOLS = {
     "igcConvolutionForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcGetConvolutionBackwardDataWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
     "igcConvolutionBackwardData": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "igcGetConvolutionBackwardFilterWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
+    "igcConvolutionBackwardFilter": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
     "igcGetKernelCount": (_i, []),
     "igcGetKernelName": (ctypes.c_char_p, [_i]),
@@ -233,6 +236,23 @@ def convolution_backward_data(handle, alpha, wdesc, w_ptr, dydesc, dy_ptr, conv,
     return lib().igcConvolutionBackwardData(
         handle.ptr, ctypes.byref(a), wdesc.ptr, _vp(w_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
+
+
+def get_backward_filter_workspace_size(handle, xdesc, dydesc, conv, dwdesc):
+    out = _sz(12345)
+    check(lib().igcGetConvolutionBackwardFilterWorkspaceSize(handle.ptr, xdesc.ptr, dydesc.ptr, conv.ptr, dwdesc.ptr,
+                                                             ctypes.byref(out)),
+          "igcGetConvolutionBackwardFilterWorkspaceSize")
+    return out.value
+
+
+def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, conv, beta, dwdesc, dw_ptr,
+                                workspace_ptr=0, workspace_bytes=0):
+    """igcConvolutionBackwardFilter with device pointers given as integers; returns the status."""
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcConvolutionBackwardFilter(
+        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
+        _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
 
 
 def kernel_names():

@@ -43,7 +43,7 @@ constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad};
 
 int kernel_count() {
     int n = 0;
@@ -232,6 +232,7 @@ static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
 // staging a patch of the zero-extended image needs every tile's pixel range to fit it.
 static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
     const int gmode = ki.gmode;
+    if (gmode == 6) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
     if (gmode >= 4) {
@@ -414,6 +415,107 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
     k.ysN = (int)b.dxs[0]; k.ysK = (int)b.dxs[1]; k.ysP = (int)(b.dxs[2] * b.u); k.ysQ = (int)(b.dxs[3] * b.v);
     (void)es;
     return true;
+}
+
+
+// ---- backward filter ------------------------------------------------------------------
+// dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x0[n,c,row(p,r),col(q,s)]: an implicit GEMM with rows
+// k, columns i = (c,r,s) and the reduction over j = (n,p,q).  The gathered operand is x
+// again, with the two index sets exchanged: a column fixes (c, tap) and therefore the
+// window origin tap - pad (tap counted in reading direction), a reduction index adds
+// (p*u, q*v).  The kernel's generic gather does exactly that once its divisors, strides
+// and multipliers are renamed; the first operand is dy, read through its strides.  The
+// output is small (K x CRS) and the reduction long (NPQ), so the reduction is cut into
+// ranges that run as separate workgroups, each writing a partial result into the
+// workspace; a second kernel adds the parts in order (deterministic) and applies alpha
+// and beta.  Without workspace the whole reduction runs in one range, straight into dw.
+struct BackwardFilterProblem {
+    Problem pr;        // launch parameters with splits = 1, writing dw directly
+    int kernel_id;
+    long long ksteps;  // reduction steps in all
+    long long tiles;   // output tiles
+    uint32_t out_elems;  // K*C*R*S
+};
+
+static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDescriptor_t dy,
+                                          igcConvolutionDescriptor_t cv, igcFilterDescriptor_t dw,
+                                          BackwardFilterProblem *out) {
+    if (!x || !dy || !cv || !dw) return IGC_STATUS_BAD_PARAM;
+    if (!x->set || !dy->set || !cv->set || !dw->set) return IGC_STATUS_NOT_INITIALIZED;
+    if (x->dim[1] != dw->c || dy->dim[1] != dw->k || dy->dim[0] != x->dim[0]) return IGC_STATUS_BAD_PARAM;
+    const long long P = out_dim(x->dim[2], dw->r, cv->u, cv->pad_h);
+    const long long Q = out_dim(x->dim[3], dw->s, cv->v, cv->pad_w);
+    if (P < 1 || Q < 1 || dy->dim[2] != P || dy->dim[3] != Q) return IGC_STATUS_BAD_PARAM;
+    const bool f32 = x->dtype == IGC_DATA_FLOAT && dy->dtype == IGC_DATA_FLOAT;
+    const bool b16 = x->dtype == IGC_DATA_BFLOAT16 && dy->dtype == IGC_DATA_BFLOAT16;
+    if (!(f32 || b16) || dw->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    const int es = elem_size(x->dtype);
+    const long long xb = extent(x->dim, x->stride) * es, dyb = extent(dy->dim, dy->stride) * es;
+    const long long CRS = (long long)dw->c * dw->r * dw->s, NPQ = (long long)x->dim[0] * P * Q;
+    const long long dwb = (long long)dw->k * CRS * 4;
+    if (xb >= kMaxBytes || dyb >= kMaxBytes || dwb >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
+    if (NPQ >= (1ll << 30) || CRS >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
+    // packed 16-bit window coordinates: here the reduction index contributes up to
+    // (P-1)*u <= H + 2 pad - R, which must stay below 2^14 like the image size itself
+    if (x->dim[2] + 2ll * cv->pad_h > (1 << 14) || x->dim[3] + 2ll * cv->pad_w > (1 << 14)) return IGC_STATUS_NOT_SUPPORTED;
+    if (!out) return IGC_STATUS_SUCCESS;
+
+    *out = BackwardFilterProblem{};
+    Problem &pr = out->pr;
+    pr.bf16 = b16;
+    pr.vec = 16 / es;
+    pr.only_gmode = 6;
+    ConvKernelParams &k = pr.kp;
+    const bool flip = cv->mode == IGC_CONVOLUTION;
+    k.x_bytes = (uint32_t)xb;
+    k.w_bytes = (uint32_t)dyb;
+    k.y_bytes = (uint32_t)dwb;
+    k.N = x->dim[0]; k.C = x->dim[1]; k.H = x->dim[2]; k.W = x->dim[3];
+    k.K = dw->k; k.R = dw->r; k.S = dw->s; k.P = (int)P; k.Q = dw->s;
+    // columns (c,r,s): window origin (tap - pad) with the tap in reading direction
+    k.PQ = dw->r * dw->s; k.NPQ = (int)CRS;
+    k.u = flip ? -1 : 1; k.v = flip ? -1 : 1;
+    k.pad_h = flip ? cv->pad_h - (dw->r - 1) : cv->pad_h;
+    k.pad_w = flip ? cv->pad_w - (dw->s - 1) : cv->pad_w;
+    // reduction (n,p,q): adds (p*u, q*v)
+    k.RS = (int)(P * Q); k.CRS = (int)NPQ;
+    const int red_inner = (int)Q;
+    k.flip = 0; k.redMulH = cv->u; k.redMulW = cv->v;
+    k.Wp = 1; k.HpWp = 1;
+    magic_for(1, &k.mWp); magic_for(1, &k.mHpWp);
+    magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
+    magic_for((uint32_t)k.RS, &k.mRS); magic_for((uint32_t)red_inner, &k.mS);
+    k.S = red_inner;   // (from here on S is the reduction's inner divisor, Q of the forward pass)
+    k.xsN = (int)x->stride[1]; k.xsC = (int)x->stride[0]; k.xsH = (int)x->stride[2]; k.xsW = (int)x->stride[3];
+    k.ysN = dw->r * dw->s; k.ysK = (int)CRS; k.ysP = dw->s; k.ysQ = 1;
+    k.wsRow = (int)dy->stride[1]; k.wsRed = (int)dy->stride[0]; k.wsTapR = (int)dy->stride[2]; k.wsTapS = (int)dy->stride[3];
+    k.splits = 1;
+    out->out_elems = (uint32_t)(dw->k * CRS);
+    // kernel: the smaller row tile when it covers K
+    int id = -1;
+    for (int i = 0; i < kernel_count(); ++i) {
+        const KernelInfo &ki = *kernel_info(i);
+        if (ki.gmode != 6 || ki.bf16 != b16) continue;
+        if (id < 0 || (dw->k <= 64 ? ki.BM < kernel_info(id)->BM : ki.BM > kernel_info(id)->BM)) id = i;
+    }
+    if (id < 0) return IGC_STATUS_NOT_SUPPORTED;
+    out->kernel_id = id;
+    const KernelInfo &ki = *kernel_info(id);
+    out->ksteps = (NPQ + ki.BK - 1) / ki.BK;
+    out->tiles = (long long)((dw->k + ki.BM - 1) / ki.BM) * ((CRS + ki.BN - 1) / ki.BN);
+    return IGC_STATUS_SUCCESS;
+}
+
+// How to cut the reduction: enough workgroups to fill the chip twice over, ranges of an even
+// number of steps and not shorter than 8; at most max_parts ranges.
+static void backward_filter_split(const BackwardFilterProblem &b, long long max_parts, int *splits, int *steps_per_split) {
+    long long want = std::max<long long>(1, (2 * kComputeUnits + b.tiles - 1) / b.tiles);
+    want = std::min(want, std::max<long long>(1, b.ksteps / 8));
+    want = std::min(want, std::max<long long>(1, max_parts));
+    long long per = (b.ksteps + want - 1) / want;
+    per += per & 1;
+    *steps_per_split = (int)per;
+    *splits = (int)((b.ksteps + per - 1) / per);
 }
 
 }  // namespace igc
@@ -715,6 +817,60 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
         }
     for (const Launch &l : launches)
         if (kernel_info(l.id)->launch(l.pr.kp, l.grid, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolutionBackwardFilterWorkspaceSize(igcHandle_t handle, igcTensorDescriptor_t xDesc,
+                                                       igcTensorDescriptor_t dyDesc, igcConvolutionDescriptor_t convDesc,
+                                                       igcFilterDescriptor_t dwDesc, size_t *sizeInBytes) {
+    if (!handle || !sizeInBytes) return IGC_STATUS_BAD_PARAM;
+    BackwardFilterProblem b;
+    const igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int splits, per;
+    backward_filter_split(b, 1 << 20, &splits, &per);
+    *sizeInBytes = splits > 1 ? (size_t)splits * b.out_elems * 4 : 0;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, igcTensorDescriptor_t xDesc, const void *x,
+                                       igcTensorDescriptor_t dyDesc, const void *dy, igcConvolutionDescriptor_t convDesc,
+                                       void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
+                                       igcFilterDescriptor_t dwDesc, void *dw) {
+    if (!handle || !alpha || !beta || !x || !dy || !dw) return IGC_STATUS_BAD_PARAM;
+    BackwardFilterProblem b;
+    igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const int es = b.pr.bf16 ? 2 : 4;
+    if ((uintptr_t)x % es || (uintptr_t)dy % es || (uintptr_t)dw % 4 || (uintptr_t)workSpace % 4) return IGC_STATUS_BAD_PARAM;
+    const size_t part_bytes = (size_t)b.out_elems * 4;
+    int splits, per;
+    backward_filter_split(b, workSpace ? (long long)(workSpaceSizeInBytes / part_bytes) : 0, &splits, &per);
+    ConvKernelParams &k = b.pr.kp;
+    igcConvolutionForwardPlan plan;
+    st = fill_plan(b.kernel_id, &b.pr, &plan);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const float a = *static_cast<const float *>(alpha), bt = *static_cast<const float *>(beta);
+    k.x = x;
+    k.w = dy;
+    k.splits = splits;
+    k.stepsPerSplit = splits > 1 ? per : (int)(b.ksteps + (b.ksteps & 1));
+    k.ySplitBytes = (uint32_t)part_bytes;
+    k.tilesPerXcd = (int)((b.tiles * splits + 7) / 8);
+    if ((long long)k.tilesPerXcd * 8 >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
+    if (splits > 1) {
+        k.y = workSpace;
+        k.alpha = 1.f;
+        k.beta = 0.f;
+    } else {
+        k.y = dw;
+        k.alpha = a;
+        k.beta = bt;
+    }
+    if (kernel_info(b.kernel_id)->launch(k, 8 * k.tilesPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    if (splits > 1 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
+                                       b.out_elems, a, bt, handle->stream) != 0)
+        return IGC_STATUS_EXECUTION_FAILED;
     return IGC_STATUS_SUCCESS;
 }
 

@@ -177,7 +177,12 @@ enum GatherMode {
     // whole channels (BK = 36), so which tap an element has never changes; the nine
     // per-column tap offsets (window test folded in) are built once per tile and the
     // loop holds no vector instruction at all.  Any pad, stride, mode.
-    GATHER_TAPS9 = 3
+    GATHER_TAPS9 = 3,
+    // Backward-filter: the generic gather with the roles of the two index sets exchanged.
+    // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
+    // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
+    // the reduction may be cut into several ranges, one workgroup each (see the main loop).
+    GATHER_WGRAD = 6
 };
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
@@ -210,6 +215,7 @@ struct KernelConfig {
     static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
+    static_assert(GMODE != GATHER_WGRAD || (!VECA && 256 % BK == 0), "one reduction index per thread, element-wise first operand");
     static_assert(GMODE != GATHER_TAPS9 || (VECA && BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
@@ -219,6 +225,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
     constexpr int GM = Cfg::GMODE;
+    constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
@@ -236,8 +243,16 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // columns of D_m) and cut into 8 contiguous ranges, one per XCD, so that the
     // workgroups which share input rows and columns also share an L2.  The grid is
     // rounded up to 8 ranges of equal length; a workgroup past the last tile leaves.
-    const int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
-    if (tile >= p.tilesM * p.tilesN) return;
+    int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
+    // GATHER_WGRAD: the tile numbers repeat once per range of the reduction
+    int split = 0;
+    if constexpr (GM == GATHER_WGRAD) {
+        if (tile >= p.tilesM * p.tilesN * p.splits) return;
+        split = tile / (p.tilesM * p.tilesN);
+        tile -= split * (p.tilesM * p.tilesN);
+    } else {
+        if (tile >= p.tilesM * p.tilesN) return;
+    }
     const int tile_m = tile % p.tilesM;
     const int tile_n = tile / p.tilesM;
     const int m0 = tile_m * BM;
@@ -245,7 +260,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
 
     const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
-    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
+    // (each range of a cut reduction writes its own copy of the output, y_bytes long)
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
+        static_cast<char *>(p.y) + (size_t)split * p.ySplitBytes, 0, p.y_bytes, kBufferWord3);
 
     // ---- gather role: this lane's column j -> (n,p,q) (loop invariant) ------------
     // hw0 packs (p*u - pad_h, q*v - pad_w) as two 16-bit fields (two's complement);
@@ -335,6 +352,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     int sc_tau = 0;
     uint32_t vtap = kOutOfRange;
     uint32_t sc_cso[GM == GATHER_TAPS9 ? KPT / 9 : 1];
+    uint32_t a_jo = 0;  // GATHER_WGRAD: offset of this thread's reduction index in the first operand
 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
     // reduction range.  The per-thread part of the offset is fixed, the step's part is a
@@ -346,7 +364,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     for (int ps = 0; ps < A_PASSES; ++ps) {
         const int row = m0 + a_row[ps];
         const bool ok = row < p.K && a_row[ps] < BM;
-        if constexpr (GM == GATHER_TAPMAJOR)
+        if constexpr (GM == GATHER_WGRAD)
+            // (rows beyond K are never stored: they may read row 0; the reduction index's part of
+            // the offset, which also carries the out-of-range marker, is added per step)
+            a_voff[ps] = (uint32_t)(row < p.K ? row : 0) * (uint32_t)p.wsRow * ES;
+        else if constexpr (GM == GATHER_TAPMAJOR)
             a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.wsRow + (uint32_t)a_kk[ps] * (uint32_t)p.wsRed) * ES : kOutOfRange;
         else
             a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)a_kk[ps]) * ES : kOutOfRange;
@@ -355,7 +377,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
     // each fits between two MFMAs.
     auto decode1 = [&](int tau) {
-        if constexpr (GM == GATHER_GENERIC || GM == GATHER_NOPAD) {
+        if constexpr (GEN || GM == GATHER_NOPAD) {
             // i -> (c, r*S+s) for i = first index of the run + lane
             sc_tau = __builtin_amdgcn_readfirstlane(tau);
             dec_il = (uint32_t)(tau * BK + kpart * KPT) + (uint32_t)lane;
@@ -389,14 +411,27 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         }
     };
     auto decode2 = [&]() {
-        if constexpr (GM == GATHER_GENERIC || GM == GATHER_NOPAD) {
+        if constexpr (GEN || GM == GATHER_NOPAD) {
             const uint32_t r = magic_div(dec_rs, p.mS);
             const uint32_t sx = dec_rs - r * (uint32_t)p.S;
-            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
-            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            // window coordinates of the element: the tap, inverted for eq. 2; for
+            // GATHER_WGRAD the reduction index is an output pixel and they are (p*u, q*v)
+            const uint32_t tr = (p.flip ? (uint32_t)p.R - 1u - r : r) * (GM == GATHER_WGRAD ? (uint32_t)p.redMulH : 1u);
+            const uint32_t ts = (p.flip ? (uint32_t)p.S - 1u - sx : sx) * (GM == GATHER_WGRAD ? (uint32_t)p.redMulW : 1u);
             const uint32_t so = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
             const bool live = dec_il < (uint32_t)p.CRS;
-            if constexpr (GM == GATHER_GENERIC) {
+            if constexpr (GM == GATHER_WGRAD) {
+                // first operand: this thread's reduction index (the same in all its passes)
+                const uint32_t ja = (uint32_t)(sc_tau * BK + a_kk[0]);
+                const uint32_t n = magic_div(ja, p.mRS);
+                const uint32_t rem = ja - n * (uint32_t)p.RS;
+                const uint32_t pp = magic_div(rem, p.mS);
+                const uint32_t qq = rem - pp * (uint32_t)p.S;
+                a_jo = ja < (uint32_t)p.CRS
+                           ? (n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES
+                           : kOutOfRange;
+            }
+            if constexpr (GEN) {
                 dec_so = so;
                 dec_tap = live ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
             } else {
@@ -405,7 +440,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             // When C*R*S is not a multiple of BK the last step is ragged: on entering it
             // (once per tile) the filter offsets of the indices beyond the range are
             // replaced by the out-of-range marker.
-            if (sc_tau == p.tail_step) {
+            if (GM != GATHER_WGRAD && sc_tau == p.tail_step) {
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps)
                     a_voff[ps] = (uint32_t)(sc_tau * BK + a_kk[ps]) < (uint32_t)p.CRS ? a_voff[ps] : kOutOfRange;
@@ -424,7 +459,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     };
     auto load_a = [&](int set, int tau, int ps) {
         uint32_t voffa = a_voff[ps], soff;
-        if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
+        if constexpr (GM == GATHER_WGRAD) {
+            voffa += a_jo;
+            soff = 0;
+        } else if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
             soff = sc_asoff;  // (TAPS9: C % 4 == 0, so a row never ends inside a step)
         } else {
             // (a reduction range that ends inside the last step: masked in place by decode2)
@@ -443,7 +481,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) {
         uint32_t vo, so;
-        if constexpr (GM == GATHER_GENERIC) {
+        if constexpr (GEN) {
             // lane e's decode as scalars, then the window test
             const uint32_t d = __builtin_amdgcn_readlane(dec_so, e);
             const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
@@ -639,11 +677,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         });
     };
 
-    const int ksteps = p.ksteps;
-    // Prologue: request tiles 0 and 1 back to back, then write tile 0 to LDS stage 0 as
-    // it arrives (tile 1 stays in flight, it is written during step 0).
-    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, 0); });
-    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, 1); });
+    // The steps of this workgroup: all of them, or (GATHER_WGRAD) one range of an even
+    // number of steps; a range that reaches past the last step reads zeros there, and what
+    // the pipeline requests past the end of a range is never used.
+    const int t_begin = GM == GATHER_WGRAD ? split * p.stepsPerSplit : 0;
+    const int t_end = GM == GATHER_WGRAD ? t_begin + p.stepsPerSplit : p.ksteps;
+    // Prologue: request the first two tiles back to back, then write the first to LDS stage
+    // 0 as it arrives (the second stays in flight, it is written during the first step).
+    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, t_begin); });
+    static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 1, t_begin + 1); });
     static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, 0, 0); });
     lds_barrier();
     read_frags(0, 0, 0);
@@ -653,7 +695,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     __builtin_amdgcn_sched_barrier(0);
     // (always whole pairs of steps - an odd count runs one extra step on zero tiles - so
     // that the loop body stays a single basic block)
-    for (int t = 0; t < ksteps; t += 2) {
+    for (int t = t_begin; t < t_end; t += 2) {
         step(std::integral_constant<int, 0>{}, t);
         step(std::integral_constant<int, 1>{}, t + 1);
     }

@@ -13,7 +13,8 @@ struct KernelInfo {
     bool swap;      // lanes run along output channels in the epilogue
     bool veca;      // filter rows fetched with 16-byte loads (needs CRS % VEC == 0, aligned w)
     int gmode;      // gather mode: 0 generic, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
-                    // 4 channel vectors (bf16, nine taps, unit channel stride), 5 the same from a staged image patch
+                    // 4 channel vectors (bf16, nine taps, unit channel stride), 5 the same from a staged image patch,
+                    // 6 backward-filter (generic gather, roles of columns and reduction exchanged)
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
@@ -27,7 +28,12 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels;
+    kGroupBF16Channels, kGroupWgrad;
+
+// Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
+// returns the runtime's error code.
+int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
+                     void *stream);
 
 int kernel_count();
 const KernelInfo *kernel_info(int id);  // nullptr when out of range

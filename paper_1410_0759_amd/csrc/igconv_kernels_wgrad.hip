@@ -1,0 +1,36 @@
+// Backward-filter kernels: the generic gather with columns (c,r,s) and the reduction over
+// (n,p,q), plus the kernel that adds up the ranges of a cut reduction.
+#include "igconv_instantiate.hpp"
+
+//    name, bf16, BM, BN, BK, WM, WN, swap, veca, gather mode
+#define IGC_KERNEL_LIST(X) \
+    X("f32 64x128x32 wgrad", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
+    X("f32 128x128x32 wgrad", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
+    X("bf16 64x128x32 wgrad", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
+    X("bf16 128x128x32 wgrad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD)
+
+IGC_DEFINE_GROUP(kGroupWgrad)
+
+namespace igc {
+
+// out[e] = alpha * (part_0[e] + part_1[e] + ...) + beta * out[e], parts `stride` floats apart.
+// The parts are added in order, so the result does not depend on how the work was spread.
+__global__ __launch_bounds__(256) void igconv_sum_parts_kernel(const float *parts, float *out, uint32_t n, int count,
+                                                               uint32_t stride, float alpha, float beta) {
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+    if (e >= n) return;
+    float acc = 0.f;
+    for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + e];
+    float r = alpha * acc;
+    if (beta != 0.f) r += beta * out[e];
+    out[e] = r;
+}
+
+int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
+                     void *stream) {
+    void *argv[] = {&parts, &out, &n, &count, &stride, &alpha, &beta};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_parts_kernel), dim3((n + 255u) / 256u),
+                                            dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace igc

@@ -36,7 +36,14 @@ struct ConvKernelParams {
     // m*wsRow + c*wsRed + wTap0 + r*wsTapR + s*wsTapS (tap-major kernels only; the others
     // read the packed K,C,R,S order directly).  Forward: (C*R*S, R*S, 0, S, 1).  Backward-data
     // exchanges the roles of k and c and walks a subset of the taps backwards.
+    // Backward-filter reuses them for its first operand dy[n,k,p,q]: row (k) stride wsRow, and
+    // n, p, q strides in wsRed, wsTapR, wsTapS.
     int32_t wsRow, wsRed, wTap0, wsTapR, wsTapS;
+    // Backward-filter: window coordinates of reduction index (n,p,q) are (p*redMulH, q*redMulW);
+    // the reduction is cut into `splits` ranges of stepsPerSplit (even) steps, range s writing
+    // its result at y + s*ySplitBytes.
+    int32_t redMulH, redMulW, splits, stepsPerSplit;
+    uint32_t ySplitBytes;
     // zero-extended image: Wp = W + 2 pad_w pixels per row, HpWp = (H + 2 pad_h) * Wp per image
     int32_t Wp, HpWp;
     Magic mWp, mHpWp;

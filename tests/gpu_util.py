@@ -187,3 +187,38 @@ def run_backward_data(dy, w, hw, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CO
                                       dxdesc, out.ptr)
     ig.check(st, "igcConvolutionBackwardData")
     return out.result()
+
+
+def run_backward_filter(x, dy, rs, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0,
+                        dw_old=None, dtype="f32", workspace="full"):
+    """One igcConvolutionBackwardFilter call; returns (dw as float64 (K,C,R,S), workspace
+    bytes the library asked for).  ``workspace``: "full" (what the library asks for), "none",
+    or a number of bytes."""
+    handle = ig.Handle()
+    handle.set_stream(torch.cuda.current_stream().cuda_stream)
+    N, C, H, W = x.shape
+    _, K, P, Q = dy.shape
+    R, S = rs
+    dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+    x_dev, xs = to_device_strided(x, dtype)
+    dy_dev, dys = to_device_strided(dy, dtype)
+    xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
+    dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
+    dwdesc = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
+    conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+    shape = (K, C, R, S)
+    out = GuardedOutput(shape, (C * R * S, R * S, S, 1))
+    asked = ig.get_backward_filter_workspace_size(handle, xdesc, dydesc, conv, dwdesc)
+    nbytes = asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
+    ws = GuardedOutput((1, 1, 1, max(nbytes // 4, 1)), (0, 0, 0, 1))
+    ws.prefill(value=float("nan"))
+    if dw_old is not None:
+        out.prefill(old=dw_old)
+    else:
+        out.prefill(value=float("nan"))
+    st = ig.convolution_backward_filter(handle, alpha, xdesc, x_dev.data_ptr(), dydesc, dy_dev.data_ptr(), conv, beta,
+                                        dwdesc, out.ptr, ws.ptr if nbytes else 0, nbytes)
+    ig.check(st, "igcConvolutionBackwardFilter")
+    res = out.result()
+    ws.result()   # guard bands of the workspace
+    return res, asked

@@ -83,3 +83,66 @@ def test_backward_data_is_the_transpose_of_forward_on_the_gpu():
     dx = gu.run_backward_data(dy, w, (H, W), pad, stride, 1)
     lhs, rhs = float(np.sum(y * dy)), float(np.sum(dx * x))
     assert abs(lhs - rhs) <= 1e-4 * max(1.0, abs(lhs))
+
+
+# ------------------------------------------------------------------ backward filter
+def _check_bf(prob, dtype, mode, alpha=1.0, beta=0.0, x_layout="NCHW", dy_layout="NCHW", workspace="full", seed=0):
+    gu = _gpu()
+    N, C, H, W, K, R, S, pad, stride = prob
+    P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
+    x = wl.with_layout(_rnd(seed + 1, (N, C, H, W), dtype), x_layout)
+    dy = wl.with_layout(_rnd(seed + 2, (N, K, P, Q), dtype), dy_layout)
+    dw_old = _rnd(seed + 3, (K, C, R, S), "f32") if beta != 0.0 else None
+    print("backward filter", prob, dtype, mode, alpha, beta, x_layout, dy_layout, workspace, flush=True)
+    got, asked = gu.run_backward_filter(x, dy, (R, S), pad, stride, mode, alpha, beta, dw_old, dtype, workspace)
+    want = oc.conv_backward_filter(x, dy, (R, S), pad=pad, stride=stride, mode=mode, alpha=alpha, beta=beta, dw_old=dw_old)
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got)), "non-finite output (NaN prefill or workspace leaked)"
+    err = gu.rel_err(got, want)
+    assert err <= gu.TOL[dtype], "rel err %.3g > %.3g" % (err, gu.TOL[dtype])
+    return got, asked
+
+
+BF_PROBLEMS = BWD_PROBLEMS + [
+    (16, 24, 28, 28, 40, 3, 3, (1, 1), (1, 1)),       # long reduction: cut into many ranges
+    (8, 3, 57, 57, 96, 11, 11, (0, 0), (4, 4)),       # many columns, few channels
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("prob", BF_PROBLEMS, ids=[str(i) for i in range(len(BF_PROBLEMS))])
+def test_backward_filter_sweep(prob, dtype, mode):
+    _check_bf(prob, dtype, mode, seed=10 * BF_PROBLEMS.index(prob))
+
+
+@pytest.mark.parametrize("x_layout,dy_layout", [("NHWC", "NHWC"), ("NHWC", "NCHW"), ("NCHW", "NHWC")])
+def test_backward_filter_layouts(x_layout, dy_layout):
+    _check_bf(BF_PROBLEMS[1], "f32", 1, x_layout=x_layout, dy_layout=dy_layout)
+    _check_bf(BF_PROBLEMS[2], "bf16", 0, x_layout=x_layout, dy_layout=dy_layout)
+
+
+def test_backward_filter_workspace_sizes_and_accumulate():
+    """Any workspace size works (none: one range straight into dw; partial: fewer ranges), the
+    results agree to rounding, and alpha/beta apply once whatever the number of ranges."""
+    prob = BF_PROBLEMS[-2]
+    full, asked = _check_bf(prob, "f32", 1, alpha=0.5, beta=-1.5)
+    K, C, R, S = prob[4], prob[1], prob[5], prob[6]
+    part = K * C * R * S * 4
+    assert asked >= 2 * part and asked % part == 0, "this problem should be cut into several ranges"
+    for ws in ("none", part, 3 * part + 8, asked + 4096):
+        got, _ = _check_bf(prob, "f32", 1, alpha=0.5, beta=-1.5, workspace=ws)
+        assert np.max(np.abs(got - full)) <= 1e-4 * np.max(np.abs(full))
+    again, _ = _check_bf(prob, "f32", 1, alpha=0.5, beta=-1.5)
+    assert np.array_equal(again, full), "same call, same bits"
+
+
+def test_backward_filter_is_the_transpose_of_forward_on_the_gpu():
+    gu = _gpu()
+    N, C, H, W, K, R, S, pad, stride = BWD_PROBLEMS[2]
+    x, w = _rnd(1, (N, C, H, W), "f32"), _rnd(2, (K, C, R, S), "f32")
+    y, _ = gu.run(x, w, pad, stride, 0)
+    dy = _rnd(3, y.shape, "f32")
+    dw, _ = gu.run_backward_filter(x, dy, (R, S), pad, stride, 0)
+    lhs, rhs = float(np.sum(y * dy)), float(np.sum(dw * w))
+    assert abs(lhs - rhs) <= 1e-4 * max(1.0, abs(lhs))

@@ -73,6 +73,8 @@ def test_every_kernel_variant():
     numbers of reduction steps)."""
     import paper_1410_0759_amd as ig
     for kid, name in _kernel_cases():
+        if "wgrad" in name:   # backward-filter kernels: covered by the backward tests
+            continue
         dtype = "bf16" if name.startswith("bf16") else "f32"
         vec = "vecw" in name
         swap = "swap" in name
