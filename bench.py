@@ -79,6 +79,61 @@ def run_config(index, steps, warmup, oracle_seconds, kernel=None, workload=None)
     }
 
 
+def run_backward(index, steps, warmup, oracle_seconds):
+    """Backward data and backward filter at one workload's size: seeded dy of the forward
+    output's shape, timing of each pass, parity against the oracle's backward forms on the
+    first n images (backward data: those images of dx; backward filter: the same pass run
+    on those images alone, since every image contributes to every filter element)."""
+    import numpy as np
+    import workloads as wl
+    from oracle import conv_oracle as oc
+    from tests import gpu_util as gu
+
+    w_ = wl.by_index(index)
+    x, w, _ = wl.make_inputs(w_)
+    pad, stride = (w_.pad_h, w_.pad_w), (w_.u, w_.v)
+    dy = np.random.default_rng(14100759 * 10 + w_.index + 300).uniform(-1, 1, size=(w_.N, w_.K, w_.P, w_.Q)).astype(np.float32)
+    if w_.dtype == "bf16":
+        dy = wl.round_to_bf16(dy)
+    dy = wl.with_layout(dy, w_.y_layout)
+    cores = len(os.sched_getaffinity(0))
+    macs_per_image = w_.flops / 2 / w_.N
+    n = int(max(1, min(w_.N, oracle_seconds * 0.2e9 * cores / macs_per_image)))
+    out = {"workload": w_.name, "dtype": w_.dtype, "gflop": w_.flops / 1e9, "parity_images": n,
+           "tolerance": gu.TOL[w_.dtype]}
+
+    class _Timed:   # adapts the backward objects to time_gpu
+        def __init__(self, g):
+            self.g = g
+
+        def launch(self, alpha, beta):
+            self.g.launch(alpha, beta)
+
+    g = gu.GpuBackwardData(dy, w, (w_.H, w_.W), pad, stride, w_.mode, w_.dtype, w_.x_layout)
+    g.out.prefill(value=float("nan"))
+    g.launch(1.0, 0.0)
+    got = g.out.result()
+    t0 = time.perf_counter()
+    want = oc.conv_backward_data(dy[:n], w, (w_.H, w_.W), pad=pad, stride=stride, mode=w_.mode)
+    cpu_s = time.perf_counter() - t0
+    ms = time_gpu(_Timed(g), 1.0, 0.0, steps, warmup)
+    out["backward_data"] = {"ms": ms, "tflops": w_.flops / ms / 1e9, "frac_of_peak": w_.flops / ms / 1e9 / PEAK_TFLOPS[w_.dtype],
+                            "rel_err": gu.rel_err(got[:n], want), "oracle_seconds": cpu_s}
+    del g
+
+    g = gu.GpuBackwardFilter(x, dy, (w_.R, w_.S), pad, stride, w_.mode, w_.dtype)
+    g.out.prefill(value=float("nan"))
+    ms = time_gpu(_Timed(g), 1.0, 0.0, steps, warmup)
+    assert np.all(np.isfinite(g.out.result()))
+    got, _ = gu.run_backward_filter(x[:n], dy[:n], (w_.R, w_.S), pad, stride, w_.mode, dtype=w_.dtype)
+    t0 = time.perf_counter()
+    want = oc.conv_backward_filter(x[:n], dy[:n], (w_.R, w_.S), pad=pad, stride=stride, mode=w_.mode)
+    cpu_s = time.perf_counter() - t0
+    out["backward_filter"] = {"ms": ms, "tflops": w_.flops / ms / 1e9, "frac_of_peak": w_.flops / ms / 1e9 / PEAK_TFLOPS[w_.dtype],
+                              "workspace_bytes": g.asked, "rel_err": gu.rel_err(got, want), "oracle_seconds": cpu_s}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +144,8 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the Table-2 layers at mini-batches 16..256 (not part of the default run)")
     ap.add_argument("--no-table2", action="store_true", help="skip the paper's Table-2 layer collection")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward-data / backward-filter section")
+    ap.add_argument("--backward-only", type=int, default=0, help="time only the backward passes of this workload (1-5)")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -114,6 +171,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.backward_only:
+        print(json.dumps(run_backward(args.backward_only, args.steps, args.warmup, 1.0)))
+        return
+
     head = run_config(args.config, args.steps, args.warmup, args.oracle_seconds, args.kernel)
     per_config = []
     if not args.only:
@@ -132,6 +193,12 @@ def main():
             r = run_config(None, max(20, args.steps // 10), max(10, args.warmup // 5), 1.0, workload=w_)
             r["paper_tflops"] = {hw: v[i] for hw, v in wl.TABLE3_PAPER_TFLOPS.items()}
             table2.append(r)
+
+    # The two backward passes at the sizes of workloads 2-5 (same FLOP count as forward).
+    backward = []
+    if not args.only and not args.no_backward:
+        for i in (2, 3, 4, 5):
+            backward.append(run_backward(i, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0))
 
     # Mini-batch sweep over the Table-2 layers (the paper reports 86 % of its maximum
     # throughput at a mini-batch of 16): average TFLOP/s over the five layers per batch size.
@@ -173,6 +240,7 @@ def main():
         "per_config": per_config,
         "table2_layers": table2,
         "table2_batch_sweep": batch_sweep,
+        "backward": backward,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
                          "on GTX 980, fp32, its own Table-2 layers",
     }

@@ -162,63 +162,83 @@ def layout_strides(shape, layout):
     raise ValueError(layout)
 
 
+class GpuBackwardData:
+    """One backward-data problem set up on the GPU through the C ABI."""
+
+    def __init__(self, dy, w, hw, pad, stride, mode, dtype="f32", dx_layout="NCHW"):
+        self.handle = ig.Handle()
+        N, K, P, Q = dy.shape
+        _, C, R, S = w.shape
+        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        self.dy_dev, dys = to_device_strided(dy, dtype)
+        self.w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
+        self.dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
+        self.wdesc = ig.FilterDescriptor().set(dt, K, C, R, S)
+        self.conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+        shape = (N, C, hw[0], hw[1])
+        self.out = GuardedOutput(shape, layout_strides(shape, dx_layout))
+        self.dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, self.out.strides)
+        assert ig.get_backward_data_workspace_size(self.handle, self.wdesc, self.dydesc, self.conv, self.dxdesc) == 0
+
+    def launch(self, alpha=1.0, beta=0.0):
+        self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
+        st = ig.convolution_backward_data(self.handle, alpha, self.wdesc, self.w_dev.data_ptr(), self.dydesc,
+                                          self.dy_dev.data_ptr(), self.conv, beta, self.dxdesc, self.out.ptr)
+        ig.check(st, "igcConvolutionBackwardData")
+
+
 def run_backward_data(dy, w, hw, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0,
                       dx_old=None, dtype="f32", dx_layout="NCHW"):
     """One igcConvolutionBackwardData call; returns dx as float64, logical (N,C,H,W)."""
-    handle = ig.Handle()
-    handle.set_stream(torch.cuda.current_stream().cuda_stream)
-    N, K, P, Q = dy.shape
-    _, C, R, S = w.shape
-    dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
-    dy_dev, dys = to_device_strided(dy, dtype)
-    w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
-    dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
-    wdesc = ig.FilterDescriptor().set(dt, K, C, R, S)
-    conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
-    shape = (N, C, hw[0], hw[1])
-    out = GuardedOutput(shape, layout_strides(shape, dx_layout))
-    dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, out.strides)
-    assert ig.get_backward_data_workspace_size(handle, wdesc, dydesc, conv, dxdesc) == 0
+    g = GpuBackwardData(dy, w, hw, pad, stride, mode, dtype, dx_layout)
     if dx_old is not None:
-        out.prefill(old=dx_old)
+        g.out.prefill(old=dx_old)
     else:
-        out.prefill(value=float("nan"))
-    st = ig.convolution_backward_data(handle, alpha, wdesc, w_dev.data_ptr(), dydesc, dy_dev.data_ptr(), conv, beta,
-                                      dxdesc, out.ptr)
-    ig.check(st, "igcConvolutionBackwardData")
-    return out.result()
+        g.out.prefill(value=float("nan"))
+    g.launch(alpha, beta)
+    return g.out.result()
+
+
+class GpuBackwardFilter:
+    """One backward-filter problem set up on the GPU through the C ABI.  ``workspace``: "full"
+    (what the library asks for), "none", or a number of bytes."""
+
+    def __init__(self, x, dy, rs, pad, stride, mode, dtype="f32", workspace="full"):
+        self.handle = ig.Handle()
+        N, C, H, W = x.shape
+        _, K, P, Q = dy.shape
+        R, S = rs
+        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        self.x_dev, xs = to_device_strided(x, dtype)
+        self.dy_dev, dys = to_device_strided(dy, dtype)
+        self.xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
+        self.dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
+        self.dwdesc = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
+        self.conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
+        self.out = GuardedOutput((K, C, R, S), (C * R * S, R * S, S, 1))
+        self.asked = ig.get_backward_filter_workspace_size(self.handle, self.xdesc, self.dydesc, self.conv, self.dwdesc)
+        self.ws_bytes = self.asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
+        self.ws = GuardedOutput((1, 1, 1, max(self.ws_bytes // 4, 1)), (0, 0, 0, 1))
+        self.ws.prefill(value=float("nan"))
+
+    def launch(self, alpha=1.0, beta=0.0):
+        self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
+        st = ig.convolution_backward_filter(self.handle, alpha, self.xdesc, self.x_dev.data_ptr(), self.dydesc,
+                                            self.dy_dev.data_ptr(), self.conv, beta, self.dwdesc, self.out.ptr,
+                                            self.ws.ptr if self.ws_bytes else 0, self.ws_bytes)
+        ig.check(st, "igcConvolutionBackwardFilter")
 
 
 def run_backward_filter(x, dy, rs, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0,
                         dw_old=None, dtype="f32", workspace="full"):
     """One igcConvolutionBackwardFilter call; returns (dw as float64 (K,C,R,S), workspace
-    bytes the library asked for).  ``workspace``: "full" (what the library asks for), "none",
-    or a number of bytes."""
-    handle = ig.Handle()
-    handle.set_stream(torch.cuda.current_stream().cuda_stream)
-    N, C, H, W = x.shape
-    _, K, P, Q = dy.shape
-    R, S = rs
-    dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
-    x_dev, xs = to_device_strided(x, dtype)
-    dy_dev, dys = to_device_strided(dy, dtype)
-    xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
-    dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
-    dwdesc = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
-    conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
-    shape = (K, C, R, S)
-    out = GuardedOutput(shape, (C * R * S, R * S, S, 1))
-    asked = ig.get_backward_filter_workspace_size(handle, xdesc, dydesc, conv, dwdesc)
-    nbytes = asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
-    ws = GuardedOutput((1, 1, 1, max(nbytes // 4, 1)), (0, 0, 0, 1))
-    ws.prefill(value=float("nan"))
+    bytes the library asked for)."""
+    g = GpuBackwardFilter(x, dy, rs, pad, stride, mode, dtype, workspace)
     if dw_old is not None:
-        out.prefill(old=dw_old)
+        g.out.prefill(old=dw_old)
     else:
-        out.prefill(value=float("nan"))
-    st = ig.convolution_backward_filter(handle, alpha, xdesc, x_dev.data_ptr(), dydesc, dy_dev.data_ptr(), conv, beta,
-                                        dwdesc, out.ptr, ws.ptr if nbytes else 0, nbytes)
-    ig.check(st, "igcConvolutionBackwardFilter")
-    res = out.result()
-    ws.result()   # guard bands of the workspace
-    return res, asked
+        g.out.prefill(value=float("nan"))
+    g.launch(alpha, beta)
+    res = g.out.result()
+    g.ws.result()   # guard bands of the workspace
+    return res, g.asked

@@ -146,3 +146,37 @@ def test_backward_filter_is_the_transpose_of_forward_on_the_gpu():
     dw, _ = gu.run_backward_filter(x, dy, (R, S), pad, stride, 0)
     lhs, rhs = float(np.sum(y * dy)), float(np.sum(dw * w))
     assert abs(lhs - rhs) <= 1e-4 * max(1.0, abs(lhs))
+
+
+# ------------------------------------------------------------------ the workloads' own sizes
+@pytest.mark.parametrize("index", [3, 4, 5])
+def test_backward_at_workload_size(index):
+    """Backward data and backward filter at the size of workloads 3-5, in the launch
+    configuration the bench times; compared with the oracle on the first images (backward
+    data: those images of dx, all elements; backward filter: the pass run on those images)
+    and, at full size, through the transpose identity <dy, forward(x,w)> = <dx, x> = <dw, w>
+    with the forward result from the library."""
+    gu = _gpu()
+    w_ = wl.by_index(index)
+    x, w, _ = wl.make_inputs(w_)
+    pad, stride = (w_.pad_h, w_.pad_w), (w_.u, w_.v)
+    dy = np.random.default_rng(77 + index).uniform(-1, 1, size=(w_.N, w_.K, w_.P, w_.Q)).astype(np.float32)
+    if w_.dtype == "bf16":
+        dy = wl.round_to_bf16(dy)
+    dy = wl.with_layout(dy, w_.y_layout)
+    n = 4
+    print("backward at workload size", w_.name, flush=True)
+    dx = gu.run_backward_data(dy, w, (w_.H, w_.W), pad, stride, w_.mode, dtype=w_.dtype, dx_layout=w_.x_layout)
+    want = oc.conv_backward_data(dy[:n], w, (w_.H, w_.W), pad=pad, stride=stride, mode=w_.mode)
+    assert gu.rel_err(dx[:n], want) <= gu.TOL[w_.dtype]
+    dw_n, _ = gu.run_backward_filter(x[:n], dy[:n], (w_.R, w_.S), pad, stride, w_.mode, dtype=w_.dtype)
+    want = oc.conv_backward_filter(x[:n], dy[:n], (w_.R, w_.S), pad=pad, stride=stride, mode=w_.mode)
+    assert gu.rel_err(dw_n, want) <= gu.TOL[w_.dtype]
+    dw, asked = gu.run_backward_filter(x, dy, (w_.R, w_.S), pad, stride, w_.mode, dtype=w_.dtype)
+    assert asked > 0
+    y, _ = gu.run(x, w, pad, stride, w_.mode, dtype=w_.dtype, y_layout=w_.y_layout)
+    lhs = float(np.sum(y * dy.astype(np.float64)))
+    scale = float(np.sqrt(np.sum(y * y) * np.sum(dy.astype(np.float64) ** 2)))
+    tol = 1e-5 if w_.dtype == "f32" else 1e-3
+    assert abs(lhs - float(np.sum(dx * x.astype(np.float64)))) <= tol * scale
+    assert abs(lhs - float(np.sum(dw * w.astype(np.float64)))) <= tol * scale

@@ -161,6 +161,54 @@ def test_forward_rejects_bad_arguments_before_any_gpu_call():
     assert _fwd_status(x, w, c, y, handle=h) == ig.IGC_STATUS_NOT_SUPPORTED
 
 
+def test_backward_passes_validate_before_any_gpu_call():
+    """Backward data / backward filter: workspace queries and every rejection path run
+    without a GPU (fake device pointers; a rejected call launches nothing)."""
+    h = ig.Handle()
+    x, w, c, y = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 1))
+    assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 0
+    K, C, R, S = 4, 3, 3, 3
+    ws = ig.get_backward_filter_workspace_size(h, x, y, c, w)
+    assert ws % (K * C * R * S * 4) == 0
+    L = ig.lib()
+    one = ctypes.c_float(1.0)
+    fake = ctypes.c_void_p(256)
+
+    def bd(wd=w, dyd=y, cd=c, dxd=x, wp=fake, dyp=fake, dxp=fake):
+        return L.igcConvolutionBackwardData(h.ptr, ctypes.byref(one), wd.ptr, wp, dyd.ptr, dyp, cd.ptr, None, 0,
+                                            ctypes.byref(one), dxd.ptr, dxp)
+
+    def bf(xd=x, dyd=y, cd=c, dwd=w, xp=fake, dyp=fake, dwp=fake, wsp=None):
+        return L.igcConvolutionBackwardFilter(h.ptr, ctypes.byref(one), xd.ptr, xp, dyd.ptr, dyp, cd.ptr, wsp, 0,
+                                              ctypes.byref(one), dwd.ptr, dwp)
+
+    assert bd(dxp=None) == ig.IGC_STATUS_BAD_PARAM and bf(dwp=None) == ig.IGC_STATUS_BAD_PARAM
+    assert bd(dyp=ctypes.c_void_p(258)) == ig.IGC_STATUS_BAD_PARAM          # misaligned float pointer
+    assert bf(wsp=ctypes.c_void_p(258)) == ig.IGC_STATUS_BAD_PARAM
+    # dy whose size is not eq. 1 of dx's
+    _, _, _, ybad = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 1), ydims=(2, 4, 5, 9))
+    assert bd(dyd=ybad) == ig.IGC_STATUS_BAD_PARAM and bf(dyd=ybad) == ig.IGC_STATUS_BAD_PARAM
+    # channel counts that do not match the filter
+    xbad = ig.TensorDescriptor().set(0, 2, 5, 9, 8, (5 * 72, 72, 8, 1))
+    assert bd(dxd=xbad) == ig.IGC_STATUS_BAD_PARAM and bf(xd=xbad) == ig.IGC_STATUS_BAD_PARAM
+    # dx with aliasing strides
+    xalias = ig.TensorDescriptor().set(0, 2, 3, 9, 8, (0, 72, 8, 1))
+    assert bd(dxd=xalias) == ig.IGC_STATUS_BAD_PARAM
+    # data types: dx / dw are float; the inputs agree with each other
+    xb16 = ig.TensorDescriptor().set(1, 2, 3, 9, 8, (216, 72, 8, 1))
+    assert bd(dxd=xb16) == ig.IGC_STATUS_NOT_SUPPORTED
+    assert bf(xd=xb16) == ig.IGC_STATUS_NOT_SUPPORTED                       # x bf16 with dy float
+    wb16 = ig.FilterDescriptor().set(1, 4, 3, 3, 3)
+    assert bf(dwd=wb16) == ig.IGC_STATUS_NOT_SUPPORTED and bd(wd=wb16) == ig.IGC_STATUS_NOT_SUPPORTED
+    # descriptors never set
+    assert bd(dxd=ig.TensorDescriptor()) == ig.IGC_STATUS_NOT_INITIALIZED
+    assert bf(dwd=ig.FilterDescriptor()) == ig.IGC_STATUS_NOT_INITIALIZED
+    # backward filter: the window coordinates must fit 14 bits
+    xl, wl_, cl, yl = _descs(N=1, C=1, H=16000, W=8, K=1, R=3, S=3, pad=(300, 1))
+    assert L.igcConvolutionBackwardFilter(h.ptr, ctypes.byref(one), xl.ptr, fake, yl.ptr, fake, cl.ptr, None, 0,
+                                          ctypes.byref(one), wl_.ptr, fake) == ig.IGC_STATUS_NOT_SUPPORTED
+
+
 def test_setters_reject_bad_values():
     L = ig.lib()
     t = ig.TensorDescriptor()
