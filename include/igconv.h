@@ -241,7 +241,8 @@ typedef struct {
     int tileM;       /* rows of O_m (output feature maps) per workgroup */
     int tileN;       /* columns of O_m (output pixels n,p,q) per workgroup */
     int tileK;       /* reduction elements (c,r,s) per step */
-    int gridX;       /* workgroups launched: the tile count rounded up to a multiple of 8 (XCDs) */
+    int gridX;       /* workgroups launched, a multiple of 8 (XCDs): at most as many as the chip holds at
+                        once, each then computing several tiles one after the other */
     int kSteps;      /* reduction steps: ceil(CRS / tileK); R*S*ceil(C / tileK) in tap-major order */
     int threads;     /* threads per workgroup */
     int ldsBytes;    /* LDS per workgroup */

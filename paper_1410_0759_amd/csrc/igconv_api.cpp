@@ -276,6 +276,16 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     return IGC_STATUS_SUCCESS;
 }
 
+// Workgroups launched per XCD.  The kernels of igconv_kernel.hpp are persistent: as many
+// workgroups as the chip holds at once (32 compute units per XCD, one or two workgroups
+// each depending on their LDS), each walking through several tiles; the channel-vector
+// bf16 kernels take one tile per workgroup.
+static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
+    if (ki.gmode == 4 || ki.gmode == 5) return tiles_per_xcd;
+    const int occ = std::max(1, std::min(2, (160 * 1024) / ki.ldsBytes));
+    return std::min(tiles_per_xcd, (kComputeUnits / 8) * occ);
+}
+
 static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan) {
     const KernelInfo &ki = *kernel_info(id);
     ConvKernelParams &k = pr->kp;
@@ -292,12 +302,13 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     if ((ki.gmode == 0 || ki.gmode == 2) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
+    k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
     if (plan) {
         plan->kernelId = id;
         plan->tileM = ki.BM;
         plan->tileN = ki.BN;
         plan->tileK = ki.BK;
-        plan->gridX = 8 * k.tilesPerXcd;
+        plan->gridX = 8 * k.wgsPerXcd;
         plan->kSteps = k.ksteps;
         plan->threads = ki.threads;
         plan->ldsBytes = ki.ldsBytes;
@@ -858,6 +869,7 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     k.ySplitBytes = (uint32_t)part_bytes;
     k.tilesPerXcd = (int)((b.tiles * splits + 7) / 8);
     if ((long long)k.tilesPerXcd * 8 >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
+    k.wgsPerXcd = workgroups_per_xcd(*kernel_info(b.kernel_id), k.tilesPerXcd);
     if (splits > 1) {
         k.y = workSpace;
         k.alpha = 1.f;
@@ -867,7 +879,7 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
         k.alpha = a;
         k.beta = bt;
     }
-    if (kernel_info(b.kernel_id)->launch(k, 8 * k.tilesPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    if (kernel_info(b.kernel_id)->launch(k, 8 * k.wgsPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
     if (splits > 1 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
                                        b.out_elems, a, bt, handle->stream) != 0)
         return IGC_STATUS_EXECUTION_FAILED;

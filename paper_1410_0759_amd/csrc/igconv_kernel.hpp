@@ -241,29 +241,27 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The tiles
     // are numbered with the M tiles of one column tile adjacent (they gather the same
     // columns of D_m) and cut into 8 contiguous ranges, one per XCD, so that the
-    // workgroups which share input rows and columns also share an L2.  The grid is
-    // rounded up to 8 ranges of equal length; a workgroup past the last tile leaves.
-    int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
-    // GATHER_WGRAD: the tile numbers repeat once per range of the reduction
-    int split = 0;
-    if constexpr (GM == GATHER_WGRAD) {
-        if (tile >= p.tilesM * p.tilesN * p.splits) return;
-        split = tile / (p.tilesM * p.tilesN);
-        tile -= split * (p.tilesM * p.tilesN);
-    } else {
-        if (tile >= p.tilesM * p.tilesN) return;
-    }
-    const int tile_m = tile % p.tilesM;
-    const int tile_n = tile / p.tilesM;
-    const int m0 = tile_m * BM;
-    const int n0 = tile_n * BN;
+    // workgroups which share input rows and columns also share an L2.  A workgroup is
+    // persistent: it takes every wgsPerXcd-th tile of its XCD's range, and its pipeline
+    // runs on across tile boundaries (see the main loop).  GATHER_WGRAD: the tile numbers
+    // repeat once per range of the reduction.
+    const int wg_xcd = (int)(blockIdx.x % 8u), wg_local = (int)(blockIdx.x / 8u);
+    const int tiles_mn = p.tilesM * p.tilesN;
+    const int tiles_total = GM == GATHER_WGRAD ? tiles_mn * p.splits : tiles_mn;
+    // number of this workgroup's i-th tile; tiles_total when it has no i-th tile
+    auto tile_number = [&](int i) {
+        const int local = wg_local + i * p.wgsPerXcd;
+        const int t = wg_xcd * p.tilesPerXcd + local;
+        return local < p.tilesPerXcd && t < tiles_total ? t : tiles_total;
+    };
+    if (tile_number(0) >= tiles_total) return;
+    // The tile whose loads are being issued ("tile state", set by setup_tile below).  A tile
+    // number of tiles_total stands for "no tile": its columns (or, for GATHER_WGRAD, its
+    // reduction range) lie beyond the end, so that all it gathers is zeros.
+    int m0 = 0, n0 = 0, split = 0, t_begin = 0;
 
     const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
-    // (each range of a cut reduction writes its own copy of the output, y_bytes long)
-    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
-        static_cast<char *>(p.y) + (size_t)split * p.ySplitBytes, 0, p.y_bytes, kBufferWord3);
-
     // ---- gather role: this lane's column j -> (n,p,q) (loop invariant) ------------
     // hw0 packs (p*u - pad_h, q*v - pad_w) as two 16-bit fields (two's complement);
     // adding a packed tap (tr, ts) gives the input coordinates of that tap, and the
@@ -274,8 +272,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     const int kpart = wave / Cfg::CG;
     const int jl = cg * 64 + lane;
     u16x2 hw0;
-    uint32_t colbase_b;  // byte offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
-    {
+    uint32_t colbase_b = 0;  // byte offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
+    auto setup_column = [&]() {
         const int j = n0 + jl;
         const bool cv = j < p.NPQ;
         const uint32_t jj = cv ? (uint32_t)j : 0u;
@@ -291,7 +289,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         if (!cv) {
             hw0[1] = 0x8000;           // no tap of a column beyond NPQ is ever in range
         }
-    }
+    };
     u16x2 hw_max;
     hw_max[1] = (uint16_t)(p.H - 1);
     hw_max[0] = (uint16_t)(p.W - 1);
@@ -305,18 +303,21 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         return ok ? colbase_b + (tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
     };
     // GATHER_NOPAD: the window origin of a valid column, else the out-of-range marker.
-    const uint32_t vcol = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
+    uint32_t vcol = kOutOfRange;
     // GATHER_TAPS9: the nine tap offsets of this column (tap t = r*3+s... in general
     // r*S+s with R*S = 9), eq. 2's inversion applied.
     uint32_t vtaps[GM == GATHER_TAPS9 ? 9 : 1];
-    if constexpr (GM == GATHER_TAPS9) {
+    auto setup_taps = [&]() {
+        vcol = hw0[1] == 0x8000 ? kOutOfRange : colbase_b;
+        if constexpr (GM == GATHER_TAPS9) {
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const uint32_t r = magic_div((uint32_t)t, p.mS);
-            const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
-            vtaps[t] = tap_offset(p.flip ? (uint32_t)p.R - 1u - r : r, p.flip ? (uint32_t)p.S - 1u - sx : sx);
+            for (int t = 0; t < 9; ++t) {
+                const uint32_t r = magic_div((uint32_t)t, p.mS);
+                const uint32_t sx = (uint32_t)t - r * (uint32_t)p.S;
+                vtaps[t] = tap_offset(p.flip ? (uint32_t)p.R - 1u - r : r, p.flip ? (uint32_t)p.S - 1u - sx : sx);
+            }
         }
-    }
+    };
 
     // ---- filter-tile role ----------------------------------------------------------
     // 16-byte path: the tile is BM rows of BK/VEC vectors, dealt to the threads in order;
@@ -360,8 +361,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // c0 + a_kk, tap of the step, i.e. a strided read (stride R*S elements in the
     // forward pass); row, channel and tap strides come from the launch parameters.
     uint32_t a_voff[A_PASSES];
+    auto setup_rows = [&]() {
 #pragma unroll
-    for (int ps = 0; ps < A_PASSES; ++ps) {
+      for (int ps = 0; ps < A_PASSES; ++ps) {
         const int row = m0 + a_row[ps];
         const bool ok = row < p.K && a_row[ps] < BM;
         if constexpr (GM == GATHER_WGRAD)
@@ -372,7 +374,21 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.wsRow + (uint32_t)a_kk[ps] * (uint32_t)p.wsRed) * ES : kOutOfRange;
         else
             a_voff[ps] = ok ? ((uint32_t)row * (uint32_t)p.CRS + (uint32_t)a_kk[ps]) * ES : kOutOfRange;
-    }
+      }
+    };
+    // Everything the loads of a tile depend on.
+    auto setup_tile = [&](int tile) {
+        if constexpr (GM == GATHER_WGRAD) {
+            split = tile / tiles_mn;
+            tile -= split * tiles_mn;
+            t_begin = split * p.stepsPerSplit;
+        }
+        m0 = (tile % p.tilesM) * BM;
+        n0 = (tile / p.tilesM) * BN;
+        setup_column();
+        setup_taps();
+        setup_rows();
+    };
 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
     // each fits between two MFMAs.
@@ -648,10 +664,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // MFMA.  Tiles beyond the last step read as zeros (out-of-range requests), so no
     // step is special; the loop is unrolled by two because the register set and the LDS
     // stage alternate.
-    auto step = [&](auto parity, int t) {
+    auto step = [&](auto parity, int k2) {   // k2: the step whose tiles are requested during this one
         constexpr int cur = decltype(parity)::value, nxt = cur ^ 1;
         constexpr int fs0 = (G & 1) ? cur : 0;  // fragment set of this step's group 0
-        const int k2 = t + 2;  // number of the tile requested during this step
         static_for<NM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             constexpr int g = m / MPG_FULL < G - 1 ? m / MPG_FULL : G - 1;
@@ -677,11 +692,12 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         });
     };
 
-    // The steps of this workgroup: all of them, or (GATHER_WGRAD) one range of an even
-    // number of steps; a range that reaches past the last step reads zeros there, and what
-    // the pipeline requests past the end of a range is never used.
-    const int t_begin = GM == GATHER_WGRAD ? split * p.stepsPerSplit : 0;
-    const int t_end = GM == GATHER_WGRAD ? t_begin + p.stepsPerSplit : p.ksteps;
+    // A tile takes `nsteps` steps, rounded up to whole pairs (an odd count runs one extra
+    // step on zero tiles), so that the loop body stays a single basic block.  GATHER_WGRAD: a
+    // tile is one range of an even number of steps; a range that reaches past the last step
+    // reads zeros there.
+    const int nsteps = GM == GATHER_WGRAD ? p.stepsPerSplit : ((p.ksteps + 1) & ~1);
+    setup_tile(tile_number(0));
     // Prologue: request the first two tiles back to back, then write the first to LDS stage
     // 0 as it arrives (the second stays in flight, it is written during the first step).
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, t_begin); });
@@ -693,14 +709,31 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // with the loop's back edge, waits for every load at the top of each step.
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __builtin_amdgcn_sched_barrier(0);
-    // (always whole pairs of steps - an odd count runs one extra step on zero tiles - so
-    // that the loop body stays a single basic block)
-    for (int t = t_begin; t < t_end; t += 2) {
-        step(std::integral_constant<int, 0>{}, t);
-        step(std::integral_constant<int, 1>{}, t + 1);
+    for (int it = 1;; ++it) {
+        for (int t = 2; t < nsteps; t += 2) {
+            step(std::integral_constant<int, 0>{}, t_begin + t);
+            step(std::integral_constant<int, 1>{}, t_begin + t + 1);
+        }
+        // The last two steps of this tile request the first two steps of the workgroup's next
+        // tile (of "no tile" after the last one): its operands arrive and its first fragments
+        // are read while this tile is still being multiplied and stored.
+        const int out_m0 = m0, out_n0 = n0, out_split = split;
+        const int next = tile_number(it);
+        setup_tile(next);
+        step(std::integral_constant<int, 0>{}, t_begin);
+        step(std::integral_constant<int, 1>{}, t_begin + 1);
+        // (each range of a cut reduction writes its own copy of the output, y_bytes long)
+        const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
+            static_cast<char *>(p.y) + (size_t)out_split * p.ySplitBytes, 0, p.y_bytes, kBufferWord3);
+        store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
+        if (next >= tiles_total) break;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
     }
-
-    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, m0 + wm * Cfg::TM, n0 + wn * Cfg::TN, half, l32);
 }
 
 }  // namespace igc

@@ -30,6 +30,7 @@ struct ConvKernelParams {
     float alpha, beta;
     int32_t tilesM, tilesN;
     int32_t tilesPerXcd;  // ceil(tilesM * tilesN / 8): tiles are dealt to the 8 XCDs in contiguous ranges
+    int32_t wgsPerXcd;    // workgroups launched per XCD (grid = 8 * wgsPerXcd); each takes every wgsPerXcd-th tile of its range
     int32_t ksteps;  // reduction steps of the chosen kernel (depends on its reduction order)
     int32_t tail_step;  // first step in which the reduction range ends inside the step, else -1
     // Where the filter element (row m, reduction channel c, tap (r,s)) lives, in elements:
