@@ -249,7 +249,8 @@ typedef struct {
     int swapOperands;/* 1 when lanes run along k in the epilogue (y's c-stride is 1) */
     int vecFilterLoads; /* 1 when filter rows are fetched with 16-byte loads */
     int gatherMode;  /* 0 generic window test, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
-                        4 bf16 channel vectors, 5 bf16 channel vectors from a staged image patch */
+                        4 bf16 channel vectors, 5 bf16 channel vectors from a staged image patch,
+                        7 unpadded with tap offsets tabulated in LDS (short reductions) */
 } igcConvolutionForwardPlan;
 
 igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle,

@@ -39,6 +39,7 @@ namespace igc {
 
 // MI355X: 256 compute units; the tile heuristic balances workgroups over them.
 constexpr int kComputeUnits = 256;
+constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-reduction unpadded kernels
 constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels (Bf16cConfig::PATCH_PIX)
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
@@ -176,7 +177,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 // chunks of BK, or tap-major: per tap, the channels in chunks of BK.
 static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
-    if (ki.gmode >= 3) return k.C / (ki.BK / 9);
+    if (ki.gmode == 3 || ki.gmode == 4 || ki.gmode == 5) return k.C / (ki.BK / 9);
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
@@ -199,9 +200,9 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // The channel-vector bf16 kernels are bound by their loads, not by the MFMA pipe: measured,
     // a step costs about 2.75 units per filter row and 1 (1.5 when gathered tap by tap) per
     // column, plus a small MFMA term; the scale makes them comparable with the line below.
-    if (ki.gmode >= 4)
+    if (ki.gmode == 4 || ki.gmode == 5)
         return tile_times * steps * 1000.0 * (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
-    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : 6.0));
+    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (ki.gmode == 7 ? 14.0 : 6.0)));
     return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
 }
 
@@ -234,8 +235,12 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     const int gmode = ki.gmode;
     if (gmode == 6) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
+    if (gmode == 7) {   // unpadded, and every step the kernel can request has an entry in its offset table
+        const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
+        return k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries;
+    }
     if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
-    if (gmode >= 4) {
+    if (gmode == 4 || gmode == 5) {
         if (!(x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
               k.xsW % 8 == 0))
             return false;
@@ -299,7 +304,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     // the last channel chunk; filter order, the last step; none when everything divides
     k.tail_step = -1;
     if (ki.gmode == 1 && k.C % ki.BK != 0) k.tail_step = (int)((long long)(k.C / ki.BK) * k.RS);
-    if ((ki.gmode == 0 || ki.gmode == 2) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
+    if ((ki.gmode == 0 || ki.gmode == 2 || ki.gmode == 7) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);

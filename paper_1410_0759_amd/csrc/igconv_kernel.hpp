@@ -178,12 +178,20 @@ enum GatherMode {
     // per-column tap offsets (window test folded in) are built once per tile and the
     // loop holds no vector instruction at all.  Any pad, stride, mode.
     GATHER_TAPS9 = 3,
+    // GATHER_NOPAD for short reductions: the per-index tap offsets are computed once per
+    // workgroup into an LDS table (kOffsetTableEntries entries: every step the kernel can
+    // request, the two steps the pipeline asks for past the end included), so that a step
+    // fetches its offsets with one LDS read instead of decoding them with vector
+    // instructions, which would stall the fp32 MFMA.
+    GATHER_NOPAD_TABLE = 7,
     // Backward-filter: the generic gather with the roles of the two index sets exchanged.
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
     // the reduction may be cut into several ranges, one workgroup each (see the main loop).
     GATHER_WGRAD = 6
 };
+
+constexpr int kOffsetTableEntries = 2048;
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
 struct KernelConfig {
@@ -201,7 +209,8 @@ struct KernelConfig {
     static constexpr int LDV = (BK / VEC + 1) | 1;
     static constexpr int LD = LDV * VEC;
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
-    static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE;
+    static constexpr int TABLE_BYTES = GMODE_ == GATHER_NOPAD_TABLE ? kOffsetTableEntries * 4 : 0;
+    static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE + TABLE_BYTES;
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
     static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
     static constexpr int CG = BN / 64;               // column groups of 64 lanes
@@ -226,11 +235,13 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
     constexpr int GM = Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
+    constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
     elem_t *const ldsA = lds;                       // [2][BM][LD]
     elem_t *const ldsB = lds + 2 * Cfg::A_ELEMS;    // [2][BN][LD]
+    __shared__ uint32_t so_table[GM == GATHER_NOPAD_TABLE ? kOffsetTableEntries : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -393,7 +404,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
     // each fits between two MFMAs.
     auto decode1 = [&](int tau) {
-        if constexpr (GEN || GM == GATHER_NOPAD) {
+        if constexpr (GM == GATHER_NOPAD_TABLE) {
+            sc_tau = __builtin_amdgcn_readfirstlane(tau);
+            dec_so = so_table[sc_tau * BK + kpart * KPT + (lane < KPT ? lane : KPT - 1)];
+        } else if constexpr (GEN || GM == GATHER_NOPAD) {
             // i -> (c, r*S+s) for i = first index of the run + lane
             sc_tau = __builtin_amdgcn_readfirstlane(tau);
             dec_il = (uint32_t)(tau * BK + kpart * KPT) + (uint32_t)lane;
@@ -427,7 +441,13 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         }
     };
     auto decode2 = [&]() {
-        if constexpr (GEN || GM == GATHER_NOPAD) {
+        if constexpr (GM == GATHER_NOPAD_TABLE) {
+            if (sc_tau == p.tail_step) {   // (see below)
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_voff[ps] = (uint32_t)(sc_tau * BK + a_kk[ps]) < (uint32_t)p.CRS ? a_voff[ps] : kOutOfRange;
+            }
+        } else if constexpr (GEN || GM == GATHER_NOPAD) {
             const uint32_t r = magic_div(dec_rs, p.mS);
             const uint32_t sx = dec_rs - r * (uint32_t)p.S;
             // window coordinates of the element: the tap, inverted for eq. 2; for
@@ -509,7 +529,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         } else if constexpr (GM == GATHER_TAPMAJOR) {
             vo = vtap;
             so = __builtin_amdgcn_readlane(dec_so, e);
-        } else if constexpr (GM == GATHER_NOPAD) {
+        } else if constexpr (NOPADX) {
             vo = vcol;
             so = __builtin_amdgcn_readlane(dec_so, e);
         } else {
@@ -697,6 +717,21 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // tile is one range of an even number of steps; a range that reaches past the last step
     // reads zeros there.
     const int nsteps = GM == GATHER_WGRAD ? p.stepsPerSplit : ((p.ksteps + 1) & ~1);
+    if constexpr (GM == GATHER_NOPAD_TABLE) {
+        // offset of reduction index i = (c,r,s) relative to the window origin, or the buffer size
+        // for an index past the end (the host checked that (nsteps + 2) * BK entries fit)
+        for (uint32_t i = (uint32_t)tid; i < (uint32_t)(nsteps + 2) * BK; i += 256u) {
+            const uint32_t c = magic_div(i, p.mRS);
+            const uint32_t rs = i - c * (uint32_t)p.RS;
+            const uint32_t r = magic_div(rs, p.mS);
+            const uint32_t sx = rs - r * (uint32_t)p.S;
+            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+            const uint32_t so = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+            so_table[i] = i < (uint32_t)p.CRS ? so : p.x_bytes;
+        }
+        lds_barrier();
+    }
     setup_tile(tile_number(0));
     // Prologue: request the first two tiles back to back, then write the first to LDS stage
     // 0 as it arrives (the second stays in flight, it is written during the first step).

@@ -67,6 +67,11 @@ def _kernel_cases():
     return out
 
 
+def _names():
+    import paper_1410_0759_amd as ig
+    return ig.kernel_names()
+
+
 def test_every_kernel_variant():
     """Each kernel of the table, forced, on problems with tails in every GEMM dimension
     (K not a tile multiple, NPQ ragged, CRS not a multiple of the k tile; odd and even
@@ -131,8 +136,12 @@ def test_gather_modes_are_chosen():
     _, plan = _check(x, w, (2, 1), (1, 1), 1, "f32", tag="mode tapmajor")
     assert plan.gatherMode == 1 and plan.kSteps == 15
     x, w = wl.random_problem(4, 2, 3, 12, 12, 8, 5, 5)
-    _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad")
-    assert plan.gatherMode == 2 and plan.kSteps == 3
+    _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad table")
+    assert plan.gatherMode == 7 and plan.kSteps == 3      # short reduction: tap offsets tabulated in LDS
+    xl, wl_ = wl.random_problem(4, 1, 100, 9, 9, 8, 5, 5)
+    _, plan = _check(xl, wl_, (0, 0), (1, 1), 0, "f32", kernel=[i for i, n in enumerate(_names()) if n == "f32 32x128x32 nopad"][0],
+                     tag="mode nopad")
+    assert plan.gatherMode == 2 and plan.kSteps == 79     # (2500 indices would not fit the table)
     _, plan = _check(x, w, (2, 2), (1, 1), 0, "f32", tag="mode generic")
     assert plan.gatherMode == 0
     _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode generic swap")
