@@ -110,7 +110,7 @@ struct Problem {
     ConvKernelParams kp;
     bool bf16;
     int vec;  // elements per 16 bytes of input
-    int only_gmode = -1;      // >= 0: the one gather mode that can run this problem
+    unsigned mode_mask = 0;   // non-zero: bit g set when gather mode g can run this problem
     bool zero_steps = false;  // nothing to accumulate: the kernel only scales the old output
 };
 
@@ -255,7 +255,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     const bool can_vec = w_aligned && (k.CRS % pr.vec == 0);
     // Lanes should run along y's unit-stride dimension in the epilogue.
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
-    if (h->kernelOverride >= 0 && pr.only_gmode < 0) {   // (the override is for the forward pass)
+    if (h->kernelOverride >= 0 && pr.mode_mask == 0) {   // (the override is for the forward pass)
         const KernelInfo *ki = kernel_info(h->kernelOverride);
         if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(*ki, k, x_aligned))
             return IGC_STATUS_NOT_SUPPORTED;
@@ -267,7 +267,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
-        if (pr.only_gmode >= 0 && ki.gmode != pr.only_gmode) continue;
+        if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -407,7 +407,7 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
     *pr = Problem{};
     pr->bf16 = b.bf16;
     pr->vec = b.bf16 ? 8 : 4;
-    pr->only_gmode = 1;
+    pr->mode_mask = (1u << 1) | (1u << 3);   // tap-major, or the nine-tap table when the phase has nine taps
     pr->zero_steps = ah.taps == 0 || aw.taps == 0;
     ConvKernelParams &k = pr->kp;
     const int es = b.bf16 ? 2 : 4;
@@ -480,7 +480,7 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     Problem &pr = out->pr;
     pr.bf16 = b16;
     pr.vec = 16 / es;
-    pr.only_gmode = 6;
+    pr.mode_mask = 1u << 6;
     ConvKernelParams &k = pr.kp;
     const bool flip = cv->mode == IGC_CONVOLUTION;
     k.x_bytes = (uint32_t)xb;

@@ -225,7 +225,7 @@ struct KernelConfig {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
     static_assert(GMODE != GATHER_WGRAD || (!VECA && 256 % BK == 0), "one reduction index per thread, element-wise first operand");
-    static_assert(GMODE != GATHER_TAPS9 || (VECA && BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
+    static_assert(GMODE != GATHER_TAPS9 || (BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
 template <class Cfg>
@@ -377,7 +377,16 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
       for (int ps = 0; ps < A_PASSES; ++ps) {
         const int row = m0 + a_row[ps];
         const bool ok = row < p.K && a_row[ps] < BM;
-        if constexpr (GM == GATHER_WGRAD)
+        if constexpr (GM == GATHER_TAPS9 && !Cfg::VECA) {
+            // element-wise filter reads through the row / channel / tap strides (backward data,
+            // or a filter that is not 16-byte aligned): channel a_kk/9 of the step, tap a_kk%9
+            const uint32_t ch = (uint32_t)a_kk[ps] / 9u, t = (uint32_t)a_kk[ps] % 9u;
+            const uint32_t r = magic_div(t, p.mS);
+            const uint32_t sx = t - r * (uint32_t)p.S;
+            const uint32_t off = (uint32_t)row * (uint32_t)p.wsRow + ch * (uint32_t)p.wsRed + (uint32_t)p.wTap0 +
+                                 r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS;
+            a_voff[ps] = ok ? off * ES : kOutOfRange;
+        } else if constexpr (GM == GATHER_WGRAD)
             // (rows beyond K are never stored: they may read row 0; the reduction index's part of
             // the offset, which also carries the out-of-range marker, is added per step)
             a_voff[ps] = (uint32_t)(row < p.K ? row : 0) * (uint32_t)p.wsRow * ES;
@@ -433,7 +442,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         } else {
             const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)tau);
             const uint32_t live = mask_lt(ut, (uint32_t)p.ksteps);
-            sc_asoff = ((ut * BK * ES) & live) | (p.w_bytes & ~live);
+            const uint32_t astep = Cfg::VECA ? (uint32_t)BK : (uint32_t)(BK / 9) * (uint32_t)p.wsRed;  // elements per step in a filter row
+            sc_asoff = ((ut * astep * ES) & live) | (p.w_bytes & ~live);
             const uint32_t c = ut * (BK / 9) + (uint32_t)(kpart * (KPT / 9));
 #pragma unroll
             for (int q = 0; q < KPT / 9; ++q)

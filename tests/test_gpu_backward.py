@@ -33,6 +33,10 @@ BWD_PROBLEMS = [
     (2, 7, 12, 40, 33, 1, 7, (0, 3), (1, 3)),
     (2, 2, 8, 8, 4, 4, 4, (3, 3), (1, 1)),            # "full" padding
     (2, 8, 10, 11, 5, 3, 3, (0, 0), (3, 3)),          # stride leaves rows and columns unread
+    (2, 24, 12, 13, 64, 3, 3, (1, 1), (1, 1)),        # nine taps, K in fours: nine-tap table with strided filter reads
+    (3, 70, 9, 9, 132, 3, 3, (0, 2), (1, 1)),         # the same with several row tiles and an odd step count
+    (1, 8, 20, 21, 16, 9, 9, (4, 4), (3, 3)),         # 9x9 with stride 3: every phase has nine taps
+    (2, 6, 11, 10, 12, 1, 9, (0, 4), (1, 1)),         # nine taps in a row
 ]
 
 
