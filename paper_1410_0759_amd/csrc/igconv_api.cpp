@@ -233,7 +233,7 @@ static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
 // staging a patch of the zero-extended image needs every tile's pixel range to fit it.
 static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
     const int gmode = ki.gmode;
-    if (gmode == 6) return false;  // backward-filter kernels are chosen by that pass itself
+    if (gmode == 6 || gmode == 8) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 7) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
@@ -450,6 +450,7 @@ struct BackwardFilterProblem {
     int kernel_id;
     long long ksteps;  // reduction steps in all
     long long tiles;   // output tiles
+    long long tiles_n; // of which along the columns
     uint32_t out_elems;  // K*C*R*S
 };
 
@@ -507,25 +508,44 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     k.wsRow = (int)dy->stride[1]; k.wsRed = (int)dy->stride[0]; k.wsTapR = (int)dy->stride[2]; k.wsTapS = (int)dy->stride[3];
     k.splits = 1;
     out->out_elems = (uint32_t)(dw->k * CRS);
-    // kernel: the smaller row tile when it covers K
+    // Two ways to run it.  Enough channels to fill a column tile: columns ordered (tap, channel),
+    // one tap per tile (gather mode 8; any filter size).  Otherwise the generic gather over
+    // columns (c,r,s) set up above (mode 6).  Row tile: the smaller one when it covers K.
+    const bool by_tap = dw->c >= 24;
+    const int want_bm = dw->k <= 64 ? 64 : 128;
+    const int want_bn = !by_tap ? 128 : ((dw->c - 1) % 128 < 64 ? 64 : 128);   // (least padding of C)
     int id = -1;
     for (int i = 0; i < kernel_count(); ++i) {
         const KernelInfo &ki = *kernel_info(i);
-        if (ki.gmode != 6 || ki.bf16 != b16) continue;
-        if (id < 0 || (dw->k <= 64 ? ki.BM < kernel_info(id)->BM : ki.BM > kernel_info(id)->BM)) id = i;
+        if (ki.gmode == (by_tap ? 8 : 6) && ki.bf16 == b16 && ki.BM == want_bm && ki.BN == want_bn) id = i;
     }
     if (id < 0) return IGC_STATUS_NOT_SUPPORTED;
     out->kernel_id = id;
     const KernelInfo &ki = *kernel_info(id);
     out->ksteps = (NPQ + ki.BK - 1) / ki.BK;
-    out->tiles = (long long)((dw->k + ki.BM - 1) / ki.BM) * ((CRS + ki.BN - 1) / ki.BN);
+    pr.mode_mask = 1u << ki.gmode;
+    if (by_tap) {
+        // columns: channels c < C at distance R*S in dw, the tap chosen per tile; PQ = channel
+        // blocks per tap, Q = S and R = R decode the tile's tap; the window test uses the
+        // forward pads and mode directly
+        const int cblocks = (dw->c + ki.BN - 1) / ki.BN;
+        k.NPQ = dw->c; k.PQ = cblocks; k.Q = dw->s; k.R = dw->r;
+        k.flip = flip ? 1 : 0; k.pad_h = cv->pad_h; k.pad_w = cv->pad_w; k.u = 1; k.v = 1;
+        magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
+        k.ysQ = dw->r * dw->s; k.ysN = 0; k.ysP = 0;
+        out->tiles_n = (long long)dw->r * dw->s * cblocks;
+    } else {
+        out->tiles_n = (CRS + ki.BN - 1) / ki.BN;
+    }
+    out->tiles = (long long)((dw->k + ki.BM - 1) / ki.BM) * out->tiles_n;
     return IGC_STATUS_SUCCESS;
 }
 
-// How to cut the reduction: enough workgroups to fill the chip twice over, ranges of an even
-// number of steps and not shorter than 8; at most max_parts ranges.
+// How to cut the reduction: as many ranges as keep all (tile, range) workgroups resident at
+// once (two per compute unit) - one more would leave a second, nearly empty round -, ranges
+// of an even number of steps and not shorter than 8; at most max_parts ranges.
 static void backward_filter_split(const BackwardFilterProblem &b, long long max_parts, int *splits, int *steps_per_split) {
-    long long want = std::max<long long>(1, (2 * kComputeUnits + b.tiles - 1) / b.tiles);
+    long long want = std::max<long long>(1, (2 * kComputeUnits) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));
     long long per = (b.ksteps + want - 1) / want;
@@ -866,6 +886,7 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     igcConvolutionForwardPlan plan;
     st = fill_plan(b.kernel_id, &b.pr, &plan);
     if (st != IGC_STATUS_SUCCESS) return st;
+    k.tilesN = (int)b.tiles_n;
     const float a = *static_cast<const float *>(alpha), bt = *static_cast<const float *>(beta);
     k.x = x;
     k.w = dy;

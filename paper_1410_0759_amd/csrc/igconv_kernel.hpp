@@ -79,12 +79,13 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
 // (contiguous for NHWC) and rows are pixels.  krow0 / col0: first output channel / first
 // column (n,p,q) of this wavefront's blocks.  Whatever does not depend on the lane goes
 // into the store's scalar offset where that is possible; a wavefront whose blocks lie
-// fully inside K x NPQ needs no per-element test.
-template <bool SWAP, int MB, int NB>
+// fully inside K x NPQ needs no per-element test.  LINEAR: column j sits at j*ysQ.
+template <bool SWAP, int MB, int NB, bool LINEAR = false>
 __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_buffer_rsrc_t ybuf,
                                            f32x16 (&acc)[MB][NB], int krow0, int col0, int half, int l32) {
     const bool use_beta = p.beta != 0.f;
     auto pixel_offset = [&](uint32_t j) -> uint32_t {  // element offset of column j = (n,p,q) in y
+        if constexpr (LINEAR) return j * (uint32_t)p.ysQ;   // columns a fixed distance apart
         const uint32_t n = magic_div(j, p.mPQ);
         const uint32_t rem = j - n * (uint32_t)p.PQ;
         const uint32_t pp = magic_div(rem, p.mQ);
@@ -188,7 +189,13 @@ enum GatherMode {
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
     // the reduction may be cut into several ranges, one workgroup each (see the main loop).
-    GATHER_WGRAD = 6
+    GATHER_WGRAD = 6,
+    // Backward-filter with the columns ordered (tap, channel) and one tap per tile: lanes run
+    // along the reduction index (n,p,q) - consecutive pixels, coalesced loads - and decode it
+    // once per step, window test included, since the tile's tap is a scalar; the elements of
+    // a thread are channels, reached through a scalar offset.  No vector instruction per
+    // gathered element.  Any R, S, pad, stride; wants C to fill a column tile.
+    GATHER_WGRAD_TAP = 8
 };
 
 constexpr int kOffsetTableEntries = 2048;
@@ -224,7 +231,9 @@ struct KernelConfig {
     static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
-    static_assert(GMODE != GATHER_WGRAD || (!VECA && 256 % BK == 0), "one reduction index per thread, element-wise first operand");
+    static_assert((GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP) || (!VECA && 256 % BK == 0),
+                  "one reduction index per thread, element-wise first operand");
+    static_assert(GMODE != GATHER_WGRAD_TAP || BK == 32, "a half wavefront spans the reduction indices of a step");
     static_assert(GMODE != GATHER_TAPS9 || (BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
@@ -236,6 +245,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int GM = Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
+    constexpr bool WG = GM == GATHER_WGRAD || GM == GATHER_WGRAD_TAP;   // backward filter: cut reduction, dy as first operand
+    constexpr bool WGT = GM == GATHER_WGRAD_TAP;
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
@@ -258,7 +269,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // repeat once per range of the reduction.
     const int wg_xcd = (int)(blockIdx.x % 8u), wg_local = (int)(blockIdx.x / 8u);
     const int tiles_mn = p.tilesM * p.tilesN;
-    const int tiles_total = GM == GATHER_WGRAD ? tiles_mn * p.splits : tiles_mn;
+    const int tiles_total = WG ? tiles_mn * p.splits : tiles_mn;
     // number of this workgroup's i-th tile; tiles_total when it has no i-th tile
     auto tile_number = [&](int i) {
         const int local = wg_local + i * p.wgsPerXcd;
@@ -350,7 +361,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // in the other set to be written to LDS.
     u32x4 a_vec[2][Cfg::VECA ? A_PASSES : 1];
     elem_t a_sca[2][Cfg::VECA ? 1 : A_PASSES];
-    elem_t b_val[2][KPT];
+    elem_t b_val[2][KPT > BN / 8 ? KPT : BN / 8];
     // Per-lane decode, lane L standing for element L of this wavefront's run of the
     // step.  GATHER_GENERIC: byte offset of the tap relative to the window origin
     // (dec_so) and the packed tap (dec_tap).  GATHER_NOPAD / GATHER_TAPMAJOR: the
@@ -364,7 +375,17 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     int sc_tau = 0;
     uint32_t vtap = kOutOfRange;
     uint32_t sc_cso[GM == GATHER_TAPS9 ? KPT / 9 : 1];
-    uint32_t a_jo = 0;  // GATHER_WGRAD: offset of this thread's reduction index in the first operand
+    uint32_t a_jo = 0;  // backward filter: offset of this thread's reduction index in the first operand
+    // GATHER_WGRAD_TAP: this thread's reduction index of a step is lane % 32; its columns are
+    // BN/8 consecutive channels starting at wave*(BN/4) + (lane/32)*(BN/8) of the tile.  Per
+    // tile: the tap's window offset and the scalar offset of the wavefront's first channel;
+    // per step: the pixel's offset for this tap (window test folded in).
+    constexpr int WT_E = BN / 8;
+    const int wt_kk = lane & 31;
+    const int wt_col = wave * (BN / 4) + half * WT_E;
+    const uint32_t wt_laneoff = (uint32_t)(half * WT_E) * (uint32_t)p.xsN * ES;
+    int sc_tap_h = 0, sc_tap_w = 0, sc_tapidx = 0;
+    uint32_t sc_colso = 0, wt_pix = kOutOfRange, wt_n = 0, wt_rem = 0, wt_j = 0;
 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
     // reduction range.  The per-thread part of the offset is fixed, the step's part is a
@@ -386,7 +407,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             const uint32_t off = (uint32_t)row * (uint32_t)p.wsRow + ch * (uint32_t)p.wsRed + (uint32_t)p.wTap0 +
                                  r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS;
             a_voff[ps] = ok ? off * ES : kOutOfRange;
-        } else if constexpr (GM == GATHER_WGRAD)
+        } else if constexpr (WG)
             // (rows beyond K are never stored: they may read row 0; the reduction index's part of
             // the offset, which also carries the out-of-range marker, is added per step)
             a_voff[ps] = (uint32_t)(row < p.K ? row : 0) * (uint32_t)p.wsRow * ES;
@@ -398,22 +419,41 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     };
     // Everything the loads of a tile depend on.
     auto setup_tile = [&](int tile) {
-        if constexpr (GM == GATHER_WGRAD) {
+        if constexpr (WG) {
             split = tile / tiles_mn;
             tile -= split * tiles_mn;
             t_begin = split * p.stepsPerSplit;
         }
         m0 = (tile % p.tilesM) * BM;
-        n0 = (tile / p.tilesM) * BN;
-        setup_column();
-        setup_taps();
+        if constexpr (WGT) {
+            // column tile -> (tap, channel block); PQ holds the channel blocks per tap, Q and P
+            // the filter's S and R
+            const uint32_t tn = (uint32_t)(tile / p.tilesM);
+            const uint32_t tap = magic_div(tn, p.mPQ);
+            const uint32_t r = magic_div(tap, p.mQ);
+            const uint32_t sx = tap - r * (uint32_t)p.Q;
+            sc_tapidx = (int)tap;
+            sc_tap_h = (int)(p.flip ? (uint32_t)p.R - 1u - r : r) - p.pad_h;
+            sc_tap_w = (int)(p.flip ? (uint32_t)p.Q - 1u - sx : sx) - p.pad_w;
+            n0 = (int)(tn - tap * (uint32_t)p.PQ) * BN;   // first channel of the tile
+            sc_colso = (uint32_t)(n0 + wave * (BN / 4)) * (uint32_t)p.xsN * ES;
+        } else {
+            n0 = (tile / p.tilesM) * BN;
+            setup_column();
+            setup_taps();
+        }
         setup_rows();
     };
 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
     // each fits between two MFMAs.
     auto decode1 = [&](int tau) {
-        if constexpr (GM == GATHER_NOPAD_TABLE) {
+        if constexpr (WGT) {
+            sc_tau = __builtin_amdgcn_readfirstlane(tau);
+            wt_j = (uint32_t)(sc_tau * BK + wt_kk);
+            wt_n = magic_div(wt_j, p.mRS);
+            wt_rem = wt_j - wt_n * (uint32_t)p.RS;
+        } else if constexpr (GM == GATHER_NOPAD_TABLE) {
             sc_tau = __builtin_amdgcn_readfirstlane(tau);
             dec_so = so_table[sc_tau * BK + kpart * KPT + (lane < KPT ? lane : KPT - 1)];
         } else if constexpr (GEN || GM == GATHER_NOPAD) {
@@ -451,7 +491,16 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         }
     };
     auto decode2 = [&]() {
-        if constexpr (GM == GATHER_NOPAD_TABLE) {
+        if constexpr (WGT) {
+            const uint32_t pp = magic_div(wt_rem, p.mS);
+            const uint32_t qq = wt_rem - pp * (uint32_t)p.S;
+            const bool live = wt_j < (uint32_t)p.CRS;
+            const uint32_t hh = pp * (uint32_t)p.redMulH + (uint32_t)sc_tap_h;   // (wraps below zero: fails the test)
+            const uint32_t ww = qq * (uint32_t)p.redMulW + (uint32_t)sc_tap_w;
+            const bool ok = live && hh < (uint32_t)p.H && ww < (uint32_t)p.W;
+            wt_pix = ok ? (wt_n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * ES + wt_laneoff : kOutOfRange;
+            a_jo = live ? (wt_n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES : kOutOfRange;
+        } else if constexpr (GM == GATHER_NOPAD_TABLE) {
             if (sc_tau == p.tail_step) {   // (see below)
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps)
@@ -505,7 +554,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     };
     auto load_a = [&](int set, int tau, int ps) {
         uint32_t voffa = a_voff[ps], soff;
-        if constexpr (GM == GATHER_WGRAD) {
+        if constexpr (WG) {
             voffa += a_jo;
             soff = 0;
         } else if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
@@ -527,7 +576,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) {
         uint32_t vo, so;
-        if constexpr (GEN) {
+        if constexpr (WGT) {
+            vo = wt_pix;
+            so = sc_colso + (uint32_t)e * (uint32_t)p.xsN * ES;
+        } else if constexpr (GEN) {
             // lane e's decode as scalars, then the window test
             const uint32_t d = __builtin_amdgcn_readlane(dec_so, e);
             const u16x2 tap = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_readlane(dec_tap, e));
@@ -566,6 +618,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr bool B_W16 = (KPT * ES) % 16 == 0;
     constexpr int B_WE = B_W16 ? VEC : VEC / 2;  // elements per write
     auto write_b = [&](int set, int buf, int q) {
+        if constexpr (WGT) {   // one element: channel wt_col + q, this thread's reduction index
+            ldsB[buf * Cfg::B_ELEMS + (wt_col + q) * LD + wt_kk] = b_val[set][q];
+            return;
+        }
         elem_t *const dst = ldsB + buf * Cfg::B_ELEMS + jl * LD + kpart * KPT + q * B_WE;
         uint32_t v[4];
         if constexpr (Cfg::BF16) {
@@ -587,8 +643,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
 
     // Moving one tile is a list of small items: NL load items (decode halves, filter
     // loads, gathered elements) and NW LDS-write items.
-    constexpr int NW_A = A_PASSES, NW_B = KPT / B_WE, NW = NW_A + NW_B;
-    constexpr int NL = 2 + A_PASSES + KPT;
+    constexpr int NB_ELEMS = WGT ? WT_E : KPT;   // gathered elements per thread and step
+    constexpr int NW_A = A_PASSES, NW_B = WGT ? WT_E : KPT / B_WE, NW = NW_A + NW_B;
+    constexpr int NL = 2 + A_PASSES + NB_ELEMS;
     auto load_item = [&](int i, int set, int tau) {
         if (i == 0) decode1(tau);
         else if (i == 1) decode2();
@@ -726,7 +783,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // step on zero tiles), so that the loop body stays a single basic block.  GATHER_WGRAD: a
     // tile is one range of an even number of steps; a range that reaches past the last step
     // reads zeros there.
-    const int nsteps = GM == GATHER_WGRAD ? p.stepsPerSplit : ((p.ksteps + 1) & ~1);
+    const int nsteps = WG ? p.stepsPerSplit : ((p.ksteps + 1) & ~1);
     if constexpr (GM == GATHER_NOPAD_TABLE) {
         // offset of reduction index i = (c,r,s) relative to the window origin, or the buffer size
         // for an index past the end (the host checked that (nsteps + 2) * BK entries fit)
@@ -762,15 +819,17 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         // The last two steps of this tile request the first two steps of the workgroup's next
         // tile (of "no tile" after the last one): its operands arrive and its first fragments
         // are read while this tile is still being multiplied and stored.
-        const int out_m0 = m0, out_n0 = n0, out_split = split;
+        const int out_m0 = m0, out_n0 = n0, out_split = split, out_tap = sc_tapidx;
         const int next = tile_number(it);
         setup_tile(next);
         step(std::integral_constant<int, 0>{}, t_begin);
         step(std::integral_constant<int, 1>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
+        // (GATHER_WGRAD_TAP: the columns are channels, 'R*S' elements apart; the tile's tap moves the base)
+        const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + (WGT ? (uint32_t)out_tap * 4u : 0u);
         const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
-            static_cast<char *>(p.y) + (size_t)out_split * p.ySplitBytes, 0, p.y_bytes, kBufferWord3);
-        store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
+            static_cast<char *>(p.y) + ybase, 0, p.y_bytes - (WGT ? (uint32_t)out_tap * 4u : 0u), kBufferWord3);
+        store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
         if (next >= tiles_total) break;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)

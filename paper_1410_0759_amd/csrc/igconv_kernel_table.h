@@ -15,7 +15,8 @@ struct KernelInfo {
     int gmode;      // gather mode: 0 generic, 1 tap-major reduction order, 2 unpadded, 3 nine-tap table,
                     // 4 channel vectors (bf16, nine taps, unit channel stride), 5 the same from a staged image patch,
                     // 6 backward-filter (generic gather, roles of columns and reduction exchanged),
-                    // 7 unpadded with the tap offsets in an LDS table (short reductions)
+                    // 7 unpadded with the tap offsets in an LDS table (short reductions),
+                    // 8 backward-filter with columns (tap, channel), one tap per tile
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).

@@ -7,7 +7,15 @@
     X("f32 64x128x32 wgrad", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
     X("f32 128x128x32 wgrad", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
     X("bf16 64x128x32 wgrad", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
-    X("bf16 128x128x32 wgrad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD)
+    X("bf16 128x128x32 wgrad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
+    X("f32 64x64x32 wgrad tap", false, 64, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("f32 128x64x32 wgrad tap", false, 128, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("f32 64x128x32 wgrad tap", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("f32 128x128x32 wgrad tap", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("bf16 64x64x32 wgrad tap", true, 64, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("bf16 128x64x32 wgrad tap", true, 128, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("bf16 64x128x32 wgrad tap", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("bf16 128x128x32 wgrad tap", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP)
 
 IGC_DEFINE_GROUP(kGroupWgrad)
 
