@@ -1,21 +1,32 @@
-"""Compile the C oracle with gcc into ``oracle/libconv_oracle.so`` (host code only)."""
+"""Compile the C oracles with gcc into ``oracle/lib*_oracle.so`` (host code only)."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "conv_oracle.c")
 LIB = os.path.join(HERE, "libconv_oracle.so")
+POINTWISE_SRC = os.path.join(HERE, "pointwise_oracle.c")
+POINTWISE_LIB = os.path.join(HERE, "libpointwise_oracle.so")
+
+
+def _compile(src, lib, force, extra):
+    if not force and os.path.exists(lib) and os.path.getmtime(lib) >= os.path.getmtime(src):
+        return lib
+    cmd = ["gcc", "-O2", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra"] + extra + ["-o", lib + ".tmp", src]
+    subprocess.run(cmd, check=True)
+    os.replace(lib + ".tmp", lib)
+    return lib
 
 
 def build(force: bool = True) -> str:
-    """Build the shared library; with ``force=False`` keep an existing up-to-date one."""
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
-        return LIB
-    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
-           "-o", LIB + ".tmp", SRC]
-    subprocess.run(cmd, check=True)
-    os.replace(LIB + ".tmp", LIB)
-    return LIB
+    """Build both shared libraries; with ``force=False`` keep existing up-to-date ones.
+    Returns the path of the convolution oracle."""
+    _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"])
+    return _compile(SRC, LIB, force, ["-fopenmp"])
+
+
+def build_pointwise(force: bool = False) -> str:
+    return _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"])
 
 
 if __name__ == "__main__":
