@@ -56,10 +56,27 @@ typedef enum {
     IGC_CROSS_CORRELATION = 1 /* tap r reads row p*u + r - pad_h (Section 2.1.1, last paragraph) */
 } igcConvolutionMode;
 
+typedef enum {
+    IGC_ACTIVATION_SIGMOID = 0, /* 1 / (1 + exp(-x)) */
+    IGC_ACTIVATION_RELU = 1,    /* max(x, 0) */
+    IGC_ACTIVATION_TANH = 2
+} igcActivationMode;
+
+typedef enum {
+    IGC_SOFTMAX_MODE_INSTANCE = 0, /* per image over (c,h,w) */
+    IGC_SOFTMAX_MODE_CHANNEL = 1   /* per (n,h,w) over c */
+} igcSoftmaxMode;
+
+typedef enum {
+    IGC_POOLING_MAX = 0,
+    IGC_POOLING_AVERAGE = 1 /* mean of the window's elements that lie inside the image */
+} igcPoolingMode;
+
 typedef struct igcContext *igcHandle_t;
 typedef struct igcTensorStruct *igcTensorDescriptor_t;
 typedef struct igcFilterStruct *igcFilterDescriptor_t;
 typedef struct igcConvolutionStruct *igcConvolutionDescriptor_t;
+typedef struct igcPoolingStruct *igcPoolingDescriptor_t;
 
 /* Human-readable name of a status; never NULL; static storage. */
 const char *igcGetErrorString(igcStatus status);
@@ -230,6 +247,64 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha,
                                        void *workSpace, size_t workSpaceSizeInBytes,
                                        const void *beta,
                                        igcFilterDescriptor_t dwDesc, void *dw);
+
+/* ---- other functions (Section 2.2: activations, softmax, pooling, tensor addition) ----
+ * Bandwidth-bound kernels on float tensors laid out by their descriptors (any non-negative
+ * strides for inputs; outputs non-aliasing).  All of them blend like the convolutions:
+ * out = alpha * value + beta * out, alpha and beta HOST floats, out read only when
+ * *beta != 0.  Common errors: BAD_PARAM for null pointers, mismatched dimensions, aliasing
+ * output strides or misaligned pointers; NOT_INITIALIZED for unset descriptors;
+ * NOT_SUPPORTED for data types other than float, byte offsets of 2^31 or more;
+ * EXECUTION_FAILED when the runtime rejects the launch.  Validation precedes any GPU call.
+ * An input may be the output buffer itself (same descriptor, same pointer: in-place) but
+ * must not overlap it otherwise. */
+
+/* y = alpha * f(x) + beta * y, f per igcActivationMode; x and y have equal dimensions. */
+igcStatus igcActivationForward(igcHandle_t handle, igcActivationMode mode, const void *alpha,
+                               igcTensorDescriptor_t xDesc, const void *x,
+                               const void *beta, igcTensorDescriptor_t yDesc, void *y);
+
+/* dx = alpha * dy * f'(.) + beta * dx, with f' taken from the forward OUTPUT y for the
+ * sigmoid (y(1-y)) and tanh (1-y^2) and from the forward INPUT x for the rectifier (1 where
+ * x > 0).  All four tensors have equal dimensions. */
+igcStatus igcActivationBackward(igcHandle_t handle, igcActivationMode mode, const void *alpha,
+                                igcTensorDescriptor_t yDesc, const void *y,
+                                igcTensorDescriptor_t dyDesc, const void *dy,
+                                igcTensorDescriptor_t xDesc, const void *x,
+                                const void *beta, igcTensorDescriptor_t dxDesc, void *dx);
+
+/* y = alpha * b + beta * y with b broadcast along each dimension in which it has size 1
+ * (its other dimensions equal y's): a bias (1,C,1,1) added to every pixel, a full tensor
+ * added element by element, and everything in between. */
+igcStatus igcAddTensor(igcHandle_t handle, const void *alpha,
+                       igcTensorDescriptor_t bDesc, const void *b,
+                       const void *beta, igcTensorDescriptor_t yDesc, void *y);
+
+/* y = alpha * softmax(x) + beta * y over the groups igcSoftmaxMode names, computed the
+ * numerically stable way: exp(x - max of the group) / sum of those. */
+igcStatus igcSoftmaxForward(igcHandle_t handle, igcSoftmaxMode mode, const void *alpha,
+                            igcTensorDescriptor_t xDesc, const void *x,
+                            const void *beta, igcTensorDescriptor_t yDesc, void *y);
+
+/* Pooling descriptor: window size, zero border on each side (pad < window), stride. */
+igcStatus igcCreatePoolingDescriptor(igcPoolingDescriptor_t *desc);
+igcStatus igcDestroyPoolingDescriptor(igcPoolingDescriptor_t desc);
+igcStatus igcSetPooling2dDescriptor(igcPoolingDescriptor_t desc, igcPoolingMode mode,
+                                    int windowHeight, int windowWidth,
+                                    int pad_h, int pad_w, int u, int v);
+igcStatus igcGetPooling2dDescriptor(igcPoolingDescriptor_t desc, igcPoolingMode *mode,
+                                    int *windowHeight, int *windowWidth,
+                                    int *pad_h, int *pad_w, int *u, int *v);
+/* n = x.n, c = x.c, p = floor((H + 2 pad_h - windowHeight)/u) + 1, q likewise (eq. 1 with
+ * the window in place of the filter).  BAD_PARAM if p or q would be < 1. */
+igcStatus igcGetPooling2dForwardOutputDim(igcPoolingDescriptor_t poolDesc,
+                                          igcTensorDescriptor_t xDesc,
+                                          int *n, int *c, int *p, int *q);
+/* y[n,c,p,q] = alpha * (max or mean over the window starting at (p*u - pad_h, q*v - pad_w),
+ * elements outside the image taking no part) + beta * y. */
+igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc, const void *alpha,
+                            igcTensorDescriptor_t xDesc, const void *x,
+                            const void *beta, igcTensorDescriptor_t yDesc, void *y);
 
 /* ---- introspection and tuning (host only; no GPU call) ----------------------------
  * The launch plan the library derives for a problem: the tile of the lowered

@@ -17,6 +17,10 @@ __all__ = [
     "get_output_dim", "get_workspace_size", "get_plan", "convolution_forward",
     "get_backward_data_workspace_size", "convolution_backward_data",
     "get_backward_filter_workspace_size", "convolution_backward_filter",
+    "PoolingDescriptor", "get_pooling_output_dim", "activation_forward", "activation_backward", "add_tensor",
+    "softmax_forward", "pooling_forward",
+    "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
+    "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
 ]
 
@@ -27,6 +31,9 @@ LIB_PATH = os.path.join(HERE, "libigconv.so")
  IGC_STATUS_NOT_INITIALIZED, IGC_STATUS_ALLOC_FAILED, IGC_STATUS_EXECUTION_FAILED) = range(6)
 IGC_DATA_FLOAT, IGC_DATA_BFLOAT16 = 0, 1
 IGC_CONVOLUTION, IGC_CROSS_CORRELATION = 0, 1
+IGC_ACTIVATION_SIGMOID, IGC_ACTIVATION_RELU, IGC_ACTIVATION_TANH = 0, 1, 2
+IGC_SOFTMAX_MODE_INSTANCE, IGC_SOFTMAX_MODE_CHANNEL = 0, 1
+IGC_POOLING_MAX, IGC_POOLING_AVERAGE = 0, 1
 
 
 class igcConvolutionForwardPlan(ctypes.Structure):
@@ -65,6 +72,16 @@ DECLARED_SYMBOLS = {
     "igcConvolutionBackwardData": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcGetConvolutionBackwardFilterWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
     "igcConvolutionBackwardFilter": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "igcActivationForward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcActivationBackward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcAddTensor": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcSoftmaxForward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcCreatePoolingDescriptor": (_i, [_P(_vp)]),
+    "igcDestroyPoolingDescriptor": (_i, [_vp]),
+    "igcSetPooling2dDescriptor": (_i, [_vp, _i, _i, _i, _i, _i, _i, _i]),
+    "igcGetPooling2dDescriptor": (_i, [_vp] + [_P(_i)] * 7),
+    "igcGetPooling2dForwardOutputDim": (_i, [_vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
+    "igcPoolingForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
     "igcGetKernelCount": (_i, []),
     "igcGetKernelName": (ctypes.c_char_p, [_i]),
@@ -189,6 +206,56 @@ class ConvolutionDescriptor(_Owned):
         check(lib().igcGetConvolution2dDescriptor(self.ptr, *[ctypes.byref(a) for a in v]),
               "igcGetConvolution2dDescriptor")
         return tuple(a.value for a in v)
+
+
+class PoolingDescriptor(_Owned):
+    _create, _destroy = "igcCreatePoolingDescriptor", "igcDestroyPoolingDescriptor"
+
+    def set(self, mode, win_h, win_w, pad_h, pad_w, u, v):
+        check(lib().igcSetPooling2dDescriptor(self.ptr, mode, win_h, win_w, pad_h, pad_w, u, v),
+              "igcSetPooling2dDescriptor")
+        return self
+
+    def get(self):
+        v = [_i() for _ in range(7)]
+        check(lib().igcGetPooling2dDescriptor(self.ptr, *[ctypes.byref(a) for a in v]), "igcGetPooling2dDescriptor")
+        return tuple(a.value for a in v)
+
+
+def get_pooling_output_dim(pool, xdesc):
+    v = [_i() for _ in range(4)]
+    check(lib().igcGetPooling2dForwardOutputDim(pool.ptr, xdesc.ptr, *[ctypes.byref(a) for a in v]),
+          "igcGetPooling2dForwardOutputDim")
+    return tuple(a.value for a in v)
+
+
+def activation_forward(handle, mode, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcActivationForward(handle.ptr, mode, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
+                                      ydesc.ptr, _vp(y_ptr))
+
+
+def activation_backward(handle, mode, alpha, ydesc, y_ptr, dydesc, dy_ptr, xdesc, x_ptr, beta, dxdesc, dx_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcActivationBackward(handle.ptr, mode, ctypes.byref(a), ydesc.ptr, _vp(y_ptr), dydesc.ptr, _vp(dy_ptr),
+                                       xdesc.ptr, _vp(x_ptr), ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
+
+
+def add_tensor(handle, alpha, bdesc, b_ptr, beta, ydesc, y_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcAddTensor(handle.ptr, ctypes.byref(a), bdesc.ptr, _vp(b_ptr), ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
+
+
+def softmax_forward(handle, mode, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcSoftmaxForward(handle.ptr, mode, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
+                                   ydesc.ptr, _vp(y_ptr))
+
+
+def pooling_forward(handle, pool, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcPoolingForward(handle.ptr, pool.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
+                                   ydesc.ptr, _vp(y_ptr))
 
 
 def get_output_dim(conv, xdesc, wdesc):

@@ -11,29 +11,7 @@
 #include "igconv_kernel_table.h"
 #include "igconv_params.h"
 
-struct igcContext {
-    void *stream = nullptr;
-    int kernelOverride = -1;
-};
-
-struct igcTensorStruct {
-    bool set = false;
-    igcDataType dtype = IGC_DATA_FLOAT;
-    int dim[4] = {0, 0, 0, 0};           // n, c, h, w
-    long long stride[4] = {0, 0, 0, 0};  // elements
-};
-
-struct igcFilterStruct {
-    bool set = false;
-    igcDataType dtype = IGC_DATA_FLOAT;
-    int k = 0, c = 0, r = 0, s = 0;
-};
-
-struct igcConvolutionStruct {
-    bool set = false;
-    int pad_h = 0, pad_w = 0, u = 1, v = 1;
-    igcConvolutionMode mode = IGC_CROSS_CORRELATION;
-};
+#include "igconv_desc.h"
 
 namespace igc {
 
@@ -73,37 +51,11 @@ static bool magic_for(uint32_t d, Magic *m) {
     return true;
 }
 
-static int elem_size(igcDataType t) { return t == IGC_DATA_BFLOAT16 ? 2 : 4; }
-
 // eq. 1: ceil((H - R + 1 + 2 pad) / u); <= 0 when there is no output.
 static long long out_dim(long long H, long long R, long long u, long long pad) {
     const long long num = H - R + 1 + 2 * pad;
     if (num <= 0) return 0;
     return (num + u - 1) / u;
-}
-
-// Elements spanned by a strided 4-D tensor: 1 + sum (dim-1)*stride.
-static long long extent(const int dim[4], const long long stride[4]) {
-    long long e = 1;
-    for (int i = 0; i < 4; ++i) e += (long long)(dim[i] - 1) * stride[i];
-    return e;
-}
-
-// True when every index tuple lands on its own element.  Sufficient test: with the
-// dimensions of size > 1 sorted by stride, each stride must step over everything
-// the smaller-stride dimensions span.
-static bool non_aliasing(const int dim[4], const long long stride[4]) {
-    int idx[4], n = 0;
-    for (int i = 0; i < 4; ++i)
-        if (dim[i] > 1) idx[n++] = i;
-    std::sort(idx, idx + n, [&](int a, int b) { return stride[a] < stride[b]; });
-    long long span = 1;  // elements covered so far
-    for (int t = 0; t < n; ++t) {
-        const int i = idx[t];
-        if (stride[i] < span) return false;
-        span += (long long)(dim[i] - 1) * stride[i];
-    }
-    return true;
 }
 
 struct Problem {

@@ -1,0 +1,569 @@
+// The library's other functions (paper, Section 2.2): activations, softmax, pooling and
+// tensor addition with broadcasting.  All are bound by HBM bandwidth, so the kernels only
+// care about two things: every wavefront reads and writes consecutive addresses, and no
+// tensor is read twice from memory when once suffices.
+//
+// Element-wise functions (activations, addition): the host orders the four dimensions by the
+// output's strides, drops those of size 1 and merges neighbours that are contiguous in every
+// tensor involved, so that a packed tensor becomes one run of elements and "bias (1,C,1,1)
+// onto NCHW" becomes (N*C rows) x (H*W contiguous elements); threads then run along the
+// innermost dimension, four elements each (16-byte accesses) when every tensor allows it.
+// Softmax per location: one thread per (n,h,w), lanes along the contiguous spatial dimension,
+// running maximum and rescaled sum in one pass over the channels, a second pass to write.
+// Softmax per image: one workgroup per image, the same two passes with a block reduction.
+// Pooling: one thread per output element, ordered by the output's strides.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+
+#include "igconv_desc.h"
+#include "igconv_params.h"
+
+namespace igc {
+namespace {
+
+constexpr long long kMaxBytesOther = 1ll << 31;
+
+bool magic_of(uint32_t d, Magic *m) {
+    if (d < 1u || d >= (1u << 31)) return false;
+    uint32_t shift = 0;
+    while ((1ull << shift) < d) ++shift;
+    const unsigned __int128 one = 1;
+    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;
+    m->mul = (uint32_t)(q - (one << 32));
+    m->shift = shift;
+    return true;
+}
+
+__device__ __forceinline__ uint32_t mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
+
+// Up to four dimensions, outermost first, with the element strides of up to four tensors
+// (tensor 0 is the output).
+constexpr int kMaxTensors = 4;
+struct View {
+    int rank;
+    uint32_t dim[4];
+    Magic mdim[4];
+    uint32_t stride[kMaxTensors][4];
+    int which[4];   // logical dimension (0 n, 1 c, 2 h, 3 w) behind each entry (meaningful when nothing was merged)
+};
+
+// Builds the view: dimensions ordered by the output's stride (largest first); with `merge`,
+// size-1 dimensions dropped and neighbours merged where every tensor is contiguous across them.
+View make_view(const int dim[4], const long long (*stride)[4], int tensors, bool merge) {
+    int order[4] = {0, 1, 2, 3};
+    std::stable_sort(order, order + 4, [&](int a, int b) { return stride[0][a] > stride[0][b]; });
+    View v{};
+    for (int i = 0; i < 4; ++i) {
+        const int d = order[i];
+        if (merge && dim[d] == 1) continue;
+        bool fused = false;
+        if (merge && v.rank > 0) {
+            fused = true;
+            for (int t = 0; t < tensors; ++t)
+                if ((long long)v.stride[t][v.rank - 1] != stride[t][d] * dim[d]) fused = false;
+        }
+        if (fused) {
+            v.dim[v.rank - 1] *= (uint32_t)dim[d];
+            for (int t = 0; t < tensors; ++t) v.stride[t][v.rank - 1] = (uint32_t)stride[t][d];
+        } else {
+            v.dim[v.rank] = (uint32_t)dim[d];
+            v.which[v.rank] = d;
+            for (int t = 0; t < tensors; ++t) v.stride[t][v.rank] = (uint32_t)stride[t][d];
+            ++v.rank;
+        }
+    }
+    if (v.rank == 0) {   // a single element
+        v.rank = 1;
+        v.dim[0] = 1;
+    }
+    for (int i = 0; i < v.rank; ++i) magic_of(v.dim[i], &v.mdim[i]);
+    return v;
+}
+
+// idx (row-major over the view's dimensions) -> element offset in each of `T` tensors
+template <int T>
+__device__ __forceinline__ void offsets_of(const View &v, uint32_t idx, uint32_t scale_inner, uint32_t (&off)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t) off[t] = 0;
+    uint32_t rem = idx;
+    for (int d = v.rank - 1; d >= 0; --d) {
+        uint32_t i;
+        if (d == 0) {
+            i = rem;
+        } else {
+            const uint32_t q = mdiv(rem, v.mdim[d]);
+            i = rem - q * v.dim[d];
+            rem = q;
+        }
+        if (d == v.rank - 1) i *= scale_inner;
+#pragma unroll
+        for (int t = 0; t < T; ++t) off[t] += i * v.stride[t][d];
+    }
+}
+
+enum EwOp { EW_ACT_FWD = 0, EW_ACT_BWD = 1, EW_ADD = 2 };
+
+struct EwArgs {
+    View v;          // tensor 0: output; 1..: inputs
+    uint32_t count;  // work items: elements, or groups of four in vector mode
+    int op, mode;
+    float alpha, beta;
+    float *out;
+    const float *in[3];
+};
+
+__device__ __forceinline__ float act_fwd(int mode, float x) {
+    if (mode == IGC_ACTIVATION_SIGMOID) return 1.f / (1.f + __expf(-x));
+    if (mode == IGC_ACTIVATION_RELU) return fmaxf(x, 0.f);
+    // tanh(x) = 1 - 2 / (exp(2x) + 1): exact limits for large |x|, no cancellation near 0 beyond rounding
+    const float e = __expf(2.f * x);
+    return 1.f - 2.f / (e + 1.f);
+}
+
+__device__ __forceinline__ float ew_value(const EwArgs &a, float i0, float i1, float i2) {
+    if (a.op == EW_ACT_FWD) return act_fwd(a.mode, i0);
+    if (a.op == EW_ADD) return i0;
+    // backward: i0 = y, i1 = dy, i2 = x
+    float d;
+    if (a.mode == IGC_ACTIVATION_SIGMOID) d = i0 * (1.f - i0);
+    else if (a.mode == IGC_ACTIVATION_RELU) d = i2 > 0.f ? 1.f : 0.f;
+    else d = 1.f - i0 * i0;
+    return i1 * d;
+}
+
+// VEC = 4: each thread handles four consecutive elements of the innermost dimension, which every
+// tensor either walks with stride 1 (16-byte access) or does not walk at all (stride 0: broadcast).
+template <int VEC>
+__global__ __launch_bounds__(256) void igconv_elementwise_kernel(const EwArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.count) return;
+    const int nin = a.op == EW_ACT_BWD ? 3 : 1;
+    uint32_t off[4];
+    offsets_of<4>(a.v, idx, VEC, off);
+    float in[3][VEC];
+    for (int t = 0; t < nin; ++t) {
+        // (the rectifier's backward pass does not need y, the others do not need x)
+        if (a.op == EW_ACT_BWD && ((a.mode == IGC_ACTIVATION_RELU && t == 0) || (a.mode != IGC_ACTIVATION_RELU && t == 2))) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) in[t][e] = 0.f;
+            continue;
+        }
+        const float *src = a.in[t] + off[t + 1];
+        if (VEC == 4 && a.v.stride[t + 1][a.v.rank - 1] == 1u) {
+            const float4 q = *reinterpret_cast<const float4 *>(src);
+            in[t][0] = q.x; in[t][1] = q.y; in[t][2] = q.z; in[t][VEC - 1] = q.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) in[t][e] = src[0];   // VEC == 1, or a broadcast element
+        }
+    }
+    float res[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) res[e] = a.alpha * ew_value(a, in[0][e], in[1][e], in[2][e]);
+    float *dst = a.out + off[0];
+    if (a.beta != 0.f) {
+        if (VEC == 4) {
+            const float4 o = *reinterpret_cast<const float4 *>(dst);
+            res[0] += a.beta * o.x; res[1] += a.beta * o.y; res[2] += a.beta * o.z; res[VEC - 1] += a.beta * o.w;
+        } else {
+            res[0] += a.beta * dst[0];
+        }
+    }
+    if (VEC == 4) {
+        *reinterpret_cast<float4 *>(dst) = make_float4(res[0], res[1], res[2], res[VEC - 1]);
+    } else {
+        dst[0] = res[0];
+    }
+}
+
+// ---- softmax -------------------------------------------------------------------------
+struct SoftmaxArgs {
+    View v;            // CHANNEL: the (n,h,w) locations (tensor 0: y, tensor 1: x); INSTANCE: (c,h,w) of one image
+    uint32_t count;    // locations (CHANNEL) / elements per image (INSTANCE)
+    uint32_t C;
+    uint32_t ysC, xsC; // CHANNEL: channel strides; INSTANCE: image strides
+    float alpha, beta;
+    float *y;
+    const float *x;
+};
+
+// running (max, sum of exp(x - max)) pair, merged with another
+__device__ __forceinline__ void sm_merge(float &m, float &s, float m2, float s2) {
+    const float mm = fmaxf(m, m2);
+    s = (m == mm ? s : s * __expf(m - mm)) + (m2 == mm ? s2 : s2 * __expf(m2 - mm));
+    m = mm;
+}
+
+__global__ __launch_bounds__(256) void igconv_softmax_channel_kernel(const SoftmaxArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.count) return;
+    uint32_t off[2];
+    offsets_of<2>(a.v, idx, 1u, off);
+    const float *x = a.x + off[1];
+    float m = -INFINITY, s = 0.f;
+    for (uint32_t c = 0; c < a.C; ++c) {
+        const float v = x[c * a.xsC];
+        if (v > m) {
+            s = s * __expf(m - v) + 1.f;   // (exp(-inf) = 0 on the first element)
+            m = v;
+        } else {
+            s += __expf(v - m);
+        }
+    }
+    const float inv = a.alpha / s;
+    float *y = a.y + off[0];
+    for (uint32_t c = 0; c < a.C; ++c) {
+        float r = __expf(x[c * a.xsC] - m) * inv;
+        if (a.beta != 0.f) r += a.beta * y[c * a.ysC];
+        y[c * a.ysC] = r;
+    }
+}
+
+__global__ __launch_bounds__(256) void igconv_softmax_instance_kernel(const SoftmaxArgs a) {
+    __shared__ float sh_m[4], sh_s[4];
+    const float *x = a.x + (size_t)blockIdx.x * a.xsC;
+    float *y = a.y + (size_t)blockIdx.x * a.ysC;
+    float m = -INFINITY, s = 0.f;
+    for (uint32_t i = threadIdx.x; i < a.count; i += 256u) {
+        uint32_t off[2];
+        offsets_of<2>(a.v, i, 1u, off);
+        const float v = x[off[1]];
+        if (v > m) {
+            s = s * __expf(m - v) + 1.f;
+            m = v;
+        } else {
+            s += __expf(v - m);
+        }
+    }
+    // (a thread that saw no element holds (-inf, 0); merging with it must not produce NaN)
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float m2 = __shfl_xor(m, d), s2 = __shfl_xor(s, d);
+        if (m2 != -INFINITY) {
+            if (m == -INFINITY) { m = m2; s = s2; } else sm_merge(m, s, m2, s2);
+        }
+    }
+    if ((threadIdx.x & 63u) == 0u) {
+        sh_m[threadIdx.x >> 6] = m;
+        sh_s[threadIdx.x >> 6] = s;
+    }
+    __syncthreads();
+    m = sh_m[0];
+    s = sh_s[0];
+    for (int w = 1; w < 4; ++w)
+        if (sh_m[w] != -INFINITY) {
+            if (m == -INFINITY) { m = sh_m[w]; s = sh_s[w]; } else sm_merge(m, s, sh_m[w], sh_s[w]);
+        }
+    const float inv = a.alpha / s;
+    for (uint32_t i = threadIdx.x; i < a.count; i += 256u) {
+        uint32_t off[2];
+        offsets_of<2>(a.v, i, 1u, off);
+        float r = __expf(x[off[1]] - m) * inv;
+        if (a.beta != 0.f) r += a.beta * y[off[0]];
+        y[off[0]] = r;
+    }
+}
+
+// ---- pooling ---------------------------------------------------------------------------
+struct PoolArgs {
+    View v;          // output (n,c,p,q) ordered by y's strides, nothing merged; tensor 0: y
+    uint32_t count;
+    int mode, H, W, win_h, win_w, pad_h, pad_w, u, v_;
+    uint32_t xs[4];
+    float alpha, beta;
+    float *y;
+    const float *x;
+};
+
+__global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.count) return;
+    // idx -> logical (n,c,p,q) and the output offset
+    uint32_t coord[4] = {0, 0, 0, 0}, yoff = 0, rem = idx;
+    for (int d = a.v.rank - 1; d >= 0; --d) {
+        uint32_t i;
+        if (d == 0) {
+            i = rem;
+        } else {
+            const uint32_t q = mdiv(rem, a.v.mdim[d]);
+            i = rem - q * a.v.dim[d];
+            rem = q;
+        }
+        coord[a.v.which[d]] = i;
+        yoff += i * a.v.stride[0][d];
+    }
+    const int h0 = (int)coord[2] * a.u - a.pad_h, w0 = (int)coord[3] * a.v_ - a.pad_w;
+    const float *x = a.x + coord[0] * a.xs[0] + coord[1] * a.xs[1];
+    float m = -INFINITY, s = 0.f;
+    int cnt = 0;
+    for (int r = 0; r < a.win_h; ++r) {
+        const int h = h0 + r;
+        if (h < 0 || h >= a.H) continue;
+        for (int c = 0; c < a.win_w; ++c) {
+            const int w = w0 + c;
+            if (w < 0 || w >= a.W) continue;
+            const float val = x[(uint32_t)h * a.xs[2] + (uint32_t)w * a.xs[3]];
+            m = fmaxf(m, val);
+            s += val;
+            ++cnt;
+        }
+    }
+    float r = a.alpha * (a.mode == IGC_POOLING_MAX ? m : s / (float)cnt);
+    if (a.beta != 0.f) r += a.beta * a.y[yoff];
+    a.y[yoff] = r;
+}
+
+// ---- host side ---------------------------------------------------------------------------
+template <class Kernel, class Args>
+igcStatus launch(Kernel kernel, const char *what, const Args &args, uint32_t blocks, void *stream) {
+    Args copy = args;
+    void *argv[] = {&copy};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(256), argv, 0,
+                                         static_cast<hipStream_t>(stream));
+    if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
+        std::fprintf(stderr, "igconv: launch of %s failed: %s\n", what, hipGetErrorString(e));
+    return e == hipSuccess ? IGC_STATUS_SUCCESS : IGC_STATUS_EXECUTION_FAILED;
+}
+
+igcStatus check_float_tensor(igcTensorDescriptor_t d, bool output) {
+    if (!d) return IGC_STATUS_BAD_PARAM;
+    if (!d->set) return IGC_STATUS_NOT_INITIALIZED;
+    if (d->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    if (extent(d->dim, d->stride) * 4 >= kMaxBytesOther) return IGC_STATUS_NOT_SUPPORTED;
+    if (output && !non_aliasing(d->dim, d->stride)) return IGC_STATUS_BAD_PARAM;
+    return IGC_STATUS_SUCCESS;
+}
+
+bool same_dims(igcTensorDescriptor_t a, igcTensorDescriptor_t b) {
+    for (int i = 0; i < 4; ++i)
+        if (a->dim[i] != b->dim[i]) return false;
+    return true;
+}
+
+// Element-wise launch: output `y` and `nin` inputs with (possibly broadcast) strides.
+igcStatus run_elementwise(igcHandle_t h, int op, int mode, float alpha, float beta, igcTensorDescriptor_t yd, void *y,
+                          int nin, const long long (*in_stride)[4], const void *const *in) {
+    long long stride[kMaxTensors][4] = {};
+    for (int d = 0; d < 4; ++d) stride[0][d] = yd->stride[d];
+    for (int t = 0; t < nin; ++t)
+        for (int d = 0; d < 4; ++d) stride[t + 1][d] = in_stride[t][d];
+    EwArgs a{};
+    a.v = make_view(yd->dim, stride, nin + 1, /*merge=*/true);
+    const uint32_t inner = a.v.dim[a.v.rank - 1];
+    uint32_t total = 1;
+    for (int i = 0; i < a.v.rank; ++i) total *= a.v.dim[i];
+    // four elements per thread when the innermost run allows 16-byte accesses in every tensor
+    bool vec = inner % 4 == 0 && (uintptr_t)y % 16 == 0 && a.v.stride[0][a.v.rank - 1] == 1;
+    for (int t = 0; t <= nin && vec; ++t) {
+        const uint32_t si = a.v.stride[t][a.v.rank - 1];
+        if (si > 1) vec = false;
+        if (t > 0 && si == 1 && (uintptr_t)in[t - 1] % 16 != 0) vec = false;
+        for (int d = 0; d + 1 < a.v.rank; ++d)
+            if (si == 1 && a.v.stride[t][d] % 4 != 0) vec = false;
+    }
+    a.op = op; a.mode = mode; a.alpha = alpha; a.beta = beta;
+    a.out = static_cast<float *>(y);
+    for (int t = 0; t < nin; ++t) a.in[t] = static_cast<const float *>(in[t]);
+    if (vec) {
+        a.v.dim[a.v.rank - 1] = inner / 4;
+        magic_of(a.v.dim[a.v.rank - 1], &a.v.mdim[a.v.rank - 1]);
+        a.count = total / 4;
+        return launch(&igconv_elementwise_kernel<4>, "igconv_elementwise_kernel", a, (a.count + 255u) / 256u, h->stream);
+    }
+    a.count = total;
+    return launch(&igconv_elementwise_kernel<1>, "igconv_elementwise_kernel", a, (a.count + 255u) / 256u, h->stream);
+}
+
+}  // namespace
+}  // namespace igc
+
+using namespace igc;
+
+extern "C" {
+
+igcStatus igcActivationForward(igcHandle_t handle, igcActivationMode mode, const void *alpha, igcTensorDescriptor_t xDesc,
+                               const void *x, const void *beta, igcTensorDescriptor_t yDesc, void *y) {
+    if (!handle || !alpha || !beta || !x || !y) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_ACTIVATION_SIGMOID && mode != IGC_ACTIVATION_RELU && mode != IGC_ACTIVATION_TANH) return IGC_STATUS_BAD_PARAM;
+    igcStatus st = check_float_tensor(xDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(yDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (!same_dims(xDesc, yDesc) || (uintptr_t)x % 4 || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    const void *in[1] = {x};
+    return run_elementwise(handle, EW_ACT_FWD, mode, *static_cast<const float *>(alpha), *static_cast<const float *>(beta),
+                           yDesc, y, 1, &xDesc->stride, in);
+}
+
+igcStatus igcActivationBackward(igcHandle_t handle, igcActivationMode mode, const void *alpha, igcTensorDescriptor_t yDesc,
+                                const void *y, igcTensorDescriptor_t dyDesc, const void *dy, igcTensorDescriptor_t xDesc,
+                                const void *x, const void *beta, igcTensorDescriptor_t dxDesc, void *dx) {
+    if (!handle || !alpha || !beta || !y || !dy || !x || !dx) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_ACTIVATION_SIGMOID && mode != IGC_ACTIVATION_RELU && mode != IGC_ACTIVATION_TANH) return IGC_STATUS_BAD_PARAM;
+    igcTensorDescriptor_t ins[3] = {yDesc, dyDesc, xDesc};
+    for (igcTensorDescriptor_t d : ins) {
+        const igcStatus st = check_float_tensor(d, false);
+        if (st != IGC_STATUS_SUCCESS) return st;
+    }
+    const igcStatus st = check_float_tensor(dxDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    for (igcTensorDescriptor_t d : ins)
+        if (!same_dims(d, dxDesc)) return IGC_STATUS_BAD_PARAM;
+    if ((uintptr_t)y % 4 || (uintptr_t)dy % 4 || (uintptr_t)x % 4 || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    long long strides[3][4];
+    for (int t = 0; t < 3; ++t)
+        for (int d = 0; d < 4; ++d) strides[t][d] = ins[t]->stride[d];
+    const void *in[3] = {y, dy, x};
+    return run_elementwise(handle, EW_ACT_BWD, mode, *static_cast<const float *>(alpha), *static_cast<const float *>(beta),
+                           dxDesc, dx, 3, strides, in);
+}
+
+igcStatus igcAddTensor(igcHandle_t handle, const void *alpha, igcTensorDescriptor_t bDesc, const void *b, const void *beta,
+                       igcTensorDescriptor_t yDesc, void *y) {
+    if (!handle || !alpha || !beta || !b || !y) return IGC_STATUS_BAD_PARAM;
+    igcStatus st = check_float_tensor(bDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(yDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    long long bs[1][4];
+    for (int d = 0; d < 4; ++d) {
+        if (bDesc->dim[d] != 1 && bDesc->dim[d] != yDesc->dim[d]) return IGC_STATUS_BAD_PARAM;
+        bs[0][d] = bDesc->dim[d] == 1 ? 0 : bDesc->stride[d];   // a broadcast dimension is not walked
+    }
+    if ((uintptr_t)b % 4 || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    const void *in[1] = {b};
+    return run_elementwise(handle, EW_ADD, 0, *static_cast<const float *>(alpha), *static_cast<const float *>(beta), yDesc, y,
+                           1, bs, in);
+}
+
+igcStatus igcSoftmaxForward(igcHandle_t handle, igcSoftmaxMode mode, const void *alpha, igcTensorDescriptor_t xDesc,
+                            const void *x, const void *beta, igcTensorDescriptor_t yDesc, void *y) {
+    if (!handle || !alpha || !beta || !x || !y) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_SOFTMAX_MODE_INSTANCE && mode != IGC_SOFTMAX_MODE_CHANNEL) return IGC_STATUS_BAD_PARAM;
+    igcStatus st = check_float_tensor(xDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(yDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (!same_dims(xDesc, yDesc) || (uintptr_t)x % 4 || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    SoftmaxArgs a{};
+    a.alpha = *static_cast<const float *>(alpha);
+    a.beta = *static_cast<const float *>(beta);
+    a.y = static_cast<float *>(y);
+    a.x = static_cast<const float *>(x);
+    a.C = (uint32_t)xDesc->dim[1];
+    long long stride[kMaxTensors][4] = {};
+    int dim[4];
+    if (mode == IGC_SOFTMAX_MODE_CHANNEL) {
+        // the locations (n,h,w): the channel dimension is taken out (size 1), the rest ordered by
+        // x's strides so that neighbouring threads read neighbouring addresses
+        for (int d = 0; d < 4; ++d) {
+            dim[d] = d == 1 ? 1 : xDesc->dim[d];
+            stride[0][d] = xDesc->stride[d];   // ordering key: the input's layout
+            stride[1][d] = yDesc->stride[d];
+        }
+        View v = make_view(dim, stride, 2, /*merge=*/true);
+        // (make_view orders by tensor 0 = x here; the kernel wants tensor 0 = y)
+        for (int i = 0; i < v.rank; ++i) std::swap(v.stride[0][i], v.stride[1][i]);
+        a.v = v;
+        a.count = 1;
+        for (int i = 0; i < v.rank; ++i) a.count *= v.dim[i];
+        a.xsC = (uint32_t)xDesc->stride[1];
+        a.ysC = (uint32_t)yDesc->stride[1];
+        return launch(&igconv_softmax_channel_kernel, "igconv_softmax_channel_kernel", a, (a.count + 255u) / 256u, handle->stream);
+    }
+    for (int d = 0; d < 4; ++d) {
+        dim[d] = d == 0 ? 1 : xDesc->dim[d];
+        stride[0][d] = xDesc->stride[d];
+        stride[1][d] = yDesc->stride[d];
+    }
+    View v = make_view(dim, stride, 2, /*merge=*/true);
+    for (int i = 0; i < v.rank; ++i) std::swap(v.stride[0][i], v.stride[1][i]);
+    a.v = v;
+    a.count = 1;
+    for (int i = 0; i < v.rank; ++i) a.count *= v.dim[i];
+    a.xsC = (uint32_t)xDesc->stride[0];
+    a.ysC = (uint32_t)yDesc->stride[0];
+    return launch(&igconv_softmax_instance_kernel, "igconv_softmax_instance_kernel", a, (uint32_t)xDesc->dim[0], handle->stream);
+}
+
+igcStatus igcCreatePoolingDescriptor(igcPoolingDescriptor_t *desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    igcPoolingStruct *p = new (std::nothrow) igcPoolingStruct;
+    if (!p) return IGC_STATUS_ALLOC_FAILED;
+    *desc = p;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcDestroyPoolingDescriptor(igcPoolingDescriptor_t desc) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    delete desc;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcSetPooling2dDescriptor(igcPoolingDescriptor_t desc, igcPoolingMode mode, int windowHeight, int windowWidth,
+                                    int pad_h, int pad_w, int u, int v) {
+    if (!desc) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_POOLING_MAX && mode != IGC_POOLING_AVERAGE) return IGC_STATUS_BAD_PARAM;
+    if (windowHeight < 1 || windowWidth < 1 || u < 1 || v < 1 || pad_h < 0 || pad_w < 0) return IGC_STATUS_BAD_PARAM;
+    if (pad_h >= windowHeight || pad_w >= windowWidth) return IGC_STATUS_BAD_PARAM;   // every window must meet the image
+    desc->mode = mode;
+    desc->win_h = windowHeight; desc->win_w = windowWidth;
+    desc->pad_h = pad_h; desc->pad_w = pad_w; desc->u = u; desc->v = v;
+    desc->set = true;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetPooling2dDescriptor(igcPoolingDescriptor_t desc, igcPoolingMode *mode, int *windowHeight, int *windowWidth,
+                                    int *pad_h, int *pad_w, int *u, int *v) {
+    if (!desc || !mode || !windowHeight || !windowWidth || !pad_h || !pad_w || !u || !v) return IGC_STATUS_BAD_PARAM;
+    if (!desc->set) return IGC_STATUS_NOT_INITIALIZED;
+    *mode = desc->mode;
+    *windowHeight = desc->win_h; *windowWidth = desc->win_w;
+    *pad_h = desc->pad_h; *pad_w = desc->pad_w; *u = desc->u; *v = desc->v;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetPooling2dForwardOutputDim(igcPoolingDescriptor_t poolDesc, igcTensorDescriptor_t xDesc, int *n, int *c,
+                                          int *p, int *q) {
+    if (!poolDesc || !xDesc || !n || !c || !p || !q) return IGC_STATUS_BAD_PARAM;
+    if (!poolDesc->set || !xDesc->set) return IGC_STATUS_NOT_INITIALIZED;
+    const long long nh = (long long)xDesc->dim[2] + 2 * poolDesc->pad_h - poolDesc->win_h;
+    const long long nw = (long long)xDesc->dim[3] + 2 * poolDesc->pad_w - poolDesc->win_w;
+    if (nh < 0 || nw < 0) return IGC_STATUS_BAD_PARAM;
+    *n = xDesc->dim[0];
+    *c = xDesc->dim[1];
+    *p = (int)(nh / poolDesc->u + 1);
+    *q = (int)(nw / poolDesc->v + 1);
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc, const void *alpha, igcTensorDescriptor_t xDesc,
+                            const void *x, const void *beta, igcTensorDescriptor_t yDesc, void *y) {
+    if (!handle || !alpha || !beta || !x || !y || !poolDesc) return IGC_STATUS_BAD_PARAM;
+    if (!poolDesc->set) return IGC_STATUS_NOT_INITIALIZED;
+    igcStatus st = check_float_tensor(xDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(yDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int n, c, p, q;
+    st = igcGetPooling2dForwardOutputDim(poolDesc, xDesc, &n, &c, &p, &q);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (yDesc->dim[0] != n || yDesc->dim[1] != c || yDesc->dim[2] != p || yDesc->dim[3] != q) return IGC_STATUS_BAD_PARAM;
+    if ((uintptr_t)x % 4 || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    PoolArgs a{};
+    long long stride[kMaxTensors][4] = {};
+    for (int d = 0; d < 4; ++d) stride[0][d] = yDesc->stride[d];
+    a.v = make_view(yDesc->dim, stride, 1, /*merge=*/false);
+    a.count = (uint32_t)((long long)n * c * p * q);
+    a.mode = poolDesc->mode;
+    a.H = xDesc->dim[2]; a.W = xDesc->dim[3];
+    a.win_h = poolDesc->win_h; a.win_w = poolDesc->win_w;
+    a.pad_h = poolDesc->pad_h; a.pad_w = poolDesc->pad_w; a.u = poolDesc->u; a.v_ = poolDesc->v;
+    for (int d = 0; d < 4; ++d) a.xs[d] = (uint32_t)xDesc->stride[d];
+    a.alpha = *static_cast<const float *>(alpha);
+    a.beta = *static_cast<const float *>(beta);
+    a.y = static_cast<float *>(y);
+    a.x = static_cast<const float *>(x);
+    return launch(&igconv_pooling_kernel, "igconv_pooling_kernel", a, (a.count + 255u) / 256u, handle->stream);
+}
+
+}  // extern "C"

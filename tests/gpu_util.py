@@ -242,3 +242,65 @@ def run_backward_filter(x, dy, rs, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_
     res = g.out.result()
     g.ws.result()   # guard bands of the workspace
     return res, g.asked
+
+
+# ---------------------------------------------------------------- other functions
+def _desc_for(a):
+    """(device tensor, float descriptor) of a float32 numpy array read through its strides."""
+    dev, strides = to_device_strided(a, "f32")
+    return dev, ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *a.shape, strides)
+
+
+def _handle():
+    h = ig.Handle()
+    h.set_stream(torch.cuda.current_stream().cuda_stream)
+    return h
+
+
+def _output(shape, layout, old):
+    out = GuardedOutput(shape, layout_strides(shape, layout))
+    if old is not None:
+        out.prefill(old=old)
+    else:
+        out.prefill(value=float("nan"))
+    return out, ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, out.strides)
+
+
+def run_activation_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
+    xd, xdesc = _desc_for(x)
+    out, ydesc = _output(x.shape, layout, y_old)
+    ig.check(ig.activation_forward(_handle(), mode, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcActivationForward")
+    return out.result()
+
+
+def run_activation_backward(mode, y, dy, x, alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
+    yd, ydesc = _desc_for(y)
+    dyd, dydesc = _desc_for(dy)
+    xd, xdesc = _desc_for(x)
+    out, dxdesc = _output(x.shape, layout, dx_old)
+    ig.check(ig.activation_backward(_handle(), mode, alpha, ydesc, yd.data_ptr(), dydesc, dyd.data_ptr(), xdesc,
+                                    xd.data_ptr(), beta, dxdesc, out.ptr), "igcActivationBackward")
+    return out.result()
+
+
+def run_add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
+    bd, bdesc = _desc_for(b)
+    out, ydesc = _output(tuple(shape), layout, y_old)
+    ig.check(ig.add_tensor(_handle(), alpha, bdesc, bd.data_ptr(), beta, ydesc, out.ptr), "igcAddTensor")
+    return out.result()
+
+
+def run_softmax_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
+    xd, xdesc = _desc_for(x)
+    out, ydesc = _output(x.shape, layout, y_old)
+    ig.check(ig.softmax_forward(_handle(), mode, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcSoftmaxForward")
+    return out.result()
+
+
+def run_pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
+    xd, xdesc = _desc_for(x)
+    pool = ig.PoolingDescriptor().set(mode, window[0], window[1], pad[0], pad[1], stride[0], stride[1])
+    shape = ig.get_pooling_output_dim(pool, xdesc)
+    out, ydesc = _output(shape, layout, y_old)
+    ig.check(ig.pooling_forward(_handle(), pool, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcPoolingForward")
+    return out.result()

@@ -1,0 +1,122 @@
+"""GPU parity of the library's other functions (activations, tensor addition, softmax,
+pooling) against the CPU oracle, element by element.  Bar: max|gpu - oracle| / max|oracle|
+<= 2e-5 (fp32), the same as for the convolutions."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import workloads as wl
+from oracle import pointwise_oracle as po
+
+TOL = 2e-5
+
+
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import gpu_util
+    return gpu_util
+
+
+def rnd(seed, *shape, lo=-4.0, hi=4.0):
+    return np.random.default_rng(seed).uniform(lo, hi, size=shape).astype(np.float32)
+
+
+def close(got, want):
+    gu = _gpu()
+    assert got.shape == want.shape and np.all(np.isfinite(got))
+    err = gu.rel_err(got, want)
+    assert err <= TOL, err
+
+
+SHAPES = [(2, 3, 5, 7), (1, 1, 1, 1), (3, 16, 12, 12), (2, 5, 9, 64), (4, 130, 3, 3), (1, 2, 1, 1000)]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["sigmoid", "relu", "tanh"])
+@pytest.mark.parametrize("shape", SHAPES, ids=[str(i) for i in range(len(SHAPES))])
+def test_activation_forward(shape, mode):
+    gu = _gpu()
+    x = rnd(1, *shape)
+    close(gu.run_activation_forward(mode, x), po.activation_forward(mode, x))
+    old = rnd(2, *shape)
+    close(gu.run_activation_forward(mode, wl.with_layout(x, "NHWC"), 0.5, -1.5, old, "NHWC"),
+          po.activation_forward(mode, x, 0.5, -1.5, old))
+    # input and output in different layouts; a pitched (sliced) input
+    close(gu.run_activation_forward(mode, wl.with_layout(x, "NHWC"), layout="NCHW"), po.activation_forward(mode, x))
+    wide = rnd(3, shape[0], shape[1], shape[2], shape[3] + 3)
+    close(gu.run_activation_forward(mode, wide[..., 1:-2]), po.activation_forward(mode, np.ascontiguousarray(wide[..., 1:-2])))
+
+
+def test_activation_extremes_and_in_place():
+    gu = _gpu()
+    import torch
+    import paper_1410_0759_amd as ig
+    x = np.array([-200.0, -30.0, -1e-3, 0.0, 1e-3, 30.0, 200.0, 88.0], dtype=np.float32).reshape(1, 2, 2, 2)
+    for mode in (0, 1, 2):
+        close(gu.run_activation_forward(mode, x), po.activation_forward(mode, x))
+    # in place: x and y are the same buffer with the same descriptor
+    x = rnd(4, 2, 8, 6, 10)
+    t = torch.from_numpy(x).cuda()
+    d = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *x.shape, (480, 60, 10, 1))
+    h = ig.Handle()
+    ig.check(ig.activation_forward(h, ig.IGC_ACTIVATION_TANH, 1.0, d, t.data_ptr(), 0.0, d, t.data_ptr()), "in place")
+    torch.cuda.synchronize()
+    close(t.cpu().numpy().astype(np.float64), po.activation_forward(po.TANH, x))
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["sigmoid", "relu", "tanh"])
+def test_activation_backward(mode):
+    gu = _gpu()
+    for shape in SHAPES:
+        x, dy = rnd(5, *shape), rnd(6, *shape)
+        y = po.activation_forward(mode, x).astype(np.float32)
+        close(gu.run_activation_backward(mode, y, dy, x), po.activation_backward(mode, y, dy, x))
+        old = rnd(7, *shape)
+        close(gu.run_activation_backward(mode, wl.with_layout(y, "NHWC"), dy, wl.with_layout(x, "NHWC"), 2.0, 0.5, old, "NHWC"),
+              po.activation_backward(mode, y, dy, x, 2.0, 0.5, old))
+
+
+def test_add_tensor_broadcasting():
+    gu = _gpu()
+    for shape in SHAPES:
+        N, C, H, W = shape
+        old = rnd(8, *shape)
+        for bshape in [(1, C, 1, 1), shape, (N, 1, 1, W), (1, 1, 1, 1), (1, C, H, 1)]:
+            b = rnd(9, *bshape)
+            for layout in ("NCHW", "NHWC"):
+                close(gu.run_add_tensor(b, shape, 2.0, 1.0, old, layout), po.add_tensor(b, shape, 2.0, 1.0, old))
+        close(gu.run_add_tensor(rnd(10, 1, C, 1, 1), shape), po.add_tensor(rnd(10, 1, C, 1, 1), shape))
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["instance", "channel"])
+def test_softmax_forward(mode):
+    gu = _gpu()
+    for shape in SHAPES + [(64, 1000, 1, 1), (2, 21, 33, 17)]:
+        x = rnd(11, *shape, lo=-10, hi=10)
+        want = po.softmax_forward(mode, x)
+        close(gu.run_softmax_forward(mode, x), want)
+        close(gu.run_softmax_forward(mode, wl.with_layout(x, "NHWC"), layout="NHWC"), want)
+        old = rnd(12, *shape)
+        close(gu.run_softmax_forward(mode, x, 0.5, 2.0, old, "NHWC"), po.softmax_forward(mode, x, 0.5, 2.0, old))
+    # stability: huge values, a dominant element
+    x = (rnd(13, 2, 7, 3, 3) + np.float32(3000.0)).astype(np.float32)
+    close(gu.run_softmax_forward(mode, x), po.softmax_forward(mode, x))
+    x = rnd(14, 2, 7, 3, 3)
+    x[:, 2] += 500.0
+    close(gu.run_softmax_forward(mode, x), po.softmax_forward(mode, x))
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["max", "average"])
+def test_pooling_forward(mode):
+    gu = _gpu()
+    cases = [((2, 3, 9, 11), (2, 2), (0, 0), (2, 2)), ((2, 3, 9, 11), (3, 3), (1, 1), (2, 2)),
+             ((1, 5, 13, 13), (3, 2), (1, 0), (1, 3)), ((3, 96, 27, 27), (3, 3), (0, 0), (2, 2)),
+             ((2, 4, 7, 7), (7, 7), (0, 0), (1, 1)), ((2, 4, 8, 8), (5, 5), (2, 2), (4, 4)), ((1, 1, 1, 1), (1, 1), (0, 0), (1, 1))]
+    for shape, win, pad, st in cases:
+        x = rnd(15, *shape) - np.float32(5.0)     # all negative: a zero border must never win the maximum
+        want = po.pooling_forward(mode, x, win, pad, st)
+        close(gu.run_pooling_forward(mode, x, win, pad, st), want)
+        close(gu.run_pooling_forward(mode, wl.with_layout(x, "NHWC"), win, pad, st, layout="NHWC"), want)
+        old = rnd(16, *want.shape)
+        close(gu.run_pooling_forward(mode, x, win, pad, st, 0.5, -1.0, old), po.pooling_forward(mode, x, win, pad, st, 0.5, -1.0, old))

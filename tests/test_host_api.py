@@ -212,6 +212,43 @@ def test_backward_passes_validate_before_any_gpu_call():
                                           ctypes.byref(one), wl_.ptr, fake) == ig.IGC_STATUS_NOT_SUPPORTED
 
 
+def test_other_functions_validate_before_any_gpu_call():
+    """Activations, tensor addition, softmax, pooling: descriptor handling and every rejection
+    path without a GPU."""
+    h = ig.Handle()
+    L = ig.lib()
+    one = ctypes.c_float(1.0)
+    fake = ctypes.c_void_p(256)
+    t = lambda n, c, hh, ww, dt=0, st=None: ig.TensorDescriptor().set(dt, n, c, hh, ww, st or (c * hh * ww, hh * ww, ww, 1))
+    x, y = t(2, 3, 8, 8), t(2, 3, 8, 8)
+    act = lambda xd=x, yd=y, mode=1, xp=fake, yp=fake: L.igcActivationForward(h.ptr, mode, ctypes.byref(one), xd.ptr, xp,
+                                                                             ctypes.byref(one), yd.ptr, yp)
+    assert act(mode=7) == ig.IGC_STATUS_BAD_PARAM and act(yp=None) == ig.IGC_STATUS_BAD_PARAM
+    assert act(yd=t(2, 3, 8, 9)) == ig.IGC_STATUS_BAD_PARAM                     # dimensions differ
+    assert act(yd=t(2, 3, 8, 8, st=(0, 64, 8, 1))) == ig.IGC_STATUS_BAD_PARAM   # aliasing output
+    assert act(xd=t(2, 3, 8, 8, dt=1)) == ig.IGC_STATUS_NOT_SUPPORTED           # bf16
+    assert act(xd=ig.TensorDescriptor()) == ig.IGC_STATUS_NOT_INITIALIZED
+    assert act(xp=ctypes.c_void_p(258)) == ig.IGC_STATUS_BAD_PARAM
+    add = lambda bd: L.igcAddTensor(h.ptr, ctypes.byref(one), bd.ptr, fake, ctypes.byref(one), y.ptr, fake)
+    assert add(t(1, 4, 1, 1)) == ig.IGC_STATUS_BAD_PARAM                        # 4 is neither 1 nor C
+    sm = lambda mode: L.igcSoftmaxForward(h.ptr, mode, ctypes.byref(one), x.ptr, fake, ctypes.byref(one), y.ptr, None)
+    assert sm(1) == ig.IGC_STATUS_BAD_PARAM
+    assert L.igcSoftmaxForward(h.ptr, 5, ctypes.byref(one), x.ptr, fake, ctypes.byref(one), y.ptr, fake) == ig.IGC_STATUS_BAD_PARAM
+    # pooling descriptor: round trip, output size, rejections
+    pool = ig.PoolingDescriptor().set(ig.IGC_POOLING_AVERAGE, 3, 2, 1, 0, 2, 3)
+    assert pool.get() == (ig.IGC_POOLING_AVERAGE, 3, 2, 1, 0, 2, 3)
+    assert ig.get_pooling_output_dim(pool, t(2, 3, 9, 11)) == (2, 3, (9 + 2 - 3) // 2 + 1, (11 - 2) // 3 + 1)
+    for bad in [(0, 0, 2, 0, 0, 1, 1), (0, 2, 2, 2, 0, 1, 1), (0, 2, 2, 0, 0, 0, 1), (9, 2, 2, 0, 0, 1, 1), (0, 2, 2, -1, 0, 1, 1)]:
+        with pytest.raises(ig.IgcError):
+            ig.PoolingDescriptor().set(*bad)
+    with pytest.raises(ig.IgcError):
+        ig.get_pooling_output_dim(ig.PoolingDescriptor().set(0, 5, 5, 0, 0, 1, 1), t(1, 1, 4, 4))    # window larger than the image
+    with pytest.raises(ig.IgcError):
+        ig.get_pooling_output_dim(ig.PoolingDescriptor(), x)                                         # never set
+    pf = lambda yd: L.igcPoolingForward(h.ptr, pool.ptr, ctypes.byref(one), t(2, 3, 9, 11).ptr, fake, ctypes.byref(one), yd.ptr, fake)
+    assert pf(t(2, 3, 5, 5)) == ig.IGC_STATUS_BAD_PARAM                          # y is not (2,3,5,4)
+
+
 def test_setters_reject_bad_values():
     L = ig.lib()
     t = ig.TensorDescriptor()
