@@ -245,7 +245,8 @@ def test_other_functions_validate_before_any_gpu_call():
         ig.get_pooling_output_dim(ig.PoolingDescriptor().set(0, 5, 5, 0, 0, 1, 1), t(1, 1, 4, 4))    # window larger than the image
     with pytest.raises(ig.IgcError):
         ig.get_pooling_output_dim(ig.PoolingDescriptor(), x)                                         # never set
-    pf = lambda yd: L.igcPoolingForward(h.ptr, pool.ptr, ctypes.byref(one), t(2, 3, 9, 11).ptr, fake, ctypes.byref(one), yd.ptr, fake)
+    xp = t(2, 3, 9, 11)
+    pf = lambda yd: L.igcPoolingForward(h.ptr, pool.ptr, ctypes.byref(one), xp.ptr, fake, ctypes.byref(one), yd.ptr, fake)
     assert pf(t(2, 3, 5, 5)) == ig.IGC_STATUS_BAD_PARAM                          # y is not (2,3,5,4)
 
 
