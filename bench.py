@@ -134,6 +134,95 @@ def run_backward(index, steps, warmup, oracle_seconds):
     return out
 
 
+def run_other_functions(steps, warmup):
+    """The bandwidth-bound functions (activations, bias addition, softmax, pooling) on
+    layer-sized float tensors: time per call, algorithmic bytes (each tensor once) per second
+    against the 8 TB/s HBM peak, parity against the oracle on the first image(s)."""
+    import numpy as np
+    import torch
+    import paper_1410_0759_amd as ig
+    from oracle import pointwise_oracle as po
+    from tests import gpu_util as gu
+
+    HBM_PEAK = 8000.0   # GB/s
+    rng = np.random.default_rng(14100759 * 10 + 900)
+    h = ig.Handle()
+    h.set_stream(torch.cuda.current_stream().cuda_stream)
+    out = []
+
+    def timed(call):
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def dev(a):
+        t = torch.from_numpy(a).cuda()
+        n, c, hh, ww = a.shape
+        return t, ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, n, c, hh, ww, (c * hh * ww, hh * ww, ww, 1))
+
+    def record(name, shape, nbytes, ms, err):
+        out.append({"function": name, "shape": list(shape), "ms": ms, "algorithmic_bytes": nbytes,
+                    "gb_per_s": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK, "rel_err": err})
+
+    shape = (128, 64, 56, 56)
+    x = rng.uniform(-3, 3, size=shape).astype(np.float32)
+    xt, xd = dev(x)
+    yt, yd = dev(np.zeros(shape, np.float32))
+    nb = x.nbytes
+    for mode, nm in ((ig.IGC_ACTIVATION_RELU, "relu"), (ig.IGC_ACTIVATION_TANH, "tanh")):
+        call = lambda: ig.check(ig.activation_forward(h, mode, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), nm)
+        ms = timed(call)
+        err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.activation_forward(mode, x[:2]))
+        record("activation forward " + nm, shape, 2 * nb, ms, err)
+    dyt, dyd = dev(rng.uniform(-1, 1, size=shape).astype(np.float32))
+    dxt, dxd = dev(np.zeros(shape, np.float32))
+    call = lambda: ig.check(ig.activation_backward(h, ig.IGC_ACTIVATION_TANH, 1.0, yd, yt.data_ptr(), dyd, dyt.data_ptr(),
+                                                   xd, xt.data_ptr(), 0.0, dxd, dxt.data_ptr()), "tanh backward")
+    ms = timed(call)
+    err = gu.rel_err(dxt[:2].cpu().numpy().astype(np.float64),
+                     po.activation_backward(po.TANH, yt[:2].cpu().numpy(), dyt[:2].cpu().numpy(), x[:2]))
+    record("activation backward tanh", shape, 3 * nb, ms, err)
+    bias = rng.uniform(-1, 1, size=(1, 64, 1, 1)).astype(np.float32)
+    bt = torch.from_numpy(bias).cuda()
+    bd = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, 1, 64, 1, 1, (64, 1, 1, 1))
+    yt.copy_(xt)
+    ig.check(ig.add_tensor(h, 1.0, bd, bt.data_ptr(), 1.0, yd, yt.data_ptr()), "bias")
+    err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.add_tensor(bias, (2,) + shape[1:], 1.0, 1.0, x[:2]))
+    ms = timed(lambda: ig.check(ig.add_tensor(h, 1.0, bd, bt.data_ptr(), 1.0, yd, yt.data_ptr()), "bias"))
+    record("bias addition in place (1,C,1,1)", shape, 2 * nb, ms, err)
+    del xt, yt, dyt, dxt
+
+    for mode, nm, shape in ((ig.IGC_SOFTMAX_MODE_CHANNEL, "softmax per location", (32, 21, 128, 128)),
+                            (ig.IGC_SOFTMAX_MODE_INSTANCE, "softmax per image", (256, 1000, 1, 1))):
+        x = rng.uniform(-8, 8, size=shape).astype(np.float32)
+        xt, xd = dev(x)
+        yt, yd = dev(np.zeros(shape, np.float32))
+        ms = timed(lambda: ig.check(ig.softmax_forward(h, mode, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), nm))
+        err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.softmax_forward(mode, x[:2]))
+        record(nm, shape, 2 * x.nbytes, ms, err)
+        del xt, yt
+
+    shape = (128, 96, 55, 55)
+    x = rng.uniform(-3, 3, size=shape).astype(np.float32)
+    xt, xd = dev(x)
+    for mode, nm in ((ig.IGC_POOLING_MAX, "max"), (ig.IGC_POOLING_AVERAGE, "average")):
+        pool = ig.PoolingDescriptor().set(mode, 3, 3, 0, 0, 2, 2)
+        oshape = ig.get_pooling_output_dim(pool, xd)
+        yt, yd = dev(np.zeros(oshape, np.float32))
+        ms = timed(lambda: ig.check(ig.pooling_forward(h, pool, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), nm))
+        err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.pooling_forward(mode, x[:2], (3, 3), (0, 0), (2, 2)))
+        record("pooling 3x3 stride 2 " + nm, shape, x.nbytes + yt.numel() * 4, ms, err)
+        del yt
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,6 +235,8 @@ def main():
     ap.add_argument("--no-table2", action="store_true", help="skip the paper's Table-2 layer collection")
     ap.add_argument("--no-backward", action="store_true", help="skip the backward-data / backward-filter section")
     ap.add_argument("--backward-only", type=int, default=0, help="time only the backward passes of this workload (1-5)")
+    ap.add_argument("--no-other", action="store_true", help="skip the section on activations, softmax, pooling, bias addition")
+    ap.add_argument("--other-only", action="store_true", help="time only that section")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -175,6 +266,10 @@ def main():
         print(json.dumps(run_backward(args.backward_only, args.steps, args.warmup, 1.0)))
         return
 
+    if args.other_only:
+        print(json.dumps(run_other_functions(max(20, args.steps // 5), max(10, args.warmup // 5))))
+        return
+
     head = run_config(args.config, args.steps, args.warmup, args.oracle_seconds, args.kernel)
     per_config = []
     if not args.only:
@@ -199,6 +294,10 @@ def main():
     if not args.only and not args.no_backward:
         for i in (2, 3, 4, 5):
             backward.append(run_backward(i, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0))
+
+    other = []
+    if not args.only and not args.no_other:
+        other = run_other_functions(max(20, args.steps // 5), max(10, args.warmup // 5))
 
     # Mini-batch sweep over the Table-2 layers (the paper reports 86 % of its maximum
     # throughput at a mini-batch of 16): average TFLOP/s over the five layers per batch size.
@@ -241,6 +340,7 @@ def main():
         "table2_layers": table2,
         "table2_batch_sweep": batch_sweep,
         "backward": backward,
+        "other_functions": other,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
                          "on GTX 980, fp32, its own Table-2 layers",
     }

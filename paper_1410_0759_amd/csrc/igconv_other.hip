@@ -273,6 +273,7 @@ struct PoolArgs {
     uint32_t count;
     int mode, H, W, win_h, win_w, pad_h, pad_w, u, v_;
     uint32_t xs[4];
+    uint32_t x_bytes, y_bytes;   // extents, the limits of the buffer descriptors
     float alpha, beta;
     float *y;
     const float *x;
@@ -296,24 +297,29 @@ __global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
         yoff += i * a.v.stride[0][d];
     }
     const int h0 = (int)coord[2] * a.u - a.pad_h, w0 = (int)coord[3] * a.v_ - a.pad_w;
-    const float *x = a.x + coord[0] * a.xs[0] + coord[1] * a.xs[1];
+    // Both tensors are accessed through buffer descriptors of their extents: an offset outside
+    // a tensor reads as zero / is not written, it cannot touch foreign memory.
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.y_bytes, 0x00020000u);
+    const uint32_t plane = coord[0] * a.xs[0] + coord[1] * a.xs[1];
+    // the part of the window that lies inside the image (never empty: pad < window); inside
+    // it h0 + r and w0 + c are non-negative
+    const int r0 = h0 < 0 ? -h0 : 0, r1 = min(a.win_h, a.H - h0);
+    const int c0 = w0 < 0 ? -w0 : 0, c1 = min(a.win_w, a.W - w0);
     float m = -INFINITY, s = 0.f;
-    int cnt = 0;
-    for (int r = 0; r < a.win_h; ++r) {
-        const int h = h0 + r;
-        if (h < 0 || h >= a.H) continue;
-        for (int c = 0; c < a.win_w; ++c) {
-            const int w = w0 + c;
-            if (w < 0 || w >= a.W) continue;
-            const float val = x[(uint32_t)h * a.xs[2] + (uint32_t)w * a.xs[3]];
+    for (int r = r0; r < r1; ++r) {
+        const uint32_t row = plane + (uint32_t)(h0 + r) * a.xs[2];
+        for (int c = c0; c < c1; ++c) {
+            const uint32_t e = row + (uint32_t)(w0 + c) * a.xs[3];
+            const float val = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, e * 4u, 0, 0));
             m = fmaxf(m, val);
             s += val;
-            ++cnt;
         }
     }
+    const int cnt = (r1 - r0) * (c1 - c0);
     float r = a.alpha * (a.mode == IGC_POOLING_MAX ? m : s / (float)cnt);
-    if (a.beta != 0.f) r += a.beta * a.y[yoff];
-    a.y[yoff] = r;
+    if (a.beta != 0.f) r += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, yoff * 4u, 0, 0));
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), ybuf, yoff * 4u, 0, 0);
 }
 
 // ---- host side ---------------------------------------------------------------------------
@@ -559,6 +565,8 @@ igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc,
     a.win_h = poolDesc->win_h; a.win_w = poolDesc->win_w;
     a.pad_h = poolDesc->pad_h; a.pad_w = poolDesc->pad_w; a.u = poolDesc->u; a.v_ = poolDesc->v;
     for (int d = 0; d < 4; ++d) a.xs[d] = (uint32_t)xDesc->stride[d];
+    a.x_bytes = (uint32_t)(extent(xDesc->dim, xDesc->stride) * 4);
+    a.y_bytes = (uint32_t)(extent(yDesc->dim, yDesc->stride) * 4);
     a.alpha = *static_cast<const float *>(alpha);
     a.beta = *static_cast<const float *>(beta);
     a.y = static_cast<float *>(y);
