@@ -248,6 +248,24 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha,
                                        const void *beta,
                                        igcFilterDescriptor_t dwDesc, void *dw);
 
+/* ---- forward convolution with the bias addition and the activation fused into its
+ * epilogue (Section 2.2 lists both as separate functions; run separately they would each
+ * read and write y once more) ---------------------------------------------------------
+ *
+ *   y[n,k,p,q] = f( alpha * conv(x,w)[n,k,p,q] + beta * y[n,k,p,q] + bias[k] )
+ *
+ * Everything as for igcConvolutionForward, plus: bias (device, read) is K packed floats or
+ * NULL for none; activation is an igcActivationMode or IGC_ACTIVATION_IDENTITY (-1) for
+ * none.  BAD_PARAM for any other activation value or a misaligned bias pointer. */
+#define IGC_ACTIVATION_IDENTITY (-1)
+igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *alpha,
+                                              igcTensorDescriptor_t xDesc, const void *x,
+                                              igcFilterDescriptor_t wDesc, const void *w,
+                                              igcConvolutionDescriptor_t convDesc,
+                                              void *workSpace, size_t workSpaceSizeInBytes,
+                                              const void *beta, const void *bias, int activation,
+                                              igcTensorDescriptor_t yDesc, void *y);
+
 /* ---- other functions (Section 2.2: activations, softmax, pooling, tensor addition) ----
  * Bandwidth-bound kernels on float tensors laid out by their descriptors (any non-negative
  * strides for inputs; outputs non-aliasing).  All of them blend like the convolutions:

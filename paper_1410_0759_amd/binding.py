@@ -18,7 +18,7 @@ __all__ = [
     "get_backward_data_workspace_size", "convolution_backward_data",
     "get_backward_filter_workspace_size", "convolution_backward_filter",
     "PoolingDescriptor", "get_pooling_output_dim", "activation_forward", "activation_backward", "add_tensor",
-    "softmax_forward", "pooling_forward",
+    "softmax_forward", "pooling_forward", "convolution_bias_activation_forward", "IGC_ACTIVATION_IDENTITY",
     "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
@@ -32,6 +32,7 @@ LIB_PATH = os.path.join(HERE, "libigconv.so")
 IGC_DATA_FLOAT, IGC_DATA_BFLOAT16 = 0, 1
 IGC_CONVOLUTION, IGC_CROSS_CORRELATION = 0, 1
 IGC_ACTIVATION_SIGMOID, IGC_ACTIVATION_RELU, IGC_ACTIVATION_TANH = 0, 1, 2
+IGC_ACTIVATION_IDENTITY = -1
 IGC_SOFTMAX_MODE_INSTANCE, IGC_SOFTMAX_MODE_CHANNEL = 0, 1
 IGC_POOLING_MAX, IGC_POOLING_AVERAGE = 0, 1
 
@@ -82,6 +83,7 @@ DECLARED_SYMBOLS = {
     "igcGetPooling2dDescriptor": (_i, [_vp] + [_P(_i)] * 7),
     "igcGetPooling2dForwardOutputDim": (_i, [_vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
     "igcPoolingForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcConvolutionBiasActivationForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _i, _vp, _vp]),
     "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
     "igcGetKernelCount": (_i, []),
     "igcGetKernelName": (ctypes.c_char_p, [_i]),
@@ -320,6 +322,15 @@ def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, con
     return lib().igcConvolutionBackwardFilter(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
+
+
+def convolution_bias_activation_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, bias_ptr, activation,
+                                        ydesc, y_ptr):
+    """igcConvolutionBiasActivationForward; bias_ptr 0 for no bias, activation -1 for none."""
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcConvolutionBiasActivationForward(
+        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr, None, 0, ctypes.byref(b),
+        _vp(bias_ptr), activation, ydesc.ptr, _vp(y_ptr))
 
 
 def kernel_names():

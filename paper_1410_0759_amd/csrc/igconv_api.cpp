@@ -737,9 +737,18 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha, igcTensor
                                 igcFilterDescriptor_t wDesc, const void *w, igcConvolutionDescriptor_t convDesc,
                                 void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
                                 igcTensorDescriptor_t yDesc, void *y) {
+    return igcConvolutionBiasActivationForward(handle, alpha, xDesc, x, wDesc, w, convDesc, workSpace, workSpaceSizeInBytes,
+                                               beta, nullptr, IGC_ACTIVATION_IDENTITY, yDesc, y);
+}
+
+igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *alpha, igcTensorDescriptor_t xDesc, const void *x,
+                                              igcFilterDescriptor_t wDesc, const void *w, igcConvolutionDescriptor_t convDesc,
+                                              void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
+                                              const void *bias, int activation, igcTensorDescriptor_t yDesc, void *y) {
     (void)workSpace;
     (void)workSpaceSizeInBytes;
     if (!handle || !alpha || !beta || !x || !w || !y) return IGC_STATUS_BAD_PARAM;
+    if (activation < IGC_ACTIVATION_IDENTITY || activation > IGC_ACTIVATION_TANH || (uintptr_t)bias % 4) return IGC_STATUS_BAD_PARAM;
     Problem pr;
     igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
     if (st != IGC_STATUS_SUCCESS) return st;
@@ -756,6 +765,8 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha, igcTensor
     pr.kp.y = y;
     pr.kp.alpha = *static_cast<const float *>(alpha);
     pr.kp.beta = *static_cast<const float *>(beta);
+    pr.kp.bias = static_cast<const float *>(bias);
+    pr.kp.act = activation;
     const int err = kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream);
     return err == 0 ? IGC_STATUS_SUCCESS : IGC_STATUS_EXECUTION_FAILED;
 }

@@ -84,6 +84,27 @@ template <bool SWAP, int MB, int NB, bool LINEAR = false>
 __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_buffer_rsrc_t ybuf,
                                            f32x16 (&acc)[MB][NB], int krow0, int col0, int half, int l32) {
     const bool use_beta = p.beta != 0.f;
+    // Fused tail (Section 2.2's bias addition and activation, applied while the result is
+    // still in registers): out = f(alpha*acc + beta*y + bias[k]).  The 32 bias values of a
+    // row block are fetched one per lane; where rows are spread over registers, the value of
+    // a register's row comes from the lane that holds it.
+    const bool fused = p.bias != nullptr || p.act >= 0;   // wavefront-uniform
+    float bvec[MB];
+    {
+        const __amdgpu_buffer_rsrc_t bbuf = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(p.bias), 0, p.bias != nullptr ? (uint32_t)p.K * 4u : 0u, kBufferWord3);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            bvec[mb] = fused ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bbuf, (uint32_t)(krow0 + mb * 32 + l32) * 4u, 0, 0))
+                             : 0.f;   // (rows beyond K, or no bias at all: reads as zero)
+    }
+    auto row_bias = [&](int mb, int v) -> float {   // bias of the row register v of block row mb holds in this lane
+        if (!fused) return 0.f;
+        const int r0 = 8 * (v / 4) + (v % 4);
+        const float b0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bvec[mb]), r0));
+        const float b1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bvec[mb]), r0 + 4));
+        return half ? b1 : b0;
+    };
     auto pixel_offset = [&](uint32_t j) -> uint32_t {  // element offset of column j = (n,p,q) in y
         if constexpr (LINEAR) return j * (uint32_t)p.ysQ;   // columns a fixed distance apart
         const uint32_t n = magic_div(j, p.mPQ);
@@ -92,11 +113,17 @@ __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_b
         const uint32_t qq = rem - pp * (uint32_t)p.Q;
         return n * (uint32_t)p.ysN + pp * (uint32_t)p.ysP + qq * (uint32_t)p.ysQ;
     };
-    auto emit = [&](float a, uint32_t voff, uint32_t soff) {
+    auto emit = [&](float a, uint32_t voff, uint32_t soff, float b) {
         float out = p.alpha * a;
         if (use_beta) {
             const float old = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, voff, soff, 0));
             out += p.beta * old;
+        }
+        if (fused) {
+            out += b;
+            if (p.act == 0) out = 1.f / (1.f + __expf(-out));                   // sigmoid
+            else if (p.act == 1) out = fmaxf(out, 0.f);                         // rectified linear
+            else if (p.act == 2) out = 1.f - 2.f / (__expf(2.f * out) + 1.f);   // tanh
         }
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, voff, soff, 0);
     };
@@ -114,14 +141,14 @@ __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_b
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        emit(acc[mb][nb][v], vo, (uint32_t)(krow0 + mb * 32 + 8 * (v / 4) + (v % 4)) * (uint32_t)p.ysK * 4u);
+                        emit(acc[mb][nb][v], vo, (uint32_t)(krow0 + mb * 32 + 8 * (v / 4) + (v % 4)) * (uint32_t)p.ysK * 4u, row_bias(mb, v));
             } else {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int k = krow0 + mb * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                        emit(acc[mb][nb][v], pv && k < p.K ? (poff + (uint32_t)k * (uint32_t)p.ysK) * 4u : kOutOfRange, 0u);
+                        emit(acc[mb][nb][v], pv && k < p.K ? (poff + (uint32_t)k * (uint32_t)p.ysK) * 4u : kOutOfRange, 0u, row_bias(mb, v));
                     }
             }
         }
@@ -144,7 +171,7 @@ __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_b
                 for (int v = 0; v < 16; ++v) {
                     const int r0 = 8 * (v / 4) + (v % 4);
                     const uint32_t d0 = __builtin_amdgcn_readlane(pd, r0), d1 = __builtin_amdgcn_readlane(pd, r0 + 4);
-                    emit(acc[mb][nb][v], kv ? koff + (half ? d1 : d0) : kOutOfRange, 0u);
+                    emit(acc[mb][nb][v], kv ? koff + (half ? d1 : d0) : kOutOfRange, 0u, bvec[mb]);
                 }
             }
         }

@@ -28,6 +28,8 @@ struct ConvKernelParams {
     int32_t xsN, xsC, xsH, xsW;  // element strides of x
     int32_t ysN, ysK, ysP, ysQ;  // element strides of y
     float alpha, beta;
+    const float *bias = nullptr;   // K floats added per output feature map before the activation, or null
+    int32_t act = -1;    // activation applied last: 0 sigmoid, 1 rectified linear, 2 tanh, -1 none
     int32_t tilesM, tilesN;
     int32_t tilesPerXcd;  // ceil(tilesM * tilesN / 8): tiles are dealt to the 8 XCDs in contiguous ranges
     int32_t wgsPerXcd;    // workgroups launched per XCD (grid = 8 * wgsPerXcd); each takes every wgsPerXcd-th tile of its range

@@ -304,3 +304,45 @@ def test_table2_layer_sampled(layer):
         err = gu.rel_err(got[sl], want)
         print("workload", w_.name, "kernel", plan.kernelId, "images", sl, "rel err", err, flush=True)
         assert err <= gu.TOL["f32"]
+
+
+# ------------------------------------------------------------------ fused epilogue
+def test_fused_bias_and_activation():
+    """y = f(alpha*conv + beta*y + bias[k]) in one kernel, against the composition of the
+    oracles (convolution, tensor addition with broadcasting, activation); every epilogue
+    variant: pixels or channels along the lanes, full and ragged tiles, fp32 and bf16 kernels."""
+    from oracle import pointwise_oracle as po
+    gu = _gpu()
+    cases = [
+        # N, C, H, W, K, R, S, pad, stride, dtype, x layout, y layout
+        (2, 5, 15, 17, 150, 3, 3, (1, 1), (1, 1), "f32", "NCHW", "NCHW"),
+        (2, 8, 15, 17, 130, 3, 3, (1, 1), (1, 1), "f32", "NCHW", "NHWC"),
+        (4, 16, 16, 16, 64, 3, 3, (1, 1), (1, 1), "f32", "NCHW", "NCHW"),     # full tiles: the unmasked store path
+        (2, 3, 31, 31, 96, 11, 11, (0, 0), (4, 4), "f32", "NCHW", "NCHW"),
+        (3, 48, 13, 11, 70, 3, 3, (1, 1), (1, 1), "bf16", "NHWC", "NHWC"),    # channel-vector kernel
+        (3, 32, 13, 11, 40, 3, 3, (1, 1), (1, 1), "bf16", "NHWC", "NCHW"),
+        (2, 7, 9, 9, 33, 5, 5, (2, 2), (2, 2), "bf16", "NCHW", "NCHW"),
+    ]
+    for i, (N, C, H, W, K, R, S, pad, stride, dtype, xl, yl) in enumerate(cases):
+        x, w = wl.random_problem(50 + i, N, C, H, W, K, R, S, x_layout=xl, dtype=dtype)
+        bias = np.random.default_rng(60 + i).uniform(-1, 1, size=K).astype(np.float32)
+        raw = oc.conv_forward(x, w, pad=pad, stride=stride, mode=1)
+        y0 = np.random.default_rng(70 + i).uniform(-1, 1, size=raw.shape).astype(np.float32)
+        for act, alpha, beta, with_bias in [(1, 1.0, 0.0, True), (0, 0.5, -1.5, True), (2, 2.0, 1.0, True),
+                                            (-1, 1.0, 0.0, True), (1, 1.0, 0.0, False)]:
+            print("fused", cases[i], act, alpha, beta, with_bias, flush=True)
+            g = gu.GpuConv(x, w, pad, stride, 1, dtype=dtype, y_layout=yl)
+            if beta != 0.0:
+                g.prefill(y0=y0)
+            else:
+                g.prefill(value=float("nan"))
+            g.launch_fused(alpha, beta, bias if with_bias else None, act)
+            got = g.result()
+            pre = alpha * raw + (beta * y0.astype(np.float64) if beta != 0.0 else 0.0)
+            if with_bias:
+                pre = pre + po.add_tensor(bias.reshape(1, K, 1, 1), raw.shape)
+            want = pre if act < 0 else po.activation_forward(act, pre.astype(np.float32))
+            # (the activation oracle takes float32 inputs: compare with the matching slack)
+            assert np.all(np.isfinite(got))
+            err = gu.rel_err(got, want)
+            assert err <= gu.TOL[dtype], (cases[i], act, err)
