@@ -209,6 +209,36 @@ def run_other_functions(steps, warmup):
         record(nm, shape, 2 * x.nbytes, ms, err)
         del xt, yt
 
+    # bias addition and rectifier fused into the convolution's epilogue, against the three calls
+    # one after the other, on the mid-layer workload
+    import workloads as wl
+    from oracle import conv_oracle as oc
+    w_ = wl.by_index(3)
+    cx, cw, _ = wl.make_inputs(w_)
+    g = gu.GpuConv(cx, cw, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, dtype=w_.dtype, y_layout=w_.y_layout, handle=h)
+    cb = rng.uniform(-1, 1, size=w_.K).astype(np.float32)
+    g.prefill(value=float("nan"))
+    g.launch_fused(1.0, 0.0, cb, ig.IGC_ACTIVATION_RELU)
+    n = 2
+    want = po.activation_forward(po.RELU, (oc.conv_forward(cx[:n], cw, pad=(w_.pad_h, w_.pad_w), stride=(w_.u, w_.v), mode=w_.mode)
+                                           + po.add_tensor(cb.reshape(1, -1, 1, 1), (n, w_.K, w_.P, w_.Q))).astype(np.float32))
+    err = gu.rel_err(g.result()[:n], want)
+    bdev = g.bias_dev
+    fused_call = lambda: ig.check(ig.convolution_bias_activation_forward(
+        h, 1.0, g.xdesc, g.x_dev.data_ptr(), g.wdesc, g.w_dev.data_ptr(), g.conv, 0.0, bdev.data_ptr(),
+        ig.IGC_ACTIVATION_RELU, g.ydesc, g.y_ptr), "fused")
+    bdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, 1, w_.K, 1, 1, (w_.K, 1, 1, 1))
+
+    def separate_calls():
+        g.launch(1.0, 0.0)
+        ig.check(ig.add_tensor(h, 1.0, bdesc, bdev.data_ptr(), 1.0, g.ydesc, g.y_ptr), "bias")
+        ig.check(ig.activation_forward(h, ig.IGC_ACTIVATION_RELU, 1.0, g.ydesc, g.y_ptr, 0.0, g.ydesc, g.y_ptr), "relu")
+
+    ms_fused, ms_sep = timed(fused_call), timed(separate_calls)
+    out.append({"function": "convolution + bias + rectifier, fused epilogue (" + w_.name + ")", "ms": ms_fused,
+                "ms_as_three_calls": ms_sep, "tflops": w_.flops / ms_fused / 1e9, "rel_err": err})
+    del g
+
     shape = (128, 96, 55, 55)
     x = rng.uniform(-3, 3, size=shape).astype(np.float32)
     xt, xd = dev(x)

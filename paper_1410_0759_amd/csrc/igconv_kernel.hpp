@@ -80,24 +80,30 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) {
 // column (n,p,q) of this wavefront's blocks.  Whatever does not depend on the lane goes
 // into the store's scalar offset where that is possible; a wavefront whose blocks lie
 // fully inside K x NPQ needs no per-element test.  LINEAR: column j sits at j*ysQ.
+// The 32 bias values of each row block of a wavefront's tile, one per lane (zero when no bias
+// is given or the row lies beyond K).  Loaded well before the epilogue that uses them, so
+// that the epilogue does not have to wait behind the loads already in flight for the next tile.
+template <int MB>
+__device__ __forceinline__ void load_bias(const ConvKernelParams &p, int krow0, int l32, float (&bvec)[MB]) {
+    const __amdgpu_buffer_rsrc_t bbuf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(p.bias), 0, p.bias != nullptr ? (uint32_t)p.K * 4u : 0u, kBufferWord3);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+        bvec[mb] = p.bias != nullptr ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                            bbuf, (uint32_t)(krow0 + mb * 32 + l32) * 4u, 0, 0))
+                                     : 0.f;
+}
+
 template <bool SWAP, int MB, int NB, bool LINEAR = false>
 __device__ __forceinline__ void store_tile(const ConvKernelParams &p, __amdgpu_buffer_rsrc_t ybuf,
-                                           f32x16 (&acc)[MB][NB], int krow0, int col0, int half, int l32) {
+                                           f32x16 (&acc)[MB][NB], const float (&bvec)[MB], int krow0, int col0, int half,
+                                           int l32) {
     const bool use_beta = p.beta != 0.f;
     // Fused tail (Section 2.2's bias addition and activation, applied while the result is
-    // still in registers): out = f(alpha*acc + beta*y + bias[k]).  The 32 bias values of a
-    // row block are fetched one per lane; where rows are spread over registers, the value of
-    // a register's row comes from the lane that holds it.
+    // still in registers): out = f(alpha*acc + beta*y + bias[k]).  bvec holds the 32 bias
+    // values of each row block, one per lane; where rows are spread over registers, the value
+    // of a register's row comes from the lane that holds it.
     const bool fused = p.bias != nullptr || p.act >= 0;   // wavefront-uniform
-    float bvec[MB];
-    {
-        const __amdgpu_buffer_rsrc_t bbuf = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(p.bias), 0, p.bias != nullptr ? (uint32_t)p.K * 4u : 0u, kBufferWord3);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-            bvec[mb] = fused ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(bbuf, (uint32_t)(krow0 + mb * 32 + l32) * 4u, 0, 0))
-                             : 0.f;   // (rows beyond K, or no bias at all: reads as zero)
-    }
     auto row_bias = [&](int mb, int v) -> float {   // bias of the row register v of block row mb holds in this lane
         if (!fused) return 0.f;
         const int r0 = 8 * (v / 4) + (v % 4);
@@ -827,6 +833,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         lds_barrier();
     }
     setup_tile(tile_number(0));
+    float bias_cur[MB], bias_next[MB];
+    load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bias_cur);
     // Prologue: request the first two tiles back to back, then write the first to LDS stage
     // 0 as it arrives (the second stays in flight, it is written during the first step).
     static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, 0, t_begin); });
@@ -849,6 +857,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         const int out_m0 = m0, out_n0 = n0, out_split = split, out_tap = sc_tapidx;
         const int next = tile_number(it);
         setup_tile(next);
+        load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bias_next);
         step(std::integral_constant<int, 0>{}, t_begin);
         step(std::integral_constant<int, 1>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
@@ -856,8 +865,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + (WGT ? (uint32_t)out_tap * 4u : 0u);
         const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
             static_cast<char *>(p.y) + ybase, 0, p.y_bytes - (WGT ? (uint32_t)out_tap * 4u : 0u), kBufferWord3);
-        store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
+        store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, bias_cur, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
         if (next >= tiles_total) break;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) bias_cur[mb] = bias_next[mb];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll

@@ -223,6 +223,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    float bvec[MB];   // bias of the wavefront's rows, fetched long before the epilogue
+    load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bvec);
     constexpr int G = TAPS, MPG = MB * NB, NM = G * MPG, SB = NM - MPG;
     u32x4 fragA[2][MB], fragB[2][NB];
     // (wm*TM + mb*32 and wn*TN + nb*32 are multiples of 16, so the half swap depends on l32 only)
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         step(std::integral_constant<int, 1>{}, t + 1);
     }
 
-    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, m0 + wm * Cfg::TM, n0 + wn * Cfg::TN, half, l32);
+    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bvec, m0 + wm * Cfg::TM, n0 + wn * Cfg::TN, half, l32);
 }
 
 }  // namespace igc
