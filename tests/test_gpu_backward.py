@@ -184,3 +184,40 @@ def test_backward_at_workload_size(index):
     tol = 1e-5 if w_.dtype == "f32" else 1e-3
     assert abs(lhs - float(np.sum(dx * x.astype(np.float64)))) <= tol * scale
     assert abs(lhs - float(np.sum(dw * w.astype(np.float64)))) <= tol * scale
+
+
+# ------------------------------------------------------------------ seeded random problems, all three passes
+def _random_problem(rng):
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    if rng.random() < 0.3:
+        R, S = 3, 3
+    u, v = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    pad = (int(rng.integers(0, R)), int(rng.integers(0, S)))
+    H, W = int(rng.integers(R, R + 14)), int(rng.integers(S, S + 14))
+    N, C, K = int(rng.integers(1, 4)), int(rng.choice([1, 3, 4, 16, 24, 33, 64])), int(rng.choice([1, 5, 8, 32, 70, 130]))
+    return N, C, H, W, K, R, S, pad, (u, v)
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_problems_forward_and_both_backward_passes(chunk):
+    """40 seeded random problems (filter 1..5, stride 1..3, any pad below the filter size, odd
+    channel counts, both layouts, both modes, both data types): every pass against its oracle."""
+    gu = _gpu()
+    rng = np.random.default_rng(4242 + chunk)
+    for i in range(10):
+        N, C, H, W, K, R, S, pad, stride = prob = _random_problem(rng)
+        dtype = "bf16" if rng.random() < 0.4 else "f32"
+        mode = int(rng.integers(0, 2))
+        xl, yl = ("NHWC" if rng.random() < 0.5 else "NCHW"), ("NHWC" if rng.random() < 0.5 else "NCHW")
+        P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
+        x = wl.with_layout(_rnd(100 * chunk + i, (N, C, H, W), dtype), xl)
+        w = _rnd(100 * chunk + i + 50, (K, C, R, S), dtype)
+        dy = wl.with_layout(_rnd(100 * chunk + i + 70, (N, K, P, Q), dtype), yl)
+        print("random problem", prob, dtype, mode, xl, yl, flush=True)
+        y, _ = gu.run(x, w, pad, stride, mode, dtype=dtype, y_layout=yl)
+        assert gu.rel_err(y, oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)) <= gu.TOL[dtype]
+        dx = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, dtype=dtype, dx_layout=xl)
+        want = oc.conv_backward_data(dy, w, (H, W), pad=pad, stride=stride, mode=mode)
+        assert np.max(np.abs(dx - want)) <= gu.TOL[dtype] * max(np.max(np.abs(want)), 1e-30)
+        dw, _ = gu.run_backward_filter(x, dy, (R, S), pad, stride, mode, dtype=dtype)
+        assert gu.rel_err(dw, oc.conv_backward_filter(x, dy, (R, S), pad=pad, stride=stride, mode=mode)) <= gu.TOL[dtype]
