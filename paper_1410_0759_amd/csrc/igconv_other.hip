@@ -279,6 +279,9 @@ struct PoolArgs {
     const float *x;
 };
 
+// WH, WW: the window size when it is known at compile time (loops unrolled, loads issued back
+// to back), 0 to take it from the arguments.
+template <int WH, int WW>
 __global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
     const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= a.count) return;
@@ -304,16 +307,32 @@ __global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
     const uint32_t plane = coord[0] * a.xs[0] + coord[1] * a.xs[1];
     // the part of the window that lies inside the image (never empty: pad < window); inside
     // it h0 + r and w0 + c are non-negative
-    const int r0 = h0 < 0 ? -h0 : 0, r1 = min(a.win_h, a.H - h0);
-    const int c0 = w0 < 0 ? -w0 : 0, c1 = min(a.win_w, a.W - w0);
+    const int win_h = WH ? WH : a.win_h, win_w = WW ? WW : a.win_w;
+    const int r0 = h0 < 0 ? -h0 : 0, r1 = min(win_h, a.H - h0);
+    const int c0 = w0 < 0 ? -w0 : 0, c1 = min(win_w, a.W - w0);
     float m = -INFINITY, s = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const uint32_t row = plane + (uint32_t)(h0 + r) * a.xs[2];
-        for (int c = c0; c < c1; ++c) {
-            const uint32_t e = row + (uint32_t)(w0 + c) * a.xs[3];
-            const float val = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, e * 4u, 0, 0));
-            m = fmaxf(m, val);
-            s += val;
+    if constexpr (WH != 0) {
+        // every element of the window is requested; those outside [r0,r1) x [c0,c1) with the
+        // out-of-range marker as offset, which reads as zero and is then left out
+#pragma unroll
+        for (int r = 0; r < WH; ++r)
+#pragma unroll
+            for (int c = 0; c < WW; ++c) {
+                const bool in = r >= r0 && r < r1 && c >= c0 && c < c1;
+                const uint32_t e = plane + (uint32_t)(h0 + r) * a.xs[2] + (uint32_t)(w0 + c) * a.xs[3];
+                const float val = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, in ? e * 4u : 0x80000000u, 0, 0));
+                m = in ? fmaxf(m, val) : m;
+                s += val;
+            }
+    } else {
+        for (int r = r0; r < r1; ++r) {
+            const uint32_t row = plane + (uint32_t)(h0 + r) * a.xs[2];
+            for (int c = c0; c < c1; ++c) {
+                const uint32_t e = row + (uint32_t)(w0 + c) * a.xs[3];
+                const float val = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, e * 4u, 0, 0));
+                m = fmaxf(m, val);
+                s += val;
+            }
         }
     }
     const int cnt = (r1 - r0) * (c1 - c0);
@@ -571,7 +590,10 @@ igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc,
     a.beta = *static_cast<const float *>(beta);
     a.y = static_cast<float *>(y);
     a.x = static_cast<const float *>(x);
-    return launch(&igconv_pooling_kernel, "igconv_pooling_kernel", a, (a.count + 255u) / 256u, handle->stream);
+    const uint32_t blocks = (a.count + 255u) / 256u;
+    if (a.win_h == 3 && a.win_w == 3) return launch(&igconv_pooling_kernel<3, 3>, "igconv_pooling_kernel", a, blocks, handle->stream);
+    if (a.win_h == 2 && a.win_w == 2) return launch(&igconv_pooling_kernel<2, 2>, "igconv_pooling_kernel", a, blocks, handle->stream);
+    return launch(&igconv_pooling_kernel<0, 0>, "igconv_pooling_kernel", a, blocks, handle->stream);
 }
 
 }  // extern "C"
