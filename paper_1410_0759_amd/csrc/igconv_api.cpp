@@ -191,7 +191,7 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
         return k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries;
     }
-    if (gmode == 3) return k.RS == 9 && k.C % 4 == 0;  // (its 16-byte filter loads are checked apart)
+    if (gmode == 3) return k.RS == 9 && k.C % (ki.BK / 9) == 0;  // whole steps of BK/9 channels (16-byte filter loads: checked apart)
     if (gmode == 4 || gmode == 5) {
         if (!(x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
               k.xsW % 8 == 0))

@@ -11,6 +11,8 @@
     X("f32 96x128x32 nopad vecw", false, 96, 128, 32, 1, 4, false, true, GATHER_NOPAD) \
     X("f32 128x128x32 nopad", false, 128, 128, 32, 2, 2, false, false, GATHER_NOPAD) \
     X("f32 128x128x32 nopad vecw", false, 128, 128, 32, 2, 2, false, true, GATHER_NOPAD) \
+    X("f32 64x64x32 nopad", false, 64, 64, 32, 2, 2, false, false, GATHER_NOPAD) \
+    X("f32 64x64x32 nopad vecw", false, 64, 64, 32, 2, 2, false, true, GATHER_NOPAD) \
     X("f32 32x128x32 nopad table", false, 32, 128, 32, 1, 4, false, false, GATHER_NOPAD_TABLE) \
     X("f32 64x128x32 nopad table", false, 64, 128, 32, 2, 2, false, false, GATHER_NOPAD_TABLE) \
     X("f32 96x128x32 nopad table", false, 96, 128, 32, 1, 4, false, false, GATHER_NOPAD_TABLE) \

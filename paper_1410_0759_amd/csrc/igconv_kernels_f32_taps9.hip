@@ -10,6 +10,7 @@
     X("f32 128x128x36 taps9", false, 128, 128, 36, 2, 2, false, true, GATHER_TAPS9) \
     X("f32 64x128x36 taps9 swap", false, 64, 128, 36, 2, 2, true, true, GATHER_TAPS9) \
     X("f32 96x128x36 taps9 swap", false, 96, 128, 36, 1, 4, true, true, GATHER_TAPS9) \
+    X("f32 64x64x72 taps9", false, 64, 64, 72, 2, 2, false, true, GATHER_TAPS9) \
     X("f32 64x128x36 taps9 strided", false, 64, 128, 36, 2, 2, false, false, GATHER_TAPS9) \
     X("f32 96x128x36 taps9 strided", false, 96, 128, 36, 1, 4, false, false, GATHER_TAPS9) \
     X("f32 128x128x36 taps9 strided", false, 128, 128, 36, 2, 2, false, false, GATHER_TAPS9) \
