@@ -146,6 +146,23 @@ igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle,
                                                 igcTensorDescriptor_t yDesc,
                                                 size_t *sizeInBytes);
 
+/* ---- optional workspace of the forward pass ------------------------------------------
+ * igcConvolutionForward never needs a workspace.  A problem with so few output tiles that
+ * most of the chip would idle (small mini-batches: Section 4 discusses them) can however be
+ * run faster when the caller lends one: the reduction over (c,r,s) is then cut into ranges
+ * computed side by side, each leaving a partial copy of y in the workspace, and a second
+ * kernel adds the parts in a fixed order (deterministic) and applies alpha and beta.  This
+ * query reports the size that allows the finest cut the library would choose, 0 when
+ * cutting would not help or does not apply (y with gaps between its elements, the bf16
+ * channel-vector kernels).  Any smaller size passed to igcConvolutionForward is fine
+ * (fewer ranges, or none). */
+igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle,
+                                                        igcTensorDescriptor_t xDesc,
+                                                        igcFilterDescriptor_t wDesc,
+                                                        igcConvolutionDescriptor_t convDesc,
+                                                        igcTensorDescriptor_t yDesc,
+                                                        size_t *sizeInBytes);
+
 /* ---- forward convolution (eq. 3, Section 2.1.1; algorithm of Section 3.1) ---------
  *
  *   y[n,k,p,q] = alpha * sum_{c,r,s} w[k,c,r,s] * x0[n,c,hh,ww] + beta * y[n,k,p,q]
@@ -160,8 +177,9 @@ igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle,
  *  - *beta == 0 makes y write-only: NaN or Inf already in y does not propagate.
  *  - y must not overlap x or w.  x may have zero or overlapping strides; y's strides
  *    must address every output element at a distinct location (else BAD_PARAM).
- *  - workSpace / workSpaceSizeInBytes are accepted for interface symmetry and
- *    ignored; NULL / 0 is fine.
+ *  - workSpace / workSpaceSizeInBytes: NULL / 0 is always fine.  A workspace (device,
+ *    4-byte aligned, owned by the caller, not overlapping x, w or y) is used only as
+ *    igcGetConvolutionForwardOptionalWorkspaceSize describes.
  *  - NOT_SUPPORTED: any other data-type combination, or a tensor whose largest byte
  *    offset reaches 2^31.
  *  - EXECUTION_FAILED: the kernel launch was rejected by the runtime.

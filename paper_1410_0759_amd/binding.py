@@ -14,7 +14,7 @@ __all__ = [
     "IGC_DATA_FLOAT", "IGC_DATA_BFLOAT16", "IGC_CONVOLUTION", "IGC_CROSS_CORRELATION",
     "igcConvolutionForwardPlan", "DECLARED_SYMBOLS",
     "Handle", "TensorDescriptor", "FilterDescriptor", "ConvolutionDescriptor",
-    "get_output_dim", "get_workspace_size", "get_plan", "convolution_forward",
+    "get_output_dim", "get_workspace_size", "get_optional_workspace_size", "get_plan", "convolution_forward",
     "get_backward_data_workspace_size", "convolution_backward_data",
     "get_backward_filter_workspace_size", "convolution_backward_filter",
     "PoolingDescriptor", "get_pooling_output_dim", "activation_forward", "activation_backward", "add_tensor",
@@ -68,6 +68,7 @@ DECLARED_SYMBOLS = {
     "igcGetConvolution2dDescriptor": (_i, [_vp, _P(_i), _P(_i), _P(_i), _P(_i), _P(_i)]),
     "igcGetConvolution2dForwardOutputDim": (_i, [_vp, _vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
     "igcGetConvolutionForwardWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
+    "igcGetConvolutionForwardOptionalWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
     "igcConvolutionForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcGetConvolutionBackwardDataWorkspaceSize": (_i, [_vp, _vp, _vp, _vp, _vp, _P(_sz)]),
     "igcConvolutionBackwardData": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
@@ -271,6 +272,14 @@ def get_workspace_size(handle, xdesc, wdesc, conv, ydesc):
     out = _sz(12345)
     check(lib().igcGetConvolutionForwardWorkspaceSize(handle.ptr, xdesc.ptr, wdesc.ptr, conv.ptr, ydesc.ptr,
                                                       ctypes.byref(out)), "igcGetConvolutionForwardWorkspaceSize")
+    return out.value
+
+
+def get_optional_workspace_size(handle, xdesc, wdesc, conv, ydesc):
+    out = _sz(12345)
+    check(lib().igcGetConvolutionForwardOptionalWorkspaceSize(handle.ptr, xdesc.ptr, wdesc.ptr, conv.ptr, ydesc.ptr,
+                                                              ctypes.byref(out)),
+          "igcGetConvolutionForwardOptionalWorkspaceSize")
     return out.value
 
 

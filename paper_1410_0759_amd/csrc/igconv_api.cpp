@@ -243,6 +243,35 @@ static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * occ);
 }
 
+// Forward pass on a problem with few tiles: with a workspace the reduction can be cut into
+// ranges as in the backward-filter pass (partial results summed in order afterwards), which
+// puts idle compute units to work.  Returns the number of ranges (1: do not cut) and the
+// steps per range.  Only for kernels whose steps stand alone (modes 0-3), outputs packed
+// without gaps, and no fused epilogue; no range shorter than 8 steps.  The number of ranges
+// minimises a small model of the run time in units of one reduction step: the busiest
+// compute unit holds ceil(tiles*s/256) workgroups, which share its MFMA pipes, each taking
+// its range plus a fixed start-up/epilogue share (about 6 steps); cutting adds the summing
+// pass (about 12).  Cutting must win by a tenth, or it is not done.
+static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool packed_y, long long max_parts, int *per_out) {
+    *per_out = (k.ksteps + 1) & ~1;
+    if (ki.gmode > 3 || !packed_y) return 1;
+    const long long tiles = (long long)k.tilesM * k.tilesN;
+    const long long smax = std::min<long long>(std::min<long long>(64, k.ksteps / 8), max_parts);
+    const double kFixed = 6.0, kSumPass = 12.0;
+    auto cost = [&](long long s) {
+        const long long per = (k.ksteps + s - 1) / s;
+        return (double)((tiles * s + kComputeUnits - 1) / kComputeUnits) * ((double)per + kFixed) + (s > 1 ? kSumPass : 0.0);
+    };
+    long long best = 1;
+    for (long long s = 2; s <= smax; ++s)
+        if (cost(s) < cost(best)) best = s;
+    if (best == 1 || cost(best) > 0.9 * cost(1)) return 1;
+    long long per = (k.ksteps + best - 1) / best;
+    per += per & 1;
+    *per_out = (int)per;
+    return (int)((k.ksteps + per - 1) / per);
+}
+
 static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan) {
     const KernelInfo &ki = *kernel_info(id);
     ConvKernelParams &k = pr->kp;
@@ -260,6 +289,8 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
+    k.splits = 1;
+    k.stepsPerSplit = (k.ksteps + 1) & ~1;
     if (plan) {
         plan->kernelId = id;
         plan->tileM = ki.BM;
@@ -688,6 +719,25 @@ igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle, igcTensorDes
     return IGC_STATUS_SUCCESS;
 }
 
+igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcTensorDescriptor_t xDesc,
+                                                        igcFilterDescriptor_t wDesc, igcConvolutionDescriptor_t convDesc,
+                                                        igcTensorDescriptor_t yDesc, size_t *sizeInBytes) {
+    if (!handle || !sizeInBytes) return IGC_STATUS_BAD_PARAM;
+    Problem pr;
+    igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int id = -1;
+    st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    st = fill_plan(id, &pr, nullptr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)pr.kp.K * pr.kp.NPQ;
+    int per;
+    const int splits = forward_split(*kernel_info(id), pr.kp, packed, 1 << 20, &per);
+    *sizeInBytes = splits > 1 ? (size_t)splits * pr.kp.y_bytes : 0;
+    return IGC_STATUS_SUCCESS;
+}
+
 igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle, igcTensorDescriptor_t xDesc, igcFilterDescriptor_t wDesc,
                                        igcConvolutionDescriptor_t convDesc, igcTensorDescriptor_t yDesc,
                                        igcConvolutionForwardPlan *plan) {
@@ -745,8 +795,6 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
                                               igcFilterDescriptor_t wDesc, const void *w, igcConvolutionDescriptor_t convDesc,
                                               void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
                                               const void *bias, int activation, igcTensorDescriptor_t yDesc, void *y) {
-    (void)workSpace;
-    (void)workSpaceSizeInBytes;
     if (!handle || !alpha || !beta || !x || !w || !y) return IGC_STATUS_BAD_PARAM;
     if (activation < IGC_ACTIVATION_IDENTITY || activation > IGC_ACTIVATION_TANH || (uintptr_t)bias % 4) return IGC_STATUS_BAD_PARAM;
     Problem pr;
@@ -767,8 +815,32 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     pr.kp.beta = *static_cast<const float *>(beta);
     pr.kp.bias = static_cast<const float *>(bias);
     pr.kp.act = activation;
-    const int err = kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream);
-    return err == 0 ? IGC_STATUS_SUCCESS : IGC_STATUS_EXECUTION_FAILED;
+    // A small problem with a workspace: cut the reduction into ranges (see forward_split).
+    int grid = plan.gridX;
+    int splits = 1;
+    if (workSpace && (uintptr_t)workSpace % 4 == 0 && !bias && activation == IGC_ACTIVATION_IDENTITY) {
+        ConvKernelParams &k = pr.kp;
+        const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)k.K * k.NPQ;
+        int per;
+        splits = forward_split(*kernel_info(id), k, packed, (long long)(workSpaceSizeInBytes / k.y_bytes), &per);
+        if (splits > 1) {
+            k.splits = splits;
+            k.stepsPerSplit = per;
+            k.ySplitBytes = k.y_bytes;
+            k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN * splits + 7) / 8);
+            k.wgsPerXcd = workgroups_per_xcd(*kernel_info(id), k.tilesPerXcd);
+            grid = 8 * k.wgsPerXcd;
+            k.y = workSpace;
+            k.alpha = 1.f;
+            k.beta = 0.f;
+        }
+    }
+    if (kernel_info(id)->launch(pr.kp, grid, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    if (splits > 1 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(y), pr.kp.y_bytes / 4, splits,
+                                       pr.kp.y_bytes / 4, *static_cast<const float *>(alpha),
+                                       *static_cast<const float *>(beta), handle->stream) != 0)
+        return IGC_STATUS_EXECUTION_FAILED;
+    return IGC_STATUS_SUCCESS;
 }
 
 igcStatus igcGetConvolutionBackwardDataWorkspaceSize(igcHandle_t handle, igcFilterDescriptor_t wDesc,

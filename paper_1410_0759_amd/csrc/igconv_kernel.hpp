@@ -298,11 +298,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // columns of D_m) and cut into 8 contiguous ranges, one per XCD, so that the
     // workgroups which share input rows and columns also share an L2.  A workgroup is
     // persistent: it takes every wgsPerXcd-th tile of its XCD's range, and its pipeline
-    // runs on across tile boundaries (see the main loop).  GATHER_WGRAD: the tile numbers
-    // repeat once per range of the reduction.
+    // runs on across tile boundaries (see the main loop).
     const int wg_xcd = (int)(blockIdx.x % 8u), wg_local = (int)(blockIdx.x / 8u);
     const int tiles_mn = p.tilesM * p.tilesN;
-    const int tiles_total = WG ? tiles_mn * p.splits : tiles_mn;
+    const int tiles_total = tiles_mn * p.splits;   // (splits >= 1; above 1 the tile numbers repeat once per range of the reduction)
     // number of this workgroup's i-th tile; tiles_total when it has no i-th tile
     auto tile_number = [&](int i) {
         const int local = wg_local + i * p.wgsPerXcd;
@@ -452,7 +451,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     };
     // Everything the loads of a tile depend on.
     auto setup_tile = [&](int tile) {
-        if constexpr (WG) {
+        if (p.splits > 1) {
             split = tile / tiles_mn;
             tile -= split * tiles_mn;
             t_begin = split * p.stepsPerSplit;
@@ -812,11 +811,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         });
     };
 
-    // A tile takes `nsteps` steps, rounded up to whole pairs (an odd count runs one extra
-    // step on zero tiles), so that the loop body stays a single basic block.  GATHER_WGRAD: a
-    // tile is one range of an even number of steps; a range that reaches past the last step
-    // reads zeros there.
-    const int nsteps = WG ? p.stepsPerSplit : ((p.ksteps + 1) & ~1);
+    // A tile takes `nsteps` steps, a whole number of pairs (an odd count runs one extra step
+    // on zero tiles), so that the loop body stays a single basic block.  When the reduction is
+    // cut into ranges (backward filter; forward on small problems with a workspace), a tile is
+    // one range; a range that reaches past the last step reads zeros there.
+    const int nsteps = p.stepsPerSplit;   // (even; the host rounds an odd number of steps up)
     if constexpr (GM == GATHER_NOPAD_TABLE) {
         // offset of reduction index i = (c,r,s) relative to the window origin, or the buffer size
         // for an index past the end (the host checked that (nsteps + 2) * BK entries fit)

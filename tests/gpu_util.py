@@ -83,9 +83,21 @@ class GpuConv:
 
     def launch(self, alpha=1.0, beta=0.0):
         self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
+        ws = getattr(self, "ws", None)
         st = ig.convolution_forward(self.handle, alpha, self.xdesc, self.x_dev.data_ptr(), self.wdesc,
-                                    self.w_dev.data_ptr(), self.conv, beta, self.ydesc, self.y_ptr)
+                                    self.w_dev.data_ptr(), self.conv, beta, self.ydesc, self.y_ptr,
+                                    ws.ptr if ws is not None else 0, self.ws_bytes if ws is not None else 0)
         ig.check(st, "igcConvolutionForward")
+
+    def lend_workspace(self, nbytes=None):
+        """Give later launches a workspace (default: the size the library reports as useful);
+        returns that reported size."""
+        asked = ig.get_optional_workspace_size(self.handle, self.xdesc, self.wdesc, self.conv, self.ydesc)
+        self.ws_bytes = asked if nbytes is None else int(nbytes)
+        self.ws = GuardedOutput((1, 1, 1, max(self.ws_bytes // 4, 1)), (0, 0, 0, 1)) if self.ws_bytes else None
+        if self.ws is not None:
+            self.ws.prefill(value=float("nan"))
+        return asked
 
     def launch_fused(self, alpha, beta, bias, activation):
         """y = f(alpha*conv + beta*y + bias[k]); bias a float32 vector of K values or None."""

@@ -348,3 +348,53 @@ def test_fused_bias_and_activation():
             assert np.all(np.isfinite(got))
             err = gu.rel_err(got, want)
             assert err <= gu.TOL[dtype], (cases[i], act, err)
+
+
+# ------------------------------------------------------------------ optional workspace (small problems)
+def test_forward_with_optional_workspace():
+    """Few output tiles and a long reduction: with a lent workspace the reduction is cut into
+    ranges and summed in order.  Same result as without (to rounding), bitwise repeatable, any
+    workspace size accepted, the mandatory workspace query still reports zero."""
+    import paper_1410_0759_amd as ig
+    gu = _gpu()
+    cases = [
+        # N, C, H, W, K, R, S, pad, stride, y layout
+        (2, 128, 17, 17, 128, 7, 7, (0, 0), (1, 1), "NCHW"),     # unpadded, long filter rows
+        (1, 256, 13, 13, 96, 3, 3, (1, 1), (1, 1), "NCHW"),      # nine-tap table
+        (2, 200, 9, 9, 40, 5, 3, (2, 1), (1, 1), "NHWC"),        # tap-major, channels along the lanes
+        (1, 300, 11, 11, 24, 3, 3, (1, 1), (2, 2), "NCHW"),
+    ]
+    for i, (N, C, H, W, K, R, S, pad, stride, yl) in enumerate(cases):
+        x, w = wl.random_problem(90 + i, N, C, H, W, K, R, S)
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=1)
+        y0 = np.random.default_rng(95 + i).uniform(-1, 1, size=want.shape).astype(np.float32)
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=1, alpha=0.5, beta=-1.5, y_old=y0)
+        g = gu.GpuConv(x, w, pad, stride, 1, y_layout=yl)
+        assert ig.get_workspace_size(g.handle, g.xdesc, g.wdesc, g.conv, g.ydesc) == 0
+        outs = []
+        asked = None
+        for ws in ("none", "asked", "asked", "one part", "odd"):
+            if ws == "none":
+                pass
+            elif ws == "asked":
+                asked = g.lend_workspace()
+                part = int(np.prod(want.shape)) * 4
+                assert asked >= 2 * part and asked % part == 0, "this problem should be cut into ranges"
+            elif ws == "one part":
+                g.lend_workspace(part)               # too small to cut: runs as without
+            else:
+                g.lend_workspace(3 * part + 12)
+            print("optional workspace", cases[i], ws, flush=True)
+            g.prefill(y0=y0)
+            g.launch(0.5, -1.5)
+            got = g.result()
+            if getattr(g, "ws", None) is not None:
+                g.ws.result()                        # guard bands of the workspace
+            assert gu.rel_err(got, want) <= gu.TOL["f32"]
+            outs.append(got)
+        assert np.array_equal(outs[1], outs[2]), "same call, same bits"
+        assert np.array_equal(outs[0], outs[3])
+    # a problem with plenty of tiles is not cut; neither is one whose y has gaps
+    x, w = wl.random_problem(99, 8, 16, 40, 40, 64, 3, 3)
+    g = gu.GpuConv(x, w, (1, 1), (1, 1), 1)
+    assert g.lend_workspace() == 0

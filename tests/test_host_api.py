@@ -94,6 +94,26 @@ def test_workload_dims_and_plans():
         assert plan.swapOperands == (1 if w_.y_layout == "NHWC" else 0)
 
 
+def test_optional_forward_workspace_is_only_asked_for_where_cutting_the_reduction_pays():
+    """The mandatory workspace query reports zero for every problem; the optional one a whole
+    number of copies of y for a problem with few tiles and a long reduction, zero otherwise."""
+    h = ig.Handle()
+    small = _descs(N=2, C=128, H=17, W=17, K=128, R=7, S=7, pad=(0, 0))
+    assert ig.get_workspace_size(h, *small) == 0
+    ws = ig.get_optional_workspace_size(h, *small)
+    ybytes = 2 * 128 * 11 * 11 * 4
+    assert ws >= 2 * ybytes and ws % ybytes == 0
+    for w_ in wl.WORKLOADS[1:4]:     # the fp32 workloads fill the chip: nothing to gain
+        nchw = lambda n, c, hh, ww: (c * hh * ww, hh * ww, ww, 1)
+        d = _descs(w_.N, w_.C, w_.H, w_.W, w_.K, w_.R, w_.S, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, 0,
+                   xs=nchw(w_.N, w_.C, w_.H, w_.W), ys=nchw(w_.N, w_.K, w_.P, w_.Q))
+        assert ig.get_optional_workspace_size(h, *d) == 0
+    # a short reduction is never cut; neither is an output with gaps between its elements
+    assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3)) == 0
+    gaps = _descs(N=2, C=128, H=17, W=17, K=128, R=7, S=7, pad=(0, 0), ys=(128 * 11 * 12, 11 * 12, 12, 1))
+    assert ig.get_optional_workspace_size(h, *gaps) == 0
+
+
 def test_bf16_channel_vector_modes_are_offered_only_where_they_apply():
     """bf16, nine taps, channels contiguous and in sixteens: 16-byte channel vectors, read from
     a staged patch of the zero-extended image while every tile's pixel range fits it (512
