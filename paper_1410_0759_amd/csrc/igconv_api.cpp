@@ -150,10 +150,12 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // D_m; measured on the box, gathering one element costs about as much MFMA time as
     // `gather` multiply-add rows, depending on the mode.
     // The channel-vector bf16 kernels are bound by their loads, not by the MFMA pipe: measured,
-    // a step costs about 2.75 units per filter row and 1 (1.5 when gathered tap by tap) per
-    // column, plus a small MFMA term; the scale makes them comparable with the line below.
+    // a step costs about 2.75 units per filter row (2.4 with coalesced row loads) and 1 (1.5
+    // when gathered tap by tap) per column, plus a small MFMA term; the scale makes them
+    // comparable with the line below.
     if (ki.gmode == 4 || ki.gmode == 5)
-        return tile_times * steps * 1000.0 * (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
+        return tile_times * steps * 1000.0 *
+               ((ki.variant == 1 ? 2.4 : 2.75) * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (ki.gmode == 7 ? 14.0 : 6.0)));
     return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
 }

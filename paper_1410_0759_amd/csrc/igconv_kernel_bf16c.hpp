@@ -36,9 +36,17 @@
 
 namespace igc {
 
-template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false>
+template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false, bool COALA_ = false>
 struct Bf16cConfig {
     static constexpr bool PATCH = PATCH_;
+    // COALA: filter rows loaded with neighbouring lanes on neighbouring 16-byte chunks of a row
+    // (18 lanes per row and step, 14 rows per pass) and scattered into the tap planes element by
+    // element, instead of one thread per half row with a register transposition: a load
+    // instruction then touches a dozen cache lines instead of 64, and the L1's rate of line
+    // lookups is what bounds these kernels.
+    static constexpr bool COALA = COALA_;
+    static constexpr int RPP = 14;                               // rows per pass (14 x 18 = 252 threads)
+    static constexpr int NAP = (BM_ + RPP - 1) / RPP;            // passes
     static constexpr int PATCH_PIX = 512;                   // pixels of the zero-extended image per tile
     static constexpr int PATCH_PLANE = PATCH_PIX * 16 + 128;  // one channel half; +128 B: halves on disjoint banks
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
@@ -49,7 +57,10 @@ struct Bf16cConfig {
     static constexpr int ROW_BYTES = CH * 2;                // one row of one tap: two 16-byte halves
     // Every thread stages filter rows, so that the main loop has no divergent code: the
     // F_m planes always hold THREADS/2 rows, of which the first BM are used.
-    static constexpr int AR = THREADS / 2;
+    // (COALA: one spare row for the four idle threads, then rounded up to 4 mod 8 rows: that plane
+    // stride spreads the 2-byte scatter writes best over the LDS banks - 2.1 instead of 3.0 cycles
+    // per write instruction in a model of the 64 banks)
+    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : THREADS / 2;
     static constexpr int A_BYTES = TAPS * AR * ROW_BYTES;
     static constexpr int B_BYTES = PATCH ? 2 * PATCH_PLANE : TAPS * BN * ROW_BYTES;
     static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
@@ -169,8 +180,36 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
                                 : kOutOfRange;
     const int a_woff = plane_off(a_row, ha);
 
+    // COALA: thread = (row ca_r + 14*i in pass i, chunk ca_q of the row's 18); the four threads past
+    // 252 load nothing and write to the spare row.  The eight elements of chunk ca_q are the
+    // (channel, tap) pairs f = 8*ca_q + j -> (f / 9, f % 9); ca_base[j] is where element j goes
+    // relative to the row's 32 bytes in plane 0 (bit 4 of it is the channel half, which the
+    // row's swizzle bit flips).
+    constexpr bool COALA = Cfg::COALA;
+    constexpr int NAP = COALA ? Cfg::NAP : 1;
+    constexpr int NAL = COALA ? NAP : TAPS;      // filter loads per thread and step
+    const bool ca_on = tid < 18 * Cfg::RPP;
+    const int ca_q = tid % 18, ca_r = tid / 18;
+    uint32_t ca_voff[NAP];
+    int ca_row[NAP], ca_base[8];
+    if constexpr (COALA) {
+#pragma unroll
+        for (int i = 0; i < NAP; ++i) {
+            const int row = ca_on ? ca_r + Cfg::RPP * i : Cfg::NAP * Cfg::RPP;
+            ca_voff[i] = (ca_on && row < BM && m0 + row < p.K) ? ((uint32_t)(m0 + row) * (uint32_t)p.CRS) * 2u + (uint32_t)ca_q * 16u
+                                                              : kOutOfRange;
+            // (the swizzle bit of the row rides in bit 30: it is XORed into bit 4 of ca_base below)
+            ca_row[i] = (row * 32) | (((row >> 3) & 1) << 30);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int f = 8 * ca_q + j, c = f / 9, t = f % 9;
+            ca_base[j] = t * (Cfg::AR * 32) + (c >> 3) * 16 + (c & 7) * 2;
+        }
+    }
+
     // registers holding the tiles in flight (two sets)
-    u32x4 a_reg[2][TAPS], b_reg[2][NBL];
+    u32x4 a_reg[2][NAL], b_reg[2][NBL];
     uint32_t sc_asoff = 0, sc_bsoff = 0;
 
     auto decode = [&](int tau) {
@@ -179,8 +218,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         sc_asoff = ((ut * (uint32_t)(Cfg::BK * 2)) & live) | (p.w_bytes & ~live);   // 16 channels x 9 taps of a row
         sc_bsoff = ((ut * (uint32_t)(Cfg::CH * 2) * (uint32_t)p.xsC) & live) | (p.x_bytes & ~live);
     };
-    auto load_a = [&](int set, int q) {   // q-th 16 bytes of this thread's 72 elements
-        a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, sc_asoff, 0);
+    auto load_a = [&](int set, int q) {   // q-th 16 bytes of this thread's 72 elements; COALA: the chunk of pass q
+        if constexpr (COALA)
+            a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, ca_voff[q], sc_asoff, 0);
+        else
+            a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, sc_asoff, 0);
     };
     auto load_b = [&](int set, int i) {
         b_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, b_voff[i], sc_bsoff, 0);
@@ -188,6 +230,16 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     // Tap t of the thread's 8 channels: element (c, t) sits at position c*9 + t of the 72
     // loaded ones, i.e. 16-bit half (c*9+t)&1 of dword (c*9+t)>>1.
     auto write_a = [&](int set, int buf, int t) {
+        if constexpr (COALA) {   // t: the pass; eight 2-byte elements to their tap planes
+            const int rowbase = ca_row[t] & 0x3fffffff, flip = (ca_row[t] >> 30) << 4;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t d = a_reg[set][t][j >> 1];
+                *reinterpret_cast<uint16_t *>(ldsA + buf * Cfg::A_BYTES + rowbase + (ca_base[j] ^ flip)) =
+                    (uint16_t)((j & 1) ? d >> 16 : d);
+            }
+            return;
+        }
         u32x4 o;
 #pragma unroll
         for (int jd = 0; jd < 4; ++jd) {
@@ -203,15 +255,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
         constexpr int kStride = PATCH ? 128 * 16 : BN * 32;  // 128 pixels further / next tap plane
         *reinterpret_cast<u32x4 *>(ldsB + buf * Cfg::B_BYTES + i * kStride + b_woff) = b_reg[set][i];
     };
-    constexpr int NL = 1 + TAPS + NBL, NW = TAPS + NBL;
+    constexpr int NL = 1 + NAL + NBL, NW = NAL + NBL;
     auto load_item = [&](int i, int set, int tau) {
         if (i == 0) decode(tau);
-        else if (i <= TAPS) load_a(set, i - 1);
-        else load_b(set, i - 1 - TAPS);
+        else if (i <= NAL) load_a(set, i - 1);
+        else load_b(set, i - 1 - NAL);
     };
     auto write_item = [&](int i, int set, int buf) {
-        if (i < TAPS) write_a(set, buf, i);
-        else write_b(set, buf, i - TAPS);
+        if (i < NAL) write_a(set, buf, i);
+        else write_b(set, buf, i - NAL);
     };
 
     // ---- MFMA role -------------------------------------------------------------------
@@ -289,7 +341,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
             }
             // Loads go out in two bursts (filter rows, then pixels): a thread's loads hit the same
             // few cache lines, which a 32 KB L1 only keeps if nothing else comes between them.
-            constexpr int l0 = m == 0 ? 0 : (m == 1 ? 1 + TAPS : NL), l1 = m == 0 ? 1 + TAPS : NL;
+            constexpr int l0 = m == 0 ? 0 : (m == 1 ? 1 + NAL : NL), l1 = m == 0 ? 1 + NAL : NL;
             static_for<(l1 > l0 ? l1 - l0 : 0)>([&](auto ic) { load_item(l0 + decltype(ic)::value, cur, k2); });
             constexpr int WS = NW < SB ? NW : SB;
             if constexpr (m >= SB - WS && m < SB) {

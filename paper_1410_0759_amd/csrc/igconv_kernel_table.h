@@ -21,6 +21,7 @@ struct KernelInfo {
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
+    int variant = 0;  // bf16 channel-vector kernels: 1 when filter rows are loaded coalesced and scattered to LDS
 };
 
 struct KernelGroup {
