@@ -312,6 +312,14 @@ def main():
             else:
                 per_config.append(run_config(i, args.steps, args.warmup, 3.0))
 
+    # The bf16 workload again at a mini-batch of 256: at N = 32 it has 200 tiles for 256 compute
+    # units and 12 us of work at peak; this shows the same kernels with the chip filled.
+    bf16_large = None
+    if not args.only:
+        import workloads as wl
+        bf16_large = run_config(None, max(30, args.steps // 3), max(20, args.warmup // 2), 1.0,
+                                workload=wl.shrink(wl.by_index(5), 256))
+
     # The paper's own layer collection (its Table 2) with synthetic data, beside the numbers
     # its Table 3 reports for 2014 hardware.
     table2 = []
@@ -376,6 +384,7 @@ def main():
         "device": {"name": props.name, "compute_units": props.multi_processor_count,
                    "clock_mhz": getattr(props, "clock_rate", 0) / 1e3},
         "per_config": per_config,
+        "bf16_workload_at_mini_batch_256": bf16_large,
         "table2_layers": table2,
         "table2_batch_sweep": batch_sweep,
         "backward": backward,
