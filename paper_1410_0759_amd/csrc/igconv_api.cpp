@@ -4,6 +4,8 @@
 #include "../../include/igconv.h"
 
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <algorithm>
 #include <vector>
 #include <new>
@@ -187,7 +189,7 @@ static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
 // staging a patch of the zero-extended image needs every tile's pixel range to fit it.
 static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
     const int gmode = ki.gmode;
-    if (gmode == 6 || gmode == 8) return false;  // backward-filter kernels are chosen by that pass itself
+    if (gmode == 6 || gmode == 8 || gmode == 9) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 7) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
@@ -497,12 +499,23 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     // one tap per tile (gather mode 8; any filter size).  Otherwise the generic gather over
     // columns (c,r,s) set up above (mode 6).  Row tile: the smaller one when it covers K.
     const bool by_tap = dw->c >= 24;
-    const int want_bm = dw->k <= 64 ? 64 : 128;
+    const bool unpadded = !by_tap && cv->pad_h == 0 && cv->pad_w == 0;   // few channels, no padding: mode 9
+    const int want_mode = by_tap ? 8 : (unpadded ? 9 : 6);
+    // row tile: least padding of K among 64, 96 (fp32 only), 128; the larger one on a tie
+    int want_bm = 64;
+    for (int bm : {96, 128}) {
+        if (bm == 96 && b16) continue;
+        const long long pad_new = (long long)((dw->k + bm - 1) / bm) * bm, pad_old = (long long)((dw->k + want_bm - 1) / want_bm) * want_bm;
+        if (pad_new <= pad_old) want_bm = bm;
+    }
     const int want_bn = !by_tap ? 128 : ((dw->c - 1) % 128 < 64 ? 64 : 128);   // (least padding of C)
     int id = -1;
-    for (int i = 0; i < kernel_count(); ++i) {
-        const KernelInfo &ki = *kernel_info(i);
-        if (ki.gmode == (by_tap ? 8 : 6) && ki.bf16 == b16 && ki.BM == want_bm && ki.BN == want_bn) id = i;
+    for (int attempt = 0; attempt < 2 && id < 0; ++attempt) {
+        for (int i = 0; i < kernel_count(); ++i) {
+            const KernelInfo &ki = *kernel_info(i);
+            if (ki.gmode == want_mode && ki.bf16 == b16 && ki.BM == want_bm && ki.BN == want_bn) id = i;
+        }
+        if (id < 0) want_bm = 128;   // (not every tile shape exists with 96 rows)
     }
     if (id < 0) return IGC_STATUS_NOT_SUPPORTED;
     out->kernel_id = id;
@@ -519,6 +532,13 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
         magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
         k.ysQ = dw->r * dw->s; k.ysN = 0; k.ysP = 0;
         out->tiles_n = (long long)dw->r * dw->s * cblocks;
+    } else if (unpadded) {
+        // columns (c,r,s) in filter order at distance 1 in dw; PQ = R*S, Q = S and R decode a column
+        k.NPQ = (int)CRS; k.PQ = dw->r * dw->s; k.Q = dw->s; k.R = dw->r;
+        k.flip = flip ? 1 : 0; k.pad_h = 0; k.pad_w = 0; k.u = 1; k.v = 1;
+        magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
+        k.ysQ = 1; k.ysN = 0; k.ysP = 0;
+        out->tiles_n = (CRS + ki.BN - 1) / ki.BN;
     } else {
         out->tiles_n = (CRS + ki.BN - 1) / ki.BN;
     }
@@ -942,6 +962,9 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
         k.alpha = a;
         k.beta = bt;
     }
+    if (getenv("IGCONV_DEBUG"))
+        fprintf(stderr, "igconv: backward filter with '%s', %lld tiles x %d ranges of %d steps\n", kernel_info(b.kernel_id)->name,
+                b.tiles, splits, k.stepsPerSplit);
     if (kernel_info(b.kernel_id)->launch(k, 8 * k.wgsPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
     if (splits > 1 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
                                        b.out_elems, a, bt, handle->stream) != 0)

@@ -228,7 +228,12 @@ enum GatherMode {
     // once per step, window test included, since the tile's tap is a scalar; the elements of
     // a thread are channels, reached through a scalar offset.  No vector instruction per
     // gathered element.  Any R, S, pad, stride; wants C to fill a column tile.
-    GATHER_WGRAD_TAP = 8
+    GATHER_WGRAD_TAP = 8,
+    // Backward-filter without padding (every tap of every output pixel lies inside the image)
+    // for few channels: lanes along the reduction index as above, columns in filter order
+    // (c,r,s); each thread keeps the offsets of its columns in registers for the whole tile
+    // and a gathered element costs one vector addition.
+    GATHER_WGRAD_NOPAD = 9
 };
 
 constexpr int kOffsetTableEntries = 2048;
@@ -264,9 +269,9 @@ struct KernelConfig {
     static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
-    static_assert((GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP) || (!VECA && 256 % BK == 0),
+    static_assert((GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD) || (!VECA && 256 % BK == 0),
                   "one reduction index per thread, element-wise first operand");
-    static_assert(GMODE != GATHER_WGRAD_TAP || BK == 32, "a half wavefront spans the reduction indices of a step");
+    static_assert((GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD) || BK == 32, "a half wavefront spans the reduction indices of a step");
     static_assert(GMODE != GATHER_TAPS9 || (BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
@@ -278,8 +283,9 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int GM = Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
-    constexpr bool WG = GM == GATHER_WGRAD || GM == GATHER_WGRAD_TAP;   // backward filter: cut reduction, dy as first operand
-    constexpr bool WGT = GM == GATHER_WGRAD_TAP;
+    constexpr bool WGN = GM == GATHER_WGRAD_NOPAD;
+    constexpr bool WG = GM == GATHER_WGRAD || GM == GATHER_WGRAD_TAP || WGN;   // backward filter: dy as first operand
+    constexpr bool WGT = GM == GATHER_WGRAD_TAP || WGN;                        // lanes along the reduction index
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
@@ -417,6 +423,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     const int wt_col = wave * (BN / 4) + half * WT_E;
     const uint32_t wt_laneoff = (uint32_t)(half * WT_E) * (uint32_t)p.xsN * ES;
     int sc_tap_h = 0, sc_tap_w = 0, sc_tapidx = 0;
+    uint32_t wn_col[WGN ? WT_E : 1];   // GATHER_WGRAD_NOPAD: offsets of this thread's columns (c,r,s) in x
     uint32_t sc_colso = 0, wt_pix = kOutOfRange, wt_n = 0, wt_rem = 0, wt_j = 0;
 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
@@ -457,7 +464,20 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             t_begin = split * p.stepsPerSplit;
         }
         m0 = (tile % p.tilesM) * BM;
-        if constexpr (WGT) {
+        if constexpr (WGN) {
+            n0 = (tile / p.tilesM) * BN;
+#pragma unroll
+            for (int e = 0; e < WT_E; ++e) {
+                // column i -> (c, r, s) with PQ = R*S and Q = S of the filter; tap in reading direction
+                const uint32_t i = (uint32_t)(n0 + wt_col + e);
+                const uint32_t c = magic_div(i, p.mPQ);
+                const uint32_t rs = i - c * (uint32_t)p.PQ;
+                const uint32_t r = magic_div(rs, p.mQ);
+                const uint32_t sx = rs - r * (uint32_t)p.Q;
+                const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r, ts = p.flip ? (uint32_t)p.Q - 1u - sx : sx;
+                wn_col[e] = i < (uint32_t)p.NPQ ? (c * (uint32_t)p.xsN + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
+            }
+        } else if constexpr (WGT) {
             // column tile -> (tap, channel block); PQ holds the channel blocks per tap, Q and P
             // the filter's S and R
             const uint32_t tn = (uint32_t)(tile / p.tilesM);
@@ -529,8 +549,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             const bool live = wt_j < (uint32_t)p.CRS;
             const uint32_t hh = pp * (uint32_t)p.redMulH + (uint32_t)sc_tap_h;   // (wraps below zero: fails the test)
             const uint32_t ww = qq * (uint32_t)p.redMulW + (uint32_t)sc_tap_w;
-            const bool ok = live && hh < (uint32_t)p.H && ww < (uint32_t)p.W;
-            wt_pix = ok ? (wt_n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * ES + wt_laneoff : kOutOfRange;
+            const bool ok = live && (WGN || (hh < (uint32_t)p.H && ww < (uint32_t)p.W));   // (no padding: always inside)
+            wt_pix = ok ? (wt_n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * ES + (WGN ? 0u : wt_laneoff) : kOutOfRange;
             a_jo = live ? (wt_n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES : kOutOfRange;
         } else if constexpr (GM == GATHER_NOPAD_TABLE) {
             if (sc_tau == p.tail_step) {   // (see below)
@@ -608,7 +628,12 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) {
         uint32_t vo, so;
-        if constexpr (WGT) {
+        if constexpr (WGN) {
+            // (a dead reduction index or a column past the end carries the out-of-range marker; when
+            // both do, the sum wraps to a valid offset, but such a column is never stored)
+            vo = wt_pix + wn_col[e];
+            so = 0;
+        } else if constexpr (WGT) {
             vo = wt_pix;
             so = sc_colso + (uint32_t)e * (uint32_t)p.xsN * ES;
         } else if constexpr (GEN) {
@@ -861,9 +886,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         step(std::integral_constant<int, 1>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
         // (GATHER_WGRAD_TAP: the columns are channels, 'R*S' elements apart; the tile's tap moves the base)
-        const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + (WGT ? (uint32_t)out_tap * 4u : 0u);
+        const uint32_t ytap = GM == GATHER_WGRAD_TAP ? (uint32_t)out_tap * 4u : 0u;
+        const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + ytap;
         const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
-            static_cast<char *>(p.y) + ybase, 0, p.y_bytes - (WGT ? (uint32_t)out_tap * 4u : 0u), kBufferWord3);
+            static_cast<char *>(p.y) + ybase, 0, p.y_bytes - ytap, kBufferWord3);
         store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, bias_cur, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
         if (next >= tiles_total) break;
 #pragma unroll

@@ -16,7 +16,8 @@ struct KernelInfo {
                     // 4 channel vectors (bf16, nine taps, unit channel stride), 5 the same from a staged image patch,
                     // 6 backward-filter (generic gather, roles of columns and reduction exchanged),
                     // 7 unpadded with the tap offsets in an LDS table (short reductions),
-                    // 8 backward-filter with columns (tap, channel), one tap per tile
+                    // 8 backward-filter with columns (tap, channel), one tap per tile,
+                    // 9 backward-filter without padding, few channels
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).

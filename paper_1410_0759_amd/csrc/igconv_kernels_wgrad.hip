@@ -15,7 +15,14 @@
     X("bf16 64x64x32 wgrad tap", true, 64, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
     X("bf16 128x64x32 wgrad tap", true, 128, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
     X("bf16 64x128x32 wgrad tap", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("bf16 128x128x32 wgrad tap", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP)
+    X("bf16 128x128x32 wgrad tap", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
+    X("f32 64x128x32 wgrad nopad", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
+    X("f32 96x128x32 wgrad nopad", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD_NOPAD) \
+    X("f32 128x128x32 wgrad nopad", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
+    X("f32 96x128x32 wgrad tap", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD_TAP) \
+    X("f32 96x128x32 wgrad", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD) \
+    X("bf16 64x128x32 wgrad nopad", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
+    X("bf16 128x128x32 wgrad nopad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD)
 
 IGC_DEFINE_GROUP(kGroupWgrad)
 
