@@ -120,7 +120,7 @@ def run_backward(index, steps, warmup, oracle_seconds):
     cpu_s = time.perf_counter() - t0
     ms = time_gpu(_Timed(g), 1.0, 0.0, steps, warmup)
     out["backward_data"] = {"ms": ms, "tflops": w_.flops / ms / 1e9, "frac_of_peak": w_.flops / ms / 1e9 / PEAK_TFLOPS[w_.dtype],
-                            "rel_err": gu.rel_err(got[:n], want), "oracle_seconds": cpu_s}
+                            "workspace_bytes": g.asked, "rel_err": gu.rel_err(got[:n], want), "oracle_seconds": cpu_s}
     del g
 
     g = gu.GpuBackwardFilter(x, dy, (w_.R, w_.S), pad, stride, w_.mode, w_.dtype)

@@ -202,9 +202,16 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
  *
  * i.e. the transpose of igcConvolutionForward with respect to x, for the same filter and
  * convolution descriptors.  It runs as an implicit GEMM as well (rows c, columns (n,h,w),
- * reduction (k,r,s)): the gathered operand is dy, no lowered matrix is stored and no
- * workspace is needed; with strides u, v above 1 one launch is made per residue class of
- * (h mod u, w mod v), each reducing over exactly the taps that reach it.
+ * reduction (k,r,s)): the gathered operand is dy, no lowered matrix is stored; with strides
+ * u, v above 1 one launch is made per residue class of (h mod u, w mod v), each reducing
+ * over exactly the taps that reach it.
+ *
+ * Workspace (device, may be null / smaller: then the general route runs, same result up to
+ * rounding order): igcGetConvolutionBackwardDataWorkspaceSize returns 0 except for bfloat16
+ * problems with u = v = 1, R*S = 9, K a multiple of 16, pad <= filter size - 1 and dy's
+ * channel stride 1, where it returns K*C*R*S*2 bytes: the pass is then the forward pass
+ * over dy with the filter's k and c exchanged (written to the workspace, 16-byte aligned,
+ * by a small kernel on the same stream) and uses the forward pass's fastest kernels.
  *
  *  - w (device, read): packed K,C,R,S.  dy (device, read): laid out by dyDesc, dimensions
  *    (N, K, P, Q) with P, Q = eq. 1 of dxDesc's H, W.  dx (device, written; read only when

@@ -421,6 +421,39 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
 }
 
 
+// bf16 with unit stride, nine taps and dy's channels contiguous: backward data IS a forward
+// pass over dy with the filter's k and c exchanged and its taps read in the other direction
+// (tap g of the gather is filter tap R-1-g resp. g for eq. 2), pad R-1-pad.  With the
+// exchanged filter written to a workspace (K*C*9 elements) the channel-vector kernels of
+// the forward pass apply.  False when the problem does not have that shape.
+static bool backward_data_as_forward(const BackwardDataProblem &b, Problem *pr) {
+    if (!b.bf16 || b.u != 1 || b.v != 1 || b.R * b.S != 9 || b.K % 16 != 0 || b.dys[1] != 1) return false;
+    if (b.pad_h > b.R - 1 || b.pad_w > b.S - 1) return false;
+    *pr = Problem{};
+    pr->bf16 = true;
+    pr->vec = 8;
+    pr->mode_mask = (1u << 4) | (1u << 5);
+    ConvKernelParams &k = pr->kp;
+    k.x_bytes = (uint32_t)b.dy_bytes;
+    k.w_bytes = (uint32_t)b.w_bytes;
+    k.y_bytes = (uint32_t)b.dx_bytes;
+    k.N = b.N; k.C = b.K; k.H = b.P; k.W = b.Q;
+    k.K = b.C; k.R = b.R; k.S = b.S; k.P = b.H; k.Q = b.W;
+    k.pad_h = b.R - 1 - b.pad_h; k.pad_w = b.S - 1 - b.pad_w; k.u = 1; k.v = 1;
+    k.flip = b.flip ? 0 : 1;
+    k.RS = 9; k.CRS = b.K * 9; k.PQ = b.H * b.W; k.NPQ = b.N * k.PQ;
+    k.Wp = k.W + 2 * k.pad_w;
+    k.HpWp = (int)std::min<long long>((long long)(k.H + 2 * k.pad_h) * k.Wp, 0x7fffffff);
+    if (!magic_for((uint32_t)k.Wp, &k.mWp) || !magic_for((uint32_t)k.HpWp, &k.mHpWp)) return false;
+    if (!magic_for((uint32_t)k.PQ, &k.mPQ) || !magic_for((uint32_t)k.Q, &k.mQ) ||
+        !magic_for((uint32_t)k.RS, &k.mRS) || !magic_for((uint32_t)k.S, &k.mS))
+        return false;
+    k.wsRow = k.CRS; k.wsRed = k.RS; k.wTap0 = 0; k.wsTapR = k.S; k.wsTapS = 1;
+    k.xsN = (int)b.dys[0]; k.xsC = 1; k.xsH = (int)b.dys[2]; k.xsW = (int)b.dys[3];
+    k.ysN = (int)b.dxs[0]; k.ysK = (int)b.dxs[1]; k.ysP = (int)b.dxs[2]; k.ysQ = (int)b.dxs[3];
+    return true;
+}
+
 // ---- backward filter ------------------------------------------------------------------
 // dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x0[n,c,row(p,r),col(q,s)]: an implicit GEMM with rows
 // k, columns i = (c,r,s) and the reduction over j = (n,p,q).  The gathered operand is x
@@ -869,9 +902,11 @@ igcStatus igcGetConvolutionBackwardDataWorkspaceSize(igcHandle_t handle, igcFilt
                                                      igcTensorDescriptor_t dyDesc, igcConvolutionDescriptor_t convDesc,
                                                      igcTensorDescriptor_t dxDesc, size_t *sizeInBytes) {
     if (!handle || !sizeInBytes) return IGC_STATUS_BAD_PARAM;
-    const igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, nullptr);
+    BackwardDataProblem b;
+    const igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
-    *sizeInBytes = 0;
+    Problem pr;
+    *sizeInBytes = backward_data_as_forward(b, &pr) ? (size_t)b.w_bytes : 0;
     return IGC_STATUS_SUCCESS;
 }
 
@@ -879,14 +914,34 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
                                      igcTensorDescriptor_t dyDesc, const void *dy, igcConvolutionDescriptor_t convDesc,
                                      void *workSpace, size_t workSpaceSizeInBytes, const void *beta,
                                      igcTensorDescriptor_t dxDesc, void *dx) {
-    (void)workSpace;
-    (void)workSpaceSizeInBytes;
     if (!handle || !alpha || !beta || !w || !dy || !dx) return IGC_STATUS_BAD_PARAM;
     BackwardDataProblem b;
     igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
     const int es = b.bf16 ? 2 : 4;
     if ((uintptr_t)dy % es || (uintptr_t)w % es || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    // The forward pass over dy with the exchanged filter, when the shape allows and the caller
+    // lends room for that filter; else the general route below.
+    {
+        Problem pr;
+        int id = -1;
+        if (workSpace && (uintptr_t)workSpace % 16 == 0 && backward_data_as_forward(b, &pr) &&
+            workSpaceSizeInBytes >= (size_t)b.w_bytes &&
+            choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/((uintptr_t)dy % 16) == 0, &id) == IGC_STATUS_SUCCESS) {
+            igcConvolutionForwardPlan plan;
+            st = fill_plan(id, &pr, &plan);
+            if (st != IGC_STATUS_SUCCESS) return st;
+            pr.kp.x = dy;
+            pr.kp.w = workSpace;
+            pr.kp.y = dx;
+            pr.kp.alpha = *static_cast<const float *>(alpha);
+            pr.kp.beta = *static_cast<const float *>(beta);
+            if (getenv("IGCONV_DEBUG")) fprintf(stderr, "igconv: backward data as a forward pass, kernel %s\n", kernel_info(id)->name);
+            if (launch_filter_exchange9(w, workSpace, b.K, b.C, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+            if (kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+            return IGC_STATUS_SUCCESS;
+        }
+    }
     // plan every phase before the first launch, so that a rejected problem launches nothing
     struct Launch { Problem pr; int id; int grid; };
     std::vector<Launch> launches;

@@ -39,6 +39,10 @@ extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGro
 int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
                      void *stream);
 
+// wt[c][k][t] = w[k][c][t] for 2-byte elements, t < 9 (the filter with its first two
+// dimensions exchanged, each pair's nine taps kept in order); returns the runtime's error code.
+int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream);
+
 int kernel_count();
 const KernelInfo *kernel_info(int id);  // nullptr when out of range
 

@@ -48,4 +48,34 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
+// wt[c][k][t] = w[k][c][t] for 2-byte elements (t: the taps of one (k,c) pair, kept in order):
+// a workgroup moves a block of 16 k x 16 c through LDS so that both sides are read and
+// written in runs of 16*taps elements.  Host guarantees sizes below 2^31.
+template <int taps>
+__global__ __launch_bounds__(256) void igconv_filter_exchange_kernel(const uint16_t *w, uint16_t *wt, int K, int C) {
+    __shared__ uint16_t blk[16 * 16 * taps];
+    const int k0 = blockIdx.x * 16, c0 = blockIdx.y * 16;
+    const int run = 16 * taps, total = 16 * run;
+    for (int e = threadIdx.x; e < total; e += 256) {
+        const int k = e / run, rem = e - k * run;     // rem = c_local * taps + t
+        const int c = rem / taps;
+        uint16_t v = 0;
+        if (k0 + k < K && c0 + c < C) v = w[((size_t)(k0 + k) * C + c0) * taps + rem];
+        blk[e] = v;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < total; e += 256) {
+        const int c = e / run, rem = e - c * run;     // rem = k_local * taps + t
+        const int k = rem / taps, t = rem - k * taps;
+        if (k0 + k < K && c0 + c < C) wt[((size_t)(c0 + c) * K + k0) * taps + rem] = blk[(k * 16 + c) * taps + t];
+    }
+}
+
+int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream) {
+    void *argv[] = {&w, &wt, &K, &C};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<9>),
+                                            dim3((K + 15) / 16, (C + 15) / 16), dim3(256), argv, 0,
+                                            static_cast<hipStream_t>(stream)));
+}
+
 }  // namespace igc

@@ -184,9 +184,10 @@ def layout_strides(shape, layout):
 
 
 class GpuBackwardData:
-    """One backward-data problem set up on the GPU through the C ABI."""
+    """One backward-data problem set up on the GPU through the C ABI.  ``workspace``: "full"
+    (what the library asks for), "none", or a number of bytes."""
 
-    def __init__(self, dy, w, hw, pad, stride, mode, dtype="f32", dx_layout="NCHW"):
+    def __init__(self, dy, w, hw, pad, stride, mode, dtype="f32", dx_layout="NCHW", workspace="full"):
         self.handle = ig.Handle()
         N, K, P, Q = dy.shape
         _, C, R, S = w.shape
@@ -199,24 +200,32 @@ class GpuBackwardData:
         shape = (N, C, hw[0], hw[1])
         self.out = GuardedOutput(shape, layout_strides(shape, dx_layout))
         self.dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, self.out.strides)
-        assert ig.get_backward_data_workspace_size(self.handle, self.wdesc, self.dydesc, self.conv, self.dxdesc) == 0
+        self.asked = ig.get_backward_data_workspace_size(self.handle, self.wdesc, self.dydesc, self.conv, self.dxdesc)
+        self.ws_bytes = self.asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
+        self.ws = GuardedOutput((1, 1, 1, max((self.ws_bytes + 3) // 4, 1)), (0, 0, 0, 1))
+        self.ws.prefill(value=float("nan"))
 
     def launch(self, alpha=1.0, beta=0.0):
         self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
         st = ig.convolution_backward_data(self.handle, alpha, self.wdesc, self.w_dev.data_ptr(), self.dydesc,
-                                          self.dy_dev.data_ptr(), self.conv, beta, self.dxdesc, self.out.ptr)
+                                          self.dy_dev.data_ptr(), self.conv, beta, self.dxdesc, self.out.ptr,
+                                          self.ws.ptr if self.ws_bytes else 0, self.ws_bytes)
         ig.check(st, "igcConvolutionBackwardData")
 
 
 def run_backward_data(dy, w, hw, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_CORRELATION, alpha=1.0, beta=0.0,
-                      dx_old=None, dtype="f32", dx_layout="NCHW"):
-    """One igcConvolutionBackwardData call; returns dx as float64, logical (N,C,H,W)."""
-    g = GpuBackwardData(dy, w, hw, pad, stride, mode, dtype, dx_layout)
+                      dx_old=None, dtype="f32", dx_layout="NCHW", workspace="full", asked=None):
+    """One igcConvolutionBackwardData call; returns dx as float64, logical (N,C,H,W).  ``asked``:
+    a list that receives the workspace size the library asked for."""
+    g = GpuBackwardData(dy, w, hw, pad, stride, mode, dtype, dx_layout, workspace)
+    if asked is not None:
+        asked.append(g.asked)
     if dx_old is not None:
         g.out.prefill(old=dx_old)
     else:
         g.out.prefill(value=float("nan"))
     g.launch(alpha, beta)
+    g.ws.result()   # (guard bands of the workspace)
     return g.out.result()
 
 

@@ -40,7 +40,8 @@ BWD_PROBLEMS = [
 ]
 
 
-def _check_bd(prob, dtype, mode, alpha=1.0, beta=0.0, dx_layout="NCHW", dy_layout="NCHW", seed=0):
+def _check_bd(prob, dtype, mode, alpha=1.0, beta=0.0, dx_layout="NCHW", dy_layout="NCHW", seed=0, workspace="full",
+              asked=None):
     gu = _gpu()
     N, C, H, W, K, R, S, pad, stride = prob
     P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
@@ -48,7 +49,7 @@ def _check_bd(prob, dtype, mode, alpha=1.0, beta=0.0, dx_layout="NCHW", dy_layou
     w = _rnd(seed + 2, (K, C, R, S), dtype)
     dx_old = _rnd(seed + 3, (N, C, H, W), "f32") if beta != 0.0 else None
     print("backward data", prob, dtype, mode, alpha, beta, dx_layout, dy_layout, flush=True)
-    got = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, alpha, beta, dx_old, dtype, dx_layout)
+    got = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, alpha, beta, dx_old, dtype, dx_layout, workspace, asked)
     want = oc.conv_backward_data(dy, w, (H, W), pad=pad, stride=stride, mode=mode, alpha=alpha, beta=beta, dx_old=dx_old)
     assert got.shape == want.shape
     assert np.all(np.isfinite(got)), "non-finite output (NaN prefill leaked or garbage)"
@@ -75,6 +76,38 @@ def test_backward_data_accumulates():
     for prob in (BWD_PROBLEMS[1], BWD_PROBLEMS[4], BWD_PROBLEMS[8]):
         _check_bd(prob, "f32", 1, alpha=0.5, beta=-1.5)
         _check_bd(prob, "f32", 0, alpha=2.0, beta=1.0, dx_layout="NHWC")
+
+
+# bf16, unit stride, nine taps, dy with contiguous channels (K a multiple of 16): the library asks
+# for room for the filter with k and c exchanged and runs the forward pass's channel-vector
+# kernels over dy.  N, C, H, W, K, R, S, pad, stride
+BWD_AS_FORWARD = [
+    (2, 16, 9, 11, 16, 3, 3, (1, 1), (1, 1)),
+    (3, 40, 14, 13, 144, 3, 3, (1, 1), (1, 1)),      # C not a multiple of the exchange block, several row tiles
+    (2, 5, 12, 10, 32, 3, 3, (0, 0), (1, 1)),        # pad 0 becomes "full" padding of dy
+    (2, 24, 8, 9, 48, 3, 3, (2, 2), (1, 1)),         # "full" padding becomes pad 0
+    (2, 7, 6, 20, 32, 1, 9, (0, 3), (1, 1)),         # nine taps in a row
+    (1, 130, 28, 28, 64, 3, 3, (1, 0), (1, 1)),      # unequal pads, 130 rows
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+@pytest.mark.parametrize("prob", BWD_AS_FORWARD, ids=[str(i) for i in range(len(BWD_AS_FORWARD))])
+def test_backward_data_bf16_channel_vectors(prob, mode):
+    N, C, H, W, K, R, S, pad, stride = prob
+    for dx_layout in ("NHWC", "NCHW"):
+        asked = []
+        _check_bd(prob, "bf16", mode, dx_layout=dx_layout, dy_layout="NHWC", seed=7, asked=asked)
+        assert asked == [K * C * 9 * 2]
+    # the same problem without the workspace (general route), and with one that is too small
+    _check_bd(prob, "bf16", mode, dx_layout="NHWC", dy_layout="NHWC", seed=7, workspace="none")
+    _check_bd(prob, "bf16", mode, dx_layout="NHWC", dy_layout="NHWC", seed=7, workspace=K * C * 9 * 2 - 2)
+    _check_bd(prob, "bf16", mode, alpha=-0.5, beta=2.0, dx_layout="NHWC", dy_layout="NHWC", seed=8)
+    # shapes that do not qualify ask for nothing
+    asked = []
+    _check_bd(prob, "bf16", mode, dy_layout="NCHW", seed=7, asked=asked)
+    _check_bd(prob, "f32", mode, dy_layout="NHWC", seed=7, asked=asked)
+    assert asked == [0, 0]
 
 
 def test_backward_data_is_the_transpose_of_forward_on_the_gpu():

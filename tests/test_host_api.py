@@ -190,6 +190,19 @@ def test_backward_passes_validate_before_any_gpu_call():
     h = ig.Handle()
     x, w, c, y = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 1))
     assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 0
+    # bf16, unit stride, nine taps, K in sixteens, dy with unit channel stride: room for the
+    # filter with k and c exchanged; any of these conditions missing: none
+    def bd_ws(K=32, stride=(1, 1), dt=ig.IGC_DATA_BFLOAT16, nhwc=True, R=3, S=3, pad=(1, 1)):
+        xb, wb, cb, yb = _descs(N=2, C=5, H=9, W=8, K=K, R=R, S=S, pad=pad, stride=stride, dt=dt)
+        n, k, p_, q = yb.get()[1]
+        yb = ig.TensorDescriptor().set(dt, n, k, p_, q, (p_ * q * k, 1, q * k, k) if nhwc else (k * p_ * q, p_ * q, q, 1))
+        dxb = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *xb.get()[1], xb.get()[2])
+        return ig.get_backward_data_workspace_size(h, wb, yb, cb, dxb)
+    assert bd_ws() == 32 * 5 * 9 * 2
+    assert bd_ws(pad=(0, 2)) == 32 * 5 * 9 * 2
+    assert bd_ws(R=1, S=9, pad=(0, 4)) == 32 * 5 * 9 * 2
+    assert bd_ws(K=24) == 0 and bd_ws(stride=(1, 2)) == 0 and bd_ws(dt=ig.IGC_DATA_FLOAT) == 0
+    assert bd_ws(nhwc=False) == 0 and bd_ws(R=5, S=5, pad=(2, 2)) == 0
     K, C, R, S = 4, 3, 3, 3
     ws = ig.get_backward_filter_workspace_size(h, x, y, c, w)
     assert ws % (K * C * R * S * 4) == 0
