@@ -176,3 +176,99 @@ int pointwise_oracle_pooling_forward(int mode, const float *x, const long long *
                 }
     return 0;
 }
+
+/* Softmax backward.  With y the forward result of a group and dy the gradient with respect
+ * to y, the Jacobian dy_j/dx_i = y_j (delta_ij - y_i) gives
+ *     dx_i = y_i * (dy_i - sum_j dy_j y_j),   j over the group (see the forward function). */
+int pointwise_oracle_softmax_backward(int mode, const float *y, const long long *ys,
+                                      const float *dy, const long long *dys,
+                                      int N, int C, int H, int W, double alpha, double beta,
+                                      const double *dx_old, double *dx, const long long *dxs)
+{
+    if (mode < 0 || mode > 1 || N < 1 || C < 1 || H < 1 || W < 1) return -1;
+    if (beta != 0.0 && dx_old == NULL) return -2;
+    for (int n = 0; n < N; ++n) {
+        int groups_h = mode == SOFTMAX_INSTANCE ? 1 : H, groups_w = mode == SOFTMAX_INSTANCE ? 1 : W;
+        for (int gh = 0; gh < groups_h; ++gh)
+            for (int gw = 0; gw < groups_w; ++gw) {
+                int h0 = mode == SOFTMAX_INSTANCE ? 0 : gh, h1 = mode == SOFTMAX_INSTANCE ? H : gh + 1;
+                int w0 = mode == SOFTMAX_INSTANCE ? 0 : gw, w1 = mode == SOFTMAX_INSTANCE ? W : gw + 1;
+                double dot = 0.0;
+                for (int c = 0; c < C; ++c)
+                    for (int h = h0; h < h1; ++h)
+                        for (int w = w0; w < w1; ++w)
+                            dot += (double)dy[at(dys, n, c, h, w)] * (double)y[at(ys, n, c, h, w)];
+                for (int c = 0; c < C; ++c)
+                    for (int h = h0; h < h1; ++h)
+                        for (int w = w0; w < w1; ++w) {
+                            long long o = at(dxs, n, c, h, w);
+                            double v = alpha * ((double)y[at(ys, n, c, h, w)] * ((double)dy[at(dys, n, c, h, w)] - dot));
+                            if (beta != 0.0) v += beta * dx_old[o];
+                            dx[o] = v;
+                        }
+            }
+    }
+    return 0;
+}
+
+/* Pooling backward: the gradient dy of every window goes back to the input elements the
+ * window's value came from.  AVERAGE: each in-image element of the window receives
+ * dy / (number of in-image elements) - the transpose of the forward map.  MAX: the
+ * in-image element holding the maximum receives dy; among equal maxima the first in scan
+ * order (rows, then columns, of the window).  An element covered by several windows sums
+ * their contributions.  `scratch` holds N*C*H*W doubles (packed N,C,H,W) for the raw sum. */
+int pointwise_oracle_pooling_backward(int mode, const float *x, const long long *xs,
+                                      const float *dy, const long long *dys,
+                                      int N, int C, int H, int W, int win_h, int win_w,
+                                      int pad_h, int pad_w, int u, int v, double alpha, double beta,
+                                      const double *dx_old, double *dx, const long long *dxs, int P, int Q,
+                                      double *scratch)
+{
+    if (mode < 0 || mode > 1 || N < 1 || C < 1 || H < 1 || W < 1) return -1;
+    if (win_h < 1 || win_w < 1 || u < 1 || v < 1 || pad_h < 0 || pad_w < 0) return -4;
+    if (pad_h >= win_h || pad_w >= win_w) return -5;
+    if (H + 2 * pad_h < win_h || W + 2 * pad_w < win_w) return -6;
+    if (P != (H + 2 * pad_h - win_h) / u + 1 || Q != (W + 2 * pad_w - win_w) / v + 1) return -7;
+    if (beta != 0.0 && dx_old == NULL) return -2;
+    if (scratch == NULL) return -3;
+    for (long long i = 0; i < (long long)N * C * H * W; ++i) scratch[i] = 0.0;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c) {
+            double *g = scratch + ((long long)n * C + c) * H * W;
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    double grad = (double)dy[at(dys, n, c, p, q)];
+                    double m = -INFINITY;
+                    int count = 0, mh = -1, mw = -1;
+                    for (int r = 0; r < win_h; ++r)
+                        for (int s = 0; s < win_w; ++s) {
+                            int h = p * u + r - pad_h, w = q * v + s - pad_w;
+                            if (h < 0 || h >= H || w < 0 || w >= W) continue;
+                            double val = (double)x[at(xs, n, c, h, w)];
+                            if (count == 0 || val > m) { m = val; mh = h; mw = w; }
+                            ++count;
+                        }
+                    if (count == 0) return -8;
+                    if (mode == POOL_MAX) {
+                        g[mh * W + mw] += grad;
+                    } else {
+                        for (int r = 0; r < win_h; ++r)
+                            for (int s = 0; s < win_w; ++s) {
+                                int h = p * u + r - pad_h, w = q * v + s - pad_w;
+                                if (h < 0 || h >= H || w < 0 || w >= W) continue;
+                                g[h * W + w] += grad / count;
+                            }
+                    }
+                }
+        }
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int w = 0; w < W; ++w) {
+                    long long o = at(dxs, n, c, h, w);
+                    double val = alpha * scratch[(((long long)n * C + c) * H + h) * W + w];
+                    if (beta != 0.0) val += beta * dx_old[o];
+                    dx[o] = val;
+                }
+    return 0;
+}

@@ -123,3 +123,32 @@ def pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=
         ctypes.c_void_p(old_ptr), ctypes.c_void_p(y.ctypes.data), _strides(y), ctypes.c_int(P), ctypes.c_int(Q)),
         "pooling_forward")
     return y
+
+
+def softmax_backward(mode, y, dy, alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
+    y, dy = _f32(y), _f32(dy)
+    assert y.shape == dy.shape
+    dx, old_ptr, _keep = _out(y.shape, layout, dx_old, beta)
+    _check(_load().pointwise_oracle_softmax_backward(
+        ctypes.c_int(mode), ctypes.c_void_p(y.ctypes.data), _strides(y), ctypes.c_void_p(dy.ctypes.data), _strides(dy),
+        *[ctypes.c_int(d) for d in y.shape], ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(old_ptr),
+        ctypes.c_void_p(dx.ctypes.data), _strides(dx)), "softmax_backward")
+    return dx
+
+
+def pooling_backward(mode, x, dy, window, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
+    x, dy = _f32(x), _f32(dy)
+    N, C, H, W = x.shape
+    P = pooling_output_dim(H, window[0], pad[0], stride[0])
+    Q = pooling_output_dim(W, window[1], pad[1], stride[1])
+    assert dy.shape == (N, C, P, Q)
+    dx, old_ptr, _keep = _out((N, C, H, W), layout, dx_old, beta)
+    scratch = np.empty(N * C * H * W, dtype=np.float64)
+    _check(_load().pointwise_oracle_pooling_backward(
+        ctypes.c_int(mode), ctypes.c_void_p(x.ctypes.data), _strides(x), ctypes.c_void_p(dy.ctypes.data), _strides(dy),
+        *[ctypes.c_int(d) for d in x.shape],
+        ctypes.c_int(window[0]), ctypes.c_int(window[1]), ctypes.c_int(pad[0]), ctypes.c_int(pad[1]),
+        ctypes.c_int(stride[0]), ctypes.c_int(stride[1]), ctypes.c_double(alpha), ctypes.c_double(beta),
+        ctypes.c_void_p(old_ptr), ctypes.c_void_p(dx.ctypes.data), _strides(dx), ctypes.c_int(P), ctypes.c_int(Q),
+        ctypes.c_void_p(scratch.ctypes.data)), "pooling_backward")
+    return dx

@@ -150,3 +150,113 @@ def test_pooling_against_torch_and_identities():
                           po.pooling_forward(po.POOL_MAX, x, (3, 3), (1, 1), (2, 2)))
     with pytest.raises(ValueError):
         po.pooling_forward(po.POOL_MAX, x, (2, 2), pad=(2, 0))      # pad >= window
+
+
+# ---------------------------------------------------------------- backward forms of softmax and pooling
+def test_softmax_backward_closed_forms():
+    # two elements, x = (0, ln 3): y = (1/4, 3/4).  dy = (1, 0): dot = 1/4,
+    # dx = (1/4 * (1 - 1/4), 3/4 * (0 - 1/4)) = (3/16, -3/16)
+    y = np.array([0.25, 0.75], dtype=np.float32).reshape(1, 2, 1, 1)
+    dy = np.array([1.0, 0.0], dtype=np.float32).reshape(1, 2, 1, 1)
+    for mode in (po.SOFTMAX_CHANNEL, po.SOFTMAX_INSTANCE):
+        assert np.array_equal(po.softmax_backward(mode, y, dy).ravel(), [3 / 16, -3 / 16])
+    # the same two numbers along w: one group per image, but single-element groups per location
+    yw, dyw = y.reshape(1, 1, 1, 2), dy.reshape(1, 1, 1, 2)
+    assert np.array_equal(po.softmax_backward(po.SOFTMAX_INSTANCE, yw, dyw).ravel(), [3 / 16, -3 / 16])
+    assert np.array_equal(po.softmax_backward(po.SOFTMAX_CHANNEL, yw, dyw).ravel(), [0.25 * (1 - 0.25), 0.0])
+    # a uniform y = 1/n: dx_i = (dy_i - mean(dy)) / n; a constant dy: dx = 0 (y sums to one)
+    n = 8
+    yu = np.full((2, n, 1, 1), 1.0 / n, dtype=np.float32)
+    d = rnd(3, 2, n, 1, 1)
+    want = (d.astype(np.float64) - d.astype(np.float64).mean(axis=1, keepdims=True)) / n
+    assert np.allclose(po.softmax_backward(po.SOFTMAX_CHANNEL, yu, d), want, rtol=0, atol=1e-15)
+    ys = po.softmax_forward(po.SOFTMAX_CHANNEL, rnd(4, 2, 5, 3, 4)).astype(np.float32)
+    assert np.max(np.abs(po.softmax_backward(po.SOFTMAX_CHANNEL, ys, np.full_like(ys, 2.5)))) < 1e-6
+    # alpha, beta and layouts
+    old = rnd(5, 2, 5, 3, 4).astype(np.float64)
+    dd = rnd(6, 2, 5, 3, 4)
+    raw = po.softmax_backward(po.SOFTMAX_CHANNEL, ys, dd)
+    assert np.allclose(po.softmax_backward(po.SOFTMAX_CHANNEL, nhwc(ys), dd, alpha=2.0, beta=-0.5, dx_old=old, layout="NHWC"),
+                       2.0 * raw - 0.5 * old, rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("mode", [po.SOFTMAX_INSTANCE, po.SOFTMAX_CHANNEL])
+def test_softmax_backward_is_the_transposed_jacobian_of_forward(mode):
+    """Central differences of the (separately pinned) forward function, element by element:
+    dx_i = sum_j dy_j * d y_j / d x_i.  Inputs on a 1/64 grid and a step of 1/512 are exact in
+    fp32, so the only error is the O(step^2) truncation."""
+    rng = np.random.default_rng(11)
+    x = (rng.integers(-128, 128, size=(2, 3, 2, 2)) / 64.0).astype(np.float32)
+    dy = rnd(12, 2, 3, 2, 2)
+    y = po.softmax_forward(mode, x)
+    got = po.softmax_backward(mode, y.astype(np.float32), dy)
+    eps = 1.0 / 512
+    want = np.zeros(x.shape)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += eps
+        xm[idx] -= eps
+        dydx = (po.softmax_forward(mode, xp) - po.softmax_forward(mode, xm)) / (2 * eps)
+        want[idx] = np.sum(dydx * dy.astype(np.float64))
+    assert np.max(np.abs(got - want)) < 5e-6
+
+
+def test_pooling_backward_hand_cases():
+    x = np.arange(1, 17, dtype=np.float32).reshape(1, 1, 4, 4)
+    dy = np.array([[1.0, 2.0], [3.0, 4.0]], dtype=np.float32).reshape(1, 1, 2, 2)
+    # 2x2 windows, stride 2: each window's maximum is its bottom-right corner
+    mx = po.pooling_backward(po.POOL_MAX, x, dy, (2, 2), stride=(2, 2))[0, 0]
+    assert np.array_equal(mx, [[0, 0, 0, 0], [0, 1, 0, 2], [0, 0, 0, 0], [0, 3, 0, 4]])
+    av = po.pooling_backward(po.POOL_AVERAGE, x, dy, (2, 2), stride=(2, 2))[0, 0]
+    assert np.array_equal(av, np.kron(dy[0, 0], np.ones((2, 2))) / 4)
+    # 3x3, pad 1, stride 3 on 4x4: windows (0,0): rows/cols {0,1} (4 elements), (0,1): rows {0,1}, cols {2,3},
+    # (1,0): rows {2,3}, cols {0,1}, (1,1): rows/cols {2,3}; maxima at (1,1), (1,3), (3,1), (3,3)
+    mx = po.pooling_backward(po.POOL_MAX, x, dy, (3, 3), pad=(1, 1), stride=(3, 3))[0, 0]
+    assert np.array_equal(mx, [[0, 0, 0, 0], [0, 1, 0, 2], [0, 0, 0, 0], [0, 3, 0, 4]])
+    av = po.pooling_backward(po.POOL_AVERAGE, x, dy, (3, 3), pad=(1, 1), stride=(3, 3))[0, 0]
+    assert np.array_equal(av, np.kron(dy[0, 0], np.ones((2, 2))) / 4)
+    # overlapping windows (3 wide, stride 1, one row): x = (1, 5, 2, 4): windows {1,5,2} and {5,2,4} both
+    # pick the 5; averages: element 0 gets a/3, elements 1,2 get (a+b)/3, element 3 gets b/3
+    x1 = np.array([1, 5, 2, 4], dtype=np.float32).reshape(1, 1, 1, 4)
+    d1 = np.array([3.0, 6.0], dtype=np.float32).reshape(1, 1, 1, 2)
+    assert np.array_equal(po.pooling_backward(po.POOL_MAX, x1, d1, (1, 3)).ravel(), [0, 9, 0, 0])
+    assert np.array_equal(po.pooling_backward(po.POOL_AVERAGE, x1, d1, (1, 3)).ravel(), [1, 3, 3, 2])
+    # equal maxima: the first in scan order receives the gradient (all-equal data: the top-left in-image element)
+    c = np.full((1, 1, 4, 4), 7.0, dtype=np.float32)
+    mx = po.pooling_backward(po.POOL_MAX, c, dy, (3, 3), pad=(1, 1), stride=(3, 3))[0, 0]
+    assert np.array_equal(mx, [[1, 0, 2, 0], [0, 0, 0, 0], [3, 0, 4, 0], [0, 0, 0, 0]])
+    # all-negative data next to the zero border: the border never takes the gradient
+    mx = po.pooling_backward(po.POOL_MAX, -x, dy, (3, 3), pad=(1, 1), stride=(3, 3))[0, 0]
+    assert np.array_equal(mx, [[1, 0, 2, 0], [0, 0, 0, 0], [3, 0, 4, 0], [0, 0, 0, 0]])
+
+
+def test_pooling_backward_against_torch_autograd_and_the_transpose_identity():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(21)
+    # distinct values (a permutation), so that every maximum is unique
+    x = (rng.permutation(2 * 3 * 9 * 11).reshape(2, 3, 9, 11) / 16.0 - 10.0).astype(np.float32)
+    for win, pad, st in [((2, 2), (0, 0), (2, 2)), ((3, 3), (1, 1), (2, 2)), ((3, 2), (1, 0), (1, 3)), ((5, 5), (2, 2), (4, 4)),
+                         ((3, 3), (0, 0), (1, 1)), ((2, 2), (0, 0), (3, 3))]:
+        P, Q = po.pooling_output_dim(9, win[0], pad[0], st[0]), po.pooling_output_dim(11, win[1], pad[1], st[1])
+        dy = rnd(22, 2, 3, P, Q)
+        for mode in (po.POOL_MAX, po.POOL_AVERAGE):
+            xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+            if mode == po.POOL_MAX:
+                yt = torch.nn.functional.max_pool2d(xt, win, st, pad)
+            else:
+                yt = torch.nn.functional.avg_pool2d(xt, win, st, pad, count_include_pad=False)
+            yt.backward(torch.tensor(dy, dtype=torch.float64))
+            got = po.pooling_backward(mode, x, dy, win, pad, st)
+            assert np.allclose(got, xt.grad.numpy(), rtol=0, atol=1e-14), (win, pad, st, mode)
+            # every window hands out exactly its gradient
+            assert abs(got.sum() - dy.astype(np.float64).sum()) < 1e-10
+        # average pooling is linear: <forward(x), dy> = <x, backward(dy)>
+        lhs = np.sum(po.pooling_forward(po.POOL_AVERAGE, x, win, pad, st) * dy)
+        rhs = np.sum(po.pooling_backward(po.POOL_AVERAGE, x, dy, win, pad, st) * x)
+        assert abs(lhs - rhs) < 1e-9
+    # elements no window reaches (stride 3, 2x2 windows) get beta * old only
+    old = rnd(23, 2, 3, 9, 11).astype(np.float64)
+    dy = rnd(24, 2, 3, 3, 4)
+    got = po.pooling_backward(po.POOL_MAX, nhwc(x), dy, (2, 2), stride=(3, 3), alpha=2.0, beta=0.5, dx_old=old, layout="NHWC")
+    assert np.array_equal(got[:, :, 2::3, :], 0.5 * old[:, :, 2::3, :])
+    assert np.allclose(got, 2.0 * po.pooling_backward(po.POOL_MAX, x, dy, (2, 2), stride=(3, 3)) + 0.5 * old, atol=1e-15)
