@@ -209,7 +209,14 @@ def run_other_functions(steps, warmup):
         ms = timed(lambda: ig.check(ig.softmax_forward(h, mode, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), nm))
         err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.softmax_forward(mode, x[:2]))
         record(nm, shape, 2 * x.nbytes, ms, err)
-        del xt, yt
+        dy = rng.uniform(-1, 1, size=shape).astype(np.float32)
+        dyt, dyd = dev(dy)
+        dxt, dxd = dev(np.zeros(shape, np.float32))
+        ms = timed(lambda: ig.check(ig.softmax_backward(h, mode, 1.0, yd, yt.data_ptr(), dyd, dyt.data_ptr(), 0.0, dxd,
+                                                        dxt.data_ptr()), nm))
+        err = gu.rel_err(dxt[:2].cpu().numpy().astype(np.float64), po.softmax_backward(mode, yt[:2].cpu().numpy(), dy[:2]))
+        record(nm + ", backward", shape, 3 * x.nbytes, ms, err)
+        del xt, yt, dyt, dxt
 
     # bias addition and rectifier fused into the convolution's epilogue, against the three calls
     # one after the other, on the mid-layer workload
@@ -252,7 +259,15 @@ def run_other_functions(steps, warmup):
         ms = timed(lambda: ig.check(ig.pooling_forward(h, pool, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), nm))
         err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.pooling_forward(mode, x[:2], (3, 3), (0, 0), (2, 2)))
         record("pooling 3x3 stride 2 " + nm, shape, x.nbytes + yt.numel() * 4, ms, err)
-        del yt
+        dy = rng.uniform(-1, 1, size=oshape).astype(np.float32)
+        dyt, dyd = dev(dy)
+        dxt, dxd = dev(np.zeros(shape, np.float32))
+        ms = timed(lambda: ig.check(ig.pooling_backward(h, pool, 1.0, dyd, dyt.data_ptr(), xd, xt.data_ptr(), 0.0, dxd,
+                                                        dxt.data_ptr()), nm))
+        err = gu.rel_err(dxt[:2].cpu().numpy().astype(np.float64), po.pooling_backward(mode, x[:2], dy[:2], (3, 3), (0, 0), (2, 2)))
+        # (the average does not read x)
+        record("pooling 3x3 stride 2 " + nm + ", backward", shape, (2 if mode == ig.IGC_POOLING_MAX else 1) * x.nbytes + dy.nbytes, ms, err)
+        del yt, dyt, dxt
     return out
 
 

@@ -329,6 +329,15 @@ igcStatus igcSoftmaxForward(igcHandle_t handle, igcSoftmaxMode mode, const void 
                             igcTensorDescriptor_t xDesc, const void *x,
                             const void *beta, igcTensorDescriptor_t yDesc, void *y);
 
+/* Softmax backward (Section 2: every routine has a backward form): with y the forward
+ * result and dy the gradient with respect to it,
+ *   dx_i = alpha * y_i * (dy_i - sum over the group of dy_j * y_j) + beta * dx_i,
+ * the groups as in igcSoftmaxForward.  y, dy, dx have equal dimensions. */
+igcStatus igcSoftmaxBackward(igcHandle_t handle, igcSoftmaxMode mode, const void *alpha,
+                             igcTensorDescriptor_t yDesc, const void *y,
+                             igcTensorDescriptor_t dyDesc, const void *dy,
+                             const void *beta, igcTensorDescriptor_t dxDesc, void *dx);
+
 /* Pooling descriptor: window size, zero border on each side (pad < window), stride. */
 igcStatus igcCreatePoolingDescriptor(igcPoolingDescriptor_t *desc);
 igcStatus igcDestroyPoolingDescriptor(igcPoolingDescriptor_t desc);
@@ -348,6 +357,18 @@ igcStatus igcGetPooling2dForwardOutputDim(igcPoolingDescriptor_t poolDesc,
 igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc, const void *alpha,
                             igcTensorDescriptor_t xDesc, const void *x,
                             const void *beta, igcTensorDescriptor_t yDesc, void *y);
+
+/* Pooling backward: dx = alpha * (sum over the windows covering an input element of that
+ * window's share of dy) + beta * dx.  Average: every in-image element of a window receives
+ * dy / (number of in-image elements).  Maximum: the in-image element holding the window's
+ * maximum receives dy, the first in scan order (rows, then columns) among equal ones; the
+ * maximum is found again from the forward INPUT x, so the forward result is not needed.
+ * dy has the dimensions igcGetPooling2dForwardOutputDim gives for xDesc; dx those of x.
+ * Input elements no window reaches receive beta * dx.  Deterministic (no atomics). */
+igcStatus igcPoolingBackward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc, const void *alpha,
+                             igcTensorDescriptor_t dyDesc, const void *dy,
+                             igcTensorDescriptor_t xDesc, const void *x,
+                             const void *beta, igcTensorDescriptor_t dxDesc, void *dx);
 
 /* ---- introspection and tuning (host only; no GPU call) ----------------------------
  * The launch plan the library derives for a problem: the tile of the lowered

@@ -341,6 +341,134 @@ __global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), ybuf, yoff * 4u, 0, 0);
 }
 
+// ---- softmax backward --------------------------------------------------------------------
+// dx_i = y_i * (dy_i - sum_j dy_j y_j), j over the group (Jacobian of the softmax applied
+// to dy).  Same decomposition as forward: two passes, the first for the dot product.
+struct SoftmaxBwdArgs {
+    View v;            // tensor 0: y (ordering key), 1: dx, 2: dy
+    uint32_t count, C;
+    uint32_t sC[3];    // CHANNEL: channel strides of y, dx, dy; INSTANCE: image strides
+    float alpha, beta;
+    const float *y, *dy;
+    float *dx;
+};
+
+__global__ __launch_bounds__(256) void igconv_softmax_bwd_channel_kernel(const SoftmaxBwdArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.count) return;
+    uint32_t off[3];
+    offsets_of<3>(a.v, idx, 1u, off);
+    const float *y = a.y + off[0], *dy = a.dy + off[2];
+    float *dx = a.dx + off[1];
+    float dot = 0.f;
+    for (uint32_t c = 0; c < a.C; ++c) dot += dy[c * a.sC[2]] * y[c * a.sC[0]];
+    for (uint32_t c = 0; c < a.C; ++c) {
+        float r = a.alpha * (y[c * a.sC[0]] * (dy[c * a.sC[2]] - dot));
+        if (a.beta != 0.f) r += a.beta * dx[c * a.sC[1]];
+        dx[c * a.sC[1]] = r;
+    }
+}
+
+__global__ __launch_bounds__(256) void igconv_softmax_bwd_instance_kernel(const SoftmaxBwdArgs a) {
+    __shared__ float sh[4];
+    const float *y = a.y + (size_t)blockIdx.x * a.sC[0], *dy = a.dy + (size_t)blockIdx.x * a.sC[2];
+    float *dx = a.dx + (size_t)blockIdx.x * a.sC[1];
+    float dot = 0.f;
+    for (uint32_t i = threadIdx.x; i < a.count; i += 256u) {
+        uint32_t off[3];
+        offsets_of<3>(a.v, i, 1u, off);
+        dot += dy[off[2]] * y[off[0]];
+    }
+    for (int d = 32; d >= 1; d >>= 1) dot += __shfl_xor(dot, d);
+    if ((threadIdx.x & 63u) == 0u) sh[threadIdx.x >> 6] = dot;
+    __syncthreads();
+    dot = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    for (uint32_t i = threadIdx.x; i < a.count; i += 256u) {
+        uint32_t off[3];
+        offsets_of<3>(a.v, i, 1u, off);
+        float r = a.alpha * (y[off[0]] * (dy[off[2]] - dot));
+        if (a.beta != 0.f) r += a.beta * dx[off[1]];
+        dx[off[1]] = r;
+    }
+}
+
+// ---- pooling backward ---------------------------------------------------------------------
+// One thread per input element (n,c,h,w), ordered by dx's strides; it visits the windows that
+// cover it (at most ceil(win/stride) per axis) in order and sums their contributions, so the
+// result does not depend on scheduling.  AVERAGE: dy / (in-image elements of the window).
+// MAX: dy when this element is the window's maximum and no element before it in scan order
+// (rows, then columns) equals it.
+struct PoolBwdArgs {
+    View v;          // input (n,c,h,w) ordered by dx's strides, nothing merged; tensor 0: dx
+    uint32_t count;
+    int mode, H, W, P, Q, win_h, win_w, pad_h, pad_w, u, v_;
+    uint32_t xs[4], dys[4];
+    uint32_t x_bytes, dy_bytes, dx_bytes;
+    float alpha, beta;
+    float *dx;
+    const float *x, *dy;
+};
+
+__global__ __launch_bounds__(256) void igconv_pooling_bwd_kernel(const PoolBwdArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.count) return;
+    uint32_t coord[4] = {0, 0, 0, 0}, dxoff = 0, rem = idx;
+    for (int d = a.v.rank - 1; d >= 0; --d) {
+        uint32_t i;
+        if (d == 0) {
+            i = rem;
+        } else {
+            const uint32_t q = mdiv(rem, a.v.mdim[d]);
+            i = rem - q * a.v.dim[d];
+            rem = q;
+        }
+        coord[a.v.which[d]] = i;
+        dxoff += i * a.v.stride[0][d];
+    }
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t dybuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.dy), 0, a.dy_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t dxbuf = __builtin_amdgcn_make_buffer_rsrc(a.dx, 0, a.dx_bytes, 0x00020000u);
+    const int h = (int)coord[2], w = (int)coord[3];
+    // windows p with p*u - pad <= h <= p*u - pad + win - 1, inside [0, P)
+    const int th = h + a.pad_h - (a.win_h - 1), tw = w + a.pad_w - (a.win_w - 1);
+    const int p_lo = th <= 0 ? 0 : (th + a.u - 1) / a.u, p_hi = min(a.P - 1, (h + a.pad_h) / a.u);
+    const int q_lo = tw <= 0 ? 0 : (tw + a.v_ - 1) / a.v_, q_hi = min(a.Q - 1, (w + a.pad_w) / a.v_);
+    const uint32_t xplane = coord[0] * a.xs[0] + coord[1] * a.xs[1];
+    const uint32_t dyplane = coord[0] * a.dys[0] + coord[1] * a.dys[1];
+    float own = 0.f;
+    if (a.mode == IGC_POOLING_MAX)
+        own = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                  xbuf, (xplane + (uint32_t)h * a.xs[2] + (uint32_t)w * a.xs[3]) * 4u, 0, 0));
+    float acc = 0.f;
+    for (int p = p_lo; p <= p_hi; ++p) {
+        // the in-image rows [r0, r1) and columns [c0, c1) of the window, as image coordinates
+        const int r0 = max(p * a.u - a.pad_h, 0), r1 = min(p * a.u - a.pad_h + a.win_h, a.H);
+        for (int q = q_lo; q <= q_hi; ++q) {
+            const int c0 = max(q * a.v_ - a.pad_w, 0), c1 = min(q * a.v_ - a.pad_w + a.win_w, a.W);
+            const float g = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                dybuf, (dyplane + (uint32_t)p * a.dys[2] + (uint32_t)q * a.dys[3]) * 4u, 0, 0));
+            if (a.mode == IGC_POOLING_MAX) {
+                bool mine = true;
+                for (int r = r0; r < r1; ++r) {
+                    const uint32_t row = xplane + (uint32_t)r * a.xs[2];
+                    for (int c = c0; c < c1; ++c) {
+                        const float val = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                            xbuf, (row + (uint32_t)c * a.xs[3]) * 4u, 0, 0));
+                        const bool before = r < h || (r == h && c < w);
+                        if (before ? val >= own : val > own) mine = false;
+                    }
+                }
+                if (mine) acc += g;
+            } else {
+                acc += g / (float)((r1 - r0) * (c1 - c0));
+            }
+        }
+    }
+    float r = a.alpha * acc;
+    if (a.beta != 0.f) r += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dxbuf, dxoff * 4u, 0, 0));
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), dxbuf, dxoff * 4u, 0, 0);
+}
+
 // ---- host side ---------------------------------------------------------------------------
 template <class Kernel, class Args>
 igcStatus launch(Kernel kernel, const char *what, const Args &args, uint32_t blocks, void *stream) {
@@ -594,6 +722,87 @@ igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc,
     if (a.win_h == 3 && a.win_w == 3) return launch(&igconv_pooling_kernel<3, 3>, "igconv_pooling_kernel", a, blocks, handle->stream);
     if (a.win_h == 2 && a.win_w == 2) return launch(&igconv_pooling_kernel<2, 2>, "igconv_pooling_kernel", a, blocks, handle->stream);
     return launch(&igconv_pooling_kernel<0, 0>, "igconv_pooling_kernel", a, blocks, handle->stream);
+}
+
+igcStatus igcSoftmaxBackward(igcHandle_t handle, igcSoftmaxMode mode, const void *alpha, igcTensorDescriptor_t yDesc,
+                             const void *y, igcTensorDescriptor_t dyDesc, const void *dy, const void *beta,
+                             igcTensorDescriptor_t dxDesc, void *dx) {
+    if (!handle || !alpha || !beta || !y || !dy || !dx) return IGC_STATUS_BAD_PARAM;
+    if (mode != IGC_SOFTMAX_MODE_INSTANCE && mode != IGC_SOFTMAX_MODE_CHANNEL) return IGC_STATUS_BAD_PARAM;
+    igcStatus st = check_float_tensor(yDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(dyDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(dxDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (!same_dims(yDesc, dxDesc) || !same_dims(dyDesc, dxDesc)) return IGC_STATUS_BAD_PARAM;
+    if ((uintptr_t)y % 4 || (uintptr_t)dy % 4 || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    SoftmaxBwdArgs a{};
+    a.alpha = *static_cast<const float *>(alpha);
+    a.beta = *static_cast<const float *>(beta);
+    a.y = static_cast<const float *>(y);
+    a.dy = static_cast<const float *>(dy);
+    a.dx = static_cast<float *>(dx);
+    a.C = (uint32_t)yDesc->dim[1];
+    // the group's dimension(s) taken out: the channel (per location) or nothing but the image
+    // index (per image); the rest ordered by y's strides
+    const int out_dim = mode == IGC_SOFTMAX_MODE_CHANNEL ? 1 : 0;
+    long long stride[kMaxTensors][4] = {};
+    int dim[4];
+    for (int d = 0; d < 4; ++d) {
+        dim[d] = d == out_dim ? 1 : yDesc->dim[d];
+        stride[0][d] = yDesc->stride[d];
+        stride[1][d] = dxDesc->stride[d];
+        stride[2][d] = dyDesc->stride[d];
+    }
+    a.v = make_view(dim, stride, 3, /*merge=*/true);
+    a.count = 1;
+    for (int i = 0; i < a.v.rank; ++i) a.count *= a.v.dim[i];
+    a.sC[0] = (uint32_t)yDesc->stride[out_dim];
+    a.sC[1] = (uint32_t)dxDesc->stride[out_dim];
+    a.sC[2] = (uint32_t)dyDesc->stride[out_dim];
+    if (mode == IGC_SOFTMAX_MODE_CHANNEL)
+        return launch(&igconv_softmax_bwd_channel_kernel, "igconv_softmax_bwd_channel_kernel", a, (a.count + 255u) / 256u,
+                      handle->stream);
+    return launch(&igconv_softmax_bwd_instance_kernel, "igconv_softmax_bwd_instance_kernel", a, (uint32_t)yDesc->dim[0],
+                  handle->stream);
+}
+
+igcStatus igcPoolingBackward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc, const void *alpha, igcTensorDescriptor_t dyDesc,
+                             const void *dy, igcTensorDescriptor_t xDesc, const void *x, const void *beta,
+                             igcTensorDescriptor_t dxDesc, void *dx) {
+    if (!handle || !alpha || !beta || !x || !dy || !dx || !poolDesc) return IGC_STATUS_BAD_PARAM;
+    if (!poolDesc->set) return IGC_STATUS_NOT_INITIALIZED;
+    igcStatus st = check_float_tensor(xDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(dyDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(dxDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int n, c, p, q;
+    st = igcGetPooling2dForwardOutputDim(poolDesc, xDesc, &n, &c, &p, &q);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (dyDesc->dim[0] != n || dyDesc->dim[1] != c || dyDesc->dim[2] != p || dyDesc->dim[3] != q) return IGC_STATUS_BAD_PARAM;
+    if (!same_dims(xDesc, dxDesc)) return IGC_STATUS_BAD_PARAM;
+    if ((uintptr_t)x % 4 || (uintptr_t)dy % 4 || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    PoolBwdArgs a{};
+    long long stride[kMaxTensors][4] = {};
+    for (int d = 0; d < 4; ++d) stride[0][d] = dxDesc->stride[d];
+    a.v = make_view(dxDesc->dim, stride, 1, /*merge=*/false);
+    a.count = (uint32_t)((long long)n * c * xDesc->dim[2] * xDesc->dim[3]);
+    a.mode = poolDesc->mode;
+    a.H = xDesc->dim[2]; a.W = xDesc->dim[3]; a.P = p; a.Q = q;
+    a.win_h = poolDesc->win_h; a.win_w = poolDesc->win_w;
+    a.pad_h = poolDesc->pad_h; a.pad_w = poolDesc->pad_w; a.u = poolDesc->u; a.v_ = poolDesc->v;
+    for (int d = 0; d < 4; ++d) {
+        a.xs[d] = (uint32_t)xDesc->stride[d];
+        a.dys[d] = (uint32_t)dyDesc->stride[d];
+    }
+    a.x_bytes = (uint32_t)(extent(xDesc->dim, xDesc->stride) * 4);
+    a.dy_bytes = (uint32_t)(extent(dyDesc->dim, dyDesc->stride) * 4);
+    a.dx_bytes = (uint32_t)(extent(dxDesc->dim, dxDesc->stride) * 4);
+    a.alpha = *static_cast<const float *>(alpha);
+    a.beta = *static_cast<const float *>(beta);
+    a.dx = static_cast<float *>(dx);
+    a.x = static_cast<const float *>(x);
+    a.dy = static_cast<const float *>(dy);
+    return launch(&igconv_pooling_bwd_kernel, "igconv_pooling_bwd_kernel", a, (a.count + 255u) / 256u, handle->stream);
 }
 
 }  // extern "C"

@@ -334,3 +334,22 @@ def run_pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, b
     out, ydesc = _output(shape, layout, y_old)
     ig.check(ig.pooling_forward(_handle(), pool, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcPoolingForward")
     return out.result()
+
+
+def run_softmax_backward(mode, y, dy, alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
+    yd, ydesc = _desc_for(y)
+    dyd, dydesc = _desc_for(dy)
+    out, dxdesc = _output(y.shape, layout, dx_old)
+    ig.check(ig.softmax_backward(_handle(), mode, alpha, ydesc, yd.data_ptr(), dydesc, dyd.data_ptr(), beta, dxdesc, out.ptr),
+             "igcSoftmaxBackward")
+    return out.result()
+
+
+def run_pooling_backward(mode, x, dy, window, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
+    xd, xdesc = _desc_for(x)
+    dyd, dydesc = _desc_for(dy)
+    pool = ig.PoolingDescriptor().set(mode, window[0], window[1], pad[0], pad[1], stride[0], stride[1])
+    out, dxdesc = _output(x.shape, layout, dx_old)
+    ig.check(ig.pooling_backward(_handle(), pool, alpha, dydesc, dyd.data_ptr(), xdesc, xd.data_ptr(), beta, dxdesc, out.ptr),
+             "igcPoolingBackward")
+    return out.result()

@@ -120,3 +120,43 @@ def test_pooling_forward(mode):
         close(gu.run_pooling_forward(mode, wl.with_layout(x, "NHWC"), win, pad, st, layout="NHWC"), want)
         old = rnd(16, *want.shape)
         close(gu.run_pooling_forward(mode, x, win, pad, st, 0.5, -1.0, old), po.pooling_forward(mode, x, win, pad, st, 0.5, -1.0, old))
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["instance", "channel"])
+def test_softmax_backward(mode):
+    gu = _gpu()
+    for shape in SHAPES + [(64, 1000, 1, 1), (2, 21, 33, 17)]:
+        y = po.softmax_forward(mode, rnd(31, *shape, lo=-4, hi=4)).astype(np.float32)
+        dy = rnd(32, *shape)
+        print("softmax backward", mode, shape, flush=True)
+        want = po.softmax_backward(mode, y, dy)
+        close(gu.run_softmax_backward(mode, y, dy), want)
+        close(gu.run_softmax_backward(mode, wl.with_layout(y, "NHWC"), dy, layout="NHWC"), want)
+        close(gu.run_softmax_backward(mode, y, wl.with_layout(dy, "NHWC")), want)
+        old = rnd(33, *shape)
+        close(gu.run_softmax_backward(mode, y, dy, 0.5, 2.0, old, "NHWC"), po.softmax_backward(mode, y, dy, 0.5, 2.0, old))
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["max", "average"])
+def test_pooling_backward(mode):
+    gu = _gpu()
+    cases = [((2, 3, 9, 11), (2, 2), (0, 0), (2, 2)), ((2, 3, 9, 11), (3, 3), (1, 1), (2, 2)),
+             ((1, 5, 13, 13), (3, 2), (1, 0), (1, 3)), ((3, 96, 27, 27), (3, 3), (0, 0), (2, 2)),
+             ((2, 4, 7, 7), (7, 7), (0, 0), (1, 1)), ((2, 4, 8, 8), (5, 5), (2, 2), (4, 4)), ((1, 1, 1, 1), (1, 1), (0, 0), (1, 1)),
+             ((2, 3, 10, 12), (3, 3), (0, 0), (1, 1)), ((2, 3, 11, 9), (2, 2), (0, 0), (3, 3)), ((1, 2, 6, 30), (1, 5), (0, 2), (1, 2))]
+    for shape, win, pad, st in cases:
+        x = rnd(35, *shape) - np.float32(5.0)
+        P, Q = po.pooling_output_dim(shape[2], win[0], pad[0], st[0]), po.pooling_output_dim(shape[3], win[1], pad[1], st[1])
+        dy = rnd(36, shape[0], shape[1], P, Q)
+        print("pooling backward", mode, shape, win, pad, st, flush=True)
+        want = po.pooling_backward(mode, x, dy, win, pad, st)
+        close(gu.run_pooling_backward(mode, x, dy, win, pad, st), want)
+        close(gu.run_pooling_backward(mode, wl.with_layout(x, "NHWC"), wl.with_layout(dy, "NHWC"), win, pad, st, layout="NHWC"), want)
+        old = rnd(37, *shape)
+        close(gu.run_pooling_backward(mode, x, dy, win, pad, st, 0.5, -1.0, old), po.pooling_backward(mode, x, dy, win, pad, st, 0.5, -1.0, old))
+    # equal maxima: data on a coarse grid (many ties inside every window); the first in scan order takes the gradient
+    x = np.round(rnd(38, 2, 3, 12, 14)).astype(np.float32)
+    for win, pad, st in [((3, 3), (1, 1), (2, 2)), ((2, 2), (0, 0), (1, 1)), ((4, 3), (2, 1), (2, 1))]:
+        P, Q = po.pooling_output_dim(12, win[0], pad[0], st[0]), po.pooling_output_dim(14, win[1], pad[1], st[1])
+        dy = rnd(39, 2, 3, P, Q)
+        close(gu.run_pooling_backward(mode, x, dy, win, pad, st), po.pooling_backward(mode, x, dy, win, pad, st))

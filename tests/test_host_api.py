@@ -281,6 +281,18 @@ def test_other_functions_validate_before_any_gpu_call():
     xp = t(2, 3, 9, 11)
     pf = lambda yd: L.igcPoolingForward(h.ptr, pool.ptr, ctypes.byref(one), xp.ptr, fake, ctypes.byref(one), yd.ptr, fake)
     assert pf(t(2, 3, 5, 5)) == ig.IGC_STATUS_BAD_PARAM                          # y is not (2,3,5,4)
+    # backward forms: dimensions of every tensor are checked, outputs must not alias
+    smb = lambda yd=x, dyd=x, dxd=y, mode=1, p=fake: L.igcSoftmaxBackward(h.ptr, mode, ctypes.byref(one), yd.ptr, fake, dyd.ptr, p,
+                                                                          ctypes.byref(one), dxd.ptr, fake)
+    assert smb(mode=2) == ig.IGC_STATUS_BAD_PARAM and smb(p=None) == ig.IGC_STATUS_BAD_PARAM
+    assert smb(dyd=t(2, 3, 8, 9)) == ig.IGC_STATUS_BAD_PARAM and smb(yd=t(2, 4, 8, 8)) == ig.IGC_STATUS_BAD_PARAM
+    assert smb(dxd=t(2, 3, 8, 8, st=(192, 64, 8, 0))) == ig.IGC_STATUS_BAD_PARAM
+    assert smb(dyd=t(2, 3, 8, 8, dt=1)) == ig.IGC_STATUS_NOT_SUPPORTED
+    pb = lambda dyd=t(2, 3, 5, 4), xd=xp, dxd=t(2, 3, 9, 11), pd=pool: L.igcPoolingBackward(
+        h.ptr, pd.ptr, ctypes.byref(one), dyd.ptr, fake, xd.ptr, fake, ctypes.byref(one), dxd.ptr, fake)
+    assert pb(dyd=t(2, 3, 5, 5)) == ig.IGC_STATUS_BAD_PARAM and pb(dxd=t(2, 3, 9, 12)) == ig.IGC_STATUS_BAD_PARAM
+    assert pb(pd=ig.PoolingDescriptor()) == ig.IGC_STATUS_NOT_INITIALIZED
+    assert pb(dxd=t(2, 3, 9, 11, st=(0, 99, 11, 1))) == ig.IGC_STATUS_BAD_PARAM
 
 
 def test_setters_reject_bad_values():
