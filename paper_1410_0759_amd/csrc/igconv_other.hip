@@ -469,12 +469,107 @@ __global__ __launch_bounds__(256) void igconv_pooling_bwd_kernel(const PoolBwdAr
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), dxbuf, dxoff * 4u, 0, 0);
 }
 
+// The same function for tensors whose w stride is 1 (x, dy and dx): a workgroup takes TH input
+// rows of one (n,c) plane.  It loads the rows of x its windows touch into LDS with coalesced
+// reads (MAX only), finds each covering window's share once - the position of its maximum and
+// dy, or dy / count - into LDS, and then every input element of the strip sums the shares of
+// the windows covering it, in window order.  HBM sees x, dy and dx once, in whole rows.
+struct PoolBwdRowsArgs {
+    int mode, H, W, P, Q, win_h, win_w, pad_h, pad_w, u, v_;
+    int TH, strips, C;          // input rows per workgroup, workgroups per plane, planes are (n,c)
+    Magic mStrips, mC, mu, mv, mW, mQ;
+    uint32_t xs[3], dys[3], dxs[3];   // n, c, h strides
+    uint32_t x_bytes, dy_bytes, dx_bytes;
+    int xrows_max, wrows_max;   // LDS room: rows of x, rows of windows
+    float alpha, beta;
+    float *dx;
+    const float *x, *dy;
+};
+
+__global__ __launch_bounds__(256) void igconv_pooling_bwd_rows_kernel(const PoolBwdRowsArgs a) {
+    extern __shared__ float pool_lds[];
+    float *xl = pool_lds;                                  // [xrows_max][W]
+    float *gl = pool_lds + a.xrows_max * a.W;              // [wrows_max][Q] share of dy
+    int *al = reinterpret_cast<int *>(gl + a.wrows_max * a.Q);   // [wrows_max][Q] position h*W + w of the maximum
+    const uint32_t plane = mdiv(blockIdx.x, a.mStrips), strip = blockIdx.x - plane * (uint32_t)a.strips;
+    const uint32_t n = mdiv(plane, a.mC), c = plane - n * (uint32_t)a.C;
+    const int h0 = (int)strip * a.TH, h1 = min(h0 + a.TH, a.H);
+    const int t0 = h0 + a.pad_h - (a.win_h - 1);
+    const int p_lo = t0 <= 0 ? 0 : (int)mdiv((uint32_t)(t0 + a.u - 1), a.mu);
+    const int p_hi = min(a.P - 1, (int)mdiv((uint32_t)(h1 - 1 + a.pad_h), a.mu));
+    const int nprow = max(p_hi - p_lo + 1, 0);
+    const int xr0 = max(p_lo * a.u - a.pad_h, 0), xr1 = min(p_hi * a.u - a.pad_h + a.win_h, a.H);
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t dybuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.dy), 0, a.dy_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t dxbuf = __builtin_amdgcn_make_buffer_rsrc(a.dx, 0, a.dx_bytes, 0x00020000u);
+    const bool is_max = a.mode == IGC_POOLING_MAX;
+    if (is_max && nprow > 0) {
+        const uint32_t base = n * a.xs[0] + c * a.xs[1];
+        const int cnt = (xr1 - xr0) * a.W;
+        for (int i = threadIdx.x; i < cnt; i += 256) {
+            const uint32_t r = mdiv((uint32_t)i, a.mW), w = (uint32_t)i - r * (uint32_t)a.W;
+            xl[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                xbuf, (base + ((uint32_t)xr0 + r) * a.xs[2] + w) * 4u, 0, 0));
+        }
+    }
+    __syncthreads();
+    {
+        const uint32_t base = n * a.dys[0] + c * a.dys[1];
+        const int cnt = nprow * a.Q;
+        for (int wi = threadIdx.x; wi < cnt; wi += 256) {
+            const uint32_t pr = mdiv((uint32_t)wi, a.mQ), q = (uint32_t)wi - pr * (uint32_t)a.Q;
+            const int p = p_lo + (int)pr;
+            const int r0 = max(p * a.u - a.pad_h, 0), r1 = min(p * a.u - a.pad_h + a.win_h, a.H);
+            const int c0 = max((int)q * a.v_ - a.pad_w, 0), c1 = min((int)q * a.v_ - a.pad_w + a.win_w, a.W);
+            const float g = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                dybuf, (base + (uint32_t)p * a.dys[2] + q) * 4u, 0, 0));
+            if (is_max) {
+                float m = -INFINITY;
+                int arg = r0 * a.W + c0;
+                for (int r = r0; r < r1; ++r)
+                    for (int cc = c0; cc < c1; ++cc) {
+                        const float val = xl[(r - xr0) * a.W + cc];
+                        if (val > m) {     // strictly greater: the first of equal maxima stays
+                            m = val;
+                            arg = r * a.W + cc;
+                        }
+                    }
+                al[wi] = arg;
+                gl[wi] = g;
+            } else {
+                gl[wi] = g / (float)((r1 - r0) * (c1 - c0));
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t base = n * a.dxs[0] + c * a.dxs[1];
+    const int cnt = (h1 - h0) * a.W;
+    for (int i = threadIdx.x; i < cnt; i += 256) {
+        const uint32_t r = mdiv((uint32_t)i, a.mW);
+        const int w = i - (int)r * a.W, h = h0 + (int)r;
+        const int th = h + a.pad_h - (a.win_h - 1), tw = w + a.pad_w - (a.win_w - 1);
+        const int pl = th <= 0 ? 0 : (int)mdiv((uint32_t)(th + a.u - 1), a.mu), ph = min(a.P - 1, (int)mdiv((uint32_t)(h + a.pad_h), a.mu));
+        const int ql = tw <= 0 ? 0 : (int)mdiv((uint32_t)(tw + a.v_ - 1), a.mv), qh = min(a.Q - 1, (int)mdiv((uint32_t)(w + a.pad_w), a.mv));
+        const int self = h * a.W + w;
+        float acc = 0.f;
+        for (int p = pl; p <= ph; ++p)
+            for (int q = ql; q <= qh; ++q) {
+                const int wi = (p - p_lo) * a.Q + q;
+                if (!is_max || al[wi] == self) acc += gl[wi];
+            }
+        const uint32_t off = (base + (uint32_t)h * a.dxs[2] + (uint32_t)w) * 4u;
+        float res = a.alpha * acc;
+        if (a.beta != 0.f) res += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dxbuf, off, 0, 0));
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, res), dxbuf, off, 0, 0);
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------
 template <class Kernel, class Args>
-igcStatus launch(Kernel kernel, const char *what, const Args &args, uint32_t blocks, void *stream) {
+igcStatus launch(Kernel kernel, const char *what, const Args &args, uint32_t blocks, void *stream, size_t lds_bytes = 0) {
     Args copy = args;
     void *argv[] = {&copy};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(256), argv, 0,
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(256), argv, lds_bytes,
                                          static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
         std::fprintf(stderr, "igconv: launch of %s failed: %s\n", what, hipGetErrorString(e));
@@ -802,6 +897,43 @@ igcStatus igcPoolingBackward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc
     a.dx = static_cast<float *>(dx);
     a.x = static_cast<const float *>(x);
     a.dy = static_cast<const float *>(dy);
+    // w stride 1 everywhere: the row-strip kernel, with as many rows per workgroup (at most 64)
+    // as its LDS (rows of x, two words per covering window) allows within 64 KB
+    if (xDesc->stride[3] == 1 && dyDesc->stride[3] == 1 && dxDesc->stride[3] == 1 && !std::getenv("IGCONV_POOL_GENERAL")) {
+        PoolBwdRowsArgs r{};
+        r.mode = a.mode; r.H = a.H; r.W = a.W; r.P = p; r.Q = q;
+        r.win_h = a.win_h; r.win_w = a.win_w; r.pad_h = a.pad_h; r.pad_w = a.pad_w; r.u = a.u; r.v_ = a.v_;
+        r.C = c;
+        for (int d = 0; d < 3; ++d) {
+            r.xs[d] = (uint32_t)xDesc->stride[d];
+            r.dys[d] = (uint32_t)dyDesc->stride[d];
+            r.dxs[d] = (uint32_t)dxDesc->stride[d];
+        }
+        r.x_bytes = a.x_bytes; r.dy_bytes = a.dy_bytes; r.dx_bytes = a.dx_bytes;
+        r.alpha = a.alpha; r.beta = a.beta; r.dx = a.dx; r.x = a.x; r.dy = a.dy;
+        for (int th = std::min(64, r.H); th >= 1; th = th > 1 ? (th + 1) / 2 : 0) {
+            const int strips = (r.H + th - 1) / th;
+            int xrows = 0, wrows = 0;
+            for (int s = 0; s < strips; ++s) {
+                const int h0 = s * th, h1 = std::min(h0 + th, r.H);
+                const int t0 = h0 + r.pad_h - (r.win_h - 1);
+                const int p_lo = t0 <= 0 ? 0 : (t0 + r.u - 1) / r.u, p_hi = std::min(p - 1, (h1 - 1 + r.pad_h) / r.u);
+                if (p_hi < p_lo) continue;
+                wrows = std::max(wrows, p_hi - p_lo + 1);
+                xrows = std::max(xrows, std::min(p_hi * r.u - r.pad_h + r.win_h, r.H) - std::max(p_lo * r.u - r.pad_h, 0));
+            }
+            if (r.mode != IGC_POOLING_MAX) xrows = 0;
+            const long long lds = ((long long)xrows * r.W + 2ll * wrows * r.Q) * 4;
+            const long long blocks = (long long)n * c * strips;
+            if (lds > 64 * 1024 || blocks >= (1ll << 31)) continue;
+            r.TH = th; r.strips = strips; r.xrows_max = xrows; r.wrows_max = wrows;
+            if (!magic_of((uint32_t)strips, &r.mStrips) || !magic_of((uint32_t)c, &r.mC) || !magic_of((uint32_t)r.u, &r.mu) ||
+                !magic_of((uint32_t)r.v_, &r.mv) || !magic_of((uint32_t)r.W, &r.mW) || !magic_of((uint32_t)r.Q, &r.mQ))
+                break;
+            return launch(&igconv_pooling_bwd_rows_kernel, "igconv_pooling_bwd_rows_kernel", r, (uint32_t)blocks, handle->stream,
+                          (size_t)lds);
+        }
+    }
     return launch(&igconv_pooling_bwd_kernel, "igconv_pooling_bwd_kernel", a, (a.count + 255u) / 256u, handle->stream);
 }
 

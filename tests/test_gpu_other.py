@@ -143,7 +143,10 @@ def test_pooling_backward(mode):
     cases = [((2, 3, 9, 11), (2, 2), (0, 0), (2, 2)), ((2, 3, 9, 11), (3, 3), (1, 1), (2, 2)),
              ((1, 5, 13, 13), (3, 2), (1, 0), (1, 3)), ((3, 96, 27, 27), (3, 3), (0, 0), (2, 2)),
              ((2, 4, 7, 7), (7, 7), (0, 0), (1, 1)), ((2, 4, 8, 8), (5, 5), (2, 2), (4, 4)), ((1, 1, 1, 1), (1, 1), (0, 0), (1, 1)),
-             ((2, 3, 10, 12), (3, 3), (0, 0), (1, 1)), ((2, 3, 11, 9), (2, 2), (0, 0), (3, 3)), ((1, 2, 6, 30), (1, 5), (0, 2), (1, 2))]
+             ((2, 3, 10, 12), (3, 3), (0, 0), (1, 1)), ((2, 3, 11, 9), (2, 2), (0, 0), (3, 3)), ((1, 2, 6, 30), (1, 5), (0, 2), (1, 2)),
+             ((3, 5, 55, 55), (3, 3), (0, 0), (2, 2)), ((2, 3, 37, 20), (3, 3), (1, 1), (1, 1)),
+             ((1, 2, 9, 700), (3, 3), (1, 1), (1, 1)),       # wide rows: fewer rows per workgroup
+             ((1, 1, 4, 2000), (3, 3), (1, 1), (1, 1))]      # too wide for the row-strip kernel
     for shape, win, pad, st in cases:
         x = rnd(35, *shape) - np.float32(5.0)
         P, Q = po.pooling_output_dim(shape[2], win[0], pad[0], st[0]), po.pooling_output_dim(shape[3], win[1], pad[1], st[1])
