@@ -15,7 +15,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense matrix peaks (256 CUs x 2.4 GHz)
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6, "f64": 78.6}   # MI355X dense matrix peaks (256 CUs x 2.4 GHz)
 
 
 def time_gpu(g, alpha, beta, steps, warmup):
@@ -133,6 +133,56 @@ def run_backward(index, steps, warmup, oracle_seconds):
     cpu_s = time.perf_counter() - t0
     out["backward_filter"] = {"ms": ms, "tflops": w_.flops / ms / 1e9, "frac_of_peak": w_.flops / ms / 1e9 / PEAK_TFLOPS[w_.dtype],
                               "workspace_bytes": g.asked, "rel_err": gu.rel_err(got, want), "oracle_seconds": cpu_s}
+    return out
+
+
+def run_double_precision(steps, warmup):
+    """The three passes in double precision at the shape of the mid-layer workload on 64 images
+    (float32-valued inputs held as doubles, so that the oracle, which takes float32 values and
+    works in double, gives the expected result directly; parity on the first image)."""
+    import numpy as np
+    import workloads as wl
+    from oracle import conv_oracle as oc
+    from tests import gpu_util as gu
+
+    w_ = wl.shrink(wl.by_index(3), 64)
+    x, w, _ = wl.make_inputs(w_)
+    pad, stride = (w_.pad_h, w_.pad_w), (w_.u, w_.v)
+    dy = np.random.default_rng(14100759 * 10 + 640).uniform(-1, 1, size=(w_.N, w_.K, w_.P, w_.Q)).astype(np.float32)
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    out = {"workload": w_.name + " in double precision", "dtype": "f64", "gflop": w_.flops / 1e9, "tolerance": gu.TOL["f64"]}
+
+    class _Timed:
+        def __init__(self, g):
+            self.g = g
+
+        def launch(self, alpha, beta):
+            self.g.launch(alpha, beta)
+
+    def entry(ms, err):
+        return {"ms": ms, "tflops": w_.flops / ms / 1e9, "frac_of_peak": w_.flops / ms / 1e9 / PEAK_TFLOPS["f64"], "rel_err": err}
+
+    g = gu.GpuConv(x64, w64, pad, stride, w_.mode, dtype="f64")
+    g.prefill(value=float("nan"))
+    g.launch(1.0, 0.0)
+    err = gu.rel_err(g.result()[:1], oc.conv_forward(x[:1], w, pad=pad, stride=stride, mode=w_.mode))
+    out["forward"] = entry(time_gpu(g, 1.0, 0.0, steps, warmup), err)
+    import paper_1410_0759_amd as ig
+    out["forward"]["kernel"] = ig.kernel_names()[g.plan().kernelId]
+    del g
+    g = gu.GpuBackwardData(dy64, w64, (w_.H, w_.W), pad, stride, w_.mode, "f64")
+    g.out.prefill(value=float("nan"))
+    g.launch(1.0, 0.0)
+    err = gu.rel_err(g.out.result()[:1], oc.conv_backward_data(dy[:1], w, (w_.H, w_.W), pad=pad, stride=stride, mode=w_.mode))
+    out["backward_data"] = entry(time_gpu(_Timed(g), 1.0, 0.0, steps, warmup), err)
+    del g
+    g = gu.GpuBackwardFilter(x64, dy64, (w_.R, w_.S), pad, stride, w_.mode, "f64")
+    g.out.prefill(value=float("nan"))
+    ms = time_gpu(_Timed(g), 1.0, 0.0, steps, warmup)
+    got, _ = gu.run_backward_filter(x64[:1], dy64[:1], (w_.R, w_.S), pad, stride, w_.mode, dtype="f64")
+    err = gu.rel_err(got, oc.conv_backward_filter(x[:1], dy[:1], (w_.R, w_.S), pad=pad, stride=stride, mode=w_.mode))
+    out["backward_filter"] = entry(ms, err)
+    out["backward_filter"]["workspace_bytes"] = g.asked
     return out
 
 
@@ -285,6 +335,7 @@ def main():
     ap.add_argument("--backward-only", type=int, default=0, help="time only the backward passes of this workload (1-5)")
     ap.add_argument("--no-other", action="store_true", help="skip the section on activations, softmax, pooling, bias addition")
     ap.add_argument("--other-only", action="store_true", help="time only that section")
+    ap.add_argument("--f64-only", action="store_true", help="time only the double-precision section")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -316,6 +367,10 @@ def main():
 
     if args.other_only:
         print(json.dumps(run_other_functions(max(20, args.steps // 5), max(10, args.warmup // 5))))
+        return
+
+    if args.f64_only:
+        print(json.dumps(run_double_precision(max(20, args.steps // 10), max(10, args.warmup // 5))))
         return
 
     head = run_config(args.config, args.steps, args.warmup, args.oracle_seconds, args.kernel)
@@ -352,8 +407,10 @@ def main():
             backward.append(run_backward(i, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0))
 
     other = []
+    double_precision = None
     if not args.only and not args.no_other:
         other = run_other_functions(max(20, args.steps // 5), max(10, args.warmup // 5))
+        double_precision = run_double_precision(max(20, args.steps // 10), max(10, args.warmup // 5))
 
     # Mini-batch sweep over the Table-2 layers (the paper reports 86 % of its maximum
     # throughput at a mini-batch of 16): average TFLOP/s over the five layers per batch size.
@@ -404,6 +461,7 @@ def main():
         "table2_batch_sweep": batch_sweep,
         "backward": backward,
         "other_functions": other,
+        "double_precision": double_precision,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
                          "on GTX 980, fp32, its own Table-2 layers",
     }

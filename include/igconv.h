@@ -48,7 +48,8 @@ typedef enum {
 
 typedef enum {
     IGC_DATA_FLOAT = 0,   /* IEEE binary32 */
-    IGC_DATA_BFLOAT16 = 1 /* upper 16 bits of a binary32 */
+    IGC_DATA_BFLOAT16 = 1, /* upper 16 bits of a binary32 */
+    IGC_DATA_DOUBLE = 2    /* IEEE binary64 (Section 2: single and double precision) */
 } igcDataType;
 
 typedef enum {

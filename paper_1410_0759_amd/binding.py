@@ -11,7 +11,7 @@ __all__ = [
     "lib", "IgcError", "check",
     "IGC_STATUS_SUCCESS", "IGC_STATUS_BAD_PARAM", "IGC_STATUS_NOT_SUPPORTED",
     "IGC_STATUS_NOT_INITIALIZED", "IGC_STATUS_ALLOC_FAILED", "IGC_STATUS_EXECUTION_FAILED",
-    "IGC_DATA_FLOAT", "IGC_DATA_BFLOAT16", "IGC_CONVOLUTION", "IGC_CROSS_CORRELATION",
+    "IGC_DATA_FLOAT", "IGC_DATA_BFLOAT16", "IGC_DATA_DOUBLE", "IGC_CONVOLUTION", "IGC_CROSS_CORRELATION",
     "igcConvolutionForwardPlan", "DECLARED_SYMBOLS",
     "Handle", "TensorDescriptor", "FilterDescriptor", "ConvolutionDescriptor",
     "get_output_dim", "get_workspace_size", "get_optional_workspace_size", "get_plan", "convolution_forward",
@@ -29,7 +29,7 @@ LIB_PATH = os.path.join(HERE, "libigconv.so")
 
 (IGC_STATUS_SUCCESS, IGC_STATUS_BAD_PARAM, IGC_STATUS_NOT_SUPPORTED,
  IGC_STATUS_NOT_INITIALIZED, IGC_STATUS_ALLOC_FAILED, IGC_STATUS_EXECUTION_FAILED) = range(6)
-IGC_DATA_FLOAT, IGC_DATA_BFLOAT16 = 0, 1
+IGC_DATA_FLOAT, IGC_DATA_BFLOAT16, IGC_DATA_DOUBLE = 0, 1, 2
 IGC_CONVOLUTION, IGC_CROSS_CORRELATION = 0, 1
 IGC_ACTIVATION_SIGMOID, IGC_ACTIVATION_RELU, IGC_ACTIVATION_TANH = 0, 1, 2
 IGC_ACTIVATION_IDENTITY = -1
@@ -167,6 +167,14 @@ class Handle(_Owned):
 
     def set_kernel_override(self, kernel_id):
         check(lib().igcSetKernelOverride(self.ptr, kernel_id), "igcSetKernelOverride")
+
+
+def _scalars(out_desc, alpha, beta):
+    """alpha and beta as the host scalars the library expects: doubles for double-precision
+    problems (told by the output's descriptor), floats otherwise."""
+    dt = out_desc.get()[0]
+    t = ctypes.c_double if dt == IGC_DATA_DOUBLE else ctypes.c_float
+    return t(alpha), t(beta)
 
 
 class TensorDescriptor(_Owned):
@@ -307,7 +315,7 @@ def get_plan(handle, xdesc, wdesc, conv, ydesc):
 def convolution_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, ydesc, y_ptr,
                         workspace_ptr=0, workspace_bytes=0):
     """igcConvolutionForward with device pointers given as integers; returns the status."""
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcConvolutionForward(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
@@ -324,7 +332,7 @@ def get_backward_data_workspace_size(handle, wdesc, dydesc, conv, dxdesc):
 def convolution_backward_data(handle, alpha, wdesc, w_ptr, dydesc, dy_ptr, conv, beta, dxdesc, dx_ptr,
                               workspace_ptr=0, workspace_bytes=0):
     """igcConvolutionBackwardData with device pointers given as integers; returns the status."""
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(dxdesc, alpha, beta)
     return lib().igcConvolutionBackwardData(
         handle.ptr, ctypes.byref(a), wdesc.ptr, _vp(w_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
@@ -341,7 +349,7 @@ def get_backward_filter_workspace_size(handle, xdesc, dydesc, conv, dwdesc):
 def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, conv, beta, dwdesc, dw_ptr,
                                 workspace_ptr=0, workspace_bytes=0):
     """igcConvolutionBackwardFilter with device pointers given as integers; returns the status."""
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(dwdesc, alpha, beta)
     return lib().igcConvolutionBackwardFilter(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
@@ -350,7 +358,7 @@ def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, con
 def convolution_bias_activation_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, bias_ptr, activation,
                                         ydesc, y_ptr):
     """igcConvolutionBiasActivationForward; bias_ptr 0 for no bias, activation -1 for none."""
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcConvolutionBiasActivationForward(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr, None, 0, ctypes.byref(b),
         _vp(bias_ptr), activation, ydesc.ptr, _vp(y_ptr))
@@ -381,6 +389,6 @@ def tensor_descriptor_for(t, dtype=None):
         strides = [s // t.itemsize for s in t.strides]
         is_bf16 = False
     if dtype is None:
-        dtype = IGC_DATA_BFLOAT16 if is_bf16 else IGC_DATA_FLOAT
+        dtype = IGC_DATA_BFLOAT16 if is_bf16 else (IGC_DATA_DOUBLE if "float64" in str(t.dtype) else IGC_DATA_FLOAT)
     n, c, h, w = t.shape
     return TensorDescriptor().set(dtype, n, c, h, w, strides)

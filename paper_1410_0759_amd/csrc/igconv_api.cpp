@@ -24,7 +24,7 @@ constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64};
 
 int kernel_count() {
     int n = 0;
@@ -63,6 +63,7 @@ static long long out_dim(long long H, long long R, long long u, long long pad) {
 struct Problem {
     ConvKernelParams kp;
     bool bf16;
+    bool f64 = false;  // double precision in and out
     int vec;  // elements per 16 bytes of input
     unsigned mode_mask = 0;   // non-zero: bit g set when gather mode g can run this problem
     bool zero_steps = false;  // nothing to accumulate: the kernel only scales the old output
@@ -83,11 +84,12 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 
     const bool f32 = x->dtype == IGC_DATA_FLOAT && w->dtype == IGC_DATA_FLOAT;
     const bool b16 = x->dtype == IGC_DATA_BFLOAT16 && w->dtype == IGC_DATA_BFLOAT16;
-    if (!(f32 || b16) || y->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    const bool f64 = x->dtype == IGC_DATA_DOUBLE && w->dtype == IGC_DATA_DOUBLE;
+    if (!(f32 || b16 || f64) || y->dtype != (f64 ? IGC_DATA_DOUBLE : IGC_DATA_FLOAT)) return IGC_STATUS_NOT_SUPPORTED;
 
     const int es = elem_size(x->dtype);
     const long long xb = extent(x->dim, x->stride) * es;
-    const long long yb = extent(y->dim, y->stride) * 4;
+    const long long yb = extent(y->dim, y->stride) * elem_size(y->dtype);
     const long long CRS = (long long)w->c * w->r * w->s;
     const long long wb = (long long)w->k * CRS * es;
     const long long NPQ = (long long)x->dim[0] * P * Q;
@@ -122,6 +124,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
         k.xsN = (int)x->stride[0]; k.xsC = (int)x->stride[1]; k.xsH = (int)x->stride[2]; k.xsW = (int)x->stride[3];
         k.ysN = (int)y->stride[0]; k.ysK = (int)y->stride[1]; k.ysP = (int)y->stride[2]; k.ysQ = (int)y->stride[3];
         out->bf16 = b16;
+        out->f64 = f64;
         out->vec = 16 / es;
     }
     return IGC_STATUS_SUCCESS;
@@ -213,7 +216,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     const bool want_swap = k.ysK == 1 && k.K > 1 && !(k.ysQ == 1 && k.Q > 1);
     if (h->kernelOverride >= 0 && pr.mode_mask == 0) {   // (the override is for the forward pass)
         const KernelInfo *ki = kernel_info(h->kernelOverride);
-        if (!ki || ki->bf16 != pr.bf16 || (ki->veca && !can_vec) || !gather_mode_ok(*ki, k, x_aligned))
+        if (!ki || ki->bf16 != pr.bf16 || ki->f64 != pr.f64 || (ki->veca && !can_vec) || !gather_mode_ok(*ki, k, x_aligned))
             return IGC_STATUS_NOT_SUPPORTED;
         *id_out = h->kernelOverride;
         return IGC_STATUS_SUCCESS;
@@ -222,7 +225,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
     double best_cost = 0;
     for (int id = 0; id < kernel_count(); ++id) {
         const KernelInfo &ki = *kernel_info(id);
-        if (ki.bf16 != pr.bf16 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
+        if (ki.bf16 != pr.bf16 || ki.f64 != pr.f64 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
@@ -242,7 +245,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.f64) return tiles_per_xcd;
     const int occ = std::max(1, std::min(2, (160 * 1024) / ki.ldsBytes));
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * occ);
 }
@@ -347,7 +350,7 @@ static PhaseAxis phase_axis(int H, int R, int pad, int u, bool flip, int ph) {
 struct BackwardDataProblem {
     // validated sizes, forward naming
     int N, C, H, W, K, R, S, P, Q, pad_h, pad_w, u, v;
-    bool flip, bf16;
+    bool flip, bf16, f64;
     long long dys[4], dxs[4];
     long long dy_bytes, w_bytes, dx_bytes;
 };
@@ -363,11 +366,13 @@ static igcStatus validate_backward_data(igcFilterDescriptor_t w, igcTensorDescri
     if (!non_aliasing(dx->dim, dx->stride)) return IGC_STATUS_BAD_PARAM;
     const bool f32 = dy->dtype == IGC_DATA_FLOAT && w->dtype == IGC_DATA_FLOAT;
     const bool b16 = dy->dtype == IGC_DATA_BFLOAT16 && w->dtype == IGC_DATA_BFLOAT16;
-    if (!(f32 || b16) || dx->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    const bool f64 = dy->dtype == IGC_DATA_DOUBLE && w->dtype == IGC_DATA_DOUBLE;
+    if (!(f32 || b16 || f64) || dx->dtype != (f64 ? IGC_DATA_DOUBLE : IGC_DATA_FLOAT)) return IGC_STATUS_NOT_SUPPORTED;
     const int es = elem_size(dy->dtype);
     BackwardDataProblem b{};
+    b.f64 = f64;
     b.dy_bytes = extent(dy->dim, dy->stride) * es;
-    b.dx_bytes = extent(dx->dim, dx->stride) * 4;
+    b.dx_bytes = extent(dx->dim, dx->stride) * elem_size(dx->dtype);
     b.w_bytes = (long long)w->k * w->c * w->r * w->s * es;
     if (b.dy_bytes >= kMaxBytes || b.dx_bytes >= kMaxBytes || b.w_bytes >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
     if ((long long)dx->dim[0] * dx->dim[2] * dx->dim[3] >= (1ll << 30) || (long long)w->k * w->r * w->s >= (1ll << 30))
@@ -393,16 +398,19 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
     if (ah.count <= 0 || aw.count <= 0) return false;
     *pr = Problem{};
     pr->bf16 = b.bf16;
-    pr->vec = b.bf16 ? 8 : 4;
-    pr->mode_mask = (1u << 1) | (1u << 3);   // tap-major, or the nine-tap table when the phase has nine taps
+    pr->f64 = b.f64;
+    pr->vec = b.bf16 ? 8 : (b.f64 ? 2 : 4);
+    // tap-major, or the nine-tap table when the phase has nine taps; double precision: its one gather
+    pr->mode_mask = b.f64 ? 1u << 0 : (1u << 1) | (1u << 3);
     pr->zero_steps = ah.taps == 0 || aw.taps == 0;
     ConvKernelParams &k = pr->kp;
     const int es = b.bf16 ? 2 : 4;
+    const int out_es = b.f64 ? 8 : 4;
     const int Rp = std::max(ah.taps, 1), Sp = std::max(aw.taps, 1);
     *dx_offset = (long long)ph * b.dxs[2] + (long long)pw * b.dxs[3];
     k.x_bytes = (uint32_t)b.dy_bytes;
     k.w_bytes = (uint32_t)b.w_bytes;
-    k.y_bytes = (uint32_t)(b.dx_bytes - *dx_offset * 4);
+    k.y_bytes = (uint32_t)(b.dx_bytes - *dx_offset * out_es);
     // the gather runs over dy: its channels are the reduction, its rows and columns the image
     k.N = b.N; k.C = b.K; k.H = b.P; k.W = b.Q;
     k.K = b.C; k.R = Rp; k.S = Sp; k.P = ah.count; k.Q = aw.count;
@@ -485,11 +493,12 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     if (P < 1 || Q < 1 || dy->dim[2] != P || dy->dim[3] != Q) return IGC_STATUS_BAD_PARAM;
     const bool f32 = x->dtype == IGC_DATA_FLOAT && dy->dtype == IGC_DATA_FLOAT;
     const bool b16 = x->dtype == IGC_DATA_BFLOAT16 && dy->dtype == IGC_DATA_BFLOAT16;
-    if (!(f32 || b16) || dw->dtype != IGC_DATA_FLOAT) return IGC_STATUS_NOT_SUPPORTED;
+    const bool f64 = x->dtype == IGC_DATA_DOUBLE && dy->dtype == IGC_DATA_DOUBLE;
+    if (!(f32 || b16 || f64) || dw->dtype != (f64 ? IGC_DATA_DOUBLE : IGC_DATA_FLOAT)) return IGC_STATUS_NOT_SUPPORTED;
     const int es = elem_size(x->dtype);
     const long long xb = extent(x->dim, x->stride) * es, dyb = extent(dy->dim, dy->stride) * es;
     const long long CRS = (long long)dw->c * dw->r * dw->s, NPQ = (long long)x->dim[0] * P * Q;
-    const long long dwb = (long long)dw->k * CRS * 4;
+    const long long dwb = (long long)dw->k * CRS * elem_size(dw->dtype);
     if (xb >= kMaxBytes || dyb >= kMaxBytes || dwb >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
     if (NPQ >= (1ll << 30) || CRS >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
     // packed 16-bit window coordinates: here the reduction index contributes up to
@@ -500,6 +509,7 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     *out = BackwardFilterProblem{};
     Problem &pr = out->pr;
     pr.bf16 = b16;
+    pr.f64 = f64;
     pr.vec = 16 / es;
     pr.mode_mask = 1u << 6;
     ConvKernelParams &k = pr.kp;
@@ -531,9 +541,18 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     // Two ways to run it.  Enough channels to fill a column tile: columns ordered (tap, channel),
     // one tap per tile (gather mode 8; any filter size).  Otherwise the generic gather over
     // columns (c,r,s) set up above (mode 6).  Row tile: the smaller one when it covers K.
-    const bool by_tap = dw->c >= 24;
-    const bool unpadded = !by_tap && cv->pad_h == 0 && cv->pad_w == 0;   // few channels, no padding: mode 9
+    const bool by_tap = dw->c >= 24 && !f64;   // (double precision has the generic gather only)
+    const bool unpadded = !by_tap && !f64 && cv->pad_h == 0 && cv->pad_w == 0;   // few channels, no padding: mode 9
     const int want_mode = by_tap ? 8 : (unpadded ? 9 : 6);
+    if (f64) {
+        for (int i = 0; i < kernel_count(); ++i)
+            if (kernel_info(i)->f64 && kernel_info(i)->gmode == 6) out->kernel_id = i;
+        const KernelInfo &kf = *kernel_info(out->kernel_id);
+        out->ksteps = (NPQ + kf.BK - 1) / kf.BK;
+        out->tiles_n = (CRS + kf.BN - 1) / kf.BN;
+        out->tiles = (long long)((dw->k + kf.BM - 1) / kf.BM) * out->tiles_n;
+        return IGC_STATUS_SUCCESS;
+    }
     // row tile: least padding of K among 64, 96 (fp32 only), 128; the larger one on a tie
     int want_bm = 64;
     for (int bm : {96, 128}) {
@@ -654,7 +673,7 @@ igcStatus igcSetTensor4dDescriptor(igcTensorDescriptor_t desc, igcDataType dataT
                                    int w, long long nStride, long long cStride, long long hStride,
                                    long long wStride) {
     if (!desc) return IGC_STATUS_BAD_PARAM;
-    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16) return IGC_STATUS_BAD_PARAM;
+    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16 && dataType != IGC_DATA_DOUBLE) return IGC_STATUS_BAD_PARAM;
     if (n < 1 || c < 1 || h < 1 || w < 1) return IGC_STATUS_BAD_PARAM;
     if (nStride < 0 || cStride < 0 || hStride < 0 || wStride < 0) return IGC_STATUS_BAD_PARAM;
     const int dim[4] = {n, c, h, w};
@@ -699,7 +718,7 @@ igcStatus igcDestroyFilterDescriptor(igcFilterDescriptor_t desc) {
 
 igcStatus igcSetFilter4dDescriptor(igcFilterDescriptor_t desc, igcDataType dataType, int k, int c, int r, int s) {
     if (!desc) return IGC_STATUS_BAD_PARAM;
-    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16) return IGC_STATUS_BAD_PARAM;
+    if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16 && dataType != IGC_DATA_DOUBLE) return IGC_STATUS_BAD_PARAM;
     if (k < 1 || c < 1 || r < 1 || s < 1) return IGC_STATUS_BAD_PARAM;
     desc->dtype = dataType;
     desc->k = k; desc->c = c; desc->r = r; desc->s = s;
@@ -788,7 +807,7 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcT
     if (st != IGC_STATUS_SUCCESS) return st;
     const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)pr.kp.K * pr.kp.NPQ;
     int per;
-    const int splits = forward_split(*kernel_info(id), pr.kp, packed, 1 << 20, &per);
+    const int splits = pr.f64 ? 1 : forward_split(*kernel_info(id), pr.kp, packed, 1 << 20, &per);
     *sizeInBytes = splits > 1 ? (size_t)splits * pr.kp.y_bytes : 0;
     return IGC_STATUS_SUCCESS;
 }
@@ -855,8 +874,9 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     Problem pr;
     igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
     if (st != IGC_STATUS_SUCCESS) return st;
-    const int es = pr.bf16 ? 2 : 4;
-    if ((uintptr_t)x % es || (uintptr_t)w % es || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    const int es = pr.bf16 ? 2 : (pr.f64 ? 8 : 4);
+    if ((uintptr_t)x % es || (uintptr_t)w % es || (uintptr_t)y % (pr.f64 ? 8 : 4)) return IGC_STATUS_BAD_PARAM;
+    if (pr.f64 && (bias || activation != IGC_ACTIVATION_IDENTITY)) return IGC_STATUS_NOT_SUPPORTED;
     int id = -1;
     st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, /*x_aligned=*/((uintptr_t)x % 16) == 0, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
@@ -866,14 +886,19 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     pr.kp.x = x;
     pr.kp.w = w;
     pr.kp.y = y;
-    pr.kp.alpha = *static_cast<const float *>(alpha);
-    pr.kp.beta = *static_cast<const float *>(beta);
+    if (pr.f64) {
+        pr.kp.alpha64 = *static_cast<const double *>(alpha);
+        pr.kp.beta64 = *static_cast<const double *>(beta);
+    } else {
+        pr.kp.alpha = *static_cast<const float *>(alpha);
+        pr.kp.beta = *static_cast<const float *>(beta);
+    }
     pr.kp.bias = static_cast<const float *>(bias);
     pr.kp.act = activation;
     // A small problem with a workspace: cut the reduction into ranges (see forward_split).
     int grid = plan.gridX;
     int splits = 1;
-    if (workSpace && (uintptr_t)workSpace % 4 == 0 && !bias && activation == IGC_ACTIVATION_IDENTITY) {
+    if (workSpace && (uintptr_t)workSpace % 4 == 0 && !bias && activation == IGC_ACTIVATION_IDENTITY && !pr.f64) {
         ConvKernelParams &k = pr.kp;
         const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)k.K * k.NPQ;
         int per;
@@ -918,8 +943,8 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
     BackwardDataProblem b;
     igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
-    const int es = b.bf16 ? 2 : 4;
-    if ((uintptr_t)dy % es || (uintptr_t)w % es || (uintptr_t)dx % 4) return IGC_STATUS_BAD_PARAM;
+    const int es = b.bf16 ? 2 : (b.f64 ? 8 : 4);
+    if ((uintptr_t)dy % es || (uintptr_t)w % es || (uintptr_t)dx % (b.f64 ? 8 : 4)) return IGC_STATUS_BAD_PARAM;
     // The forward pass over dy with the exchanged filter, when the shape allows and the caller
     // lends room for that filter; else the general route below.
     {
@@ -958,9 +983,15 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
             l.grid = plan.gridX;
             l.pr.kp.x = dy;
             l.pr.kp.w = w;
-            l.pr.kp.y = static_cast<float *>(dx) + off;
-            l.pr.kp.alpha = *static_cast<const float *>(alpha);
-            l.pr.kp.beta = *static_cast<const float *>(beta);
+            if (b.f64) {
+                l.pr.kp.y = static_cast<double *>(dx) + off;
+                l.pr.kp.alpha64 = *static_cast<const double *>(alpha);
+                l.pr.kp.beta64 = *static_cast<const double *>(beta);
+            } else {
+                l.pr.kp.y = static_cast<float *>(dx) + off;
+                l.pr.kp.alpha = *static_cast<const float *>(alpha);
+                l.pr.kp.beta = *static_cast<const float *>(beta);
+            }
             launches.push_back(l);
         }
     for (const Launch &l : launches)
@@ -977,7 +1008,7 @@ igcStatus igcGetConvolutionBackwardFilterWorkspaceSize(igcHandle_t handle, igcTe
     if (st != IGC_STATUS_SUCCESS) return st;
     int splits, per;
     backward_filter_split(b, 1 << 20, &splits, &per);
-    *sizeInBytes = splits > 1 ? (size_t)splits * b.out_elems * 4 : 0;
+    *sizeInBytes = splits > 1 ? (size_t)splits * b.out_elems * (b.pr.f64 ? 8 : 4) : 0;
     return IGC_STATUS_SUCCESS;
 }
 
@@ -989,9 +1020,10 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     BackwardFilterProblem b;
     igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
-    const int es = b.pr.bf16 ? 2 : 4;
-    if ((uintptr_t)x % es || (uintptr_t)dy % es || (uintptr_t)dw % 4 || (uintptr_t)workSpace % 4) return IGC_STATUS_BAD_PARAM;
-    const size_t part_bytes = (size_t)b.out_elems * 4;
+    const bool f64 = b.pr.f64;
+    const int es = b.pr.bf16 ? 2 : (f64 ? 8 : 4), out_es = f64 ? 8 : 4;
+    if ((uintptr_t)x % es || (uintptr_t)dy % es || (uintptr_t)dw % out_es || (uintptr_t)workSpace % out_es) return IGC_STATUS_BAD_PARAM;
+    const size_t part_bytes = (size_t)b.out_elems * out_es;
     int splits, per;
     backward_filter_split(b, workSpace ? (long long)(workSpaceSizeInBytes / part_bytes) : 0, &splits, &per);
     ConvKernelParams &k = b.pr.kp;
@@ -999,7 +1031,8 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     st = fill_plan(b.kernel_id, &b.pr, &plan);
     if (st != IGC_STATUS_SUCCESS) return st;
     k.tilesN = (int)b.tiles_n;
-    const float a = *static_cast<const float *>(alpha), bt = *static_cast<const float *>(beta);
+    const float a = f64 ? 0.f : *static_cast<const float *>(alpha), bt = f64 ? 0.f : *static_cast<const float *>(beta);
+    const double a64 = f64 ? *static_cast<const double *>(alpha) : 0.0, bt64 = f64 ? *static_cast<const double *>(beta) : 0.0;
     k.x = x;
     k.w = dy;
     k.splits = splits;
@@ -1010,19 +1043,23 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     k.wgsPerXcd = workgroups_per_xcd(*kernel_info(b.kernel_id), k.tilesPerXcd);
     if (splits > 1) {
         k.y = workSpace;
-        k.alpha = 1.f;
-        k.beta = 0.f;
+        k.alpha = 1.f; k.alpha64 = 1.0;
+        k.beta = 0.f; k.beta64 = 0.0;
     } else {
         k.y = dw;
-        k.alpha = a;
-        k.beta = bt;
+        k.alpha = a; k.alpha64 = a64;
+        k.beta = bt; k.beta64 = bt64;
     }
     if (getenv("IGCONV_DEBUG"))
         fprintf(stderr, "igconv: backward filter with '%s', %lld tiles x %d ranges of %d steps\n", kernel_info(b.kernel_id)->name,
                 b.tiles, splits, k.stepsPerSplit);
     if (kernel_info(b.kernel_id)->launch(k, 8 * k.wgsPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
-    if (splits > 1 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
-                                       b.out_elems, a, bt, handle->stream) != 0)
+    if (splits > 1 && f64 &&
+        launch_sum_parts_f64(static_cast<const double *>(workSpace), static_cast<double *>(dw), b.out_elems, splits, b.out_elems,
+                             a64, bt64, handle->stream) != 0)
+        return IGC_STATUS_EXECUTION_FAILED;
+    if (splits > 1 && !f64 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
+                                               b.out_elems, a, bt, handle->stream) != 0)
         return IGC_STATUS_EXECUTION_FAILED;
     return IGC_STATUS_SUCCESS;
 }

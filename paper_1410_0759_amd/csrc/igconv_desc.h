@@ -39,7 +39,7 @@ struct igcPoolingStruct {
 
 namespace igc {
 
-inline int elem_size(igcDataType t) { return t == IGC_DATA_BFLOAT16 ? 2 : 4; }
+inline int elem_size(igcDataType t) { return t == IGC_DATA_BFLOAT16 ? 2 : (t == IGC_DATA_DOUBLE ? 8 : 4); }
 
 // Elements spanned by a strided 4-D tensor: 1 + sum (dim-1)*stride.
 inline long long extent(const int dim[4], const long long stride[4]) {

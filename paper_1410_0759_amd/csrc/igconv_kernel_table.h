@@ -23,6 +23,7 @@ struct KernelInfo {
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
     int variant = 0;  // bf16 channel-vector kernels: 1 when filter rows are loaded coalesced and scattered to LDS
+    bool f64 = false; // double precision in and out (alpha64 / beta64 of the parameters apply)
 };
 
 struct KernelGroup {
@@ -32,7 +33,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.
@@ -42,6 +43,9 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
 // wt[c][k][t] = w[k][c][t] for 2-byte elements, t < 9 (the filter with its first two
 // dimensions exchanged, each pair's nine taps kept in order); returns the runtime's error code.
 int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream);
+
+int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count, uint32_t stride, double alpha, double beta,
+                         void *stream);
 
 int kernel_count();
 const KernelInfo *kernel_info(int id);  // nullptr when out of range

@@ -1,0 +1,54 @@
+// Double-precision kernels (v_mfma_f64_16x16x4_f64) and the ordered sum of double partial results.
+#include <cstdio>
+#include <cstdlib>
+
+#include "igconv_kernel_f64.hpp"
+#include "igconv_kernel_table.h"
+
+namespace igc {
+
+template <bool WGRAD>
+static int launch_f64(const ConvKernelParams &p, int grid, void *stream) {
+    ConvKernelParams args = p;
+    void *argv[] = {&args};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_f64_kernel<WGRAD>), dim3(grid), dim3(256), argv, 0,
+                                         static_cast<hipStream_t>(stream));
+    if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
+        std::fprintf(stderr, "igconv: launch of igconv_f64_kernel failed: %s\n", hipGetErrorString(e));
+    return static_cast<int>(e);
+}
+
+template __global__ void igconv_f64_kernel<false>(const ConvKernelParams);
+template __global__ void igconv_f64_kernel<true>(const ConvKernelParams);
+
+// out[e] = alpha * (part_0[e] + part_1[e] + ...) + beta * out[e] in double, parts added in order.
+__global__ __launch_bounds__(256) void igconv_sum_parts_f64_kernel(const double *parts, double *out, uint32_t n, int count,
+                                                                   uint32_t stride, double alpha, double beta) {
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+    if (e >= n) return;
+    double acc = 0.0;
+    for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + e];
+    double r = alpha * acc;
+    if (beta != 0.0) r += beta * out[e];
+    out[e] = r;
+}
+
+int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count, uint32_t stride, double alpha, double beta,
+                         void *stream) {
+    void *argv[] = {&parts, &out, &n, &count, &stride, &alpha, &beta};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_parts_f64_kernel), dim3((n + 255u) / 256u),
+                                            dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+}
+
+#if !defined(__HIP_DEVICE_COMPILE__)
+static KernelInfo f64_row(const char *name, int gmode, int (*launch)(const ConvKernelParams &, int, void *)) {
+    KernelInfo k{name, false, kF64BM, kF64BN, kF64BK, false, false, gmode, 256, kF64LdsBytes, launch};
+    k.f64 = true;
+    return k;
+}
+static const KernelInfo kRows[] = {f64_row("f64 64x64x16 generic", 0, &launch_f64<false>),
+                                   f64_row("f64 64x64x16 wgrad", 6, &launch_f64<true>)};
+const KernelGroup kGroupF64 = {kRows, sizeof(kRows) / sizeof(kRows[0])};
+#endif
+
+}  // namespace igc

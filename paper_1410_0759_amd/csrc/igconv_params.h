@@ -28,6 +28,7 @@ struct ConvKernelParams {
     int32_t xsN, xsC, xsH, xsW;  // element strides of x
     int32_t ysN, ysK, ysP, ysQ;  // element strides of y
     float alpha, beta;
+    double alpha64 = 0.0, beta64 = 0.0;   // the same for the double-precision kernels
     const float *bias = nullptr;   // K floats added per output feature map before the activation, or null
     int32_t act = -1;    // activation applied last: 0 sigmoid, 1 rectified linear, 2 tanh, -1 none
     int32_t tilesM, tilesN;

@@ -12,6 +12,14 @@ GUARD = 4096          # elements of guard band before and after y
 GUARD_VALUE = 777.25
 
 
+def _dt(dtype):
+    return {"f32": ig.IGC_DATA_FLOAT, "bf16": ig.IGC_DATA_BFLOAT16, "f64": ig.IGC_DATA_DOUBLE}[dtype]
+
+
+def _out_torch(dtype):
+    return torch.float64 if dtype == "f64" else torch.float32
+
+
 def elem_strides(a):
     return [s // a.itemsize for s in a.strides]
 
@@ -27,6 +35,7 @@ def to_device_strided(a, dtype):
     n = extent(a.shape, strides)
     flat = np.lib.stride_tricks.as_strided(a, shape=(n,), strides=(a.itemsize,))
     t = torch.from_numpy(np.ascontiguousarray(flat))
+    assert (a.dtype == np.float64) == (dtype == "f64")
     if dtype == "bf16":
         t = t.to(torch.bfloat16)
         assert torch.equal(t.float(), torch.from_numpy(np.ascontiguousarray(flat)))
@@ -41,7 +50,8 @@ class GpuConv:
         self.handle = handle or ig.Handle()
         N, C, H, W = x.shape
         K, _, R, S = w.shape
-        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        dt = _dt(dtype)
+        self.esize = 8 if dtype == "f64" else 4
         self.x_dev, xs = to_device_strided(x, dtype)
         self.w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
         self.xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
@@ -58,13 +68,13 @@ class GpuConv:
                 raise ValueError(y_layout)
         self.ystrides = tuple(y_strides)
         self.yext = y_extent or extent(self.yshape, self.ystrides)
-        self.ydesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, n, k, p, q, self.ystrides)
-        self.ybuf = torch.full((self.yext + 2 * GUARD,), GUARD_VALUE, dtype=torch.float32, device="cuda")
+        self.ydesc = ig.TensorDescriptor().set(ig.IGC_DATA_DOUBLE if dtype == "f64" else ig.IGC_DATA_FLOAT, n, k, p, q, self.ystrides)
+        self.ybuf = torch.full((self.yext + 2 * GUARD,), GUARD_VALUE, dtype=_out_torch(dtype), device="cuda")
         self.flops = 2 * n * k * p * q * C * R * S
 
     @property
     def y_ptr(self):
-        return self.ybuf.data_ptr() + 4 * GUARD
+        return self.ybuf.data_ptr() + self.esize * GUARD
 
     def y_view(self):
         """Logical (N,K,P,Q) view of the device output."""
@@ -74,7 +84,7 @@ class GpuConv:
         inner = self.ybuf[GUARD:GUARD + self.yext]
         if y0 is not None:
             inner.fill_(float("nan"))
-            self.y_view().copy_(torch.from_numpy(np.ascontiguousarray(y0)).cuda())
+            self.y_view().copy_(torch.from_numpy(np.ascontiguousarray(y0)).cuda().to(self.ybuf.dtype))
         else:
             inner.fill_(value)
 
@@ -135,7 +145,9 @@ def rel_err(got, want):
     return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
 
 
-TOL = {"f32": 2e-5, "bf16": 1e-2}
+# (double precision: sums of up to ~1e5 products of magnitude <= 1, each rounded to 2^-53, leave
+# errors of 1e-14 relative to the largest output; 1e-12 tells a double path from a float one by 5 orders)
+TOL = {"f32": 2e-5, "bf16": 1e-2, "f64": 1e-12}
 
 
 def _device_tensor(a, dtype):
@@ -146,14 +158,14 @@ def _device_tensor(a, dtype):
 class GuardedOutput:
     """A float32 device buffer for a strided logical 4-D tensor, with guard bands."""
 
-    def __init__(self, shape, strides):
+    def __init__(self, shape, strides, dtype="f32"):
         self.shape, self.strides = tuple(shape), tuple(strides)
         self.ext = extent(self.shape, self.strides)
-        self.buf = torch.full((self.ext + 2 * GUARD,), GUARD_VALUE, dtype=torch.float32, device="cuda")
+        self.buf = torch.full((self.ext + 2 * GUARD,), GUARD_VALUE, dtype=_out_torch(dtype), device="cuda")
 
     @property
     def ptr(self):
-        return self.buf.data_ptr() + 4 * GUARD
+        return self.buf.data_ptr() + self.buf.element_size() * GUARD
 
     def view(self):
         return torch.as_strided(self.buf, self.shape, self.strides, storage_offset=GUARD)
@@ -162,7 +174,7 @@ class GuardedOutput:
         inner = self.buf[GUARD:GUARD + self.ext]
         if old is not None:
             inner.fill_(float("nan"))
-            self.view().copy_(torch.from_numpy(np.ascontiguousarray(old)).cuda())
+            self.view().copy_(torch.from_numpy(np.ascontiguousarray(old)).cuda().to(self.buf.dtype))
         else:
             inner.fill_(value)
 
@@ -191,15 +203,15 @@ class GpuBackwardData:
         self.handle = ig.Handle()
         N, K, P, Q = dy.shape
         _, C, R, S = w.shape
-        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        dt = _dt(dtype)
         self.dy_dev, dys = to_device_strided(dy, dtype)
         self.w_dev, _ = to_device_strided(np.ascontiguousarray(w), dtype)
         self.dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
         self.wdesc = ig.FilterDescriptor().set(dt, K, C, R, S)
         self.conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
         shape = (N, C, hw[0], hw[1])
-        self.out = GuardedOutput(shape, layout_strides(shape, dx_layout))
-        self.dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, self.out.strides)
+        self.out = GuardedOutput(shape, layout_strides(shape, dx_layout), dtype)
+        self.dxdesc = ig.TensorDescriptor().set(ig.IGC_DATA_DOUBLE if dtype == "f64" else ig.IGC_DATA_FLOAT, *shape, self.out.strides)
         self.asked = ig.get_backward_data_workspace_size(self.handle, self.wdesc, self.dydesc, self.conv, self.dxdesc)
         self.ws_bytes = self.asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
         self.ws = GuardedOutput((1, 1, 1, max((self.ws_bytes + 3) // 4, 1)), (0, 0, 0, 1))
@@ -238,17 +250,18 @@ class GpuBackwardFilter:
         N, C, H, W = x.shape
         _, K, P, Q = dy.shape
         R, S = rs
-        dt = ig.IGC_DATA_BFLOAT16 if dtype == "bf16" else ig.IGC_DATA_FLOAT
+        dt = _dt(dtype)
         self.x_dev, xs = to_device_strided(x, dtype)
         self.dy_dev, dys = to_device_strided(dy, dtype)
         self.xdesc = ig.TensorDescriptor().set(dt, N, C, H, W, xs)
         self.dydesc = ig.TensorDescriptor().set(dt, N, K, P, Q, dys)
-        self.dwdesc = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
+        self.dwdesc = ig.FilterDescriptor().set(ig.IGC_DATA_DOUBLE if dtype == "f64" else ig.IGC_DATA_FLOAT, K, C, R, S)
         self.conv = ig.ConvolutionDescriptor().set(pad[0], pad[1], stride[0], stride[1], mode)
-        self.out = GuardedOutput((K, C, R, S), (C * R * S, R * S, S, 1))
+        self.out = GuardedOutput((K, C, R, S), (C * R * S, R * S, S, 1), dtype)
         self.asked = ig.get_backward_filter_workspace_size(self.handle, self.xdesc, self.dydesc, self.conv, self.dwdesc)
         self.ws_bytes = self.asked if workspace == "full" else (0 if workspace == "none" else int(workspace))
-        self.ws = GuardedOutput((1, 1, 1, max(self.ws_bytes // 4, 1)), (0, 0, 0, 1))
+        es = 8 if dtype == "f64" else 4
+        self.ws = GuardedOutput((1, 1, 1, max(self.ws_bytes // es, 1)), (0, 0, 0, 1), dtype)
         self.ws.prefill(value=float("nan"))
 
     def launch(self, alpha=1.0, beta=0.0):

@@ -180,7 +180,7 @@ def test_forward_rejects_bad_arguments_before_any_gpu_call():
     assert _fwd_status(xbig, w, c, y) == ig.IGC_STATUS_NOT_SUPPORTED
     # kernel override of the wrong data type
     h = ig.Handle()
-    h.set_kernel_override(len(ig.kernel_names()) - 1)       # a bf16 kernel
+    h.set_kernel_override(len(ig.kernel_names()) - 1)       # a kernel of another data type
     assert _fwd_status(x, w, c, y, handle=h) == ig.IGC_STATUS_NOT_SUPPORTED
 
 
@@ -355,3 +355,25 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError):
         b.lib()
+
+
+def test_double_precision_is_planned_and_mixed_types_are_rejected():
+    h = ig.Handle()
+    D, F = ig.IGC_DATA_DOUBLE, ig.IGC_DATA_FLOAT
+    x, w, c, y = _descs(N=2, C=5, H=9, W=8, K=70, dt=D, ydt=D)
+    plan = ig.get_plan(h, x, w, c, y)
+    assert (plan.tileM, plan.tileN, plan.tileK, plan.gatherMode) == (64, 64, 16, 0)
+    assert ig.kernel_names()[plan.kernelId].startswith("f64")
+    assert plan.gridX >= 2 * ((2 * 9 * 8 + 63) // 64) and plan.gridX % 8 == 0      # one workgroup per tile
+    assert ig.get_workspace_size(h, x, w, c, y) == 0 and ig.get_optional_workspace_size(h, x, w, c, y) == 0
+    assert _fwd_status(x, w, c, _descs(N=2, C=5, H=9, W=8, K=70, dt=D, ydt=F)[3]) == ig.IGC_STATUS_NOT_SUPPORTED
+    xf = _descs(N=2, C=5, H=9, W=8, K=70)[0]
+    assert _fwd_status(xf, w, c, y) == ig.IGC_STATUS_NOT_SUPPORTED
+    # backward passes: the output's type follows the inputs'
+    assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 0
+    assert ig.get_backward_filter_workspace_size(h, x, y, c, w) % (70 * 5 * 9 * 8) == 0
+    with pytest.raises(ig.IgcError):
+        ig.get_backward_data_workspace_size(h, w, y, c, xf)
+    wf = ig.FilterDescriptor().set(F, 70, 5, 3, 3)
+    with pytest.raises(ig.IgcError):
+        ig.get_backward_filter_workspace_size(h, x, y, c, wf)
