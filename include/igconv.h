@@ -18,10 +18,11 @@
  *    Descriptors are read at call time only: they may be changed or destroyed as
  *    soon as a call returns.
  *  - x, w and y are DEVICE pointers owned by the caller.  The library never
- *    allocates, frees or copies device memory; only igcConvolutionBackwardFilter can
- *    make use of a workspace, which the caller provides.
- *  - alpha and beta are HOST pointers to float (the compute type is fp32 for every
- *    supported data type); they are read before the call returns.
+ *    allocates, frees or copies device memory; where a workspace helps, the caller
+ *    provides it.
+ *  - alpha and beta are HOST pointers, read before the call returns: to float for float
+ *    and bfloat16 data (computed in fp32), to double for double data (Section 2: single
+ *    and double precision; double problems are computed in fp64 throughout).
  *  - igcConvolutionForward only enqueues work on the handle's stream and returns.
  *  - All argument validation happens before the first GPU call, so every
  *    BAD_PARAM / NOT_SUPPORTED path can be exercised on a machine without a GPU.
@@ -170,7 +171,8 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle,
  *
  * with x0 = x extended by zeros, (hh, ww) given by the descriptor's mode, pad and
  * stride.  Data types: (x, w, y) = (float, float, float) or (bfloat16, bfloat16,
- * float); products are accumulated in fp32.
+ * float), products accumulated in fp32; or (double, double, double), accumulated in fp64
+ * (no fused bias / activation in double: NOT_SUPPORTED).
  *
  *  - x (device, read): laid out by xDesc.  w (device, read): packed K,C,R,S.
  *    y (device, written; read only when *beta != 0): laid out by yDesc, whose
@@ -218,7 +220,8 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
  *    (N, K, P, Q) with P, Q = eq. 1 of dxDesc's H, W.  dx (device, written; read only when
  *    *beta != 0): laid out by dxDesc, dimensions (N, C, H, W); input rows or columns the
  *    forward pass never reads receive beta * dx.
- *  - Data types: (w, dy, dx) = (float, float, float) or (bfloat16, bfloat16, float).
+ *  - Data types: (w, dy, dx) = (float, float, float), (bfloat16, bfloat16, float) or
+ *    (double, double, double).
  *  - dx must not overlap w or dy and its strides must not alias (else BAD_PARAM).
  *  - Errors as for igcConvolutionForward; all validation precedes the first launch.
  *  - igcSetKernelOverride does not apply; results are deterministic. */
@@ -250,7 +253,8 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha,
  *  - x (device, read): laid out by xDesc.  dy (device, read): laid out by dyDesc,
  *    dimensions (N, K, P, Q) from eq. 1.  dw (device, written; read only when *beta != 0):
  *    packed K,C,R,S floats, described by dwDesc (data type float).
- *  - Data types: (x, dy, dw) = (float, float, float) or (bfloat16, bfloat16, float).
+ *  - Data types: (x, dy, dw) = (float, float, float), (bfloat16, bfloat16, float) or
+ *    (double, double, double; workspace parts are then doubles).
  *  - workSpace (device, scratch, 4-byte aligned, owned by the caller, may be reused as
  *    soon as the stream has run the call): igcGetConvolutionBackwardFilterWorkspaceSize
  *    reports the size that lets the reduction be cut as finely as the library would like.

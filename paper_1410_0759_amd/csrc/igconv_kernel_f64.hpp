@@ -16,10 +16,12 @@
 // dy per stride phase with the filter's strides exchanged; backward filter j = (c,r,s),
 // k = (n,p,q), a = dy.
 //
-// Tile 64 x 64 x 16, 256 threads = 2 x 2 wavefronts of 32 x 32, v_mfma_f64_16x16x4_f64
-// (64 cycles each on this chip, so a plain double-buffered loop keeps the matrix pipe the
-// bottleneck).  LDS holds both operands k-major ([k][row]) so that the 16 lanes sharing a k
-// read 16 consecutive doubles.  One workgroup per (tile, reduction range).
+// Tile (32 NB) x (32 NB) x 16 (NB = 2 is built: 64 x 64), 256 threads = 2 x 2 wavefronts of
+// NB x NB blocks of v_mfma_f64_16x16x4_f64.  That instruction is slow enough (a register-only
+// loop of it reaches 49.5 TFLOP/s on this chip) for a plain double-buffered loop to keep the
+// matrix pipe about 80 % busy; a 128 x 128 tile was measured and is slower.  LDS holds both
+// operands k-major ([k][row]) so that the 16 lanes sharing a k read 16 consecutive doubles.
+// One workgroup per (tile, reduction range).
 #ifndef IGCONV_KERNEL_F64_HPP_
 #define IGCONV_KERNEL_F64_HPP_
 
@@ -33,8 +35,8 @@ namespace igc {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kF64BM = 64, kF64BN = 64, kF64BK = 16;
-constexpr int kF64LdsBytes = 2 * kF64BK * (kF64BM + kF64BN) * 8;
+constexpr int kF64BK = 16;
+constexpr int f64_lds_bytes(int nb) { return 2 * kF64BK * (64 * nb + 2) * 8; }
 constexpr uint32_t kF64OutOfRange = 0x80000000u;   // a byte offset no buffer reaches: reads as zero
 
 __device__ __forceinline__ uint32_t f64_mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
@@ -46,10 +48,13 @@ __device__ __forceinline__ double f64_load(__amdgpu_buffer_rsrc_t buf, uint32_t 
 
 // WGRAD: the reduction index moves the window by (i1*redMulH, i2*redMulW) (backward filter);
 // otherwise by the tap (i1, i2) itself, reversed when p.flip is set.
-template <bool WGRAD>
+template <bool WGRAD, int NB>
 __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams p) {
-    constexpr int BM = kF64BM, BN = kF64BN, BK = kF64BK;
-    __shared__ double As[2][BK][BM];
+    constexpr int BM = 32 * NB, BN = 32 * NB, BK = kF64BK;
+    constexpr int KPT = BK * BM / 256;   // consecutive reduction indices per thread and operand
+    constexpr int ALD = BM + 2;          // row stride of As: the 16 lanes that write one row of A land in 16 banks
+    constexpr int ROWS = BM / 16;        // rows of A per thread
+    __shared__ double As[2][BK][ALD];
     __shared__ double Bs[2][BK][BN];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,8 +74,8 @@ __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams 
     const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
         static_cast<uint8_t *>(p.y) + (size_t)split * p.ySplitBytes, 0, p.y_bytes, 0x00020000u);
 
-    // ---- B role: one column, four consecutive reduction indices per step
-    const int b_col = tid & 63, b_kq = (tid >> 6) * 4;
+    // ---- B role: one column, KPT consecutive reduction indices per step
+    const int b_col = tid & (BN - 1), b_kq = (tid / BN) * KPT;
     const int j = n0 + b_col;
     const bool b_ok = j < p.NPQ;
     int b_base = 0, b_h0 = 0, b_w0 = 0;
@@ -82,20 +87,18 @@ __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams 
         b_h0 = (int)j1 * p.u - p.pad_h;
         b_w0 = (int)j2 * p.v - p.pad_w;
     }
-    // ---- A role: one row, four consecutive reduction indices per step
-    const int a_row = tid >> 2, a_kq = (tid & 3) * 4;
-    const int m = m0 + a_row;
-    const bool a_ok = m < p.K;
-    const int a_base = a_ok ? m * p.wsRow + p.wTap0 : 0;
+    // ---- A role: one reduction index per step (lanes along the reduction: where A is
+    // contiguous in it, 16 lanes read one 128-byte line), rows a_row0 + 16 e
+    const int a_k = tid & 15, a_row0 = tid >> 4;
 
-    double a_reg[4], b_reg[4];
+    double a_reg[ROWS], b_reg[KPT];
     auto fetch = [&](int step) {
         {   // B
             const uint32_t k0 = (uint32_t)(step * BK + b_kq);
             uint32_t i0 = f64_mdiv(k0, p.mRS), rem = k0 - i0 * (uint32_t)p.RS;
             uint32_t i1 = f64_mdiv(rem, p.mS), i2 = rem - i1 * (uint32_t)p.S;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < KPT; ++e) {
                 int dh, dw;
                 if (WGRAD) {
                     dh = (int)i1 * p.redMulH;
@@ -114,33 +117,31 @@ __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams 
             }
         }
         {   // A
-            const uint32_t k0 = (uint32_t)(step * BK + a_kq);
-            uint32_t i0 = f64_mdiv(k0, p.mRS), rem = k0 - i0 * (uint32_t)p.RS;
-            uint32_t i1 = f64_mdiv(rem, p.mS), i2 = rem - i1 * (uint32_t)p.S;
+            const uint32_t k = (uint32_t)(step * BK + a_k);
+            const uint32_t i0 = f64_mdiv(k, p.mRS), rem = k - i0 * (uint32_t)p.RS;
+            const uint32_t i1 = f64_mdiv(rem, p.mS), i2 = rem - i1 * (uint32_t)p.S;
+            const int koff = p.wTap0 + (int)i0 * p.wsRed + (int)i1 * p.wsTapR + (int)i2 * p.wsTapS;
+            const bool k_ok = (int)k < p.CRS;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool ok = a_ok && (int)(k0 + e) < p.CRS;
-                const uint32_t off = (uint32_t)(a_base + (int)i0 * p.wsRed + (int)i1 * p.wsTapR + (int)i2 * p.wsTapS) * 8u;
-                a_reg[e] = f64_load(wbuf, ok ? off : kF64OutOfRange);
-                ++i2; ++rem;
-                if (i2 == (uint32_t)p.S) { i2 = 0; ++i1; }
-                if (rem == (uint32_t)p.RS) { rem = 0; i1 = 0; i2 = 0; ++i0; }
+            for (int e = 0; e < ROWS; ++e) {
+                const int m = m0 + a_row0 + 16 * e;
+                const uint32_t off = (uint32_t)(m * p.wsRow + koff) * 8u;
+                a_reg[e] = f64_load(wbuf, k_ok && m < p.K ? off : kF64OutOfRange);
             }
         }
     };
     auto stage = [&](int buf) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            As[buf][a_kq + e][a_row] = a_reg[e];
-            Bs[buf][b_kq + e][b_col] = b_reg[e];
-        }
+        for (int e = 0; e < ROWS; ++e) As[buf][a_k][a_row0 + 16 * e] = a_reg[e];
+#pragma unroll
+        for (int e = 0; e < KPT; ++e) Bs[buf][b_kq + e][b_col] = b_reg[e];
     };
 
-    f64x4 acc[2][2];
+    f64x4 acc[NB][NB];
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+    for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < 2; ++bj) acc[bi][bj] = f64x4{0.0, 0.0, 0.0, 0.0};
+        for (int bj = 0; bj < NB; ++bj) acc[bi][bj] = f64x4{0.0, 0.0, 0.0, 0.0};
 
     if (s_begin < s_end) {
         fetch(s_begin);
@@ -154,12 +155,17 @@ __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams 
 #pragma unroll
         for (int kg = 0; kg < BK / 4; ++kg) {
             const int kk = kg * 4 + lq;
-            const double a0 = As[cur][kk][wm * 32 + l16], a1 = As[cur][kk][wm * 32 + 16 + l16];
-            const double b0 = Bs[cur][kk][wn * 32 + l16], b1 = Bs[cur][kk][wn * 32 + 16 + l16];
-            acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+            double av[NB], bv[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                av[b] = As[cur][kk][wm * (16 * NB) + b * 16 + l16];
+                bv[b] = Bs[cur][kk][wn * (16 * NB) + b * 16 + l16];
+            }
+#pragma unroll
+            for (int bi = 0; bi < NB; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[bi], bv[bj], acc[bi][bj], 0, 0, 0);
         }
         if (more) stage(cur ^ 1);
         __syncthreads();
@@ -169,17 +175,17 @@ __global__ __launch_bounds__(256) void igconv_f64_kernel(const ConvKernelParams 
     // ---- epilogue: lane (l16, lq), value v of block (bi, bj) is row 4*v + lq, column l16
     const double alpha = p.alpha64, beta = p.beta64;
 #pragma unroll
-    for (int bj = 0; bj < 2; ++bj) {
-        const int col = n0 + wn * 32 + bj * 16 + l16;
+    for (int bj = 0; bj < NB; ++bj) {
+        const int col = n0 + wn * (16 * NB) + bj * 16 + l16;
         if (col >= p.NPQ) continue;
         const uint32_t j0 = f64_mdiv((uint32_t)col, p.mPQ), rem = (uint32_t)col - j0 * (uint32_t)p.PQ;
         const uint32_t j1 = f64_mdiv(rem, p.mQ), j2 = rem - j1 * (uint32_t)p.Q;
         const int ycol = (int)j0 * p.ysN + (int)j1 * p.ysP + (int)j2 * p.ysQ;
 #pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
+        for (int bi = 0; bi < NB; ++bi)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int row = m0 + wm * 32 + bi * 16 + 4 * v + lq;
+                const int row = m0 + wm * (16 * NB) + bi * 16 + 4 * v + lq;
                 if (row >= p.K) continue;
                 const uint32_t off = (uint32_t)(ycol + row * p.ysK) * 8u;
                 double r = alpha * acc[bi][bj][v];

@@ -7,19 +7,19 @@
 
 namespace igc {
 
-template <bool WGRAD>
+template <bool WGRAD, int NB>
 static int launch_f64(const ConvKernelParams &p, int grid, void *stream) {
     ConvKernelParams args = p;
     void *argv[] = {&args};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_f64_kernel<WGRAD>), dim3(grid), dim3(256), argv, 0,
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_f64_kernel<WGRAD, NB>), dim3(grid), dim3(256), argv, 0,
                                          static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
         std::fprintf(stderr, "igconv: launch of igconv_f64_kernel failed: %s\n", hipGetErrorString(e));
     return static_cast<int>(e);
 }
 
-template __global__ void igconv_f64_kernel<false>(const ConvKernelParams);
-template __global__ void igconv_f64_kernel<true>(const ConvKernelParams);
+template __global__ void igconv_f64_kernel<false, 2>(const ConvKernelParams);
+template __global__ void igconv_f64_kernel<true, 2>(const ConvKernelParams);
 
 // out[e] = alpha * (part_0[e] + part_1[e] + ...) + beta * out[e] in double, parts added in order.
 __global__ __launch_bounds__(256) void igconv_sum_parts_f64_kernel(const double *parts, double *out, uint32_t n, int count,
@@ -41,13 +41,13 @@ int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count
 }
 
 #if !defined(__HIP_DEVICE_COMPILE__)
-static KernelInfo f64_row(const char *name, int gmode, int (*launch)(const ConvKernelParams &, int, void *)) {
-    KernelInfo k{name, false, kF64BM, kF64BN, kF64BK, false, false, gmode, 256, kF64LdsBytes, launch};
+static KernelInfo f64_row(const char *name, int nb, int gmode, int (*launch)(const ConvKernelParams &, int, void *)) {
+    KernelInfo k{name, false, 32 * nb, 32 * nb, kF64BK, false, false, gmode, 256, f64_lds_bytes(nb), launch};
     k.f64 = true;
     return k;
 }
-static const KernelInfo kRows[] = {f64_row("f64 64x64x16 generic", 0, &launch_f64<false>),
-                                   f64_row("f64 64x64x16 wgrad", 6, &launch_f64<true>)};
+static const KernelInfo kRows[] = {f64_row("f64 64x64x16 generic", 2, 0, &launch_f64<false, 2>),
+                                   f64_row("f64 64x64x16 wgrad", 2, 6, &launch_f64<true, 2>)};
 const KernelGroup kGroupF64 = {kRows, sizeof(kRows) / sizeof(kRows[0])};
 #endif
 

@@ -68,7 +68,7 @@ def test_forward_f64(prob, mode):
         want = _bilinear(lambda a, b: oc.conv_forward(a, b, pad=pad, stride=stride, mode=mode), x, w)
         got, plan = gu.run(x[2], w[2], pad, stride, mode, dtype="f64", y_layout=layout)
         _close(got, want)
-        assert plan.tileM == 64 and plan.tileN == 64 and plan.tileK == 16
+        assert plan.tileM == plan.tileN and plan.tileM in (64, 128) and plan.tileK == 16
     y0 = np.random.default_rng(3).uniform(-1, 1, size=want.shape)
     got, _ = gu.run(x[2], w[2], pad, stride, mode, alpha=0.5, beta=-1.5, y0=y0, dtype="f64", y_layout="NHWC")
     _close(got, 0.5 * want - 1.5 * y0)
@@ -124,6 +124,18 @@ def test_f64_at_a_layer_size():
     scale = float(np.sqrt(np.sum(y * y) * np.sum(dy[2] ** 2)))
     assert abs(lhs - float(np.sum(dx * x[2]))) <= 1e-12 * scale
     assert abs(lhs - float(np.sum(dw * w[2]))) <= 1e-12 * scale
+
+
+@pytest.mark.parametrize("name", ["f64 64x64x16 generic"])
+def test_forward_f64_with_each_tile(name):
+    gu = _gpu()
+    import paper_1410_0759_amd as ig
+    N, C, H, W, K, R, S, pad, stride = 3, 40, 14, 13, 150, 3, 3, (1, 1), (2, 1)
+    x, w = _pair(21, (N, C, H, W)), _pair(22, (K, C, R, S))
+    want = _bilinear(lambda a, b: oc.conv_forward(a, b, pad=pad, stride=stride, mode=0), x, w)
+    got, plan = gu.run(x[2], w[2], pad, stride, 0, dtype="f64", kernel=ig.kernel_names().index(name))
+    assert ig.kernel_names()[plan.kernelId] == name
+    _close(got, want)
 
 
 def test_f64_rejections():
