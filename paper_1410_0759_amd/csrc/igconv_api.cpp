@@ -24,7 +24,7 @@ constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels};
 
 int kernel_count() {
     int n = 0;
@@ -192,7 +192,7 @@ static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
 // staging a patch of the zero-extended image needs every tile's pixel range to fit it.
 static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
     const int gmode = ki.gmode;
-    if (gmode == 6 || gmode == 8 || gmode == 9) return false;  // backward-filter kernels are chosen by that pass itself
+    if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 7) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
@@ -245,7 +245,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.f64) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.f64) return tiles_per_xcd;
     const int occ = std::max(1, std::min(2, (160 * 1024) / ki.ldsBytes));
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * occ);
 }
@@ -484,7 +484,7 @@ struct BackwardFilterProblem {
 
 static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDescriptor_t dy,
                                           igcConvolutionDescriptor_t cv, igcFilterDescriptor_t dw,
-                                          BackwardFilterProblem *out) {
+                                          BackwardFilterProblem *out, bool aligned16 = true) {
     if (!x || !dy || !cv || !dw) return IGC_STATUS_BAD_PARAM;
     if (!x->set || !dy->set || !cv->set || !dw->set) return IGC_STATUS_NOT_INITIALIZED;
     if (x->dim[1] != dw->c || dy->dim[1] != dw->k || dy->dim[0] != x->dim[0]) return IGC_STATUS_BAD_PARAM;
@@ -542,8 +542,13 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     // one tap per tile (gather mode 8; any filter size).  Otherwise the generic gather over
     // columns (c,r,s) set up above (mode 6).  Row tile: the smaller one when it covers K.
     const bool by_tap = dw->c >= 24 && !f64;   // (double precision has the generic gather only)
+    // bf16 with unit channel strides, whole 16-byte channel vectors everywhere: columns (tap, channel) as for
+    // mode 8, operands loaded as channel vectors and transposed on the way into LDS (mode 10)
+    bool vectors = b16 && by_tap && aligned16 && x->stride[1] == 1 && dy->stride[1] == 1 && dw->c % 8 == 0 && dw->k % 8 == 0;
+    for (int d : {0, 2, 3})
+        if (x->stride[d] % 8 != 0 || dy->stride[d] % 8 != 0) vectors = false;
     const bool unpadded = !by_tap && !f64 && cv->pad_h == 0 && cv->pad_w == 0;   // few channels, no padding: mode 9
-    const int want_mode = by_tap ? 8 : (unpadded ? 9 : 6);
+    const int want_mode = vectors ? 10 : (by_tap ? 8 : (unpadded ? 9 : 6));
     if (f64) {
         for (int i = 0; i < kernel_count(); ++i)
             if (kernel_info(i)->f64 && kernel_info(i)->gmode == 6) out->kernel_id = i;
@@ -557,6 +562,7 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     int want_bm = 64;
     for (int bm : {96, 128}) {
         if (bm == 96 && b16) continue;
+        if (vectors && dw->k <= 64) continue;   // (the vector kernels run one tile per workgroup: no gain from padding K)
         const long long pad_new = (long long)((dw->k + bm - 1) / bm) * bm, pad_old = (long long)((dw->k + want_bm - 1) / want_bm) * want_bm;
         if (pad_new <= pad_old) want_bm = bm;
     }
@@ -1018,7 +1024,7 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
                                        igcFilterDescriptor_t dwDesc, void *dw) {
     if (!handle || !alpha || !beta || !x || !dy || !dw) return IGC_STATUS_BAD_PARAM;
     BackwardFilterProblem b;
-    igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b);
+    igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b, (uintptr_t)x % 16 == 0 && (uintptr_t)dy % 16 == 0);
     if (st != IGC_STATUS_SUCCESS) return st;
     const bool f64 = b.pr.f64;
     const int es = b.pr.bf16 ? 2 : (f64 ? 8 : 4), out_es = f64 ? 8 : 4;

@@ -17,7 +17,8 @@ struct KernelInfo {
                     // 6 backward-filter (generic gather, roles of columns and reduction exchanged),
                     // 7 unpadded with the tap offsets in an LDS table (short reductions),
                     // 8 backward-filter with columns (tap, channel), one tap per tile,
-                    // 9 backward-filter without padding, few channels
+                    // 9 backward-filter without padding, few channels,
+                    // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
@@ -33,7 +34,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.

@@ -174,6 +174,37 @@ def test_backward_filter_workspace_sizes_and_accumulate():
     assert np.array_equal(again, full), "same call, same bits"
 
 
+# bf16 with contiguous channels in x and dy, C >= 24, C and K multiples of 8: the channel-vector
+# kernels (operand tiles transposed in registers).  N, C, H, W, K, R, S, pad, stride
+BF_VECTOR_PROBLEMS = [
+    (2, 24, 12, 13, 64, 3, 3, (1, 1), (1, 1)),
+    (3, 40, 14, 13, 152, 3, 3, (1, 1), (1, 1)),       # ragged row and column tiles
+    (1, 136, 7, 9, 8, 3, 3, (1, 1), (1, 1)),          # 63 pixels: a single, partial step; K below a vector row tile
+    (2, 32, 9, 9, 72, 1, 1, (0, 0), (1, 1)),          # 1x1
+    (2, 24, 15, 17, 40, 5, 5, (2, 2), (2, 2)),        # stride 2, 25 taps
+    (2, 64, 10, 12, 200, 3, 2, (0, 1), (1, 2)),       # unequal filter, pads and strides
+    (5, 48, 20, 20, 96, 3, 3, (2, 2), (1, 1)),        # "full" padding, 2420 pixels: several ranges
+    (1, 24, 6, 70, 16, 1, 7, (0, 3), (1, 3)),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+@pytest.mark.parametrize("prob", BF_VECTOR_PROBLEMS, ids=[str(i) for i in range(len(BF_VECTOR_PROBLEMS))])
+def test_backward_filter_bf16_channel_vectors(prob, mode):
+    kw = dict(x_layout="NHWC", dy_layout="NHWC", seed=5)
+    first, asked = _check_bf(prob, "bf16", mode, **kw)
+    again, _ = _check_bf(prob, "bf16", mode, **kw)
+    assert np.array_equal(first, again)            # ordered sum of the ranges: repeatable bit by bit
+    _check_bf(prob, "bf16", mode, workspace="none", **kw)
+    K, C, R, S = prob[4], prob[1], prob[5], prob[6]
+    if asked:
+        _check_bf(prob, "bf16", mode, workspace=2 * K * C * R * S * 4, **kw)   # room for two ranges only
+    _check_bf(prob, "bf16", mode, alpha=0.5, beta=-2.0, **kw)
+    _check_bf(prob, "bf16", mode, alpha=0.5, beta=-2.0, workspace="none", **kw)
+    # one operand without contiguous channels: the element-wise kernels take over
+    _check_bf(prob, "bf16", mode, x_layout="NHWC", dy_layout="NCHW", seed=5)
+
+
 def test_backward_filter_is_the_transpose_of_forward_on_the_gpu():
     gu = _gpu()
     N, C, H, W, K, R, S, pad, stride = BWD_PROBLEMS[2]
