@@ -480,6 +480,10 @@ struct BackwardFilterProblem {
     long long tiles;   // output tiles
     long long tiles_n; // of which along the columns
     uint32_t out_elems;  // K*C*R*S
+    // channel-vector kernels (gather mode 10): a part of the workspace holds [tap][row position][column position],
+    // rows and columns padded to whole tiles; 0 for the other kernels, whose parts are copies of dw
+    long long pos_rows = 0, pos_cols = 0;
+    long long part_elems() const { return pos_rows ? pos_rows * pos_cols * (out_elems / (pr.kp.K * (long long)pr.kp.NPQ)) : out_elems; }
 };
 
 static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDescriptor_t dy,
@@ -590,6 +594,11 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
         magic_for((uint32_t)k.PQ, &k.mPQ); magic_for((uint32_t)k.Q, &k.mQ);
         k.ysQ = dw->r * dw->s; k.ysN = 0; k.ysP = 0;
         out->tiles_n = (long long)dw->r * dw->s * cblocks;
+        if (ki.gmode == 10) {
+            out->pos_rows = (long long)((dw->k + ki.BM - 1) / ki.BM) * ki.BM;
+            out->pos_cols = (long long)cblocks * ki.BN;
+            if (out->pos_rows * out->pos_cols * dw->r * dw->s * 4 >= kMaxBytes) return IGC_STATUS_NOT_SUPPORTED;
+        }
     } else if (unpadded) {
         // columns (c,r,s) in filter order at distance 1 in dw; PQ = R*S, Q = S and R decode a column
         k.NPQ = (int)CRS; k.PQ = dw->r * dw->s; k.Q = dw->s; k.R = dw->r;
@@ -1014,7 +1023,8 @@ igcStatus igcGetConvolutionBackwardFilterWorkspaceSize(igcHandle_t handle, igcTe
     if (st != IGC_STATUS_SUCCESS) return st;
     int splits, per;
     backward_filter_split(b, 1 << 20, &splits, &per);
-    *sizeInBytes = splits > 1 ? (size_t)splits * b.out_elems * (b.pr.f64 ? 8 : 4) : 0;
+    // (the channel-vector kernels want their workspace even for a single range: see the entry point)
+    *sizeInBytes = splits > 1 || b.pos_rows ? (size_t)splits * b.part_elems() * (b.pr.f64 ? 8 : 4) : 0;
     return IGC_STATUS_SUCCESS;
 }
 
@@ -1029,9 +1039,13 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     const bool f64 = b.pr.f64;
     const int es = b.pr.bf16 ? 2 : (f64 ? 8 : 4), out_es = f64 ? 8 : 4;
     if ((uintptr_t)x % es || (uintptr_t)dy % es || (uintptr_t)dw % out_es || (uintptr_t)workSpace % out_es) return IGC_STATUS_BAD_PARAM;
-    const size_t part_bytes = (size_t)b.out_elems * out_es;
+    const size_t part_bytes = (size_t)b.part_elems() * out_es;
     int splits, per;
-    backward_filter_split(b, workSpace ? (long long)(workSpaceSizeInBytes / part_bytes) : 0, &splits, &per);
+    const long long room = workSpace ? (long long)(workSpaceSizeInBytes / part_bytes) : 0;
+    backward_filter_split(b, room, &splits, &per);
+    // Channel-vector kernels: with room for at least one part the results go to the workspace in accumulator
+    // order (coalesced) and the summing kernel moves them to dw; writing dw's layout from the tile is slow.
+    const bool positions = b.pos_rows != 0 && room >= 1;
     ConvKernelParams &k = b.pr.kp;
     igcConvolutionForwardPlan plan;
     st = fill_plan(b.kernel_id, &b.pr, &plan);
@@ -1047,10 +1061,14 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     k.tilesPerXcd = (int)((b.tiles * splits + 7) / 8);
     if ((long long)k.tilesPerXcd * 8 >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     k.wgsPerXcd = workgroups_per_xcd(*kernel_info(b.kernel_id), k.tilesPerXcd);
-    if (splits > 1) {
+    if (splits > 1 || positions) {
         k.y = workSpace;
         k.alpha = 1.f; k.alpha64 = 1.0;
         k.beta = 0.f; k.beta64 = 0.0;
+        if (positions) {
+            k.ysN = 1; k.ysP = (int)b.pos_rows; k.ysK = (int)b.pos_cols;
+            k.y_bytes = (uint32_t)part_bytes;
+        }
     } else {
         k.y = dw;
         k.alpha = a; k.alpha64 = a64;
@@ -1064,6 +1082,15 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
         launch_sum_parts_f64(static_cast<const double *>(workSpace), static_cast<double *>(dw), b.out_elems, splits, b.out_elems,
                              a64, bt64, handle->stream) != 0)
         return IGC_STATUS_EXECUTION_FAILED;
+    if (positions) {
+        const KernelInfo &ki = *kernel_info(b.kernel_id);
+        const int RS = (int)(b.out_elems / ((long long)k.K * k.NPQ));
+        if (launch_sum_positions(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
+                                 (uint32_t)b.part_elems(), a, bt, k.NPQ, RS, ki.BM, ki.BN, (int)b.pos_rows, (int)b.pos_cols,
+                                 handle->stream) != 0)
+            return IGC_STATUS_EXECUTION_FAILED;
+        return IGC_STATUS_SUCCESS;
+    }
     if (splits > 1 && !f64 && launch_sum_parts(static_cast<const float *>(workSpace), static_cast<float *>(dw), b.out_elems, splits,
                                                b.out_elems, a, bt, handle->stream) != 0)
         return IGC_STATUS_EXECUTION_FAILED;

@@ -45,6 +45,10 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
 // dimensions exchanged, each pair's nine taps kept in order); returns the runtime's error code.
 int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream);
 
+// The same for the channel-vector backward-filter kernels, whose parts are stored as [tap][row position][column
+// position] (KP x CP positions per tap, tiles of BM x BN): see igconv_kernel_wgrad_bf16c.hpp.
+int launch_sum_positions(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta, int C,
+                         int RS, int BM, int BN, int KP, int CP, void *stream);
 int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count, uint32_t stride, double alpha, double beta,
                          void *stream);
 

@@ -22,8 +22,12 @@
 // computes the 64 offsets of a step, one pixel per lane, two steps ahead, into a small LDS
 // table; the loading threads fetch their 8 offsets with two 16-byte LDS reads.
 //
-// One workgroup per (tile, reduction range); partial results go to the workspace and are
-// added in order by the summing kernel, as for the other backward-filter kernels.
+// One workgroup per (tile, reduction range).  With a workspace the results are stored in
+// the order the accumulators have them, [range][tap][row position][column position] padded
+// to whole tiles (32 lanes write 128 contiguous bytes), and igconv_sum_positions_kernel adds
+// the ranges in order while it moves the sums to dw[k][c][r][s]; dw itself has one tap's
+// elements 4*R*S bytes apart, and writing it from here (no workspace) costs as much as the
+// whole reduction.
 #ifndef IGCONV_KERNEL_WGRAD_BF16C_HPP_
 #define IGCONV_KERNEL_WGRAD_BF16C_HPP_
 
@@ -47,9 +51,10 @@ struct WgradBf16cConfig {
     static constexpr int BM = BM_, BN = BN_, BK = kWgcBK;
     static constexpr int THREADS = 256;
     static constexpr int STAGE_BYTES = (BM + BN) * kWgcRowBytes;
-    static constexpr int TABLE_BYTES = 2 * 2 * kWgcBK * 4;   // [slot][operand][pixel]
+    static constexpr int TABLE_BYTES = 2 * 4 * kWgcBK * 4;   // [slot][wavefront][pixel]: wavefronts 0, 1 hold dy's and x's offsets
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES + TABLE_BYTES;
     static_assert(BM % 64 == 0 && BN % 64 == 0 && BM + BN <= 256, "one 8x8 block per thread");
+    // (with BM + BN < 256 the last wavefronts repeat blocks of the x operand: same loads, same values written)
 };
 
 __device__ __forceinline__ uint32_t wgc_mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
@@ -60,7 +65,7 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
     constexpr int MB = BM / 64, NB = BN / 64;      // 32x32 blocks per wavefront (2 x 2 wavefronts)
     constexpr int RB = kWgcRowBytes;
     __shared__ __attribute__((aligned(16))) uint8_t lds[Cfg::LDS_BYTES];
-    uint32_t *const table = reinterpret_cast<uint32_t *>(lds + 2 * Cfg::STAGE_BYTES);   // [2][2][64]
+    uint32_t *const table = reinterpret_cast<uint32_t *>(lds + 2 * Cfg::STAGE_BYTES);   // [2][4][64]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -87,42 +92,39 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
     const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
         static_cast<uint8_t *>(p.y) + (size_t)split * p.ySplitBytes, 0, p.y_bytes, 0x00020000u);
 
-    // ---- offsets of the 64 pixels of a step: wavefront 0 for dy, wavefront 1 for x, one pixel per lane
+    // ---- offsets of the 64 pixels of a step: wavefront 0 for dy, wavefront 1 for x, one pixel per lane.
+    // (Wavefronts 2 and 3 do the same into slots nobody reads: the loop stays free of branches, which
+    // keeps the compiler from waiting for all outstanding loads at block boundaries.)
+    const bool table_dy = (wave & 1) == 0;
     auto fill_table = [&](int step) {
-        if (wave >= 2) return;
         const uint32_t i = (uint32_t)step * BK + (uint32_t)lane;
         const uint32_t n = wgc_mdiv(i, p.mRS), rem = i - n * (uint32_t)p.RS;
         const uint32_t pp = wgc_mdiv(rem, p.mS), qq = rem - pp * (uint32_t)p.S;
         const bool live = i < (uint32_t)p.CRS && step < s_end;
-        uint32_t off;
-        if (wave == 0) {
-            off = live ? (n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * 2u : kWgcOutOfRange;
-        } else {
-            const uint32_t hh = pp * (uint32_t)p.redMulH + (uint32_t)tap_h;   // (wraps below zero: fails the test)
-            const uint32_t ww = qq * (uint32_t)p.redMulW + (uint32_t)tap_w;
-            const bool ok = live && hh < (uint32_t)p.H && ww < (uint32_t)p.W;
-            off = ok ? (n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * 2u : kWgcOutOfRange;
-        }
-        table[((step & 1) * 2 + wave) * BK + lane] = off;
+        const uint32_t hh = table_dy ? pp : pp * (uint32_t)p.redMulH + (uint32_t)tap_h;   // (wraps below zero: fails the test)
+        const uint32_t ww = table_dy ? qq : qq * (uint32_t)p.redMulW + (uint32_t)tap_w;
+        const bool ok = live && (table_dy || (hh < (uint32_t)p.H && ww < (uint32_t)p.W));
+        const uint32_t sn = table_dy ? (uint32_t)p.wsRed : (uint32_t)p.xsC, sh = table_dy ? (uint32_t)p.wsTapR : (uint32_t)p.xsH,
+                       sw = table_dy ? (uint32_t)p.wsTapS : (uint32_t)p.xsW;
+        table[((step & 1) * 4 + wave) * BK + lane] = ok ? (n * sn + hh * sh + ww * sw) * 2u : kWgcOutOfRange;
     };
 
     // ---- loading role: thread -> (operand, channel vector cv, pixel group pg)
-    const bool role_a = tid < BM, role_b = !role_a && tid < BM + BN;
-    const int blk = role_a ? tid : tid - BM;
+    const bool role_a = wave < BM / 64;      // (uniform over a wavefront: the buffer descriptor is chosen by a scalar select)
+    const int blk = role_a ? tid : (tid - BM) % BN;
     constexpr int NVA = BM / 8, NVB = BN / 8;
     const int cv = role_a ? blk % NVA : blk % NVB;
     const int pg = role_a ? blk / NVA : blk / NVB;     // 0..7
     // byte offset of the channel vector inside a pixel; out of range when the tile overhangs K resp. C
     const int ch0 = (role_a ? m0 : n0) + cv * 8;
-    const uint32_t vec_off = (role_a || role_b) && ch0 < (role_a ? p.K : p.NPQ) ? (uint32_t)ch0 * 2u : kWgcOutOfRange;
+    const uint32_t vec_off = ch0 < (role_a ? p.K : p.NPQ) ? (uint32_t)ch0 * 2u : kWgcOutOfRange;
     // LDS: row position of channel (cv, ch) is ch*NV + cv (B rows follow the BM rows of A)
     const int row0 = role_a ? cv : BM + cv;
     const int row_step = role_a ? NVA : NVB;
 
     wg_u32x4 ld[8];
     auto fetch = [&](int step) {
-        if (!(role_a || role_b)) return;
-        const uint32_t *t = table + ((step & 1) * 2 + (role_a ? 0 : 1)) * BK + pg * 8;
+        const uint32_t *t = table + ((step & 1) * 4 + (role_a ? 0 : 1)) * BK + pg * 8;
         const wg_u32x4 o0 = *reinterpret_cast<const wg_u32x4 *>(t), o1 = *reinterpret_cast<const wg_u32x4 *>(t + 4);
         const uint32_t offs[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
 #pragma unroll
@@ -134,7 +136,6 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
     };
     // 8 pixels x 8 channels -> 8 channels x 8 pixels, one 16-byte LDS row piece per channel
     auto stage = [&](int buf) {
-        if (!(role_a || role_b)) return;
         uint8_t *base = lds + buf * Cfg::STAGE_BYTES + pg * 16;
 #pragma unroll
         for (int ch = 0; ch < 8; ++ch) {
@@ -158,15 +159,12 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
     fill_table(s_begin);
     fill_table(s_begin + 1);
     __syncthreads();
-    if (s_begin < s_end) {
-        fetch(s_begin);
-        stage(0);
-    }
+    fetch(s_begin);
+    stage(0);
     __syncthreads();
     int cur = 0;
     for (int s = s_begin; s < s_end; ++s) {
-        const bool more = s + 1 < s_end;
-        if (more) fetch(s + 1);
+        fetch(s + 1);           // (past the range's end the table holds out-of-range offsets: zeros are loaded)
         fill_table(s + 2);      // (slot of step s: its offsets were fetched before the last barrier)
         const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
         const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
@@ -183,12 +181,34 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
                 for (int j = 0; j < NB; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        if (more) stage(cur ^ 1);
+        // (the loads issued at the top of this step are consumed only now: without this fence the
+        // compiler moves the transposition, and with it the wait for the loads, up behind the first MFMA)
+        __builtin_amdgcn_sched_barrier(0);
+        stage(cur ^ 1);
         __syncthreads();
         cur ^= 1;
     }
 
-    // ---- epilogue: dw[k*ysK + c*ysQ + tap]; MFMA row/column index -> channel through the LDS row positions
+    // ---- epilogue.  Workspace (ysN != 0): [tap][row position][column position], ysP x ysK positions per tap.
+    if (p.ysN != 0) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const uint32_t col = (uint32_t)(n0 + wn * (BN / 2) + j * 32 + l32);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t row = (uint32_t)(m0 + wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * half + (v % 4));
+                    const uint32_t off = ((tap * (uint32_t)p.ysP + row) * (uint32_t)p.ysK + col) * 4u;
+                    // (alpha is 1 here; the product keeps the store's source in an ordinary vector register -
+                    // storing the accumulator element directly was compiled into 16 stores of element 0)
+                    const float r = p.alpha * acc[i][j][v];
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), ybuf, off, 0, 0);
+                }
+        }
+        return;
+    }
+    // Straight into dw[k*ysK + c*ysQ + tap]; MFMA row/column index -> channel through the LDS row positions
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         const int posc = wn * (BN / 2) + j * 32 + l32;
