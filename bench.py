@@ -81,7 +81,7 @@ def run_config(index, steps, warmup, oracle_seconds, kernel=None, workload=None,
     }
 
 
-def run_backward(index, steps, warmup, oracle_seconds):
+def run_backward(index, steps, warmup, oracle_seconds, workload=None):
     """Backward data and backward filter at one workload's size: seeded dy of the forward
     output's shape, timing of each pass, parity against the oracle's backward forms on the
     first n images (backward data: those images of dx; backward filter: the same pass run
@@ -91,7 +91,7 @@ def run_backward(index, steps, warmup, oracle_seconds):
     from oracle import conv_oracle as oc
     from tests import gpu_util as gu
 
-    w_ = wl.by_index(index)
+    w_ = workload if workload is not None else wl.by_index(index)
     x, w, _ = wl.make_inputs(w_)
     pad, stride = (w_.pad_h, w_.pad_w), (w_.u, w_.v)
     dy = np.random.default_rng(14100759 * 10 + w_.index + 300).uniform(-1, 1, size=(w_.N, w_.K, w_.P, w_.Q)).astype(np.float32)
@@ -362,7 +362,9 @@ def main():
         del src, dst
 
     if args.backward_only:
-        print(json.dumps(run_backward(args.backward_only, args.steps, args.warmup, 1.0)))
+        import workloads as wl
+        big = wl.shrink(wl.by_index(5), 256) if args.backward_only == 6 else None     # (6: the bf16 workload at a mini-batch of 256)
+        print(json.dumps(run_backward(args.backward_only, args.steps, args.warmup, 1.0, workload=big)))
         return
 
     if args.other_only:
@@ -405,6 +407,8 @@ def main():
     if not args.only and not args.no_backward:
         for i in (2, 3, 4, 5):
             backward.append(run_backward(i, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0))
+        import workloads as wl
+        backward.append(run_backward(None, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0, workload=wl.shrink(wl.by_index(5), 256)))
 
     other = []
     double_precision = None

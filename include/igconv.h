@@ -259,8 +259,11 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha,
  *    soon as the stream has run the call): igcGetConvolutionBackwardFilterWorkspaceSize
  *    reports the size that lets the reduction be cut as finely as the library would like.
  *    Any smaller size is accepted, NULL / 0 included: the reduction is then cut into as
- *    many ranges as fit (a multiple of K*C*R*S*4 bytes each), down to a single range that
- *    writes dw directly - same result up to summation order, less parallelism.
+ *    many ranges as fit (a part is K*C*R*S results; for bfloat16 x and dy with unit channel
+ *    strides K and C are rounded up to the kernel's tiles, and the workspace is used even for
+ *    a single range, because that kernel keeps its results in another order than dw's),
+ *    down to a single range that writes dw directly - same result up to summation order,
+ *    less parallelism.
  *  - dw and workSpace must not overlap x, dy or each other.
  *  - NOT_SUPPORTED also when H + 2*pad_h or W + 2*pad_w exceeds 2^14.
  *  - Other errors as for igcConvolutionForward; igcSetKernelOverride does not apply. */

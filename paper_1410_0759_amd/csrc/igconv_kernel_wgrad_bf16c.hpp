@@ -122,8 +122,9 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
     const int row0 = role_a ? cv : BM + cv;
     const int row_step = role_a ? NVA : NVB;
 
-    wg_u32x4 ld[8];
-    auto fetch = [&](int step) {
+    // two register sets: the loads of step t go to set (t - first step) & 1
+    wg_u32x4 ld0[8], ld1[8];
+    auto fetch = [&](int step, wg_u32x4 (&ld)[8]) {
         const uint32_t *t = table + ((step & 1) * 4 + (role_a ? 0 : 1)) * BK + pg * 8;
         const wg_u32x4 o0 = *reinterpret_cast<const wg_u32x4 *>(t), o1 = *reinterpret_cast<const wg_u32x4 *>(t + 4);
         const uint32_t offs[8] = {o0[0], o0[1], o0[2], o0[3], o1[0], o1[1], o1[2], o1[3]};
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
         }
     };
     // 8 pixels x 8 channels -> 8 channels x 8 pixels, one 16-byte LDS row piece per channel
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, const wg_u32x4 (&ld)[8]) {
         uint8_t *base = lds + buf * Cfg::STAGE_BYTES + pg * 16;
 #pragma unroll
         for (int ch = 0; ch < 8; ++ch) {
@@ -155,17 +156,14 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- pipeline: table two steps ahead, global loads one step ahead
-    fill_table(s_begin);
-    fill_table(s_begin + 1);
-    __syncthreads();
-    fetch(s_begin);
-    stage(0);
-    __syncthreads();
-    int cur = 0;
-    for (int s = s_begin; s < s_end; ++s) {
-        fetch(s + 1);           // (past the range's end the table holds out-of-range offsets: zeros are loaded)
-        fill_table(s + 2);      // (slot of step s: its offsets were fetched before the last barrier)
+    // ---- pipeline: global loads two steps ahead (their transposition into LDS, one step later, then
+    // never waits and can be spread between the MFMAs of the running step), offset table three steps ahead.
+    // Step s computes from LDS stage `cur`, moves the loaded data of step s+1 to the other stage and
+    // requests step s+2; past the range's end the table holds out-of-range offsets, so the extra step of
+    // an odd range and the look-ahead load zeros.
+    auto body = [&](int s, int cur, wg_u32x4 (&ld_new)[8], const wg_u32x4 (&ld_next)[8]) {
+        fetch(s + 2, ld_new);       // (table slot of step s)
+        fill_table(s + 3);          // (slot of step s+1: its offsets were fetched before the last barrier)
         const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
         const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
 #pragma unroll
@@ -181,12 +179,21 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
                 for (int j = 0; j < NB; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
-        // (the loads issued at the top of this step are consumed only now: without this fence the
-        // compiler moves the transposition, and with it the wait for the loads, up behind the first MFMA)
-        __builtin_amdgcn_sched_barrier(0);
-        stage(cur ^ 1);
+        stage(cur ^ 1, ld_next);
         __syncthreads();
-        cur ^= 1;
+    };
+    fill_table(s_begin);
+    fill_table(s_begin + 1);
+    __syncthreads();
+    fetch(s_begin, ld0);
+    fetch(s_begin + 1, ld1);
+    __syncthreads();
+    fill_table(s_begin + 2);
+    stage(0, ld0);
+    __syncthreads();
+    for (int s = s_begin; s < s_end; s += 2) {
+        body(s, 0, ld0, ld1);
+        body(s + 1, 1, ld1, ld0);
     }
 
     // ---- epilogue.  Workspace (ysN != 0): [tap][row position][column position], ysP x ysK positions per tap.

@@ -22,28 +22,35 @@ static int launch_wgc(const ConvKernelParams &p, int grid, void *stream) {
 // out[k][c][t] = alpha * sum over the parts of part[t][row position of k][column position of c] + beta * out[k][c][t]:
 // adds the ranges in order and undoes the order the channel-vector kernels keep their results in
 // (channel 8 cv + ch of a tile of B channels sits at position ch*(B/8) + cv; parts are KP x CP positions per tap).
+// One thread per (row position, column position), lanes along the column positions: every tap's read is a
+// contiguous run per wavefront, and a thread writes the R*S taps of its (k, c), contiguous in dw.
 __global__ __launch_bounds__(256) void igconv_sum_positions_kernel(const float *parts, float *out, uint32_t n, int count,
                                                                    uint32_t stride, float alpha, float beta, int C, int RS,
                                                                    int BM, int BN, int KP, int CP) {
     const uint32_t e = blockIdx.x * 256u + threadIdx.x;
-    if (e >= n) return;
-    const uint32_t kc = e / (uint32_t)RS, t = e - kc * (uint32_t)RS;
-    const uint32_t k = kc / (uint32_t)C, c = kc - k * (uint32_t)C;
-    const uint32_t kl = k % (uint32_t)BM, cl = c % (uint32_t)BN;
-    const uint32_t row = k - kl + (kl % 8u) * (uint32_t)(BM / 8) + kl / 8u;
-    const uint32_t col = c - cl + (cl % 8u) * (uint32_t)(BN / 8) + cl / 8u;
-    const size_t src = ((size_t)t * KP + row) * CP + col;
-    float acc = 0.f;
-    for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + src];
-    float r = alpha * acc;
-    if (beta != 0.f) r += beta * out[e];
-    out[e] = r;
+    if (e >= (uint32_t)KP * (uint32_t)CP) return;
+    const uint32_t row = e / (uint32_t)CP, col = e - row * (uint32_t)CP;
+    const uint32_t rl = row % (uint32_t)BM, cl = col % (uint32_t)BN;
+    const uint32_t nva = (uint32_t)BM / 8u, nvb = (uint32_t)BN / 8u;
+    const uint32_t k = row - rl + (rl % nva) * 8u + rl / nva;     // position ch*nv + cv holds channel 8 cv + ch
+    const uint32_t c = col - cl + (cl % nvb) * 8u + cl / nvb;
+    if (c >= (uint32_t)C || (size_t)(k * (uint32_t)C + c) * RS >= n) return;
+    float *dst = out + (size_t)(k * (uint32_t)C + c) * RS;
+    for (int t = 0; t < RS; ++t) {
+        const size_t src = ((size_t)t * KP + row) * CP + col;
+        float acc = 0.f;
+        for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + src];
+        float r = alpha * acc;
+        if (beta != 0.f) r += beta * dst[t];
+        dst[t] = r;
+    }
 }
 
 int launch_sum_positions(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta, int C,
                          int RS, int BM, int BN, int KP, int CP, void *stream) {
     void *argv[] = {&parts, &out, &n, &count, &stride, &alpha, &beta, &C, &RS, &BM, &BN, &KP, &CP};
-    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_positions_kernel), dim3((n + 255u) / 256u),
+    const uint32_t threads = (uint32_t)KP * (uint32_t)CP;
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_positions_kernel), dim3((threads + 255u) / 256u),
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
