@@ -285,3 +285,44 @@ def test_random_problems_forward_and_both_backward_passes(chunk):
         assert np.max(np.abs(dx - want)) <= gu.TOL[dtype] * max(np.max(np.abs(want)), 1e-30)
         dw, _ = gu.run_backward_filter(x, dy, (R, S), pad, stride, mode, dtype=dtype)
         assert gu.rel_err(dw, oc.conv_backward_filter(x, dy, (R, S), pad=pad, stride=stride, mode=mode)) <= gu.TOL[dtype]
+
+
+# ------------------------------------------------------------------ extents just below the 2^31-byte limit
+def test_all_passes_with_a_tensor_of_almost_two_gibibytes():
+    """x (and dx) of 1 x 8 x 8191 x 8191 floats = 2 146 959 392 bytes, 524 256 bytes below the
+    limit of the 32-bit byte offsets: the last rows of the last channel sit at the highest
+    offsets the library can form.  3x3, stride 2, no padding.  The oracle checks the top and the
+    bottom strip of every result (a strip of the image is a problem of its own)."""
+    gu = _gpu()
+    N, C, H, W, K, R, S, stride = 1, 8, 8191, 8191, 4, 3, 3, (2, 2)
+    P, Q = oc.output_dim(H, R, 2, 0), oc.output_dim(W, S, 2, 0)
+    rng = np.random.default_rng(2031)
+    x = rng.random(size=(N, C, H, W), dtype=np.float32) - np.float32(0.5)
+    w = _rnd(1, (K, C, R, S), "f32")
+    rows = 65                       # image rows in a strip: 32 output rows
+    prow = (rows - R) // 2 + 1
+    print("forward near the offset limit", flush=True)
+    y, _ = gu.run(x, w, (0, 0), stride, 1)
+    assert y.shape == (N, K, P, Q)
+    for strip, out in ((slice(0, rows), slice(0, prow)), (slice(H - rows, H), slice(P - prow, P))):
+        want = oc.conv_forward(np.ascontiguousarray(x[:, :, strip]), w, stride=stride, mode=1)
+        assert gu.rel_err(y[:, :, out], want) <= gu.TOL["f32"]
+    del y
+    print("backward filter near the offset limit", flush=True)
+    # dy zero except in the top and bottom strips: dw is then the sum of the two strips' own results
+    dy = np.zeros((N, K, P, Q), dtype=np.float32)
+    dy[:, :, :prow] = rng.random(size=(N, K, prow, Q), dtype=np.float32) - np.float32(0.5)
+    dy[:, :, P - prow:] = rng.random(size=(N, K, prow, Q), dtype=np.float32) - np.float32(0.5)
+    dw, _ = gu.run_backward_filter(x, dy, (R, S), (0, 0), stride, 1)
+    want = (oc.conv_backward_filter(np.ascontiguousarray(x[:, :, :rows]), np.ascontiguousarray(dy[:, :, :prow]), (R, S), stride=stride, mode=1)
+            + oc.conv_backward_filter(np.ascontiguousarray(x[:, :, H - rows:]), np.ascontiguousarray(dy[:, :, P - prow:]), (R, S), stride=stride, mode=1))
+    assert gu.rel_err(dw, want) <= gu.TOL["f32"]
+    del x
+    print("backward data near the offset limit", flush=True)
+    dx = gu.run_backward_data(dy, w, (H, W), (0, 0), stride, 1)
+    assert dx.shape == (N, C, H, W)
+    top = oc.conv_backward_data(np.ascontiguousarray(dy[:, :, :prow]), w, (rows, W), stride=stride, mode=1)
+    bottom = oc.conv_backward_data(np.ascontiguousarray(dy[:, :, P - prow:]), w, (rows, W), stride=stride, mode=1)
+    assert gu.rel_err(dx[:, :, :rows], top) <= gu.TOL["f32"]
+    assert gu.rel_err(dx[:, :, H - rows:], bottom) <= gu.TOL["f32"]
+    assert not np.any(dx[:, :, rows:H - rows])      # rows that only zero gradients reach
