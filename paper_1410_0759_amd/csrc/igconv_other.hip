@@ -341,6 +341,74 @@ __global__ __launch_bounds__(256) void igconv_pooling_kernel(const PoolArgs a) {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, r), ybuf, yoff * 4u, 0, 0);
 }
 
+// The same function for tensors whose w stride is 1: a workgroup takes TP output rows of one
+// (n,c) plane, loads the rows of x their windows touch into LDS with whole-row reads and
+// computes its outputs from there: x leaves HBM once, in contiguous runs.
+struct PoolRowsArgs {
+    int mode, H, W, P, Q, win_h, win_w, pad_h, pad_w, u, v_;
+    int TP, strips, C;           // output rows per workgroup, workgroups per plane, planes are (n,c)
+    Magic mStrips, mC, mW, mQ;
+    uint32_t xs[3], ys[3];       // n, c, h strides
+    uint32_t x_bytes, y_bytes;
+    float alpha, beta;
+    float *y;
+    const float *x;
+};
+
+template <int WH, int WW>
+__global__ __launch_bounds__(256) void igconv_pooling_rows_kernel(const PoolRowsArgs a) {
+    extern __shared__ float pool_rows_lds[];
+    const uint32_t plane = mdiv(blockIdx.x, a.mStrips), strip = blockIdx.x - plane * (uint32_t)a.strips;
+    const uint32_t n = mdiv(plane, a.mC), c = plane - n * (uint32_t)a.C;
+    const int p0 = (int)strip * a.TP, p1 = min(p0 + a.TP, a.P);
+    const int win_h = WH ? WH : a.win_h, win_w = WW ? WW : a.win_w;
+    const int xr0 = max(p0 * a.u - a.pad_h, 0), xr1 = min((p1 - 1) * a.u - a.pad_h + win_h, a.H);
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.y_bytes, 0x00020000u);
+    {
+        const uint32_t base = n * a.xs[0] + c * a.xs[1];
+        const int cnt = (xr1 - xr0) * a.W;
+        for (int i = threadIdx.x; i < cnt; i += 256) {
+            const uint32_t r = mdiv((uint32_t)i, a.mW), w = (uint32_t)i - r * (uint32_t)a.W;
+            pool_rows_lds[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                xbuf, (base + ((uint32_t)xr0 + r) * a.xs[2] + w) * 4u, 0, 0));
+        }
+    }
+    __syncthreads();
+    const uint32_t base = n * a.ys[0] + c * a.ys[1];
+    const int cnt = (p1 - p0) * a.Q;
+    for (int i = threadIdx.x; i < cnt; i += 256) {
+        const uint32_t pr = mdiv((uint32_t)i, a.mQ), q = (uint32_t)i - pr * (uint32_t)a.Q;
+        const int p = p0 + (int)pr;
+        const int h0 = p * a.u - a.pad_h, w0 = (int)q * a.v_ - a.pad_w;
+        // the part of the window inside the image (never empty: pad < window)
+        const int r0 = max(h0, 0), r1 = min(h0 + win_h, a.H), c0 = max(w0, 0), c1 = min(w0 + win_w, a.W);
+        float m = -INFINITY, s = 0.f;
+        if (WH != 0 && r1 - r0 == WH && c1 - c0 == WW) {     // whole window inside: fixed trip counts
+            const float *src = pool_rows_lds + (r0 - xr0) * a.W + c0;
+#pragma unroll
+            for (int r = 0; r < (WH ? WH : 1); ++r)
+#pragma unroll
+                for (int cc = 0; cc < (WW ? WW : 1); ++cc) {
+                    const float val = src[r * a.W + cc];
+                    m = fmaxf(m, val);
+                    s += val;
+                }
+        } else {
+            for (int r = r0; r < r1; ++r)
+                for (int cc = c0; cc < c1; ++cc) {
+                    const float val = pool_rows_lds[(r - xr0) * a.W + cc];
+                    m = fmaxf(m, val);
+                    s += val;
+                }
+        }
+        float res = a.alpha * (a.mode == IGC_POOLING_MAX ? m : s / (float)((r1 - r0) * (c1 - c0)));
+        const uint32_t off = (base + (uint32_t)p * a.ys[2] + q) * 4u;
+        if (a.beta != 0.f) res += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, off, 0, 0));
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, res), ybuf, off, 0, 0);
+    }
+}
+
 // ---- softmax backward --------------------------------------------------------------------
 // dx_i = y_i * (dy_i - sum_j dy_j y_j), j over the group (Jacobian of the softmax applied
 // to dy).  Same decomposition as forward: two passes, the first for the dot product.
@@ -481,6 +549,7 @@ struct PoolBwdRowsArgs {
     uint32_t xs[3], dys[3], dxs[3];   // n, c, h strides
     uint32_t x_bytes, dy_bytes, dx_bytes;
     int xrows_max, wrows_max;   // LDS room: rows of x, rows of windows
+    int wpi, rpi;               // rows of windows / of the image the 256 threads cover at a time with one column each (0: rows too wide)
     float alpha, beta;
     float *dx;
     const float *x, *dy;
@@ -515,14 +584,12 @@ __global__ __launch_bounds__(256) void igconv_pooling_bwd_rows_kernel(const Pool
     __syncthreads();
     {
         const uint32_t base = n * a.dys[0] + c * a.dys[1];
-        const int cnt = nprow * a.Q;
-        for (int wi = threadIdx.x; wi < cnt; wi += 256) {
-            const uint32_t pr = mdiv((uint32_t)wi, a.mQ), q = (uint32_t)wi - pr * (uint32_t)a.Q;
-            const int p = p_lo + (int)pr;
+        // the share of window (p_lo + pr, q), whose in-image columns are [c0, c1)
+        auto window = [&](int pr, int q, int c0, int c1) {
+            const int p = p_lo + pr, wi = pr * a.Q + q;
             const int r0 = max(p * a.u - a.pad_h, 0), r1 = min(p * a.u - a.pad_h + a.win_h, a.H);
-            const int c0 = max((int)q * a.v_ - a.pad_w, 0), c1 = min((int)q * a.v_ - a.pad_w + a.win_w, a.W);
             const float g = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                dybuf, (base + (uint32_t)p * a.dys[2] + q) * 4u, 0, 0));
+                dybuf, (base + (uint32_t)p * a.dys[2] + (uint32_t)q) * 4u, 0, 0));
             if (is_max) {
                 float m = -INFINITY;
                 int arg = r0 * a.W + c0;
@@ -539,17 +606,28 @@ __global__ __launch_bounds__(256) void igconv_pooling_bwd_rows_kernel(const Pool
             } else {
                 gl[wi] = g / (float)((r1 - r0) * (c1 - c0));
             }
+        };
+        if (a.wpi) {
+            // a thread keeps its column and walks down the window rows: the column's arithmetic is done once
+            const int slot = (int)mdiv(threadIdx.x, a.mQ), q = (int)threadIdx.x - slot * a.Q;
+            const int c0 = max(q * a.v_ - a.pad_w, 0), c1 = min(q * a.v_ - a.pad_w + a.win_w, a.W);
+            if (slot < a.wpi)
+                for (int pr = slot; pr < nprow; pr += a.wpi) window(pr, q, c0, c1);
+        } else {   // rows wider than the workgroup: element by element
+            const int cnt = nprow * a.Q;
+            for (int wi = threadIdx.x; wi < cnt; wi += 256) {
+                const int pr = (int)mdiv((uint32_t)wi, a.mQ), q = wi - pr * a.Q;
+                window(pr, q, max(q * a.v_ - a.pad_w, 0), min(q * a.v_ - a.pad_w + a.win_w, a.W));
+            }
         }
     }
     __syncthreads();
     const uint32_t base = n * a.dxs[0] + c * a.dxs[1];
-    const int cnt = (h1 - h0) * a.W;
-    for (int i = threadIdx.x; i < cnt; i += 256) {
-        const uint32_t r = mdiv((uint32_t)i, a.mW);
-        const int w = i - (int)r * a.W, h = h0 + (int)r;
-        const int th = h + a.pad_h - (a.win_h - 1), tw = w + a.pad_w - (a.win_w - 1);
+    // input element (h0 + r, w), covered by the window columns [ql, qh]
+    auto element = [&](int r, int w, int ql, int qh) {
+        const int h = h0 + r;
+        const int th = h + a.pad_h - (a.win_h - 1);
         const int pl = th <= 0 ? 0 : (int)mdiv((uint32_t)(th + a.u - 1), a.mu), ph = min(a.P - 1, (int)mdiv((uint32_t)(h + a.pad_h), a.mu));
-        const int ql = tw <= 0 ? 0 : (int)mdiv((uint32_t)(tw + a.v_ - 1), a.mv), qh = min(a.Q - 1, (int)mdiv((uint32_t)(w + a.pad_w), a.mv));
         const int self = h * a.W + w;
         float acc = 0.f;
         for (int p = pl; p <= ph; ++p)
@@ -561,6 +639,26 @@ __global__ __launch_bounds__(256) void igconv_pooling_bwd_rows_kernel(const Pool
         float res = a.alpha * acc;
         if (a.beta != 0.f) res += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(dxbuf, off, 0, 0));
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, res), dxbuf, off, 0, 0);
+    };
+    auto q_range = [&](int w, int &ql, int &qh) {
+        const int tw = w + a.pad_w - (a.win_w - 1);
+        ql = tw <= 0 ? 0 : (int)mdiv((uint32_t)(tw + a.v_ - 1), a.mv);
+        qh = min(a.Q - 1, (int)mdiv((uint32_t)(w + a.pad_w), a.mv));
+    };
+    if (a.rpi) {
+        const int slot = (int)mdiv(threadIdx.x, a.mW), w = (int)threadIdx.x - slot * a.W;
+        int ql, qh;
+        q_range(w, ql, qh);
+        if (slot < a.rpi)
+            for (int r = slot; r < h1 - h0; r += a.rpi) element(r, w, ql, qh);
+    } else {
+        const int cnt = (h1 - h0) * a.W;
+        for (int i = threadIdx.x; i < cnt; i += 256) {
+            const int r = (int)mdiv((uint32_t)i, a.mW), w = i - r * a.W;
+            int ql, qh;
+            q_range(w, ql, qh);
+            element(r, w, ql, qh);
+        }
     }
 }
 
@@ -814,6 +912,35 @@ igcStatus igcPoolingForward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc,
     a.y = static_cast<float *>(y);
     a.x = static_cast<const float *>(x);
     const uint32_t blocks = (a.count + 255u) / 256u;
+    // w stride 1 in x and y: the row-strip kernel, with as many output rows per workgroup (at most 64) as
+    // fit its LDS (the rows of x they touch) within 64 KB
+    if (xDesc->stride[3] == 1 && yDesc->stride[3] == 1 && !std::getenv("IGCONV_POOL_GENERAL")) {
+        PoolRowsArgs r{};
+        r.mode = a.mode; r.H = a.H; r.W = a.W; r.P = p; r.Q = q;
+        r.win_h = a.win_h; r.win_w = a.win_w; r.pad_h = a.pad_h; r.pad_w = a.pad_w; r.u = a.u; r.v_ = a.v_;
+        r.C = c;
+        for (int d = 0; d < 3; ++d) {
+            r.xs[d] = (uint32_t)xDesc->stride[d];
+            r.ys[d] = (uint32_t)yDesc->stride[d];
+        }
+        r.x_bytes = a.x_bytes; r.y_bytes = a.y_bytes; r.alpha = a.alpha; r.beta = a.beta; r.y = a.y; r.x = a.x;
+        for (int tp = std::min(64, p); tp >= 1; tp = tp > 1 ? (tp + 1) / 2 : 0) {
+            const long long xrows = std::min<long long>((long long)(tp - 1) * r.u + r.win_h, r.H);
+            const long long lds = xrows * r.W * 4;
+            const int strips = (p + tp - 1) / tp;
+            const long long nblocks = (long long)n * c * strips;
+            if (lds > 64 * 1024 || nblocks >= (1ll << 31)) continue;
+            r.TP = tp; r.strips = strips;
+            if (!magic_of((uint32_t)strips, &r.mStrips) || !magic_of((uint32_t)c, &r.mC) || !magic_of((uint32_t)r.W, &r.mW) ||
+                !magic_of((uint32_t)r.Q, &r.mQ))
+                break;
+            if (a.win_h == 3 && a.win_w == 3)
+                return launch(&igconv_pooling_rows_kernel<3, 3>, "igconv_pooling_rows_kernel", r, (uint32_t)nblocks, handle->stream, (size_t)lds);
+            if (a.win_h == 2 && a.win_w == 2)
+                return launch(&igconv_pooling_rows_kernel<2, 2>, "igconv_pooling_rows_kernel", r, (uint32_t)nblocks, handle->stream, (size_t)lds);
+            return launch(&igconv_pooling_rows_kernel<0, 0>, "igconv_pooling_rows_kernel", r, (uint32_t)nblocks, handle->stream, (size_t)lds);
+        }
+    }
     if (a.win_h == 3 && a.win_w == 3) return launch(&igconv_pooling_kernel<3, 3>, "igconv_pooling_kernel", a, blocks, handle->stream);
     if (a.win_h == 2 && a.win_w == 2) return launch(&igconv_pooling_kernel<2, 2>, "igconv_pooling_kernel", a, blocks, handle->stream);
     return launch(&igconv_pooling_kernel<0, 0>, "igconv_pooling_kernel", a, blocks, handle->stream);
@@ -927,6 +1054,8 @@ igcStatus igcPoolingBackward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc
             const long long blocks = (long long)n * c * strips;
             if (lds > 64 * 1024 || blocks >= (1ll << 31)) continue;
             r.TH = th; r.strips = strips; r.xrows_max = xrows; r.wrows_max = wrows;
+            r.wpi = r.Q <= 256 ? 256 / r.Q : 0;
+            r.rpi = r.W <= 256 ? 256 / r.W : 0;
             if (!magic_of((uint32_t)strips, &r.mStrips) || !magic_of((uint32_t)c, &r.mC) || !magic_of((uint32_t)r.u, &r.mu) ||
                 !magic_of((uint32_t)r.v_, &r.mv) || !magic_of((uint32_t)r.W, &r.mW) || !magic_of((uint32_t)r.Q, &r.mQ))
                 break;

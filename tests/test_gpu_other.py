@@ -112,8 +112,13 @@ def test_pooling_forward(mode):
     gu = _gpu()
     cases = [((2, 3, 9, 11), (2, 2), (0, 0), (2, 2)), ((2, 3, 9, 11), (3, 3), (1, 1), (2, 2)),
              ((1, 5, 13, 13), (3, 2), (1, 0), (1, 3)), ((3, 96, 27, 27), (3, 3), (0, 0), (2, 2)),
-             ((2, 4, 7, 7), (7, 7), (0, 0), (1, 1)), ((2, 4, 8, 8), (5, 5), (2, 2), (4, 4)), ((1, 1, 1, 1), (1, 1), (0, 0), (1, 1))]
+             ((2, 4, 7, 7), (7, 7), (0, 0), (1, 1)), ((2, 4, 8, 8), (5, 5), (2, 2), (4, 4)), ((1, 1, 1, 1), (1, 1), (0, 0), (1, 1)),
+             ((3, 5, 55, 55), (3, 3), (0, 0), (2, 2)), ((2, 3, 37, 20), (3, 3), (1, 1), (1, 1)), ((2, 3, 11, 9), (2, 2), (0, 0), (3, 3)),
+             ((2, 2, 130, 40), (2, 2), (1, 1), (2, 2)),      # more output rows than one workgroup takes
+             ((1, 2, 9, 700), (3, 3), (1, 1), (1, 1)),       # wide rows: fewer rows per workgroup
+             ((1, 1, 4, 6000), (3, 3), (1, 1), (1, 1))]      # too wide for the row-strip kernel
     for shape, win, pad, st in cases:
+        print("pooling forward", mode, shape, win, pad, st, flush=True)
         x = rnd(15, *shape) - np.float32(5.0)     # all negative: a zero border must never win the maximum
         want = po.pooling_forward(mode, x, win, pad, st)
         close(gu.run_pooling_forward(mode, x, win, pad, st), want)
