@@ -172,7 +172,9 @@ class Handle(_Owned):
 def _scalars(out_desc, alpha, beta):
     """alpha and beta as the host scalars the library expects: doubles for double-precision
     problems (told by the output's descriptor), floats otherwise."""
-    dt = out_desc.get()[0]
+    dt = getattr(out_desc, "dtype", None)      # (remembered by set(): no library call on the launch path)
+    if dt is None:
+        dt = out_desc.get()[0]
     t = ctypes.c_double if dt == IGC_DATA_DOUBLE else ctypes.c_float
     return t(alpha), t(beta)
 
@@ -183,6 +185,7 @@ class TensorDescriptor(_Owned):
     def set(self, dtype, n, c, h, w, strides):
         check(lib().igcSetTensor4dDescriptor(self.ptr, dtype, n, c, h, w, *[int(s) for s in strides]),
               "igcSetTensor4dDescriptor")
+        self.dtype = dtype
         return self
 
     def get(self):
@@ -198,6 +201,7 @@ class FilterDescriptor(_Owned):
 
     def set(self, dtype, k, c, r, s):
         check(lib().igcSetFilter4dDescriptor(self.ptr, dtype, k, c, r, s), "igcSetFilter4dDescriptor")
+        self.dtype = dtype
         return self
 
     def get(self):
