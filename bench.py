@@ -249,6 +249,14 @@ def run_other_functions(steps, warmup):
     err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.add_tensor(bias, (2,) + shape[1:], 1.0, 1.0, x[:2]))
     ms = timed(lambda: ig.check(ig.add_tensor(h, 1.0, bd, bt.data_ptr(), 1.0, yd, yt.data_ptr()), "bias"))
     record("bias addition in place (1,C,1,1)", shape, 2 * nb, ms, err)
+    # change of layout: NCHW -> NHWC and back
+    nhwc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, (shape[2] * shape[3] * shape[1], 1, shape[3] * shape[1], shape[1]))
+    ig.check(ig.transform_tensor(h, 1.0, xd, xt.data_ptr(), 0.0, nhwc, yt.data_ptr()), "to NHWC")
+    ms = timed(lambda: ig.check(ig.transform_tensor(h, 1.0, xd, xt.data_ptr(), 0.0, nhwc, yt.data_ptr()), "to NHWC"))
+    got = torch.as_strided(yt.view(-1), shape, (shape[2] * shape[3] * shape[1], 1, shape[3] * shape[1], shape[1]))[:2].cpu().numpy()
+    record("tensor transformation NCHW -> NHWC", shape, 2 * nb, ms, gu.rel_err(got.astype(np.float64), po.add_tensor(x[:2], (2,) + shape[1:])))
+    ms = timed(lambda: ig.check(ig.transform_tensor(h, 1.0, nhwc, yt.data_ptr(), 0.0, dxd, dxt.data_ptr()), "to NCHW"))
+    record("tensor transformation NHWC -> NCHW", shape, 2 * nb, ms, gu.rel_err(dxt[:2].cpu().numpy().astype(np.float64), po.add_tensor(x[:2], (2,) + shape[1:])))
     del xt, yt, dyt, dxt
 
     for mode, nm, shape in ((ig.IGC_SOFTMAX_MODE_CHANNEL, "softmax per location", (32, 21, 128, 128)),

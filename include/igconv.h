@@ -331,6 +331,16 @@ igcStatus igcAddTensor(igcHandle_t handle, const void *alpha,
                        igcTensorDescriptor_t bDesc, const void *b,
                        const void *beta, igcTensorDescriptor_t yDesc, void *y);
 
+/* Tensor transformation (Section 2: auxiliary routines for the manipulation of 4-d tensors):
+ * y = alpha * x + beta * y for two tensors of equal dimensions and any strides, i.e. a change
+ * of layout (NCHW <-> NHWC, pitched <-> packed, a slice into a tensor of its own).  Where x
+ * and y are contiguous along different dimensions, 64 x 64 tiles go through LDS so that both
+ * sides are accessed in contiguous runs.  x and y must not overlap unless their descriptors
+ * are identical. */
+igcStatus igcTransformTensor(igcHandle_t handle, const void *alpha,
+                             igcTensorDescriptor_t xDesc, const void *x,
+                             const void *beta, igcTensorDescriptor_t yDesc, void *y);
+
 /* y = alpha * softmax(x) + beta * y over the groups igcSoftmaxMode names, computed the
  * numerically stable way: exp(x - max of the group) / sum of those. */
 igcStatus igcSoftmaxForward(igcHandle_t handle, igcSoftmaxMode mode, const void *alpha,

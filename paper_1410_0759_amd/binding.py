@@ -18,7 +18,7 @@ __all__ = [
     "get_backward_data_workspace_size", "convolution_backward_data",
     "get_backward_filter_workspace_size", "convolution_backward_filter",
     "PoolingDescriptor", "get_pooling_output_dim", "activation_forward", "activation_backward", "add_tensor",
-    "softmax_forward", "pooling_forward", "softmax_backward", "pooling_backward", "convolution_bias_activation_forward", "IGC_ACTIVATION_IDENTITY",
+    "softmax_forward", "pooling_forward", "softmax_backward", "pooling_backward", "transform_tensor", "convolution_bias_activation_forward", "IGC_ACTIVATION_IDENTITY",
     "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
@@ -85,6 +85,7 @@ DECLARED_SYMBOLS = {
     "igcGetPooling2dForwardOutputDim": (_i, [_vp, _vp, _P(_i), _P(_i), _P(_i), _P(_i)]),
     "igcPoolingForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcSoftmaxBackward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcTransformTensor": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcPoolingBackward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcConvolutionBiasActivationForward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _i, _vp, _vp]),
     "igcGetConvolutionForwardPlan": (_i, [_vp, _vp, _vp, _vp, _vp, _P(igcConvolutionForwardPlan)]),
@@ -273,6 +274,11 @@ def pooling_forward(handle, pool, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
     a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
     return lib().igcPoolingForward(handle.ptr, pool.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
                                    ydesc.ptr, _vp(y_ptr))
+
+
+def transform_tensor(handle, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
+    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    return lib().igcTransformTensor(handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
 
 
 def softmax_backward(handle, mode, alpha, ydesc, y_ptr, dydesc, dy_ptr, beta, dxdesc, dx_ptr):

@@ -662,6 +662,53 @@ __global__ __launch_bounds__(256) void igconv_pooling_bwd_rows_kernel(const Pool
     }
 }
 
+// ---- tensor transformation (change of layout) ----------------------------------------------
+// y = alpha * x + beta * y where x is contiguous along one dimension (A) and y along another (B):
+// a workgroup moves a 64 x 64 tile of the (A, B) plane through LDS, reading runs along A and
+// writing runs along B, so that both tensors see contiguous accesses.  The (at most two)
+// remaining dimensions are enumerated by the block index.
+struct TransposeArgs {
+    uint32_t dimA, dimB, tilesA, tilesB, outer1;   // outer index = o0 * outer1 + o1
+    Magic mTilesA, mTilesB, mOuter1;
+    uint32_t xsB, ysA;                              // (x's stride along A and y's along B are 1)
+    uint32_t xsO[2], ysO[2];
+    uint32_t x_bytes, y_bytes;
+    float alpha, beta;
+    float *y;
+    const float *x;
+};
+
+__global__ __launch_bounds__(256) void igconv_transpose_kernel(const TransposeArgs a) {
+    __shared__ float tile[64][65];
+    uint32_t rem = blockIdx.x;
+    const uint32_t q1 = mdiv(rem, a.mTilesA), ta = rem - q1 * a.tilesA;
+    const uint32_t q2 = mdiv(q1, a.mTilesB), tb = q1 - q2 * a.tilesB;
+    const uint32_t o0 = mdiv(q2, a.mOuter1), o1 = q2 - o0 * a.outer1;
+    const uint32_t a0 = ta * 64u, b0 = tb * 64u;
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, 0x00020000u);
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, a.y_bytes, 0x00020000u);
+    const uint32_t xbase = o0 * a.xsO[0] + o1 * a.xsO[1], ybase = o0 * a.ysO[0] + o1 * a.ysO[1];
+    const uint32_t lane = threadIdx.x & 63u, grp = threadIdx.x >> 6;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t bl = (uint32_t)r * 4u + grp, ia = a0 + lane, ib = b0 + bl;
+        const bool ok = ia < a.dimA && ib < a.dimB;
+        tile[bl][lane] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+            xbuf, ok ? (xbase + ia + ib * a.xsB) * 4u : 0x80000000u, 0, 0));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t al = (uint32_t)r * 4u + grp, ia = a0 + al, ib = b0 + lane;
+        if (ia < a.dimA && ib < a.dimB) {
+            const uint32_t off = (ybase + ia * a.ysA + ib) * 4u;
+            float res = a.alpha * tile[lane][al];
+            if (a.beta != 0.f) res += a.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, off, 0, 0));
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, res), ybuf, off, 0, 0);
+        }
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------------
 template <class Kernel, class Args>
 igcStatus launch(Kernel kernel, const char *what, const Args &args, uint32_t blocks, void *stream, size_t lds_bytes = 0) {
@@ -1064,6 +1111,56 @@ igcStatus igcPoolingBackward(igcHandle_t handle, igcPoolingDescriptor_t poolDesc
         }
     }
     return launch(&igconv_pooling_bwd_kernel, "igconv_pooling_bwd_kernel", a, (a.count + 255u) / 256u, handle->stream);
+}
+
+igcStatus igcTransformTensor(igcHandle_t handle, const void *alpha, igcTensorDescriptor_t xDesc, const void *x, const void *beta,
+                             igcTensorDescriptor_t yDesc, void *y) {
+    if (!handle || !alpha || !beta || !x || !y) return IGC_STATUS_BAD_PARAM;
+    igcStatus st = check_float_tensor(xDesc, false);
+    if (st == IGC_STATUS_SUCCESS) st = check_float_tensor(yDesc, true);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    if (!same_dims(xDesc, yDesc) || (uintptr_t)x % 4 || (uintptr_t)y % 4) return IGC_STATUS_BAD_PARAM;
+    const float a = *static_cast<const float *>(alpha), b = *static_cast<const float *>(beta);
+    // Dimensions ordered by y's strides, merged where both tensors allow.  If x is contiguous along another
+    // dimension than y (a change of layout), tiles of that plane go through LDS; else element by element.
+    long long stride[kMaxTensors][4] = {};
+    for (int d = 0; d < 4; ++d) {
+        stride[0][d] = yDesc->stride[d];
+        stride[1][d] = xDesc->stride[d];
+    }
+    const View v = make_view(yDesc->dim, stride, 2, /*merge=*/true);
+    const int B = v.rank - 1;
+    int A = -1;
+    for (int d = 0; d < v.rank; ++d)
+        if (v.stride[1][d] == 1u && v.dim[d] > 1u) A = d;
+    if (v.rank >= 2 && v.rank <= 4 && v.stride[0][B] == 1u && A >= 0 && A != B && v.dim[A] >= 16u && v.dim[B] >= 16u) {
+        TransposeArgs t{};
+        t.dimA = v.dim[A]; t.dimB = v.dim[B];
+        t.tilesA = (t.dimA + 63u) / 64u; t.tilesB = (t.dimB + 63u) / 64u;
+        t.xsB = v.stride[1][B]; t.ysA = v.stride[0][A];
+        uint32_t outer[2] = {1u, 1u};
+        int no = 0;
+        for (int d = 0; d < v.rank; ++d)
+            if (d != A && d != B) {
+                outer[no] = v.dim[d];
+                t.xsO[no] = v.stride[1][d];
+                t.ysO[no] = v.stride[0][d];
+                ++no;
+            }
+        t.outer1 = outer[1];
+        const long long blocks = (long long)t.tilesA * t.tilesB * outer[0] * outer[1];
+        if (no <= 2 && blocks < (1ll << 31) && magic_of(t.tilesA, &t.mTilesA) && magic_of(t.tilesB, &t.mTilesB) &&
+            magic_of(t.outer1, &t.mOuter1)) {
+            t.x_bytes = (uint32_t)(extent(xDesc->dim, xDesc->stride) * 4);
+            t.y_bytes = (uint32_t)(extent(yDesc->dim, yDesc->stride) * 4);
+            t.alpha = a; t.beta = b;
+            t.y = static_cast<float *>(y);
+            t.x = static_cast<const float *>(x);
+            return launch(&igconv_transpose_kernel, "igconv_transpose_kernel", t, (uint32_t)blocks, handle->stream);
+        }
+    }
+    const void *in[1] = {x};
+    return run_elementwise(handle, EW_ADD, 0, a, b, yDesc, y, 1, &xDesc->stride, in);
 }
 
 }  // extern "C"

@@ -366,3 +366,17 @@ def run_pooling_backward(mode, x, dy, window, pad=(0, 0), stride=(1, 1), alpha=1
     ig.check(ig.pooling_backward(_handle(), pool, alpha, dydesc, dyd.data_ptr(), xdesc, xd.data_ptr(), beta, dxdesc, out.ptr),
              "igcPoolingBackward")
     return out.result()
+
+
+def run_transform_tensor(x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW", y_strides=None):
+    """igcTransformTensor from x (read through its numpy strides) into a tensor of the given
+    layout (or explicit element strides)."""
+    xd, xdesc = _desc_for(x)
+    if y_strides is None:
+        out, ydesc = _output(x.shape, layout, y_old)
+    else:
+        out = GuardedOutput(x.shape, y_strides)
+        out.prefill(old=y_old) if y_old is not None else out.prefill(value=float("nan"))
+        ydesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *x.shape, out.strides)
+    ig.check(ig.transform_tensor(_handle(), alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcTransformTensor")
+    return out.result()

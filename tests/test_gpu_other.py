@@ -168,3 +168,27 @@ def test_pooling_backward(mode):
         P, Q = po.pooling_output_dim(12, win[0], pad[0], st[0]), po.pooling_output_dim(14, win[1], pad[1], st[1])
         dy = rnd(39, 2, 3, P, Q)
         close(gu.run_pooling_backward(mode, x, dy, win, pad, st), po.pooling_backward(mode, x, dy, win, pad, st))
+
+
+def test_transform_tensor_changes_layout():
+    gu = _gpu()
+    for shape in SHAPES + [(3, 70, 9, 11), (2, 64, 56, 56), (1, 200, 1, 33), (5, 17, 64, 1), (2, 16, 4, 4), (2, 130, 3, 67)]:
+        x = rnd(41, *shape)
+        want = x.astype(np.float64)
+        old = rnd(42, *shape)
+        for src in ("NCHW", "NHWC"):
+            for dst in ("NCHW", "NHWC"):
+                print("transform", shape, src, dst, flush=True)
+                xs = wl.with_layout(x, src)
+                assert np.array_equal(gu.run_transform_tensor(xs, layout=dst), want)        # a copy is exact
+                close(gu.run_transform_tensor(xs, -0.5, 2.0, old, dst), po.add_tensor(x, shape, -0.5, 2.0, old))
+    # a pitched destination (rows padded to 80 elements) and a channel slice as the source
+    x = rnd(43, 2, 24, 9, 70)
+    y_strides = (24 * 9 * 80, 9 * 80, 80, 1)
+    assert np.array_equal(gu.run_transform_tensor(wl.with_layout(x, "NHWC"), y_strides=y_strides), x.astype(np.float64))
+    part = wl.with_layout(x, "NHWC")[:, 4:20]
+    assert np.array_equal(gu.run_transform_tensor(part, layout="NCHW"), x[:, 4:20].astype(np.float64))
+    # other orders of the dimensions: w-major source into NCHW, h-major destination
+    xt = np.ascontiguousarray(x.transpose(3, 0, 1, 2)).transpose(1, 2, 3, 0)        # memory order W,N,C,H
+    assert np.array_equal(gu.run_transform_tensor(xt, layout="NCHW"), x.astype(np.float64))
+    assert np.array_equal(gu.run_transform_tensor(x, y_strides=(24 * 70 * 9, 70 * 9, 1, 9)), x.astype(np.float64))

@@ -281,6 +281,9 @@ def test_other_functions_validate_before_any_gpu_call():
     xp = t(2, 3, 9, 11)
     pf = lambda yd: L.igcPoolingForward(h.ptr, pool.ptr, ctypes.byref(one), xp.ptr, fake, ctypes.byref(one), yd.ptr, fake)
     assert pf(t(2, 3, 5, 5)) == ig.IGC_STATUS_BAD_PARAM                          # y is not (2,3,5,4)
+    tt = lambda xd=x, yd=y, p=fake: L.igcTransformTensor(h.ptr, ctypes.byref(one), xd.ptr, p, ctypes.byref(one), yd.ptr, fake)
+    assert tt(yd=t(2, 3, 8, 9)) == ig.IGC_STATUS_BAD_PARAM and tt(p=None) == ig.IGC_STATUS_BAD_PARAM
+    assert tt(yd=t(2, 3, 8, 8, st=(0, 64, 8, 1))) == ig.IGC_STATUS_BAD_PARAM and tt(xd=t(2, 3, 8, 8, dt=1)) == ig.IGC_STATUS_NOT_SUPPORTED
     # backward forms: dimensions of every tensor are checked, outputs must not alias
     smb = lambda yd=x, dyd=x, dxd=y, mode=1, p=fake: L.igcSoftmaxBackward(h.ptr, mode, ctypes.byref(one), yd.ptr, fake, dyd.ptr, p,
                                                                           ctypes.byref(one), dxd.ptr, fake)
