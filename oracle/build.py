@@ -7,10 +7,12 @@ SRC = os.path.join(HERE, "conv_oracle.c")
 LIB = os.path.join(HERE, "libconv_oracle.so")
 POINTWISE_SRC = os.path.join(HERE, "pointwise_oracle.c")
 POINTWISE_LIB = os.path.join(HERE, "libpointwise_oracle.so")
+POINTWISE_DEPS = (os.path.join(HERE, "pointwise_oracle_impl.inc"),)
 
 
-def _compile(src, lib, force, extra):
-    if not force and os.path.exists(lib) and os.path.getmtime(lib) >= os.path.getmtime(src):
+def _compile(src, lib, force, extra, deps=()):
+    newest = max(os.path.getmtime(f) for f in (src,) + tuple(deps))
+    if not force and os.path.exists(lib) and os.path.getmtime(lib) >= newest:
         return lib
     cmd = ["gcc", "-O2", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra"] + extra + ["-o", lib + ".tmp", src]
     subprocess.run(cmd, check=True)
@@ -21,12 +23,12 @@ def _compile(src, lib, force, extra):
 def build(force: bool = True) -> str:
     """Build both shared libraries; with ``force=False`` keep existing up-to-date ones.
     Returns the path of the convolution oracle."""
-    _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"])
+    _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"], POINTWISE_DEPS)
     return _compile(SRC, LIB, force, ["-fopenmp"])
 
 
 def build_pointwise(force: bool = False) -> str:
-    return _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"])
+    return _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"], POINTWISE_DEPS)
 
 
 if __name__ == "__main__":

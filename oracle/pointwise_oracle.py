@@ -31,9 +31,17 @@ def _strides(a):
 
 
 def _f32(a):
+    """A 4-D input array: float32, or float64 for the double-precision form of a function."""
     a = np.asarray(a)
-    assert a.dtype == np.float32 and a.ndim == 4
+    assert a.dtype in (np.float32, np.float64) and a.ndim == 4
     return a
+
+
+def _fn(name, *arrays):
+    """The library entry for the arrays' common element type."""
+    dt = arrays[0].dtype
+    assert all(a.dtype == dt for a in arrays), "all inputs of a call share one element type"
+    return getattr(_load(), ("pointwise_oracle_f64_" if dt == np.float64 else "pointwise_oracle_") + name)
 
 
 def _out(shape, layout, old, beta):
@@ -64,7 +72,7 @@ def _check(rc, what):
 def activation_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     x = _f32(x)
     y, old_ptr, _keep = _out(x.shape, layout, y_old, beta)
-    _check(_load().pointwise_oracle_activation_forward(
+    _check(_fn("activation_forward", x)(
         ctypes.c_int(mode), ctypes.c_void_p(x.ctypes.data), _strides(x), *[ctypes.c_int(d) for d in x.shape],
         ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(old_ptr), ctypes.c_void_p(y.ctypes.data),
         _strides(y)), "activation_forward")
@@ -75,7 +83,7 @@ def activation_backward(mode, y, dy, x, alpha=1.0, beta=0.0, dx_old=None, layout
     y, dy, x = _f32(y), _f32(dy), _f32(x)
     assert y.shape == dy.shape == x.shape
     dx, old_ptr, _keep = _out(x.shape, layout, dx_old, beta)
-    _check(_load().pointwise_oracle_activation_backward(
+    _check(_fn("activation_backward", y, dy, x)(
         ctypes.c_int(mode), ctypes.c_void_p(y.ctypes.data), _strides(y), ctypes.c_void_p(dy.ctypes.data), _strides(dy),
         ctypes.c_void_p(x.ctypes.data), _strides(x), *[ctypes.c_int(d) for d in x.shape],
         ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(old_ptr), ctypes.c_void_p(dx.ctypes.data),
@@ -87,7 +95,7 @@ def add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     """alpha * b (broadcast along its size-1 dimensions to ``shape``) + beta * y_old."""
     b = _f32(b)
     y, old_ptr, _keep = _out(tuple(shape), layout, y_old, beta)
-    _check(_load().pointwise_oracle_add_tensor(
+    _check(_fn("add_tensor", b)(
         ctypes.c_void_p(b.ctypes.data), _strides(b), *[ctypes.c_int(d) for d in b.shape],
         *[ctypes.c_int(d) for d in shape], ctypes.c_double(alpha), ctypes.c_double(beta),
         ctypes.c_void_p(old_ptr), ctypes.c_void_p(y.ctypes.data), _strides(y)), "add_tensor")
@@ -97,7 +105,7 @@ def add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
 def softmax_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     x = _f32(x)
     y, old_ptr, _keep = _out(x.shape, layout, y_old, beta)
-    _check(_load().pointwise_oracle_softmax_forward(
+    _check(_fn("softmax_forward", x)(
         ctypes.c_int(mode), ctypes.c_void_p(x.ctypes.data), _strides(x), *[ctypes.c_int(d) for d in x.shape],
         ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(old_ptr), ctypes.c_void_p(y.ctypes.data),
         _strides(y)), "softmax_forward")
@@ -116,7 +124,7 @@ def pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, beta=
     if P < 1 or Q < 1:
         raise ValueError("no output")
     y, old_ptr, _keep = _out((N, C, P, Q), layout, y_old, beta)
-    _check(_load().pointwise_oracle_pooling_forward(
+    _check(_fn("pooling_forward", x)(
         ctypes.c_int(mode), ctypes.c_void_p(x.ctypes.data), _strides(x), *[ctypes.c_int(d) for d in x.shape],
         ctypes.c_int(window[0]), ctypes.c_int(window[1]), ctypes.c_int(pad[0]), ctypes.c_int(pad[1]),
         ctypes.c_int(stride[0]), ctypes.c_int(stride[1]), ctypes.c_double(alpha), ctypes.c_double(beta),
@@ -129,7 +137,7 @@ def softmax_backward(mode, y, dy, alpha=1.0, beta=0.0, dx_old=None, layout="NCHW
     y, dy = _f32(y), _f32(dy)
     assert y.shape == dy.shape
     dx, old_ptr, _keep = _out(y.shape, layout, dx_old, beta)
-    _check(_load().pointwise_oracle_softmax_backward(
+    _check(_fn("softmax_backward", y, dy)(
         ctypes.c_int(mode), ctypes.c_void_p(y.ctypes.data), _strides(y), ctypes.c_void_p(dy.ctypes.data), _strides(dy),
         *[ctypes.c_int(d) for d in y.shape], ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(old_ptr),
         ctypes.c_void_p(dx.ctypes.data), _strides(dx)), "softmax_backward")
@@ -144,7 +152,7 @@ def pooling_backward(mode, x, dy, window, pad=(0, 0), stride=(1, 1), alpha=1.0, 
     assert dy.shape == (N, C, P, Q)
     dx, old_ptr, _keep = _out((N, C, H, W), layout, dx_old, beta)
     scratch = np.empty(N * C * H * W, dtype=np.float64)
-    _check(_load().pointwise_oracle_pooling_backward(
+    _check(_fn("pooling_backward", x, dy)(
         ctypes.c_int(mode), ctypes.c_void_p(x.ctypes.data), _strides(x), ctypes.c_void_p(dy.ctypes.data), _strides(dy),
         *[ctypes.c_int(d) for d in x.shape],
         ctypes.c_int(window[0]), ctypes.c_int(window[1]), ctypes.c_int(pad[0]), ctypes.c_int(pad[1]),

@@ -260,3 +260,42 @@ def test_pooling_backward_against_torch_autograd_and_the_transpose_identity():
     got = po.pooling_backward(po.POOL_MAX, nhwc(x), dy, (2, 2), stride=(3, 3), alpha=2.0, beta=0.5, dx_old=old, layout="NHWC")
     assert np.array_equal(got[:, :, 2::3, :], 0.5 * old[:, :, 2::3, :])
     assert np.allclose(got, 2.0 * po.pooling_backward(po.POOL_MAX, x, dy, (2, 2), stride=(3, 3)) + 0.5 * old, atol=1e-15)
+
+
+# ---------------------------------------------------------------- double-precision inputs
+def test_double_inputs_share_the_arithmetic_and_are_not_truncated():
+    """The functions for double inputs are the same bodies compiled for another element type: on
+    float32-representable data both forms agree bit for bit, and on data that needs all 53 bits
+    they follow scipy / numpy / torch in double (a truncation to float would miss by ~1e-8)."""
+    torch = pytest.importorskip("torch")
+    from scipy.special import expit, softmax
+    x32 = rnd(51, 2, 5, 6, 7)
+    d32 = rnd(52, 2, 5, 6, 7)
+    x64, d64 = x32.astype(np.float64), d32.astype(np.float64)
+    for mode in (po.SIGMOID, po.RELU, po.TANH):
+        assert np.array_equal(po.activation_forward(mode, x64), po.activation_forward(mode, x32))
+        y32 = po.activation_forward(mode, x32).astype(np.float32)
+        assert np.array_equal(po.activation_backward(mode, y32.astype(np.float64), d64, x64), po.activation_backward(mode, y32, d32, x32))
+    for mode in (po.SOFTMAX_INSTANCE, po.SOFTMAX_CHANNEL):
+        assert np.array_equal(po.softmax_forward(mode, x64), po.softmax_forward(mode, x32))
+        y32 = po.softmax_forward(mode, x32).astype(np.float32)
+        assert np.array_equal(po.softmax_backward(mode, y32.astype(np.float64), d64), po.softmax_backward(mode, y32, d32))
+    for mode in (po.POOL_MAX, po.POOL_AVERAGE):
+        assert np.array_equal(po.pooling_forward(mode, x64, (3, 3), (1, 1), (2, 2)), po.pooling_forward(mode, x32, (3, 3), (1, 1), (2, 2)))
+        g32 = rnd(53, 2, 5, 3, 4)
+        assert np.array_equal(po.pooling_backward(mode, x64, g32.astype(np.float64), (3, 3), (1, 1), (2, 2)),
+                              po.pooling_backward(mode, x32, g32, (3, 3), (1, 1), (2, 2)))
+    assert np.array_equal(po.add_tensor(x64[:, :, :1, :1], x32.shape, 2.0), po.add_tensor(x32[:, :, :1, :1], x32.shape, 2.0))
+    # full-precision data
+    x = np.random.default_rng(54).uniform(-3, 3, size=(2, 5, 6, 7))
+    assert np.max(np.abs(x - x.astype(np.float32))) > 1e-8
+    assert np.allclose(po.activation_forward(po.SIGMOID, x), expit(x), rtol=1e-15, atol=0)
+    assert np.allclose(po.activation_forward(po.TANH, x), np.tanh(x), rtol=1e-15, atol=1e-16)
+    assert np.array_equal(po.activation_forward(po.RELU, x), np.maximum(x, 0.0))
+    assert np.allclose(po.softmax_forward(po.SOFTMAX_CHANNEL, x), softmax(x, axis=1), rtol=1e-14, atol=0)
+    xt = torch.tensor(x)
+    assert np.array_equal(po.pooling_forward(po.POOL_MAX, x, (3, 3), (1, 1), (2, 2)), torch.nn.functional.max_pool2d(xt, 3, 2, 1).numpy())
+    assert np.allclose(po.pooling_forward(po.POOL_AVERAGE, x, (2, 2), stride=(2, 2)), torch.nn.functional.avg_pool2d(xt, 2, 2).numpy(), rtol=1e-15)
+    assert np.array_equal(po.add_tensor(x, x.shape), x)
+    with pytest.raises(AssertionError):
+        po.activation_backward(po.TANH, x, x.astype(np.float32), x)      # one element type per call
