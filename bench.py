@@ -326,6 +326,37 @@ def run_other_functions(steps, warmup):
         # (the average does not read x)
         record("pooling 3x3 stride 2 " + nm + ", backward", shape, (2 if mode == ig.IGC_POOLING_MAX else 1) * x.nbytes + dy.nbytes, ms, err)
         del yt, dyt, dxt
+    del xt
+
+    # the double-precision forms (same kernels compiled for double): one element-wise function and pooling
+    def dev64(a):
+        t = torch.from_numpy(a).cuda()
+        n, c, hh, ww = a.shape
+        return t, ig.TensorDescriptor().set(ig.IGC_DATA_DOUBLE, n, c, hh, ww, (c * hh * ww, hh * ww, ww, 1))
+
+    shape = (128, 64, 56, 56)
+    x = rng.uniform(-3, 3, size=shape)
+    xt, xd = dev64(x)
+    yt, yd = dev64(np.zeros(shape))
+    ms = timed(lambda: ig.check(ig.activation_forward(h, ig.IGC_ACTIVATION_TANH, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), "tanh f64"))
+    record("activation forward tanh, double precision", shape, 2 * x.nbytes, ms,
+           gu.rel_err(yt[:1].cpu().numpy(), po.activation_forward(po.TANH, x[:1])))
+    del xt, yt
+    shape = (128, 96, 55, 55)
+    x = rng.uniform(-3, 3, size=shape)
+    xt, xd = dev64(x)
+    pool = ig.PoolingDescriptor().set(ig.IGC_POOLING_MAX, 3, 3, 0, 0, 2, 2)
+    oshape = ig.get_pooling_output_dim(pool, xd)
+    yt, yd = dev64(np.zeros(oshape))
+    ms = timed(lambda: ig.check(ig.pooling_forward(h, pool, 1.0, xd, xt.data_ptr(), 0.0, yd, yt.data_ptr()), "pool f64"))
+    record("pooling 3x3 stride 2 max, double precision", shape, x.nbytes + yt.numel() * 8, ms,
+           gu.rel_err(yt[:1].cpu().numpy(), po.pooling_forward(po.POOL_MAX, x[:1], (3, 3), (0, 0), (2, 2))))
+    dy = rng.uniform(-1, 1, size=oshape)
+    dyt, dyd = dev64(dy)
+    dxt, dxd = dev64(np.zeros(shape))
+    ms = timed(lambda: ig.check(ig.pooling_backward(h, pool, 1.0, dyd, dyt.data_ptr(), xd, xt.data_ptr(), 0.0, dxd, dxt.data_ptr()), "pool bwd f64"))
+    record("pooling 3x3 stride 2 max, backward, double precision", shape, 2 * x.nbytes + dy.nbytes, ms,
+           gu.rel_err(dxt[:1].cpu().numpy(), po.pooling_backward(po.POOL_MAX, x[:1], dy[:1], (3, 3), (0, 0), (2, 2))))
     return out
 
 

@@ -300,12 +300,13 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
                                               igcTensorDescriptor_t yDesc, void *y);
 
 /* ---- other functions (Section 2.2: activations, softmax, pooling, tensor addition) ----
- * Bandwidth-bound kernels on float tensors laid out by their descriptors (any non-negative
- * strides for inputs; outputs non-aliasing).  All of them blend like the convolutions:
- * out = alpha * value + beta * out, alpha and beta HOST floats, out read only when
- * *beta != 0.  Common errors: BAD_PARAM for null pointers, mismatched dimensions, aliasing
+ * Bandwidth-bound kernels on float tensors, or on double tensors (Section 2: every routine in
+ * single and double precision; all tensors of a call share one type), laid out by their
+ * descriptors (any non-negative strides for inputs; outputs non-aliasing).  All of them blend
+ * like the convolutions: out = alpha * value + beta * out, alpha and beta HOST floats (HOST
+ * doubles for double tensors), out read only when *beta != 0.  Common errors: BAD_PARAM for null pointers, mismatched dimensions, aliasing
  * output strides or misaligned pointers; NOT_INITIALIZED for unset descriptors;
- * NOT_SUPPORTED for data types other than float, byte offsets of 2^31 or more;
+ * NOT_SUPPORTED for bfloat16 or mixed data types, byte offsets of 2^31 or more;
  * EXECUTION_FAILED when the runtime rejects the launch.  Validation precedes any GPU call.
  * An input may be the output buffer itself (same descriptor, same pointer: in-place) but
  * must not overlap it otherwise. */

@@ -248,47 +248,47 @@ def get_pooling_output_dim(pool, xdesc):
 
 
 def activation_forward(handle, mode, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcActivationForward(handle.ptr, mode, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
                                       ydesc.ptr, _vp(y_ptr))
 
 
 def activation_backward(handle, mode, alpha, ydesc, y_ptr, dydesc, dy_ptr, xdesc, x_ptr, beta, dxdesc, dx_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(dxdesc, alpha, beta)
     return lib().igcActivationBackward(handle.ptr, mode, ctypes.byref(a), ydesc.ptr, _vp(y_ptr), dydesc.ptr, _vp(dy_ptr),
                                        xdesc.ptr, _vp(x_ptr), ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
 
 
 def add_tensor(handle, alpha, bdesc, b_ptr, beta, ydesc, y_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcAddTensor(handle.ptr, ctypes.byref(a), bdesc.ptr, _vp(b_ptr), ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
 
 
 def softmax_forward(handle, mode, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcSoftmaxForward(handle.ptr, mode, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
                                    ydesc.ptr, _vp(y_ptr))
 
 
 def pooling_forward(handle, pool, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcPoolingForward(handle.ptr, pool.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b),
                                    ydesc.ptr, _vp(y_ptr))
 
 
 def transform_tensor(handle, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(ydesc, alpha, beta)
     return lib().igcTransformTensor(handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
 
 
 def softmax_backward(handle, mode, alpha, ydesc, y_ptr, dydesc, dy_ptr, beta, dxdesc, dx_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(dxdesc, alpha, beta)
     return lib().igcSoftmaxBackward(handle.ptr, mode, ctypes.byref(a), ydesc.ptr, _vp(y_ptr), dydesc.ptr, _vp(dy_ptr),
                                     ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
 
 
 def pooling_backward(handle, pool, alpha, dydesc, dy_ptr, xdesc, x_ptr, beta, dxdesc, dx_ptr):
-    a, b = ctypes.c_float(alpha), ctypes.c_float(beta)
+    a, b = _scalars(dxdesc, alpha, beta)
     return lib().igcPoolingBackward(handle.ptr, pool.ptr, ctypes.byref(a), dydesc.ptr, _vp(dy_ptr), xdesc.ptr, _vp(x_ptr),
                                     ctypes.byref(b), dxdesc.ptr, _vp(dx_ptr))
 

@@ -289,9 +289,10 @@ def run_backward_filter(x, dy, rs, pad=(0, 0), stride=(1, 1), mode=ig.IGC_CROSS_
 
 # ---------------------------------------------------------------- other functions
 def _desc_for(a):
-    """(device tensor, float descriptor) of a float32 numpy array read through its strides."""
-    dev, strides = to_device_strided(a, "f32")
-    return dev, ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *a.shape, strides)
+    """(device tensor, descriptor) of a float32 or float64 numpy array read through its strides."""
+    dtype = "f64" if a.dtype == np.float64 else "f32"
+    dev, strides = to_device_strided(a, dtype)
+    return dev, ig.TensorDescriptor().set(_dt(dtype), *a.shape, strides)
 
 
 def _handle():
@@ -300,18 +301,20 @@ def _handle():
     return h
 
 
-def _output(shape, layout, old):
-    out = GuardedOutput(shape, layout_strides(shape, layout))
+def _output(shape, layout, old, like=None):
+    """Guarded output tensor of the element type of the array ``like`` (default float32)."""
+    dtype = "f64" if like is not None and like.dtype == np.float64 else "f32"
+    out = GuardedOutput(shape, layout_strides(shape, layout), dtype)
     if old is not None:
         out.prefill(old=old)
     else:
         out.prefill(value=float("nan"))
-    return out, ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, out.strides)
+    return out, ig.TensorDescriptor().set(_dt(dtype), *shape, out.strides)
 
 
 def run_activation_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     xd, xdesc = _desc_for(x)
-    out, ydesc = _output(x.shape, layout, y_old)
+    out, ydesc = _output(x.shape, layout, y_old, x)
     ig.check(ig.activation_forward(_handle(), mode, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcActivationForward")
     return out.result()
 
@@ -320,7 +323,7 @@ def run_activation_backward(mode, y, dy, x, alpha=1.0, beta=0.0, dx_old=None, la
     yd, ydesc = _desc_for(y)
     dyd, dydesc = _desc_for(dy)
     xd, xdesc = _desc_for(x)
-    out, dxdesc = _output(x.shape, layout, dx_old)
+    out, dxdesc = _output(x.shape, layout, dx_old, x)
     ig.check(ig.activation_backward(_handle(), mode, alpha, ydesc, yd.data_ptr(), dydesc, dyd.data_ptr(), xdesc,
                                     xd.data_ptr(), beta, dxdesc, out.ptr), "igcActivationBackward")
     return out.result()
@@ -328,14 +331,14 @@ def run_activation_backward(mode, y, dy, x, alpha=1.0, beta=0.0, dx_old=None, la
 
 def run_add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     bd, bdesc = _desc_for(b)
-    out, ydesc = _output(tuple(shape), layout, y_old)
+    out, ydesc = _output(tuple(shape), layout, y_old, b)
     ig.check(ig.add_tensor(_handle(), alpha, bdesc, bd.data_ptr(), beta, ydesc, out.ptr), "igcAddTensor")
     return out.result()
 
 
 def run_softmax_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     xd, xdesc = _desc_for(x)
-    out, ydesc = _output(x.shape, layout, y_old)
+    out, ydesc = _output(x.shape, layout, y_old, x)
     ig.check(ig.softmax_forward(_handle(), mode, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcSoftmaxForward")
     return out.result()
 
@@ -344,7 +347,7 @@ def run_pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, b
     xd, xdesc = _desc_for(x)
     pool = ig.PoolingDescriptor().set(mode, window[0], window[1], pad[0], pad[1], stride[0], stride[1])
     shape = ig.get_pooling_output_dim(pool, xdesc)
-    out, ydesc = _output(shape, layout, y_old)
+    out, ydesc = _output(shape, layout, y_old, x)
     ig.check(ig.pooling_forward(_handle(), pool, alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcPoolingForward")
     return out.result()
 
@@ -352,7 +355,7 @@ def run_pooling_forward(mode, x, window, pad=(0, 0), stride=(1, 1), alpha=1.0, b
 def run_softmax_backward(mode, y, dy, alpha=1.0, beta=0.0, dx_old=None, layout="NCHW"):
     yd, ydesc = _desc_for(y)
     dyd, dydesc = _desc_for(dy)
-    out, dxdesc = _output(y.shape, layout, dx_old)
+    out, dxdesc = _output(y.shape, layout, dx_old, y)
     ig.check(ig.softmax_backward(_handle(), mode, alpha, ydesc, yd.data_ptr(), dydesc, dyd.data_ptr(), beta, dxdesc, out.ptr),
              "igcSoftmaxBackward")
     return out.result()
@@ -362,7 +365,7 @@ def run_pooling_backward(mode, x, dy, window, pad=(0, 0), stride=(1, 1), alpha=1
     xd, xdesc = _desc_for(x)
     dyd, dydesc = _desc_for(dy)
     pool = ig.PoolingDescriptor().set(mode, window[0], window[1], pad[0], pad[1], stride[0], stride[1])
-    out, dxdesc = _output(x.shape, layout, dx_old)
+    out, dxdesc = _output(x.shape, layout, dx_old, x)
     ig.check(ig.pooling_backward(_handle(), pool, alpha, dydesc, dyd.data_ptr(), xdesc, xd.data_ptr(), beta, dxdesc, out.ptr),
              "igcPoolingBackward")
     return out.result()
@@ -373,10 +376,11 @@ def run_transform_tensor(x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW", y_st
     layout (or explicit element strides)."""
     xd, xdesc = _desc_for(x)
     if y_strides is None:
-        out, ydesc = _output(x.shape, layout, y_old)
+        out, ydesc = _output(x.shape, layout, y_old, x)
     else:
-        out = GuardedOutput(x.shape, y_strides)
+        dtype = "f64" if x.dtype == np.float64 else "f32"
+        out = GuardedOutput(x.shape, y_strides, dtype)
         out.prefill(old=y_old) if y_old is not None else out.prefill(value=float("nan"))
-        ydesc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *x.shape, out.strides)
+        ydesc = ig.TensorDescriptor().set(_dt(dtype), *x.shape, out.strides)
     ig.check(ig.transform_tensor(_handle(), alpha, xdesc, xd.data_ptr(), beta, ydesc, out.ptr), "igcTransformTensor")
     return out.result()
