@@ -398,3 +398,62 @@ def test_forward_with_optional_workspace():
     x, w = wl.random_problem(99, 8, 16, 40, 40, 64, 3, 3)
     g = gu.GpuConv(x, w, (1, 1), (1, 1), 1)
     assert g.lend_workspace() == 0
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    """The library only enqueues kernels on the handle's stream (no allocation, no memset, no
+    synchronisation), so a sequence of its calls can be captured in a HIP graph: forward with
+    fused bias and rectifier, backward filter with its workspace and summing pass, backward data.
+    Every replay, on new input contents and with eager work between the replays, must give the
+    eager results bit for bit."""
+    gu = _gpu()
+    import torch
+    import paper_1410_0759_amd as ig
+    N, C, H, W, K, R, S, pad, stride = 4, 24, 20, 19, 40, 3, 3, (1, 1), (1, 1)
+    P, Q = oc.output_dim(H, R, 1, 1), oc.output_dim(W, S, 1, 1)
+    rng = np.random.default_rng(5)
+    mk = lambda *s: torch.from_numpy(rng.uniform(-1, 1, size=s).astype(np.float32)).cuda()
+    x, w, dy, bias = mk(N, C, H, W), mk(K, C, R, S), mk(N, K, P, Q), mk(K)
+    y, dw, dx = torch.empty(N, K, P, Q, device="cuda"), torch.empty(K, C, R, S, device="cuda"), torch.empty(N, C, H, W, device="cuda")
+    td = lambda t: ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *t.shape, t.stride())
+    xd, yd, dyd, dxd = td(x), td(y), td(dy), td(dx)
+    wd = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
+    conv = ig.ConvolutionDescriptor().set(1, 1, 1, 1, ig.IGC_CROSS_CORRELATION)
+    h = ig.Handle()
+    ws_bytes = ig.get_backward_filter_workspace_size(h, xd, dyd, conv, wd)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes // 4, device="cuda")
+
+    def calls():
+        h.set_stream(torch.cuda.current_stream().cuda_stream)
+        ig.check(ig.convolution_bias_activation_forward(h, 1.0, xd, x.data_ptr(), wd, w.data_ptr(), conv, 0.0, bias.data_ptr(),
+                                                        ig.IGC_ACTIVATION_RELU, yd, y.data_ptr()), "forward")
+        ig.check(ig.convolution_backward_filter(h, 1.0, xd, x.data_ptr(), dyd, dy.data_ptr(), conv, 0.0, wd, dw.data_ptr(),
+                                                ws.data_ptr(), ws_bytes), "backward filter")
+        ig.check(ig.convolution_backward_data(h, 1.0, wd, w.data_ptr(), dyd, dy.data_ptr(), conv, 0.0, dxd, dx.data_ptr()), "backward data")
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):      # (warm-up on the capture stream, as graph capture wants)
+        calls()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for rep in range(3):
+        for t in (x, w, dy, bias):
+            t.copy_(mk(*t.shape))
+        for t in (y, dw, dx):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (y, dw, dx)]
+        for t in (y, dw, dx):
+            t.fill_(float("nan"))
+        calls()                         # eager, between the replays
+        torch.cuda.synchronize()
+        for g, e in zip(got, (y, dw, dx)):
+            assert torch.equal(g, e), "replay %d differs from the eager result" % rep
+    want = oc.conv_forward(x.cpu().numpy(), w.cpu().numpy(), pad=pad, stride=stride, mode=1)
+    want = np.maximum(want + bias.cpu().numpy().astype(np.float64).reshape(1, -1, 1, 1), 0.0)
+    assert gu.rel_err(y.cpu().numpy().astype(np.float64), want) <= gu.TOL["f32"]
