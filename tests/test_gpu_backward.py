@@ -270,7 +270,8 @@ def test_random_problems_forward_and_both_backward_passes(chunk):
     rng = np.random.default_rng(4242 + chunk)
     for i in range(10):
         N, C, H, W, K, R, S, pad, stride = prob = _random_problem(rng)
-        dtype = "bf16" if rng.random() < 0.4 else "f32"
+        r_ = rng.random()
+        dtype = "bf16" if r_ < 0.35 else ("f64" if r_ < 0.5 else "f32")
         mode = int(rng.integers(0, 2))
         xl, yl = ("NHWC" if rng.random() < 0.5 else "NCHW"), ("NHWC" if rng.random() < 0.5 else "NCHW")
         P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
@@ -278,12 +279,14 @@ def test_random_problems_forward_and_both_backward_passes(chunk):
         w = _rnd(100 * chunk + i + 50, (K, C, R, S), dtype)
         dy = wl.with_layout(_rnd(100 * chunk + i + 70, (N, K, P, Q), dtype), yl)
         print("random problem", prob, dtype, mode, xl, yl, flush=True)
-        y, _ = gu.run(x, w, pad, stride, mode, dtype=dtype, y_layout=yl)
+        # (double precision: float32-valued data held as doubles - the oracle takes float32 values and works in double)
+        gx, gw, gdy = (x, w, dy) if dtype != "f64" else (x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64))
+        y, _ = gu.run(gx, gw, pad, stride, mode, dtype=dtype, y_layout=yl)
         assert gu.rel_err(y, oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)) <= gu.TOL[dtype]
-        dx = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, dtype=dtype, dx_layout=xl)
+        dx = gu.run_backward_data(gdy, gw, (H, W), pad, stride, mode, dtype=dtype, dx_layout=xl)
         want = oc.conv_backward_data(dy, w, (H, W), pad=pad, stride=stride, mode=mode)
         assert np.max(np.abs(dx - want)) <= gu.TOL[dtype] * max(np.max(np.abs(want)), 1e-30)
-        dw, _ = gu.run_backward_filter(x, dy, (R, S), pad, stride, mode, dtype=dtype)
+        dw, _ = gu.run_backward_filter(gx, gdy, (R, S), pad, stride, mode, dtype=dtype)
         assert gu.rel_err(dw, oc.conv_backward_filter(x, dy, (R, S), pad=pad, stride=stride, mode=mode)) <= gu.TOL[dtype]
 
 
