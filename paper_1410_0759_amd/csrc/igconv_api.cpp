@@ -161,8 +161,9 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 4 || ki.gmode == 5)
         return tile_times * steps * 1000.0 *
                ((ki.variant == 1 ? 2.4 : 2.75) * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
-    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (ki.gmode == 7 ? 14.0 : 6.0)));
-    return tile_times * steps * (double)ki.BN * ki.BK * (ki.BM + gather);
+    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (ki.gmode == 7 || ki.gmode == 11 ? 14.0 : 6.0)));
+    // (mode 11 multiplies only half of its last step)
+    return tile_times * (ki.gmode == 11 ? steps - 0.5 : (double)steps) * (double)ki.BN * ki.BK * (ki.BM + gather);
 }
 
 // Gather modes a kernel may use for this problem (see the kernel source): the unpadded
@@ -194,9 +195,12 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     const int gmode = ki.gmode;
     if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
-    if (gmode == 7) {   // unpadded, and every step the kernel can request has an entry in its offset table
+    if (gmode == 7 || gmode == 11) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
-        return k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries;
+        if (!(k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries)) return false;
+        // the short last step: an even number of steps, the last with at most half a step of real indices
+        const long long last = k.CRS - (steps - 1) * ki.BK;
+        return gmode == 7 || (steps % 2 == 0 && last <= ki.BK / 2);
     }
     if (gmode == 3) return k.RS == 9 && k.C % (ki.BK / 9) == 0;  // whole steps of BK/9 channels (16-byte filter loads: checked apart)
     if (gmode == 4 || gmode == 5) {
@@ -292,7 +296,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     // the last channel chunk; filter order, the last step; none when everything divides
     k.tail_step = -1;
     if (ki.gmode == 1 && k.C % ki.BK != 0) k.tail_step = (int)((long long)(k.C / ki.BK) * k.RS);
-    if ((ki.gmode == 0 || ki.gmode == 2 || ki.gmode == 7) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
+    if ((ki.gmode == 0 || ki.gmode == 2 || ki.gmode == 7 || ki.gmode == 11) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);

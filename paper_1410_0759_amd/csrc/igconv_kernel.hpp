@@ -218,6 +218,10 @@ enum GatherMode {
     // fetches its offsets with one LDS read instead of decoding them with vector
     // instructions, which would stall the fp32 MFMA.
     GATHER_NOPAD_TABLE = 7,
+    // The same for problems whose last reduction step holds at most half a step of real
+    // indices (C*R*S mod BK in 1..BK/2, an even number of steps): that step runs only half of
+    // its k-groups, the others would multiply zeros.
+    GATHER_NOPAD_TABLE_SHORT = 11,
     // Backward-filter: the generic gather with the roles of the two index sets exchanged.
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
@@ -254,7 +258,7 @@ struct KernelConfig {
     static constexpr int LDV = (BK / VEC + 1) | 1;
     static constexpr int LD = LDV * VEC;
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
-    static constexpr int TABLE_BYTES = GMODE_ == GATHER_NOPAD_TABLE ? kOffsetTableEntries * 4 : 0;
+    static constexpr int TABLE_BYTES = GMODE_ == GATHER_NOPAD_TABLE || GMODE_ == GATHER_NOPAD_TABLE_SHORT ? kOffsetTableEntries * 4 : 0;
     static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE + TABLE_BYTES;
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
     static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
@@ -280,7 +284,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LD = Cfg::LD;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
-    constexpr int GM = Cfg::GMODE;
+    constexpr bool SHORT_LAST = Cfg::GMODE == GATHER_NOPAD_TABLE_SHORT;
+    constexpr int GM = SHORT_LAST ? (int)GATHER_NOPAD_TABLE : Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
     constexpr bool WGN = GM == GATHER_WGRAD_NOPAD;
@@ -808,26 +813,34 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // MFMA.  Tiles beyond the last step read as zeros (out-of-range requests), so no
     // step is special; the loop is unrolled by two because the register set and the LDS
     // stage alternate.
-    auto step = [&](auto parity, int k2) {   // k2: the step whose tiles are requested during this one
+    // `groups`: the k-groups this step multiplies - all G of them, or (SHORT_LAST, last step of a
+    // tile) only the first G/2, the rest of the step being zeros; both even, so that the fragment
+    // sets keep alternating in step.
+    // (always_inline: the accumulators must stay in registers; left to its own judgement the inliner gives up on
+    // bodies of this size and the captured arrays move to scratch memory)
+    auto step_groups = [&](auto parity, auto groups, int k2) __attribute__((always_inline)) {   // k2: the step whose tiles are requested during this one
         constexpr int cur = decltype(parity)::value, nxt = cur ^ 1;
+        constexpr int GS = decltype(groups)::value;
+        constexpr int NMS = GS == G ? NM : GS * MPG_FULL;      // MFMAs of this step
+        constexpr int SBS = GS == G ? SB : NMS - MPG_FULL;     // first MFMA of its last group
         constexpr int fs0 = (G & 1) ? cur : 0;  // fragment set of this step's group 0
-        static_for<NM>([&](auto mc) {
+        static_for<NMS>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
-            constexpr int g = m / MPG_FULL < G - 1 ? m / MPG_FULL : G - 1;
+            constexpr int g = m / MPG_FULL < GS - 1 ? m / MPG_FULL : GS - 1;
             constexpr int j = m - g * MPG_FULL;
             constexpr int fs = (fs0 + g) & 1;
-            if constexpr (j == 0 && g + 1 < G) read_frags(cur, g + 1, fs ^ 1);
-            if constexpr (m == SB) {
+            if constexpr (j == 0 && g + 1 < GS) read_frags(cur, g + 1, fs ^ 1);
+            if constexpr (m == SBS) {
                 lds_barrier();
                 read_frags(nxt, 0, fs ^ 1);
             }
-            // load items i with floor(i * NM / NL) == m: tile t+2 -> set cur
-            constexpr int l0 = (m * NL + NM - 1) / NM, l1 = ((m + 1) * NL + NM - 1) / NM;
+            // load items i with floor(i * NMS / NL) == m: tile t+2 -> set cur
+            constexpr int l0 = (m * NL + NMS - 1) / NMS, l1 = ((m + 1) * NL + NMS - 1) / NMS;
             static_for<l1 - l0>([&](auto ic) { load_item(l0 + decltype(ic)::value, cur, k2); });
             // write items, packed into the slots before the barrier: tile t+1, set nxt -> stage nxt
-            constexpr int WS = NW < SB ? NW : SB;   // slots used for writes
-            if constexpr (m >= SB - WS && m < SB) {
-                constexpr int q = m - (SB - WS);
+            constexpr int WS = NW < SBS ? NW : SBS;   // slots used for writes
+            if constexpr (m >= SBS - WS && m < SBS) {
+                constexpr int q = m - (SBS - WS);
                 constexpr int w0 = (q * NW + WS - 1) / WS, w1 = ((q + 1) * NW + WS - 1) / WS;
                 static_for<w1 - w0>([&](auto ic) { write_item(w0 + decltype(ic)::value, nxt, nxt); });
             }
@@ -835,6 +848,8 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
             __builtin_amdgcn_sched_barrier(0);
         });
     };
+    auto step = [&](auto parity, int k2) __attribute__((always_inline)) { step_groups(parity, std::integral_constant<int, G>{}, k2); };
+    static_assert(!SHORT_LAST || (REM == 0 && G % 4 == 0), "half a step must be a whole, even number of full k-groups");
 
     // A tile takes `nsteps` steps, a whole number of pairs (an odd count runs one extra step
     // on zero tiles), so that the loop body stays a single basic block.  When the reduction is
@@ -883,7 +898,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         setup_tile(next);
         load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bias_next);
         step(std::integral_constant<int, 0>{}, t_begin);
-        step(std::integral_constant<int, 1>{}, t_begin + 1);
+        step_groups(std::integral_constant<int, 1>{}, std::integral_constant<int, SHORT_LAST ? G / 2 : G>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
         // (GATHER_WGRAD_TAP: the columns are channels, 'R*S' elements apart; the tile's tap moves the base)
         const uint32_t ytap = GM == GATHER_WGRAD_TAP ? (uint32_t)out_tap * 4u : 0u;

@@ -18,6 +18,7 @@ struct KernelInfo {
                     // 7 unpadded with the tap offsets in an LDS table (short reductions),
                     // 8 backward-filter with columns (tap, channel), one tap per tile,
                     // 9 backward-filter without padding, few channels,
+                    // 11 mode 7 with a last step of half the k-groups,
                     // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers
     int threads;
     int ldsBytes;

@@ -101,6 +101,12 @@ def test_every_kernel_variant():
             ]
             if "x72 " in name:   # steps of eight channels
                 problems = [(n_, 8 * ((c_ + 7) // 8), h_, w_, k_, r_, s_, pd, st) for (n_, c_, h_, w_, k_, r_, s_, pd, st) in problems]
+        if "table short" in name:   # an even number of steps, the last one at most half full
+            problems = [
+                (3, 5, 15, 17, 150, 3, 3, (0, 0), (1, 1)),        # C*R*S = 45: 2 steps, 13 in the last
+                (2, 3, 35, 33, 96, 11, 11, (0, 0), (4, 4)),       # 363: 12 steps, 11 in the last
+                (2, 7, 12, 9, 70, 5, 3, (0, 0), (1, 2)),          # 105: 4 steps, 9 in the last
+            ]
         channels = "channels" in name or "patch" in name
         if channels:   # nine taps, channels in sixteens and contiguous; odd and even step counts
             vec = True
@@ -140,6 +146,12 @@ def test_gather_modes_are_chosen():
     x, w = wl.random_problem(4, 2, 3, 12, 12, 8, 5, 5)
     _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad table")
     assert plan.gatherMode == 7 and plan.kSteps == 3      # short reduction: tap offsets tabulated in LDS
+    x, w = wl.random_problem(4, 2, 3, 35, 33, 96, 11, 11)
+    _, plan = _check(x, w, (0, 0), (4, 4), 1, "f32", tag="mode nopad table, short last step")
+    assert plan.gatherMode == 11 and plan.kSteps == 12    # 363 = 11 * 32 + 11: the last step runs half of its k-groups
+    x, w = wl.random_problem(4, 2, 1, 20, 20, 33, 7, 7)
+    _, plan = _check(x, w, (0, 0), (2, 1), 1, "f32", tag="mode nopad table, 17 indices in the last step")
+    assert plan.gatherMode == 7 and plan.kSteps == 2
     xl, wl_ = wl.random_problem(4, 1, 100, 9, 9, 8, 5, 5)
     _, plan = _check(xl, wl_, (0, 0), (1, 1), 0, "f32", kernel=[i for i, n in enumerate(_names()) if n == "f32 32x128x32 nopad"][0],
                      tag="mode nopad")
