@@ -329,3 +329,51 @@ def test_all_passes_with_a_tensor_of_almost_two_gibibytes():
     assert gu.rel_err(dx[:, :, :rows], top) <= gu.TOL["f32"]
     assert gu.rel_err(dx[:, :, H - rows:], bottom) <= gu.TOL["f32"]
     assert not np.any(dx[:, :, rows:H - rows])      # rows that only zero gradients reach
+
+
+def test_bf16_channel_vector_routes_fall_back_on_pointers_off_the_16_byte_grid():
+    """The channel-vector kernels read 16-byte vectors; tensors that start 2 bytes off that grid
+    (or a workspace that does) must take the element-wise routes and give the same results."""
+    gu = _gpu()
+    import torch
+    import paper_1410_0759_amd as ig
+    N, C, H, W, K, R, S = 2, 32, 9, 10, 48, 3, 3
+    x = wl.with_layout(_rnd(1, (N, C, H, W), "bf16"), "NHWC")
+    dy = wl.with_layout(_rnd(2, (N, K, H, W), "bf16"), "NHWC")
+    w = _rnd(3, (K, C, R, S), "bf16")
+    want_dw = oc.conv_backward_filter(x, dy, (R, S), pad=(1, 1), mode=1)
+    want_dx = oc.conv_backward_data(dy, w, (H, W), pad=(1, 1), mode=1)
+
+    def shifted(a):      # device copy of a's memory span, starting one element after a 256-byte boundary
+        flat = np.ascontiguousarray(np.lib.stride_tricks.as_strided(a, shape=(gu.extent(a.shape, gu.elem_strides(a)),), strides=(a.itemsize,)))
+        buf = torch.zeros(flat.size + 8, dtype=torch.bfloat16, device="cuda")
+        buf[1:1 + flat.size].copy_(torch.from_numpy(flat).to(torch.bfloat16))
+        assert buf.data_ptr() % 16 == 0
+        return buf, buf.data_ptr() + 2
+
+    BF = ig.IGC_DATA_BFLOAT16
+    xd = ig.TensorDescriptor().set(BF, N, C, H, W, gu.elem_strides(x))
+    dyd = ig.TensorDescriptor().set(BF, N, K, H, W, gu.elem_strides(dy))
+    wd = ig.FilterDescriptor().set(BF, K, C, R, S)
+    dwd = ig.FilterDescriptor().set(ig.IGC_DATA_FLOAT, K, C, R, S)
+    dxd = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, N, C, H, W, (C * H * W, H * W, W, 1))
+    conv = ig.ConvolutionDescriptor().set(1, 1, 1, 1, ig.IGC_CROSS_CORRELATION)
+    h = ig.Handle()
+    h.set_stream(torch.cuda.current_stream().cuda_stream)
+    xb, xp = shifted(x)
+    dyb, dyp = shifted(dy)
+    wb, wp = shifted(w)
+    ws_bytes = ig.get_backward_filter_workspace_size(h, xd, dyd, conv, dwd)
+    ws = torch.empty(ws_bytes // 4 + 4, device="cuda")
+    dw = torch.full((K, C, R, S), float("nan"), device="cuda")
+    ig.check(ig.convolution_backward_filter(h, 1.0, xd, xp, dyd, dyp, conv, 0.0, dwd, dw.data_ptr(), ws.data_ptr(), ws_bytes), "wgrad")
+    torch.cuda.synchronize()
+    assert gu.rel_err(dw.cpu().numpy().astype(np.float64), want_dw) <= gu.TOL["bf16"]
+    ws2_bytes = ig.get_backward_data_workspace_size(h, wd, dyd, conv, dxd)
+    assert ws2_bytes == K * C * 9 * 2
+    ws2 = torch.empty(ws2_bytes // 4 + 4, device="cuda")
+    for dy_ptr, ws_ptr in ((dyp, ws2.data_ptr()), (dyp, ws2.data_ptr() + 4)):   # dy off the grid; the workspace off it too
+        dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+        ig.check(ig.convolution_backward_data(h, 1.0, wd, wp, dyd, dy_ptr, conv, 0.0, dxd, dx.data_ptr(), ws_ptr, ws2_bytes), "dgrad")
+        torch.cuda.synchronize()
+        assert gu.rel_err(dx.cpu().numpy().astype(np.float64), want_dx) <= gu.TOL["bf16"]
