@@ -211,8 +211,8 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
  *
  * Workspace (device, may be null / smaller: then the general route runs, same result up to
  * rounding order): igcGetConvolutionBackwardDataWorkspaceSize returns 0 except for bfloat16
- * problems with u = v = 1, R*S = 9, K a multiple of 16, pad <= filter size - 1 and dy's
- * channel stride 1, where it returns K*C*R*S*2 bytes: the pass is then the forward pass
+ * problems with u = v = 1, R*S = 9 (K a multiple of 16) or R = S = 1 (K a multiple of 8),
+ * pad <= filter size - 1 and dy's channel stride 1, where it returns K*C*R*S*2 bytes: the pass is then the forward pass
  * over dy with the filter's k and c exchanged (written to the workspace, 16-byte aligned,
  * by a small kernel on the same stream) and uses the forward pass's fastest kernels.
  *

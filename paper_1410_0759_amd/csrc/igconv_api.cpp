@@ -24,7 +24,7 @@ constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise};
 
 int kernel_count() {
     int n = 0;
@@ -135,6 +135,7 @@ static igcStatus validate(igcTensorDescriptor_t x, igcFilterDescriptor_t w,
 static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     if (ki.gmode == 1) return (long long)k.RS * ((k.C + ki.BK - 1) / ki.BK);
     if (ki.gmode == 3 || ki.gmode == 4 || ki.gmode == 5) return k.C / (ki.BK / 9);
+    if (ki.gmode == 12) return (k.C + ki.BK - 1) / ki.BK;
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
@@ -158,6 +159,8 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // a step costs about 2.75 units per filter row (2.4 with coalesced row loads) and 1 (1.5
     // when gathered tap by tap) per column, plus a small MFMA term; the scale makes them
     // comparable with the line below.
+    // (1x1 filters over channel vectors: loads of both operands and a small MFMA term per step of 64 channels)
+    if (ki.gmode == 12) return tile_times * steps * 1000.0 * (1.0 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 64.0);
     if (ki.gmode == 4 || ki.gmode == 5)
         return tile_times * steps * 1000.0 *
                ((ki.variant == 1 ? 2.4 : 2.75) * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
@@ -203,6 +206,8 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
         return gmode == 7 || (steps % 2 == 0 && last <= ki.BK / 2);
     }
     if (gmode == 3) return k.RS == 9 && k.C % (ki.BK / 9) == 0;  // whole steps of BK/9 channels (16-byte filter loads: checked apart)
+    if (gmode == 12)   // 1x1 filters, whole 16-byte channel vectors in x and in the filter rows
+        return x_aligned && k.RS == 1 && k.C % 8 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 && k.xsW % 8 == 0;
     if (gmode == 4 || gmode == 5) {
         if (!(x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
               k.xsW % 8 == 0))
@@ -249,7 +254,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.f64) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || ki.f64) return tiles_per_xcd;
     const int occ = std::max(1, std::min(2, (160 * 1024) / ki.ldsBytes));
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * occ);
 }
@@ -433,18 +438,19 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
 }
 
 
-// bf16 with unit stride, nine taps and dy's channels contiguous: backward data IS a forward
-// pass over dy with the filter's k and c exchanged and its taps read in the other direction
-// (tap g of the gather is filter tap R-1-g resp. g for eq. 2), pad R-1-pad.  With the
-// exchanged filter written to a workspace (K*C*9 elements) the channel-vector kernels of
-// the forward pass apply.  False when the problem does not have that shape.
+// bf16 with unit stride, nine taps or one and dy's channels contiguous: backward data IS a
+// forward pass over dy with the filter's k and c exchanged and its taps read in the other
+// direction (tap g of the gather is filter tap R-1-g resp. g for eq. 2), pad R-1-pad.  With
+// the exchanged filter written to a workspace (K*C*R*S elements) the channel-vector kernels
+// of the forward pass apply.  False when the problem does not have that shape.
 static bool backward_data_as_forward(const BackwardDataProblem &b, Problem *pr) {
-    if (!b.bf16 || b.u != 1 || b.v != 1 || b.R * b.S != 9 || b.K % 16 != 0 || b.dys[1] != 1) return false;
+    const int taps = b.R * b.S;
+    if (!b.bf16 || b.u != 1 || b.v != 1 || (taps != 9 && taps != 1) || b.K % (taps == 9 ? 16 : 8) != 0 || b.dys[1] != 1) return false;
     if (b.pad_h > b.R - 1 || b.pad_w > b.S - 1) return false;
     *pr = Problem{};
     pr->bf16 = true;
     pr->vec = 8;
-    pr->mode_mask = (1u << 4) | (1u << 5);
+    pr->mode_mask = taps == 9 ? (1u << 4) | (1u << 5) : 1u << 12;
     ConvKernelParams &k = pr->kp;
     k.x_bytes = (uint32_t)b.dy_bytes;
     k.w_bytes = (uint32_t)b.w_bytes;
@@ -453,7 +459,7 @@ static bool backward_data_as_forward(const BackwardDataProblem &b, Problem *pr) 
     k.K = b.C; k.R = b.R; k.S = b.S; k.P = b.H; k.Q = b.W;
     k.pad_h = b.R - 1 - b.pad_h; k.pad_w = b.S - 1 - b.pad_w; k.u = 1; k.v = 1;
     k.flip = b.flip ? 0 : 1;
-    k.RS = 9; k.CRS = b.K * 9; k.PQ = b.H * b.W; k.NPQ = b.N * k.PQ;
+    k.RS = taps; k.CRS = b.K * taps; k.PQ = b.H * b.W; k.NPQ = b.N * k.PQ;
     k.Wp = k.W + 2 * k.pad_w;
     k.HpWp = (int)std::min<long long>((long long)(k.H + 2 * k.pad_h) * k.Wp, 0x7fffffff);
     if (!magic_for((uint32_t)k.Wp, &k.mWp) || !magic_for((uint32_t)k.HpWp, &k.mHpWp)) return false;
@@ -981,7 +987,7 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
             pr.kp.alpha = *static_cast<const float *>(alpha);
             pr.kp.beta = *static_cast<const float *>(beta);
             if (getenv("IGCONV_DEBUG")) fprintf(stderr, "igconv: backward data as a forward pass, kernel %s\n", kernel_info(id)->name);
-            if (launch_filter_exchange9(w, workSpace, b.K, b.C, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+            if (launch_filter_exchange(w, workSpace, b.K, b.C, b.R * b.S, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
             if (kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
             return IGC_STATUS_SUCCESS;
         }

@@ -1,0 +1,142 @@
+// Forward convolution with 1x1 filters for bf16 tensors whose channels are contiguous in x
+// (paper, Section 3: with R = S = 1 the lowered matrix D_m is x itself, read through strides):
+//
+//   y[n,k,p,q] = sum_c w[k][c] * x[n, p*u - pad_h, q*v - pad_w, c]
+//
+// a plain product of two operands that are both contiguous along the reduction (the filter
+// row of k, the channel vector of a pixel), so both go to LDS as they are loaded, 16 bytes =
+// 8 channels per load, 8 neighbouring lanes reading 128 contiguous bytes of one row.
+// Tile BM x BN x 64 channels, 2 x 2 wavefronts, v_mfma_f32_32x32x16_bf16; LDS rows of
+// 64 channels + 16 bytes (an odd number of 16-byte units: conflict-free 16-byte accesses);
+// global loads two steps ahead in two register sets, a loop without branches, one barrier
+// per step.  One workgroup per tile.  The epilogue is the shared one (alpha/beta, bias,
+// activation, either orientation of the output).
+#ifndef IGCONV_KERNEL_BF16_PW_HPP_
+#define IGCONV_KERNEL_BF16_PW_HPP_
+
+#include "igconv_kernel.hpp"
+
+namespace igc {
+
+constexpr int kPwBK = 64;                     // channels per step
+constexpr int kPwRowBytes = kPwBK * 2 + 16;
+
+template <int BM_, int BN_, bool SWAP_>
+struct Bf16PwConfig {
+    static constexpr int BM = BM_, BN = BN_, BK = kPwBK;
+    static constexpr bool SWAP = SWAP_;
+    static constexpr int THREADS = 256;
+    static constexpr int STAGE_BYTES = (BM + BN) * kPwRowBytes;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "2 x 2 wavefronts of whole 32 x 32 blocks");
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKernelParams p) {
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
+    constexpr int MB = BM / 64, NB = BN / 64;
+    constexpr int RB = kPwRowBytes;
+    constexpr int NA = BM / 32, NBV = BN / 32;      // 16-byte loads per thread and step: rows tid/8 + 32 i
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(16))) uint8_t lds[Cfg::LDS_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
+    if (tile >= p.tilesM * p.tilesN) return;
+    const int m0 = (tile % p.tilesM) * BM, n0 = (tile / p.tilesM) * BN;
+
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
+    const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
+
+    // ---- loading role: channel vector vec of the step, rows (filter rows / pixels) tid/8 + 32 i
+    const int vec = tid & 7, row = tid >> 3;
+    uint32_t a_off[NA], b_off[NBV];     // byte offsets of the rows' first channel, or the out-of-range marker
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int m = m0 + row + 32 * i;
+        a_off[i] = m < p.K ? (uint32_t)m * (uint32_t)p.C * 2u : kOutOfRange;
+    }
+#pragma unroll
+    for (int i = 0; i < NBV; ++i) {
+        const int j = n0 + row + 32 * i;
+        const uint32_t jj = j < p.NPQ ? (uint32_t)j : 0u;
+        const uint32_t n = magic_div(jj, p.mPQ), rem = jj - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ), qq = rem - pp * (uint32_t)p.Q;
+        const uint32_t h = pp * (uint32_t)p.u - (uint32_t)p.pad_h, w = qq * (uint32_t)p.v - (uint32_t)p.pad_w;   // (wrap below zero: fail the test)
+        const bool ok = j < p.NPQ && h < (uint32_t)p.H && w < (uint32_t)p.W;
+        b_off[i] = ok ? (n * (uint32_t)p.xsN + h * (uint32_t)p.xsH + w * (uint32_t)p.xsW) * 2u : kOutOfRange;
+    }
+    u32x4_t a0[NA], b0[NBV], a1[NA], b1[NBV];
+    auto fetch = [&](int step, u32x4_t (&a)[NA], u32x4_t (&b)[NBV]) {
+        const int ch = step * BK + vec * 8;
+        const uint32_t co = ch < p.C ? (uint32_t)ch * 2u : kOutOfRange;     // (also every step past the last one)
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+            a[i] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (a_off[i] | co) >= kOutOfRange ? kOutOfRange : a_off[i] + co, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NBV; ++i)
+            b[i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, (b_off[i] | co) >= kOutOfRange ? kOutOfRange : b_off[i] + co, 0, 0);
+    };
+    auto stage = [&](int buf, const u32x4_t (&a)[NA], const u32x4_t (&b)[NBV]) {
+        uint8_t *base = lds + buf * Cfg::STAGE_BYTES + row * RB + vec * 16;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4_t *>(base + 32 * i * RB) = a[i];
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) *reinterpret_cast<u32x4_t *>(base + (BM + 32 * i) * RB) = b[i];
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    float bias[MB];
+    load_bias<MB>(p, m0 + wm * (BM / 2), l32, bias);
+
+    // step s multiplies LDS stage `cur`, moves the loaded data of step s+1 to the other stage and requests
+    // step s+2 (zeros past the end, so an odd number of steps simply runs one more)
+    auto body = [&](int s, int cur, u32x4_t (&a_new)[NA], u32x4_t (&b_new)[NBV], const u32x4_t (&a_next)[NA],
+                    const u32x4_t (&b_next)[NBV]) __attribute__((always_inline)) {
+        fetch(s + 2, a_new, b_new);
+        const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
+        const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 av[MB], bv[NB];
+#pragma unroll
+            for (int i = 0; i < MB; ++i) av[i] = *reinterpret_cast<const bf16x8 *>(a_base + i * 32 * RB + ks * 32);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) bv[j] = *reinterpret_cast<const bf16x8 *>(b_base + j * 32 * RB + ks * 32);
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    if constexpr (Cfg::SWAP)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                }
+        }
+        stage(cur ^ 1, a_next, b_next);
+        __syncthreads();
+    };
+    fetch(0, a0, b0);
+    fetch(1, a1, b1);
+    stage(0, a0, b0);
+    __syncthreads();
+    for (int s = 0; s < p.ksteps; s += 2) {
+        body(s, 0, a0, b0, a1, b1);
+        body(s + 1, 1, a1, b1, a0, b0);
+    }
+    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bias, m0 + wm * (BM / 2), n0 + wn * (BN / 2), half, l32);
+}
+
+}  // namespace igc
+#endif

@@ -19,6 +19,7 @@ struct KernelInfo {
                     // 8 backward-filter with columns (tap, channel), one tap per tile,
                     // 9 backward-filter without padding, few channels,
                     // 11 mode 7 with a last step of half the k-groups,
+                    // 12 1x1 filters over channel vectors (bf16, unit channel stride): both operands loaded as they are,
                     // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers
     int threads;
     int ldsBytes;
@@ -35,16 +36,16 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.
 int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
                      void *stream);
 
-// wt[c][k][t] = w[k][c][t] for 2-byte elements, t < 9 (the filter with its first two
-// dimensions exchanged, each pair's nine taps kept in order); returns the runtime's error code.
-int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream);
+// wt[c][k][t] = w[k][c][t] for 2-byte elements, t < taps, taps 9 or 1 (the filter with its first two
+// dimensions exchanged, each pair's taps kept in order); returns the runtime's error code.
+int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream);
 
 // The same for the channel-vector backward-filter kernels, whose parts are stored as [tap][row position][column
 // position] (KP x CP positions per tap, tiles of BM x BN): see igconv_kernel_wgrad_bf16c.hpp.

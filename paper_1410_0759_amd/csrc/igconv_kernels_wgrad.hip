@@ -71,9 +71,11 @@ __global__ __launch_bounds__(256) void igconv_filter_exchange_kernel(const uint1
     }
 }
 
-int launch_filter_exchange9(const void *w, void *wt, int K, int C, void *stream) {
+int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream) {
     void *argv[] = {&w, &wt, &K, &C};
-    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<9>),
+    const void *kernel = taps == 9 ? reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<9>)
+                                   : reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<1>);
+    return static_cast<int>(hipLaunchKernel(kernel,
                                             dim3((K + 15) / 16, (C + 15) / 16), dim3(256), argv, 0,
                                             static_cast<hipStream_t>(stream)));
 }

@@ -88,6 +88,8 @@ BWD_AS_FORWARD = [
     (2, 24, 8, 9, 48, 3, 3, (2, 2), (1, 1)),         # "full" padding becomes pad 0
     (2, 7, 6, 20, 32, 1, 9, (0, 3), (1, 1)),         # nine taps in a row
     (1, 130, 28, 28, 64, 3, 3, (1, 0), (1, 1)),      # unequal pads, 130 rows
+    (2, 40, 9, 11, 48, 1, 1, (0, 0), (1, 1)),        # 1x1: the filter transposed, then a plain product
+    (3, 7, 14, 13, 136, 1, 1, (0, 0), (1, 1)),
 ]
 
 
@@ -98,10 +100,10 @@ def test_backward_data_bf16_channel_vectors(prob, mode):
     for dx_layout in ("NHWC", "NCHW"):
         asked = []
         _check_bd(prob, "bf16", mode, dx_layout=dx_layout, dy_layout="NHWC", seed=7, asked=asked)
-        assert asked == [K * C * 9 * 2]
+        assert asked == [K * C * R * S * 2]
     # the same problem without the workspace (general route), and with one that is too small
     _check_bd(prob, "bf16", mode, dx_layout="NHWC", dy_layout="NHWC", seed=7, workspace="none")
-    _check_bd(prob, "bf16", mode, dx_layout="NHWC", dy_layout="NHWC", seed=7, workspace=K * C * 9 * 2 - 2)
+    _check_bd(prob, "bf16", mode, dx_layout="NHWC", dy_layout="NHWC", seed=7, workspace=K * C * R * S * 2 - 2)
     _check_bd(prob, "bf16", mode, alpha=-0.5, beta=2.0, dx_layout="NHWC", dy_layout="NHWC", seed=8)
     # shapes that do not qualify ask for nothing
     asked = []

@@ -107,8 +107,17 @@ def test_every_kernel_variant():
                 (2, 3, 35, 33, 96, 11, 11, (0, 0), (4, 4)),       # 363: 12 steps, 11 in the last
                 (2, 7, 12, 9, 70, 5, 3, (0, 0), (1, 2)),          # 105: 4 steps, 9 in the last
             ]
-        channels = "channels" in name or "patch" in name
-        if channels:   # nine taps, channels in sixteens and contiguous; odd and even step counts
+        channels = "channels" in name or "patch" in name or "pointwise" in name
+        if "pointwise" in name:   # 1x1 filters, channels in eights and contiguous; one step, several, a ragged last one; strides, a border
+            vec = True
+            problems = [
+                (3, 16, 15, 17, 150, 1, 1, (0, 0), (1, 1)),
+                (2, 72, 21, 9, 45, 1, 1, (0, 0), (2, 1)),
+                (2, 200, 9, 30, 33, 1, 1, (1, 2), (1, 2)),
+                (1, 8, 12, 7, 200, 1, 1, (0, 0), (1, 1)),
+                (2, 128, 14, 14, 64, 1, 1, (0, 0), (1, 1)),
+            ]
+        elif channels:   # nine taps, channels in sixteens and contiguous; odd and even step counts
             vec = True
             problems = [
                 (3, 16, 15, 17, 150, 3, 3, (1, 1), (1, 1)),
@@ -152,6 +161,9 @@ def test_gather_modes_are_chosen():
     x, w = wl.random_problem(4, 2, 1, 20, 20, 33, 7, 7)
     _, plan = _check(x, w, (0, 0), (2, 1), 1, "f32", tag="mode nopad table, 17 indices in the last step")
     assert plan.gatherMode == 7 and plan.kSteps == 2
+    xp_, wp_ = wl.random_problem(5, 2, 64, 14, 14, 96, 1, 1, dtype="bf16")
+    _, plan = _check(wl.with_layout(xp_, "NHWC"), wp_, (0, 0), (1, 1), 1, "bf16", y_layout="NHWC", tag="mode pointwise")
+    assert plan.gatherMode == 12 and plan.kSteps == 1 and plan.swapOperands == 1
     xl, wl_ = wl.random_problem(4, 1, 100, 9, 9, 8, 5, 5)
     _, plan = _check(xl, wl_, (0, 0), (1, 1), 0, "f32", kernel=[i for i, n in enumerate(_names()) if n == "f32 32x128x32 nopad"][0],
                      tag="mode nopad")
