@@ -60,7 +60,10 @@ struct Bf16cConfig {
     // (COALA: one spare row for the four idle threads, then rounded up to 4 mod 8 rows: that plane
     // stride spreads the 2-byte scatter writes best over the LDS banks - 2.1 instead of 3.0 cycles
     // per write instruction in a model of the 64 banks)
-    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : THREADS / 2;
+    // (one thread per half row: with fewer than THREADS/2 rows the idle threads load nothing and
+    // write to 16 spare rows past the tile's - a two-way bank conflict on writes nobody reads -
+    // so that two workgroups fit a compute unit)
+    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : (BM_ < THREADS / 2 ? BM_ + 16 : THREADS / 2);
     static constexpr int A_BYTES = TAPS * AR * ROW_BYTES;
     static constexpr int B_BYTES = PATCH ? 2 * PATCH_PLANE : TAPS * BN * ROW_BYTES;
     static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     const uint32_t a_voff = (a_row < BM && m0 + a_row < p.K)
                                 ? ((uint32_t)(m0 + a_row) * (uint32_t)p.CRS + (uint32_t)ha * 72u) * 2u
                                 : kOutOfRange;
-    const int a_woff = plane_off(a_row, ha);
+    const int a_woff = plane_off(a_row < BM ? a_row : BM + (a_row & 15), ha);
 
     // COALA: thread = (row ca_r + 14*i in pass i, chunk ca_q of the row's 18); the four threads past
     // 252 load nothing and write to the spare row.  The eight elements of chunk ca_q are the
