@@ -151,7 +151,11 @@ def test_pooling_backward(mode):
              ((2, 3, 10, 12), (3, 3), (0, 0), (1, 1)), ((2, 3, 11, 9), (2, 2), (0, 0), (3, 3)), ((1, 2, 6, 30), (1, 5), (0, 2), (1, 2)),
              ((3, 5, 55, 55), (3, 3), (0, 0), (2, 2)), ((2, 3, 37, 20), (3, 3), (1, 1), (1, 1)),
              ((1, 2, 9, 700), (3, 3), (1, 1), (1, 1)),       # wide rows: fewer rows per workgroup
-             ((1, 1, 4, 2000), (3, 3), (1, 1), (1, 1))]      # too wide for the row-strip kernel
+             ((1, 1, 4, 2000), (3, 3), (1, 1), (1, 1)),      # too wide for the row-strip kernel
+             # stride 2 both ways (a thread per 2 x 2 cell of inputs): several strips of rows, a last row and
+             # column no window reaches, zero borders
+             ((2, 2, 130, 40), (3, 3), (1, 1), (2, 2)), ((2, 2, 130, 40), (2, 2), (1, 1), (2, 2)),
+             ((2, 3, 10, 12), (3, 3), (0, 0), (2, 2)), ((1, 2, 70, 255), (3, 3), (2, 2), (2, 2)), ((1, 2, 66, 256), (2, 2), (0, 0), (2, 2))]
     for shape, win, pad, st in cases:
         x = rnd(35, *shape) - np.float32(5.0)
         P, Q = po.pooling_output_dim(shape[2], win[0], pad[0], st[0]), po.pooling_output_dim(shape[3], win[1], pad[1], st[1])
