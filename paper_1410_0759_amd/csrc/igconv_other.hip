@@ -137,6 +137,13 @@ __device__ __forceinline__ real_t rload(__amdgpu_buffer_rsrc_t buf, uint32_t off
 __device__ __forceinline__ void rstore(__amdgpu_buffer_rsrc_t buf, uint32_t off4, real_t v) {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), buf, off4, 0, 0);
 }
+// 16 bytes at once (the address need only be a multiple of 4)
+constexpr int kWide = 4;
+typedef float wide_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ wide_t rload_wide(__amdgpu_buffer_rsrc_t buf, uint32_t off4) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(wide_t, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(buf, off4, 0, 0));
+}
 __device__ __forceinline__ real_t rexp(real_t x) { return __expf(x); }
 __device__ __forceinline__ real_t rmax(real_t a, real_t b) { return fmaxf(a, b); }
 #include "igconv_other_impl.inc"
@@ -153,6 +160,12 @@ __device__ __forceinline__ real_t rload(__amdgpu_buffer_rsrc_t buf, uint32_t off
 }
 __device__ __forceinline__ void rstore(__amdgpu_buffer_rsrc_t buf, uint32_t off4, real_t v) {
     __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, v), buf, off4 >= 0x80000000u ? 0x80000000u : off4 * 2u, 0, 0);
+}
+constexpr int kWide = 2;
+typedef double wide_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ wide_t rload_wide(__amdgpu_buffer_rsrc_t buf, uint32_t off4) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(wide_t, (u32x4_t)__builtin_amdgcn_raw_buffer_load_b128(buf, off4 >= 0x80000000u ? 0x80000000u : off4 * 2u, 0, 0));
 }
 __device__ __forceinline__ real_t rexp(real_t x) { return exp(x); }
 __device__ __forceinline__ real_t rmax(real_t a, real_t b) { return fmax(a, b); }
