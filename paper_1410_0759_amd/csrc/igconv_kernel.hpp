@@ -222,6 +222,10 @@ enum GatherMode {
     // indices (C*R*S mod BK in 1..BK/2, an even number of steps): that step runs only half of
     // its k-groups, the others would multiply zeros.
     GATHER_NOPAD_TABLE_SHORT = 11,
+    // GATHER_NOPAD_TABLE for an odd number of steps: the loop runs pairs of steps, and the second
+    // step of a tile's last pair, which would multiply zeros, does its side work only (requests
+    // and LDS writes for the workgroup's next tile) and no MFMA.
+    GATHER_NOPAD_TABLE_ODD = 13,
     // Backward-filter: the generic gather with the roles of the two index sets exchanged.
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
@@ -258,7 +262,10 @@ struct KernelConfig {
     static constexpr int LDV = (BK / VEC + 1) | 1;
     static constexpr int LD = LDV * VEC;
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
-    static constexpr int TABLE_BYTES = GMODE_ == GATHER_NOPAD_TABLE || GMODE_ == GATHER_NOPAD_TABLE_SHORT ? kOffsetTableEntries * 4 : 0;
+    static constexpr int TABLE_BYTES =
+        GMODE_ == GATHER_NOPAD_TABLE || GMODE_ == GATHER_NOPAD_TABLE_SHORT || GMODE_ == GATHER_NOPAD_TABLE_ODD ? kOffsetTableEntries * 4 : 0;
+    // Steps of 16 leave room (LDS, registers) for three workgroups per compute unit.
+    static constexpr int MIN_WAVES = BK_ == 16 ? 3 : 1;
     static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE + TABLE_BYTES;
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
     static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
@@ -280,12 +287,13 @@ struct KernelConfig {
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams p) {
+__global__ __launch_bounds__(256, Cfg::MIN_WAVES) void igconv_fwd_kernel(const ConvKernelParams p) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LD = Cfg::LD;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
     constexpr bool SHORT_LAST = Cfg::GMODE == GATHER_NOPAD_TABLE_SHORT;
-    constexpr int GM = SHORT_LAST ? (int)GATHER_NOPAD_TABLE : Cfg::GMODE;
+    constexpr bool ODD_LAST = Cfg::GMODE == GATHER_NOPAD_TABLE_ODD;
+    constexpr int GM = SHORT_LAST || ODD_LAST ? (int)GATHER_NOPAD_TABLE : Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
     constexpr bool WGN = GM == GATHER_WGRAD_NOPAD;
@@ -815,7 +823,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
     // stage alternate.
     // `groups`: the k-groups this step multiplies - all G of them, or (SHORT_LAST, last step of a
     // tile) only the first G/2, the rest of the step being zeros; both even, so that the fragment
-    // sets keep alternating in step.
+    // sets keep alternating in step; or (ODD_LAST, last step of a tile) none.
     // (always_inline: the accumulators must stay in registers; left to its own judgement the inliner gives up on
     // bodies of this size and the captured arrays move to scratch memory)
     auto step_groups = [&](auto parity, auto groups, int k2) __attribute__((always_inline)) {   // k2: the step whose tiles are requested during this one
@@ -824,6 +832,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         constexpr int NMS = GS == G ? NM : GS * MPG_FULL;      // MFMAs of this step
         constexpr int SBS = GS == G ? SB : NMS - MPG_FULL;     // first MFMA of its last group
         constexpr int fs0 = (G & 1) ? cur : 0;  // fragment set of this step's group 0
+        if constexpr (GS == 0) {
+            // nothing to multiply: the step's side work only, then the first fragments of the next
+            // step into the set that step starts with
+            static_for<NL>([&](auto ic) { load_item(decltype(ic)::value, cur, k2); });
+            static_for<NW>([&](auto ic) { write_item(decltype(ic)::value, nxt, nxt); });
+            lds_barrier();
+            read_frags(nxt, 0, (G & 1) ? nxt : 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         static_for<NMS>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             constexpr int g = m / MPG_FULL < GS - 1 ? m / MPG_FULL : GS - 1;
@@ -898,7 +915,7 @@ __global__ __launch_bounds__(256) void igconv_fwd_kernel(const ConvKernelParams 
         setup_tile(next);
         load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bias_next);
         step(std::integral_constant<int, 0>{}, t_begin);
-        step_groups(std::integral_constant<int, 1>{}, std::integral_constant<int, SHORT_LAST ? G / 2 : G>{}, t_begin + 1);
+        step_groups(std::integral_constant<int, 1>{}, std::integral_constant<int, SHORT_LAST ? G / 2 : (ODD_LAST ? 0 : G)>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
         // (GATHER_WGRAD_TAP: the columns are channels, 'R*S' elements apart; the tile's tap moves the base)
         const uint32_t ytap = GM == GATHER_WGRAD_TAP ? (uint32_t)out_tap * 4u : 0u;

@@ -19,6 +19,7 @@ struct KernelInfo {
                     // 8 backward-filter with columns (tap, channel), one tap per tile,
                     // 9 backward-filter without padding, few channels,
                     // 11 mode 7 with a last step of half the k-groups,
+                    // 13 mode 7 for an odd number of steps (the step that rounds the count up is not multiplied),
                     // 12 1x1 filters over channel vectors (bf16, unit channel stride): both operands loaded as they are,
                     // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers
     int threads;

@@ -19,6 +19,10 @@
     X("f32 128x128x32 nopad table", false, 128, 128, 32, 2, 2, false, false, GATHER_NOPAD_TABLE) \
     X("f32 96x128x32 nopad table vecw", false, 96, 128, 32, 1, 4, false, true, GATHER_NOPAD_TABLE) \
     X("f32 128x128x32 nopad table vecw", false, 128, 128, 32, 2, 2, false, true, GATHER_NOPAD_TABLE) \
+    X("f32 96x128x16 nopad table", false, 96, 128, 16, 1, 4, false, false, GATHER_NOPAD_TABLE) \
+    X("f32 96x128x16 nopad table odd", false, 96, 128, 16, 1, 4, false, false, GATHER_NOPAD_TABLE_ODD) \
+    X("f32 64x128x16 nopad table", false, 64, 128, 16, 2, 2, false, false, GATHER_NOPAD_TABLE) \
+    X("f32 64x128x16 nopad table odd", false, 64, 128, 16, 2, 2, false, false, GATHER_NOPAD_TABLE_ODD) \
     X("f32 32x128x32 nopad table short", false, 32, 128, 32, 1, 4, false, false, GATHER_NOPAD_TABLE_SHORT) \
     X("f32 64x128x32 nopad table short", false, 64, 128, 32, 2, 2, false, false, GATHER_NOPAD_TABLE_SHORT) \
     X("f32 96x128x32 nopad table short", false, 96, 128, 32, 1, 4, false, false, GATHER_NOPAD_TABLE_SHORT) \

@@ -87,11 +87,16 @@ def test_workload_dims_and_plans():
         tiles = -(-w_.K // plan.tileM) * -(-(w_.N * w_.P * w_.Q) // plan.tileN)
         per_xcd = -(-tiles // 8)
         if plan.gatherMode not in (4, 5):   # persistent workgroups: at most what 32 compute units per XCD hold
-            per_xcd = min(per_xcd, 32 * max(1, min(2, 160 * 1024 // plan.ldsBytes)))
+            # (two by LDS and registers; three for the kernels with steps of 16)
+            per_xcd = min(per_xcd, 32 * max(1, min(3 if plan.tileK == 16 else 2, 160 * 1024 // plan.ldsBytes)))
         assert plan.gridX == 8 * per_xcd
         assert plan.kSteps in (-(-(w_.C * w_.R * w_.S) // plan.tileK), w_.R * w_.S * -(-w_.C // plan.tileK))
         assert plan.ldsBytes <= 160 * 1024
         assert plan.swapOperands == (1 if w_.y_layout == "NHWC" else 0)
+        if w_ is wl.WORKLOADS[1]:
+            # 363 reduction indices, unpadded, 96 output channels: tap offsets from the LDS table, 23 steps
+            # of 16 (three workgroups per compute unit), the step that rounds 23 up is not multiplied
+            assert (plan.gatherMode, plan.kSteps, plan.tileM, plan.tileK) == (13, 23, 96, 16)
 
 
 def test_optional_forward_workspace_is_only_asked_for_where_cutting_the_reduction_pays():
