@@ -87,8 +87,10 @@ def test_workload_dims_and_plans():
         tiles = -(-w_.K // plan.tileM) * -(-(w_.N * w_.P * w_.Q) // plan.tileN)
         per_xcd = -(-tiles // 8)
         if plan.gatherMode not in (4, 5):   # persistent workgroups: at most what 32 compute units per XCD hold
-            # (two by LDS and registers; three for the kernels with steps of 16)
-            per_xcd = min(per_xcd, 32 * max(1, min(3 if plan.tileK == 16 else 2, 160 * 1024 // plan.ldsBytes)))
+            # (two by LDS and registers; three or, for tiles up to 64 x 128, four for the kernels with steps of 16)
+            by_regs = (4 if plan.tileM * plan.tileN <= 64 * 128 else 3) if plan.tileK == 16 else (
+                4 if plan.gatherMode == 2 and plan.tileM * plan.tileN <= 64 * 64 and plan.tileK == 32 else 2)
+            per_xcd = min(per_xcd, 32 * max(1, min(by_regs, 160 * 1024 // plan.ldsBytes)))
         assert plan.gridX == 8 * per_xcd
         assert plan.kSteps in (-(-(w_.C * w_.R * w_.S) // plan.tileK), w_.R * w_.S * -(-w_.C // plan.tileK))
         assert plan.ldsBytes <= 160 * 1024
