@@ -172,9 +172,14 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // scale makes them comparable with the line below.
     // (1x1 filters over channel vectors: loads of both operands and a small MFMA term per step of 64 channels)
     if (ki.gmode == 12) return tile_times * steps * 1000.0 * (1.0 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 64.0);
-    if (ki.gmode == 4 || ki.gmode == 5)
-        return tile_times * steps * 1000.0 *
+    if (ki.gmode == 4 || ki.gmode == 5) {
+        // (two teams per workgroup, each on half of the steps, plus the exchange of the results: for problems
+        // that leave compute units without a workgroup; with more tiles two workgroups per compute unit do the same)
+        if (ki.variant == 2 && tiles > kComputeUnits) return 1e300;
+        const double st = ki.variant == 2 ? (double)((steps + 1) / 2 + 2) : (double)steps;
+        return tile_times * st * 1000.0 *
                ((ki.variant == 1 ? 2.9 : 2.75) * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
+    }
     const bool table = ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13;
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (table ? 14.0 : 6.0)));
     // (mode 11 multiplies only half of its last step; mode 13 skips the step that rounds an odd count up;

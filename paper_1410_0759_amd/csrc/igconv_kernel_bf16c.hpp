@@ -36,9 +36,15 @@
 
 namespace igc {
 
-template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false, bool COALA_ = false>
+template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false, bool COALA_ = false, int TEAMS_ = 1>
 struct Bf16cConfig {
     static constexpr bool PATCH = PATCH_;
+    // TEAMS = 2: a workgroup of 512 threads, two teams of four wavefronts, each running the whole
+    // pipeline below in its own half of LDS over its half of the reduction steps; the second team's
+    // accumulators are added to the first's through LDS before the epilogue (a fixed order).  For
+    // problems with fewer tiles than compute units, where one workgroup per compute unit spends most
+    // of a step waiting for its loads: two teams keep twice as many loads in flight.
+    static constexpr int TEAMS = TEAMS_;
     // COALA: filter rows loaded with neighbouring lanes on neighbouring 16-byte chunks of a row
     // (18 lanes per row and step, 14 rows per pass) and scattered into the tap planes element by
     // element, instead of one thread per half row with a register transposition: a load
@@ -51,40 +57,45 @@ struct Bf16cConfig {
     static constexpr int PATCH_PLANE = PATCH_PIX * 16 + 128;  // one channel half; +128 B: halves on disjoint banks
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
     static constexpr bool SWAP = SWAP_;
-    static constexpr int THREADS = 256;
+    static constexpr int TEAM_THREADS = 256;
+    static constexpr int THREADS = TEAM_THREADS * TEAMS_;
     static constexpr int TAPS = 9, CH = 16;                 // per reduction step
     static constexpr int BK = TAPS * CH;
     static constexpr int ROW_BYTES = CH * 2;                // one row of one tap: two 16-byte halves
     // Every thread stages filter rows, so that the main loop has no divergent code: the
-    // F_m planes always hold THREADS/2 rows, of which the first BM are used.
+    // F_m planes always hold TEAM_THREADS/2 rows, of which the first BM are used.
     // (COALA: one spare row for the four idle threads, then rounded up to 4 mod 8 rows: that plane
     // stride spreads the 2-byte scatter writes best over the LDS banks - 2.1 instead of 3.0 cycles
     // per write instruction in a model of the 64 banks)
-    // (one thread per half row: with fewer than THREADS/2 rows the idle threads load nothing and
+    // (one thread per half row: with fewer than TEAM_THREADS/2 rows the idle threads load nothing and
     // write to 16 spare rows past the tile's - a two-way bank conflict on writes nobody reads -
     // so that two workgroups fit a compute unit)
-    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : (BM_ < THREADS / 2 ? BM_ + 16 : THREADS / 2);
+    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : (BM_ < TEAM_THREADS / 2 ? BM_ + 16 : TEAM_THREADS / 2);
     static constexpr int A_BYTES = TAPS * AR * ROW_BYTES;
     static constexpr int B_BYTES = PATCH ? 2 * PATCH_PLANE : TAPS * BN * ROW_BYTES;
-    static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
+    static constexpr int TEAM_LDS_BYTES = 2 * (A_BYTES + B_BYTES);
+    static constexpr int LDS_BYTES = TEAMS_ * TEAM_LDS_BYTES;
     static constexpr int TM = BM / WM, TN = BN / WN;
     static constexpr int MB = TM / 32, NB = TN / 32;
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave blocks are 32x32 multiples");
-    static_assert(BM <= AR && (PATCH || 2 * BN == THREADS), "thread = (row or column, channel half)");
+    static_assert(BM <= AR && (PATCH || 2 * BN == TEAM_THREADS), "thread = (row or column, channel half)");
+    static_assert(TEAMS_ == 1 || (TEAMS_ == 2 && !COALA_ && BM_ * BN_ * 4 <= TEAM_LDS_BYTES), "two teams: the second team's results pass through its LDS");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelParams p) {
+__global__ __launch_bounds__(Cfg::THREADS) void igconv_fwd_bf16c_kernel(const ConvKernelParams p) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, MB = Cfg::MB, NB = Cfg::NB;
     constexpr int TAPS = Cfg::TAPS;
 
     __shared__ __attribute__((aligned(16))) uint8_t lds[Cfg::LDS_BYTES];
-    uint8_t *const ldsA = lds;                      // [2][TAPS][AR][32]
-    uint8_t *const ldsB = lds + 2 * Cfg::A_BYTES;   // [2][TAPS][BN][32]
+    // (two teams: `tid` is the thread's number within its team, `wave` the wavefront's)
+    const int team = Cfg::TEAMS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    uint8_t *const ldsA = lds + team * Cfg::TEAM_LDS_BYTES;   // [2][TAPS][AR][32]
+    uint8_t *const ldsB = ldsA + 2 * Cfg::A_BYTES;            // [2][TAPS][BN][32]
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5;
@@ -215,9 +226,14 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     u32x4 a_reg[2][NAL], b_reg[2][NBL];
     uint32_t sc_asoff = 0, sc_bsoff = 0;
 
+    // Steps of this team: [s_begin, s_end); every team runs `team_steps` of them (the workgroup's
+    // barriers are common), the ones past s_end on zeros.
+    const int team_steps = Cfg::TEAMS > 1 ? ((p.ksteps + Cfg::TEAMS - 1) / Cfg::TEAMS + 1) & ~1 : p.ksteps;
+    const int s_begin = team * team_steps;
+    const int s_end = Cfg::TEAMS > 1 ? min(p.ksteps, s_begin + team_steps) : p.ksteps;
     auto decode = [&](int tau) {
-        const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)tau);
-        const uint32_t live = mask_lt(ut, (uint32_t)p.ksteps);
+        const uint32_t ut = __builtin_amdgcn_readfirstlane((uint32_t)(s_begin + tau));
+        const uint32_t live = mask_lt(ut, (uint32_t)max(s_end, 0));
         sc_asoff = ((ut * (uint32_t)(Cfg::BK * 2)) & live) | (p.w_bytes & ~live);   // 16 channels x 9 taps of a row
         sc_bsoff = ((ut * (uint32_t)(Cfg::CH * 2) * (uint32_t)p.xsC) & live) | (p.x_bytes & ~live);
     };
@@ -363,11 +379,39 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16c_kernel(const ConvKernelP
     read_frags(0, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): enter the loop with no load outstanding
     __builtin_amdgcn_sched_barrier(0);
-    for (int t = 0; t < p.ksteps; t += 2) {
+    for (int t = 0; t < team_steps; t += 2) {
         step(std::integral_constant<int, 0>{}, t);
         step(std::integral_constant<int, 1>{}, t + 1);
     }
 
+    if constexpr (Cfg::TEAMS > 1) {
+        // the second team's sums go to the first through the second team's LDS (all of its reads
+        // are done: barrier), 16 bytes per lane and piece: lane-contiguous, conflict-free
+        __syncthreads();
+        f32x4 *const xch = reinterpret_cast<f32x4 *>(lds + Cfg::TEAM_LDS_BYTES) + (wave * MB * NB * 4) * 64 + lane;
+        if (team == 1) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        xch[((mb * NB + nb) * 4 + c) * 64] =
+                            f32x4{acc[mb][nb][4 * c], acc[mb][nb][4 * c + 1], acc[mb][nb][4 * c + 2], acc[mb][nb][4 * c + 3]};
+        }
+        __syncthreads();
+        if (team == 1) return;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const f32x4 o = xch[((mb * NB + nb) * 4 + c) * 64];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[mb][nb][4 * c + e] += o[e];
+                }
+    }
     store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bvec, m0 + wm * Cfg::TM, n0 + wn * Cfg::TN, half, l32);
 }
 

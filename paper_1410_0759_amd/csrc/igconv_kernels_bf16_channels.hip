@@ -27,9 +27,17 @@ static int launch_bf16c(const ConvKernelParams &p, int grid, void *stream) {
     X("bf16 64x128x144 patch rows", 64, 128, 2, 2, false, true, true) \
     X("bf16 64x128x144 patch rows swap", 64, 128, 2, 2, true, true, true)
 
+// two teams of four wavefronts per workgroup, each on half of the reduction steps
+#define IGC_BF16C_TEAMS_LIST(X) \
+    X("bf16 64x256x144 patch teams", 64, 256, 1, 4, false, true, false) \
+    X("bf16 64x256x144 patch teams swap", 64, 256, 1, 4, true, true, false)
+
 #define IGC_BF16C_INSTANTIATE(NAME, BM, BN, WM, WN, SWAP, PATCH, COALA) \
     template __global__ void igconv_fwd_bf16c_kernel<Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA>>(const ConvKernelParams);
 IGC_BF16C_LIST(IGC_BF16C_INSTANTIATE)
+#define IGC_BF16C_TEAMS_INSTANTIATE(NAME, BM, BN, WM, WN, SWAP, PATCH, COALA) \
+    template __global__ void igconv_fwd_bf16c_kernel<Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA, 2>>(const ConvKernelParams);
+IGC_BF16C_TEAMS_LIST(IGC_BF16C_TEAMS_INSTANTIATE)
 
 #if !defined(__HIP_DEVICE_COMPILE__)
 #define IGC_BF16C_ROW(NAME, BM, BN, WM, WN, SWAP, PATCH, COALA)                                 \
@@ -37,7 +45,12 @@ IGC_BF16C_LIST(IGC_BF16C_INSTANTIATE)
      Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA>::LDS_BYTES,                                 \
      &launch_bf16c<Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA>>, COALA ? 1 : 0},
 static_assert(Bf16cConfig<128, 128, 2, 2, false, true>::PATCH_PIX == 512, "the host's patch capacity must match");
-static const KernelInfo kRows[] = {IGC_BF16C_LIST(IGC_BF16C_ROW)};
+// (variant 2: the two-team kernels)
+#define IGC_BF16C_TEAMS_ROW(NAME, BM, BN, WM, WN, SWAP, PATCH, COALA)                                 \
+    {NAME, true, BM, BN, Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA, 2>::BK, SWAP, true, PATCH ? 5 : 4, 512, \
+     Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA, 2>::LDS_BYTES,                                 \
+     &launch_bf16c<Bf16cConfig<BM, BN, WM, WN, SWAP, PATCH, COALA, 2>>, 2},
+static const KernelInfo kRows[] = {IGC_BF16C_LIST(IGC_BF16C_ROW) IGC_BF16C_TEAMS_LIST(IGC_BF16C_TEAMS_ROW)};
 const KernelGroup kGroupBF16Channels = {kRows, sizeof(kRows) / sizeof(kRows[0])};
 #endif
 
