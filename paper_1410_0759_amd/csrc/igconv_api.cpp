@@ -166,10 +166,8 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // D_m; measured on the box, gathering one element costs about as much MFMA time as
     // `gather` multiply-add rows, depending on the mode.
     // The channel-vector bf16 kernels are bound by their loads, not by the MFMA pipe: measured,
-    // a step costs about 2.75 units per filter row (2.9 with coalesced row loads and 2-byte LDS
-    // scatter: slower than the register transposition since two workgroups of the latter fit a
-    // compute unit) and 1 (1.5 when gathered tap by tap) per column, plus a small MFMA term; the
-    // scale makes them comparable with the line below.
+    // a step costs about 2.75 units per filter row and 1 (1.5 when gathered tap by tap) per column,
+    // plus a small MFMA term; the scale makes them comparable with the line below.
     // (1x1 filters over channel vectors: loads of both operands and a small MFMA term per step of 64 channels)
     if (ki.gmode == 12) return tile_times * steps * 1000.0 * (1.0 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 64.0);
     if (ki.gmode == 4 || ki.gmode == 5) {
@@ -178,7 +176,7 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
         if (ki.variant == 2 && tiles > kComputeUnits) return 1e300;
         const double st = ki.variant == 2 ? (double)((steps + 1) / 2 + 2) : (double)steps;
         return tile_times * st * 1000.0 *
-               ((ki.variant == 1 ? 2.9 : 2.75) * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
+               (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     }
     const bool table = ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13;
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (table ? 14.0 : 6.0)));

@@ -36,7 +36,7 @@
 
 namespace igc {
 
-template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false, bool COALA_ = false, int TEAMS_ = 1>
+template <int BM_, int BN_, int WM_, int WN_, bool SWAP_, bool PATCH_ = false, int TEAMS_ = 1>
 struct Bf16cConfig {
     static constexpr bool PATCH = PATCH_;
     // TEAMS = 2: a workgroup of 512 threads, two teams of four wavefronts, each running the whole
@@ -45,14 +45,6 @@ struct Bf16cConfig {
     // problems with fewer tiles than compute units, where one workgroup per compute unit spends most
     // of a step waiting for its loads: two teams keep twice as many loads in flight.
     static constexpr int TEAMS = TEAMS_;
-    // COALA: filter rows loaded with neighbouring lanes on neighbouring 16-byte chunks of a row
-    // (18 lanes per row and step, 14 rows per pass) and scattered into the tap planes element by
-    // element, instead of one thread per half row with a register transposition: a load
-    // instruction then touches a dozen cache lines instead of 64, and the L1's rate of line
-    // lookups is what bounds these kernels.
-    static constexpr bool COALA = COALA_;
-    static constexpr int RPP = 14;                               // rows per pass (14 x 18 = 252 threads)
-    static constexpr int NAP = (BM_ + RPP - 1) / RPP;            // passes
     static constexpr int PATCH_PIX = 512;                   // pixels of the zero-extended image per tile
     static constexpr int PATCH_PLANE = PATCH_PIX * 16 + 128;  // one channel half; +128 B: halves on disjoint banks
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
@@ -64,13 +56,10 @@ struct Bf16cConfig {
     static constexpr int ROW_BYTES = CH * 2;                // one row of one tap: two 16-byte halves
     // Every thread stages filter rows, so that the main loop has no divergent code: the
     // F_m planes always hold TEAM_THREADS/2 rows, of which the first BM are used.
-    // (COALA: one spare row for the four idle threads, then rounded up to 4 mod 8 rows: that plane
-    // stride spreads the 2-byte scatter writes best over the LDS banks - 2.1 instead of 3.0 cycles
-    // per write instruction in a model of the 64 banks)
     // (one thread per half row: with fewer than TEAM_THREADS/2 rows the idle threads load nothing and
     // write to 16 spare rows past the tile's - a two-way bank conflict on writes nobody reads -
     // so that two workgroups fit a compute unit)
-    static constexpr int AR = COALA_ ? ((NAP * RPP + 1 + 3) / 8) * 8 + 4 : (BM_ < TEAM_THREADS / 2 ? BM_ + 16 : TEAM_THREADS / 2);
+    static constexpr int AR = BM_ < TEAM_THREADS / 2 ? BM_ + 16 : TEAM_THREADS / 2;
     static constexpr int A_BYTES = TAPS * AR * ROW_BYTES;
     static constexpr int B_BYTES = PATCH ? 2 * PATCH_PLANE : TAPS * BN * ROW_BYTES;
     static constexpr int TEAM_LDS_BYTES = 2 * (A_BYTES + B_BYTES);
@@ -80,7 +69,7 @@ struct Bf16cConfig {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave blocks are 32x32 multiples");
     static_assert(BM <= AR && (PATCH || 2 * BN == TEAM_THREADS), "thread = (row or column, channel half)");
-    static_assert(TEAMS_ == 1 || (TEAMS_ == 2 && !COALA_ && BM_ * BN_ * 4 <= TEAM_LDS_BYTES), "two teams: the second team's results pass through its LDS");
+    static_assert(TEAMS_ == 1 || (TEAMS_ == 2 && BM_ * BN_ * 4 <= TEAM_LDS_BYTES), "two teams: the second team's results pass through its LDS");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -194,33 +183,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_fwd_bf16c_kernel(const Co
                                 : kOutOfRange;
     const int a_woff = plane_off(a_row < BM ? a_row : BM + (a_row & 15), ha);
 
-    // COALA: thread = (row ca_r + 14*i in pass i, chunk ca_q of the row's 18); the four threads past
-    // 252 load nothing and write to the spare row.  The eight elements of chunk ca_q are the
-    // (channel, tap) pairs f = 8*ca_q + j -> (f / 9, f % 9); ca_base[j] is where element j goes
-    // relative to the row's 32 bytes in plane 0 (bit 4 of it is the channel half, which the
-    // row's swizzle bit flips).
-    constexpr bool COALA = Cfg::COALA;
-    constexpr int NAP = COALA ? Cfg::NAP : 1;
-    constexpr int NAL = COALA ? NAP : TAPS;      // filter loads per thread and step
-    const bool ca_on = tid < 18 * Cfg::RPP;
-    const int ca_q = tid % 18, ca_r = tid / 18;
-    uint32_t ca_voff[NAP];
-    int ca_row[NAP], ca_base[8];
-    if constexpr (COALA) {
-#pragma unroll
-        for (int i = 0; i < NAP; ++i) {
-            const int row = ca_on ? ca_r + Cfg::RPP * i : Cfg::NAP * Cfg::RPP;
-            ca_voff[i] = (ca_on && row < BM && m0 + row < p.K) ? ((uint32_t)(m0 + row) * (uint32_t)p.CRS) * 2u + (uint32_t)ca_q * 16u
-                                                              : kOutOfRange;
-            // (the swizzle bit of the row rides in bit 30: it is XORed into bit 4 of ca_base below)
-            ca_row[i] = (row * 32) | (((row >> 3) & 1) << 30);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int f = 8 * ca_q + j, c = f / 9, t = f % 9;
-            ca_base[j] = t * (Cfg::AR * 32) + (c >> 3) * 16 + (c & 7) * 2;
-        }
-    }
+    constexpr int NAL = TAPS;      // filter loads per thread and step
 
     // registers holding the tiles in flight (two sets)
     u32x4 a_reg[2][NAL], b_reg[2][NBL];
@@ -237,11 +200,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_fwd_bf16c_kernel(const Co
         sc_asoff = ((ut * (uint32_t)(Cfg::BK * 2)) & live) | (p.w_bytes & ~live);   // 16 channels x 9 taps of a row
         sc_bsoff = ((ut * (uint32_t)(Cfg::CH * 2) * (uint32_t)p.xsC) & live) | (p.x_bytes & ~live);
     };
-    auto load_a = [&](int set, int q) {   // q-th 16 bytes of this thread's 72 elements; COALA: the chunk of pass q
-        if constexpr (COALA)
-            a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, ca_voff[q], sc_asoff, 0);
-        else
-            a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, sc_asoff, 0);
+    auto load_a = [&](int set, int q) {   // q-th 16 bytes of this thread's 72 elements
+        a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, sc_asoff, 0);
     };
     auto load_b = [&](int set, int i) {
         b_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, b_voff[i], sc_bsoff, 0);
@@ -249,16 +209,6 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_fwd_bf16c_kernel(const Co
     // Tap t of the thread's 8 channels: element (c, t) sits at position c*9 + t of the 72
     // loaded ones, i.e. 16-bit half (c*9+t)&1 of dword (c*9+t)>>1.
     auto write_a = [&](int set, int buf, int t) {
-        if constexpr (COALA) {   // t: the pass; eight 2-byte elements to their tap planes
-            const int rowbase = ca_row[t] & 0x3fffffff, flip = (ca_row[t] >> 30) << 4;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t d = a_reg[set][t][j >> 1];
-                *reinterpret_cast<uint16_t *>(ldsA + buf * Cfg::A_BYTES + rowbase + (ca_base[j] ^ flip)) =
-                    (uint16_t)((j & 1) ? d >> 16 : d);
-            }
-            return;
-        }
         u32x4 o;
 #pragma unroll
         for (int jd = 0; jd < 4; ++jd) {

@@ -26,8 +26,8 @@ struct KernelInfo {
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
-    int variant = 0;  // bf16 channel-vector kernels: 1 when filter rows are loaded coalesced and scattered to LDS,
-                      // 2 for two teams of four wavefronts per workgroup (512 threads), each on half of the steps
+    int variant = 0;  // bf16 channel-vector kernels: 2 for two teams of four wavefronts per workgroup (512 threads),
+                      // each on half of the steps
     bool f64 = false; // double precision in and out (alpha64 / beta64 of the parameters apply)
 };
 
