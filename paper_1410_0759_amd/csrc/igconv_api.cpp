@@ -24,7 +24,7 @@ constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise, &kGroupF32Teams};
 
 int kernel_count() {
     int n = 0;
@@ -67,6 +67,7 @@ struct Problem {
     int vec;  // elements per 16 bytes of input
     unsigned mode_mask = 0;   // non-zero: bit g set when gather mode g can run this problem
     bool zero_steps = false;  // nothing to accumulate: the kernel only scales the old output
+    bool no_teams = false;    // leave the fp32 team kernels out of the choice (a workspace cuts the reduction further)
 };
 
 // Everything igcConvolutionForward checks that does not need the data pointers.
@@ -179,6 +180,17 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
                (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     }
     const bool table = ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13;
+    if (ki.variant == 2) {
+        // Teams: one tile per workgroup and one workgroup per compute unit at a time; each team multiplies its
+        // share of the steps, the teams of a compute unit sharing its MFMA pipes - the work per compute unit is
+        // that of the plain kernel, but its waits are covered (measured: about 0.8 of the time when the plain
+        // kernel runs one workgroup per compute unit) and a fixed cost of about three steps is added.  Offered
+        // only where the plain kernels leave compute units with a single workgroup or none.
+        const int teams = ki.threads / 256;
+        if (tiles > kComputeUnits || steps < 8 * teams) return 1e300;
+        const double gather2 = ki.gmode == 2 ? 29.0 : 6.0;
+        return 0.8 * ((double)steps + 3.0 * teams) * (double)ki.BN * ki.BK * (ki.BM + gather2);
+    }
     const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (table ? 14.0 : 6.0)));
     // (mode 11 multiplies only half of its last step; mode 13 skips the step that rounds an odd count up;
     // steps of 16 with three workgroups per compute unit: measured 2.7 % faster than steps of 32 with two)
@@ -254,6 +266,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || ki.f64 != pr.f64 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
+        if (pr.no_teams && ki.variant == 2 && ki.gmode < 4) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -272,7 +285,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || ki.f64) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || ki.f64 || ki.variant == 2) return tiles_per_xcd;
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
 }
 
@@ -287,7 +300,7 @@ static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
 // pass (about 12).  Cutting must win by a tenth, or it is not done.
 static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool packed_y, long long max_parts, int *per_out) {
     *per_out = (k.ksteps + 1) & ~1;
-    if (ki.gmode > 3 || !packed_y) return 1;
+    if (ki.gmode > 3 || ki.variant == 2 || !packed_y) return 1;
     const long long tiles = (long long)k.tilesM * k.tilesN;
     const long long smax = std::min<long long>(std::min<long long>(64, k.ksteps / 8), max_parts);
     const double kFixed = 6.0, kSumPass = 12.0;
@@ -324,6 +337,10 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
     k.splits = 1;
     k.stepsPerSplit = (k.ksteps + 1) & ~1;
+    if (ki.variant == 2 && ki.gmode < 4) {   // (fp32 team kernels: an even number of steps per team)
+        const int teams = ki.threads / 256;
+        k.stepsPerSplit = ((k.ksteps + teams - 1) / teams + 1) & ~1;
+    }
     if (plan) {
         plan->kernelId = id;
         plan->tileM = ki.BM;
@@ -843,6 +860,7 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcT
     igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
     if (st != IGC_STATUS_SUCCESS) return st;
     int id = -1;
+    pr.no_teams = true;   // (as the forward call does when it is lent a workspace)
     st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
     st = fill_plan(id, &pr, nullptr);
@@ -920,11 +938,31 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     if ((uintptr_t)x % es || (uintptr_t)w % es || (uintptr_t)y % (pr.f64 ? 8 : 4)) return IGC_STATUS_BAD_PARAM;
     if (pr.f64 && (bias || activation != IGC_ACTIVATION_IDENTITY)) return IGC_STATUS_NOT_SUPPORTED;
     int id = -1;
-    st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, /*x_aligned=*/((uintptr_t)x % 16) == 0, &id);
-    if (st != IGC_STATUS_SUCCESS) return st;
     igcConvolutionForwardPlan plan;
-    st = fill_plan(id, &pr, &plan);
-    if (st != IGC_STATUS_SUCCESS) return st;
+    // With a workspace the reduction of a small problem is cut into ranges (below), finer than the team kernels
+    // cut it: those are left out of the choice then, unless the cut does not pay for the kernel chosen instead.
+    const bool can_cut = workSpace && (uintptr_t)workSpace % 4 == 0 && !bias && activation == IGC_ACTIVATION_IDENTITY && !pr.f64;
+    bool cut_found = false;
+    if (can_cut) {
+        Problem trial = pr;
+        trial.no_teams = true;
+        int tid_ = -1, per_ = 0;
+        if (choose(handle, trial, ((uintptr_t)w % 16) == 0, ((uintptr_t)x % 16) == 0, &tid_) == IGC_STATUS_SUCCESS &&
+            fill_plan(tid_, &trial, &plan) == IGC_STATUS_SUCCESS) {
+            const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)trial.kp.K * trial.kp.NPQ;
+            if (forward_split(*kernel_info(tid_), trial.kp, packed, (long long)(workSpaceSizeInBytes / trial.kp.y_bytes), &per_) > 1) {
+                pr = trial;
+                id = tid_;
+                cut_found = true;
+            }
+        }
+    }
+    if (!cut_found) {
+        st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, /*x_aligned=*/((uintptr_t)x % 16) == 0, &id);
+        if (st != IGC_STATUS_SUCCESS) return st;
+        st = fill_plan(id, &pr, &plan);
+        if (st != IGC_STATUS_SUCCESS) return st;
+    }
     pr.kp.x = x;
     pr.kp.w = w;
     pr.kp.y = y;
@@ -940,7 +978,7 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     // A small problem with a workspace: cut the reduction into ranges (see forward_split).
     int grid = plan.gridX;
     int splits = 1;
-    if (workSpace && (uintptr_t)workSpace % 4 == 0 && !bias && activation == IGC_ACTIVATION_IDENTITY && !pr.f64) {
+    if (can_cut) {
         ConvKernelParams &k = pr.kp;
         const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)k.K * k.NPQ;
         int per;

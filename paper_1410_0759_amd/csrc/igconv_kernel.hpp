@@ -246,14 +246,21 @@ enum GatherMode {
 
 constexpr int kOffsetTableEntries = 2048;
 
-template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC>
+// TEAMS > 1: a workgroup of TEAMS x 256 threads - TEAMS teams of four wavefronts, each running the
+// whole pipeline in its own part of LDS over its own range of the reduction steps; before the
+// epilogue the other teams' accumulators are added to the first team's through LDS, in team
+// order.  For problems with few tiles and long reductions, one tile per workgroup: the compute
+// units get several wavefronts per SIMD (which cover each other's waits) and the idle ones work.
+template <bool BF16_, int BM_, int BN_, int BK_, int WM_, int WN_, bool SWAP_, bool VECA_, int GMODE_ = GATHER_GENERIC,
+          int TEAMS_ = 1>
 struct KernelConfig {
     static constexpr int GMODE = GMODE_;
+    static constexpr int TEAMS = TEAMS_;
     static constexpr bool BF16 = BF16_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr bool SWAP = SWAP_;  // lanes run along output channels in the epilogue
     static constexpr bool VECA = VECA_;  // filter rows fetched with 16-byte loads
-    static constexpr int THREADS = 256;
+    static constexpr int THREADS = 256 * TEAMS_;
     static constexpr int ESIZE = BF16 ? 2 : 4;
     static constexpr int VEC = 16 / ESIZE;           // elements per 16-byte LDS access
     static constexpr int KG = 2 * VEC;               // reduction elements per full k-group
@@ -265,8 +272,9 @@ struct KernelConfig {
     static constexpr int TABLE_BYTES =
         GMODE_ == GATHER_NOPAD_TABLE || GMODE_ == GATHER_NOPAD_TABLE_SHORT || GMODE_ == GATHER_NOPAD_TABLE_ODD ? kOffsetTableEntries * 4 : 0;
     // Steps of 16 leave room (LDS, registers) for three workgroups per compute unit.
-    static constexpr int MIN_WAVES = BK_ == 16 ? 3 : 1;
-    static constexpr int LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE + TABLE_BYTES;
+    static constexpr int MIN_WAVES = TEAMS_ > 1 ? TEAMS_ : (BK_ == 16 ? 3 : 1);
+    static constexpr int TEAM_LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE;
+    static constexpr int LDS_BYTES = TEAMS_ * TEAM_LDS_BYTES + TABLE_BYTES;
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
     static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
     static constexpr int CG = BN / 64;               // column groups of 64 lanes
@@ -279,6 +287,8 @@ struct KernelConfig {
     static_assert(BK % VEC == 0 && BK % KPARTS == 0 && KPT % 2 == 0, "k tile granularity");
     static_assert(REM == 0 || (!BF16 && REM == 4), "a partial k-group is half a group, fp32 only");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(TEAMS_ == 1 || ((GMODE_ == GATHER_NOPAD || GMODE_ == GATHER_TAPS9) && !BF16_ && BM_ * BN_ * 4 <= TEAM_LDS_BYTES),
+                  "teams: fp32 kernels whose steps stand alone; a team's results pass through its LDS");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
     static_assert((GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD) || (!VECA && 256 % BK == 0),
                   "one reduction index per thread, element-wise first operand");
@@ -287,7 +297,7 @@ struct KernelConfig {
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(256, Cfg::MIN_WAVES) void igconv_fwd_kernel(const ConvKernelParams p) {
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kernel(const ConvKernelParams p) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LD = Cfg::LD;
     constexpr int VEC = Cfg::VEC, KG = Cfg::KG, ES = Cfg::ESIZE;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, KPT = Cfg::KPT;
@@ -301,12 +311,14 @@ __global__ __launch_bounds__(256, Cfg::MIN_WAVES) void igconv_fwd_kernel(const C
     constexpr bool WGT = GM == GATHER_WGRAD_TAP || WGN;                        // lanes along the reduction index
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
-    __shared__ __attribute__((aligned(16))) elem_t lds[2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
-    elem_t *const ldsA = lds;                       // [2][BM][LD]
-    elem_t *const ldsB = lds + 2 * Cfg::A_ELEMS;    // [2][BN][LD]
+    __shared__ __attribute__((aligned(16))) elem_t lds[Cfg::TEAMS * 2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
+    // (teams: `tid` and `wave` count within the thread's team, whose LDS follows the previous team's)
+    const int team = Cfg::TEAMS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) : 0;
+    elem_t *const ldsA = lds + team * 2 * (Cfg::A_ELEMS + Cfg::B_ELEMS);   // [2][BM][LD]
+    elem_t *const ldsB = ldsA + 2 * Cfg::A_ELEMS;                          // [2][BN][LD]
     __shared__ uint32_t so_table[GM == GATHER_NOPAD_TABLE ? kOffsetTableEntries : 1];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5;   // which half of the k-group this lane feeds
@@ -476,6 +488,7 @@ __global__ __launch_bounds__(256, Cfg::MIN_WAVES) void igconv_fwd_kernel(const C
             tile -= split * tiles_mn;
             t_begin = split * p.stepsPerSplit;
         }
+        if constexpr (Cfg::TEAMS > 1) t_begin = team * p.stepsPerSplit;   // (the host: one range, stepsPerSplit steps per team)
         m0 = (tile % p.tilesM) * BM;
         if constexpr (WGN) {
             n0 = (tile / p.tilesM) * BN;
@@ -922,6 +935,37 @@ __global__ __launch_bounds__(256, Cfg::MIN_WAVES) void igconv_fwd_kernel(const C
         const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + ytap;
         const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
             static_cast<char *>(p.y) + ybase, 0, p.y_bytes - ytap, kBufferWord3);
+        if constexpr (Cfg::TEAMS > 1) {
+            // The host gives a workgroup of teams one tile, so nothing in LDS is needed any more: the
+            // teams after the first leave their sums at the start of their LDS (16 bytes per lane and
+            // piece: lane-contiguous), the first adds them in team order.
+            __syncthreads();
+            constexpr int TEAM_F4 = Cfg::TEAM_LDS_BYTES / 16;
+            f32x4 *const xch = reinterpret_cast<f32x4 *>(lds) + (wave * MB * NB * 4) * 64 + lane;
+            if (team > 0) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            xch[team * TEAM_F4 + ((mb * NB + nb) * 4 + c) * 64] =
+                                f32x4{acc[mb][nb][4 * c], acc[mb][nb][4 * c + 1], acc[mb][nb][4 * c + 2], acc[mb][nb][4 * c + 3]};
+            }
+            __syncthreads();
+            if (team > 0) return;
+            for (int tm = 1; tm < Cfg::TEAMS; ++tm)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const f32x4 o = xch[tm * TEAM_F4 + ((mb * NB + nb) * 4 + c) * 64];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[mb][nb][4 * c + e] += o[e];
+                        }
+        }
         store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, bias_cur, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
         if (next >= tiles_total) break;
 #pragma unroll

@@ -26,8 +26,7 @@ struct KernelInfo {
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
-    int variant = 0;  // bf16 channel-vector kernels: 2 for two teams of four wavefronts per workgroup (512 threads),
-                      // each on half of the steps
+    int variant = 0;  // 2: `threads` / 256 teams of four wavefronts per workgroup, each on its share of the steps
     bool f64 = false; // double precision in and out (alpha64 / beta64 of the parameters apply)
 };
 
@@ -38,7 +37,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.
