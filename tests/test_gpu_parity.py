@@ -101,6 +101,9 @@ def test_every_kernel_variant():
             ]
             if "x72 " in name:   # steps of eight channels
                 problems = [(n_, 8 * ((c_ + 7) // 8), h_, w_, k_, r_, s_, pd, st) for (n_, c_, h_, w_, k_, r_, s_, pd, st) in problems]
+        if "teams" in name:   # long reductions: several steps per team, a ragged last step, a team left without steps
+            problems = problems + ([(2, 40, 15, 17, 150, 3, 3, (1, 1), (1, 1)), (1, 136, 9, 11, 70, 3, 3, (1, 1), (2, 1))] if taps9 else
+                                   [(2, 40, 12, 9, 70, 5, 3, (0, 0), (1, 2)), (1, 24, 20, 21, 130, 7, 7, (0, 0), (1, 1)), (2, 8, 9, 9, 40, 3, 3, (0, 0), (1, 1))])
         if "table short" in name:   # an even number of steps, the last one at most half full
             problems = [
                 (3, 5, 15, 17, 150, 3, 3, (0, 0), (1, 1)),        # C*R*S = 45: 2 steps, 13 in the last
