@@ -146,11 +146,11 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
 // partial wave as many tile-times as its fullest compute unit holds workgroups.
 // Workgroups of a kernel a compute unit holds at a time: by LDS (160 KB), and by registers (as compiled:
 // at most 512 / (VGPRs + AGPRs) waves per SIMD) two of the kernels with steps of 32 or more - four of the
-// unpadded 64 x 64 x 32 ones (112 registers) -, three or (tiles up to 64 x 128) four of those with steps
+// 64 x 64 x 32 ones (unpadded forward, backward filter by tap: 112 registers) -, three or (tiles up to 64 x 128) four of those with steps
 // of 16.  More workgroups per compute unit cover more of each other's waits: Table-2 layer 3 gained 4 %.
 static int workgroups_per_cu(const KernelInfo &ki) {
-    const bool small_nopad = ki.gmode == 2 && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
-    const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_nopad ? 4 : 2);
+    const bool small_tile = (ki.gmode == 2 || (ki.gmode == 8 && !ki.bf16)) && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
+    const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_tile ? 4 : 2);
     return std::max(1, std::min(by_regs, (160 * 1024) / ki.ldsBytes));
 }
 
@@ -658,10 +658,12 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
 }
 
 // How to cut the reduction: as many ranges as keep all (tile, range) workgroups resident at
-// once (two per compute unit) - one more would leave a second, nearly empty round -, ranges
+// once (two per compute unit, four of the small fp32 tiles) - one more would leave a second, nearly empty round -, ranges
 // of an even number of steps and not shorter than 8; at most max_parts ranges.
 static void backward_filter_split(const BackwardFilterProblem &b, long long max_parts, int *splits, int *steps_per_split) {
-    long long want = std::max<long long>(1, (2 * kComputeUnits) / b.tiles);
+    const KernelInfo *ki = kernel_info(b.kernel_id);
+    const long long per_cu = ki && !ki->f64 && ki->gmode != 10 ? workgroups_per_cu(*ki) : 2;
+    long long want = std::max<long long>(1, (per_cu * kComputeUnits) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));
     long long per = (b.ksteps + want - 1) / want;

@@ -271,10 +271,12 @@ struct KernelConfig {
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
     static constexpr int TABLE_BYTES =
         GMODE_ == GATHER_NOPAD_TABLE || GMODE_ == GATHER_NOPAD_TABLE_SHORT || GMODE_ == GATHER_NOPAD_TABLE_ODD ? kOffsetTableEntries * 4 : 0;
-    // Steps of 16 leave room (LDS, registers) for three workgroups per compute unit.
-    static constexpr int MIN_WAVES = TEAMS_ > 1 ? TEAMS_ : (BK_ == 16 ? 3 : 1);
     static constexpr int TEAM_LDS_BYTES = 2 * (A_ELEMS + B_ELEMS) * ESIZE;
     static constexpr int LDS_BYTES = TEAMS_ * TEAM_LDS_BYTES + TABLE_BYTES;
+    // Waves per SIMD the registers must allow: steps of 16 leave room (LDS, registers) for three workgroups per
+    // compute unit; where LDS lets two share it the registers must too - left alone, the kernels with the
+    // largest tiles take more than half of a SIMD's 512 and run one wave per SIMD.
+    static constexpr int MIN_WAVES = TEAMS_ > 1 ? TEAMS_ : (BK_ == 16 ? 3 : (LDS_BYTES <= 80 * 1024 ? 2 : 1));
     static constexpr int TM = BM / WM, TN = BN / WN; // per-wave output block
     static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
     static constexpr int CG = BN / 64;               // column groups of 64 lanes
