@@ -29,14 +29,39 @@ IGC_DEFINE_GROUP(kGroupWgrad)
 namespace igc {
 
 // out[e] = alpha * (part_0[e] + part_1[e] + ...) + beta * out[e], parts `stride` floats apart.
-// The parts are added in order, so the result does not depend on how the work was spread.
+// The order of the additions is fixed by `count` alone, so the result does not depend on how the
+// work was spread: the parts are cut into eight consecutive runs, a workgroup of 256 threads takes
+// 32 elements and gives each run to 32 of its threads (which add the run's parts in order, four
+// loads in flight), and the eight sums are added in order through LDS.  (One thread per element
+// adding all parts kept one load in flight per thread, on a fraction of the chip: 112 parts of
+// 147 KB took 28 us.)
 __global__ __launch_bounds__(256) void igconv_sum_parts_kernel(const float *parts, float *out, uint32_t n, int count,
                                                                uint32_t stride, float alpha, float beta) {
-    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
-    if (e >= n) return;
+    __shared__ float runs[8][32];
+    const uint32_t el = threadIdx.x & 31u, g = threadIdx.x >> 5;
+    const uint32_t e = blockIdx.x * 32u + el;
+    const int per = (count + 7) / 8, s0 = (int)g * per, s1 = min(count, s0 + per);
     float acc = 0.f;
-    for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + e];
-    float r = alpha * acc;
+    if (e < n) {
+        const float *src = parts + e;
+        int s = s0;
+        for (; s + 4 <= s1; s += 4) {
+            const float a = src[(size_t)s * stride], b = src[(size_t)(s + 1) * stride], c = src[(size_t)(s + 2) * stride],
+                        d = src[(size_t)(s + 3) * stride];
+            acc += a;
+            acc += b;
+            acc += c;
+            acc += d;
+        }
+        for (; s < s1; ++s) acc += src[(size_t)s * stride];
+    }
+    runs[g][el] = acc;
+    __syncthreads();
+    if (g != 0 || e >= n) return;
+    float sum = runs[0][el];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) sum += runs[k][el];
+    float r = alpha * sum;
     if (beta != 0.f) r += beta * out[e];
     out[e] = r;
 }
@@ -44,7 +69,7 @@ __global__ __launch_bounds__(256) void igconv_sum_parts_kernel(const float *part
 int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
                      void *stream) {
     void *argv[] = {&parts, &out, &n, &count, &stride, &alpha, &beta};
-    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_parts_kernel), dim3((n + 255u) / 256u),
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_parts_kernel), dim3((n + 31u) / 32u),
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
