@@ -24,7 +24,7 @@ static int launch_wgc(const ConvKernelParams &p, int grid, void *stream) {
 // (channel 8 cv + ch of a tile of B channels sits at position ch*(B/8) + cv; parts are KP x CP positions per tap).
 // One thread per (row position, column position), lanes along the column positions: every tap's read is a
 // contiguous run per wavefront, and a thread writes the R*S taps of its (k, c), contiguous in dw.
-__global__ __launch_bounds__(256) void igconv_sum_positions_kernel(const float *parts, float *out, uint32_t n, int count,
+__global__ __launch_bounds__(256) void igconv_sum_positions_kernel(const float *__restrict__ parts, float *__restrict__ out, uint32_t n, int count,
                                                                    uint32_t stride, float alpha, float beta, int C, int RS,
                                                                    int BM, int BN, int KP, int CP) {
     const uint32_t e = blockIdx.x * 256u + threadIdx.x;
@@ -36,7 +36,28 @@ __global__ __launch_bounds__(256) void igconv_sum_positions_kernel(const float *
     const uint32_t c = col - cl + (cl % nvb) * 8u + cl / nvb;
     if (c >= (uint32_t)C || (size_t)(k * (uint32_t)C + c) * RS >= n) return;
     float *dst = out + (size_t)(k * (uint32_t)C + c) * RS;
-    for (int t = 0; t < RS; ++t) {
+    // (three taps at a time: their loads are requested together; the parts of a tap are added in order)
+    int t = 0;
+    for (; t + 3 <= RS; t += 3) {
+        const float *s0 = parts + ((size_t)t * KP + row) * CP + col, *s1 = s0 + (size_t)KP * CP, *s2 = s1 + (size_t)KP * CP;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f;
+        for (int s = 0; s < count; ++s) {
+            const float v0 = s0[(size_t)s * stride], v1 = s1[(size_t)s * stride], v2 = s2[(size_t)s * stride];
+            a0 += v0;
+            a1 += v1;
+            a2 += v2;
+        }
+        float r0 = alpha * a0, r1 = alpha * a1, r2 = alpha * a2;
+        if (beta != 0.f) {
+            r0 += beta * dst[t];
+            r1 += beta * dst[t + 1];
+            r2 += beta * dst[t + 2];
+        }
+        dst[t] = r0;
+        dst[t + 1] = r1;
+        dst[t + 2] = r2;
+    }
+    for (; t < RS; ++t) {
         const size_t src = ((size_t)t * KP + row) * CP + col;
         float acc = 0.f;
         for (int s = 0; s < count; ++s) acc += parts[(size_t)s * stride + src];
