@@ -81,13 +81,18 @@ __global__ __launch_bounds__(256) void igconv_filter_exchange_kernel(const uint1
     __shared__ uint16_t blk[16 * 16 * taps];
     const int k0 = blockIdx.x * 16, c0 = blockIdx.y * 16;
     const int run = 16 * taps, total = 16 * run;
-    for (int e = threadIdx.x; e < total; e += 256) {
+    // (total = 256 * taps: every thread moves `taps` elements, all requested before the first is written to LDS)
+    uint16_t v[taps];
+#pragma unroll
+    for (int i = 0; i < taps; ++i) {
+        const int e = (int)threadIdx.x + 256 * i;
         const int k = e / run, rem = e - k * run;     // rem = c_local * taps + t
         const int c = rem / taps;
-        uint16_t v = 0;
-        if (k0 + k < K && c0 + c < C) v = w[((size_t)(k0 + k) * C + c0) * taps + rem];
-        blk[e] = v;
+        v[i] = 0;
+        if (k0 + k < K && c0 + c < C) v[i] = w[((size_t)(k0 + k) * C + c0) * taps + rem];
     }
+#pragma unroll
+    for (int i = 0; i < taps; ++i) blk[threadIdx.x + 256 * i] = v[i];
     __syncthreads();
     for (int e = threadIdx.x; e < total; e += 256) {
         const int c = e / run, rem = e - c * run;     // rem = k_local * taps + t
