@@ -445,7 +445,8 @@ def main():
     backward = []
     if not args.only and not args.no_backward:
         for i in (2, 3, 4, 5):
-            backward.append(run_backward(i, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0))
+            # (as for the forward pass the GPU needs tens of launches to reach steady clocks)
+            backward.append(run_backward(i, max(20, args.steps // 2), max(10, args.warmup // 2), 1.0))
         import workloads as wl
         backward.append(run_backward(None, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0, workload=wl.shrink(wl.by_index(5), 256)))
 
