@@ -215,6 +215,11 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
  * pad <= filter size - 1 and dy's channel stride 1, where it returns K*C*R*S*2 bytes: the pass is then the forward pass
  * over dy with the filter's k and c exchanged (written to the workspace, 16-byte aligned,
  * by a small kernel on the same stream) and uses the forward pass's fastest kernels.
+ * For float problems with a stride above 1 and few channels (u*v*C <= 128) it returns room for one
+ * forward pass that serves all residue classes together: the filter of that pass
+ * (u*v*C x K x ceil(R/u) x ceil(S/v) floats, rounded up to 256 bytes) followed by its result
+ * (N x u*v*C x (P + ceil(R/u) - 1) x (Q + ceil(S/v) - 1) floats); a first layer's three channels then
+ * fill the tiles of one launch instead of a sliver of the tiles of u*v launches.
  *
  *  - w (device, read): packed K,C,R,S.  dy (device, read): laid out by dyDesc, dimensions
  *    (N, K, P, Q) with P, Q = eq. 1 of dxDesc's H, W.  dx (device, written; read only when

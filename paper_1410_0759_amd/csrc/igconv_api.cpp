@@ -657,6 +657,34 @@ static igcStatus validate_backward_filter(igcTensorDescriptor_t x, igcTensorDesc
     return IGC_STATUS_SUCCESS;
 }
 
+// Backward data of a strided layer with few channels as one forward pass over dy with u*v*C output maps (see
+// igconv_kernels_wgrad.hip): float only, a stride above 1, at most 128 such maps (beyond that the per-phase
+// launches fill their tiles anyway).  The workspace holds the filter of that pass, then its result.
+struct PackedPhases {
+    int Rp, Sp, I, J, maps;
+    long long filter_bytes, bytes;   // (filter_bytes: rounded up to a multiple of 256)
+};
+
+static bool packed_phases(const BackwardDataProblem &b, PackedPhases *out) {
+    if (b.bf16 || b.f64 || b.u * b.v <= 1) return false;
+    const long long maps = (long long)b.u * b.v * b.C;
+    if (maps > 128) return false;
+    PackedPhases p{};
+    p.maps = (int)maps;
+    p.Rp = (b.R + b.u - 1) / b.u;
+    p.Sp = (b.S + b.v - 1) / b.v;
+    p.I = b.P + p.Rp - 1;
+    p.J = b.Q + p.Sp - 1;
+    const long long fb = maps * b.K * p.Rp * p.Sp * 4, yb = (long long)b.N * maps * p.I * p.J * 4;
+    p.filter_bytes = (fb + 255) / 256 * 256;
+    p.bytes = p.filter_bytes + yb;
+    if (yb >= kMaxBytes || fb >= kMaxBytes || (long long)b.N * b.C * b.H * b.W >= (1ll << 32)) return false;
+    for (int d = 0; d < 4; ++d)
+        if (b.dxs[d] >= (1ll << 32)) return false;
+    *out = p;
+    return true;
+}
+
 // How to cut the reduction: as many ranges as keep all (tile, range) workgroups resident at
 // once (two per compute unit, four of the small fp32 tiles) - one more would leave a second, nearly empty round -, ranges
 // of an even number of steps and not shorter than 8; at most max_parts ranges.
@@ -1013,7 +1041,8 @@ igcStatus igcGetConvolutionBackwardDataWorkspaceSize(igcHandle_t handle, igcFilt
     const igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
     Problem pr;
-    *sizeInBytes = backward_data_as_forward(b, &pr) ? (size_t)b.w_bytes : 0;
+    PackedPhases pp;
+    *sizeInBytes = backward_data_as_forward(b, &pr) ? (size_t)b.w_bytes : (packed_phases(b, &pp) ? (size_t)pp.bytes : 0);
     return IGC_STATUS_SUCCESS;
 }
 
@@ -1048,6 +1077,45 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
             if (kernel_info(id)->launch(pr.kp, plan.gridX, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
             return IGC_STATUS_SUCCESS;
         }
+    }
+    // A strided layer with few channels and room for the packed filter and result: one forward pass over dy
+    // for all phases together, then the move of its result to dx.
+    PackedPhases pp;
+    if (workSpace && (uintptr_t)workSpace % 16 == 0 && packed_phases(b, &pp) && workSpaceSizeInBytes >= (size_t)pp.bytes) {
+        float *const fpack = static_cast<float *>(workSpace);
+        float *const ypack = reinterpret_cast<float *>(static_cast<char *>(workSpace) + pp.filter_bytes);
+        igcTensorStruct xd, yd;
+        igcFilterStruct fd;
+        igcConvolutionStruct cd;
+        xd.set = true; xd.dtype = IGC_DATA_FLOAT;
+        for (int d = 0; d < 4; ++d) { xd.dim[d] = dyDesc->dim[d]; xd.stride[d] = dyDesc->stride[d]; }
+        fd.set = true; fd.dtype = IGC_DATA_FLOAT; fd.k = pp.maps; fd.c = b.K; fd.r = pp.Rp; fd.s = pp.Sp;
+        cd.set = true; cd.pad_h = pp.Rp - 1; cd.pad_w = pp.Sp - 1; cd.u = 1; cd.v = 1; cd.mode = IGC_CROSS_CORRELATION;
+        yd.set = true; yd.dtype = IGC_DATA_FLOAT;
+        yd.dim[0] = b.N; yd.dim[1] = pp.maps; yd.dim[2] = pp.I; yd.dim[3] = pp.J;
+        yd.stride[3] = 1; yd.stride[2] = pp.J; yd.stride[1] = (long long)pp.I * pp.J; yd.stride[0] = yd.stride[1] * pp.maps;
+        Magic mSp, mRp, mK, mC, mv, mu, mW, mH;
+        if (!magic_for((uint32_t)pp.Sp, &mSp) || !magic_for((uint32_t)pp.Rp, &mRp) || !magic_for((uint32_t)b.K, &mK) ||
+            !magic_for((uint32_t)b.C, &mC) || !magic_for((uint32_t)b.v, &mv) || !magic_for((uint32_t)b.u, &mu) ||
+            !magic_for((uint32_t)b.W, &mW) || !magic_for((uint32_t)b.H, &mH))
+            return IGC_STATUS_NOT_SUPPORTED;
+        if (getenv("IGCONV_DEBUG"))
+            fprintf(stderr, "igconv: backward data of %d phases as one forward pass with %d maps, %dx%d taps\n", b.u * b.v, pp.maps, pp.Rp, pp.Sp);
+        if (launch_pack_phase_filter(static_cast<const float *>(w), fpack, b.K, b.C, b.R, b.S, b.u, b.v, pp.Rp, pp.Sp, b.flip, mSp, mRp,
+                                     mK, mC, mv, handle->stream) != 0)
+            return IGC_STATUS_EXECUTION_FAILED;
+        const float one = 1.f, zero = 0.f;
+        const int saved = handle->kernelOverride;
+        handle->kernelOverride = -1;   // (the override names a kernel for the caller's problem, not for this one)
+        st = igcConvolutionBiasActivationForward(handle, &one, &xd, dy, &fd, fpack, &cd, nullptr, 0, &zero, nullptr,
+                                                 IGC_ACTIVATION_IDENTITY, &yd, ypack);
+        handle->kernelOverride = saved;
+        if (st != IGC_STATUS_SUCCESS) return st;
+        if (launch_phase_scatter(ypack, static_cast<float *>(dx), b.N, b.C, b.H, b.W, pp.I, pp.J, b.u, b.v, b.pad_h, b.pad_w, b.dxs,
+                                 mW, mH, mC, mu, mv, *static_cast<const float *>(alpha), *static_cast<const float *>(beta),
+                                 handle->stream) != 0)
+            return IGC_STATUS_EXECUTION_FAILED;
+        return IGC_STATUS_SUCCESS;
     }
     // plan every phase before the first launch, so that a rejected problem launches nothing
     struct Launch { Problem pr; int id; int grid; };

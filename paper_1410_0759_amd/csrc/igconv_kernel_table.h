@@ -48,6 +48,15 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
 // dimensions exchanged, each pair's taps kept in order); returns the runtime's error code.
 int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream);
 
+// Backward data of a strided layer with few channels as one forward pass (see igconv_kernels_wgrad.hip): the
+// filter of that pass, f[(a*v + b)*C + c][k][Rp][Sp], and the move of its result y' (N, u*v*C, I, J, packed)
+// to dx = alpha * y'(...) + beta * dx.  The divisors are the launch-time multiply+shift forms of the named sizes.
+int launch_pack_phase_filter(const float *w, float *f, int K, int C, int R, int S, int u, int v, int Rp, int Sp, bool flip,
+                             Magic mSp, Magic mRp, Magic mK, Magic mC, Magic mv, void *stream);
+int launch_phase_scatter(const float *y, float *dx, int N, int C, int H, int W, int I, int J, int u, int v, int pad_h, int pad_w,
+                         const long long dxs[4], Magic mW, Magic mH, Magic mC, Magic mu, Magic mv, float alpha, float beta,
+                         void *stream);
+
 // The same for the channel-vector backward-filter kernels, whose parts are stored as [tap][row position][column
 // position] (KP x CP positions per tap, tiles of BM x BN): see igconv_kernel_wgrad_bf16c.hpp.
 int launch_sum_positions(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta, int C,

@@ -73,6 +73,102 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
+// ---- backward data of a strided layer with few channels, as ONE forward pass ------------------
+// Per axis the rows of dx split into u phases: with g = h + pad, a = g mod u and i = g div u, row h
+// meets exactly the taps e = a + u*t (e counted in reading direction) and those read dy row i - t.
+// All phases share the tap grid t < R' = ceil(R/u) once a missing tap (e >= R) counts as a zero
+// weight, so that
+//   y'[n, (a,b,c), i, j] = sum_{k,t,t'} W(k,c,a+u*t,b+v*t') * dy[n,k,i-t,j-t']
+// is a stride-1 forward pass over dy with u*v*C output maps and the filter below, and
+//   dx[n,c,h,w] = y'[n, (a,b,c), i, j].
+// A first layer's three channels thus fill 48 rows of the MFMA tiles instead of 3 of 32 in each of 16
+// launches.  F[m][k][tau][sigma], m = (a*v + b)*C + c, holds W(k, c, a + u*(R'-1-tau), b + v*(S'-1-sigma))
+// - the forward kernels read tap tau at row i - (R'-1) + tau - or zero past the filter's end.
+struct PhaseFilterArgs {
+    const float *w;
+    float *f;
+    uint32_t total;          // elements of F
+    int K, C, R, S, u, v, Rp, Sp, flip;
+    Magic mSp, mRp, mK, mC, mv;
+};
+
+__global__ __launch_bounds__(256) void igconv_pack_phase_filter_kernel(const PhaseFilterArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.total) return;
+    auto mdiv = [](uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; };
+    uint32_t rest = mdiv(idx, a.mSp);
+    const uint32_t sigma = idx - rest * (uint32_t)a.Sp;
+    uint32_t q = mdiv(rest, a.mRp);
+    const uint32_t tau = rest - q * (uint32_t)a.Rp;
+    rest = q;
+    q = mdiv(rest, a.mK);
+    const uint32_t k = rest - q * (uint32_t)a.K;
+    const uint32_t m = q;
+    const uint32_t ab = mdiv(m, a.mC), c = m - ab * (uint32_t)a.C;
+    const uint32_t pa = mdiv(ab, a.mv), pb = ab - pa * (uint32_t)a.v;
+    const int e = (int)pa + a.u * (a.Rp - 1 - (int)tau), f = (int)pb + a.v * (a.Sp - 1 - (int)sigma);
+    float val = 0.f;
+    if (e < a.R && f < a.S) {
+        const int r = a.flip ? a.R - 1 - e : e, sx = a.flip ? a.S - 1 - f : f;
+        val = a.w[(((size_t)k * a.C + c) * a.R + r) * a.S + sx];
+    }
+    a.f[idx] = val;
+}
+
+int launch_pack_phase_filter(const float *w, float *f, int K, int C, int R, int S, int u, int v, int Rp, int Sp, bool flip,
+                             Magic mSp, Magic mRp, Magic mK, Magic mC, Magic mv, void *stream) {
+    PhaseFilterArgs a{w, f, (uint32_t)((size_t)u * v * C * K * Rp * Sp), K, C, R, S, u, v, Rp, Sp, flip ? 1 : 0, mSp, mRp, mK, mC, mv};
+    void *argv[] = {&a};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_pack_phase_filter_kernel),
+                                            dim3((a.total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+}
+
+// dx[n,c,h,w] = alpha * y'[n,(a,b,c),i,j] + beta * dx[n,c,h,w] (y' packed N, u*v*C, I, J; rows i >= I or columns
+// j >= J belong to input rows no window reaches: zero).  A thread per element of dx, w fastest.
+struct PhaseScatterArgs {
+    const float *y;
+    float *dx;
+    uint32_t total;          // N*C*H*W
+    int C, H, W, I, J, u, v, pad_h, pad_w;
+    uint32_t dxs[4];         // strides of dx in elements
+    Magic mW, mH, mC, mu, mv;
+    float alpha, beta;
+};
+
+__global__ __launch_bounds__(256) void igconv_phase_scatter_kernel(const PhaseScatterArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.total) return;
+    auto mdiv = [](uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; };
+    uint32_t rest = mdiv(idx, a.mW);
+    const uint32_t w = idx - rest * (uint32_t)a.W;
+    uint32_t q = mdiv(rest, a.mH);
+    const uint32_t h = rest - q * (uint32_t)a.H;
+    const uint32_t n = mdiv(q, a.mC), c = q - n * (uint32_t)a.C;
+    const uint32_t gh = h + (uint32_t)a.pad_h, gw = w + (uint32_t)a.pad_w;
+    const uint32_t i = mdiv(gh, a.mu), pa = gh - i * (uint32_t)a.u;
+    const uint32_t j = mdiv(gw, a.mv), pb = gw - j * (uint32_t)a.v;
+    float val = 0.f;
+    if (i < (uint32_t)a.I && j < (uint32_t)a.J) {
+        const uint32_t m = (pa * (uint32_t)a.v + pb) * (uint32_t)a.C + c;
+        const uint32_t maps = (uint32_t)(a.u * a.v * a.C);
+        val = a.y[(((size_t)n * maps + m) * a.I + i) * a.J + j];
+    }
+    float *dst = a.dx + (size_t)n * a.dxs[0] + (size_t)c * a.dxs[1] + (size_t)h * a.dxs[2] + (size_t)w * a.dxs[3];
+    float r = a.alpha * val;
+    if (a.beta != 0.f) r += a.beta * *dst;
+    *dst = r;
+}
+
+int launch_phase_scatter(const float *y, float *dx, int N, int C, int H, int W, int I, int J, int u, int v, int pad_h, int pad_w,
+                         const long long dxs[4], Magic mW, Magic mH, Magic mC, Magic mu, Magic mv, float alpha, float beta,
+                         void *stream) {
+    PhaseScatterArgs a{y, dx, (uint32_t)((size_t)N * C * H * W), C, H, W, I, J, u, v, pad_h, pad_w,
+                       {(uint32_t)dxs[0], (uint32_t)dxs[1], (uint32_t)dxs[2], (uint32_t)dxs[3]}, mW, mH, mC, mu, mv, alpha, beta};
+    void *argv[] = {&a};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_phase_scatter_kernel),
+                                            dim3((a.total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+}
+
 // wt[c][k][t] = w[k][c][t] for 2-byte elements (t: the taps of one (k,c) pair, kept in order):
 // a workgroup moves a block of 16 k x 16 c through LDS so that both sides are read and
 // written in runs of 16*taps elements.  Host guarantees sizes below 2^31.

@@ -78,6 +78,37 @@ def test_backward_data_accumulates():
         _check_bd(prob, "f32", 0, alpha=2.0, beta=1.0, dx_layout="NHWC")
 
 
+# float, a stride above 1 and few channels: with the workspace it asks for the library runs all phases as one
+# forward pass over dy (u*v*C output maps) and moves the result to dx; without, one launch per phase.
+# N, C, H, W, K, R, S, pad, stride
+BWD_PACKED_PHASES = [
+    (2, 3, 35, 33, 8, 11, 11, (0, 0), (4, 4)),      # the first-layer shape: 16 phases, 3x3 taps each
+    (2, 3, 37, 34, 8, 11, 11, (0, 0), (4, 4)),      # rows and columns no window reaches
+    (2, 3, 19, 18, 5, 3, 3, (1, 1), (2, 1)),        # one axis strided
+    (1, 4, 20, 21, 6, 5, 4, (2, 1), (3, 2)),        # unequal everything, padded
+    (2, 8, 17, 16, 7, 2, 2, (0, 0), (2, 2)),        # windows that do not overlap
+    (1, 2, 13, 14, 4, 2, 2, (0, 0), (3, 3)),        # stride above the filter size: phases without taps
+    (1, 3, 23, 22, 4, 7, 7, (6, 6), (2, 2)),        # "full" padding
+    (3, 32, 12, 12, 9, 3, 3, (1, 1), (2, 2)),       # 128 maps: the most the route takes
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
+def test_backward_data_strided_few_channels_both_routes(mode):
+    for i, prob in enumerate(BWD_PACKED_PHASES):
+        asked = []
+        _check_bd(prob, "f32", mode, seed=40 + i, asked=asked)
+        assert asked[0] > 0, "this problem should ask for the workspace of the one-pass route"
+        _check_bd(prob, "f32", mode, seed=40 + i, workspace="none")
+        _check_bd(prob, "f32", mode, seed=40 + i, workspace=asked[0] - 4)      # too small: the general route
+    _check_bd(BWD_PACKED_PHASES[1], "f32", mode, alpha=0.5, beta=-1.5, dx_layout="NHWC", dy_layout="NHWC")
+    _check_bd(BWD_PACKED_PHASES[3], "f32", mode, alpha=2.0, beta=1.0)
+    # many channels: the per-phase launches fill their tiles, no workspace is asked for
+    asked = []
+    _check_bd((2, 40, 12, 12, 9, 3, 3, (1, 1), (2, 2)), "f32", mode, asked=asked)
+    assert asked[0] == 0
+
+
 # bf16, unit stride, nine taps, dy with contiguous channels (K a multiple of 16): the library asks
 # for room for the filter with k and c exchanged and runs the forward pass's channel-vector
 # kernels over dy.  N, C, H, W, K, R, S, pad, stride

@@ -196,7 +196,14 @@ def test_backward_passes_validate_before_any_gpu_call():
     without a GPU (fake device pointers; a rejected call launches nothing)."""
     h = ig.Handle()
     x, w, c, y = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 1))
-    assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 0
+    # float, a stride above 1 and few channels (u*v*C <= 128 output maps): room for the filter of the one forward
+    # pass that serves all phases (6 maps x K x 2 x 3 taps, rounded up to 256 bytes) and for its result
+    # (N x 6 maps x (P + 1) x (Q + 2)); unit strides or many channels: none
+    assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 768 + 2 * 6 * 6 * 10 * 4
+    x1, w1, c1, y1 = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(1, 1))
+    assert ig.get_backward_data_workspace_size(h, w1, y1, c1, x1) == 0
+    x2, w2, c2, y2 = _descs(N=2, C=40, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 2))
+    assert ig.get_backward_data_workspace_size(h, w2, y2, c2, x2) == 0
     # bf16, unit stride, nine taps, K in sixteens, dy with unit channel stride: room for the
     # filter with k and c exchanged; any of these conditions missing: none
     def bd_ws(K=32, stride=(1, 1), dt=ig.IGC_DATA_BFLOAT16, nhwc=True, R=3, S=3, pad=(1, 1)):
