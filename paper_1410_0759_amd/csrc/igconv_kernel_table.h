@@ -48,6 +48,10 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
 // dimensions exchanged, each pair's taps kept in order); returns the runtime's error code.
 int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream);
 
+// wt[k][t][c] = w[k][c][t] for float elements (t < RS), or with `exchange` wt[c][t][k]: the filter as the tap-major
+// kernels like to read it in the forward pass resp. in backward data.  mInner: the divisor C resp. K.
+int launch_filter_taps_outer(const float *w, float *wt, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS, void *stream);
+
 // Backward data of a strided layer with few channels as one forward pass (see igconv_kernels_wgrad.hip): the
 // filter of that pass, f[(a*v + b)*C + c][k][Rp][Sp], and the move of its result y' (N, u*v*C, I, J, packed)
 // to dx = alpha * y'(...) + beta * dx.  The divisors are the launch-time multiply+shift forms of the named sizes.

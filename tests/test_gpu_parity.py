@@ -385,6 +385,42 @@ def test_fused_bias_and_activation():
 
 
 # ------------------------------------------------------------------ optional workspace (small problems)
+@pytest.mark.gpu
+def test_forward_tap_major_with_filter_workspace():
+    """A float problem that runs in tap-major order (padded, not nine taps, enough channels and plenty of tiles):
+    the optional workspace is the filter's size, the filter is rewritten there with the channel index innermost and
+    read through those strides.  Same sums in the same order: the same bits as without the workspace."""
+    import paper_1410_0759_amd as ig
+    gu = _gpu()
+    cases = [
+        # N, C, H, W, K, R, S, pad, stride, mode
+        (64, 64, 20, 20, 70, 5, 5, (2, 2), (1, 1), 1),
+        (64, 80, 21, 19, 150, 7, 3, (3, 1), (2, 1), 0),     # ragged last channel chunk, eq. 2 order
+        (48, 96, 27, 27, 64, 5, 5, (2, 2), (1, 1), 1),
+    ]
+    for i, (N, C, H, W, K, R, S, pad, stride, mode) in enumerate(cases):
+        x, w = wl.random_problem(120 + i, N, C, H, W, K, R, S)
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)
+        g = gu.GpuConv(x, w, pad, stride, mode)
+        assert g.plan().gatherMode == 1
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        plain = g.result()
+        asked = g.lend_workspace()
+        assert asked == K * C * R * S * 4
+        print("tap-major with filter workspace", cases[i], flush=True)
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        got = g.result()
+        g.ws.result()                                   # guard bands of the workspace
+        assert gu.rel_err(got, want) <= gu.TOL["f32"]
+        assert np.array_equal(got, plain)
+        g.lend_workspace(asked - 4)                      # too small: the filter is read in place
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        assert np.array_equal(g.result(), plain)
+
+
 def test_forward_with_optional_workspace():
     """Few output tiles and a long reduction: with a lent workspace the reduction is cut into
     ranges and summed in order.  Same result as without (to rounding), bitwise repeatable, any

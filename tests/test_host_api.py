@@ -115,6 +115,10 @@ def test_optional_forward_workspace_is_only_asked_for_where_cutting_the_reductio
         d = _descs(w_.N, w_.C, w_.H, w_.W, w_.K, w_.R, w_.S, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, 0,
                    xs=nchw(w_.N, w_.C, w_.H, w_.W), ys=nchw(w_.N, w_.K, w_.P, w_.Q))
         assert ig.get_optional_workspace_size(h, *d) == 0
+    # a float problem in tap-major order with plenty of tiles: room for the filter with the channel index innermost
+    big = _descs(N=64, C=64, H=20, W=20, K=70, R=5, S=5, pad=(2, 2))
+    assert ig.get_plan(h, *big).gatherMode == 1
+    assert ig.get_optional_workspace_size(h, *big) == 70 * 64 * 25 * 4 and ig.get_workspace_size(h, *big) == 0
     # a short reduction is never cut; neither is an output with gaps between its elements
     assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3)) == 0
     gaps = _descs(N=2, C=128, H=17, W=17, K=128, R=7, S=7, pad=(0, 0), ys=(128 * 11 * 12, 11 * 12, 12, 1))
@@ -202,8 +206,9 @@ def test_backward_passes_validate_before_any_gpu_call():
     assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 768 + 2 * 6 * 6 * 10 * 4
     x1, w1, c1, y1 = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(1, 1))
     assert ig.get_backward_data_workspace_size(h, w1, y1, c1, x1) == 0
+    # many channels: one launch per phase, in tap-major order: room for the filter with the reduction index innermost
     x2, w2, c2, y2 = _descs(N=2, C=40, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 2))
-    assert ig.get_backward_data_workspace_size(h, w2, y2, c2, x2) == 0
+    assert ig.get_backward_data_workspace_size(h, w2, y2, c2, x2) == 4 * 40 * 9 * 4
     # bf16, unit stride, nine taps, K in sixteens, dy with unit channel stride: room for the
     # filter with k and c exchanged; any of these conditions missing: none
     def bd_ws(K=32, stride=(1, 1), dt=ig.IGC_DATA_BFLOAT16, nhwc=True, R=3, S=3, pad=(1, 1)):
@@ -215,7 +220,9 @@ def test_backward_passes_validate_before_any_gpu_call():
     assert bd_ws() == 32 * 5 * 9 * 2
     assert bd_ws(pad=(0, 2)) == 32 * 5 * 9 * 2
     assert bd_ws(R=1, S=9, pad=(0, 4)) == 32 * 5 * 9 * 2
-    assert bd_ws(K=24) == 0 and bd_ws(stride=(1, 2)) == 0 and bd_ws(dt=ig.IGC_DATA_FLOAT) == 0
+    assert bd_ws(K=24) == 0 and bd_ws(stride=(1, 2)) == 0
+    # (float: nothing, or - should the planner run it in tap-major order - the filter's size in floats)
+    assert bd_ws(dt=ig.IGC_DATA_FLOAT) in (0, 32 * 5 * 9 * 4)
     assert bd_ws(nhwc=False) == 0 and bd_ws(R=5, S=5, pad=(2, 2)) == 0
     K, C, R, S = 4, 3, 3, 3
     ws = ig.get_backward_filter_workspace_size(h, x, y, c, w)
