@@ -186,6 +186,51 @@ def run_double_precision(steps, warmup, index=3):
     return out
 
 
+def run_padded_filters(steps, warmup):
+    """Layers outside the paper's collection whose filters are neither nine taps nor unpadded (a 5x5 and a 7x7
+    layer with zero borders): forward and backward data in tap-major order, without a workspace and with the
+    optional one of the filter's size (the filter rewritten with the reduction's channel index innermost).
+    Parity on the first image against the oracle."""
+    import numpy as np
+    import workloads as wl
+    from oracle import conv_oracle as oc
+    from tests import gpu_util as gu
+    import paper_1410_0759_amd as ig
+
+    out = []
+    for (N, C, H, W, K, R, S, pad) in ((128, 96, 27, 27, 256, 5, 5, (2, 2)), (128, 64, 56, 56, 64, 7, 7, (3, 3))):
+        x, w = wl.random_problem(700 + R, N, C, H, W, K, R, S)
+        flops = 2.0 * N * K * H * W * C * R * S
+        entry = {"shape": "N%d C%d %dx%d K%d %dx%d pad %d" % (N, C, H, W, K, R, S, pad[0]), "gflop": flops / 1e9}
+        g = gu.GpuConv(x, w, pad, (1, 1), 1)
+        entry["kernel"] = ig.kernel_names()[g.plan().kernelId]
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        entry["rel_err"] = gu.rel_err(g.result()[:1], oc.conv_forward(x[:1], w, pad=pad, stride=(1, 1), mode=1))
+        ms = time_gpu(g, 1.0, 0.0, steps, warmup)
+        entry["forward"] = {"ms": ms, "tflops": flops / ms / 1e9}
+        entry["workspace_bytes"] = g.lend_workspace()
+        ms = time_gpu(g, 1.0, 0.0, steps, warmup)
+        entry["forward_with_workspace"] = {"ms": ms, "tflops": flops / ms / 1e9}
+        del g
+        dy = np.random.default_rng(710 + R).uniform(-1, 1, size=(N, K, H, W)).astype(np.float32)
+
+        class _Timed:
+            def __init__(self, g):
+                self.g = g
+
+            def launch(self, alpha, beta):
+                self.g.launch(alpha, beta)
+
+        for ws, key in (("none", "backward_data"), ("full", "backward_data_with_workspace")):
+            g = gu.GpuBackwardData(dy, w, (H, W), pad, (1, 1), 1, "f32", "NCHW", ws)
+            ms = time_gpu(_Timed(g), 1.0, 0.0, steps, warmup)
+            entry[key] = {"ms": ms, "tflops": flops / ms / 1e9}
+            del g
+        out.append(entry)
+    return out
+
+
 def run_other_functions(steps, warmup):
     """The bandwidth-bound functions (activations, bias addition, softmax, pooling) on
     layer-sized float tensors: time per call, algorithmic bytes (each tensor once) per second
@@ -450,6 +495,10 @@ def main():
         import workloads as wl
         backward.append(run_backward(None, max(20, args.steps // 5), max(10, args.warmup // 5), 1.0, workload=wl.shrink(wl.by_index(5), 256)))
 
+    padded = []
+    if not args.only and not args.no_backward and not args.no_table2:
+        padded = run_padded_filters(max(10, args.steps // 10), max(10, args.warmup // 5))
+
     other = []
     double_precision = None
     if not args.only and not args.no_other:
@@ -504,6 +553,7 @@ def main():
         "table2_layers": table2,
         "table2_batch_sweep": batch_sweep,
         "backward": backward,
+        "padded_filter_layers": padded,
         "other_functions": other,
         "double_precision": double_precision,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
