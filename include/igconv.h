@@ -163,7 +163,11 @@ igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle,
  * filter's size, K*C*R*S*4 bytes, and with a workspace of that size (16-byte aligned) the
  * filter is first rewritten there with the channel index innermost, which makes a step's
  * filter reads contiguous; the sums and their order, hence the result's bits, are the same as
- * without the workspace (a smaller one is ignored). */
+ * without the workspace (a smaller one is ignored).
+ * A third use, for float problems with a zero border and so few channels that the library would test
+ * every gathered element against the window (the generic gather): the query reports the size of x
+ * with its border written out, N*C*(H+2*pad_h)*(W+2*pad_w)*4 bytes; with such a workspace (16-byte
+ * aligned) that copy is made first and the pass runs over it as a problem without a border. */
 igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle,
                                                         igcTensorDescriptor_t xDesc,
                                                         igcFilterDescriptor_t wDesc,

@@ -366,12 +366,12 @@ def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, con
 
 
 def convolution_bias_activation_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, bias_ptr, activation,
-                                        ydesc, y_ptr):
+                                        ydesc, y_ptr, ws_ptr=0, ws_bytes=0):
     """igcConvolutionBiasActivationForward; bias_ptr 0 for no bias, activation -1 for none."""
     a, b = _scalars(ydesc, alpha, beta)
     return lib().igcConvolutionBiasActivationForward(
-        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr, None, 0, ctypes.byref(b),
-        _vp(bias_ptr), activation, ydesc.ptr, _vp(y_ptr))
+        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), wdesc.ptr, _vp(w_ptr), conv.ptr, _vp(ws_ptr) if ws_ptr else None,
+        ws_bytes, ctypes.byref(b), _vp(bias_ptr), activation, ydesc.ptr, _vp(y_ptr))
 
 
 def kernel_names():

@@ -289,6 +289,19 @@ static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
 }
 
+// A float problem with a zero border that would run with the generic gather (few channels: every gathered element
+// is tested against the window): over a copy of x with the border written out the same layer has no border and
+// runs with its tap offsets tabulated.  Bytes of that copy, 0 when this does not apply.
+static long long padded_copy_bytes(const KernelInfo &ki, const Problem &pr, igcTensorDescriptor_t xDesc) {
+    const ConvKernelParams &k = pr.kp;
+    if (ki.gmode != 0 || pr.bf16 || pr.f64 || (k.pad_h == 0 && k.pad_w == 0)) return 0;
+    const long long bytes = (long long)k.N * k.C * (k.H + 2 * k.pad_h) * (k.W + 2 * k.pad_w) * 4;
+    if (bytes >= kMaxBytes) return 0;
+    for (int d = 0; d < 4; ++d)
+        if (xDesc->stride[d] < 0 || xDesc->stride[d] >= (1ll << 32)) return 0;
+    return bytes;
+}
+
 // Forward pass on a problem with few tiles: with a workspace the reduction can be cut into
 // ranges as in the backward-filter pass (partial results summed in order afterwards), which
 // puts idle compute units to work.  Returns the number of ranges (1: do not cut) and the
@@ -934,6 +947,8 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcT
     *sizeInBytes = splits > 1 ? (size_t)splits * pr.kp.y_bytes : 0;
     // a float problem that runs in tap-major order: room for the filter with the channel index innermost
     if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.bf16 && !pr.f64 && pr.kp.RS > 1) *sizeInBytes = (size_t)pr.kp.w_bytes;
+    // few channels and a zero border: room for x with the border written out
+    if (splits <= 1 && padded_copy_bytes(*kernel_info(id), pr, xDesc) > 0) *sizeInBytes = (size_t)padded_copy_bytes(*kernel_info(id), pr, xDesc);
     return IGC_STATUS_SUCCESS;
 }
 
@@ -1058,6 +1073,32 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
             k.y = workSpace;
             k.alpha = 1.f;
             k.beta = 0.f;
+        }
+    }
+    // Few channels, a zero border and room for x with the border written out: the copy is made and the pass runs
+    // over it as a problem without a border (alpha, beta, bias and activation unchanged).
+    {
+        const long long pb = splits <= 1 ? padded_copy_bytes(*kernel_info(id), pr, xDesc) : 0;
+        if (pb > 0 && handle->kernelOverride < 0 && workSpace && (uintptr_t)workSpace % 16 == 0 && workSpaceSizeInBytes >= (size_t)pb) {
+            const ConvKernelParams &k = pr.kp;
+            igcTensorStruct xd;
+            igcConvolutionStruct cd;
+            xd.set = true; xd.dtype = IGC_DATA_FLOAT;
+            xd.dim[0] = k.N; xd.dim[1] = k.C; xd.dim[2] = k.H + 2 * k.pad_h; xd.dim[3] = k.W + 2 * k.pad_w;
+            xd.stride[3] = 1; xd.stride[2] = xd.dim[3]; xd.stride[1] = (long long)xd.dim[2] * xd.dim[3]; xd.stride[0] = xd.stride[1] * k.C;
+            cd.set = true; cd.pad_h = 0; cd.pad_w = 0; cd.u = k.u; cd.v = k.v; cd.mode = convDesc->mode;
+            Magic mWp, mHp, mC;
+            if (magic_for((uint32_t)xd.dim[3], &mWp) && magic_for((uint32_t)xd.dim[2], &mHp) && magic_for((uint32_t)k.C, &mC)) {
+                if (launch_pad_image(static_cast<const float *>(x), static_cast<float *>(workSpace), k.N, k.C, k.H, k.W, k.pad_h, k.pad_w,
+                                     xDesc->stride, mWp, mHp, mC, handle->stream) != 0)
+                    return IGC_STATUS_EXECUTION_FAILED;
+                const int saved = handle->kernelOverride;
+                handle->kernelOverride = -1;
+                st = igcConvolutionBiasActivationForward(handle, alpha, &xd, workSpace, wDesc, w, &cd, nullptr, 0, beta, bias, activation,
+                                                         yDesc, y);
+                handle->kernelOverride = saved;
+                return st;
+            }
         }
     }
     // Tap-major order with a lent workspace of the filter's size: the filter is first rewritten with the channel

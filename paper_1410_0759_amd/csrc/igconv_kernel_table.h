@@ -52,6 +52,10 @@ int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void
 // kernels like to read it in the forward pass resp. in backward data.  mInner: the divisor C resp. K.
 int launch_filter_taps_outer(const float *w, float *wt, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS, void *stream);
 
+// xp = x with its zero border written out, packed N,C,H+2pad_h,W+2pad_w (float; x read through the strides xs).
+int launch_pad_image(const float *x, float *xp, int N, int C, int H, int W, int pad_h, int pad_w, const long long xs[4], Magic mWp,
+                     Magic mHp, Magic mC, void *stream);
+
 // Backward data of a strided layer with few channels as one forward pass (see igconv_kernels_wgrad.hip): the
 // filter of that pass, f[(a*v + b)*C + c][k][Rp][Sp], and the move of its result y' (N, u*v*C, I, J, packed)
 // to dx = alpha * y'(...) + beta * dx.  The divisors are the launch-time multiply+shift forms of the named sizes.

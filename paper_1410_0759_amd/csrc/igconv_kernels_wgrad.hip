@@ -96,6 +96,43 @@ int launch_filter_taps_outer(const float *w, float *wt, int K, int C, int RS, bo
                                             dim3((total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
+// xp = x extended by its zero border, packed N,C,H+2pad_h,W+2pad_w (float).  With few channels and a zero border
+// the forward pass has to test every gathered element against the window (the generic gather); over xp the same
+// layer has no border and runs with the tap offsets tabulated.  A thread per element of xp.
+struct PadImageArgs {
+    const float *x;
+    float *xp;
+    uint32_t total;
+    int H, W, Hp, Wp, pad_h, pad_w, C;
+    uint32_t xs[4];
+    Magic mWp, mHp, mC;
+};
+
+__global__ __launch_bounds__(256) void igconv_pad_image_kernel(const PadImageArgs a) {
+    const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= a.total) return;
+    auto mdiv = [](uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; };
+    uint32_t rest = mdiv(idx, a.mWp);
+    const uint32_t wp = idx - rest * (uint32_t)a.Wp;
+    uint32_t q = mdiv(rest, a.mHp);
+    const uint32_t hp = rest - q * (uint32_t)a.Hp;
+    const uint32_t n = mdiv(q, a.mC), c = q - n * (uint32_t)a.C;
+    const uint32_t h = hp - (uint32_t)a.pad_h, w = wp - (uint32_t)a.pad_w;   // (wrap below zero: fail the test)
+    float v = 0.f;
+    if (h < (uint32_t)a.H && w < (uint32_t)a.W) v = a.x[(size_t)n * a.xs[0] + (size_t)c * a.xs[1] + (size_t)h * a.xs[2] + (size_t)w * a.xs[3]];
+    a.xp[idx] = v;
+}
+
+int launch_pad_image(const float *x, float *xp, int N, int C, int H, int W, int pad_h, int pad_w, const long long xs[4], Magic mWp,
+                     Magic mHp, Magic mC, void *stream) {
+    const int Hp = H + 2 * pad_h, Wp = W + 2 * pad_w;
+    PadImageArgs a{x, xp, (uint32_t)((size_t)N * C * Hp * Wp), H, W, Hp, Wp, pad_h, pad_w, C,
+                   {(uint32_t)xs[0], (uint32_t)xs[1], (uint32_t)xs[2], (uint32_t)xs[3]}, mWp, mHp, mC};
+    void *argv[] = {&a};
+    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_pad_image_kernel), dim3((a.total + 255u) / 256u),
+                                            dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+}
+
 // ---- backward data of a strided layer with few channels, as ONE forward pass ------------------
 // Per axis the rows of dx split into u phases: with g = h + pad, a = g mod u and i = g div u, row h
 // meets exactly the taps e = a + u*t (e counted in reading direction) and those read dy row i - t.

@@ -113,9 +113,11 @@ class GpuConv:
         """y = f(alpha*conv + beta*y + bias[k]); bias a float32 vector of K values or None."""
         self.handle.set_stream(torch.cuda.current_stream().cuda_stream)
         self.bias_dev = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
+        ws = getattr(self, "ws", None)
         st = ig.convolution_bias_activation_forward(
             self.handle, alpha, self.xdesc, self.x_dev.data_ptr(), self.wdesc, self.w_dev.data_ptr(), self.conv, beta,
-            0 if bias is None else self.bias_dev.data_ptr(), activation, self.ydesc, self.y_ptr)
+            0 if bias is None else self.bias_dev.data_ptr(), activation, self.ydesc, self.y_ptr,
+            ws.ptr if ws is not None else 0, self.ws_bytes if ws is not None else 0)
         ig.check(st, "igcConvolutionBiasActivationForward")
 
     def result(self):

@@ -421,6 +421,45 @@ def test_forward_tap_major_with_filter_workspace():
         assert np.array_equal(g.result(), plain)
 
 
+def test_forward_few_channels_zero_border_with_image_workspace():
+    """Few channels and a zero border: the layer runs with the generic gather, or - lent a workspace for x with its
+    border written out - as a layer without a border over that copy.  Both against the oracle, with alpha/beta,
+    bias and activation passed through, channel-fastest x, and a workspace too small (ignored)."""
+    gu = _gpu()
+    cases = [
+        # N, C, H, W, K, R, S, pad, stride, mode, x layout
+        (8, 3, 40, 38, 64, 7, 7, (3, 3), (2, 2), 1, "NCHW"),
+        (4, 3, 33, 35, 24, 3, 3, (1, 1), (1, 1), 0, "NHWC"),
+        (6, 1, 28, 28, 20, 5, 5, (2, 1), (1, 2), 1, "NCHW"),
+    ]
+    for i, (N, C, H, W, K, R, S, pad, stride, mode, xl) in enumerate(cases):
+        x, w = wl.random_problem(140 + i, N, C, H, W, K, R, S)
+        xg = wl.with_layout(x, xl)
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)
+        y0 = np.random.default_rng(150 + i).uniform(-1, 1, size=want.shape).astype(np.float32)
+        want2 = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode, alpha=0.5, beta=-1.5, y_old=y0)
+        g = gu.GpuConv(xg, w, pad, stride, mode)
+        assert g.plan().gatherMode == 0
+        asked = g.lend_workspace()
+        assert asked == N * C * (H + 2 * pad[0]) * (W + 2 * pad[1]) * 4
+        print("image workspace", cases[i], flush=True)
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        assert gu.rel_err(g.result(), want) <= gu.TOL["f32"]
+        g.ws.result()                                   # guard bands of the workspace
+        g.prefill(y0=y0)
+        g.launch(0.5, -1.5)
+        assert gu.rel_err(g.result(), want2) <= gu.TOL["f32"]
+        bias = np.random.default_rng(160 + i).uniform(-1, 1, size=K).astype(np.float32)
+        g.prefill(value=float("nan"))
+        g.launch_fused(1.0, 0.0, bias, 1)
+        assert gu.rel_err(g.result(), np.maximum(want + bias[None, :, None, None], 0.0)) <= gu.TOL["f32"]
+        g.lend_workspace(asked - 4)
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        assert gu.rel_err(g.result(), want) <= gu.TOL["f32"]
+
+
 def test_forward_with_optional_workspace():
     """Few output tiles and a long reduction: with a lent workspace the reduction is cut into
     ranges and summed in order.  Same result as without (to rounding), bitwise repeatable, any

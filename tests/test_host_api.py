@@ -120,7 +120,9 @@ def test_optional_forward_workspace_is_only_asked_for_where_cutting_the_reductio
     assert ig.get_plan(h, *big).gatherMode == 1
     assert ig.get_optional_workspace_size(h, *big) == 70 * 64 * 25 * 4 and ig.get_workspace_size(h, *big) == 0
     # a short reduction is never cut; neither is an output with gaps between its elements
-    assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3)) == 0
+    assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3, pad=(0, 0))) == 0
+    # few channels and a zero border (the generic gather): room for x with the border written out
+    assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3)) == 2 * 3 * 19 * 19 * 4
     gaps = _descs(N=2, C=128, H=17, W=17, K=128, R=7, S=7, pad=(0, 0), ys=(128 * 11 * 12, 11 * 12, 12, 1))
     assert ig.get_optional_workspace_size(h, *gaps) == 0
 
