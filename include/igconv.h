@@ -158,9 +158,9 @@ igcStatus igcGetConvolutionForwardWorkspaceSize(igcHandle_t handle,
  * cutting would not help or does not apply (y with gaps between its elements, the bf16
  * channel-vector kernels).  Any smaller size passed to igcConvolutionForward is fine
  * (fewer ranges, or none).
- * A second use, for float problems the library runs in tap-major order (zero borders, a filter
- * other than 1x1 or nine taps, enough channels) when no cut is chosen: the query reports the
- * filter's size, K*C*R*S*4 bytes, and with a workspace of that size (16-byte aligned) the
+ * A second use, for float or bfloat16 problems the library runs in tap-major order (zero borders, a
+ * filter other than 1x1 or nine taps, enough channels) when no cut is chosen: the query reports the
+ * filter's size in bytes, and with a workspace of that size (16-byte aligned) the
  * filter is first rewritten there with the channel index innermost, which makes a step's
  * filter reads contiguous; the sums and their order, hence the result's bits, are the same as
  * without the workspace (a smaller one is ignored).
@@ -230,8 +230,8 @@ igcStatus igcConvolutionForward(igcHandle_t handle, const void *alpha,
  * (u*v*C x K x ceil(R/u) x ceil(S/v) floats, rounded up to 256 bytes) followed by its result
  * (N x u*v*C x (P + ceil(R/u) - 1) x (Q + ceil(S/v) - 1) floats); a first layer's three channels then
  * fill the tiles of one launch instead of a sliver of the tiles of u*v launches.
- * For other float problems whose launches all run in tap-major order (filters other than nine taps or
- * 1x1 with enough channels) it returns the filter's size, K*C*R*S*4 bytes: the filter is then first
+ * For other float or bfloat16 problems whose launches all run in tap-major order (filters other than nine
+ * taps or 1x1 with enough channels) it returns the filter's size in bytes: the filter is then first
  * rewritten with the reduction index innermost (wt[c][r][s][k]), which makes the filter reads of a
  * step contiguous; same sums in the same order, hence the same bits as without the workspace.
  *

@@ -694,10 +694,10 @@ static igcStatus plan_backward_data_phases(const igcContext *handle, const Backw
     return IGC_STATUS_SUCCESS;
 }
 
-// Float phases that all run in tap-major order (and have something to reduce): their filter reads, elements
+// Float or bfloat16 phases that all run in tap-major order (and have something to reduce): their filter reads, elements
 // C*R*S apart, become contiguous with the filter rewritten as wt[c][t][k] in a workspace of the filter's size.
 static bool phases_want_filter_workspace(const BackwardDataProblem &b, const std::vector<PhaseLaunch> &launches) {
-    if (b.bf16 || b.f64 || launches.empty() || b.K < 2) return false;
+    if (b.f64 || launches.empty() || b.K < 2) return false;
     for (const PhaseLaunch &l : launches)
         if (kernel_info(l.id)->gmode != 1) return false;
     return true;
@@ -946,7 +946,7 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcT
     const int splits = pr.f64 ? 1 : forward_split(*kernel_info(id), pr.kp, packed, 1 << 20, &per);
     *sizeInBytes = splits > 1 ? (size_t)splits * pr.kp.y_bytes : 0;
     // a float problem that runs in tap-major order: room for the filter with the channel index innermost
-    if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.bf16 && !pr.f64 && pr.kp.RS > 1) *sizeInBytes = (size_t)pr.kp.w_bytes;
+    if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.f64 && pr.kp.RS > 1) *sizeInBytes = (size_t)pr.kp.w_bytes;
     // few channels and a zero border: room for x with the border written out
     if (splits <= 1 && padded_copy_bytes(*kernel_info(id), pr, xDesc) > 0) *sizeInBytes = (size_t)padded_copy_bytes(*kernel_info(id), pr, xDesc);
     return IGC_STATUS_SUCCESS;
@@ -1104,13 +1104,12 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     // Tap-major order with a lent workspace of the filter's size: the filter is first rewritten with the channel
     // index innermost (wt[k][t][c]) and read through those strides - a step's filter elements are then contiguous
     // instead of R*S apart (a 5x5 layer with 96 channels: 74 -> 129 TFLOP/s).  Same sums in the same order.
-    if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.bf16 && !pr.f64 && pr.kp.RS > 1 && workSpace &&
+    if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.f64 && pr.kp.RS > 1 && workSpace &&
         (uintptr_t)workSpace % 16 == 0 && workSpaceSizeInBytes >= (size_t)pr.kp.w_bytes) {
         ConvKernelParams &k = pr.kp;
         Magic mC, mRS;
         if (magic_for((uint32_t)k.C, &mC) && magic_for((uint32_t)k.RS, &mRS)) {
-            if (launch_filter_taps_outer(static_cast<const float *>(w), static_cast<float *>(workSpace), k.K, k.C, k.RS, false, mC, mRS,
-                                         handle->stream) != 0)
+            if (launch_filter_taps_outer(w, workSpace, pr.bf16 ? 2 : 4, k.K, k.C, k.RS, false, mC, mRS, handle->stream) != 0)
                 return IGC_STATUS_EXECUTION_FAILED;
             k.w = workSpace;
             k.wsRow = k.CRS; k.wsRed = 1; k.wTap0 = 0; k.wsTapR = k.S * k.C; k.wsTapS = k.C;
@@ -1236,8 +1235,7 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
     if (phases_want_filter_workspace(b, launches) && workSpace && (uintptr_t)workSpace % 16 == 0 && workSpaceSizeInBytes >= (size_t)b.w_bytes) {
         Magic mK, mRS;
         if (magic_for((uint32_t)b.K, &mK) && magic_for((uint32_t)(b.R * b.S), &mRS)) {
-            if (launch_filter_taps_outer(static_cast<const float *>(w), static_cast<float *>(workSpace), b.K, b.C, b.R * b.S, true, mK,
-                                         mRS, handle->stream) != 0)
+            if (launch_filter_taps_outer(w, workSpace, b.bf16 ? 2 : 4, b.K, b.C, b.R * b.S, true, mK, mRS, handle->stream) != 0)
                 return IGC_STATUS_EXECUTION_FAILED;
             for (PhaseLaunch &l : launches) {
                 ConvKernelParams &k = l.pr.kp;

@@ -48,9 +48,10 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
 // dimensions exchanged, each pair's taps kept in order); returns the runtime's error code.
 int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream);
 
-// wt[k][t][c] = w[k][c][t] for float elements (t < RS), or with `exchange` wt[c][t][k]: the filter as the tap-major
-// kernels like to read it in the forward pass resp. in backward data.  mInner: the divisor C resp. K.
-int launch_filter_taps_outer(const float *w, float *wt, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS, void *stream);
+// wt[k][t][c] = w[k][c][t] for elements of 4 or 2 bytes (t < RS), or with `exchange` wt[c][t][k]: the filter as the
+// tap-major kernels like to read it in the forward pass resp. in backward data.  mInner: the divisor C resp. K.
+int launch_filter_taps_outer(const void *w, void *wt, int elem_bytes, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS,
+                             void *stream);
 
 // xp = x with its zero border written out, packed N,C,H+2pad_h,W+2pad_w (float; x read through the strides xs).
 int launch_pad_image(const float *x, float *xp, int N, int C, int H, int W, int pad_h, int pad_w, const long long xs[4], Magic mWp,

@@ -73,11 +73,12 @@ int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
-// wt[k][t][c] = w[k][c][t] (float; t < RS): the filter with the channel index innermost, so that the tap-major
+// wt[k][t][c] = w[k][c][t] (float or bfloat16; t < RS): the filter with the channel index innermost, so that the tap-major
 // kernels, whose step is one tap of a run of channels, read contiguous runs of a filter row instead of elements
 // RS apart.  With `exchange` the roles of k and c are exchanged as well, wt[c][t][k] = w[k][c][t]: the same for
 // backward data, whose rows are c and whose reduction runs over k.  A thread per element, writes contiguous.
-__global__ __launch_bounds__(256) void igconv_filter_taps_outer_kernel(const float *w, float *wt, uint32_t total, int K, int C, int RS,
+template <class T>
+__global__ __launch_bounds__(256) void igconv_filter_taps_outer_kernel(const T *w, T *wt, uint32_t total, int K, int C, int RS,
                                                                        int exchange, Magic mInner, Magic mRS) {
     const uint32_t idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
@@ -88,12 +89,14 @@ __global__ __launch_bounds__(256) void igconv_filter_taps_outer_kernel(const flo
     wt[idx] = w[((size_t)k * C + c) * RS + t];
 }
 
-int launch_filter_taps_outer(const float *w, float *wt, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS, void *stream) {
+int launch_filter_taps_outer(const void *w, void *wt, int elem_bytes, int K, int C, int RS, bool exchange, Magic mInner, Magic mRS,
+                             void *stream) {
     uint32_t total = (uint32_t)((size_t)K * C * RS);
     int ex = exchange ? 1 : 0;
     void *argv[] = {&w, &wt, &total, &K, &C, &RS, &ex, &mInner, &mRS};
-    return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_filter_taps_outer_kernel),
-                                            dim3((total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
+    const void *kernel = elem_bytes == 2 ? reinterpret_cast<const void *>(&igconv_filter_taps_outer_kernel<uint16_t>)
+                                         : reinterpret_cast<const void *>(&igconv_filter_taps_outer_kernel<float>);
+    return static_cast<int>(hipLaunchKernel(kernel, dim3((total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
 }
 
 // xp = x extended by its zero border, packed N,C,H+2pad_h,W+2pad_w (float).  With few channels and a zero border

@@ -162,8 +162,8 @@ def test_backward_data_bf16_channel_vectors(prob, mode):
     asked = []
     _check_bd(prob, "bf16", mode, dy_layout="NCHW", seed=7, asked=asked)
     _check_bd(prob, "f32", mode, dy_layout="NHWC", seed=7, asked=asked)
-    # (float: nothing, or the filter's size should its phases run in tap-major order)
-    assert asked[0] == 0 and asked[1] in (0, K * C * R * S * 4)
+    # (nothing, or the filter's size should the general route's launches run in tap-major order)
+    assert asked[0] in (0, K * C * R * S * 2) and asked[1] in (0, K * C * R * S * 4)
 
 
 def test_backward_data_is_the_transpose_of_forward_on_the_gpu():

@@ -398,22 +398,23 @@ def test_forward_tap_major_with_filter_workspace():
         (64, 80, 21, 19, 150, 7, 3, (3, 1), (2, 1), 0),     # ragged last channel chunk, eq. 2 order
         (48, 96, 27, 27, 64, 5, 5, (2, 2), (1, 1), 1),
     ]
-    for i, (N, C, H, W, K, R, S, pad, stride, mode) in enumerate(cases):
-        x, w = wl.random_problem(120 + i, N, C, H, W, K, R, S)
+    for i, (N, C, H, W, K, R, S, pad, stride, mode) in enumerate(cases + cases[:2]):
+        dtype = "f32" if i < len(cases) else "bf16"     # (the first two again with bfloat16 inputs)
+        x, w = wl.random_problem(120 + i, N, C, H, W, K, R, S, dtype=dtype)
         want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)
-        g = gu.GpuConv(x, w, pad, stride, mode)
+        g = gu.GpuConv(x, w, pad, stride, mode, dtype=dtype)
         assert g.plan().gatherMode == 1
         g.prefill(value=float("nan"))
         g.launch(1.0, 0.0)
         plain = g.result()
         asked = g.lend_workspace()
-        assert asked == K * C * R * S * 4
-        print("tap-major with filter workspace", cases[i], flush=True)
+        assert asked == K * C * R * S * (4 if dtype == "f32" else 2)
+        print("tap-major with filter workspace", (N, C, H, W, K, R, S, pad, stride, mode), dtype, flush=True)
         g.prefill(value=float("nan"))
         g.launch(1.0, 0.0)
         got = g.result()
         g.ws.result()                                   # guard bands of the workspace
-        assert gu.rel_err(got, want) <= gu.TOL["f32"]
+        assert gu.rel_err(got, want) <= gu.TOL[dtype]
         assert np.array_equal(got, plain)
         g.lend_workspace(asked - 4)                      # too small: the filter is read in place
         g.prefill(value=float("nan"))

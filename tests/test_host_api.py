@@ -222,10 +222,11 @@ def test_backward_passes_validate_before_any_gpu_call():
     assert bd_ws() == 32 * 5 * 9 * 2
     assert bd_ws(pad=(0, 2)) == 32 * 5 * 9 * 2
     assert bd_ws(R=1, S=9, pad=(0, 4)) == 32 * 5 * 9 * 2
-    assert bd_ws(K=24) == 0 and bd_ws(stride=(1, 2)) == 0
+    # (not that route; the general route asks for nothing, or - launches in tap-major order - for the filter's size again)
+    assert bd_ws(K=24) in (0, 24 * 5 * 9 * 2) and bd_ws(stride=(1, 2)) in (0, 32 * 5 * 9 * 2)
     # (float: nothing, or - should the planner run it in tap-major order - the filter's size in floats)
     assert bd_ws(dt=ig.IGC_DATA_FLOAT) in (0, 32 * 5 * 9 * 4)
-    assert bd_ws(nhwc=False) == 0 and bd_ws(R=5, S=5, pad=(2, 2)) == 0
+    assert bd_ws(nhwc=False) in (0, 32 * 5 * 9 * 2) and bd_ws(R=5, S=5, pad=(2, 2)) in (0, 32 * 5 * 25 * 2)
     K, C, R, S = 4, 3, 3, 3
     ws = ig.get_backward_filter_workspace_size(h, x, y, c, w)
     assert ws % (K * C * R * S * 4) == 0
