@@ -1097,7 +1097,8 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
                 st = igcConvolutionBiasActivationForward(handle, alpha, &xd, workSpace, wDesc, w, &cd, nullptr, 0, beta, bias, activation,
                                                          yDesc, y);
                 handle->kernelOverride = saved;
-                return st;
+                // (a refusal comes from the checks before any launch on y: the pass below still runs as planned)
+                if (st != IGC_STATUS_NOT_SUPPORTED) return st;
             }
         }
     }
@@ -1193,7 +1194,7 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
         if (!magic_for((uint32_t)pp.Sp, &mSp) || !magic_for((uint32_t)pp.Rp, &mRp) || !magic_for((uint32_t)b.K, &mK) ||
             !magic_for((uint32_t)b.C, &mC) || !magic_for((uint32_t)b.v, &mv) || !magic_for((uint32_t)b.u, &mu) ||
             !magic_for((uint32_t)b.W, &mW) || !magic_for((uint32_t)b.H, &mH))
-            return IGC_STATUS_NOT_SUPPORTED;
+            goto per_phase;
         if (getenv("IGCONV_DEBUG"))
             fprintf(stderr, "igconv: backward data of %d phases as one forward pass with %d maps, %dx%d taps\n", b.u * b.v, pp.maps, pp.Rp, pp.Sp);
         if (launch_pack_phase_filter(static_cast<const float *>(w), fpack, b.K, b.C, b.R, b.S, b.u, b.v, pp.Rp, pp.Sp, b.flip, mSp, mRp,
@@ -1205,6 +1206,8 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
         st = igcConvolutionBiasActivationForward(handle, &one, &xd, dy, &fd, fpack, &cd, nullptr, 0, &zero, nullptr,
                                                  IGC_ACTIVATION_IDENTITY, &yd, ypack);
         handle->kernelOverride = saved;
+        // (a refusal comes from the checks before any launch: nothing of dx is written yet, the phases run one by one)
+        if (st == IGC_STATUS_NOT_SUPPORTED) goto per_phase;
         if (st != IGC_STATUS_SUCCESS) return st;
         if (launch_phase_scatter(ypack, static_cast<float *>(dx), b.N, b.C, b.H, b.W, pp.I, pp.J, b.u, b.v, b.pad_h, b.pad_w, b.dxs,
                                  mW, mH, mC, mu, mv, *static_cast<const float *>(alpha), *static_cast<const float *>(beta),
@@ -1212,6 +1215,7 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
             return IGC_STATUS_EXECUTION_FAILED;
         return IGC_STATUS_SUCCESS;
     }
+per_phase:
     // plan every phase before the first launch, so that a rejected problem launches nothing
     std::vector<PhaseLaunch> launches;
     st = plan_backward_data_phases(handle, b, &launches);
