@@ -420,6 +420,7 @@ def main():
     ap.add_argument("--no-other", action="store_true", help="skip the section on activations, softmax, pooling, bias addition")
     ap.add_argument("--other-only", action="store_true", help="time only that section")
     ap.add_argument("--f64-only", action="store_true", help="time only the double-precision section")
+    ap.add_argument("--table2-only", action="store_true", help="time only the paper's Table-2 layer collection")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -457,6 +458,11 @@ def main():
 
     if args.f64_only:
         print(json.dumps([run_double_precision(max(20, args.steps // 10), max(10, args.warmup // 5), i) for i in (3, 4)]))
+        return
+
+    if args.table2_only:
+        import workloads as wl
+        print(json.dumps([run_config(None, args.steps, args.warmup, 1.0, workload=w_) for w_ in wl.TABLE2_LAYERS]))
         return
 
     head = run_config(args.config, args.steps, args.warmup, args.oracle_seconds, args.kernel)
