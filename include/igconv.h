@@ -454,6 +454,18 @@ igcStatus igcSetKernelOverride(igcHandle_t handle, int kernelId);
 igcStatus igcMagicDivisor(unsigned int d, unsigned int *mul, unsigned int *shift);
 unsigned int igcMagicDivide(unsigned int n, unsigned int mul, unsigned int shift);
 
+/* ---- measurement aids (bench and test tier; nothing on the hot path calls them) -----
+ * igcGetDeviceProperties: compute units and engine clock (kHz) of the current device as
+ * the runtime reports them (EXECUTION_FAILED without a GPU).
+ * igcMeasureMatrixRate: runs a register-only loop of the matrix instruction the kernels of
+ * that data type use (fp32 32x32x2, bf16 32x32x16, fp64 16x16x4; no memory traffic, two
+ * wavefronts per SIMD on every compute unit) for about `milliseconds` on the handle's
+ * stream, WAITS for it, and returns the rate in TFLOP/s: the arithmetic ceiling at the
+ * clocks the chip sustains, to be read beside the datasheet peak.  Allocates nothing on
+ * the device.  BAD_PARAM: null pointer, unknown type, milliseconds outside 1..2000. */
+igcStatus igcGetDeviceProperties(igcHandle_t handle, int *computeUnits, int *clockKHz);
+igcStatus igcMeasureMatrixRate(igcHandle_t handle, igcDataType dataType, int milliseconds, double *tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@ __all__ = [
     "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
+    "get_device_properties", "measure_matrix_rate",
 ]
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -94,6 +95,8 @@ DECLARED_SYMBOLS = {
     "igcSetKernelOverride": (_i, [_vp, _i]),
     "igcMagicDivisor": (_i, [ctypes.c_uint, _P(ctypes.c_uint), _P(ctypes.c_uint)]),
     "igcMagicDivide": (ctypes.c_uint, [ctypes.c_uint, ctypes.c_uint, ctypes.c_uint]),
+    "igcGetDeviceProperties": (_i, [_vp, _P(_i), _P(_i)]),
+    "igcMeasureMatrixRate": (_i, [_vp, _i, _i, _P(ctypes.c_double)]),
 }
 
 _lib = None
@@ -377,6 +380,20 @@ def convolution_bias_activation_forward(handle, alpha, xdesc, x_ptr, wdesc, w_pt
 def kernel_names():
     L = lib()
     return [L.igcGetKernelName(i).decode() for i in range(L.igcGetKernelCount())]
+
+
+def get_device_properties(handle):
+    """(compute units, engine clock in kHz) of the current device."""
+    cus, khz = _i(), _i()
+    check(lib().igcGetDeviceProperties(handle.ptr, ctypes.byref(cus), ctypes.byref(khz)), "igcGetDeviceProperties")
+    return cus.value, khz.value
+
+
+def measure_matrix_rate(handle, dtype, milliseconds=50):
+    """TFLOP/s of a register-only loop of the data type's matrix instruction (waits for the GPU)."""
+    out = ctypes.c_double()
+    check(lib().igcMeasureMatrixRate(handle.ptr, dtype, milliseconds, ctypes.byref(out)), "igcMeasureMatrixRate")
+    return out.value
 
 
 def magic_divisor(d):

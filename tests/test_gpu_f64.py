@@ -54,7 +54,7 @@ def _close(got, want):
     gu = _gpu()
     assert got.shape == want.shape and np.all(np.isfinite(got))
     err = gu.rel_err(got, want)
-    assert err <= gu.TOL["f64"], "rel err %.3g" % err
+    assert err <= gu.BOUND["f64"], "rel err %.3g" % err
 
 
 @pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
