@@ -21,26 +21,25 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6, "f64": 78.6}   # MI355X dense matrix peaks (256 CUs x 2.4 GHz)
 # acceptance bars of the parity measure max|gpu - oracle| / max|oracle|
 TOL = {"f32": 2e-5, "bf16": 1e-2, "f64": 1e-12}
-# The chip idles between the sections of this script (input generation, oracle runs) and needs a
-# few milliseconds of work to come back to its sustained clocks; a timed region of 20 launches of
-# 0.1 ms would otherwise measure the ramp.  Before every timed region the matrix pipes are kept
-# busy for this long with the library's register-only MFMA loop (untimed, no memory traffic).
-CLOCK_WARMUP_MS = 40
+# The chip idles between the sections of this script (input generation, oracle runs) and needs
+# some milliseconds of work to come back to its sustained engine and memory clocks; a timed region
+# of 20 launches of 0.1 ms would otherwise measure the ramp (measured: 127 us per launch of the
+# headline kernel right after an idle phase against 114 us from the hundredth launch on; a
+# register-only MFMA loop does not do it, the memory clocks matter too).  Before every timed
+# region the call itself is therefore repeated, untimed, for this long.
+CLOCK_WARMUP_MS = 30
 _warm = {"ms": CLOCK_WARMUP_MS}
-_warm_handle = None
 
 
-def warm_clocks():
-    global _warm_handle
-    ms = _warm["ms"]
-    if ms <= 0:
-        return
+def warm_clocks(call):
     import torch
-    import paper_1410_0759_amd as ig
-    if _warm_handle is None:
-        _warm_handle = ig.Handle()
-    _warm_handle.set_stream(torch.cuda.current_stream().cuda_stream)
-    ig.measure_matrix_rate(_warm_handle, ig.IGC_DATA_FLOAT, ms)
+    if _warm["ms"] <= 0:
+        return
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < _warm["ms"]:
+        for _ in range(10):
+            call()
+        torch.cuda.synchronize()
 
 
 def time_calls(call, steps, warmup):
@@ -49,7 +48,7 @@ def time_calls(call, steps, warmup):
     around all the calls, median and minimum from a second pass with an event after every
     call (back-to-back launches on one stream: the gap between two events is one call)."""
     import torch
-    warm_clocks()
+    warm_clocks(call)
     for _ in range(warmup):
         call()
     torch.cuda.synchronize()
@@ -524,7 +523,7 @@ def main():
                          "for the profiler's HBM byte counters)")
     ap.add_argument("--oracle-seconds", type=float, default=12.0, help="CPU budget of the headline oracle run")
     ap.add_argument("--clock-warmup-ms", type=int, default=CLOCK_WARMUP_MS,
-                    help="milliseconds of the register-only MFMA loop before every timed region (0: none)")
+                    help="milliseconds of untimed repetitions of the call before every timed region (0: none)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -625,7 +624,7 @@ def main():
     def compact(r):
         return {"workload": r["workload"], "dtype": r["dtype"], "ms": r["ms"], "median_ms": r["median_ms"], "min_ms": r["min_ms"],
                 "tflops": r["tflops"], "peak": r["peak_tflops"], "frac": r["frac_of_peak"],
-                "frac_at_median": r["gflop"] / r["median_ms"] / r["peak_tflops"] / 1e3,
+                "frac_at_median": r["gflop"] / r["median_ms"] / r["peak_tflops"],
                 "rel_err": r["rel_err"], "tolerance": r["tolerance"], "kernel": r["kernel"], "workspace_bytes": 0}
 
     roofline = {"bound": "mfma", "achieved": head["tflops"], "peak": head["peak_tflops"],
@@ -651,7 +650,7 @@ def main():
         "config": {"workload": head["workload"], "kernel": head["kernel"], "grid": head["grid"],
                    "parallelism": "single GPU", "workspace_bytes": 0, "copy_probe_mib": args.copy_probe_mib,
                    "clock_warmup_ms": args.clock_warmup_ms,
-                   "clock_warmup": "register-only MFMA loop before each timed region, untimed (the chip idles while inputs are drawn and the oracle runs)"},
+                   "clock_warmup": "the call itself repeated for that long before the warm-up steps of each timed region, untimed (the chip idles while inputs are drawn and the oracle runs)"},
         "frac_of_peak": head["frac_of_peak"], "rel_err_vs_oracle": head["rel_err"],
         "roofline": roofline,
         "cpu_baseline": {"value": head["oracle_tflops"], "unit": "TFLOP/s", "cores": head["oracle_threads"],

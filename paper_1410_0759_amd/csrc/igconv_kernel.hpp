@@ -622,10 +622,11 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             }
         } else if constexpr (GM == GATHER_TAPMAJOR) {
             vtap = tap_offset(sc_tr, sc_ts);
-            // When C is not a multiple of BK the last channel chunk is ragged: on
-            // entering it (once per tile; the chunks are the outer order) the filter
-            // offsets of the channels beyond C are replaced by the out-of-range marker.
-            if (sc_tau == p.tail_step) {
+            // When C is not a multiple of BK the last channel chunk is ragged: in its steps
+            // (the chunks are the outer order, so they are the last R*S steps; a range of a cut
+            // reduction may begin in the middle of them) the filter offsets of the channels
+            // beyond C are replaced by the out-of-range marker.  (tail_step = -1: never.)
+            if ((uint32_t)sc_tau >= (uint32_t)p.tail_step) {
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps)
                     a_voff[ps] = sc_c0 + (uint32_t)a_kk[ps] < (uint32_t)p.C ? a_voff[ps] : kOutOfRange;

@@ -212,6 +212,30 @@ def test_tapmajor_ragged_channel_chunks():
     _check(x, w, (0, 0), (1, 1), 1, "f32", kernel=names.index("f32 64x128x32 tapmajor"), tag="big neighbour")
 
 
+def test_tapmajor_ragged_channel_chunk_in_a_cut_reduction():
+    """The same when a lent workspace cuts the reduction into ranges, some of which begin inside the
+    ragged last channel chunk: C = 40 in chunks of 32 with 5x5 taps is 50 steps, the last 25 ragged.
+    The channels 40..63 a ragged chunk of filter k would touch are filter k+1's first 24: they hold
+    Inf (x is zero there, so filter 1's own outputs are NaN in the oracle too and are left out)."""
+    import paper_1410_0759_amd as ig
+    gu = _gpu()
+    names = ig.kernel_names()
+    x, w = wl.random_problem(77, 1, 40, 8, 8, 3, 5, 5)
+    w[1, :24] = np.float32(np.inf)
+    x[:, :24] = 0.0
+    want = oc.conv_forward(x, w, pad=(2, 2), stride=(1, 1), mode=1)
+    assert np.all(np.isnan(want[:, 1])) and np.all(np.isfinite(want[:, [0, 2]]))
+    for lend in (False, True):
+        g = gu.GpuConv(x, w, (2, 2), (1, 1), 1)
+        g.handle.set_kernel_override(names.index("f32 64x128x32 tapmajor"))
+        if lend:
+            assert g.lend_workspace() >= 2 * want.size * 4, "the reduction of this problem should be cut"
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        got = g.result()
+        assert gu.rel_err(got[:, [0, 2]], want[:, [0, 2]]) <= gu.BOUND["f32"], lend
+
+
 # ------------------------------------------------------------------ layouts through strides
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("x_layout,y_layout", [("NCHW", "NCHW"), ("NHWC", "NHWC"), ("NHWC", "NCHW"),
