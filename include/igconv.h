@@ -454,6 +454,26 @@ igcStatus igcSetKernelOverride(igcHandle_t handle, int kernelId);
 igcStatus igcMagicDivisor(unsigned int d, unsigned int *mul, unsigned int *shift);
 unsigned int igcMagicDivide(unsigned int n, unsigned int mul, unsigned int shift);
 
+/* ---- for callers that cannot allocate ----------------------------------------------
+ * igcConvolutionBackwardFilterNoAlloc is igcConvolutionBackwardFilter for callers that can
+ * neither allocate device memory nor lend a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments without the workspace, same
+ * results (bit for bit those of igcConvolutionBackwardFilter with the workspace its size query
+ * reports).  The partial results of the cut reduction go to a scratch array of
+ * IGC_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds one copy until the process ends); the call allocates and frees nothing.
+ * NOT_SUPPORTED (and a line on stderr) when the problem's workspace size exceeds the array:
+ * use igcConvolutionBackwardFilter with a workspace then.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race; calls
+ * on one stream are ordered and safe.  Nothing is kept in the array between calls. */
+#define IGC_NOALLOC_SCRATCH_BYTES (32u << 20)
+igcStatus igcConvolutionBackwardFilterNoAlloc(igcHandle_t handle, const void *alpha,
+                                              igcTensorDescriptor_t xDesc, const void *x,
+                                              igcTensorDescriptor_t dyDesc, const void *dy,
+                                              igcConvolutionDescriptor_t convDesc,
+                                              const void *beta,
+                                              igcFilterDescriptor_t dwDesc, void *dw);
+
 /* ---- measurement aids (bench and test tier; nothing on the hot path calls them) -----
  * igcGetDeviceProperties: compute units and engine clock (kHz) of the current device as
  * the runtime reports them (EXECUTION_FAILED without a GPU).

@@ -22,7 +22,7 @@ __all__ = [
     "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
-    "get_device_properties", "measure_matrix_rate",
+    "get_device_properties", "measure_matrix_rate", "convolution_backward_filter_no_alloc", "NOALLOC_SCRATCH_BYTES",
 ]
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -95,6 +95,7 @@ DECLARED_SYMBOLS = {
     "igcSetKernelOverride": (_i, [_vp, _i]),
     "igcMagicDivisor": (_i, [ctypes.c_uint, _P(ctypes.c_uint), _P(ctypes.c_uint)]),
     "igcMagicDivide": (ctypes.c_uint, [ctypes.c_uint, ctypes.c_uint, ctypes.c_uint]),
+    "igcConvolutionBackwardFilterNoAlloc": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcGetDeviceProperties": (_i, [_vp, _P(_i), _P(_i)]),
     "igcMeasureMatrixRate": (_i, [_vp, _i, _i, _P(ctypes.c_double)]),
 }
@@ -366,6 +367,17 @@ def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, con
     return lib().igcConvolutionBackwardFilter(
         handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20   # IGC_NOALLOC_SCRATCH_BYTES of include/igconv.h
+
+
+def convolution_backward_filter_no_alloc(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, conv, beta, dwdesc, dw_ptr):
+    """igcConvolutionBackwardFilterNoAlloc (no workspace argument: the library's own scratch array); returns the status."""
+    a, b = _scalars(dwdesc, alpha, beta)
+    return lib().igcConvolutionBackwardFilterNoAlloc(
+        handle.ptr, ctypes.byref(a), xdesc.ptr, _vp(x_ptr), dydesc.ptr, _vp(dy_ptr), conv.ptr,
+        ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
 
 
 def convolution_bias_activation_forward(handle, alpha, xdesc, x_ptr, wdesc, w_ptr, conv, beta, bias_ptr, activation,

@@ -405,3 +405,24 @@ def test_double_precision_is_planned_and_mixed_types_are_rejected():
     wf = ig.FilterDescriptor().set(F, 70, 5, 3, 3)
     with pytest.raises(ig.IgcError):
         ig.get_backward_filter_workspace_size(h, x, y, c, wf)
+
+
+def test_backward_filter_workspace_fits_the_no_alloc_scratch_array():
+    """igcConvolutionBackwardFilterNoAlloc serves a problem when the workspace its ordinary form asks for fits the
+    library's scratch array.  The ranges of a cut reduction are chosen so that all (tile, range) workgroups are
+    resident at once - at most 512 tiles of at most 64 KB -, so the sizes stay within the array; checked here over
+    layer shapes small and large, all three data types."""
+    h = ig.Handle()
+    worst = 0
+    for dt in (ig.IGC_DATA_FLOAT, ig.IGC_DATA_BFLOAT16, ig.IGC_DATA_DOUBLE):
+        for (N, C, H, W, K, R, pad, u) in [(64, 3, 227, 227, 96, 11, 0, 4), (128, 64, 56, 56, 64, 3, 1, 1), (128, 384, 13, 13, 256, 3, 1, 1),
+                                           (32, 512, 14, 14, 512, 3, 1, 1), (256, 512, 14, 14, 512, 3, 1, 1), (64, 128, 48, 48, 128, 1, 0, 1),
+                                           (64, 256, 28, 28, 512, 3, 1, 1), (128, 96, 27, 27, 256, 5, 2, 1), (1, 1, 5, 5, 1, 3, 0, 1),
+                                           (512, 130, 30, 30, 130, 3, 1, 1), (128, 1024, 7, 7, 1024, 1, 0, 1)]:
+            x = ig.TensorDescriptor().set(dt, N, C, H, W, (C * H * W, 1, W * C, C) if dt == ig.IGC_DATA_BFLOAT16 else (C * H * W, H * W, W, 1))
+            P = (H + 2 * pad - R) // u + 1
+            dy = ig.TensorDescriptor().set(dt, N, K, P, P, (K * P * P, 1, P * K, K) if dt == ig.IGC_DATA_BFLOAT16 else (K * P * P, P * P, P, 1))
+            dw = ig.FilterDescriptor().set(ig.IGC_DATA_DOUBLE if dt == ig.IGC_DATA_DOUBLE else ig.IGC_DATA_FLOAT, K, C, R, R)
+            conv = ig.ConvolutionDescriptor().set(pad, pad, u, u, 1)
+            worst = max(worst, ig.get_backward_filter_workspace_size(h, x, dy, conv, dw))
+    assert 0 < worst <= ig.NOALLOC_SCRATCH_BYTES, worst
