@@ -20,7 +20,6 @@ namespace igc {
 // MI355X: 256 compute units; the tile heuristic balances workgroups over them.
 constexpr int kComputeUnits = 256;
 constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-reduction unpadded kernels
-constexpr int kPatchPixels = 512;  // capacity of the patch-staging bf16 kernels (Bf16cConfig::PATCH_PIX)
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
@@ -171,6 +170,16 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
     // plus a small MFMA term; the scale makes them comparable with the line below.
     // (1x1 filters over channel vectors: loads of both operands and a small MFMA term per step of 64 channels)
     if (ki.gmode == 12) return tile_times * steps * 1000.0 * (1.0 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 64.0);
+    if (ki.gmode == 5 && ki.variant == 3) {
+        // Moving and multiplying wavefronts apart (igconv_kernel_bf16s.hpp), one workgroup per compute unit.  Two
+        // groups of multipliers (steps of 32 channels): for problems that leave compute units without a second
+        // workgroup anyway, measured 0.82 of the two-team kernel's time on such a problem.  One group on a
+        // 128 x 256 tile: measured 0.94 of the time of the 64 x 256 kernel at two workgroups per compute unit.
+        const bool two_groups = ki.BK == 288;
+        if (two_groups && tiles > kComputeUnits) return 1e300;
+        const double unit = 2.75 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 256.0;
+        return tile_times * (double)steps * 1000.0 * unit * (two_groups ? 0.92 : 1.1);
+    }
     if (ki.gmode == 4 || ki.gmode == 5) {
         // (two teams per workgroup, each on half of the steps, plus the exchange of the results: for problems
         // that leave compute units without a workgroup; with more tiles two workgroups per compute unit do the same)
@@ -242,8 +251,9 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
         if (!(x_aligned && k.RS == 9 && k.C % 16 == 0 && k.xsC == 1 && k.xsN % 8 == 0 && k.xsH % 8 == 0 &&
               k.xsW % 8 == 0))
             return false;
+        if (k.C % (ki.BK / 9) != 0) return false;   // (whole reduction steps)
         if (gmode == 5)
-            return (long long)k.N * (k.H + 2 * k.pad_h) * k.Wp < (1ll << 31) && patch_pixels_bound(k, ki.BN) <= kPatchPixels;
+            return (long long)k.N * (k.H + 2 * k.pad_h) * k.Wp < (1ll << 31) && patch_pixels_bound(k, ki.BN) <= ki.patchPixels;
     }
     return true;
 }
