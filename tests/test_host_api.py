@@ -139,7 +139,10 @@ def test_bf16_channel_vector_modes_are_offered_only_where_they_apply():
         return ig.get_plan(h, x, w, c, y)
 
     p5 = mode(32, 512, 14, 14, 512)
-    assert p5.gatherMode == 5 and p5.kSteps == 512 // 16 and p5.tileK == 144
+    # (200 tiles for 256 compute units: the kernel with two groups of multipliers, steps of 32 channels, 12 wavefronts)
+    assert p5.gatherMode == 5 and p5.kSteps == 512 // 32 and p5.tileK == 288 and p5.threads == 768 and p5.gridX == 200
+    p5 = mode(256, 512, 14, 14, 512)
+    assert p5.gatherMode == 5 and p5.kSteps == 512 // 16 and p5.tileK == 144 and (p5.tileM, p5.tileN) == (128, 256)
     assert mode(2, 32, 10, 12, 8, 1, 9, (0, 4)).gatherMode == 5          # nine taps in a row
     # a 128-column tile of a 300-pixel-wide image spans 3 rows of 302 pixels: too long for the patch
     assert mode(1, 32, 20, 300, 8).gatherMode == 4
