@@ -23,7 +23,8 @@ constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-redu
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
-                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise, &kGroupF32Teams};
+                                            &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise, &kGroupF32Teams,
+                                            &kGroupF32Masked};
 
 int kernel_count() {
     int n = 0;
@@ -200,7 +201,7 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
         const double gather2 = ki.gmode == 2 ? 29.0 : 6.0;
         return 0.8 * ((double)steps + 3.0 * teams) * (double)ki.BN * ki.BK * (ki.BM + gather2);
     }
-    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (table ? 14.0 : 6.0)));
+    const double gather = ki.gmode == 0 ? 60.0 : (ki.gmode == 1 ? 30.0 : (ki.gmode == 2 ? 29.0 : (ki.gmode == 14 ? 18.0 : (table ? 14.0 : 6.0))));
     // (mode 11 multiplies only half of its last step; mode 13 skips the step that rounds an odd count up;
     // steps of 16 with three workgroups per compute unit: measured 2.7 % faster than steps of 32 with two)
     const double eff_steps = ki.gmode == 11 ? steps - 0.5 : (ki.gmode == 13 ? steps - 1.0 : (double)steps);
@@ -236,6 +237,7 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     const int gmode = ki.gmode;
     if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
+    if (gmode == 14) return k.RS <= 63;   // (one bit of a 64-bit mask per tap, the last one spare)
     if (gmode == 7 || gmode == 11 || gmode == 13) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
         if (!(k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries)) return false;
@@ -299,12 +301,12 @@ static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
 }
 
-// A float problem with a zero border that would run with the generic gather (few channels: every gathered element
-// is tested against the window): over a copy of x with the border written out the same layer has no border and
-// runs with its tap offsets tabulated.  Bytes of that copy, 0 when this does not apply.
+// A float problem with a zero border and at most four channels (a first layer), which would run with the masked or the
+// generic gather: over a copy of x with the border written out the same layer has no border and runs with its tap
+// offsets tabulated.  Bytes of that copy, 0 when this does not apply.
 static long long padded_copy_bytes(const KernelInfo &ki, const Problem &pr, igcTensorDescriptor_t xDesc) {
     const ConvKernelParams &k = pr.kp;
-    if (ki.gmode != 0 || pr.bf16 || pr.f64 || (k.pad_h == 0 && k.pad_w == 0)) return 0;
+    if ((ki.gmode != 0 && ki.gmode != 14) || k.C > 4 || pr.bf16 || pr.f64 || (k.pad_h == 0 && k.pad_w == 0)) return 0;
     const long long bytes = (long long)k.N * k.C * (k.H + 2 * k.pad_h) * (k.W + 2 * k.pad_w) * 4;
     if (bytes >= kMaxBytes) return 0;
     for (int d = 0; d < 4; ++d)
@@ -315,7 +317,7 @@ static long long padded_copy_bytes(const KernelInfo &ki, const Problem &pr, igcT
 // Forward pass on a problem with few tiles: with a workspace the reduction can be cut into
 // ranges as in the backward-filter pass (partial results summed in order afterwards), which
 // puts idle compute units to work.  Returns the number of ranges (1: do not cut) and the
-// steps per range.  Only for kernels whose steps stand alone (modes 0-3), outputs packed
+// steps per range.  Only for kernels whose steps stand alone (modes 0-3 and 14), outputs packed
 // without gaps, and no fused epilogue; no range shorter than 8 steps.  The number of ranges
 // minimises a small model of the run time in units of one reduction step: the busiest
 // compute unit holds ceil(tiles*s/256) workgroups, which share its MFMA pipes, each taking
@@ -323,7 +325,7 @@ static long long padded_copy_bytes(const KernelInfo &ki, const Problem &pr, igcT
 // pass (about 12).  Cutting must win by a tenth, or it is not done.
 static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool packed_y, long long max_parts, int *per_out) {
     *per_out = (k.ksteps + 1) & ~1;
-    if (ki.gmode > 3 || ki.variant == 2 || !packed_y) return 1;
+    if ((ki.gmode > 3 && ki.gmode != 14) || ki.variant == 2 || !packed_y) return 1;
     const long long tiles = (long long)k.tilesM * k.tilesN;
     const long long smax = std::min<long long>(std::min<long long>(64, k.ksteps / 8), max_parts);
     const double kFixed = 6.0, kSumPass = 12.0;
@@ -354,7 +356,8 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     // the last channel chunk; filter order, the last step; none when everything divides
     k.tail_step = -1;
     if (ki.gmode == 1 && k.C % ki.BK != 0) k.tail_step = (int)((long long)(k.C / ki.BK) * k.RS);
-    if ((ki.gmode == 0 || ki.gmode == 2 || ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13) && k.CRS % ki.BK != 0) k.tail_step = k.ksteps - 1;
+    if ((ki.gmode == 0 || ki.gmode == 2 || ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13 || ki.gmode == 14) && k.CRS % ki.BK != 0)
+        k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
@@ -467,7 +470,7 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
     pr->f64 = b.f64;
     pr->vec = b.bf16 ? 8 : (b.f64 ? 2 : 4);
     // tap-major, or the nine-tap table when the phase has nine taps; double precision: its one gather
-    pr->mode_mask = b.f64 ? 1u << 0 : (1u << 1) | (1u << 3);
+    pr->mode_mask = b.f64 ? 1u << 0 : (1u << 1) | (1u << 3) | (1u << 14);
     pr->zero_steps = ah.taps == 0 || aw.taps == 0;
     ConvKernelParams &k = pr->kp;
     const int es = b.bf16 ? 2 : 4;

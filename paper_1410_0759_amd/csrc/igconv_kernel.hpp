@@ -226,6 +226,15 @@ enum GatherMode {
     // step of a tile's last pair, which would multiply zeros, does its side work only (requests
     // and LDS writes for the workgroup's next tile) and no MFMA.
     GATHER_NOPAD_TABLE_ODD = 13,
+    // i = (c,r,s) in filter order with a zero border and at most 63 taps: the tap of the next element is
+    // tracked by the scalar unit (its position in the window, its offset from the window origin and its bit
+    // number advance with every gathered element by one of three precomputed steps: scalar instructions
+    // issue beside the MFMAs), and whether it lies inside the image is one bit of a 64-bit mask per column,
+    // built once per tile.  A gathered element then costs three vector instructions (shift the mask, add
+    // the offset, merge the bit as the out-of-range marker) instead of the generic gather's seven, and none
+    // that moves data between lanes; the filter is read in its own order (contiguous rows), or, for backward
+    // data, through the row / reduction / tap strides with one decode per thread and step.
+    GATHER_MASKED = 14,
     // Backward-filter: the generic gather with the roles of the two index sets exchanged.
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
@@ -308,6 +317,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     constexpr int GM = SHORT_LAST || ODD_LAST ? (int)GATHER_NOPAD_TABLE : Cfg::GMODE;
     constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
+    constexpr bool MSK = GM == GATHER_MASKED;
+    constexpr bool MSK_STRIDED = MSK && !Cfg::VECA;   // filter through strides, one reduction index per thread
     constexpr bool WGN = GM == GATHER_WGRAD_NOPAD;
     constexpr bool WG = GM == GATHER_WGRAD || GM == GATHER_WGRAD_TAP || WGN;   // backward filter: dy as first operand
     constexpr bool WGT = GM == GATHER_WGRAD_TAP || WGN;                        // lanes along the reduction index
@@ -360,6 +371,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     const int jl = cg * 64 + lane;
     u16x2 hw0;
     uint32_t colbase_b = 0;  // byte offset of x[n, 0, p*u - pad_h, q*v - pad_w] (mod 2^32)
+    // GATHER_MASKED: bit tr*S + ts set when tap (tr, ts) of this column's window, counted in reading direction, lies
+    // outside the image; all ones for a column beyond NPQ; the bits from R*S on are always set (bit 63 serves
+    // for "no such element")
+    uint64_t inv_taps = ~0ull;
+    uint64_t ms_row_bits = 0;   // bit r*S for every window row r
+    if constexpr (GM == GATHER_MASKED)
+        for (int r = 0; r < p.R; ++r) ms_row_bits |= 1ull << (r * p.S);
     auto setup_column = [&]() {
         const int j = n0 + jl;
         const bool cv = j < p.NPQ;
@@ -375,6 +393,19 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         hw0[0] = (uint16_t)w0;
         if (!cv) {
             hw0[1] = 0x8000;           // no tap of a column beyond NPQ is ever in range
+        }
+        if constexpr (MSK) {
+            // window rows h0 .. h0+R-1: those with 0 <= h0 + t <= H-1 are valid (likewise columns)
+            const int rlo = h0 < 0 ? -h0 : 0, rhi = p.H - 1 - h0 < p.R - 1 ? p.H - 1 - h0 : p.R - 1;
+            const int clo = w0 < 0 ? -w0 : 0, chi = p.W - 1 - w0 < p.S - 1 ? p.W - 1 - w0 : p.S - 1;
+            // valid columns as a bit field of S bits, repeated for every valid row: the product with the rows'
+            // first bits (no two partial products overlap)
+            auto bits64 = [](int lo, int hi) -> uint64_t {   // bits lo..hi, none when hi < lo (0 <= lo; hi <= 63)
+                return hi >= lo ? ((~0ull >> (63 - (hi & 63))) & ~((1ull << (lo & 63)) - 1ull)) : 0ull;
+            };
+            const uint64_t cols = bits64(clo, chi);
+            const uint64_t rows = rhi >= rlo ? (ms_row_bits & bits64(rlo * p.S, rhi * p.S)) : 0ull;
+            inv_taps = cv ? ~(cols * rows) : ~0ull;
         }
     };
     u16x2 hw_max;
@@ -440,6 +471,18 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     int sc_tau = 0;
     uint32_t vtap = kOutOfRange;
     uint32_t sc_cso[GM == GATHER_TAPS9 ? KPT / 9 : 1];
+    // GATHER_MASKED: the next element of this wavefront's run - columns left in its window row and rows left in its
+    // channel (the walk follows the filter's own order r, s), byte offset from the window origin, bit number,
+    // reduction indices left after it - and the constants of the three ways to step to the one after: next
+    // column of the window; first column of the next row; first tap of the next channel.  (dir: +1, or -1 when
+    // eq. 2 inverts the filter: the window is then walked backwards.)
+    uint32_t ms_cs = 0, ms_cr = 0, ms_d = 0, ms_bit = 0, ms_left = 0;
+    const uint32_t ms_dir = p.flip ? 0xFFFFFFFFu : 1u;
+    const uint32_t ms_sm1 = (uint32_t)p.S - 1u, ms_rm1 = (uint32_t)p.R - 1u;
+    const uint32_t ms_dd0 = ms_dir * (uint32_t)p.xsW * ES;
+    const uint32_t ms_dd1 = ms_dir * ((uint32_t)p.xsH - ms_sm1 * (uint32_t)p.xsW) * ES;
+    const uint32_t ms_dd2 = ((uint32_t)p.xsC - ms_dir * (ms_sm1 * (uint32_t)p.xsW + ms_rm1 * (uint32_t)p.xsH)) * ES;
+    const uint32_t ms_db2 = 0u - ms_dir * ((uint32_t)p.RS - 1u);
     uint32_t a_jo = 0;  // backward filter: offset of this thread's reduction index in the first operand
     // GATHER_WGRAD_TAP: this thread's reduction index of a step is lane % 32; its columns are
     // BN/8 consecutive channels starting at wave*(BN/4) + (lane/32)*(BN/8) of the tile.  Per
@@ -473,7 +516,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             const uint32_t off = (uint32_t)row * (uint32_t)p.wsRow + ch * (uint32_t)p.wsRed + (uint32_t)p.wTap0 +
                                  r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS;
             a_voff[ps] = ok ? off * ES : kOutOfRange;
-        } else if constexpr (WG)
+        } else if constexpr (WG || MSK_STRIDED)
             // (rows beyond K are never stored: they may read row 0; the reduction index's part of
             // the offset, which also carries the out-of-range marker, is added per step)
             a_voff[ps] = (uint32_t)(row < p.K ? row : 0) * (uint32_t)p.wsRow * ES;
@@ -533,6 +576,22 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             wt_j = (uint32_t)(sc_tau * BK + wt_kk);
             wt_n = magic_div(wt_j, p.mRS);
             wt_rem = wt_j - wt_n * (uint32_t)p.RS;
+        } else if constexpr (MSK) {
+            // first index of this wavefront's run -> (c, r, s), all in scalar registers
+            sc_tau = __builtin_amdgcn_readfirstlane(tau);
+            const uint32_t i0 = (uint32_t)(sc_tau * BK + kpart * KPT);
+            const uint32_t c = magic_div(i0, p.mRS);
+            const uint32_t rs = i0 - c * (uint32_t)p.RS;
+            const uint32_t r = magic_div(rs, p.mS);
+            const uint32_t sx = rs - r * (uint32_t)p.S;
+            const uint32_t tr = p.flip ? ms_rm1 - r : r, ts = p.flip ? ms_sm1 - sx : sx;
+            ms_cs = ms_sm1 - sx;
+            ms_cr = ms_rm1 - r;
+            ms_d = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
+            ms_bit = tr * (uint32_t)p.S + ts;
+            // (negative, as a signed number, from the first index past the end on; a step past the last one - a
+            // backward-data phase that meets no tap runs zero steps - holds no element at all)
+            ms_left = sc_tau < p.ksteps ? (uint32_t)p.CRS - 1u - i0 : 0xFFFFFFFFu;
         } else if constexpr (GM == GATHER_NOPAD_TABLE) {
             sc_tau = __builtin_amdgcn_readfirstlane(tau);
             dec_so = so_table[sc_tau * BK + kpart * KPT + (lane < KPT ? lane : KPT - 1)];
@@ -580,6 +639,23 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             const bool ok = live && (WGN || (hh < (uint32_t)p.H && ww < (uint32_t)p.W));   // (no padding: always inside)
             wt_pix = ok ? (wt_n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * ES + (WGN ? 0u : wt_laneoff) : kOutOfRange;
             a_jo = live ? (wt_n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES : kOutOfRange;
+        } else if constexpr (MSK) {
+            if constexpr (MSK_STRIDED) {
+                // first operand: this thread's reduction index (the same in all its passes) through the
+                // reduction and tap strides
+                const uint32_t ja = (uint32_t)(sc_tau * BK + a_kk[0]);
+                const uint32_t kc = magic_div(ja, p.mRS);
+                const uint32_t rem = ja - kc * (uint32_t)p.RS;
+                const uint32_t r = magic_div(rem, p.mS);
+                const uint32_t sx = rem - r * (uint32_t)p.S;
+                a_jo = ja < (uint32_t)p.CRS && sc_tau < p.ksteps
+                           ? (kc * (uint32_t)p.wsRed + (uint32_t)p.wTap0 + r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS) * ES
+                           : kOutOfRange;
+            } else if (sc_tau == p.tail_step) {   // (ragged last step: see below)
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_voff[ps] = (uint32_t)(sc_tau * BK + a_kk[ps]) < (uint32_t)p.CRS ? a_voff[ps] : kOutOfRange;
+            }
         } else if constexpr (GM == GATHER_NOPAD_TABLE) {
             if (sc_tau == p.tail_step) {   // (see below)
 #pragma unroll
@@ -635,7 +711,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     };
     auto load_a = [&](int set, int tau, int ps) {
         uint32_t voffa = a_voff[ps], soff;
-        if constexpr (WG) {
+        if constexpr (WG || MSK_STRIDED) {
             voffa += a_jo;
             soff = 0;
         } else if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
@@ -643,7 +719,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         } else {
             // (a reduction range that ends inside the last step: masked in place by decode2)
             const uint32_t k0 = (uint32_t)tau * BK;
-            const uint32_t live = mask_lt(k0, (uint32_t)p.CRS);
+            uint32_t live = mask_lt(k0, (uint32_t)p.CRS);
+            if constexpr (MSK) live &= mask_lt((uint32_t)tau, (uint32_t)p.ksteps);
             soff = ((k0 * ES) & live) | (p.w_bytes & ~live);
         }
         if constexpr (Cfg::VECA) {
@@ -655,7 +732,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         }
     };
     // D_m tile, element e of this lane's column.
-    auto load_b = [&](int set, int e) {
+    auto load_b = [&](int set, int e) __attribute__((always_inline)) {
         uint32_t vo, so;
         if constexpr (WGN) {
             // (a dead reduction index or a column past the end carries the out-of-range marker; when
@@ -665,6 +742,13 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         } else if constexpr (WGT) {
             vo = wt_pix;
             so = sc_colso + (uint32_t)e * (uint32_t)p.xsN * ES;
+        } else if constexpr (MSK) {
+            // bit 0 of the shifted mask: 1 when the tap lies outside the image (bit 63: the index is past the end);
+            // shifted to bit 31 it puts the offset out of range (a valid offset lies below 2^31)
+            const uint32_t bit = (int32_t)ms_left < 0 ? 63u : ms_bit;
+            const uint32_t out = (uint32_t)(inv_taps >> bit);
+            vo = (out << 31) | (colbase_b + ms_d);
+            so = 0;
         } else if constexpr (GEN) {
             // lane e's decode as scalars, then the window test
             const uint32_t d = __builtin_amdgcn_readlane(dec_so, e);
@@ -689,6 +773,28 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         } else {
             b_val[set][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xbuf, vo, so, 0));
         }
+    };
+    // GATHER_MASKED: step the scalar state to the next element of the run (conditions as selects: no branch)
+    // GATHER_MASKED: step the scalar state to the next element of the run.  Ten scalar instructions chained
+    // through the carry flag (a column count that runs out borrows: the row count is decreased by that borrow,
+    // and borrows itself at the end of a channel); written out because the compiler's version of the same
+    // selects is three times as long, and what sits between two MFMAs has to fit in the time one takes.
+    auto advance_tap = [&]() __attribute__((always_inline)) {
+        uint32_t t0, t1;
+        asm volatile(
+            "s_sub_u32 %0, %0, 1\n\t"
+            "s_cselect_b32 %0, %7, %0\n\t"
+            "s_cselect_b32 %5, %10, %9\n\t"
+            "s_subb_u32 %1, %1, 0\n\t"
+            "s_cselect_b32 %1, %8, %1\n\t"
+            "s_cselect_b32 %5, %11, %5\n\t"
+            "s_cselect_b32 %6, %13, %12\n\t"
+            "s_add_u32 %2, %2, %5\n\t"
+            "s_add_u32 %3, %3, %6\n\t"
+            "s_sub_u32 %4, %4, 1"
+            : "+s"(ms_cs), "+s"(ms_cr), "+s"(ms_d), "+s"(ms_bit), "+s"(ms_left), "=&s"(t0), "=&s"(t1)
+            : "s"(ms_sm1), "s"(ms_rm1), "s"(ms_dd0), "s"(ms_dd1), "s"(ms_dd2), "s"(ms_dir), "s"(ms_db2)
+            : "scc");
     };
     auto write_a = [&](int set, int buf, int ps) {
         elem_t *const A = ldsA + buf * Cfg::A_ELEMS + a_row[ps] * LD + a_kk[ps];
@@ -731,12 +837,17 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     // loads, gathered elements) and NW LDS-write items.
     constexpr int NB_ELEMS = WGT ? WT_E : KPT;   // gathered elements per thread and step
     constexpr int NW_A = A_PASSES, NW_B = WGT ? WT_E : KPT / B_WE, NW = NW_A + NW_B;
-    constexpr int NL = 2 + A_PASSES + NB_ELEMS;
-    auto load_item = [&](int i, int set, int tau) {
+    // (GATHER_MASKED: an element is two items, its load and the step to the next one, so that neither is too long
+    // for the gap between two MFMAs)
+    constexpr int NL = 2 + A_PASSES + (MSK ? 2 : 1) * NB_ELEMS;
+    auto load_item = [&](int i, int set, int tau) __attribute__((always_inline)) {
         if (i == 0) decode1(tau);
         else if (i == 1) decode2();
         else if (i < 2 + A_PASSES) load_a(set, tau, i - 2);
-        else load_b(set, i - 2 - A_PASSES);
+        else if constexpr (MSK) {
+            if ((i - 2 - A_PASSES) % 2 == 0) load_b(set, (i - 2 - A_PASSES) / 2);
+            else advance_tap();
+        } else load_b(set, i - 2 - A_PASSES);
     };
     auto write_item = [&](int i, int set, int buf) {
         if (i < NW_A) write_a(set, buf, i);

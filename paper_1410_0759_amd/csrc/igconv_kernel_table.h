@@ -21,7 +21,8 @@ struct KernelInfo {
                     // 11 mode 7 with a last step of half the k-groups,
                     // 13 mode 7 for an odd number of steps (the step that rounds the count up is not multiplied),
                     // 12 1x1 filters over channel vectors (bf16, unit channel stride): both operands loaded as they are,
-                    // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers
+                    // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers,
+                    // 14 filter order with the tap tracked by the scalar unit and the window test in a bit mask (R*S <= 63)
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
@@ -39,7 +40,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams, kGroupF32Masked;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.

@@ -103,32 +103,33 @@ def test_backward_data_strided_few_channels_both_routes(mode):
         _check_bd(prob, "f32", mode, seed=40 + i, workspace=asked[0] - 4)      # too small: the general route
     _check_bd(BWD_PACKED_PHASES[1], "f32", mode, alpha=0.5, beta=-1.5, dx_layout="NHWC", dy_layout="NHWC")
     _check_bd(BWD_PACKED_PHASES[3], "f32", mode, alpha=2.0, beta=1.0)
-    # many channels: the per-phase launches fill their tiles; they run in tap-major order and ask for room for
-    # the filter with the reduction index innermost (next test)
+    # many channels: the per-phase launches fill their tiles; they read the filter through its strides in the
+    # reduction's own order (one decode per thread and step) and ask for nothing
     asked = []
     _check_bd((2, 40, 12, 12, 9, 3, 3, (1, 1), (2, 2)), "f32", mode, asked=asked)
-    assert asked[0] == 9 * 40 * 9 * 4
+    assert asked[0] == 0
 
 
 @pytest.mark.parametrize("mode", [0, 1], ids=["conv", "xcorr"])
 def test_backward_data_tap_major_with_filter_workspace(mode):
-    """Float phases in tap-major order (filters other than nine taps, or strided nine-tap ones whose phases have
-    fewer taps): with a workspace of the filter's size the filter is rewritten as wt[c][t][k] and read through
-    those strides.  Same sums in the same order: the same bits as without the workspace."""
+    """bfloat16 phases in tap-major order (filters other than nine taps, or strided nine-tap ones whose phases have
+    fewer taps; float problems read the filter through its strides in filter order instead): with a workspace of
+    the filter's size the filter is rewritten as wt[c][t][k] and read through those strides.  Same sums in the
+    same order: the same bits as without the workspace."""
     gu = _gpu()
     for i, prob in enumerate([(3, 40, 14, 13, 70, 5, 5, (2, 2), (1, 1)), (2, 150, 9, 11, 33, 7, 3, (3, 1), (1, 1)),
                               (2, 64, 15, 15, 48, 5, 5, (2, 2), (3, 3)), (2, 40, 12, 12, 9, 3, 3, (1, 1), (2, 2))]):
         N, C, H, W, K, R, S, pad, stride = prob
         P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
-        dy, w = _rnd(61 + i, (N, K, P, Q), "f32"), _rnd(71 + i, (K, C, R, S), "f32")
+        dy, w = _rnd(61 + i, (N, K, P, Q), "bf16"), _rnd(71 + i, (K, C, R, S), "bf16")
         want = oc.conv_backward_data(dy, w, (H, W), pad=pad, stride=stride, mode=mode)
         asked = []
         print("backward data, filter workspace", prob, mode, flush=True)
-        got = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, asked=asked)
-        assert asked[0] == K * C * R * S * 4
-        assert gu.rel_err(got, want) <= gu.BOUND["f32"]
-        assert np.array_equal(got, gu.run_backward_data(dy, w, (H, W), pad, stride, mode, workspace="none"))
-        assert np.array_equal(got, gu.run_backward_data(dy, w, (H, W), pad, stride, mode, workspace=asked[0] - 4))
+        got = gu.run_backward_data(dy, w, (H, W), pad, stride, mode, dtype="bf16", asked=asked)
+        assert asked[0] == K * C * R * S * 2
+        assert gu.rel_err(got, want) <= gu.BOUND["bf16"]
+        assert np.array_equal(got, gu.run_backward_data(dy, w, (H, W), pad, stride, mode, dtype="bf16", workspace="none"))
+        assert np.array_equal(got, gu.run_backward_data(dy, w, (H, W), pad, stride, mode, dtype="bf16", workspace=asked[0] - 4))
 
 
 # bf16, unit stride, nine taps, dy with contiguous channels (K a multiple of 16): the library asks

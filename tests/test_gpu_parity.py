@@ -158,7 +158,7 @@ def test_every_kernel_variant():
 
 def test_gather_modes_are_chosen():
     """Nine taps and channels in fours -> tap table; otherwise enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
-    filter order; few channels, padded -> generic."""
+    filter order; few channels, padded -> masked filter order (fp32, up to 63 taps) or generic."""
     x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 3, 3)
     _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode taps9")
     assert plan.gatherMode == 3 and plan.kSteps == 32 // (plan.tileK // 9)   # whole channels per step
@@ -181,6 +181,13 @@ def test_gather_modes_are_chosen():
     _, plan = _check(xl, wl_, (0, 0), (1, 1), 0, "f32", kernel=[i for i, n in enumerate(_names()) if n == "f32 32x128x32 nopad"][0],
                      tag="mode nopad")
     assert plan.gatherMode == 2 and plan.kSteps == 79     # (2500 indices would not fit the table)
+    # padded, at most 63 taps, fp32: filter order with a per-column mask of the taps that fall outside
+    _, plan = _check(x, w, (2, 2), (1, 1), 0, "f32", tag="mode masked")
+    assert plan.gatherMode == 14
+    _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode masked swap")
+    assert plan.gatherMode == 14 and plan.swapOperands == 1
+    # more than 63 taps, or bf16: per-element bounds checks
+    x, w = wl.random_problem(4, 2, 1, 20, 20, 33, 8, 8)
     _, plan = _check(x, w, (2, 2), (1, 1), 0, "f32", tag="mode generic")
     assert plan.gatherMode == 0
     _, plan = _check(x, w, (3, 1), (2, 1), 1, "f32", y_layout="NHWC", tag="mode generic swap")
@@ -414,19 +421,21 @@ def test_fused_bias_and_activation():
 # ------------------------------------------------------------------ optional workspace (small problems)
 @pytest.mark.gpu
 def test_forward_tap_major_with_filter_workspace():
-    """A float problem that runs in tap-major order (padded, not nine taps, enough channels and plenty of tiles):
+    """A problem that runs in tap-major order (padded, not nine taps, enough channels and plenty of tiles; float with more
+    than 63 taps, or bfloat16):
     the optional workspace is the filter's size, the filter is rewritten there with the channel index innermost and
     read through those strides.  Same sums in the same order: the same bits as without the workspace."""
     import paper_1410_0759_amd as ig
     gu = _gpu()
     cases = [
-        # N, C, H, W, K, R, S, pad, stride, mode
-        (64, 64, 20, 20, 70, 5, 5, (2, 2), (1, 1), 1),
-        (64, 80, 21, 19, 150, 7, 3, (3, 1), (2, 1), 0),     # ragged last channel chunk, eq. 2 order
-        (48, 96, 27, 27, 64, 5, 5, (2, 2), (1, 1), 1),
+        # N, C, H, W, K, R, S, pad, stride, mode, data type
+        # (float layers of up to 63 taps run in filter order under a mask of the taps outside, and ask for nothing)
+        (32, 64, 20, 20, 70, 9, 8, (4, 3), (1, 1), 1, "f32"),
+        (64, 80, 21, 19, 150, 13, 5, (6, 2), (2, 1), 0, "f32"),     # ragged last channel chunk, eq. 2 order
+        (64, 64, 20, 20, 70, 5, 5, (2, 2), (1, 1), 1, "bf16"),
+        (64, 80, 21, 19, 150, 7, 3, (3, 1), (2, 1), 0, "bf16"),
     ]
-    for i, (N, C, H, W, K, R, S, pad, stride, mode) in enumerate(cases + cases[:2]):
-        dtype = "f32" if i < len(cases) else "bf16"     # (the first two again with bfloat16 inputs)
+    for i, (N, C, H, W, K, R, S, pad, stride, mode, dtype) in enumerate(cases):
         x, w = wl.random_problem(120 + i, N, C, H, W, K, R, S, dtype=dtype)
         want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)
         g = gu.GpuConv(x, w, pad, stride, mode, dtype=dtype)
@@ -450,7 +459,7 @@ def test_forward_tap_major_with_filter_workspace():
 
 
 def test_forward_few_channels_zero_border_with_image_workspace():
-    """Few channels and a zero border: the layer runs with the generic gather, or - lent a workspace for x with its
+    """Few channels and a zero border: the layer runs with the masked gather, or - lent a workspace for x with its
     border written out - as a layer without a border over that copy.  Both against the oracle, with alpha/beta,
     bias and activation passed through, channel-fastest x, and a workspace too small (ignored)."""
     gu = _gpu()
@@ -467,7 +476,7 @@ def test_forward_few_channels_zero_border_with_image_workspace():
         y0 = np.random.default_rng(150 + i).uniform(-1, 1, size=want.shape).astype(np.float32)
         want2 = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode, alpha=0.5, beta=-1.5, y_old=y0)
         g = gu.GpuConv(xg, w, pad, stride, mode)
-        assert g.plan().gatherMode == 0
+        assert g.plan().gatherMode == 14
         asked = g.lend_workspace()
         assert asked == N * C * (H + 2 * pad[0]) * (W + 2 * pad[1]) * 4
         print("image workspace", cases[i], flush=True)

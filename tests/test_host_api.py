@@ -116,12 +116,15 @@ def test_optional_forward_workspace_is_only_asked_for_where_cutting_the_reductio
                    xs=nchw(w_.N, w_.C, w_.H, w_.W), ys=nchw(w_.N, w_.K, w_.P, w_.Q))
         assert ig.get_optional_workspace_size(h, *d) == 0
     # a float problem in tap-major order with plenty of tiles: room for the filter with the channel index innermost
-    big = _descs(N=64, C=64, H=20, W=20, K=70, R=5, S=5, pad=(2, 2))
+    # (more than 63 taps; with fewer a padded float layer runs in filter order with a mask of the taps outside, and asks for nothing)
+    big = _descs(N=64, C=64, H=20, W=20, K=70, R=9, S=9, pad=(4, 4))
     assert ig.get_plan(h, *big).gatherMode == 1
-    assert ig.get_optional_workspace_size(h, *big) == 70 * 64 * 25 * 4 and ig.get_workspace_size(h, *big) == 0
+    assert ig.get_optional_workspace_size(h, *big) == 70 * 64 * 81 * 4 and ig.get_workspace_size(h, *big) == 0
+    masked = _descs(N=64, C=64, H=20, W=20, K=70, R=5, S=5, pad=(2, 2))
+    assert ig.get_plan(h, *masked).gatherMode == 14 and ig.get_optional_workspace_size(h, *masked) == 0
     # a short reduction is never cut; neither is an output with gaps between its elements
     assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3, pad=(0, 0))) == 0
-    # few channels and a zero border (the generic gather): room for x with the border written out
+    # few channels and a zero border: room for x with the border written out
     assert ig.get_optional_workspace_size(h, *_descs(N=2, C=3, H=17, W=17, K=16, R=3, S=3)) == 2 * 3 * 19 * 19 * 4
     gaps = _descs(N=2, C=128, H=17, W=17, K=128, R=7, S=7, pad=(0, 0), ys=(128 * 11 * 12, 11 * 12, 12, 1))
     assert ig.get_optional_workspace_size(h, *gaps) == 0
@@ -211,9 +214,13 @@ def test_backward_passes_validate_before_any_gpu_call():
     assert ig.get_backward_data_workspace_size(h, w, y, c, x) == 768 + 2 * 6 * 6 * 10 * 4
     x1, w1, c1, y1 = _descs(N=2, C=3, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(1, 1))
     assert ig.get_backward_data_workspace_size(h, w1, y1, c1, x1) == 0
-    # many channels: one launch per phase, in tap-major order: room for the filter with the reduction index innermost
+    # many channels: one launch per phase.  bfloat16 phases run in tap-major order: room for the filter with the
+    # reduction index innermost; float phases run in filter order under a mask of the taps outside: none
     x2, w2, c2, y2 = _descs(N=2, C=40, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 2))
-    assert ig.get_backward_data_workspace_size(h, w2, y2, c2, x2) == 4 * 40 * 9 * 4
+    assert ig.get_backward_data_workspace_size(h, w2, y2, c2, x2) == 0
+    _, w2b, _, y2b = _descs(N=2, C=40, H=9, W=8, K=4, R=3, S=3, pad=(1, 1), stride=(2, 2), dt=ig.IGC_DATA_BFLOAT16,
+                            ydt=ig.IGC_DATA_BFLOAT16)
+    assert ig.get_backward_data_workspace_size(h, w2b, y2b, c2, x2) == 4 * 40 * 9 * 2       # (dx is float)
     # bf16, unit stride, nine taps, K in sixteens, dy with unit channel stride: room for the
     # filter with k and c exchanged; any of these conditions missing: none
     def bd_ws(K=32, stride=(1, 1), dt=ig.IGC_DATA_BFLOAT16, nhwc=True, R=3, S=3, pad=(1, 1)):
