@@ -24,7 +24,7 @@ constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
                                             &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise, &kGroupF32Teams,
-                                            &kGroupF32Masked};
+                                            &kGroupF32Masked, &kGroupF64Masked};
 
 int kernel_count() {
     int n = 0;
@@ -150,6 +150,8 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
 // of 16.  More workgroups per compute unit cover more of each other's waits: Table-2 layer 3 gained 4 %.
 static int workgroups_per_cu(const KernelInfo &ki) {
     const bool small_tile = (ki.gmode == 2 || (ki.gmode == 8 && !ki.bf16)) && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
+    // (double precision, pipelined: 105 registers for the 64 x 64 tile, 169 for 128 x 64)
+    if (ki.f64) return ki.gmode == 14 ? (ki.BM * ki.BN <= 64 * 64 ? 4 : 2) : 4;
     const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_tile ? 4 : 2);
     return std::max(1, std::min(by_regs, (160 * 1024) / ki.ldsBytes));
 }
@@ -297,7 +299,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || ki.f64 || ki.variant == 2) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2) return tiles_per_xcd;
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
 }
 
@@ -469,8 +471,9 @@ static bool backward_data_phase(const BackwardDataProblem &b, int ph, int pw, Pr
     pr->bf16 = b.bf16;
     pr->f64 = b.f64;
     pr->vec = b.bf16 ? 8 : (b.f64 ? 2 : 4);
-    // tap-major, or the nine-tap table when the phase has nine taps; double precision: its one gather
-    pr->mode_mask = b.f64 ? 1u << 0 : (1u << 1) | (1u << 3) | (1u << 14);
+    // tap-major, the nine-tap table when the phase has nine taps, or filter order under a tap mask; double precision:
+    // the tap mask, or the generic gather
+    pr->mode_mask = b.f64 ? (1u << 0) | (1u << 14) : (1u << 1) | (1u << 3) | (1u << 14);
     pr->zero_steps = ah.taps == 0 || aw.taps == 0;
     ConvKernelParams &k = pr->kp;
     const int es = b.bf16 ? 2 : 4;

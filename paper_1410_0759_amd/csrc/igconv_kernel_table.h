@@ -40,7 +40,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams, kGroupF32Masked;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams, kGroupF32Masked, kGroupF64Masked;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.

@@ -399,10 +399,17 @@ def test_double_precision_is_planned_and_mixed_types_are_rejected():
     D, F = ig.IGC_DATA_DOUBLE, ig.IGC_DATA_FLOAT
     x, w, c, y = _descs(N=2, C=5, H=9, W=8, K=70, dt=D, ydt=D)
     plan = ig.get_plan(h, x, w, c, y)
-    assert plan.tileM in (64, 128) and (plan.tileN, plan.tileK, plan.gatherMode) == (plan.tileM, 16, 0)
+    # (nine taps: filter order under a tap mask, the pipelined kernels; persistent workgroups, here one per tile)
+    assert plan.tileM in (64, 128) and (plan.tileN, plan.tileK, plan.gatherMode) == (64, 16, 14)
     assert ig.kernel_names()[plan.kernelId].startswith("f64")
     tiles = ((70 + plan.tileM - 1) // plan.tileM) * ((2 * 9 * 8 + plan.tileN - 1) // plan.tileN)
-    assert plan.gridX >= tiles and plan.gridX % 8 == 0      # one workgroup per tile
+    assert plan.gridX >= tiles and plan.gridX % 8 == 0
+    # more than 63 taps: the generic gather, one workgroup per tile
+    x8, w8, c8, y8 = _descs(N=2, C=5, H=9, W=8, K=70, R=8, S=8, pad=(4, 4), dt=D, ydt=D)
+    plan = ig.get_plan(h, x8, w8, c8, y8)
+    assert (plan.tileM, plan.tileN, plan.tileK, plan.gatherMode) == (64, 64, 16, 0)
+    tiles = ((70 + 63) // 64) * ((2 * 10 * 9 + 63) // 64)
+    assert plan.gridX >= tiles and plan.gridX % 8 == 0
     assert ig.get_workspace_size(h, x, w, c, y) == 0 and ig.get_optional_workspace_size(h, x, w, c, y) == 0
     assert _fwd_status(x, w, c, _descs(N=2, C=5, H=9, W=8, K=70, dt=D, ydt=F)[3]) == ig.IGC_STATUS_NOT_SUPPORTED
     xf = _descs(N=2, C=5, H=9, W=8, K=70)[0]
