@@ -19,12 +19,14 @@ namespace igc {
 
 // MI355X: 256 compute units; the tile heuristic balances workgroups over them.
 constexpr int kComputeUnits = 256;
+// gather mode 15: what loading an element costs, in multiply-add rows (see plan_cost)
+constexpr double kDirectGatherCost = 20.0;
 constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-reduction unpadded kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
 static const KernelGroup *const kGroups[] = {&kGroupF32Taps9, &kGroupF32TapMajor, &kGroupF32Nopad, &kGroupF32Generic, &kGroupF32Swap,
                                             &kGroupBF16, &kGroupBF16Channels, &kGroupWgrad, &kGroupF64, &kGroupWgradBF16Channels, &kGroupBF16Pointwise, &kGroupF32Teams,
-                                            &kGroupF32Masked, &kGroupF64Masked};
+                                            &kGroupF32Masked, &kGroupF64Masked, &kGroupF32Direct};
 
 int kernel_count() {
     int n = 0;
@@ -67,7 +69,8 @@ struct Problem {
     int vec;  // elements per 16 bytes of input
     unsigned mode_mask = 0;   // non-zero: bit g set when gather mode g can run this problem
     bool zero_steps = false;  // nothing to accumulate: the kernel only scales the old output
-    bool no_teams = false;    // leave the fp32 team kernels out of the choice (a workspace cuts the reduction further)
+    bool no_teams = false;    // leave the kernels that cut the reduction inside a workgroup (teams, gather mode 15) out of the
+                              // choice: a workspace cuts it across compute units, which measured faster where both apply
 };
 
 // Everything igcConvolutionForward checks that does not need the data pointers.
@@ -140,6 +143,15 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
+// Gather mode 15 (igconv_kernel_f32d.hpp): steps of BK reduction indices per wavefront, the workgroup's wavefronts
+// sharing the reduction evenly; a multiple of the request depth.
+static long long direct_steps_per_wave(const KernelInfo &ki, const ConvKernelParams &k) {
+    const long long waves = ki.threads / 64, steps = (k.CRS + ki.BK - 1) / ki.BK;
+    const long long per = (steps + waves - 1) / waves;
+    const long long depth = direct_depth(ki.BK);
+    return (per + depth - 1) / depth * depth;
+}
+
 // Relative cost of running the problem with one kernel variant.  Tiles are padded to
 // full size; a compute unit holds up to `occ` workgroups at a time (LDS), which share its
 // MFMA pipes, so a full wave of 256*occ workgroups takes occ tile-times, and a last,
@@ -150,6 +162,7 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
 // of 16.  More workgroups per compute unit cover more of each other's waits: Table-2 layer 3 gained 4 %.
 static int workgroups_per_cu(const KernelInfo &ki) {
     const bool small_tile = (ki.gmode == 2 || (ki.gmode == 8 && !ki.bf16)) && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
+    if (ki.gmode == 15) return 2;   // (64 KB of LDS each; 55 to 97 registers)
     // (double precision, pipelined: 105 registers for the 64 x 64 tile, 169 for 128 x 64)
     if (ki.f64) return ki.gmode == 14 ? (ki.BM * ki.BN <= 64 * 64 ? 4 : 2) : 4;
     const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_tile ? 4 : 2);
@@ -192,6 +205,17 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
                (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     }
     const bool table = ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13;
+    if (ki.gmode == 15) {
+        // 32 x 32 tiles, the wavefronts of a workgroup each on their share of the steps, operands straight from global
+        // memory: a round of one step per wavefront is waves * 8 * 32 * 32 multiply-adds, bound by the loads (two
+        // elements per lane and MFMA) rather than by the MFMA pipe; a fixed cost (offset table, exchange of the sums)
+        // of about six steps.  Measured against the pipelined kernels on the deeper layers of Table 2: ahead up to
+        // mini-batches of 32 (layer 3: 72 -> 97 TFLOP/s at 16; layer 4: 23 -> 53), level at 64, behind where tiles of
+        // 64 x 64 and more fill the chip.  Element-wise filter loads (32 cache lines per instruction): three times slower.
+        const double waves = ki.threads / 64;
+        return tile_times * ((double)direct_steps_per_wave(ki, k) + 6.0) * waves * ki.BK * 32.0 * (32.0 + kDirectGatherCost) *
+               (ki.veca ? 1.0 : 3.0);
+    }
     if (ki.variant == 2) {
         // Teams: one tile per workgroup and one workgroup per compute unit at a time; each team multiplies its
         // share of the steps, the teams of a compute unit sharing its MFMA pipes - the work per compute unit is
@@ -240,6 +264,9 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 14) return k.RS <= 63;   // (one bit of a 64-bit mask per tap, the last one spare)
+    if (gmode == 15)   // unpadded, and every index a wavefront can request has an entry in the offset table
+        return k.pad_h == 0 && k.pad_w == 0 &&
+               ((long long)(ki.threads / 64) * direct_steps_per_wave(ki, k) + direct_depth(ki.BK) + 1) * ki.BK <= kDirectTableEntries;
     if (gmode == 7 || gmode == 11 || gmode == 13) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
         if (!(k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries)) return false;
@@ -280,7 +307,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || ki.f64 != pr.f64 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
-        if (pr.no_teams && ki.variant == 2 && ki.gmode < 4) continue;
+        if (pr.no_teams && ((ki.variant == 2 && ki.gmode < 4) || ki.gmode == 15)) continue;
         double c = plan_cost(ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -299,7 +326,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || ki.gmode == 15) return tiles_per_xcd;
     return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
 }
 
@@ -365,6 +392,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
     k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
     k.splits = 1;
     k.stepsPerSplit = (k.ksteps + 1) & ~1;
+    if (ki.gmode == 15) k.stepsPerSplit = (int)direct_steps_per_wave(ki, k);
     if (ki.variant == 2 && ki.gmode < 4) {   // (fp32 team kernels: an even number of steps per team)
         const int teams = ki.threads / 256;
         k.stepsPerSplit = ((k.ksteps + teams - 1) / teams + 1) & ~1;

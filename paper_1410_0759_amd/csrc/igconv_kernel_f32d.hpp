@@ -1,0 +1,199 @@
+// fp32 forward kernel for problems with few output elements and a long reduction (small
+// mini-batches of the deeper layers): the tiles of the pipelined kernels, at least 64 x 64,
+// leave most compute units without work there, and cutting the reduction across
+// workgroups needs memory for the partial results.  Here a workgroup owns a 32 x 32 tile of
+// O_m (paper, Section 3.1: O_m = F_m . D_m, D_m never stored) and cuts the reduction among
+// its WAVES wavefronts inside the compute unit:
+//  * a wavefront multiplies ITS range of the reduction for the whole tile with
+//    v_mfma_f32_32x32x2_f32, whose operands are one element per lane - lane (l % 32, l / 32)
+//    holds F_m[row l % 32][k] and D_m[k][column l % 32] for k = l / 32 of the instruction's
+//    two - so both operands go from global memory straight into the registers the MFMA reads:
+//    no LDS tiles, no barrier in the loop.  A step is 8 NV reduction indices: a lane loads NV
+//    runs of four consecutive k of its filter row (16-byte loads when the filter allows) and
+//    gathers the 4 NV elements of its column (pad 0: every tap of a valid column lies inside
+//    the image; the offset of reduction index i relative to the window origin comes from a
+//    table in LDS built once per workgroup), then feeds them to 4 NV MFMAs; requests run
+//    DEPTH steps ahead in DEPTH register sets, each register refilled right after the MFMA
+//    that read it.  (NV = 1 is built.  NV = 4, a whole 128-byte line of every filter row per
+//    step, was measured 4 to 25 % slower: the loop is bound by the number of loads the
+//    gathers need - two elements per lane and MFMA, a dozen cache lines per gather
+//    instruction on small images - not by re-fetched filter lines.  Element-wise filter loads
+//    cost a factor of three.)
+//  * at the end the wavefronts leave their sums in LDS and every thread adds up one element
+//    of the tile over the wavefronts in order (deterministic) and stores it through y's strides
+//    with alpha, beta, bias and activation applied.
+// Indices past the end of the reduction read zeros on both sides (out-of-range requests).
+#ifndef IGCONV_KERNEL_F32D_HPP_
+#define IGCONV_KERNEL_F32D_HPP_
+
+#include "igconv_kernel.hpp"
+
+namespace igc {
+
+template <int WAVES_, bool VECA_, int NV_>
+struct DirectConfig {
+    static constexpr int WAVES = WAVES_, THREADS = 64 * WAVES_;
+    static constexpr bool VECA = VECA_;   // filter rows fetched with 16-byte loads (C*R*S a multiple of 4, aligned filter)
+    static constexpr int NV = NV_;        // runs of four reduction indices per lane and step
+    static constexpr int BM = 32, BN = 32, BK = 8 * NV_;
+    static constexpr int DEPTH = direct_depth(BK);
+    static constexpr int LDS_BYTES = kDirectTableEntries * 4;
+    static_assert(WAVES_ * 16 * 64 <= kDirectTableEntries, "the exchange of the sums reuses the table's memory");
+    static_assert(1024 % THREADS == 0, "whole elements per thread in the epilogue");
+};
+
+template <class Cfg>
+__global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKernelParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int W = Cfg::WAVES, D = Cfg::DEPTH, THREADS = Cfg::THREADS, NV = Cfg::NV, BK = Cfg::BK;
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kDirectTableEntries];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+
+    // one tile per workgroup, tiles numbered in contiguous ranges per XCD (the M tiles of a column tile adjacent)
+    const int tiles = p.tilesM * p.tilesN;
+    const int item = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
+    if (item >= tiles) return;
+    const int m0 = (item % p.tilesM) * 32, n0 = (item / p.tilesM) * 32;
+
+    // offset of reduction index i = (c,r,s) relative to the window origin; out of range past the end.  The host
+    // checked that every index a wavefront can request (its range and DEPTH + 1 steps beyond) has an entry.
+    const int steps_w = p.stepsPerSplit;   // steps per wavefront, a multiple of DEPTH
+    const uint32_t entries = (uint32_t)(W * steps_w + D + 1) * (uint32_t)BK;
+    for (uint32_t i = (uint32_t)tid; i < entries; i += (uint32_t)THREADS) {
+        const uint32_t c = magic_div(i, p.mRS);
+        const uint32_t rs = i - c * (uint32_t)p.RS;
+        const uint32_t r = magic_div(rs, p.mS);
+        const uint32_t sx = rs - r * (uint32_t)p.S;
+        const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+        const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
+        const uint32_t so = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * 4u;
+        lds[i] = i < (uint32_t)p.CRS ? so : kOutOfRange;
+    }
+    __syncthreads();
+
+    const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
+    const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
+
+    // this lane's column j -> (n,p,q): byte offset of its window origin (a valid offset lies below 2^31, so adding
+    // the marker of a dead index leaves it out of range; a column beyond NPQ reads anything: it is never stored)
+    uint32_t colbase;
+    {
+        const int j = n0 + l32;
+        const uint32_t jj = j < p.NPQ ? (uint32_t)j : 0u;
+        const uint32_t n = magic_div(jj, p.mPQ);
+        const uint32_t rem = jj - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        colbase = (n * (uint32_t)p.xsN + pp * (uint32_t)p.u * (uint32_t)p.xsH + qq * (uint32_t)p.v * (uint32_t)p.xsW) * 4u;
+    }
+    // this lane's filter row; within a step the lower half of the wavefront holds the first 4 NV reduction indices,
+    // the upper half the others (both operands alike: which k meets which MFMA is free, the sum commutes), so that
+    // a row's indices of a step are 32 NV contiguous bytes of the filter - a whole cache line for NV = 4
+    const int row = m0 + l32;
+    const uint32_t lane_k = 4u * NV * (uint32_t)half;
+    const uint32_t a_base = row < p.K ? ((uint32_t)row * (uint32_t)p.CRS + lane_k) * 4u : kOutOfRange;
+
+    u32x4 a_reg[D][NV];
+    uint32_t b_reg[D][NV][4];
+    u32x4 so4[NV];   // table entries of the step requested next
+    auto read_table = [&](int t, int v) __attribute__((always_inline)) {
+        so4[v] = *reinterpret_cast<const u32x4 *>(&lds[t * BK + (int)lane_k + 4 * v]);
+    };
+    // the request of step t in pieces, each short enough for the gap between two MFMAs
+    auto request_a = [&](int set, int t, int v) __attribute__((always_inline)) {
+        const uint32_t k0 = (uint32_t)t * (uint32_t)BK;
+        const uint32_t kk = k0 + lane_k + 4u * (uint32_t)v;
+        if constexpr (Cfg::VECA) {
+            a_reg[set][v] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, kk < (uint32_t)p.CRS ? a_base + 16u * (uint32_t)v : kOutOfRange,
+                                                                  k0 * 4u, 0);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                a_reg[set][v][e] = __builtin_amdgcn_raw_buffer_load_b32(
+                    wbuf, kk + (uint32_t)e < (uint32_t)p.CRS ? a_base + 16u * (uint32_t)v + 4u * (uint32_t)e : kOutOfRange, k0 * 4u, 0);
+        }
+    };
+    auto request_b = [&](int set, int v, int e) __attribute__((always_inline)) {
+        b_reg[set][v][e] = __builtin_amdgcn_raw_buffer_load_b32(xbuf, colbase + so4[v][e], 0, 0);
+    };
+
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+    const int t0 = wave * steps_w;
+    static_for<NV>([&](auto vc) { read_table(t0, decltype(vc)::value); });
+    static_for<D>([&](auto dc) {
+        constexpr int set = decltype(dc)::value;
+        static_for<NV>([&](auto vc) {
+            constexpr int v = decltype(vc)::value;
+            request_a(set, t0 + set, v);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) request_b(set, v, e);
+            read_table(t0 + set + 1, v);
+        });
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    for (int s = 0; s < steps_w; s += D) {
+        // (the order is pinned: one MFMA, then the request that refills the register it has just read - for step
+        // t + DEPTH, which uses the same register set; after the four MFMAs of a run its filter vector and the table
+        // entries of the step after)
+        static_for<D>([&](auto dc) {
+            constexpr int set = decltype(dc)::value;
+            const int t = t0 + s + set + D;
+            static_for<4 * NV>([&](auto ic) {
+                constexpr int v = decltype(ic)::value / 4, e = decltype(ic)::value % 4;
+                const f32x4 va = __builtin_bit_cast(f32x4, a_reg[set][v]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], __builtin_bit_cast(float, b_reg[set][v][e]), acc, 0, 0, 0);
+                request_b(set, v, e);
+                if constexpr (e == 3) {
+                    request_a(set, t, v);
+                    read_table(t + 1, v);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+
+    // the wavefronts' sums meet in LDS (the table is no longer needed): [wavefront][register][lane]
+    __syncthreads();
+    float *const xch = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) xch[(wave * 16 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, kBufferWord3);
+    const bool fused = p.bias != nullptr || p.act >= 0;
+#pragma unroll
+    for (int i = 0; i < 1024 / THREADS; ++i) {
+        // register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the tile
+        const int val = tid + i * THREADS;
+        const int v = val >> 6, l = val & 63;
+        float sum = xch[v * 64 + l];
+        for (int w = 1; w < W; ++w) sum += xch[(w * 16 + v) * 64 + l];
+        const int orow = m0 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        const int ocol = n0 + (l & 31);
+        if (orow >= p.K || ocol >= p.NPQ) continue;
+        const uint32_t n = magic_div((uint32_t)ocol, p.mPQ);
+        const uint32_t rem = (uint32_t)ocol - n * (uint32_t)p.PQ;
+        const uint32_t pp = magic_div(rem, p.mQ);
+        const uint32_t qq = rem - pp * (uint32_t)p.Q;
+        const uint32_t off = (n * (uint32_t)p.ysN + pp * (uint32_t)p.ysP + qq * (uint32_t)p.ysQ + (uint32_t)orow * (uint32_t)p.ysK) * 4u;
+        float out = p.alpha * sum;
+        if (p.beta != 0.f) out += p.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ybuf, off, 0, 0));
+        if (fused) {
+            if (p.bias != nullptr) out += p.bias[orow];
+            if (p.act == 0) out = 1.f / (1.f + __expf(-out));                   // sigmoid
+            else if (p.act == 1) out = fmaxf(out, 0.f);                         // rectified linear
+            else if (p.act == 2) out = 1.f - 2.f / (__expf(2.f * out) + 1.f);   // tanh
+        }
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, out), ybuf, off, 0, 0);
+    }
+#endif
+}
+
+}  // namespace igc
+#endif

@@ -23,6 +23,7 @@ struct KernelInfo {
                     // 12 1x1 filters over channel vectors (bf16, unit channel stride): both operands loaded as they are,
                     // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers,
                     // 14 filter order with the tap tracked by the scalar unit and the window test in a bit mask (R*S <= 63)
+                    // 15 unpadded, 32 x 32 tiles, the reduction cut among the wavefronts, operands straight from global memory
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
@@ -40,7 +41,7 @@ struct KernelGroup {
 
 // One group per translation unit of kernel instantiations.
 extern const KernelGroup kGroupF32Taps9, kGroupF32TapMajor, kGroupF32Nopad, kGroupF32Generic, kGroupF32Swap, kGroupBF16,
-    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams, kGroupF32Masked, kGroupF64Masked;
+    kGroupBF16Channels, kGroupWgrad, kGroupF64, kGroupWgradBF16Channels, kGroupBF16Pointwise, kGroupF32Teams, kGroupF32Masked, kGroupF64Masked, kGroupF32Direct;
 
 // Adds up `count` partial results (`stride` floats apart) into out = alpha*sum + beta*out;
 // returns the runtime's error code.

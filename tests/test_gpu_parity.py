@@ -83,7 +83,7 @@ def test_every_kernel_variant():
         dtype = "bf16" if name.startswith("bf16") else "f32"
         vec = "vecw" in name
         swap = "swap" in name
-        nopad = "nopad" in name
+        nopad = "nopad" in name or "direct" in name
         taps9 = "taps9" in name
         vecn = 8 if dtype == "bf16" else 4
         problems = [
@@ -101,6 +101,9 @@ def test_every_kernel_variant():
             ]
             if "x72 " in name:   # steps of eight channels
                 problems = [(n_, 8 * ((c_ + 7) // 8), h_, w_, k_, r_, s_, pd, st) for (n_, c_, h_, w_, k_, r_, s_, pd, st) in problems]
+        if "direct" in name:   # the reduction cut among 8 or 16 wavefronts: long ones, a ragged end, wavefronts left without steps
+            problems = problems + [(2, 40, 12, 9, 70, 5, 3, (0, 0), (1, 2)), (1, 24, 20, 21, 130, 7, 7, (0, 0), (1, 1)),
+                                   (2, 8 if vec else 7, 9, 9, 40, 3, 3, (0, 0), (1, 1)), (1, 4 if vec else 1, 12, 12, 33, 2, 2, (0, 0), (1, 1))]
         if "teams" in name:   # long reductions: several steps per team, a ragged last step, a team left without steps
             problems = problems + ([(2, 40, 15, 17, 150, 3, 3, (1, 1), (1, 1)), (1, 136, 9, 11, 70, 3, 3, (1, 1), (2, 1))] if taps9 else
                                    [(2, 40, 12, 9, 70, 5, 3, (0, 0), (1, 2)), (1, 24, 20, 21, 130, 7, 7, (0, 0), (1, 1)), (2, 8, 9, 9, 40, 3, 3, (0, 0), (1, 1))])
@@ -495,6 +498,37 @@ def test_forward_few_channels_zero_border_with_image_workspace():
         g.prefill(value=float("nan"))
         g.launch(1.0, 0.0)
         assert gu.rel_err(g.result(), want) <= gu.BOUND["f32"]
+
+
+def test_small_problems_run_with_the_reduction_cut_inside_the_workgroup():
+    """Few output elements and a long reduction, no workspace: 32 x 32 tiles, the reduction cut among the wavefronts of
+    a workgroup, operands straight from global memory.  Chosen by the library for such shapes; checked with eq. 2's
+    inverted filter, strides, channel-fastest x and y, alpha/beta, and the fused bias + activation."""
+    gu = _gpu()
+    cases = [
+        # N, C, H, W, K, R, S, stride, mode, x layout, y layout
+        (4, 128, 16, 16, 128, 7, 7, (1, 1), 1, "NCHW", "NCHW"),      # a deep layer of Table 2 at a mini-batch of 4
+        (2, 96, 21, 19, 70, 5, 3, (2, 1), 0, "NHWC", "NHWC"),
+        (1, 300, 9, 11, 33, 3, 4, (1, 2), 0, "NCHW", "NHWC"),
+    ]
+    for i, (N, C, H, W, K, R, S, stride, mode, xl, yl) in enumerate(cases):
+        x, w = wl.random_problem(170 + i, N, C, H, W, K, R, S)
+        want = oc.conv_forward(x, w, pad=(0, 0), stride=stride, mode=mode)
+        y0 = np.random.default_rng(175 + i).uniform(-1, 1, size=want.shape).astype(np.float32)
+        want2 = oc.conv_forward(x, w, pad=(0, 0), stride=stride, mode=mode, alpha=0.5, beta=-1.5, y_old=y0)
+        g = gu.GpuConv(wl.with_layout(x, xl), w, (0, 0), stride, mode, y_layout=yl)
+        print("direct", cases[i], flush=True)
+        assert g.plan().gatherMode == 15
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        assert gu.rel_err(g.result(), want) <= gu.BOUND["f32"]
+        g.prefill(y0=y0)
+        g.launch(0.5, -1.5)
+        assert gu.rel_err(g.result(), want2) <= gu.BOUND["f32"]
+        bias = np.random.default_rng(180 + i).uniform(-1, 1, size=K).astype(np.float32)
+        g.prefill(value=float("nan"))
+        g.launch_fused(1.0, 0.0, bias, 1)
+        assert gu.rel_err(g.result(), np.maximum(want + bias[None, :, None, None], 0.0)) <= gu.BOUND["f32"]
 
 
 def test_forward_with_optional_workspace():
