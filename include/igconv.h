@@ -486,6 +486,36 @@ igcStatus igcConvolutionBackwardFilterNoAlloc(igcHandle_t handle, const void *al
 igcStatus igcGetDeviceProperties(igcHandle_t handle, int *computeUnits, int *clockKHz);
 igcStatus igcMeasureMatrixRate(igcHandle_t handle, igcDataType dataType, int milliseconds, double *tflops);
 
+/* ---- checks of the host logic (test tier; host only, no GPU call) --------------------
+ * igcCreate reads the number of compute units of the current device into the handle (256,
+ * MI355X's, when the runtime finds no device); the launch plans size their grids and balance
+ * their tiles by it.  igcSetComputeUnits replaces that number (8..4096, else BAD_PARAM), so
+ * that the planning can be exercised for other sizes without such a device;
+ * igcGetComputeUnits reads it back.
+ *
+ * igcGetConvolutionForwardAddressReach / igcGetConvolutionBackwardDataAddressReach: for a
+ * problem the pass accepts, with the kernel and launch parameters the pass would use,
+ * reachBytes[i] = one past the largest byte offset the kernels' address arithmetic forms
+ * for an element that exists, evaluated in 64 bits from the launch parameters (strides,
+ * tap offsets, phase offsets) at the extreme indices; extentBytes[i] = the size the
+ * buffer descriptor of that argument is given.  i = 0: the gathered tensor (x, resp. dy),
+ * 1: the filter, 2: the output (y, resp. dx; backward data: the maximum over its stride
+ * phases, each relative to dx).  A correct plan has 0 < reach <= extent < 2^31 for all
+ * three; a reach beyond the extent would be an access the hardware's range check has to
+ * absorb - or, for a kernel that addressed memory directly, a fault.  Same validation and
+ * status codes as the pass itself; BAD_PARAM for null pointers. */
+igcStatus igcSetComputeUnits(igcHandle_t handle, int computeUnits);
+igcStatus igcGetComputeUnits(igcHandle_t handle, int *computeUnits);
+igcStatus igcGetConvolutionForwardAddressReach(igcHandle_t handle, igcTensorDescriptor_t xDesc,
+                                               igcFilterDescriptor_t wDesc, igcConvolutionDescriptor_t convDesc,
+                                               igcTensorDescriptor_t yDesc, long long reachBytes[3],
+                                               long long extentBytes[3]);
+igcStatus igcGetConvolutionBackwardDataAddressReach(igcHandle_t handle, igcFilterDescriptor_t wDesc,
+                                                    igcTensorDescriptor_t dyDesc,
+                                                    igcConvolutionDescriptor_t convDesc,
+                                                    igcTensorDescriptor_t dxDesc, long long reachBytes[3],
+                                                    long long extentBytes[3]);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,19 @@ def build(force: bool = True) -> str:
     return _compile(SRC, LIB, force, ["-fopenmp"])
 
 
+def build_sanitized() -> str:
+    """Both oracles and ``sanitize_main.c`` as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer (any report aborts the run); returns its path."""
+    out_dir = os.path.join(HERE, "_build")
+    os.makedirs(out_dir, exist_ok=True)
+    exe = os.path.join(out_dir, "oracle_check_san")
+    cmd = ["gcc", "-O1", "-g", "-std=c99", "-Wall", "-Wextra", "-fopenmp", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-o", exe,
+           os.path.join(HERE, "sanitize_main.c"), SRC, POINTWISE_SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def build_pointwise(force: bool = False) -> str:
     return _compile(POINTWISE_SRC, POINTWISE_LIB, force, ["-lm"], POINTWISE_DEPS)
 

@@ -23,6 +23,7 @@ __all__ = [
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
     "get_device_properties", "measure_matrix_rate", "convolution_backward_filter_no_alloc", "NOALLOC_SCRATCH_BYTES",
+    "set_compute_units", "get_compute_units", "get_forward_address_reach", "get_backward_data_address_reach",
 ]
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -98,6 +99,10 @@ DECLARED_SYMBOLS = {
     "igcConvolutionBackwardFilterNoAlloc": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcGetDeviceProperties": (_i, [_vp, _P(_i), _P(_i)]),
     "igcMeasureMatrixRate": (_i, [_vp, _i, _i, _P(ctypes.c_double)]),
+    "igcSetComputeUnits": (_i, [_vp, _i]),
+    "igcGetComputeUnits": (_i, [_vp, _P(_i)]),
+    "igcGetConvolutionForwardAddressReach": (_i, [_vp, _vp, _vp, _vp, _vp, _P(ctypes.c_longlong), _P(ctypes.c_longlong)]),
+    "igcGetConvolutionBackwardDataAddressReach": (_i, [_vp, _vp, _vp, _vp, _vp, _P(ctypes.c_longlong), _P(ctypes.c_longlong)]),
 }
 
 _lib = None
@@ -406,6 +411,32 @@ def measure_matrix_rate(handle, dtype, milliseconds=50):
     out = ctypes.c_double()
     check(lib().igcMeasureMatrixRate(handle.ptr, dtype, milliseconds, ctypes.byref(out)), "igcMeasureMatrixRate")
     return out.value
+
+
+def set_compute_units(handle, compute_units):
+    check(lib().igcSetComputeUnits(handle.ptr, compute_units), "igcSetComputeUnits")
+
+
+def get_compute_units(handle):
+    out = _i()
+    check(lib().igcGetComputeUnits(handle.ptr, ctypes.byref(out)), "igcGetComputeUnits")
+    return out.value
+
+
+def get_forward_address_reach(handle, xdesc, wdesc, conv, ydesc):
+    """((reach of x, w, y), (extent of x, w, y)) in bytes for the forward pass."""
+    reach, extent = (ctypes.c_longlong * 3)(), (ctypes.c_longlong * 3)()
+    check(lib().igcGetConvolutionForwardAddressReach(handle.ptr, xdesc.ptr, wdesc.ptr, conv.ptr, ydesc.ptr, reach, extent),
+          "igcGetConvolutionForwardAddressReach")
+    return tuple(reach), tuple(extent)
+
+
+def get_backward_data_address_reach(handle, wdesc, dydesc, conv, dxdesc):
+    """((reach of dy, w, dx), (extent of dy, w, dx)) in bytes for backward data."""
+    reach, extent = (ctypes.c_longlong * 3)(), (ctypes.c_longlong * 3)()
+    check(lib().igcGetConvolutionBackwardDataAddressReach(handle.ptr, wdesc.ptr, dydesc.ptr, conv.ptr, dxdesc.ptr, reach, extent),
+          "igcGetConvolutionBackwardDataAddressReach")
+    return tuple(reach), tuple(extent)
 
 
 def magic_divisor(d):

@@ -43,5 +43,26 @@ def build(verbose=False):
     return LIB
 
 
+def build_host_check():
+    """The host tier under AddressSanitizer and UndefinedBehaviorSanitizer: ``csrc/igconv_api.cpp`` and the driver
+    ``csrc/host_check.cpp`` compiled with both (any report aborts), linked with the ordinary objects of the kernel
+    files (their device code never runs: the driver makes no launch).  Builds those first if they are missing.
+    Returns the executable's path."""
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES if s != "igconv_api.cpp"]
+    if not all(os.path.exists(o) for o in objs):
+        build()
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g", "-O1"]
+    exe = os.path.join(OBJ, "host_check_san")
+    host_objs = []
+    for src in ("igconv_api.cpp", "host_check.cpp"):
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".san.o")
+        subprocess.run([HIPCC, "-std=c++17", "-Wall", "-Wno-unused-command-line-argument", "-x", "c++"] + san +
+                       ["-c", os.path.join(CSRC, src), "-o", obj], check=True)
+        host_objs.append(obj)
+    subprocess.run([HIPCC, "--offload-arch=gfx950"] + san + ["-o", exe] + host_objs + objs, check=True)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build_host_check() if "--host-check" in sys.argv else build(verbose=True))

@@ -17,8 +17,10 @@
 
 namespace igc {
 
-// MI355X: 256 compute units; the tile heuristic balances workgroups over them.
-constexpr int kComputeUnits = 256;
+// The tile heuristic balances workgroups over the device's compute units, whose number the handle reads from the
+// runtime when it is created (MI355X: 256; that figure also stands in on a machine without a GPU, where plans can
+// still be queried).  The kernels deal workgroups to XCDs by blockIdx % 8: gfx950 parts have 8.
+constexpr int kXcds = 8;
 // gather mode 15: what loading an element costs, in multiply-add rows (see plan_cost)
 constexpr double kDirectGatherCost = 20.0;
 constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-reduction unpadded kernels
@@ -169,15 +171,16 @@ static int workgroups_per_cu(const KernelInfo &ki) {
     return std::max(1, std::min(by_regs, (160 * 1024) / ki.ldsBytes));
 }
 
-static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
+static double plan_cost(const igcContext *h, const KernelInfo &ki, const ConvKernelParams &k) {
+    const long long cus = h->computeUnits;
     const long long tm = (k.K + ki.BM - 1) / ki.BM;
     const long long tn = (k.NPQ + ki.BN - 1) / ki.BN;
     const long long steps = kernel_steps(ki, k);
     const long long tiles = tm * tn;
     const long long occ = workgroups_per_cu(ki);
-    const long long wave = kComputeUnits * occ;
+    const long long wave = cus * occ;
     const long long rem = tiles % wave;
-    const double tile_times = (double)(tiles / wave) * occ + (double)((rem + kComputeUnits - 1) / kComputeUnits);
+    const double tile_times = (double)(tiles / wave) * occ + (double)((rem + cus - 1) / cus);
     // Per step a workgroup does BM*BN*BK multiply-adds and gathers BN*BK elements of
     // D_m; measured on the box, gathering one element costs about as much MFMA time as
     // `gather` multiply-add rows, depending on the mode.
@@ -192,14 +195,14 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
         // workgroup anyway, measured 0.82 of the two-team kernel's time on such a problem.  One group on a
         // 128 x 256 tile: measured 0.94 of the time of the 64 x 256 kernel at two workgroups per compute unit.
         const bool two_groups = ki.BK == 288;
-        if (two_groups && tiles > kComputeUnits) return 1e300;
+        if (two_groups && tiles > cus) return 1e300;
         const double unit = 2.75 * ki.BM + 1.0 * ki.BN + ki.BM * ki.BN / 256.0;
         return tile_times * (double)steps * 1000.0 * unit * (two_groups ? 0.92 : 1.1);
     }
     if (ki.gmode == 4 || ki.gmode == 5) {
         // (two teams per workgroup, each on half of the steps, plus the exchange of the results: for problems
         // that leave compute units without a workgroup; with more tiles two workgroups per compute unit do the same)
-        if (ki.variant == 2 && tiles > kComputeUnits) return 1e300;
+        if (ki.variant == 2 && tiles > cus) return 1e300;
         const double st = ki.variant == 2 ? (double)((steps + 1) / 2 + 2) : (double)steps;
         return tile_times * st * 1000.0 *
                (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
@@ -223,7 +226,7 @@ static double plan_cost(const KernelInfo &ki, const ConvKernelParams &k) {
         // kernel runs one workgroup per compute unit) and a fixed cost of about three steps is added.  Offered
         // only where the plain kernels leave compute units with a single workgroup or none.
         const int teams = ki.threads / 256;
-        if (tiles > kComputeUnits || steps < 8 * teams) return 1e300;
+        if (tiles > cus || steps < 8 * teams) return 1e300;
         const double gather2 = ki.gmode == 2 ? 29.0 : 6.0;
         return 0.8 * ((double)steps + 3.0 * teams) * (double)ki.BN * ki.BK * (ki.BM + gather2);
     }
@@ -308,7 +311,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
         if (ki.bf16 != pr.bf16 || ki.f64 != pr.f64 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
         if (pr.no_teams && ((ki.variant == 2 && ki.gmode < 4) || ki.gmode == 15)) continue;
-        double c = plan_cost(ki, k);
+        double c = plan_cost(h, ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
         if (best < 0 || c < best_cost) {
@@ -325,9 +328,9 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // workgroups as the chip holds at once (32 compute units per XCD, one or two workgroups
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
-static int workgroups_per_xcd(const KernelInfo &ki, int tiles_per_xcd) {
+static int workgroups_per_xcd(const igcContext *h, const KernelInfo &ki, int tiles_per_xcd) {
     if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || ki.gmode == 15) return tiles_per_xcd;
-    return std::min(tiles_per_xcd, (kComputeUnits / 8) * workgroups_per_cu(ki));
+    return std::min(tiles_per_xcd, std::max(1, h->computeUnits / kXcds) * workgroups_per_cu(ki));
 }
 
 // A float problem with a zero border and at most four channels (a first layer), which would run with the masked or the
@@ -352,7 +355,9 @@ static long long padded_copy_bytes(const KernelInfo &ki, const Problem &pr, igcT
 // compute unit holds ceil(tiles*s/256) workgroups, which share its MFMA pipes, each taking
 // its range plus a fixed start-up/epilogue share (about 6 steps); cutting adds the summing
 // pass (about 12).  Cutting must win by a tenth, or it is not done.
-static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool packed_y, long long max_parts, int *per_out) {
+static int forward_split(const igcContext *h, const KernelInfo &ki, const ConvKernelParams &k, bool packed_y, long long max_parts,
+                         int *per_out) {
+    const long long cus = h->computeUnits;
     *per_out = (k.ksteps + 1) & ~1;
     if ((ki.gmode > 3 && ki.gmode != 14) || ki.variant == 2 || !packed_y) return 1;
     const long long tiles = (long long)k.tilesM * k.tilesN;
@@ -360,7 +365,7 @@ static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool p
     const double kFixed = 6.0, kSumPass = 12.0;
     auto cost = [&](long long s) {
         const long long per = (k.ksteps + s - 1) / s;
-        return (double)((tiles * s + kComputeUnits - 1) / kComputeUnits) * ((double)per + kFixed) + (s > 1 ? kSumPass : 0.0);
+        return (double)((tiles * s + cus - 1) / cus) * ((double)per + kFixed) + (s > 1 ? kSumPass : 0.0);
     };
     long long best = 1;
     for (long long s = 2; s <= smax; ++s)
@@ -372,12 +377,12 @@ static int forward_split(const KernelInfo &ki, const ConvKernelParams &k, bool p
     return (int)((k.ksteps + per - 1) / per);
 }
 
-static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan) {
+static igcStatus fill_plan(const igcContext *h, int id, Problem *pr, igcConvolutionForwardPlan *plan) {
     const KernelInfo &ki = *kernel_info(id);
     ConvKernelParams &k = pr->kp;
     k.tilesM = (k.K + ki.BM - 1) / ki.BM;
     k.tilesN = (k.NPQ + ki.BN - 1) / ki.BN;
-    k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN + 7) / 8);
+    k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN + kXcds - 1) / kXcds);
     const long long steps = pr->zero_steps ? 0 : kernel_steps(ki, k);
     if (steps >= (1ll << 30)) return IGC_STATUS_NOT_SUPPORTED;
     k.ksteps = (int)steps;
@@ -389,7 +394,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         k.tail_step = k.ksteps - 1;
     // one workgroup per tile; the runtime limits a launch to fewer than 2^32 threads
     if ((long long)k.tilesM * k.tilesN >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
-    k.wgsPerXcd = workgroups_per_xcd(ki, k.tilesPerXcd);
+    k.wgsPerXcd = workgroups_per_xcd(h, ki, k.tilesPerXcd);
     k.splits = 1;
     k.stepsPerSplit = (k.ksteps + 1) & ~1;
     if (ki.gmode == 15) k.stepsPerSplit = (int)direct_steps_per_wave(ki, k);
@@ -402,7 +407,7 @@ static igcStatus fill_plan(int id, Problem *pr, igcConvolutionForwardPlan *plan)
         plan->tileM = ki.BM;
         plan->tileN = ki.BN;
         plan->tileK = ki.BK;
-        plan->gridX = 8 * k.wgsPerXcd;
+        plan->gridX = kXcds * k.wgsPerXcd;
         plan->kSteps = k.ksteps;
         plan->threads = ki.threads;
         plan->ldsBytes = ki.ldsBytes;
@@ -730,7 +735,7 @@ static igcStatus plan_backward_data_phases(const igcContext *handle, const Backw
             igcStatus st = choose(handle, l.pr, /*w_aligned=*/false, /*x_aligned=*/false, &l.id);
             if (st != IGC_STATUS_SUCCESS) return st;
             igcConvolutionForwardPlan plan;
-            st = fill_plan(l.id, &l.pr, &plan);
+            st = fill_plan(handle, l.id, &l.pr, &plan);
             if (st != IGC_STATUS_SUCCESS) return st;
             l.grid = plan.gridX;
             out->push_back(l);
@@ -778,10 +783,12 @@ static bool packed_phases(const BackwardDataProblem &b, PackedPhases *out) {
 // How to cut the reduction: as many ranges as keep all (tile, range) workgroups resident at
 // once (two per compute unit, four of the small fp32 tiles) - one more would leave a second, nearly empty round -, ranges
 // of an even number of steps and not shorter than 8; at most max_parts ranges.
-static void backward_filter_split(const BackwardFilterProblem &b, long long max_parts, int *splits, int *steps_per_split) {
+static void backward_filter_split(const igcContext *h, const BackwardFilterProblem &b, long long max_parts, int *splits,
+                                  int *steps_per_split) {
+    const long long cus = h->computeUnits;
     const KernelInfo *ki = kernel_info(b.kernel_id);
     const long long per_cu = ki && !ki->f64 && ki->gmode != 10 ? workgroups_per_cu(*ki) : 2;
-    long long want = std::max<long long>(1, (per_cu * kComputeUnits) / b.tiles);
+    long long want = std::max<long long>(1, (per_cu * cus) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));
     long long per = (b.ksteps + want - 1) / want;
@@ -812,6 +819,8 @@ igcStatus igcCreate(igcHandle_t *handle) {
     if (!handle) return IGC_STATUS_BAD_PARAM;
     igcContext *c = new (std::nothrow) igcContext;
     if (!c) return IGC_STATUS_ALLOC_FAILED;
+    const int cus = igc::query_compute_units();   // (0: no device to ask)
+    if (cus >= igc::kXcds) c->computeUnits = cus;
     *handle = c;
     return IGC_STATUS_SUCCESS;
 }
@@ -983,16 +992,91 @@ igcStatus igcGetConvolutionForwardOptionalWorkspaceSize(igcHandle_t handle, igcT
     pr.no_teams = true;   // (as the forward call does when it is lent a workspace)
     st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
-    st = fill_plan(id, &pr, nullptr);
+    st = fill_plan(handle, id, &pr, nullptr);
     if (st != IGC_STATUS_SUCCESS) return st;
     const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)pr.kp.K * pr.kp.NPQ;
     int per;
-    const int splits = pr.f64 ? 1 : forward_split(*kernel_info(id), pr.kp, packed, 1 << 20, &per);
+    const int splits = pr.f64 ? 1 : forward_split(handle, *kernel_info(id), pr.kp, packed, 1 << 20, &per);
     *sizeInBytes = splits > 1 ? (size_t)splits * pr.kp.y_bytes : 0;
     // a float problem that runs in tap-major order: room for the filter with the channel index innermost
     if (splits <= 1 && kernel_info(id)->gmode == 1 && !pr.f64 && pr.kp.RS > 1) *sizeInBytes = (size_t)pr.kp.w_bytes;
     // few channels and a zero border: room for x with the border written out
     if (splits <= 1 && padded_copy_bytes(*kernel_info(id), pr, xDesc) > 0) *sizeInBytes = (size_t)padded_copy_bytes(*kernel_info(id), pr, xDesc);
+    return IGC_STATUS_SUCCESS;
+}
+
+// One past the largest byte offset the kernels form for an existing element of each argument, in 64 bits from the
+// launch parameters: the gathered tensor at the last image, last reduction channel and the last row and column any
+// window reaches inside the image; the filter at the last row, last reduction channel and the tap of largest offset
+// (tap strides may be negative); the output at the last column and row of O_m.
+static void address_reach(const ConvKernelParams &k, int es_in, int es_out, long long reach[3]) {
+    auto last_inside = [](int outputs, int stride, int pad, int taps, int size) {
+        return std::min<long long>((long long)(outputs - 1) * stride - pad + (taps - 1), size - 1);
+    };
+    const long long hmax = last_inside(k.P, k.u, k.pad_h, k.R, k.H), wmax = last_inside(k.Q, k.v, k.pad_w, k.S, k.W);
+    reach[0] = hmax < 0 || wmax < 0
+                   ? 0
+                   : ((long long)(k.N - 1) * k.xsN + (long long)(k.C - 1) * k.xsC + hmax * k.xsH + wmax * k.xsW + 1) * es_in;
+    const long long tap_max = (long long)k.wTap0 + std::max<long long>(0, (long long)(k.R - 1) * k.wsTapR) +
+                              std::max<long long>(0, (long long)(k.S - 1) * k.wsTapS);
+    reach[1] = ((long long)(k.K - 1) * k.wsRow + (long long)(k.C - 1) * k.wsRed + tap_max + 1) * es_in;
+    reach[2] = ((long long)(k.N - 1) * k.ysN + (long long)(k.K - 1) * k.ysK + (long long)(k.P - 1) * k.ysP +
+                (long long)(k.Q - 1) * k.ysQ + 1) * es_out;
+}
+
+igcStatus igcSetComputeUnits(igcHandle_t handle, int computeUnits) {
+    if (!handle || computeUnits < kXcds || computeUnits > 4096) return IGC_STATUS_BAD_PARAM;
+    handle->computeUnits = computeUnits;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetComputeUnits(igcHandle_t handle, int *computeUnits) {
+    if (!handle || !computeUnits) return IGC_STATUS_BAD_PARAM;
+    *computeUnits = handle->computeUnits;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolutionForwardAddressReach(igcHandle_t handle, igcTensorDescriptor_t xDesc, igcFilterDescriptor_t wDesc,
+                                               igcConvolutionDescriptor_t convDesc, igcTensorDescriptor_t yDesc,
+                                               long long reachBytes[3], long long extentBytes[3]) {
+    if (!handle || !reachBytes || !extentBytes) return IGC_STATUS_BAD_PARAM;
+    Problem pr;
+    igcStatus st = validate(xDesc, wDesc, convDesc, yDesc, &pr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    int id = -1;
+    st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    st = fill_plan(handle, id, &pr, nullptr);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    address_reach(pr.kp, pr.bf16 ? 2 : (pr.f64 ? 8 : 4), pr.f64 ? 8 : 4, reachBytes);
+    extentBytes[0] = pr.kp.x_bytes; extentBytes[1] = pr.kp.w_bytes; extentBytes[2] = pr.kp.y_bytes;
+    return IGC_STATUS_SUCCESS;
+}
+
+igcStatus igcGetConvolutionBackwardDataAddressReach(igcHandle_t handle, igcFilterDescriptor_t wDesc, igcTensorDescriptor_t dyDesc,
+                                                    igcConvolutionDescriptor_t convDesc, igcTensorDescriptor_t dxDesc,
+                                                    long long reachBytes[3], long long extentBytes[3]) {
+    if (!handle || !reachBytes || !extentBytes) return IGC_STATUS_BAD_PARAM;
+    BackwardDataProblem b;
+    igcStatus st = validate_backward_data(wDesc, dyDesc, convDesc, dxDesc, &b);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    std::vector<PhaseLaunch> launches;
+    st = plan_backward_data_phases(handle, b, &launches);
+    if (st != IGC_STATUS_SUCCESS) return st;
+    const int es = b.bf16 ? 2 : (b.f64 ? 8 : 4), out_es = b.f64 ? 8 : 4;
+    for (int i = 0; i < 3; ++i) reachBytes[i] = 0;
+    for (const PhaseLaunch &l : launches) {
+        long long r[3];
+        address_reach(l.pr.kp, es, out_es, r);
+        // (a phase that meets no tap reads nothing; every phase's output offsets count from its own first element)
+        if (!l.pr.zero_steps) {
+            reachBytes[0] = std::max(reachBytes[0], r[0]);
+            reachBytes[1] = std::max(reachBytes[1], r[1]);
+        }
+        reachBytes[2] = std::max(reachBytes[2], l.dx_offset * out_es + r[2]);
+        if (l.dx_offset * out_es + (long long)l.pr.kp.y_bytes != b.dx_bytes) return IGC_STATUS_EXECUTION_FAILED;
+    }
+    extentBytes[0] = b.dy_bytes; extentBytes[1] = b.w_bytes; extentBytes[2] = b.dx_bytes;
     return IGC_STATUS_SUCCESS;
 }
 
@@ -1007,7 +1091,7 @@ igcStatus igcGetConvolutionForwardPlan(igcHandle_t handle, igcTensorDescriptor_t
     st = choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/true, &id);
     if (st != IGC_STATUS_SUCCESS) return st;
     igcConvolutionForwardPlan tmp;
-    st = fill_plan(id, &pr, &tmp);
+    st = fill_plan(handle, id, &pr, &tmp);
     if (st != IGC_STATUS_SUCCESS) return st;
     *plan = tmp;
     return IGC_STATUS_SUCCESS;
@@ -1072,9 +1156,9 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
         trial.no_teams = true;
         int tid_ = -1, per_ = 0;
         if (choose(handle, trial, ((uintptr_t)w % 16) == 0, ((uintptr_t)x % 16) == 0, &tid_) == IGC_STATUS_SUCCESS &&
-            fill_plan(tid_, &trial, &plan) == IGC_STATUS_SUCCESS) {
+            fill_plan(handle, tid_, &trial, &plan) == IGC_STATUS_SUCCESS) {
             const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)trial.kp.K * trial.kp.NPQ;
-            if (forward_split(*kernel_info(tid_), trial.kp, packed, (long long)(workSpaceSizeInBytes / trial.kp.y_bytes), &per_) > 1) {
+            if (forward_split(handle, *kernel_info(tid_), trial.kp, packed, (long long)(workSpaceSizeInBytes / trial.kp.y_bytes), &per_) > 1) {
                 pr = trial;
                 id = tid_;
                 cut_found = true;
@@ -1084,7 +1168,7 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
     if (!cut_found) {
         st = choose(handle, pr, /*w_aligned=*/((uintptr_t)w % 16) == 0, /*x_aligned=*/((uintptr_t)x % 16) == 0, &id);
         if (st != IGC_STATUS_SUCCESS) return st;
-        st = fill_plan(id, &pr, &plan);
+        st = fill_plan(handle, id, &pr, &plan);
         if (st != IGC_STATUS_SUCCESS) return st;
     }
     pr.kp.x = x;
@@ -1106,14 +1190,14 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
         ConvKernelParams &k = pr.kp;
         const bool packed = extent(yDesc->dim, yDesc->stride) == (long long)k.K * k.NPQ;
         int per;
-        splits = forward_split(*kernel_info(id), k, packed, (long long)(workSpaceSizeInBytes / k.y_bytes), &per);
+        splits = forward_split(handle, *kernel_info(id), k, packed, (long long)(workSpaceSizeInBytes / k.y_bytes), &per);
         if (splits > 1) {
             k.splits = splits;
             k.stepsPerSplit = per;
             k.ySplitBytes = k.y_bytes;
-            k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN * splits + 7) / 8);
-            k.wgsPerXcd = workgroups_per_xcd(*kernel_info(id), k.tilesPerXcd);
-            grid = 8 * k.wgsPerXcd;
+            k.tilesPerXcd = (int)(((long long)k.tilesM * k.tilesN * splits + kXcds - 1) / kXcds);
+            k.wgsPerXcd = workgroups_per_xcd(handle, *kernel_info(id), k.tilesPerXcd);
+            grid = kXcds * k.wgsPerXcd;
             k.y = workSpace;
             k.alpha = 1.f;
             k.beta = 0.f;
@@ -1205,7 +1289,7 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
             workSpaceSizeInBytes >= (size_t)b.w_bytes &&
             choose(handle, pr, /*w_aligned=*/true, /*x_aligned=*/((uintptr_t)dy % 16) == 0, &id) == IGC_STATUS_SUCCESS) {
             igcConvolutionForwardPlan plan;
-            st = fill_plan(id, &pr, &plan);
+            st = fill_plan(handle, id, &pr, &plan);
             if (st != IGC_STATUS_SUCCESS) return st;
             pr.kp.x = dy;
             pr.kp.w = workSpace;
@@ -1307,7 +1391,7 @@ igcStatus igcGetConvolutionBackwardFilterWorkspaceSize(igcHandle_t handle, igcTe
     const igcStatus st = validate_backward_filter(xDesc, dyDesc, convDesc, dwDesc, &b);
     if (st != IGC_STATUS_SUCCESS) return st;
     int splits, per;
-    backward_filter_split(b, 1 << 20, &splits, &per);
+    backward_filter_split(handle, b, 1 << 20, &splits, &per);
     // (the channel-vector kernels want their workspace even for a single range: see the entry point)
     *sizeInBytes = splits > 1 || b.pos_rows ? (size_t)splits * b.part_elems() * (b.pr.f64 ? 8 : 4) : 0;
     return IGC_STATUS_SUCCESS;
@@ -1327,13 +1411,13 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     const size_t part_bytes = (size_t)b.part_elems() * out_es;
     int splits, per;
     const long long room = workSpace ? (long long)(workSpaceSizeInBytes / part_bytes) : 0;
-    backward_filter_split(b, room, &splits, &per);
+    backward_filter_split(handle, b, room, &splits, &per);
     // Channel-vector kernels: with room for at least one part the results go to the workspace in accumulator
     // order (coalesced) and the summing kernel moves them to dw; writing dw's layout from the tile is slow.
     const bool positions = b.pos_rows != 0 && room >= 1;
     ConvKernelParams &k = b.pr.kp;
     igcConvolutionForwardPlan plan;
-    st = fill_plan(b.kernel_id, &b.pr, &plan);
+    st = fill_plan(handle, b.kernel_id, &b.pr, &plan);
     if (st != IGC_STATUS_SUCCESS) return st;
     k.tilesN = (int)b.tiles_n;
     const float a = f64 ? 0.f : *static_cast<const float *>(alpha), bt = f64 ? 0.f : *static_cast<const float *>(beta);
@@ -1343,9 +1427,9 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     k.splits = splits;
     k.stepsPerSplit = splits > 1 ? per : (int)(b.ksteps + (b.ksteps & 1));
     k.ySplitBytes = (uint32_t)part_bytes;
-    k.tilesPerXcd = (int)((b.tiles * splits + 7) / 8);
-    if ((long long)k.tilesPerXcd * 8 >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
-    k.wgsPerXcd = workgroups_per_xcd(*kernel_info(b.kernel_id), k.tilesPerXcd);
+    k.tilesPerXcd = (int)((b.tiles * splits + kXcds - 1) / kXcds);
+    if ((long long)k.tilesPerXcd * kXcds >= (1ll << 24)) return IGC_STATUS_NOT_SUPPORTED;
+    k.wgsPerXcd = workgroups_per_xcd(handle, *kernel_info(b.kernel_id), k.tilesPerXcd);
     if (splits > 1 || positions) {
         k.y = workSpace;
         k.alpha = 1.f; k.alpha64 = 1.0;
@@ -1362,7 +1446,7 @@ igcStatus igcConvolutionBackwardFilter(igcHandle_t handle, const void *alpha, ig
     if (getenv("IGCONV_DEBUG"))
         fprintf(stderr, "igconv: backward filter with '%s', %lld tiles x %d ranges of %d steps\n", kernel_info(b.kernel_id)->name,
                 b.tiles, splits, k.stepsPerSplit);
-    if (kernel_info(b.kernel_id)->launch(k, 8 * k.wgsPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
+    if (kernel_info(b.kernel_id)->launch(k, kXcds * k.wgsPerXcd, handle->stream) != 0) return IGC_STATUS_EXECUTION_FAILED;
     if (splits > 1 && f64 &&
         launch_sum_parts_f64(static_cast<const double *>(workSpace), static_cast<double *>(dw), b.out_elems, splits, b.out_elems,
                              a64, bt64, handle->stream) != 0)

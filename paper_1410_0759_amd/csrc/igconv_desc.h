@@ -10,6 +10,7 @@
 struct igcContext {
     void *stream = nullptr;
     int kernelOverride = -1;
+    int computeUnits = 256;   // of the device current when the handle was created (MI355X's 256 when there is none)
 };
 
 struct igcTensorStruct {

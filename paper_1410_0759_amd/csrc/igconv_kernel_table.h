@@ -77,6 +77,9 @@ int launch_sum_positions(const float *parts, float *out, uint32_t n, int count, 
 int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count, uint32_t stride, double alpha, double beta,
                          void *stream);
 
+// Compute units of the current device, 0 when the runtime finds none (igconv_probe.hip).
+int query_compute_units();
+
 int kernel_count();
 const KernelInfo *kernel_info(int id);  // nullptr when out of range
 

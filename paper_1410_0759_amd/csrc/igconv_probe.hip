@@ -79,6 +79,18 @@ __global__ __launch_bounds__(256) void mfma_rate_f64(int iters, double a0) {
 
 using namespace igc;
 
+namespace igc {
+int query_compute_units() {
+    int dev = 0, n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n < 1 || hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return n;
+}
+}  // namespace igc
+
 extern "C" {
 
 igcStatus igcGetDeviceProperties(igcHandle_t handle, int *computeUnits, int *clockKHz) {

@@ -443,3 +443,73 @@ def test_backward_filter_workspace_fits_the_no_alloc_scratch_array():
             conv = ig.ConvolutionDescriptor().set(pad, pad, u, u, 1)
             worst = max(worst, ig.get_backward_filter_workspace_size(h, x, dy, conv, dw))
     assert 0 < worst <= ig.NOALLOC_SCRATCH_BYTES, worst
+
+
+def _random_layer(rng):
+    """A random layer the library accepts: small sizes, every kind of stride, border and layout."""
+    N, C, K = int(rng.integers(1, 5)), int(rng.integers(1, 40)), int(rng.integers(1, 140))
+    R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+    pad = (int(rng.integers(0, R)), int(rng.integers(0, S)))
+    stride = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    H = int(rng.integers(max(1, R - 2 * pad[0]), 30))
+    W = int(rng.integers(max(1, S - 2 * pad[1]), 30))
+    return N, C, H, W, K, R, S, pad, stride
+
+
+def test_address_reach_stays_inside_the_buffer_extents():
+    """For every accepted problem the largest offset the kernels' address arithmetic forms for an existing element
+    - evaluated by the library in 64 bits from the launch parameters of the kernel it would run - lies inside the
+    extent its buffer descriptor is given, and below 2^31: forward and backward data (all stride phases), the three
+    data types, both layouts, the workloads at full size."""
+    h = ig.Handle()
+    rng = np.random.default_rng(14100759)
+    dts = (ig.IGC_DATA_FLOAT, ig.IGC_DATA_BFLOAT16, ig.IGC_DATA_DOUBLE)
+    cases = [_random_layer(rng) for _ in range(400)]
+    cases += [(w_.N, w_.C, w_.H, w_.W, w_.K, w_.R, w_.S, (w_.pad_h, w_.pad_w), (w_.u, w_.v)) for w_ in wl.WORKLOADS]
+    seen_modes = set()
+    for i, (N, C, H, W, K, R, S, pad, stride) in enumerate(cases):
+        dt = dts[i % 3]
+        ydt = ig.IGC_DATA_DOUBLE if dt == ig.IGC_DATA_DOUBLE else ig.IGC_DATA_FLOAT
+        nhwc = (i // 3) % 2 == 1
+        xs = (H * W * C, 1, W * C, C) if nhwc else None
+        x, w, c, y = _descs(N, C, H, W, K, R, S, pad, stride, i % 2, dt, xs=xs, ydt=ydt)
+        n, k, p, q = y.get()[1]
+        if nhwc:
+            y = ig.TensorDescriptor().set(ydt, n, k, p, q, (p * q * k, 1, q * k, k))
+        seen_modes.add(ig.get_plan(h, x, w, c, y).gatherMode)
+        reach, extent = ig.get_forward_address_reach(h, x, w, c, y)
+        es = {ig.IGC_DATA_FLOAT: 4, ig.IGC_DATA_BFLOAT16: 2, ig.IGC_DATA_DOUBLE: 8}[dt]
+        assert extent[1] == K * C * R * S * es and reach[1] == extent[1]          # the packed filter is read to its end
+        assert reach[2] == extent[2] == n * k * p * q * (8 if ydt == ig.IGC_DATA_DOUBLE else 4)
+        assert 0 < reach[0] <= extent[0] == N * C * H * W * es
+        assert all(e < 2 ** 31 for e in extent)
+        # backward data: dy and dx exchange the roles; dx has the input's type rule (float for bfloat16 inputs)
+        dyd = ig.TensorDescriptor().set(dt, n, k, p, q, (p * q * k, 1, q * k, k) if nhwc else (k * p * q, p * q, q, 1))
+        dxd = ig.TensorDescriptor().set(ydt, N, C, H, W, xs or (C * H * W, H * W, W, 1))
+        reach, extent = ig.get_backward_data_address_reach(h, w, dyd, c, dxd)
+        assert 0 < reach[0] <= extent[0] and 0 < reach[1] <= extent[1] and 0 < reach[2] <= extent[2], (cases[i], reach, extent)
+        # every element of dx belongs to some phase: the last one is reached
+        assert reach[2] == extent[2]
+    assert {0, 3, 14} <= seen_modes    # (generic, nine-tap table and masked plans were among them)
+
+
+def test_plans_follow_the_compute_unit_count_of_the_handle():
+    """The handle carries the device's compute-unit count (256 without a device); persistent grids and the choice
+    between tile shapes follow it."""
+    h = ig.Handle()
+    assert ig.get_compute_units(h) == 256      # no GPU here: MI355X's count stands in
+    w_ = wl.by_index(3)
+    d = _descs(w_.N, w_.C, w_.H, w_.W, w_.K, w_.R, w_.S, (w_.pad_h, w_.pad_w), (w_.u, w_.v), w_.mode, 0)
+    p256 = ig.get_plan(h, *d)
+    ig.set_compute_units(h, 304)
+    assert ig.get_compute_units(h) == 304
+    p304 = ig.get_plan(h, *d)
+    ig.set_compute_units(h, 64)
+    p64 = ig.get_plan(h, *d)
+    # cfg 3 has thousands of tiles: the persistent grid is the number of workgroups the chip holds at once
+    per_cu = p256.gridX // 256
+    assert per_cu in (1, 2, 3, 4) and p256.gridX == 256 * per_cu
+    assert p304.gridX == 304 * (p304.gridX // 304) and p64.gridX == 64 * (p64.gridX // 64)
+    for bad in (0, 7, 5000):
+        with pytest.raises(ig.IgcError):
+            ig.set_compute_units(h, bad)
