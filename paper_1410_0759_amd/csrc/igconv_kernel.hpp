@@ -17,9 +17,16 @@
 //  * MFMA: wave (wm, wn) owns a (BM/WM) x (BN/WN) block of the output tile, made of
 //    32x32 MFMA blocks (v_mfma_f32_32x32x2_f32 or v_mfma_f32_32x32x16_bf16).
 // LDS tiles are stored [row][k] with k contiguous and a row stride of BK plus 16
-// bytes: a lane reads 16 bytes of k for its row, which is bank-conflict free because
-// the stride is an odd multiple of 16 bytes.  Which k a lane feeds to which MFMA is
-// a free choice as long as both operands agree (the sum over k commutes).
+// bytes, an odd multiple of 16: a lane reads 16 bytes of k for its row, and 16
+// consecutive rows then start in 16 different groups of four banks, so the fragment
+// reads and the D_m writes (lane = row) of 16 lanes meet no conflict.  The F_m writes
+// do: they put 8 lanes (32 for element-wise loads) along one row, 128 contiguous
+// bytes, and the next row starts 144 bytes on, i.e. four banks into the first row's
+// wrap - a two-way conflict on those banks.  The counters agree that conflicts exist
+// (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE: 17 % on the first-layer workload, 25 %
+// and 33 % on the two 3x3 ones), while LDS is active 14-28 % of the time: not what
+// bounds these kernels.  Which k a lane feeds to which MFMA is a free choice as long
+// as both operands agree (the sum over k commutes).
 //
 // Every global access goes through a buffer descriptor limited to the tensor's
 // extent; an element that must read as zero (zero border of eq. 3, tile tails) is
@@ -274,7 +281,7 @@ struct KernelConfig {
     static constexpr int VEC = 16 / ESIZE;           // elements per 16-byte LDS access
     static constexpr int KG = 2 * VEC;               // reduction elements per full k-group
     // LDS row stride: at least BK plus 16 bytes, and an odd number of 16-byte units, so
-    // that 16-byte accesses of consecutive rows fall on distinct banks
+    // that 16-byte accesses of 16 consecutive rows fall on distinct banks
     static constexpr int LDV = (BK / VEC + 1) | 1;
     static constexpr int LD = LDV * VEC;
     static constexpr int A_ELEMS = BM * LD, B_ELEMS = BN * LD;
