@@ -1220,11 +1220,10 @@ igcStatus igcConvolutionBiasActivationForward(igcHandle_t handle, const void *al
                 if (launch_pad_image(static_cast<const float *>(x), static_cast<float *>(workSpace), k.N, k.C, k.H, k.W, k.pad_h, k.pad_w,
                                      xDesc->stride, mWp, mHp, mC, handle->stream) != 0)
                     return IGC_STATUS_EXECUTION_FAILED;
-                const int saved = handle->kernelOverride;
-                handle->kernelOverride = -1;
-                st = igcConvolutionBiasActivationForward(handle, alpha, &xd, workSpace, wDesc, w, &cd, nullptr, 0, beta, bias, activation,
+                igcContext inner = *handle;   // (same stream and device; the caller's handle is not touched)
+                inner.kernelOverride = -1;
+                st = igcConvolutionBiasActivationForward(&inner, alpha, &xd, workSpace, wDesc, w, &cd, nullptr, 0, beta, bias, activation,
                                                          yDesc, y);
-                handle->kernelOverride = saved;
                 // (a refusal comes from the checks before any launch on y: the pass below still runs as planned)
                 if (st != IGC_STATUS_NOT_SUPPORTED) return st;
             }
@@ -1329,11 +1328,10 @@ igcStatus igcConvolutionBackwardData(igcHandle_t handle, const void *alpha, igcF
                                      mK, mC, mv, handle->stream) != 0)
             return IGC_STATUS_EXECUTION_FAILED;
         const float one = 1.f, zero = 0.f;
-        const int saved = handle->kernelOverride;
-        handle->kernelOverride = -1;   // (the override names a kernel for the caller's problem, not for this one)
-        st = igcConvolutionBiasActivationForward(handle, &one, &xd, dy, &fd, fpack, &cd, nullptr, 0, &zero, nullptr,
+        igcContext inner = *handle;   // (same stream and device; an override names a kernel for the caller's problem, not for this one)
+        inner.kernelOverride = -1;
+        st = igcConvolutionBiasActivationForward(&inner, &one, &xd, dy, &fd, fpack, &cd, nullptr, 0, &zero, nullptr,
                                                  IGC_ACTIVATION_IDENTITY, &yd, ypack);
-        handle->kernelOverride = saved;
         // (a refusal comes from the checks before any launch: nothing of dx is written yet, the phases run one by one)
         if (st == IGC_STATUS_NOT_SUPPORTED) goto per_phase;
         if (st != IGC_STATUS_SUCCESS) return st;

@@ -245,7 +245,8 @@ enum GatherMode {
     // Backward-filter: the generic gather with the roles of the two index sets exchanged.
     // Columns are filter elements (c,r,s), the reduction runs over output pixels (n,p,q);
     // the first operand is dy, read through its strides with a per-step decode of (n,p,q);
-    // the reduction may be cut into several ranges, one workgroup each (see the main loop).
+    // the reduction may be cut into several ranges, one workgroup each.  (Modes 6, 8 and 9 are
+    // the kernel of igconv_kernel_wgrad.hpp.)
     GATHER_WGRAD = 6,
     // Backward-filter with the columns ordered (tap, channel) and one tap per tile: lanes run
     // along the reduction index (n,p,q) - consecutive pixels, coalesced loads - and decode it
@@ -308,9 +309,8 @@ struct KernelConfig {
     static_assert(TEAMS_ == 1 || ((GMODE_ == GATHER_NOPAD || GMODE_ == GATHER_TAPS9) && !BF16_ && BM_ * BN_ * 4 <= TEAM_LDS_BYTES),
                   "teams: fp32 kernels whose steps stand alone; a team's results pass through its LDS");
     static_assert(!(GMODE == GATHER_TAPMAJOR && VECA), "tap-major filter reads are strided, never 16-byte");
-    static_assert((GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD) || (!VECA && 256 % BK == 0),
-                  "one reduction index per thread, element-wise first operand");
-    static_assert((GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD) || BK == 32, "a half wavefront spans the reduction indices of a step");
+    static_assert(GMODE != GATHER_WGRAD && GMODE != GATHER_WGRAD_TAP && GMODE != GATHER_WGRAD_NOPAD,
+                  "the backward-filter gathers have their own kernel (igconv_kernel_wgrad.hpp)");
     static_assert(GMODE != GATHER_TAPS9 || (BK % 9 == 0 && KPT % 9 == 0), "whole channels of nine taps per thread");
 };
 
@@ -322,13 +322,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     constexpr bool SHORT_LAST = Cfg::GMODE == GATHER_NOPAD_TABLE_SHORT;
     constexpr bool ODD_LAST = Cfg::GMODE == GATHER_NOPAD_TABLE_ODD;
     constexpr int GM = SHORT_LAST || ODD_LAST ? (int)GATHER_NOPAD_TABLE : Cfg::GMODE;
-    constexpr bool GEN = GM == GATHER_GENERIC || GM == GATHER_WGRAD;  // per-element window test
+    constexpr bool GEN = GM == GATHER_GENERIC;  // per-element window test
     constexpr bool NOPADX = GM == GATHER_NOPAD || GM == GATHER_NOPAD_TABLE;
     constexpr bool MSK = GM == GATHER_MASKED;
     constexpr bool MSK_STRIDED = MSK && !Cfg::VECA;   // filter through strides, one reduction index per thread
-    constexpr bool WGN = GM == GATHER_WGRAD_NOPAD;
-    constexpr bool WG = GM == GATHER_WGRAD || GM == GATHER_WGRAD_TAP || WGN;   // backward filter: dy as first operand
-    constexpr bool WGT = GM == GATHER_WGRAD_TAP || WGN;                        // lanes along the reduction index
     using elem_t = typename std::conditional<Cfg::BF16, uint16_t, float>::type;
 
     __shared__ __attribute__((aligned(16))) elem_t lds[Cfg::TEAMS * 2 * (Cfg::A_ELEMS + Cfg::B_ELEMS)];
@@ -361,8 +358,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     };
     if (tile_number(0) >= tiles_total) return;
     // The tile whose loads are being issued ("tile state", set by setup_tile below).  A tile
-    // number of tiles_total stands for "no tile": its columns (or, for GATHER_WGRAD, its
-    // reduction range) lie beyond the end, so that all it gathers is zeros.
+    // number of tiles_total stands for "no tile": its columns lie beyond the end, so that all
+    // it gathers is zeros.
     int m0 = 0, n0 = 0, split = 0, t_begin = 0;
 
     const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
@@ -464,7 +461,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     // in the other set to be written to LDS.
     u32x4 a_vec[2][Cfg::VECA ? A_PASSES : 1];
     elem_t a_sca[2][Cfg::VECA ? 1 : A_PASSES];
-    elem_t b_val[2][KPT > BN / 8 ? KPT : BN / 8];
+    elem_t b_val[2][KPT];
     // Per-lane decode, lane L standing for element L of this wavefront's run of the
     // step.  GATHER_GENERIC: byte offset of the tap relative to the window origin
     // (dec_so) and the packed tap (dec_tap).  GATHER_NOPAD / GATHER_TAPMAJOR: the
@@ -490,18 +487,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     const uint32_t ms_dd1 = ms_dir * ((uint32_t)p.xsH - ms_sm1 * (uint32_t)p.xsW) * ES;
     const uint32_t ms_dd2 = ((uint32_t)p.xsC - ms_dir * (ms_sm1 * (uint32_t)p.xsW + ms_rm1 * (uint32_t)p.xsH)) * ES;
     const uint32_t ms_db2 = 0u - ms_dir * ((uint32_t)p.RS - 1u);
-    uint32_t a_jo = 0;  // backward filter: offset of this thread's reduction index in the first operand
-    // GATHER_WGRAD_TAP: this thread's reduction index of a step is lane % 32; its columns are
-    // BN/8 consecutive channels starting at wave*(BN/4) + (lane/32)*(BN/8) of the tile.  Per
-    // tile: the tap's window offset and the scalar offset of the wavefront's first channel;
-    // per step: the pixel's offset for this tap (window test folded in).
-    constexpr int WT_E = BN / 8;
-    const int wt_kk = lane & 31;
-    const int wt_col = wave * (BN / 4) + half * WT_E;
-    const uint32_t wt_laneoff = (uint32_t)(half * WT_E) * (uint32_t)p.xsN * ES;
-    int sc_tap_h = 0, sc_tap_w = 0, sc_tapidx = 0;
-    uint32_t wn_col[WGN ? WT_E : 1];   // GATHER_WGRAD_NOPAD: offsets of this thread's columns (c,r,s) in x
-    uint32_t sc_colso = 0, wt_pix = kOutOfRange, wt_n = 0, wt_rem = 0, wt_j = 0;
+    uint32_t a_jo = 0;  // GATHER_MASKED through strides: offset of this thread's reduction index in the filter
 
     // F_m tile: rows m0.., the step's reduction indices; zero beyond K and beyond the
     // reduction range.  The per-thread part of the offset is fixed, the step's part is a
@@ -523,7 +509,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             const uint32_t off = (uint32_t)row * (uint32_t)p.wsRow + ch * (uint32_t)p.wsRed + (uint32_t)p.wTap0 +
                                  r * (uint32_t)p.wsTapR + sx * (uint32_t)p.wsTapS;
             a_voff[ps] = ok ? off * ES : kOutOfRange;
-        } else if constexpr (WG || MSK_STRIDED)
+        } else if constexpr (MSK_STRIDED)
             // (rows beyond K are never stored: they may read row 0; the reduction index's part of
             // the offset, which also carries the out-of-range marker, is added per step)
             a_voff[ps] = (uint32_t)(row < p.K ? row : 0) * (uint32_t)p.wsRow * ES;
@@ -542,48 +528,16 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         }
         if constexpr (Cfg::TEAMS > 1) t_begin = team * p.stepsPerSplit;   // (the host: one range, stepsPerSplit steps per team)
         m0 = (tile % p.tilesM) * BM;
-        if constexpr (WGN) {
-            n0 = (tile / p.tilesM) * BN;
-#pragma unroll
-            for (int e = 0; e < WT_E; ++e) {
-                // column i -> (c, r, s) with PQ = R*S and Q = S of the filter; tap in reading direction
-                const uint32_t i = (uint32_t)(n0 + wt_col + e);
-                const uint32_t c = magic_div(i, p.mPQ);
-                const uint32_t rs = i - c * (uint32_t)p.PQ;
-                const uint32_t r = magic_div(rs, p.mQ);
-                const uint32_t sx = rs - r * (uint32_t)p.Q;
-                const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r, ts = p.flip ? (uint32_t)p.Q - 1u - sx : sx;
-                wn_col[e] = i < (uint32_t)p.NPQ ? (c * (uint32_t)p.xsN + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES : kOutOfRange;
-            }
-        } else if constexpr (WGT) {
-            // column tile -> (tap, channel block); PQ holds the channel blocks per tap, Q and P
-            // the filter's S and R
-            const uint32_t tn = (uint32_t)(tile / p.tilesM);
-            const uint32_t tap = magic_div(tn, p.mPQ);
-            const uint32_t r = magic_div(tap, p.mQ);
-            const uint32_t sx = tap - r * (uint32_t)p.Q;
-            sc_tapidx = (int)tap;
-            sc_tap_h = (int)(p.flip ? (uint32_t)p.R - 1u - r : r) - p.pad_h;
-            sc_tap_w = (int)(p.flip ? (uint32_t)p.Q - 1u - sx : sx) - p.pad_w;
-            n0 = (int)(tn - tap * (uint32_t)p.PQ) * BN;   // first channel of the tile
-            sc_colso = (uint32_t)(n0 + wave * (BN / 4)) * (uint32_t)p.xsN * ES;
-        } else {
-            n0 = (tile / p.tilesM) * BN;
-            setup_column();
-            setup_taps();
-        }
+        n0 = (tile / p.tilesM) * BN;
+        setup_column();
+        setup_taps();
         setup_rows();
     };
 
     // Start of the load of tile number tau (reduction step tau), in two halves so that
     // each fits between two MFMAs.
     auto decode1 = [&](int tau) {
-        if constexpr (WGT) {
-            sc_tau = __builtin_amdgcn_readfirstlane(tau);
-            wt_j = (uint32_t)(sc_tau * BK + wt_kk);
-            wt_n = magic_div(wt_j, p.mRS);
-            wt_rem = wt_j - wt_n * (uint32_t)p.RS;
-        } else if constexpr (MSK) {
+        if constexpr (MSK) {
             // first index of this wavefront's run -> (c, r, s), all in scalar registers
             sc_tau = __builtin_amdgcn_readfirstlane(tau);
             const uint32_t i0 = (uint32_t)(sc_tau * BK + kpart * KPT);
@@ -637,16 +591,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         }
     };
     auto decode2 = [&]() {
-        if constexpr (WGT) {
-            const uint32_t pp = magic_div(wt_rem, p.mS);
-            const uint32_t qq = wt_rem - pp * (uint32_t)p.S;
-            const bool live = wt_j < (uint32_t)p.CRS;
-            const uint32_t hh = pp * (uint32_t)p.redMulH + (uint32_t)sc_tap_h;   // (wraps below zero: fails the test)
-            const uint32_t ww = qq * (uint32_t)p.redMulW + (uint32_t)sc_tap_w;
-            const bool ok = live && (WGN || (hh < (uint32_t)p.H && ww < (uint32_t)p.W));   // (no padding: always inside)
-            wt_pix = ok ? (wt_n * (uint32_t)p.xsC + hh * (uint32_t)p.xsH + ww * (uint32_t)p.xsW) * ES + (WGN ? 0u : wt_laneoff) : kOutOfRange;
-            a_jo = live ? (wt_n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES : kOutOfRange;
-        } else if constexpr (MSK) {
+        if constexpr (MSK) {
             if constexpr (MSK_STRIDED) {
                 // first operand: this thread's reduction index (the same in all its passes) through the
                 // reduction and tap strides
@@ -672,23 +617,11 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         } else if constexpr (GEN || GM == GATHER_NOPAD) {
             const uint32_t r = magic_div(dec_rs, p.mS);
             const uint32_t sx = dec_rs - r * (uint32_t)p.S;
-            // window coordinates of the element: the tap, inverted for eq. 2; for
-            // GATHER_WGRAD the reduction index is an output pixel and they are (p*u, q*v)
-            const uint32_t tr = (p.flip ? (uint32_t)p.R - 1u - r : r) * (GM == GATHER_WGRAD ? (uint32_t)p.redMulH : 1u);
-            const uint32_t ts = (p.flip ? (uint32_t)p.S - 1u - sx : sx) * (GM == GATHER_WGRAD ? (uint32_t)p.redMulW : 1u);
+            // window coordinates of the element: the tap, inverted for eq. 2
+            const uint32_t tr = p.flip ? (uint32_t)p.R - 1u - r : r;
+            const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
             const uint32_t so = (dec_c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * ES;
             const bool live = dec_il < (uint32_t)p.CRS;
-            if constexpr (GM == GATHER_WGRAD) {
-                // first operand: this thread's reduction index (the same in all its passes)
-                const uint32_t ja = (uint32_t)(sc_tau * BK + a_kk[0]);
-                const uint32_t n = magic_div(ja, p.mRS);
-                const uint32_t rem = ja - n * (uint32_t)p.RS;
-                const uint32_t pp = magic_div(rem, p.mS);
-                const uint32_t qq = rem - pp * (uint32_t)p.S;
-                a_jo = ja < (uint32_t)p.CRS
-                           ? (n * (uint32_t)p.wsRed + pp * (uint32_t)p.wsTapR + qq * (uint32_t)p.wsTapS) * ES
-                           : kOutOfRange;
-            }
             if constexpr (GEN) {
                 dec_so = so;
                 dec_tap = live ? ((tr << 16) | ts) : 0x80000000u;  // i >= CRS: never in range
@@ -698,7 +631,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
             // When C*R*S is not a multiple of BK the last step is ragged: on entering it
             // (once per tile) the filter offsets of the indices beyond the range are
             // replaced by the out-of-range marker.
-            if (GM != GATHER_WGRAD && sc_tau == p.tail_step) {
+            if (sc_tau == p.tail_step) {
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps)
                     a_voff[ps] = (uint32_t)(sc_tau * BK + a_kk[ps]) < (uint32_t)p.CRS ? a_voff[ps] : kOutOfRange;
@@ -718,7 +651,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     };
     auto load_a = [&](int set, int tau, int ps) {
         uint32_t voffa = a_voff[ps], soff;
-        if constexpr (WG || MSK_STRIDED) {
+        if constexpr (MSK_STRIDED) {
             voffa += a_jo;
             soff = 0;
         } else if constexpr (GM == GATHER_TAPMAJOR || GM == GATHER_TAPS9) {
@@ -741,15 +674,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     // D_m tile, element e of this lane's column.
     auto load_b = [&](int set, int e) __attribute__((always_inline)) {
         uint32_t vo, so;
-        if constexpr (WGN) {
-            // (a dead reduction index or a column past the end carries the out-of-range marker; when
-            // both do, the sum wraps to a valid offset, but such a column is never stored)
-            vo = wt_pix + wn_col[e];
-            so = 0;
-        } else if constexpr (WGT) {
-            vo = wt_pix;
-            so = sc_colso + (uint32_t)e * (uint32_t)p.xsN * ES;
-        } else if constexpr (MSK) {
+        if constexpr (MSK) {
             // bit 0 of the shifted mask: 1 when the tap lies outside the image (bit 63: the index is past the end);
             // shifted to bit 31 it puts the offset out of range (a valid offset lies below 2^31)
             const uint32_t bit = (int32_t)ms_left < 0 ? 63u : ms_bit;
@@ -817,10 +742,6 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
     constexpr bool B_W16 = (KPT * ES) % 16 == 0;
     constexpr int B_WE = B_W16 ? VEC : VEC / 2;  // elements per write
     auto write_b = [&](int set, int buf, int q) {
-        if constexpr (WGT) {   // one element: channel wt_col + q, this thread's reduction index
-            ldsB[buf * Cfg::B_ELEMS + (wt_col + q) * LD + wt_kk] = b_val[set][q];
-            return;
-        }
         elem_t *const dst = ldsB + buf * Cfg::B_ELEMS + jl * LD + kpart * KPT + q * B_WE;
         uint32_t v[4];
         if constexpr (Cfg::BF16) {
@@ -842,8 +763,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
 
     // Moving one tile is a list of small items: NL load items (decode halves, filter
     // loads, gathered elements) and NW LDS-write items.
-    constexpr int NB_ELEMS = WGT ? WT_E : KPT;   // gathered elements per thread and step
-    constexpr int NW_A = A_PASSES, NW_B = WGT ? WT_E : KPT / B_WE, NW = NW_A + NW_B;
+    constexpr int NB_ELEMS = KPT;   // gathered elements per thread and step
+    constexpr int NW_A = A_PASSES, NW_B = KPT / B_WE, NW = NW_A + NW_B;
     // (GATHER_MASKED: an element is two items, its load and the step to the next one, so that neither is too long
     // for the gap between two MFMAs)
     constexpr int NL = 2 + A_PASSES + (MSK ? 2 : 1) * NB_ELEMS;
@@ -1044,18 +965,16 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
         // The last two steps of this tile request the first two steps of the workgroup's next
         // tile (of "no tile" after the last one): its operands arrive and its first fragments
         // are read while this tile is still being multiplied and stored.
-        const int out_m0 = m0, out_n0 = n0, out_split = split, out_tap = sc_tapidx;
+        const int out_m0 = m0, out_n0 = n0, out_split = split;
         const int next = tile_number(it);
         setup_tile(next);
         load_bias<MB>(p, m0 + wm * Cfg::TM, l32, bias_next);
         step(std::integral_constant<int, 0>{}, t_begin);
         step_groups(std::integral_constant<int, 1>{}, std::integral_constant<int, SHORT_LAST ? G / 2 : (ODD_LAST ? 0 : G)>{}, t_begin + 1);
         // (each range of a cut reduction writes its own copy of the output, y_bytes long)
-        // (GATHER_WGRAD_TAP: the columns are channels, 'R*S' elements apart; the tile's tap moves the base)
-        const uint32_t ytap = GM == GATHER_WGRAD_TAP ? (uint32_t)out_tap * 4u : 0u;
-        const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes + ytap;
+        const uint32_t ybase = (uint32_t)out_split * p.ySplitBytes;
         const __amdgpu_buffer_rsrc_t ybuf = __builtin_amdgcn_make_buffer_rsrc(
-            static_cast<char *>(p.y) + ybase, 0, p.y_bytes - ytap, kBufferWord3);
+            static_cast<char *>(p.y) + ybase, 0, p.y_bytes, kBufferWord3);
         if constexpr (Cfg::TEAMS > 1) {
             // The host gives a workgroup of teams one tile, so nothing in LDS is needed any more: the
             // teams after the first leave their sums at the start of their LDS (16 bytes per lane and
@@ -1087,7 +1006,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::MIN_WAVES) void igconv_fwd_kerne
                             for (int e = 0; e < 4; ++e) acc[mb][nb][4 * c + e] += o[e];
                         }
         }
-        store_tile<Cfg::SWAP, MB, NB, WGT>(p, ybuf, acc, bias_cur, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
+        store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bias_cur, out_m0 + wm * Cfg::TM, out_n0 + wn * Cfg::TN, half, l32);
         if (next >= tiles_total) break;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) bias_cur[mb] = bias_next[mb];

@@ -1,30 +1,50 @@
 // Backward-filter kernels: the generic gather with columns (c,r,s) and the reduction over
 // (n,p,q), plus the kernel that adds up the ranges of a cut reduction.
 #include "igconv_instantiate.hpp"
+#include "igconv_kernel_wgrad.hpp"
 
-//    name, bf16, BM, BN, BK, WM, WN, swap, veca, gather mode
-#define IGC_KERNEL_LIST(X) \
-    X("f32 64x128x32 wgrad", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
-    X("f32 128x128x32 wgrad", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
-    X("bf16 64x128x32 wgrad", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
-    X("bf16 128x128x32 wgrad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD) \
-    X("f32 64x64x32 wgrad tap", false, 64, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("f32 128x64x32 wgrad tap", false, 128, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("f32 64x128x32 wgrad tap", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("f32 128x128x32 wgrad tap", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("bf16 64x64x32 wgrad tap", true, 64, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("bf16 128x64x32 wgrad tap", true, 128, 64, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("bf16 64x128x32 wgrad tap", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("bf16 128x128x32 wgrad tap", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_TAP) \
-    X("f32 64x128x32 wgrad nopad", false, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
-    X("f32 96x128x32 wgrad nopad", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD_NOPAD) \
-    X("f32 128x128x32 wgrad nopad", false, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
-    X("f32 96x128x32 wgrad tap", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD_TAP) \
-    X("f32 96x128x32 wgrad", false, 96, 128, 32, 1, 4, false, false, GATHER_WGRAD) \
-    X("bf16 64x128x32 wgrad nopad", true, 64, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD) \
-    X("bf16 128x128x32 wgrad nopad", true, 128, 128, 32, 2, 2, false, false, GATHER_WGRAD_NOPAD)
+//    name, bf16, BM, BN, BK, WM, WN, gather mode
+#define IGC_WGRAD_LIST(X) \
+    X("f32 64x128x32 wgrad", false, 64, 128, 32, 2, 2, GATHER_WGRAD) \
+    X("f32 128x128x32 wgrad", false, 128, 128, 32, 2, 2, GATHER_WGRAD) \
+    X("bf16 64x128x32 wgrad", true, 64, 128, 32, 2, 2, GATHER_WGRAD) \
+    X("bf16 128x128x32 wgrad", true, 128, 128, 32, 2, 2, GATHER_WGRAD) \
+    X("f32 64x64x32 wgrad tap", false, 64, 64, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("f32 128x64x32 wgrad tap", false, 128, 64, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("f32 64x128x32 wgrad tap", false, 64, 128, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("f32 128x128x32 wgrad tap", false, 128, 128, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("bf16 64x64x32 wgrad tap", true, 64, 64, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("bf16 128x64x32 wgrad tap", true, 128, 64, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("bf16 64x128x32 wgrad tap", true, 64, 128, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("bf16 128x128x32 wgrad tap", true, 128, 128, 32, 2, 2, GATHER_WGRAD_TAP) \
+    X("f32 64x128x32 wgrad nopad", false, 64, 128, 32, 2, 2, GATHER_WGRAD_NOPAD) \
+    X("f32 96x128x32 wgrad nopad", false, 96, 128, 32, 1, 4, GATHER_WGRAD_NOPAD) \
+    X("f32 128x128x32 wgrad nopad", false, 128, 128, 32, 2, 2, GATHER_WGRAD_NOPAD) \
+    X("f32 96x128x32 wgrad tap", false, 96, 128, 32, 1, 4, GATHER_WGRAD_TAP) \
+    X("f32 96x128x32 wgrad", false, 96, 128, 32, 1, 4, GATHER_WGRAD) \
+    X("bf16 64x128x32 wgrad nopad", true, 64, 128, 32, 2, 2, GATHER_WGRAD_NOPAD) \
+    X("bf16 128x128x32 wgrad nopad", true, 128, 128, 32, 2, 2, GATHER_WGRAD_NOPAD)
 
-IGC_DEFINE_GROUP(kGroupWgrad)
+namespace igc {
+
+template <class Cfg>
+static int launch_wgrad(const ConvKernelParams &p, int grid, void *stream) {
+    return launch_checked(&igconv_wgrad_kernel<Cfg>, "igconv_wgrad_kernel", p, grid, Cfg::THREADS, stream);
+}
+
+#define IGC_WGRAD_INSTANTIATE(NAME, BF16, BM, BN, BK, WM, WN, GMODE) \
+    template __global__ void igconv_wgrad_kernel<WgradConfig<BF16, BM, BN, BK, WM, WN, GMODE>>(const ConvKernelParams);
+IGC_WGRAD_LIST(IGC_WGRAD_INSTANTIATE)
+
+#if !defined(__HIP_DEVICE_COMPILE__)
+#define IGC_WGRAD_ROW(NAME, BF16, BM, BN, BK, WM, WN, GMODE)                                         \
+    {NAME, BF16, BM, BN, BK, false, false, GMODE, 256, WgradConfig<BF16, BM, BN, BK, WM, WN, GMODE>::LDS_BYTES, \
+     &launch_wgrad<WgradConfig<BF16, BM, BN, BK, WM, WN, GMODE>>},
+static const KernelInfo kWgradRows[] = {IGC_WGRAD_LIST(IGC_WGRAD_ROW)};
+const KernelGroup kGroupWgrad = {kWgradRows, sizeof(kWgradRows) / sizeof(kWgradRows[0])};
+#endif
+
+}  // namespace igc
 
 namespace igc {
 
