@@ -29,12 +29,15 @@
 //  * transpose the rows of step tau - DA (requested DA intervals ago) and write them to plane
 //    stage (tau - DA) mod SA; they are read from step tau - DA on, i.e. PRE - DA intervals
 //    later: with SLACK = 1 the movers run one interval ahead of need, with 0 just in time;
-//  * request the patch of step tau - 1 into patch stage (tau - 1) mod SB, and before the
-//    barrier wait until the patch requested DB = PRE - 2 intervals ago has arrived: it is
+//  * request the patch of step tau - EB into patch stage (tau - EB) mod SB, EB = PRE - 2, and
+//    before the barrier wait until the patch requested DB = 1 interval ago has arrived: it is
 //    the one of step t + 1, which the barrier publishes.
 // A plane stage is written again SA steps later and a patch stage requested again SB steps
 // later, both after the barrier at which the multipliers are done with it: SA = 2 + SLACK,
-// SB = PRE = DA + 1 + SLACK.  A multiplier reads its fragments two taps ahead (three register
+// SB = 3 (read now, published next, on its way).  The filter rows wait in registers, so their
+// depth DA costs no LDS: each side alone - movers without multipliers, multipliers without
+// loads - runs the bf16 workload in 25 us, and the movers' 25 us are latency (requests
+// in flight, not bytes per second).  A multiplier reads its fragments two taps ahead (three register
 // sets), one read per MFMA slot; its barrier sits before the last two taps of a step, after
 // which it reads the first fragments of the next stage.
 //
@@ -59,8 +62,9 @@ struct Bf16sConfig {
     static constexpr int SLACK = SLACK_;
     static constexpr int PRE = DA_ + 1 + SLACK_;          // intervals before the multipliers' first step
     static constexpr int SA = 2 + SLACK_;                 // stages of filter planes
-    static constexpr int SB = PRE;                        // stages of the patch
-    static constexpr int DB = PRE - 2;                    // intervals between a patch request and the wait for it
+    static constexpr int EB = PRE - 2;                    // the patch of step tau - EB is requested in interval tau ...
+    static constexpr int SB = PRE - EB + 1;               // ... so the patch has three stages (read, published next, on its way)
+    static constexpr int DB = PRE - 1 - EB;               // intervals between a patch request and the wait for it
     static constexpr int MULT_THREADS = 256 * GROUPS_;
     static constexpr int THREADS = MULT_THREADS + 256;
     static constexpr int WAVES_PER_SIMD = THREADS / 256;
@@ -83,7 +87,7 @@ struct Bf16sConfig {
     static_assert(BM % 32 == 0 && BN % 128 == 0, "wave blocks are 32x32 multiples");
     static_assert(A_WAVES == 2 || A_WAVES == 4, "filter rows: two or four moving wavefronts");
     static_assert(PATCH_PIX % 32 == 0 && B_TOTAL % B_WAVES == 0, "patch requests divide among the wavefronts");
-    static_assert(DA_ >= 1 && DA_ <= 3 && (SLACK_ == 0 || SLACK_ == 1) && DB >= 1, "depths");
+    static_assert(DA_ >= 1 && DA_ <= 3 && (SLACK_ == 0 || SLACK_ == 1) && DB >= 1 && EB >= 1, "depths");
     static_assert(GROUPS_ == 1 || (GROUPS_ == 2 && BM * BN * 4 <= LDS_BYTES), "two groups: the second group's sums pass through LDS");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void igconv_fwd_
                     a_reg[set][q] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, a_voff + (uint32_t)q * 16u, so, 0);
             }
             if (does_b) {
-                const int sb = tau - 1;            // step whose patch is requested now
+                const int sb = tau - Cfg::EB;      // step whose patch is requested now
                 if (sb >= 0) {
                     const int stage = sb % SB;
                     const uint32_t so = b_soff(sb);
