@@ -45,8 +45,8 @@ static int launch_bf16s(const ConvKernelParams &p, int grid, void *stream) {
 #define IGC_BF16S_LIST(X) \
     X("bf16 64x256x288 patch movers two groups", 64, 256, false, 2, 448, 2, 0) \
     X("bf16 64x256x288 patch movers two groups swap", 64, 256, true, 2, 448, 2, 0) \
-    X("bf16 128x256x144 patch movers", 128, 256, false, 1, 512, 2, 0) \
-    X("bf16 128x256x144 patch movers swap", 128, 256, true, 1, 512, 2, 0)
+    X("bf16 128x256x144 patch movers", 128, 256, false, 1, 512, 2, 1) \
+    X("bf16 128x256x144 patch movers swap", 128, 256, true, 1, 512, 2, 1)
 #define IGC_BF16S_INSTANTIATE(NAME, BM, BN, SWAP, GROUPS, PIX, DA, SLACK) \
     template __global__ void igconv_fwd_bf16s_kernel<Bf16sConfig<BM, BN, SWAP, GROUPS, PIX, DA, SLACK>>(const ConvKernelParams);
 IGC_BF16S_LIST(IGC_BF16S_INSTANTIATE)
