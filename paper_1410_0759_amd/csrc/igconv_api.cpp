@@ -22,7 +22,7 @@ namespace igc {
 // still be queried).  The kernels deal workgroups to XCDs by blockIdx % 8: gfx950 parts have 8.
 constexpr int kXcds = 8;
 // gather mode 15: what loading an element costs, in multiply-add rows (see plan_cost)
-constexpr double kDirectGatherCost = 20.0;
+constexpr double kDirectGatherCost = 20.0, kDirectGatherCostStaged = 9.0;
 constexpr int kOffsetTableEntries = 2048;  // LDS offset table of the short-reduction unpadded kernels
 constexpr long long kMaxBytes = 1ll << 31;  // byte offsets must stay below this
 
@@ -150,8 +150,9 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
 static long long direct_steps_per_wave(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long waves = ki.threads / 64, steps = (k.CRS + ki.BK - 1) / ki.BK;
     const long long per = (steps + waves - 1) / waves;
-    const long long depth = direct_depth(ki.BK);
-    return (per + depth - 1) / depth * depth;
+    // (a multiple of the request depth; with the filter rows staged in LDS, of the eight steps of two row copies)
+    const long long unit = ki.variant == 1 ? 8 : direct_depth(ki.BK);
+    return (per + unit - 1) / unit * unit;
 }
 
 // Relative cost of running the problem with one kernel variant.  Tiles are padded to
@@ -164,7 +165,7 @@ static long long direct_steps_per_wave(const KernelInfo &ki, const ConvKernelPar
 // of 16.  More workgroups per compute unit cover more of each other's waits: Table-2 layer 3 gained 4 %.
 static int workgroups_per_cu(const KernelInfo &ki) {
     const bool small_tile = (ki.gmode == 2 || (ki.gmode == 8 && !ki.bf16)) && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
-    if (ki.gmode == 15) return 2;   // (64 KB of LDS each; 55 to 97 registers)
+    if (ki.gmode == 15) return ki.variant == 1 ? 1 : 2;   // (64 KB of LDS each, 128 KB with the filter rows staged; 55 to 97 registers)
     // (double precision, pipelined: 105 registers for the 64 x 64 tile, 169 for 128 x 64)
     if (ki.f64) return ki.gmode == 14 ? (ki.BM * ki.BN <= 64 * 64 ? 4 : 2) : 4;
     const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_tile ? 4 : 2);
@@ -215,9 +216,13 @@ static double plan_cost(const igcContext *h, const KernelInfo &ki, const ConvKer
         // of about six steps.  Measured against the pipelined kernels on the deeper layers of Table 2: ahead up to
         // mini-batches of 32 (layer 3: 72 -> 97 TFLOP/s at 16; layer 4: 23 -> 53), level at 64, behind where tiles of
         // 64 x 64 and more fill the chip.  Element-wise filter loads (32 cache lines per instruction): three times slower.
+        // With the filter rows staged in LDS (variant 1; one workgroup per compute unit) a filter load costs the address
+        // unit a quarter: layer 4 at 16 / 32: 53 -> 67, 56 -> 72 TFLOP/s; with more than two tiles per compute unit the
+        // two resident workgroups of the plain form do better (layer 3: 97 against 91), so it is offered up to there.
         const double waves = ki.threads / 64;
-        return tile_times * ((double)direct_steps_per_wave(ki, k) + 6.0) * waves * ki.BK * 32.0 * (32.0 + kDirectGatherCost) *
-               (ki.veca ? 1.0 : 3.0);
+        if (ki.variant == 1 && tiles > 2 * cus) return 1e300;
+        return tile_times * ((double)direct_steps_per_wave(ki, k) + 6.0) * waves * ki.BK * 32.0 *
+               (32.0 + (ki.variant == 1 ? kDirectGatherCostStaged : kDirectGatherCost)) * (ki.veca ? 1.0 : 3.0);
     }
     if (ki.variant == 2) {
         // Teams: one tile per workgroup and one workgroup per compute unit at a time; each team multiplies its
@@ -269,7 +274,7 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     if (gmode == 14) return k.RS <= 63;   // (one bit of a 64-bit mask per tap, the last one spare)
     if (gmode == 15)   // unpadded, and every index a wavefront can request has an entry in the offset table
         return k.pad_h == 0 && k.pad_w == 0 &&
-               ((long long)(ki.threads / 64) * direct_steps_per_wave(ki, k) + direct_depth(ki.BK) + 1) * ki.BK <= kDirectTableEntries;
+               ((long long)(ki.threads / 64) * direct_steps_per_wave(ki, k) + direct_depth(ki.BK, ki.variant == 1) + 1) * ki.BK <= kDirectTableEntries;
     if (gmode == 7 || gmode == 11 || gmode == 13) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
         if (!(k.pad_h == 0 && k.pad_w == 0 && (((steps + 1) & ~1ll) + 2) * ki.BK <= kOffsetTableEntries)) return false;

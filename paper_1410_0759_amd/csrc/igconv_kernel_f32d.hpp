@@ -30,14 +30,25 @@
 
 namespace igc {
 
-template <int WAVES_, bool VECA_, int NV_>
+template <int WAVES_, bool VECA_, int NV_, bool ALDS_ = false>
 struct DirectConfig {
+    // ALDS: the filter rows go through LDS.  Loaded as the MFMA wants them - lane = (row, half): 32 rows of 32 bytes - a
+    // filter load touches 32 cache lines and costs the address unit as much as the step's four gathers together; taken
+    // apart, the kernel without its filter loads or without its gathers runs at the MFMA rate, with both at half of
+    // it: it is bound by the address unit, evenly by the two.  So the wavefront copies its rows in whole lines
+    // instead (8 rows x 128 bytes per load, straight into its own piece of LDS: no registers, no LDS write
+    // instructions; 32 reduction indices = four steps per copy, two copies in flight) and reads its MFMA operand back
+    // with one 16-byte LDS read per step.  Rows sit 128 bytes apart in LDS; the 16-byte pieces of a row are stored
+    // exchanged by (row / 2) % 8, so that 16 consecutive rows' reads of one piece fall on distinct banks.
+    static constexpr bool ALDS = ALDS_;
     static constexpr int WAVES = WAVES_, THREADS = 64 * WAVES_;
     static constexpr bool VECA = VECA_;   // filter rows fetched with 16-byte loads (C*R*S a multiple of 4, aligned filter)
     static constexpr int NV = NV_;        // runs of four reduction indices per lane and step
     static constexpr int BM = 32, BN = 32, BK = 8 * NV_;
-    static constexpr int DEPTH = direct_depth(BK);
-    static constexpr int LDS_BYTES = kDirectTableEntries * 4;
+    static constexpr int DEPTH = direct_depth(BK, ALDS_);
+    static constexpr int A_STAGE_BYTES = 32 * 128;   // ALDS: 32 rows x 32 reduction indices
+    static constexpr int LDS_BYTES = kDirectTableEntries * 4 + (ALDS_ ? WAVES_ * 2 * A_STAGE_BYTES : 0);
+    static_assert(!ALDS_ || (VECA_ && NV_ == 1 && LDS_BYTES <= 160 * 1024), "staged filter rows: 16-byte loads, steps of 8");
     static_assert(WAVES_ * 16 * 64 <= kDirectTableEntries, "the exchange of the sums reuses the table's memory");
     static_assert(1024 % THREADS == 0, "whole elements per thread in the epilogue");
 };
@@ -46,7 +57,7 @@ template <class Cfg>
 __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKernelParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int W = Cfg::WAVES, D = Cfg::DEPTH, THREADS = Cfg::THREADS, NV = Cfg::NV, BK = Cfg::BK;
-    __shared__ __attribute__((aligned(16))) uint32_t lds[kDirectTableEntries];
+    __shared__ __attribute__((aligned(1024))) uint32_t lds[Cfg::LDS_BYTES / 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -126,40 +137,111 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 
     const int t0 = wave * steps_w;
-    static_for<NV>([&](auto vc) { read_table(t0, decltype(vc)::value); });
-    static_for<D>([&](auto dc) {
-        constexpr int set = decltype(dc)::value;
-        static_for<NV>([&](auto vc) {
-            constexpr int v = decltype(vc)::value;
-            request_a(set, t0 + set, v);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) request_b(set, v, e);
-            read_table(t0 + set + 1, v);
-        });
-    });
-    __builtin_amdgcn_sched_barrier(0);
-    for (int s = 0; s < steps_w; s += D) {
-        // (the order is pinned: one MFMA, then the request that refills the register it has just read - for step
-        // t + DEPTH, which uses the same register set; after the four MFMAs of a run its filter vector and the table
-        // entries of the step after)
+    if constexpr (!Cfg::ALDS) {
+        static_for<NV>([&](auto vc) { read_table(t0, decltype(vc)::value); });
         static_for<D>([&](auto dc) {
             constexpr int set = decltype(dc)::value;
-            const int t = t0 + s + set + D;
-            static_for<4 * NV>([&](auto ic) {
-                constexpr int v = decltype(ic)::value / 4, e = decltype(ic)::value % 4;
-                const f32x4 va = __builtin_bit_cast(f32x4, a_reg[set][v]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], __builtin_bit_cast(float, b_reg[set][v][e]), acc, 0, 0, 0);
-                request_b(set, v, e);
-                if constexpr (e == 3) {
-                    request_a(set, t, v);
-                    read_table(t + 1, v);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+            static_for<NV>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
+                request_a(set, t0 + set, v);
+    #pragma unroll
+                for (int e = 0; e < 4; ++e) request_b(set, v, e);
+                read_table(t0 + set + 1, v);
             });
         });
+        __builtin_amdgcn_sched_barrier(0);
+        for (int s = 0; s < steps_w; s += D) {
+            // (the order is pinned: one MFMA, then the request that refills the register it has just read - for step
+            // t + DEPTH, which uses the same register set; after the four MFMAs of a run its filter vector and the table
+            // entries of the step after)
+            static_for<D>([&](auto dc) {
+                constexpr int set = decltype(dc)::value;
+                const int t = t0 + s + set + D;
+                static_for<4 * NV>([&](auto ic) {
+                    constexpr int v = decltype(ic)::value / 4, e = decltype(ic)::value % 4;
+                    const f32x4 va = __builtin_bit_cast(f32x4, a_reg[set][v]);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], __builtin_bit_cast(float, b_reg[set][v][e]), acc, 0, 0, 0);
+                    request_b(set, v, e);
+                    if constexpr (e == 3) {
+                        request_a(set, t, v);
+                        read_table(t + 1, v);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            });
+        }
+    } else {
+        // ---- filter rows staged in LDS (see DirectConfig) ----
+        uint8_t *const a_lds = reinterpret_cast<uint8_t *>(lds + kDirectTableEntries) + wave * (2 * Cfg::A_STAGE_BYTES);
+        // copy j of a stage fills its 1 KB number j: lane -> 16-byte slot j*64 + lane = (row slot / 8, position slot % 8),
+        // which holds the row's piece position ^ ((row / 2) % 8)
+        uint32_t al_off[4], al_k[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int slot = j * 64 + lane, rowl = slot >> 3, piece = (slot & 7) ^ ((rowl >> 1) & 7);
+            al_k[j] = 4u * (uint32_t)piece;
+            al_off[j] = m0 + rowl < p.K ? ((uint32_t)(m0 + rowl) * (uint32_t)p.CRS + al_k[j]) * 4u : kOutOfRange;
+        }
+        auto request_rows = [&](int stage, int t) __attribute__((always_inline)) {   // the four steps from step t on
+            const uint32_t k0 = (uint32_t)t * 8u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    wbuf, (__attribute__((address_space(3))) void *)(a_lds + stage * Cfg::A_STAGE_BYTES + j * 1024), 16,
+                    k0 + al_k[j] < (uint32_t)p.CRS ? al_off[j] : kOutOfRange, k0 * 4u, 0, 0);
+        };
+        // this lane's operand of step i (0..3) of a stage: piece 2 i + half of row lane % 32
+        const int fr_base = l32 * 128, fr_x = (l32 >> 1) & 7;
+        auto read_rows = [&](int stage, int i) __attribute__((always_inline)) -> u32x4 {
+            return *reinterpret_cast<const u32x4 *>(a_lds + stage * Cfg::A_STAGE_BYTES + fr_base + (((2 * i + half) ^ fr_x) << 4));
+        };
+        static_assert(D == 4, "four register sets of gathered elements: one per step of a copy");
+        request_rows(0, t0);
+        request_rows(1, t0 + 4);
+        read_table(t0, 0);
+        static_for<D>([&](auto dc) {
+            constexpr int set = decltype(dc)::value;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) request_b(set, 0, e);
+            read_table(t0 + set + 1, 0);
+        });
+        // (the first copy has arrived when at most the second and the 16 gathers requested after it are outstanding)
+        asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+        u32x4 frag = read_rows(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int s = 0; s < steps_w; s += 8) {
+            static_for<8>([&](auto sc) {
+                constexpr int st = decltype(sc)::value, stage = st / 4, i = st % 4, set = st % 4;
+                const int t = t0 + s + st;
+                u32x4 next;
+                if constexpr (i < 3) {
+                    next = read_rows(stage, i + 1);
+                } else {
+                    // the other stage's copy was requested a whole copy ago; since then: the gathers of three steps
+                    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                    next = read_rows(stage ^ 1, 0);
+                }
+                const f32x4 va = __builtin_bit_cast(f32x4, frag);
+                static_for<4>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(va[e], __builtin_bit_cast(float, b_reg[set][0][e]), acc, 0, 0, 0);
+                    request_b(set, 0, e);
+                    if constexpr (e == 3) read_table(t + D + 1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                frag = next;
+                if constexpr (i == 3) {
+                    // this stage has been read to its end (its last operand is in registers): the copy after next
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    request_rows(stage, t + 5);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
+        }
     }
 
     // the wavefronts' sums meet in LDS (the table is no longer needed): [wavefront][register][lane]
+    if constexpr (Cfg::ALDS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (no copy may still be on its way into LDS)
     __syncthreads();
     float *const xch = reinterpret_cast<float *>(lds);
 #pragma unroll

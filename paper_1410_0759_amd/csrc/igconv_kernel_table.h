@@ -28,7 +28,8 @@ struct KernelInfo {
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
-    int variant = 0;  // 2: `threads` / 256 teams of four wavefronts per workgroup, each on its share of the steps;
+    int variant = 0;  // 1: (gather mode 15) the filter rows staged in LDS;
+                      // 2: `threads` / 256 teams of four wavefronts per workgroup, each on its share of the steps;
                       // 3: wavefronts that move tiles beside wavefronts that multiply (gather mode 5)
     bool f64 = false; // double precision in and out (alpha64 / beta64 of the parameters apply)
     int patchPixels = 512;  // gather mode 5: pixels of the zero-extended image a tile's staged patch can hold

@@ -18,7 +18,7 @@ struct Magic {
 // The kernels that feed the MFMAs straight from global memory (igconv_kernel_f32d.hpp): entries of their LDS table of
 // tap offsets (one per reduction index), and how many steps ahead their requests run (as many register sets).
 constexpr int kDirectTableEntries = 16384;
-constexpr int direct_depth(int bk) { return bk >= 32 ? 2 : 3; }   // (bk: reduction indices per step)
+constexpr int direct_depth(int bk, bool staged_rows = false) { return staged_rows ? 4 : (bk >= 32 ? 2 : 3); }   // (bk: reduction indices per step)
 
 struct ConvKernelParams {
     const void *x;   // input tensor D (device)
