@@ -230,9 +230,9 @@ def run_double_precision(steps, warmup, index=3):
 
 def run_padded_filters(steps, warmup):
     """Layers outside the paper's collection whose filters are neither nine taps nor unpadded (a 5x5 and a 7x7
-    layer with zero borders): forward and backward data in tap-major order, without a workspace and with the
-    optional one of the filter's size (the filter rewritten with the reduction's channel index innermost).
-    Parity on the first image against the oracle."""
+    layer with zero borders): forward and backward data without a workspace (filter order, the window test read from
+    a tap mask per column) and with whatever the optional-workspace query asks for (nothing for these float layers;
+    the keys are kept so that a workspace-dependent route would show).  Parity on the first image against the oracle."""
     import numpy as np
     import workloads as wl
     from oracle import conv_oracle as oc
