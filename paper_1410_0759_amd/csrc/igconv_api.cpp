@@ -145,7 +145,9 @@ static long long kernel_steps(const KernelInfo &ki, const ConvKernelParams &k) {
     return (k.CRS + ki.BK - 1) / ki.BK;
 }
 
-// Gather mode 15 (igconv_kernel_f32d.hpp): steps of BK reduction indices per wavefront, the workgroup's wavefronts
+static bool is_direct(int gmode) { return gmode == 15 || gmode == 16; }
+
+// Gather modes 15 and 16 (igconv_kernel_f32d.hpp): steps of BK reduction indices per wavefront, the workgroup's wavefronts
 // sharing the reduction evenly; a multiple of the request depth.
 static long long direct_steps_per_wave(const KernelInfo &ki, const ConvKernelParams &k) {
     const long long waves = ki.threads / 64, steps = (k.CRS + ki.BK - 1) / ki.BK;
@@ -165,7 +167,7 @@ static long long direct_steps_per_wave(const KernelInfo &ki, const ConvKernelPar
 // of 16.  More workgroups per compute unit cover more of each other's waits: Table-2 layer 3 gained 4 %.
 static int workgroups_per_cu(const KernelInfo &ki) {
     const bool small_tile = (ki.gmode == 2 || (ki.gmode == 8 && !ki.bf16)) && ki.BM * ki.BN <= 64 * 64 && ki.BK == 32;
-    if (ki.gmode == 15) return ki.variant == 1 ? 1 : 2;   // (64 KB of LDS each, 128 KB with the filter rows staged; 55 to 97 registers)
+    if (is_direct(ki.gmode)) return ki.variant == 1 ? 1 : (160 * 1024) / ki.ldsBytes;   // (64 or 80 KB of LDS each, 64 more with the filter rows staged)
     // (double precision, pipelined: 105 registers for the 64 x 64 tile, 169 for 128 x 64)
     if (ki.f64) return ki.gmode == 14 ? (ki.BM * ki.BN <= 64 * 64 ? 4 : 2) : 4;
     const int by_regs = ki.BK == 16 ? (ki.BM * ki.BN <= 64 * 128 ? 4 : 3) : (small_tile ? 4 : 2);
@@ -209,7 +211,7 @@ static double plan_cost(const igcContext *h, const KernelInfo &ki, const ConvKer
                (2.75 * ki.BM + (ki.gmode == 5 ? 1.0 : 1.5) * ki.BN + ki.BM * ki.BN / 256.0);
     }
     const bool table = ki.gmode == 7 || ki.gmode == 11 || ki.gmode == 13;
-    if (ki.gmode == 15) {
+    if (is_direct(ki.gmode)) {
         // 32 x 32 tiles, the wavefronts of a workgroup each on their share of the steps, operands straight from global
         // memory: a round of one step per wavefront is waves * 8 * 32 * 32 multiply-adds, bound by the loads (two
         // elements per lane and MFMA) rather than by the MFMA pipe; a fixed cost (offset table, exchange of the sums)
@@ -222,7 +224,8 @@ static double plan_cost(const igcContext *h, const KernelInfo &ki, const ConvKer
         const double waves = ki.threads / 64;
         if (ki.variant == 1 && tiles > 2 * cus) return 1e300;
         return tile_times * ((double)direct_steps_per_wave(ki, k) + 6.0) * waves * ki.BK * 32.0 *
-               (32.0 + (ki.variant == 1 ? kDirectGatherCostStaged : kDirectGatherCost)) * (ki.veca ? 1.0 : 3.0);
+               (32.0 + (ki.variant == 1 ? kDirectGatherCostStaged : kDirectGatherCost)) * (ki.veca ? 1.0 : 3.0) *
+               (ki.gmode == 16 ? 1.03 : 1.0);   // (the window test: a little behind mode 15 where both can run)
     }
     if (ki.variant == 2) {
         // Teams: one tile per workgroup and one workgroup per compute unit at a time; each team multiplies its
@@ -272,8 +275,8 @@ static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool
     if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
     if (gmode == 2) return k.pad_h == 0 && k.pad_w == 0;
     if (gmode == 14) return k.RS <= 63;   // (one bit of a 64-bit mask per tap, the last one spare)
-    if (gmode == 15)   // unpadded, and every index a wavefront can request has an entry in the offset table
-        return k.pad_h == 0 && k.pad_w == 0 &&
+    if (is_direct(gmode))   // unpadded or at most 31 taps, and every index a wavefront can request has an entry in the offset table
+        return (gmode == 16 ? k.RS <= 31 : k.pad_h == 0 && k.pad_w == 0) &&
                ((long long)(ki.threads / 64) * direct_steps_per_wave(ki, k) + direct_depth(ki.BK, ki.variant == 1) + 1) * ki.BK <= kDirectTableEntries;
     if (gmode == 7 || gmode == 11 || gmode == 13) {   // unpadded, and every step the kernel can request has an entry in its offset table
         const long long steps = (k.CRS + ki.BK - 1) / ki.BK;
@@ -315,7 +318,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
         const KernelInfo &ki = *kernel_info(id);
         if (ki.bf16 != pr.bf16 || ki.f64 != pr.f64 || (ki.veca && !can_vec) || !gather_mode_ok(ki, k, x_aligned)) continue;
         if (pr.mode_mask != 0 && !((pr.mode_mask >> ki.gmode) & 1u)) continue;
-        if (pr.no_teams && ((ki.variant == 2 && ki.gmode < 4) || ki.gmode == 15)) continue;
+        if (pr.no_teams && ((ki.variant == 2 && ki.gmode < 4) || is_direct(ki.gmode))) continue;
         double c = plan_cost(h, ki, k);
         if (ki.swap != want_swap) c *= 1.5;
         if (!ki.veca && can_vec && ki.gmode != 1) c *= 1.05;
@@ -334,7 +337,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const igcContext *h, const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || ki.gmode == 15) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || is_direct(ki.gmode)) return tiles_per_xcd;
     return std::min(tiles_per_xcd, std::max(1, h->computeUnits / kXcds) * workgroups_per_cu(ki));
 }
 
@@ -402,7 +405,7 @@ static igcStatus fill_plan(const igcContext *h, int id, Problem *pr, igcConvolut
     k.wgsPerXcd = workgroups_per_xcd(h, ki, k.tilesPerXcd);
     k.splits = 1;
     k.stepsPerSplit = (k.ksteps + 1) & ~1;
-    if (ki.gmode == 15) k.stepsPerSplit = (int)direct_steps_per_wave(ki, k);
+    if (is_direct(ki.gmode)) k.stepsPerSplit = (int)direct_steps_per_wave(ki, k);
     if (ki.variant == 2 && ki.gmode < 4) {   // (fp32 team kernels: an even number of steps per team)
         const int teams = ki.threads / 256;
         k.stepsPerSplit = ((k.ksteps + teams - 1) / teams + 1) & ~1;

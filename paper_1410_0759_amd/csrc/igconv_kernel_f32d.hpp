@@ -23,6 +23,10 @@
 //    of the tile over the wavefronts in order (deterministic) and stores it through y's strides
 //    with alpha, beta, bias and activation applied.
 // Indices past the end of the reduction read zeros on both sides (out-of-range requests).
+// With a zero border (MSK) every lane also keeps one bit per filter tap - whether that tap of its column's
+// window lies inside the image - and a second table names the tap of every reduction index: a gather
+// whose bit is clear is sent out of range and reads the border's zero (R*S <= 31; three more vector
+// instructions per gathered element, which the loop, bound by the address unit, has room for).
 #ifndef IGCONV_KERNEL_F32D_HPP_
 #define IGCONV_KERNEL_F32D_HPP_
 
@@ -30,8 +34,9 @@
 
 namespace igc {
 
-template <int WAVES_, bool VECA_, int NV_, bool ALDS_ = false>
+template <int WAVES_, bool VECA_, int NV_, bool ALDS_ = false, bool MSK_ = false>
 struct DirectConfig {
+    static constexpr bool MSK = MSK_;     // zero border: window test from a tap mask per column
     // ALDS: the filter rows go through LDS.  Loaded as the MFMA wants them - lane = (row, half): 32 rows of 32 bytes - a
     // filter load touches 32 cache lines and costs the address unit as much as the step's four gathers together; taken
     // apart, the kernel without its filter loads or without its gathers runs at the MFMA rate, with both at half of
@@ -47,8 +52,10 @@ struct DirectConfig {
     static constexpr int BM = 32, BN = 32, BK = 8 * NV_;
     static constexpr int DEPTH = direct_depth(BK, ALDS_);
     static constexpr int A_STAGE_BYTES = 32 * 128;   // ALDS: 32 rows x 32 reduction indices
-    static constexpr int LDS_BYTES = kDirectTableEntries * 4 + (ALDS_ ? WAVES_ * 2 * A_STAGE_BYTES : 0);
+    static constexpr int TAP_TABLE_BYTES = MSK_ ? kDirectTableEntries : 0;   // one byte per reduction index
+    static constexpr int LDS_BYTES = kDirectTableEntries * 4 + TAP_TABLE_BYTES + (ALDS_ ? WAVES_ * 2 * A_STAGE_BYTES : 0);
     static_assert(!ALDS_ || (VECA_ && NV_ == 1 && LDS_BYTES <= 160 * 1024), "staged filter rows: 16-byte loads, steps of 8");
+    static_assert(!MSK_ || NV_ == 1, "the tap mask is built for steps of 8");
     static_assert(WAVES_ * 16 * 64 <= kDirectTableEntries, "the exchange of the sums reuses the table's memory");
     static_assert(1024 % THREADS == 0, "whole elements per thread in the epilogue");
 };
@@ -83,6 +90,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
         const uint32_t ts = p.flip ? (uint32_t)p.S - 1u - sx : sx;
         const uint32_t so = (c * (uint32_t)p.xsC + tr * (uint32_t)p.xsH + ts * (uint32_t)p.xsW) * 4u;
         lds[i] = i < (uint32_t)p.CRS ? so : kOutOfRange;
+        // (tap in filter order; 31, whose bit no mask has, past the end: adding the marker to the offset of a window
+        // origin in the border - a negative number - could wrap back into range)
+        if constexpr (Cfg::MSK) reinterpret_cast<uint8_t *>(lds + kDirectTableEntries)[i] = i < (uint32_t)p.CRS ? (uint8_t)rs : (uint8_t)31;
     }
     __syncthreads();
 
@@ -91,7 +101,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
 
     // this lane's column j -> (n,p,q): byte offset of its window origin (a valid offset lies below 2^31, so adding
     // the marker of a dead index leaves it out of range; a column beyond NPQ reads anything: it is never stored)
-    uint32_t colbase;
+    // (MSK: the origin may lie in the border, its offset negative - kept modulo 2^32: with the offset of a tap inside
+    // the image added it is the element's true offset again)
+    uint32_t colbase, tapmask = 0u;
     {
         const int j = n0 + l32;
         const uint32_t jj = j < p.NPQ ? (uint32_t)j : 0u;
@@ -99,7 +111,17 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
         const uint32_t rem = jj - n * (uint32_t)p.PQ;
         const uint32_t pp = magic_div(rem, p.mQ);
         const uint32_t qq = rem - pp * (uint32_t)p.Q;
-        colbase = (n * (uint32_t)p.xsN + pp * (uint32_t)p.u * (uint32_t)p.xsH + qq * (uint32_t)p.v * (uint32_t)p.xsW) * 4u;
+        if constexpr (Cfg::MSK) {
+            const int h0 = (int)pp * p.u - p.pad_h, w0 = (int)qq * p.v - p.pad_w;
+            colbase = (n * (uint32_t)p.xsN + (uint32_t)h0 * (uint32_t)p.xsH + (uint32_t)w0 * (uint32_t)p.xsW) * 4u;
+            for (int r = 0, bit = 0; r < p.R; ++r)
+                for (int sx = 0; sx < p.S; ++sx, ++bit) {
+                    const int hh = h0 + (p.flip ? p.R - 1 - r : r), ww = w0 + (p.flip ? p.S - 1 - sx : sx);
+                    if ((unsigned)hh < (unsigned)p.H && (unsigned)ww < (unsigned)p.W) tapmask |= 1u << bit;
+                }
+        } else {
+            colbase = (n * (uint32_t)p.xsN + pp * (uint32_t)p.u * (uint32_t)p.xsH + qq * (uint32_t)p.v * (uint32_t)p.xsW) * 4u;
+        }
     }
     // this lane's filter row; within a step the lower half of the wavefront holds the first 4 NV reduction indices,
     // the upper half the others (both operands alike: which k meets which MFMA is free, the sum commutes), so that
@@ -111,8 +133,10 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
     u32x4 a_reg[D][NV];
     uint32_t b_reg[D][NV][4];
     u32x4 so4[NV];   // table entries of the step requested next
+    uint32_t tap4[NV];   // MSK: their taps, a byte each
     auto read_table = [&](int t, int v) __attribute__((always_inline)) {
         so4[v] = *reinterpret_cast<const u32x4 *>(&lds[t * BK + (int)lane_k + 4 * v]);
+        if constexpr (Cfg::MSK) tap4[v] = lds[kDirectTableEntries + ((t * BK + (int)lane_k + 4 * v) >> 2)];
     };
     // the request of step t in pieces, each short enough for the gap between two MFMAs
     auto request_a = [&](int set, int t, int v) __attribute__((always_inline)) {
@@ -129,7 +153,9 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
         }
     };
     auto request_b = [&](int set, int v, int e) __attribute__((always_inline)) {
-        b_reg[set][v][e] = __builtin_amdgcn_raw_buffer_load_b32(xbuf, colbase + so4[v][e], 0, 0);
+        uint32_t off = colbase + so4[v][e];
+        if constexpr (Cfg::MSK) off = ((tapmask >> ((tap4[v] >> (8 * e)) & 31u)) & 1u) ? off : kOutOfRange;
+        b_reg[set][v][e] = __builtin_amdgcn_raw_buffer_load_b32(xbuf, off, 0, 0);
     };
 
     f32x16 acc;
@@ -172,7 +198,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void igconv_f32d_kernel(const ConvKer
         }
     } else {
         // ---- filter rows staged in LDS (see DirectConfig) ----
-        uint8_t *const a_lds = reinterpret_cast<uint8_t *>(lds + kDirectTableEntries) + wave * (2 * Cfg::A_STAGE_BYTES);
+        uint8_t *const a_lds = reinterpret_cast<uint8_t *>(lds + kDirectTableEntries) + Cfg::TAP_TABLE_BYTES + wave * (2 * Cfg::A_STAGE_BYTES);
         // copy j of a stage fills its 1 KB number j: lane -> 16-byte slot j*64 + lane = (row slot / 8, position slot % 8),
         // which holds the row's piece position ^ ((row / 2) % 8)
         uint32_t al_off[4], al_k[4];

@@ -24,11 +24,12 @@ struct KernelInfo {
                     // 10 backward-filter over channel vectors (bf16, unit channel strides), tiles transposed in registers,
                     // 14 filter order with the tap tracked by the scalar unit and the window test in a bit mask (R*S <= 63)
                     // 15 unpadded, 32 x 32 tiles, the reduction cut among the wavefronts, operands straight from global memory
+                    // 16 mode 15 with a zero border: the window test from a mask with a bit per tap (R*S <= 31)
     int threads;
     int ldsBytes;
     // Enqueue on `stream` (a hipStream_t); returns the runtime's error code (0 = ok).
     int (*launch)(const ConvKernelParams &, int grid, void *stream);
-    int variant = 0;  // 1: (gather mode 15) the filter rows staged in LDS;
+    int variant = 0;  // 1: (gather modes 15, 16) the filter rows staged in LDS;
                       // 2: `threads` / 256 teams of four wavefronts per workgroup, each on its share of the steps;
                       // 3: wavefronts that move tiles beside wavefronts that multiply (gather mode 5)
     bool f64 = false; // double precision in and out (alpha64 / beta64 of the parameters apply)

@@ -83,7 +83,7 @@ def test_every_kernel_variant():
         dtype = "bf16" if name.startswith("bf16") else "f32"
         vec = "vecw" in name
         swap = "swap" in name
-        nopad = "nopad" in name or "direct" in name
+        nopad = "nopad" in name or ("direct" in name and "border" not in name)
         taps9 = "taps9" in name
         vecn = 8 if dtype == "bf16" else 4
         problems = [
@@ -104,6 +104,10 @@ def test_every_kernel_variant():
         if "direct" in name:   # the reduction cut among 8 or 16 wavefronts: long ones, a ragged end, wavefronts left without steps
             problems = problems + [(2, 40, 12, 9, 70, 5, 3, (0, 0), (1, 2)), (1, 24, 20, 21, 130, 7, 7, (0, 0), (1, 1)),
                                    (2, 8 if vec else 7, 9, 9, 40, 3, 3, (0, 0), (1, 1)), (1, 4 if vec else 1, 12, 12, 33, 2, 2, (0, 0), (1, 1))]
+            if "border" in name:   # zero borders (wider than the image allows windows wholly outside it), at most 31 taps
+                problems = [pr for pr in problems if pr[5] * pr[6] <= 31] + [
+                    (2, 40, 12, 9, 70, 5, 3, (2, 1), (1, 2)), (1, 24, 20, 21, 130, 5, 5, (2, 2), (1, 1)),
+                    (2, 8, 9, 9, 40, 3, 3, (1, 1), (1, 1)), (1, 4, 3, 4, 33, 2, 2, (3, 2), (1, 1)), (1, 12, 6, 7, 20, 5, 6, (4, 5), (2, 3))]
         if "teams" in name:   # long reductions: several steps per team, a ragged last step, a team left without steps
             problems = problems + ([(2, 40, 15, 17, 150, 3, 3, (1, 1), (1, 1)), (1, 136, 9, 11, 70, 3, 3, (1, 1), (2, 1))] if taps9 else
                                    [(2, 40, 12, 9, 70, 5, 3, (0, 0), (1, 2)), (1, 24, 20, 21, 130, 7, 7, (0, 0), (1, 1)), (2, 8, 9, 9, 40, 3, 3, (0, 0), (1, 1))])
@@ -160,14 +164,18 @@ def test_every_kernel_variant():
 
 
 def test_gather_modes_are_chosen():
-    """Nine taps and channels in fours -> tap table; otherwise enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
-    filter order; few channels, padded -> masked filter order (fp32, up to 63 taps) or generic."""
-    x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 3, 3)
+    """Nine taps and channels in fours -> tap table; more than 63 taps and enough channels -> tap-major order; few channels, unpadded -> unpadded gather in
+    filter order; few channels, padded -> masked filter order (fp32, up to 63 taps) or generic; few output elements and a long reduction
+    -> the reduction cut inside the workgroup, with a tap mask per column when there is a border."""
+    x, w = wl.random_problem(3, 8, 32, 40, 40, 64, 3, 3)
     _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode taps9")
     assert plan.gatherMode == 3 and plan.kSteps == 32 // (plan.tileK // 9)   # whole channels per step
-    x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 5, 3)
+    x, w = wl.random_problem(3, 2, 32, 12, 12, 8, 3, 3)
+    _, plan = _check(x, w, (1, 1), (1, 1), 1, "f32", tag="mode direct border")
+    assert plan.gatherMode == 16 and plan.tileM == 32 and plan.tileN == 32
+    x, w = wl.random_problem(3, 2, 32, 14, 14, 8, 9, 8)
     _, plan = _check(x, w, (2, 1), (1, 1), 1, "f32", tag="mode tapmajor")
-    assert plan.gatherMode == 1 and plan.kSteps == 15
+    assert plan.gatherMode == 1 and plan.kSteps == 72
     x, w = wl.random_problem(4, 2, 3, 12, 12, 8, 5, 5)
     _, plan = _check(x, w, (0, 0), (2, 1), 0, "f32", tag="mode nopad table")
     assert plan.gatherMode == 7 and plan.kSteps == 3      # short reduction: tap offsets tabulated in LDS
@@ -506,19 +514,24 @@ def test_small_problems_run_with_the_reduction_cut_inside_the_workgroup():
     inverted filter, strides, channel-fastest x and y, alpha/beta, and the fused bias + activation."""
     gu = _gpu()
     cases = [
-        # N, C, H, W, K, R, S, stride, mode, x layout, y layout
-        (4, 128, 16, 16, 128, 7, 7, (1, 1), 1, "NCHW", "NCHW"),      # a deep layer of Table 2 at a mini-batch of 4
-        (2, 96, 21, 19, 70, 5, 3, (2, 1), 0, "NHWC", "NHWC"),
-        (1, 300, 9, 11, 33, 3, 4, (1, 2), 0, "NCHW", "NHWC"),
+        # N, C, H, W, K, R, S, pad, stride, mode, x layout, y layout
+        (4, 128, 16, 16, 128, 7, 7, (0, 0), (1, 1), 1, "NCHW", "NCHW"),      # a deep layer of Table 2 at a mini-batch of 4
+        (2, 96, 21, 19, 70, 5, 3, (0, 0), (2, 1), 0, "NHWC", "NHWC"),
+        (1, 300, 9, 11, 33, 3, 4, (0, 0), (1, 2), 0, "NCHW", "NHWC"),
+        # with a zero border (up to 31 taps): the window test from a tap mask per column
+        (4, 256, 7, 7, 200, 3, 3, (1, 1), (1, 1), 1, "NCHW", "NCHW"),        # the last layers of a deep network at a small mini-batch
+        (2, 96, 13, 11, 70, 5, 3, (2, 1), (2, 1), 0, "NHWC", "NHWC"),
+        (1, 300, 5, 6, 33, 3, 4, (2, 3), (1, 2), 0, "NCHW", "NHWC"),
+        (3, 64, 2, 3, 40, 5, 5, (4, 4), (1, 1), 0, "NCHW", "NCHW"),          # windows that lie wholly in the border
     ]
-    for i, (N, C, H, W, K, R, S, stride, mode, xl, yl) in enumerate(cases):
+    for i, (N, C, H, W, K, R, S, pad, stride, mode, xl, yl) in enumerate(cases):
         x, w = wl.random_problem(170 + i, N, C, H, W, K, R, S)
-        want = oc.conv_forward(x, w, pad=(0, 0), stride=stride, mode=mode)
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode)
         y0 = np.random.default_rng(175 + i).uniform(-1, 1, size=want.shape).astype(np.float32)
-        want2 = oc.conv_forward(x, w, pad=(0, 0), stride=stride, mode=mode, alpha=0.5, beta=-1.5, y_old=y0)
-        g = gu.GpuConv(wl.with_layout(x, xl), w, (0, 0), stride, mode, y_layout=yl)
+        want2 = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode, alpha=0.5, beta=-1.5, y_old=y0)
+        g = gu.GpuConv(wl.with_layout(x, xl), w, pad, stride, mode, y_layout=yl)
         print("direct", cases[i], flush=True)
-        assert g.plan().gatherMode == 15
+        assert g.plan().gatherMode == (15 if pad == (0, 0) else 16)
         g.prefill(value=float("nan"))
         g.launch(1.0, 0.0)
         assert gu.rel_err(g.result(), want) <= gu.BOUND["f32"]
