@@ -441,3 +441,45 @@ def test_bf16_channel_vector_routes_fall_back_on_pointers_off_the_16_byte_grid()
         ig.check(ig.convolution_backward_data(h, 1.0, wd, wp, dyd, dy_ptr, conv, 0.0, dxd, dx.data_ptr(), ws_ptr, ws2_bytes), "dgrad")
         torch.cuda.synchronize()
         assert gu.rel_err(dx.cpu().numpy().astype(np.float64), want_dx) <= gu.BOUND["bf16"]
+
+
+def _random_layers(count, seed):
+    """Seeded random layers: sizes, taps, borders (up to "full" and beyond the filter), strides, both modes, both data
+    types, packed and channel-fastest tensors, with and without a workspace."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        dtype = ("f32", "bf16")[int(rng.integers(0, 2))]
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        u, v = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        pad = (int(rng.integers(0, R + 1)), int(rng.integers(0, S + 1)))
+        H, W = int(rng.integers(1, 25)), int(rng.integers(1, 25))
+        if H + 2 * pad[0] < R or W + 2 * pad[1] < S:
+            continue
+        N, K = int(rng.integers(1, 7)), int(rng.integers(1, 91))
+        C = int(rng.integers(1, 81))
+        if rng.integers(0, 3) == 0:
+            C = 16 * int(rng.integers(1, 6))     # whole channel vectors: the bf16 channel-vector kernels become eligible
+        layout = ("NCHW", "NHWC")[int(rng.integers(0, 2))]
+        alpha, beta = (1.0, 0.5, -2.0)[int(rng.integers(0, 3))], (0.0, 0.0, 1.0, -1.5)[int(rng.integers(0, 4))]
+        out.append(((N, C, H, W, K, R, S, pad, (u, v)), dtype, int(rng.integers(0, 2)), layout,
+                    ("full", "none")[int(rng.integers(0, 2))], alpha, beta))
+    return out
+
+
+def test_random_layers_all_three_passes():
+    """150 seeded random layers, each through the forward pass, backward data and backward filter with the kernels
+    the library picks, against the oracle (alpha and beta included)."""
+    gu = _gpu()
+    for i, (prob, dtype, mode, layout, workspace, alpha, beta) in enumerate(_random_layers(150, 2024)):
+        N, C, H, W, K, R, S, pad, stride = prob
+        print("random layer", i, prob, dtype, mode, layout, workspace, alpha, beta, flush=True)
+        x = wl.with_layout(_rnd(7000 + i, (N, C, H, W), dtype), layout)
+        w = _rnd(7100 + i, (K, C, R, S), dtype)
+        P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
+        y0 = _rnd(7150 + i, (N, K, P, Q), "f32") if beta != 0.0 else None
+        want = oc.conv_forward(x, w, pad=pad, stride=stride, mode=mode, alpha=alpha, beta=beta, y_old=y0)
+        got, _ = gu.run(x, w, pad, stride, mode, alpha, beta, y0, dtype, layout)
+        assert np.all(np.isfinite(got)) and gu.rel_err(got, want) <= gu.BOUND[dtype]
+        _check_bd(prob, dtype, mode, alpha, beta, dx_layout=layout, dy_layout=layout, seed=7200 + 3 * i, workspace=workspace)
+        _check_bf(prob, dtype, mode, alpha, beta, x_layout=layout, dy_layout=layout, seed=7400 + 3 * i, workspace=workspace)
