@@ -273,6 +273,38 @@ def run_padded_filters(steps, warmup):
     return out
 
 
+def run_small_layers(steps, warmup):
+    """Padded layers at the mini-batches of serving (a handful of images, 7x7 to 28x28 pixels, long reductions): few
+    output elements, so that tiles of 64 x 64 and more leave most compute units idle.  The library runs them with 32 x 32
+    tiles and the reduction cut among the wavefronts of a workgroup (no workspace); beside it the same call with the
+    pipelined nine-tap kernel forced, and parity of the whole output against the oracle."""
+    import workloads as wl
+    from oracle import conv_oracle as oc
+    from paper_1410_0759_amd import runner as gu
+    import paper_1410_0759_amd as ig
+
+    names = ig.kernel_names()
+    out = []
+    for (N, C, HW, K, RS) in ((4, 512, 7, 512, 3), (1, 256, 14, 256, 3), (1, 512, 28, 512, 3), (2, 128, 28, 128, 5)):
+        pad = (RS // 2, RS // 2)
+        x, w = wl.random_problem(800 + HW + RS, N, C, HW, HW, K, RS, RS)
+        flops = 2.0 * N * K * HW * HW * C * RS * RS
+        g = gu.GpuConv(x, w, pad, (1, 1), 1)
+        entry = {"shape": "N%d C%d %dx%d K%d %dx%d pad %d" % (N, C, HW, HW, K, RS, RS, pad[0]), "gflop": flops / 1e9,
+                 "kernel": names[g.plan().kernelId]}
+        g.prefill(value=float("nan"))
+        g.launch(1.0, 0.0)
+        entry["rel_err"] = gu.rel_err(g.result(), oc.conv_forward(x, w, pad=pad, stride=(1, 1), mode=1))
+        ms = time_gpu(g, 1.0, 0.0, steps, warmup)
+        entry.update({"ms": ms, "tflops": flops / ms / 1e9})
+        other = "f32 64x64x72 taps9" if RS == 3 else "f32 32x128x32 tapmajor"
+        g.handle.set_kernel_override(names.index(other))
+        ms = time_gpu(g, 1.0, 0.0, steps, warmup)
+        entry["pipelined_kernel"] = {"kernel": other, "ms": ms, "tflops": flops / ms / 1e9}
+        out.append(entry)
+    return out
+
+
 def run_other_functions(steps, warmup):
     """The bandwidth-bound functions (activations, bias addition, softmax, pooling) on
     layer-sized float tensors: time per call, algorithmic bytes (each tensor once) per second
@@ -517,6 +549,7 @@ def main():
     ap.add_argument("--f64-only", action="store_true", help="time only the double-precision section")
     ap.add_argument("--table2-only", action="store_true", help="time only the paper's Table-2 layer collection")
     ap.add_argument("--padded-only", action="store_true", help="time only the padded 5x5 / 7x7 layers")
+    ap.add_argument("--small-only", action="store_true", help="time only the padded layers at serving mini-batches")
     ap.add_argument("--kernel", type=int, default=None, help="force a kernel id for the headline workload")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference "
@@ -562,6 +595,9 @@ def main():
         return
     if args.padded_only:
         print(json.dumps(run_padded_filters(max(10, args.steps // 10), max(10, args.warmup // 5))))
+        return
+    if args.small_only:
+        print(json.dumps(run_small_layers(max(10, args.steps // 10), max(10, args.warmup // 5))))
         return
     if args.batch_sweep_only:
         print(json.dumps(run_batch_sweep(max(10, args.steps // 10), max(5, args.warmup // 10))))
@@ -610,6 +646,10 @@ def main():
     padded = []
     if not args.only and not args.no_backward and not args.no_table2:
         padded = run_padded_filters(max(10, args.steps // 10), max(10, args.warmup // 5))
+
+    small = []
+    if not args.only and not args.no_table2:
+        small = run_small_layers(max(10, args.steps // 10), max(10, args.warmup // 5))
 
     other = []
     double_precision = None
@@ -664,6 +704,7 @@ def main():
         "table2_batch_sweep": batch_sweep,
         "backward": backward,
         "padded_filter_layers": padded,
+        "small_mini_batch_layers": small,
         "other_functions": other,
         "double_precision": double_precision,
         "paper_context": "paper Table 3: 0.99-1.52 TFLOP/s (23-35% of 4.29) on Tesla K40, 1.46-2.49 (30-51% of 4.95) "
