@@ -245,11 +245,6 @@ static double plan_cost(const igcContext *h, const KernelInfo &ki, const ConvKer
     return tile_times * eff_steps * (double)ki.BN * ki.BK * (ki.BM + gather) * (ki.BK == 16 ? 0.975 : 1.0);
 }
 
-// Gather modes a kernel may use for this problem (see the kernel source): the unpadded
-// mode needs pad 0, the nine-tap table R*S = 9 and whole steps of four channels; the
-// generic and the tap-major modes always work.  The channel-vector mode (bf16) reads 8
-// channels of one pixel with one 16-byte load: R*S = 9, whole steps of 16 channels, unit
-// channel stride, every other stride a multiple of 8 elements and x itself 16-byte aligned.
 // Largest number of pixels of the zero-extended images (flat index over all images) between
 // the first pixel of a tile's first column window and the last pixel of its last column's,
 // for tiles of bn consecutive columns: an upper bound.  Going from one column to the next
@@ -270,6 +265,9 @@ static long long patch_pixels_bound(const ConvKernelParams &k, int bn) {
 // channels of one pixel with one 16-byte load: R*S = 9, whole steps of 16 channels, unit
 // channel stride, every other stride a multiple of 8 elements and x itself 16-byte aligned;
 // staging a patch of the zero-extended image needs every tile's pixel range to fit it.
+// The masked filter-order mode keeps a bit per tap (up to 63 taps); the small-tile modes that
+// cut the reduction inside a workgroup need an entry of their offset table for every index a
+// wavefront can request, and pad 0 or - with a tap mask per column - at most 31 taps.
 static bool gather_mode_ok(const KernelInfo &ki, const ConvKernelParams &k, bool x_aligned) {
     const int gmode = ki.gmode;
     if (gmode == 6 || gmode == 8 || gmode == 9 || gmode == 10) return false;  // backward-filter kernels are chosen by that pass itself
