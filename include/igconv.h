@@ -482,9 +482,17 @@ igcStatus igcConvolutionBackwardFilterNoAlloc(igcHandle_t handle, const void *al
  * wavefronts per SIMD on every compute unit) for about `milliseconds` on the handle's
  * stream, WAITS for it, and returns the rate in TFLOP/s: the arithmetic ceiling at the
  * clocks the chip sustains, to be read beside the datasheet peak.  Allocates nothing on
- * the device.  BAD_PARAM: null pointer, unknown type, milliseconds outside 1..2000. */
+ * the device.  BAD_PARAM: null pointer, unknown type, milliseconds outside 1..2000.
+ * igcMeasureMatrixRateOperands: the same loop with a choice of operand values.  randomOperands
+ * = 0: one value per lane, the same in every instruction (igcMeasureMatrixRate: the matrix
+ * pipes switch few bits and the chip holds its highest clocks).  randomOperands = 1: finite
+ * pseudo-random values of mixed sign, another set of registers with every instruction, as
+ * the operands of a real product change: the pipes draw more power, the chip sustains lower
+ * clocks, and the rate is the ceiling a kernel fed with real data can reach.  BAD_PARAM also
+ * for any other value of randomOperands. */
 igcStatus igcGetDeviceProperties(igcHandle_t handle, int *computeUnits, int *clockKHz);
 igcStatus igcMeasureMatrixRate(igcHandle_t handle, igcDataType dataType, int milliseconds, double *tflops);
+igcStatus igcMeasureMatrixRateOperands(igcHandle_t handle, igcDataType dataType, int milliseconds, int randomOperands, double *tflops);
 
 /* ---- checks of the host logic (test tier; host only, no GPU call) --------------------
  * igcCreate reads the number of compute units of the current device into the handle (256,

@@ -22,7 +22,7 @@ __all__ = [
     "IGC_ACTIVATION_SIGMOID", "IGC_ACTIVATION_RELU", "IGC_ACTIVATION_TANH", "IGC_SOFTMAX_MODE_INSTANCE",
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
-    "get_device_properties", "measure_matrix_rate", "convolution_backward_filter_no_alloc", "NOALLOC_SCRATCH_BYTES",
+    "get_device_properties", "measure_matrix_rate", "measure_matrix_rate_operands", "convolution_backward_filter_no_alloc", "NOALLOC_SCRATCH_BYTES",
     "set_compute_units", "get_compute_units", "get_forward_address_reach", "get_backward_data_address_reach",
 ]
 
@@ -99,6 +99,7 @@ DECLARED_SYMBOLS = {
     "igcConvolutionBackwardFilterNoAlloc": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcGetDeviceProperties": (_i, [_vp, _P(_i), _P(_i)]),
     "igcMeasureMatrixRate": (_i, [_vp, _i, _i, _P(ctypes.c_double)]),
+    "igcMeasureMatrixRateOperands": (_i, [_vp, _i, _i, _i, _P(ctypes.c_double)]),
     "igcSetComputeUnits": (_i, [_vp, _i]),
     "igcGetComputeUnits": (_i, [_vp, _P(_i)]),
     "igcGetConvolutionForwardAddressReach": (_i, [_vp, _vp, _vp, _vp, _vp, _P(ctypes.c_longlong), _P(ctypes.c_longlong)]),
@@ -410,6 +411,13 @@ def measure_matrix_rate(handle, dtype, milliseconds=50):
     """TFLOP/s of a register-only loop of the data type's matrix instruction (waits for the GPU)."""
     out = ctypes.c_double()
     check(lib().igcMeasureMatrixRate(handle.ptr, dtype, milliseconds, ctypes.byref(out)), "igcMeasureMatrixRate")
+    return out.value
+
+
+def measure_matrix_rate_operands(handle, dtype, milliseconds=50, random_operands=1):
+    """The same with a choice of operand values: 0 uniform (as measure_matrix_rate), 1 pseudo-random, changing with every instruction."""
+    out = ctypes.c_double()
+    check(lib().igcMeasureMatrixRateOperands(handle.ptr, dtype, milliseconds, random_operands, ctypes.byref(out)), "igcMeasureMatrixRateOperands")
     return out.value
 
 

@@ -23,52 +23,82 @@ __device__ __forceinline__ void sink(float v) {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), none, threadIdx.x * 4u, 0, 0);
 }
 
-__global__ __launch_bounds__(256) void mfma_rate_f32(int iters, float a0) {
-    f32x16 acc[kProbeAcc];
-    for (int i = 0; i < kProbeAcc; ++i)
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    const float a = a0 + threadIdx.x * 1e-9f, b = a0 * 2.f;
-    for (int it = 0; it < iters; ++it)
-#pragma unroll
-        for (int u = 0; u < kProbeUnroll; ++u)
-#pragma unroll
-            for (int i = 0; i < kProbeAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
-    float s = 0;
-    for (int i = 0; i < kProbeAcc; ++i)
-        for (int v = 0; v < 16; ++v) s += acc[i][v];
-    sink(s);
+constexpr int kProbeSets = 4;     // operand sets the instructions rotate through
+
+// Operand values of the probe.  Uniform: one value per lane, the same in every set and every instruction (the matrix
+// pipes switch few bits: the rate at the highest clocks the chip gives).  Random: finite values of mixed sign and
+// magnitude below 1, another set with every instruction, as the operands of a real product change - the pipes then
+// draw more power and the chip sustains lower clocks: the ceiling a kernel fed with real data can reach.
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ float probe_value(uint32_t index) {   // in [-1, 1)
+    return __builtin_bit_cast(float, 0x3F800000u | (probe_hash(index) >> 9)) * 2.f - 3.f;
 }
 
-__global__ __launch_bounds__(256) void mfma_rate_bf16(int iters, float a0) {
+__global__ __launch_bounds__(256) void mfma_rate_f32(int iters, float a0, int random) {
     f32x16 acc[kProbeAcc];
     for (int i = 0; i < kProbeAcc; ++i)
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    bf16x8 a, b;
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)(a0 + i);
-        b[i] = (__bf16)(a0 - i);
+    float a[kProbeSets], b[kProbeSets];
+    for (int s = 0; s < kProbeSets; ++s) {
+        const uint32_t id = (blockIdx.x * 256u + threadIdx.x) * 2u * kProbeSets + 2u * s;
+        a[s] = random ? probe_value(id) : a0 + threadIdx.x * 1e-9f;
+        b[s] = random ? probe_value(id + 1u) : a0 * 2.f;
     }
     for (int it = 0; it < iters; ++it)
 #pragma unroll
         for (int u = 0; u < kProbeUnroll; ++u)
 #pragma unroll
-            for (int i = 0; i < kProbeAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < kProbeAcc; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[(i + u) % kProbeSets], b[(i + 3 * u + 1) % kProbeSets], acc[i], 0, 0, 0);
     float s = 0;
     for (int i = 0; i < kProbeAcc; ++i)
         for (int v = 0; v < 16; ++v) s += acc[i][v];
     sink(s);
 }
 
-__global__ __launch_bounds__(256) void mfma_rate_f64(int iters, double a0) {
-    f64x4 acc[kProbeAcc];
+__global__ __launch_bounds__(256) void mfma_rate_bf16(int iters, float a0, int random) {
+    f32x16 acc[kProbeAcc];
     for (int i = 0; i < kProbeAcc; ++i)
-        for (int v = 0; v < 4; ++v) acc[i][v] = 0.0;
-    const double a = a0 + threadIdx.x * 1e-12, b = a0 * 2.0;
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    bf16x8 a[kProbeSets], b[kProbeSets];
+    for (int s = 0; s < kProbeSets; ++s)
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t id = ((blockIdx.x * 256u + threadIdx.x) * kProbeSets + s) * 16u + 2u * i;
+            a[s][i] = (__bf16)(random ? probe_value(id) : a0 + i);
+            b[s][i] = (__bf16)(random ? probe_value(id + 1u) : a0 - i);
+        }
     for (int it = 0; it < iters; ++it)
 #pragma unroll
         for (int u = 0; u < kProbeUnroll; ++u)
 #pragma unroll
-            for (int i = 0; i < kProbeAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < kProbeAcc; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + u) % kProbeSets], b[(i + 3 * u + 1) % kProbeSets], acc[i], 0, 0, 0);
+    float s = 0;
+    for (int i = 0; i < kProbeAcc; ++i)
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    sink(s);
+}
+
+__global__ __launch_bounds__(256) void mfma_rate_f64(int iters, double a0, int random) {
+    f64x4 acc[kProbeAcc];
+    for (int i = 0; i < kProbeAcc; ++i)
+        for (int v = 0; v < 4; ++v) acc[i][v] = 0.0;
+    double a[kProbeSets], b[kProbeSets];
+    for (int s = 0; s < kProbeSets; ++s) {
+        const uint32_t id = (blockIdx.x * 256u + threadIdx.x) * 4u * kProbeSets + 4u * s;
+        // (two hashed words per value: all 52 bits of the significand vary)
+        a[s] = random ? (double)probe_value(id) + (double)probe_value(id + 1u) * 0x1p-24 : a0 + threadIdx.x * 1e-12;
+        b[s] = random ? (double)probe_value(id + 2u) + (double)probe_value(id + 3u) * 0x1p-24 : a0 * 2.0;
+    }
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u)
+#pragma unroll
+            for (int i = 0; i < kProbeAcc; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[(i + u) % kProbeSets], b[(i + 3 * u + 1) % kProbeSets], acc[i], 0, 0, 0);
     double s = 0;
     for (int i = 0; i < kProbeAcc; ++i)
         for (int v = 0; v < 4; ++v) s += acc[i][v];
@@ -107,7 +137,11 @@ igcStatus igcGetDeviceProperties(igcHandle_t handle, int *computeUnits, int *clo
 }
 
 igcStatus igcMeasureMatrixRate(igcHandle_t handle, igcDataType dataType, int milliseconds, double *tflops) {
-    if (!handle || !tflops || milliseconds < 1 || milliseconds > 2000) return IGC_STATUS_BAD_PARAM;
+    return igcMeasureMatrixRateOperands(handle, dataType, milliseconds, 0, tflops);
+}
+
+igcStatus igcMeasureMatrixRateOperands(igcHandle_t handle, igcDataType dataType, int milliseconds, int randomOperands, double *tflops) {
+    if (!handle || !tflops || milliseconds < 1 || milliseconds > 2000 || (randomOperands != 0 && randomOperands != 1)) return IGC_STATUS_BAD_PARAM;
     if (dataType != IGC_DATA_FLOAT && dataType != IGC_DATA_BFLOAT16 && dataType != IGC_DATA_DOUBLE) return IGC_STATUS_BAD_PARAM;
     int cus = 0, khz = 0;
     igcStatus st = igcGetDeviceProperties(handle, &cus, &khz);
@@ -123,9 +157,9 @@ igcStatus igcMeasureMatrixRate(igcHandle_t handle, igcDataType dataType, int mil
     if (iters < 16) iters = 16;
     if (iters > (1 << 24)) iters = 1 << 24;
     auto launch = [&](int n) {
-        if (dataType == IGC_DATA_FLOAT) hipLaunchKernelGGL(mfma_rate_f32, dim3(grid), dim3(256), 0, stream, n, 1.f);
-        else if (dataType == IGC_DATA_BFLOAT16) hipLaunchKernelGGL(mfma_rate_bf16, dim3(grid), dim3(256), 0, stream, n, 1.f);
-        else hipLaunchKernelGGL(mfma_rate_f64, dim3(grid), dim3(256), 0, stream, n, 1.0);
+        if (dataType == IGC_DATA_FLOAT) hipLaunchKernelGGL(mfma_rate_f32, dim3(grid), dim3(256), 0, stream, n, 1.f, randomOperands);
+        else if (dataType == IGC_DATA_BFLOAT16) hipLaunchKernelGGL(mfma_rate_bf16, dim3(grid), dim3(256), 0, stream, n, 1.f, randomOperands);
+        else hipLaunchKernelGGL(mfma_rate_f64, dim3(grid), dim3(256), 0, stream, n, 1.0, randomOperands);
     };
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {

@@ -196,3 +196,27 @@ def test_transform_tensor_changes_layout():
     xt = np.ascontiguousarray(x.transpose(3, 0, 1, 2)).transpose(1, 2, 3, 0)        # memory order W,N,C,H
     assert np.array_equal(gu.run_transform_tensor(xt, layout="NCHW"), x.astype(np.float64))
     assert np.array_equal(gu.run_transform_tensor(x, y_strides=(24 * 70 * 9, 70 * 9, 1, 9)), x.astype(np.float64))
+
+
+def test_matrix_rate_probe():
+    """The measurement aid of the bench: the register-only MFMA loop returns a plausible rate for every data type, with
+    uniform and with pseudo-random operands (the same instruction stream, other values: never faster), and refuses bad
+    arguments."""
+    import torch
+    import paper_1410_0759_amd as ig
+    _gpu()
+    h = ig.Handle()
+    h.set_stream(torch.cuda.current_stream().cuda_stream)
+    cus, khz = ig.get_device_properties(h)
+    assert cus >= 8 and khz > 100000
+    for name, dt, peak in (("f32", ig.IGC_DATA_FLOAT, 157.3), ("bf16", ig.IGC_DATA_BFLOAT16, 2516.6), ("f64", ig.IGC_DATA_DOUBLE, 78.6)):
+        ig.measure_matrix_rate_operands(h, dt, 20, 0)   # (clocks)
+        uniform = ig.measure_matrix_rate_operands(h, dt, 40, 0)
+        same = ig.measure_matrix_rate(h, dt, 40)
+        random = ig.measure_matrix_rate_operands(h, dt, 40, 1)
+        print("matrix rate", name, uniform, same, random, flush=True)
+        assert 0.3 * peak < random <= 1.05 * uniform and uniform < 1.1 * peak
+        assert abs(same - uniform) < 0.1 * uniform
+    for bad in ((ig.IGC_DATA_FLOAT, 0, 0), (ig.IGC_DATA_FLOAT, 5000, 1), (ig.IGC_DATA_FLOAT, 10, 2), (17, 10, 0)):
+        with pytest.raises(ig.IgcError):
+            ig.measure_matrix_rate_operands(h, *bad)
