@@ -335,7 +335,7 @@ static igcStatus choose(const igcContext *h, const Problem &pr, bool w_aligned, 
 // each depending on their LDS), each walking through several tiles; the channel-vector
 // bf16 kernels take one tile per workgroup.
 static int workgroups_per_xcd(const igcContext *h, const KernelInfo &ki, int tiles_per_xcd) {
-    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || ki.gmode == 12 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || is_direct(ki.gmode)) return tiles_per_xcd;
+    if (ki.gmode == 4 || ki.gmode == 5 || ki.gmode == 10 || (ki.f64 && ki.gmode != 14) || ki.variant == 2 || is_direct(ki.gmode)) return tiles_per_xcd;
     return std::min(tiles_per_xcd, std::max(1, h->computeUnits / kXcds) * workgroups_per_cu(ki));
 }
 

@@ -9,7 +9,7 @@
 // Tile BM x BN x 64 channels, 2 x 2 wavefronts, v_mfma_f32_32x32x16_bf16; LDS rows of
 // 64 channels + 16 bytes (an odd number of 16-byte units: conflict-free 16-byte accesses);
 // global loads two steps ahead in two register sets, a loop without branches, one barrier
-// per step.  One workgroup per tile.  The epilogue is the shared one (alpha/beta, bias,
+// per step.  Persistent workgroups whose loads run on across the tile boundary.  The epilogue is the shared one (alpha/beta, bias,
 // activation, either orientation of the output).
 #ifndef IGCONV_KERNEL_BF16_PW_HPP_
 #define IGCONV_KERNEL_BF16_PW_HPP_
@@ -45,9 +45,15 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
-    const int tile = (int)(blockIdx.x % 8u) * p.tilesPerXcd + (int)(blockIdx.x / 8u);
-    if (tile >= p.tilesM * p.tilesN) return;
-    const int m0 = (tile % p.tilesM) * BM, n0 = (tile / p.tilesM) * BN;
+    // Persistent: the workgroup takes every wgsPerXcd-th tile of its XCD's contiguous range, and the load pipeline runs
+    // on across the tile boundary - the last steps of a tile request the first two of the next one, which are on their
+    // way while the finished tile's epilogue stores (a layer with few channels is a tile of one or two steps: its
+    // whole life was a wait for those loads).
+    const int tiles = p.tilesM * p.tilesN;
+    const int xcd = (int)(blockIdx.x % 8u), slot = (int)(blockIdx.x / 8u);
+    const int range_end = (xcd + 1) * p.tilesPerXcd < tiles ? (xcd + 1) * p.tilesPerXcd : tiles;
+    int tile = xcd * p.tilesPerXcd + slot;
+    if (tile >= range_end) return;
 
     const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, p.x_bytes, kBufferWord3);
     const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.w), 0, p.w_bytes, kBufferWord3);
@@ -55,32 +61,37 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
 
     // ---- loading role: channel vector vec of the step, rows (filter rows / pixels) tid/8 + 32 i
     const int vec = tid & 7, row = tid >> 3;
-    uint32_t a_off[NA], b_off[NBV];     // byte offsets of the rows' first channel, or the out-of-range marker
+    // byte offsets of the rows' first channel, or the out-of-range marker (everything, for a tile that does not exist)
+    auto tile_offsets = [&](int t, uint32_t (&a_off)[NA], uint32_t (&b_off)[NBV]) {
+        const bool live = t < range_end;
+        const int m0 = (t % p.tilesM) * BM, n0 = (t / p.tilesM) * BN;
 #pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const int m = m0 + row + 32 * i;
-        a_off[i] = m < p.K ? (uint32_t)m * (uint32_t)p.C * 2u : kOutOfRange;
-    }
+        for (int i = 0; i < NA; ++i) {
+            const int m = m0 + row + 32 * i;
+            a_off[i] = live && m < p.K ? (uint32_t)m * (uint32_t)p.C * 2u : kOutOfRange;
+        }
 #pragma unroll
-    for (int i = 0; i < NBV; ++i) {
-        const int j = n0 + row + 32 * i;
-        const uint32_t jj = j < p.NPQ ? (uint32_t)j : 0u;
-        const uint32_t n = magic_div(jj, p.mPQ), rem = jj - n * (uint32_t)p.PQ;
-        const uint32_t pp = magic_div(rem, p.mQ), qq = rem - pp * (uint32_t)p.Q;
-        const uint32_t h = pp * (uint32_t)p.u - (uint32_t)p.pad_h, w = qq * (uint32_t)p.v - (uint32_t)p.pad_w;   // (wrap below zero: fail the test)
-        const bool ok = j < p.NPQ && h < (uint32_t)p.H && w < (uint32_t)p.W;
-        b_off[i] = ok ? (n * (uint32_t)p.xsN + h * (uint32_t)p.xsH + w * (uint32_t)p.xsW) * 2u : kOutOfRange;
-    }
+        for (int i = 0; i < NBV; ++i) {
+            const int j = n0 + row + 32 * i;
+            const uint32_t jj = live && j < p.NPQ ? (uint32_t)j : 0u;
+            const uint32_t n = magic_div(jj, p.mPQ), rem = jj - n * (uint32_t)p.PQ;
+            const uint32_t pp = magic_div(rem, p.mQ), qq = rem - pp * (uint32_t)p.Q;
+            const uint32_t h = pp * (uint32_t)p.u - (uint32_t)p.pad_h, w = qq * (uint32_t)p.v - (uint32_t)p.pad_w;   // (wrap below zero: fail the test)
+            const bool ok = live && j < p.NPQ && h < (uint32_t)p.H && w < (uint32_t)p.W;
+            b_off[i] = ok ? (n * (uint32_t)p.xsN + h * (uint32_t)p.xsH + w * (uint32_t)p.xsW) * 2u : kOutOfRange;
+        }
+    };
+    uint32_t a_off[NA], b_off[NBV], a_nxt[NA], b_nxt[NBV];   // of the current tile and of the next one
     u32x4_t a0[NA], b0[NBV], a1[NA], b1[NBV];
-    auto fetch = [&](int step, u32x4_t (&a)[NA], u32x4_t (&b)[NBV]) {
+    auto fetch_from = [&](int step, const uint32_t (&ao)[NA], const uint32_t (&bo)[NBV], u32x4_t (&a)[NA], u32x4_t (&b)[NBV]) {
         const int ch = step * BK + vec * 8;
-        const uint32_t co = ch < p.C ? (uint32_t)ch * 2u : kOutOfRange;     // (also every step past the last one)
+        const uint32_t co = ch < p.C ? (uint32_t)ch * 2u : kOutOfRange;     // (also the step that makes an odd count even)
 #pragma unroll
         for (int i = 0; i < NA; ++i)
-            a[i] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (a_off[i] | co) >= kOutOfRange ? kOutOfRange : a_off[i] + co, 0, 0);
+            a[i] = __builtin_amdgcn_raw_buffer_load_b128(wbuf, (ao[i] | co) >= kOutOfRange ? kOutOfRange : ao[i] + co, 0, 0);
 #pragma unroll
         for (int i = 0; i < NBV; ++i)
-            b[i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, (b_off[i] | co) >= kOutOfRange ? kOutOfRange : b_off[i] + co, 0, 0);
+            b[i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, (bo[i] | co) >= kOutOfRange ? kOutOfRange : bo[i] + co, 0, 0);
     };
     auto stage = [&](int buf, const u32x4_t (&a)[NA], const u32x4_t (&b)[NBV]) {
         uint8_t *base = lds + buf * Cfg::STAGE_BYTES + row * RB + vec * 16;
@@ -91,20 +102,14 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
     };
 
     f32x16 acc[MB][NB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    float bias[MB];
-    load_bias<MB>(p, m0 + wm * (BM / 2), l32, bias);
+    const int steps = (p.ksteps + 1) & ~1;   // per tile, an even number: the step added to an odd count reads zeros
 
-    // step s multiplies LDS stage `cur`, moves the loaded data of step s+1 to the other stage and requests
-    // step s+2 (zeros past the end, so an odd number of steps simply runs one more)
+    // step s multiplies LDS stage `cur`, moves the loaded data of step s+1 to the other stage and requests step s+2 -
+    // of this tile, or step s+2-steps of the next one
     auto body = [&](int s, int cur, u32x4_t (&a_new)[NA], u32x4_t (&b_new)[NBV], const u32x4_t (&a_next)[NA],
                     const u32x4_t (&b_next)[NBV]) __attribute__((always_inline)) {
-        fetch(s + 2, a_new, b_new);
+        if (s + 2 < steps) fetch_from(s + 2, a_off, b_off, a_new, b_new);
+        else fetch_from(s + 2 - steps, a_nxt, b_nxt, a_new, b_new);
         const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
         const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
 #pragma unroll
@@ -127,15 +132,33 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
         stage(cur ^ 1, a_next, b_next);
         __syncthreads();
     };
-    fetch(0, a0, b0);
-    fetch(1, a1, b1);
+    tile_offsets(tile, a_off, b_off);
+    fetch_from(0, a_off, b_off, a0, b0);
+    fetch_from(1, a_off, b_off, a1, b1);
     stage(0, a0, b0);
     __syncthreads();
-    for (int s = 0; s < p.ksteps; s += 2) {
-        body(s, 0, a0, b0, a1, b1);
-        body(s + 1, 1, a1, b1, a0, b0);
+    for (; tile < range_end; tile += p.wgsPerXcd) {
+        const int m0 = (tile % p.tilesM) * BM, n0 = (tile / p.tilesM) * BN;
+        tile_offsets(tile + p.wgsPerXcd, a_nxt, b_nxt);
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        float bias[MB];
+        load_bias<MB>(p, m0 + wm * (BM / 2), l32, bias);
+        for (int s = 0; s < steps; s += 2) {
+            body(s, 0, a0, b0, a1, b1);
+            body(s + 1, 1, a1, b1, a0, b0);
+        }
+        // (LDS stage 0 and the registers now hold the next tile's first two steps)
+        store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bias, m0 + wm * (BM / 2), n0 + wn * (BN / 2), half, l32);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) a_off[i] = a_nxt[i];
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) b_off[i] = b_nxt[i];
     }
-    store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bias, m0 + wm * (BM / 2), n0 + wn * (BN / 2), half, l32);
 }
 
 }  // namespace igc
