@@ -3,8 +3,9 @@
  * the three neuron activations (sigmoid, rectified linear, hyperbolic tangent), forward
  * and backward; softmax, computed the numerically stable way (every element shifted by
  * the maximum before exponentiation), per image over (feature map, height, width) or per
- * spatial location over the feature maps; max and average pooling; and the addition of
- * tensors with optional broadcasting.  TEST INFRASTRUCTURE ONLY: used by the tests, the
+ * spatial location over the feature maps; max and average pooling; the addition of
+ * tensors with optional broadcasting; and the gradient with respect to a bias added that
+ * way (Section 4).  TEST INFRASTRUCTURE ONLY: used by the tests, the
  * smoke check and the bench's baseline leg; the HIP library never calls it and shares no
  * code with it.
  *

@@ -1,6 +1,6 @@
 """ctypes front end of the C oracle for the library's other functions
 (``pointwise_oracle.c``: activations, softmax, pooling, tensor addition with
-broadcasting).  TEST INFRASTRUCTURE ONLY.  The arithmetic lives in the C file; this
+broadcasting and its transpose, the bias gradient).  TEST INFRASTRUCTURE ONLY.  The arithmetic lives in the C file; this
 module only marshals numpy arrays and strides."""
 import ctypes
 import os
@@ -100,6 +100,23 @@ def add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
         *[ctypes.c_int(d) for d in shape], ctypes.c_double(alpha), ctypes.c_double(beta),
         ctypes.c_void_p(old_ptr), ctypes.c_void_p(y.ctypes.data), _strides(y)), "add_tensor")
     return y
+
+
+def bias_backward(dy, alpha=1.0, beta=0.0, db_old=None):
+    """alpha * (sum of dy over n, h, w per feature map) + beta * db_old: C values as float64."""
+    dy = _f32(dy)
+    db = np.empty(dy.shape[1], dtype=np.float64)
+    keep = None
+    if db_old is not None:
+        keep = np.ascontiguousarray(np.asarray(db_old, dtype=np.float64).reshape(-1))
+        assert keep.shape == db.shape
+    elif beta != 0.0:
+        raise ValueError("beta != 0 needs the old output")
+    _check(_fn("bias_backward", dy)(
+        ctypes.c_void_p(dy.ctypes.data), _strides(dy), *[ctypes.c_int(d) for d in dy.shape],
+        ctypes.c_double(alpha), ctypes.c_double(beta), ctypes.c_void_p(keep.ctypes.data if keep is not None else None),
+        ctypes.c_void_p(db.ctypes.data)), "bias_backward")
+    return db
 
 
 def softmax_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):

@@ -23,6 +23,8 @@ int pointwise_oracle_activation_backward(int mode, const float *y, const long lo
                                          double beta, const double *dx_old, double *dx, const long long *dxs);
 int pointwise_oracle_add_tensor(const float *b, const long long *bs, int bN, int bC, int bH, int bW, int N, int C, int H, int W,
                                 double alpha, double beta, const double *y_old, double *y, const long long *ys);
+int pointwise_oracle_bias_backward(const float *dy, const long long *dys, int N, int C, int H, int W, double alpha, double beta,
+                                   const double *db_old, double *db);
 int pointwise_oracle_softmax_forward(int mode, const float *x, const long long *xs, int N, int C, int H, int W, double alpha,
                                      double beta, const double *y_old, double *y, const long long *ys);
 int pointwise_oracle_softmax_backward(int mode, const float *y, const long long *ys, const float *dy, const long long *dys, int N,
@@ -101,6 +103,10 @@ int main(void)
             float *b = floats(C);
             CHECK(pointwise_oracle_add_tensor(b, bs, 1, C, 1, 1, N, C, H, W, 2.0, 1.0, dx_old, dx, xs));
             free(b);
+            double *db = doubles(C), *db_old = doubles(C);   /* and the gradient with respect to it */
+            CHECK(pointwise_oracle_bias_backward(x, xs, N, C, H, W, 1.0, 0.5, db_old, db));
+            free(db);
+            free(db_old);
         }
         {   /* pooling with the convolution's window geometry */
             long long ps[4];

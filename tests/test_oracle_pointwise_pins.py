@@ -82,6 +82,36 @@ def test_add_tensor_broadcasts_size_one_dimensions():
         po.add_tensor(rnd(10, 1, 2, 1, 1), shape)     # 2 is neither 1 nor C
 
 
+def test_bias_gradient_hand_values_and_the_transpose_of_the_broadcast():
+    """db[c] = sum of dy over images and pixels.  Hand case on the integers 0..15 as a (2,2,2,2) tensor: feature map 0
+    holds 0..3 and 8..11 (sum 44), feature map 1 holds 4..7 and 12..15 (sum 76); all ones count the N*H*W pixels; the
+    function is the transpose of add_tensor's broadcast of a (1,C,1,1) bias (<broadcast(b), dy> = <b, db>), with
+    add_tensor pinned on its own above; numpy's sum over the axes; any layout; the accumulate form."""
+    dy = np.arange(16, dtype=np.float32).reshape(2, 2, 2, 2)
+    assert np.array_equal(po.bias_backward(dy), [44.0, 76.0])
+    assert np.array_equal(po.bias_backward(np.ones((3, 5, 4, 7), dtype=np.float32)), np.full(5, 3 * 4 * 7.0))
+    dy = rnd(61, 3, 5, 4, 7)
+    b = rnd(62, 1, 5, 1, 1)
+    lhs = float(np.sum(po.add_tensor(b, dy.shape) * dy.astype(np.float64)))
+    rhs = float(np.dot(b.astype(np.float64).reshape(-1), po.bias_backward(dy)))
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), 1.0)
+    want = dy.astype(np.float64).sum(axis=(0, 2, 3))
+    assert np.allclose(po.bias_backward(dy), want, rtol=1e-14, atol=1e-13)
+    assert np.array_equal(po.bias_backward(nhwc(dy)), po.bias_backward(dy))          # strides, not layout, address dy
+    old = rnd(63, 5).astype(np.float64)
+    assert np.allclose(po.bias_backward(dy, alpha=-0.5, beta=2.0, db_old=old), -0.5 * want + 2.0 * old, rtol=1e-14, atol=1e-13)
+    with pytest.raises(ValueError):
+        po.bias_backward(dy, beta=1.0)
+    # a single large element in a sea of small ones lands in its own feature map only
+    z = np.zeros((2, 3, 4, 4), dtype=np.float32)
+    z[1, 2, 3, 0] = 7.0
+    assert np.array_equal(po.bias_backward(z), [0.0, 0.0, 7.0])
+    # double inputs are not truncated to float on the way
+    d = np.full((1, 1, 1, 2), 1.0, dtype=np.float64)
+    d[0, 0, 0, 1] = 2.0 ** -40
+    assert po.bias_backward(d)[0] == 1.0 + 2.0 ** -40
+
+
 # ---------------------------------------------------------------- softmax
 def test_softmax_hand_values_and_stability():
     # exp(0) : exp(ln 2) : exp(ln 3) = 1 : 2 : 3 -> 1/6, 2/6, 3/6 over the channels
