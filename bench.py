@@ -306,7 +306,7 @@ def run_small_layers(steps, warmup):
 
 
 def run_other_functions(steps, warmup):
-    """The bandwidth-bound functions (activations, bias addition, softmax, pooling) on
+    """The bandwidth-bound functions (activations, bias addition and bias gradient, softmax, pooling) on
     layer-sized float tensors: time per call, algorithmic bytes (each tensor once) per second
     against the 8 TB/s HBM peak, parity against the oracle on the first image(s)."""
     import numpy as np
@@ -359,6 +359,22 @@ def run_other_functions(steps, warmup):
     err = gu.rel_err(yt[:2].cpu().numpy().astype(np.float64), po.add_tensor(bias, (2,) + shape[1:], 1.0, 1.0, x[:2]))
     ms = timed(lambda: ig.check(ig.add_tensor(h, 1.0, bd, bt.data_ptr(), 1.0, yd, yt.data_ptr()), "bias"))
     record("bias addition in place (1,C,1,1)", shape, 2 * nb, ms, err)
+    # the gradient with respect to that bias: dy summed per feature map (dy read once), with the workspace it asks for
+    dbt = torch.zeros(64, dtype=torch.float32, device="cuda")
+    dy_np = dyt.cpu().numpy()
+    want_db = po.bias_backward(dy_np[:4])
+    nhwc_dy = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, (shape[2] * shape[3] * shape[1], 1, shape[3] * shape[1], shape[1]))
+    dy_nhwc = torch.from_numpy(np.ascontiguousarray(dy_np.transpose(0, 2, 3, 1))).cuda()
+    for nm, desc, t in (("NCHW", dyd, dyt), ("NHWC", nhwc_dy, dy_nhwc)):
+        few = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, 4, *shape[1:], desc.get()[2])   # (parity on four images)
+        ws_bytes = ig.get_backward_bias_workspace_size(h, desc, bd)
+        ws = torch.empty(max(ws_bytes, 8), dtype=torch.uint8, device="cuda")
+        ig.check(ig.convolution_backward_bias(h, 1.0, few, t.data_ptr(), 0.0, bd, dbt.data_ptr(), ws.data_ptr(), ws_bytes), "bias gradient")
+        err = gu.rel_err(dbt.cpu().numpy().astype(np.float64), want_db)
+        ms = timed(lambda: ig.check(ig.convolution_backward_bias(h, 1.0, desc, t.data_ptr(), 0.0, bd, dbt.data_ptr(), ws.data_ptr(), ws_bytes),
+                                    "bias gradient"))
+        record("bias gradient, dy " + nm, shape, nb, ms, err)
+    del dy_nhwc
     # change of layout: NCHW -> NHWC and back
     nhwc = ig.TensorDescriptor().set(ig.IGC_DATA_FLOAT, *shape, (shape[2] * shape[3] * shape[1], 1, shape[3] * shape[1], shape[1]))
     ig.check(ig.transform_tensor(h, 1.0, xd, xt.data_ptr(), 0.0, nhwc, yt.data_ptr()), "to NHWC")

@@ -351,6 +351,29 @@ igcStatus igcAddTensor(igcHandle_t handle, const void *alpha,
                        igcTensorDescriptor_t bDesc, const void *b,
                        const void *beta, igcTensorDescriptor_t yDesc, void *y);
 
+/* Gradient with respect to the bias of a convolution layer (Section 4: the backward pass of a
+ * convolution layer computes the gradients with respect to the bias, the filter weights and
+ * the bottom data): db[c] = alpha * (sum over n, h, w of dy[n,c,h,w]) + beta * db[c], the
+ * transpose of igcAddTensor's broadcast of a (1,C,1,1) tensor.
+ * dyDesc: float, bfloat16 or double, any non-negative strides; dbDesc: dimensions (1,C,1,1),
+ * float (double for double dy), its feature-map stride at least 1; alpha and beta: float
+ * (double for double dy), host pointers.  dy and db are device pointers owned by the caller;
+ * every sum is accumulated in double and the order of the additions is fixed (bitwise
+ * repeatable).  workSpace may be NULL: with igcGetConvolutionBackwardBiasWorkspaceSize bytes
+ * of device memory (8-byte aligned) the positions are cut into ranges across the chip, whose
+ * sums a second kernel adds in order; without, one workgroup per (group of) feature map(s)
+ * adds everything - same result to rounding, slower on large tensors.  The workspace's
+ * contents before and after the call mean nothing.  Nothing is allocated.
+ * BAD_PARAM: null pointer, db's dimensions not (1,C,1,1), negative stride, misaligned
+ * pointer; NOT_INITIALIZED: descriptor not set; NOT_SUPPORTED: other type combinations,
+ * tensors of 2 GiB or more; EXECUTION_FAILED: the runtime refused a launch. */
+igcStatus igcGetConvolutionBackwardBiasWorkspaceSize(igcHandle_t handle, igcTensorDescriptor_t dyDesc,
+                                                     igcTensorDescriptor_t dbDesc, size_t *sizeInBytes);
+igcStatus igcConvolutionBackwardBias(igcHandle_t handle, const void *alpha,
+                                     igcTensorDescriptor_t dyDesc, const void *dy,
+                                     void *workSpace, size_t workSpaceSizeInBytes,
+                                     const void *beta, igcTensorDescriptor_t dbDesc, void *db);
+
 /* Tensor transformation (Section 2: auxiliary routines for the manipulation of 4-d tensors):
  * y = alpha * x + beta * y for two tensors of equal dimensions and any strides, i.e. a change
  * of layout (NCHW <-> NHWC, pitched <-> packed, a slice into a tensor of its own).  Where x

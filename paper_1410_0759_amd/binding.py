@@ -23,7 +23,7 @@ __all__ = [
     "IGC_SOFTMAX_MODE_CHANNEL", "IGC_POOLING_MAX", "IGC_POOLING_AVERAGE",
     "kernel_names", "magic_divisor", "magic_divide", "tensor_descriptor_for",
     "get_device_properties", "measure_matrix_rate", "measure_matrix_rate_operands", "convolution_backward_filter_no_alloc", "NOALLOC_SCRATCH_BYTES",
-    "set_compute_units", "get_compute_units", "get_forward_address_reach", "get_backward_data_address_reach",
+    "get_backward_bias_workspace_size", "convolution_backward_bias", "set_compute_units", "get_compute_units", "get_forward_address_reach", "get_backward_data_address_reach",
 ]
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -79,6 +79,8 @@ DECLARED_SYMBOLS = {
     "igcActivationForward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcActivationBackward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcAddTensor": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "igcGetConvolutionBackwardBiasWorkspaceSize": (_i, [_vp, _vp, _vp, _P(_sz)]),
+    "igcConvolutionBackwardBias": (_i, [_vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp, _vp]),
     "igcSoftmaxForward": (_i, [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "igcCreatePoolingDescriptor": (_i, [_P(_vp)]),
     "igcDestroyPoolingDescriptor": (_i, [_vp]),
@@ -272,6 +274,19 @@ def activation_backward(handle, mode, alpha, ydesc, y_ptr, dydesc, dy_ptr, xdesc
 def add_tensor(handle, alpha, bdesc, b_ptr, beta, ydesc, y_ptr):
     a, b = _scalars(ydesc, alpha, beta)
     return lib().igcAddTensor(handle.ptr, ctypes.byref(a), bdesc.ptr, _vp(b_ptr), ctypes.byref(b), ydesc.ptr, _vp(y_ptr))
+
+
+def get_backward_bias_workspace_size(handle, dydesc, dbdesc):
+    out = _sz()
+    check(lib().igcGetConvolutionBackwardBiasWorkspaceSize(handle.ptr, dydesc.ptr, dbdesc.ptr, ctypes.byref(out)),
+          "igcGetConvolutionBackwardBiasWorkspaceSize")
+    return out.value
+
+
+def convolution_backward_bias(handle, alpha, dydesc, dy_ptr, beta, dbdesc, db_ptr, workspace_ptr=0, workspace_bytes=0):
+    a, b = _scalars(dbdesc, alpha, beta)
+    return lib().igcConvolutionBackwardBias(handle.ptr, ctypes.byref(a), dydesc.ptr, _vp(dy_ptr), _vp(workspace_ptr), workspace_bytes,
+                                            ctypes.byref(b), dbdesc.ptr, _vp(db_ptr))
 
 
 def softmax_forward(handle, mode, alpha, xdesc, x_ptr, beta, ydesc, y_ptr):

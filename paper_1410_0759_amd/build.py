@@ -9,7 +9,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libigconv.so")
 SOURCES = ["igconv_api.cpp", "igconv_kernels_f32_taps9.hip", "igconv_kernels_f32_tapmajor.hip", "igconv_kernels_f32_nopad.hip",
            "igconv_kernels_f32_generic.hip", "igconv_kernels_f32_masked.hip", "igconv_kernels_f32_direct.hip", "igconv_kernels_f32_swap.hip", "igconv_kernels_bf16.hip",
-           "igconv_kernels_bf16_channels.hip", "igconv_kernels_wgrad.hip", "igconv_kernels_f64.hip", "igconv_kernels_f64_masked.hip", "igconv_kernels_wgrad_bf16c.hip", "igconv_kernels_bf16_pw.hip", "igconv_kernels_f32_teams.hip", "igconv_other.hip", "igconv_probe.hip", "igconv_noalloc.hip"]
+           "igconv_kernels_bf16_channels.hip", "igconv_kernels_wgrad.hip", "igconv_kernels_f64.hip", "igconv_kernels_f64_masked.hip", "igconv_kernels_wgrad_bf16c.hip", "igconv_kernels_bf16_pw.hip", "igconv_kernels_f32_teams.hip", "igconv_other.hip", "igconv_bias_grad.hip", "igconv_probe.hip", "igconv_noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops is switched off: hipcc must not form v_pk_*_f32 from float code.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -334,6 +334,36 @@ def run_add_tensor(b, shape, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     return out.result()
 
 
+def run_backward_bias(dy, alpha=1.0, beta=0.0, db_old=None, dtype=None, workspace="full", db_stride=1, asked=None):
+    """One igcConvolutionBackwardBias call; returns db (C values) as float64.  ``dtype``: "bf16" sends dy as bfloat16
+    (default: dy's own float32 / float64); ``workspace``: "full" (what the library asks for), "none", or a number of
+    bytes; ``db_stride``: element stride between db's feature maps; ``asked``: a list that receives the size asked for."""
+    if dtype is None:
+        dtype = "f64" if dy.dtype == np.float64 else "f32"
+    dev, strides = to_device_strided(dy, dtype)
+    dydesc = ig.TensorDescriptor().set(_dt(dtype), *dy.shape, strides)
+    C = dy.shape[1]
+    out_dtype = "f64" if dtype == "f64" else "f32"
+    out = GuardedOutput((1, C, 1, 1), (C * db_stride, db_stride, 1, 1), out_dtype)
+    if db_old is not None:
+        out.prefill(old=np.asarray(db_old).reshape(1, C, 1, 1))
+    else:
+        out.prefill(value=float("nan"))
+    dbdesc = ig.TensorDescriptor().set(_dt(out_dtype), 1, C, 1, 1, out.strides)
+    h = _handle()
+    want = ig.get_backward_bias_workspace_size(h, dydesc, dbdesc)
+    if asked is not None:
+        asked.append(want)
+    ws_bytes = want if workspace == "full" else (0 if workspace == "none" else int(workspace))
+    ws = GuardedOutput((1, 1, 1, max(ws_bytes // 8, 1)), (0, 0, 0, 1), "f64")
+    ws.prefill(value=float("nan"))
+    ig.check(ig.convolution_backward_bias(h, alpha, dydesc, dev.data_ptr(), beta, dbdesc, out.ptr, ws.ptr if ws_bytes else 0, ws_bytes),
+             "igcConvolutionBackwardBias")
+    res = out.result().reshape(C)
+    ws.result()   # (guard bands of the workspace)
+    return res
+
+
 def run_softmax_forward(mode, x, alpha=1.0, beta=0.0, y_old=None, layout="NCHW"):
     xd, xdesc = _desc_for(x)
     out, ydesc = _output(x.shape, layout, y_old, x)

@@ -220,3 +220,36 @@ def test_matrix_rate_probe():
     for bad in ((ig.IGC_DATA_FLOAT, 0, 0), (ig.IGC_DATA_FLOAT, 5000, 1), (ig.IGC_DATA_FLOAT, 10, 2), (17, 10, 0)):
         with pytest.raises(ig.IgcError):
             ig.measure_matrix_rate_operands(h, *bad)
+
+
+def test_backward_bias():
+    """db[c] = alpha * sum of dy over images and pixels + beta * db: every layout and input type, with the workspace the
+    library asks for, with none and with too little (then one range), a pitched db, repeatable bit for bit."""
+    gu = _gpu()
+    shapes = SHAPES + [(5, 70, 9, 11), (16, 64, 28, 28), (3, 200, 17, 5), (64, 3, 40, 41), (2, 1, 300, 300)]
+    for i, shape in enumerate(shapes):
+        dy = rnd(300 + i, *shape, lo=-1.0, hi=1.0)
+        want = po.bias_backward(dy)
+        old = rnd(320 + i, shape[1]).astype(np.float64)
+        for layout in ("NCHW", "NHWC"):
+            dyl = wl.with_layout(dy, layout)
+            print("backward bias", shape, layout, flush=True)
+            asked = []
+            got = gu.run_backward_bias(dyl, asked=asked)
+            close(got, want)
+            assert np.array_equal(got, gu.run_backward_bias(dyl))                          # the same bits again
+            close(gu.run_backward_bias(dyl, workspace="none"), want)
+            close(gu.run_backward_bias(dyl, workspace=max(asked[0] - 8, 0)), want)         # too little: not used
+            close(gu.run_backward_bias(dyl, -0.5, 2.0, old, db_stride=3), po.bias_backward(dy, -0.5, 2.0, old))
+            # bfloat16 gradients (the oracle consumes the rounded values)
+            dyb = wl.round_to_bf16(dy)
+            close(gu.run_backward_bias(wl.with_layout(dyb, layout), dtype="bf16"), po.bias_backward(dyb))
+    # a pitched, sliced gradient: every second feature map of a larger tensor
+    big = rnd(340, 4, 24, 9, 20, lo=-1.0, hi=1.0)
+    part = big[:, 3:19:2, :, 2:17]
+    close(gu.run_backward_bias(part), po.bias_backward(np.ascontiguousarray(part)))
+    # a single large element in a sea of zeros lands in its own feature map
+    z = np.zeros((3, 130, 7, 9), dtype=np.float32)
+    z[2, 129, 6, 8] = 7.0
+    got = gu.run_backward_bias(wl.with_layout(z, "NHWC"))
+    assert got[129] == 7.0 and np.count_nonzero(got) == 1

@@ -108,3 +108,22 @@ def test_mixed_types_are_rejected():
     assert ig.activation_forward(h, 1, 1.0, d32, x.data_ptr(), 0.0, d64, x.data_ptr()) == ig.IGC_STATUS_NOT_SUPPORTED
     assert ig.activation_forward(h, 1, 1.0, d64, x.data_ptr(), 0.0, d32, x.data_ptr()) == ig.IGC_STATUS_NOT_SUPPORTED
     assert ig.transform_tensor(h, 1.0, d64, x.data_ptr(), 0.0, d32, x.data_ptr()) == ig.IGC_STATUS_NOT_SUPPORTED
+
+
+def test_backward_bias_in_double_precision():
+    """The bias gradient with double tensors: double sums, double result, double alpha and beta."""
+    gu = _gpu()
+    for i, shape in enumerate([(2, 3, 5, 7), (5, 70, 9, 11), (8, 64, 28, 28), (3, 130, 17, 5)]):
+        dy = np.random.default_rng(500 + i).uniform(-1, 1, size=shape)
+        old = np.random.default_rng(520 + i).uniform(-1, 1, size=shape[1])
+        for layout in ("NCHW", "NHWC"):
+            dyl = wl.with_layout(dy, layout)
+            want = po.bias_backward(dy)
+            for ws in ("full", "none"):
+                got = gu.run_backward_bias(dyl, workspace=ws)
+                assert gu.rel_err(got, want) <= gu.BOUND["f64"]
+            got = gu.run_backward_bias(dyl, -0.5, 2.0, old, db_stride=2)
+            assert gu.rel_err(got, po.bias_backward(dy, -0.5, 2.0, old)) <= gu.BOUND["f64"]
+    # values a float could not hold
+    d = np.ones((1, 2, 1, 2)); d[0, 1, 0, 1] = 2.0 ** -40
+    assert gu.run_backward_bias(d)[1] == 1.0 + 2.0 ** -40

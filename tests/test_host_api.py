@@ -332,6 +332,36 @@ def test_other_functions_validate_before_any_gpu_call():
     assert pb(dxd=t(2, 3, 9, 11, st=(0, 99, 11, 1))) == ig.IGC_STATUS_BAD_PARAM
 
 
+def test_backward_bias_is_validated_and_planned_before_any_gpu_call():
+    """The bias gradient: the workspace it asks for (one double per range and feature map, none for small tensors) and
+    every rejection path, without a GPU."""
+    h = ig.Handle()
+    L = ig.lib()
+    one = ctypes.c_float(1.0)
+    fake = ctypes.c_void_p(256)
+    t = lambda n, c, hh, ww, dt=0, st=None: ig.TensorDescriptor().set(dt, n, c, hh, ww, st or (c * hh * ww, hh * ww, ww, 1))
+    dy, db = t(128, 64, 56, 56), t(1, 64, 1, 1)
+    big = ig.get_backward_bias_workspace_size(h, dy, db)
+    assert big > 0 and big % (64 * 8) == 0 and big <= 1024 * 64 * 8          # whole ranges of 64 doubles, at most 1024 of them
+    assert ig.get_backward_bias_workspace_size(h, t(2, 3, 5, 7), t(1, 3, 1, 1)) == 0
+    nhwc = t(128, 64, 56, 56, st=(56 * 56 * 64, 1, 56 * 64, 64))
+    assert ig.get_backward_bias_workspace_size(h, nhwc, db) > 0
+    ig.set_compute_units(h, 64)                                               # fewer compute units, fewer ranges
+    assert 0 < ig.get_backward_bias_workspace_size(h, dy, db) < big
+    call = lambda dyd=dy, dbd=db, dyp=fake, dbp=fake: L.igcConvolutionBackwardBias(
+        h.ptr, ctypes.byref(one), dyd.ptr, dyp, None, 0, ctypes.byref(one), dbd.ptr, dbp)
+    assert call(dyp=None) == ig.IGC_STATUS_BAD_PARAM and call(dbp=None) == ig.IGC_STATUS_BAD_PARAM
+    assert call(dbd=t(1, 63, 1, 1)) == ig.IGC_STATUS_BAD_PARAM               # feature maps differ
+    assert call(dbd=t(2, 64, 1, 1)) == ig.IGC_STATUS_BAD_PARAM               # not (1,C,1,1)
+    assert call(dbd=t(1, 64, 1, 1, st=(0, 0, 1, 1))) == ig.IGC_STATUS_BAD_PARAM     # feature maps would share an element
+    assert call(dbd=t(1, 64, 1, 1, dt=1)) == ig.IGC_STATUS_NOT_SUPPORTED     # a bfloat16 result
+    assert call(dbd=t(1, 64, 1, 1, dt=2)) == ig.IGC_STATUS_NOT_SUPPORTED     # float gradients, double result
+    assert call(dyd=ig.TensorDescriptor()) == ig.IGC_STATUS_NOT_INITIALIZED
+    assert call(dyp=ctypes.c_void_p(258)) == ig.IGC_STATUS_BAD_PARAM         # misaligned
+    with pytest.raises(ig.IgcError):
+        ig.get_backward_bias_workspace_size(h, dy, t(1, 65, 1, 1))
+
+
 def test_setters_reject_bad_values():
     L = ig.lib()
     t = ig.TensorDescriptor()
