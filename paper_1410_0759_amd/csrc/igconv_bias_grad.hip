@@ -124,6 +124,7 @@ __global__ __launch_bounds__(256) void bias_grad_packed_kernel(const BiasGradArg
 #pragma unroll 8
     for (uint32_t e = begin * (uint32_t)a.C + threadIdx.x * (uint32_t)V; e < e_end; e += 256u * V) {
         const u32x4_t q = __builtin_amdgcn_raw_buffer_load_b128(buf, e * (uint32_t)sizeof(T), 0, 0);
+        // (the four dwords by name: indexed with the variable of an unrolled loop they were compiled as four copies of the first)
         const uint32_t q0 = q.x, q1 = q.y, q2 = q.z, q3 = q.w;
         if constexpr (V == 4) {
             acc[0] += (double)__builtin_bit_cast(float, q0);
