@@ -22,6 +22,10 @@
 // computes the 64 offsets of a step, one pixel per lane, two steps ahead, into a small LDS
 // table; the loading threads fetch their 8 offsets with two 16-byte LDS reads.
 //
+// A workgroup has eight wavefronts: four movers (the 256 loading threads above, one 8 x 8 block each per operand
+// and step) and four multipliers that only read fragments and issue MFMAs; they meet at one barrier per step, the
+// movers filling the LDS stage the multipliers read next.
+//
 // One workgroup per (tile, reduction range).  With a workspace the results are stored in
 // the order the accumulators have them, [range][tap][row position][column position] padded
 // to whole tiles (32 lanes write 128 contiguous bytes), and igconv_sum_positions_kernel adds
@@ -49,7 +53,11 @@ constexpr uint32_t kWgcOutOfRange = 0x80000000u;
 template <int BM_, int BN_>
 struct WgradBf16cConfig {
     static constexpr int BM = BM_, BN = BN_, BK = kWgcBK;
-    static constexpr int THREADS = 256;
+    // Eight wavefronts: four that only read operand fragments from LDS and issue MFMAs, four that load, transpose and
+    // write the tiles of the steps ahead (as in igconv_kernel_bf16s.hpp).  A wavefront issues in order: with the loads,
+    // 32 permutes and LDS writes of a step in the same stream as its 16 MFMAs the MFMA pipe waited for them (the bf16
+    // workload: 54 -> 49 us, 306 -> 277 at a mini-batch of 256; every tile shape gained).
+    static constexpr int THREADS = 512;
     static constexpr int STAGE_BYTES = (BM + BN) * kWgcRowBytes;
     static constexpr int TABLE_BYTES = 2 * 4 * kWgcBK * 4;   // [slot][wavefront][pixel]: wavefronts 0, 1 hold dy's and x's offsets
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES + TABLE_BYTES;
@@ -60,15 +68,19 @@ struct WgradBf16cConfig {
 __device__ __forceinline__ uint32_t wgc_mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
 
 template <class Cfg>
-__global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKernelParams p) {
+__global__ __launch_bounds__(Cfg::THREADS) void igconv_wgrad_bf16c_kernel(const ConvKernelParams p) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
     constexpr int MB = BM / 64, NB = BN / 64;      // 32x32 blocks per wavefront (2 x 2 wavefronts)
     constexpr int RB = kWgcRowBytes;
     __shared__ __attribute__((aligned(16))) uint8_t lds[Cfg::LDS_BYTES];
     uint32_t *const table = reinterpret_cast<uint32_t *>(lds + 2 * Cfg::STAGE_BYTES);   // [2][4][64]
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    // wavefronts 0-3 multiply, 4-7 move; both kinds number themselves 0-3 (and the moving threads 0-255)
+    const bool mover = wave_all >= 4;
+    const int wave = wave_all & 3;
+    const int tid = (int)threadIdx.x & 255;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
@@ -156,44 +168,57 @@ __global__ __launch_bounds__(256) void igconv_wgrad_bf16c_kernel(const ConvKerne
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // ---- pipeline: global loads two steps ahead (their transposition into LDS, one step later, then
-    // never waits and can be spread between the MFMAs of the running step), offset table three steps ahead.
-    // Step s computes from LDS stage `cur`, moves the loaded data of step s+1 to the other stage and
-    // requests step s+2; past the range's end the table holds out-of-range offsets, so the extra step of
-    // an odd range and the look-ahead load zeros.
-    auto body = [&](int s, int cur, wg_u32x4 (&ld_new)[8], const wg_u32x4 (&ld_next)[8]) {
-        fetch(s + 2, ld_new);       // (table slot of step s)
-        fill_table(s + 3);          // (slot of step s+1: its offsets were fetched before the last barrier)
-        const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
-        const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            wg_bf16x8 av[MB], bv[NB];
-#pragma unroll
-            for (int i = 0; i < MB; ++i) av[i] = *reinterpret_cast<const wg_bf16x8 *>(a_base + i * 32 * RB + ks * 32);
-#pragma unroll
-            for (int j = 0; j < NB; ++j) bv[j] = *reinterpret_cast<const wg_bf16x8 *>(b_base + j * 32 * RB + ks * 32);
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int j = 0; j < NB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        stage(cur ^ 1, ld_next);
+    // ---- pipeline: global loads two steps ahead (their transposition into LDS, one step later, then never waits), offset
+    // table three steps ahead.  In step s the multipliers compute from LDS stage `cur` while the movers put the loaded
+    // data of step s+1 into the other stage and request step s+2; one barrier per step for all eight wavefronts.  Past
+    // the range's end the table holds out-of-range offsets, so the extra step of an odd range and the look-ahead load zeros.
+    if (mover) {
+        auto move = [&](int s, int cur, wg_u32x4 (&ld_new)[8], const wg_u32x4 (&ld_next)[8]) {
+            fetch(s + 2, ld_new);
+            fill_table(s + 3);
+            stage(cur ^ 1, ld_next);
+            __syncthreads();
+        };
+        fill_table(s_begin);
+        fill_table(s_begin + 1);
         __syncthreads();
-    };
-    fill_table(s_begin);
-    fill_table(s_begin + 1);
-    __syncthreads();
-    fetch(s_begin, ld0);
-    fetch(s_begin + 1, ld1);
-    __syncthreads();
-    fill_table(s_begin + 2);
-    stage(0, ld0);
-    __syncthreads();
-    for (int s = s_begin; s < s_end; s += 2) {
-        body(s, 0, ld0, ld1);
-        body(s + 1, 1, ld1, ld0);
+        fetch(s_begin, ld0);
+        fetch(s_begin + 1, ld1);
+        __syncthreads();
+        fill_table(s_begin + 2);
+        stage(0, ld0);
+        __syncthreads();
+        for (int s = s_begin; s < s_end; s += 2) {
+            move(s, 0, ld0, ld1);
+            move(s + 1, 1, ld1, ld0);
+        }
+        return;
+    } else {
+        auto multiply = [&](int cur) {
+            const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
+            const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                wg_bf16x8 av[MB], bv[NB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) av[i] = *reinterpret_cast<const wg_bf16x8 *>(a_base + i * 32 * RB + ks * 32);
+#pragma unroll
+                for (int j = 0; j < NB; ++j) bv[j] = *reinterpret_cast<const wg_bf16x8 *>(b_base + j * 32 * RB + ks * 32);
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+            }
+            __syncthreads();
+        };
+        __syncthreads();
+        __syncthreads();
+        __syncthreads();
+        for (int s = s_begin; s < s_end; s += 2) {
+            multiply(0);
+            multiply(1);
+        }
     }
 
     // ---- epilogue.  Workspace (ysN != 0): [tap][row position][column position], ysP x ysK positions per tap.

@@ -12,7 +12,7 @@ template <class Cfg>
 static int launch_wgc(const ConvKernelParams &p, int grid, void *stream) {
     ConvKernelParams args = p;
     void *argv[] = {&args};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_wgrad_bf16c_kernel<Cfg>), dim3(grid), dim3(256),
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_wgrad_bf16c_kernel<Cfg>), dim3(grid), dim3(Cfg::THREADS),
                                          argv, 0, static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
         std::fprintf(stderr, "igconv: launch of igconv_wgrad_bf16c_kernel failed: %s\n", hipGetErrorString(e));
@@ -84,10 +84,9 @@ int launch_sum_positions(const float *parts, float *out, uint32_t n, int count, 
 #define IGC_WGC_INSTANTIATE(NAME, BM, BN) \
     template __global__ void igconv_wgrad_bf16c_kernel<WgradBf16cConfig<BM, BN>>(const ConvKernelParams);
 IGC_WGC_LIST(IGC_WGC_INSTANTIATE)
-
 #if !defined(__HIP_DEVICE_COMPILE__)
 #define IGC_WGC_ROW(NAME, BM, BN) \
-    {NAME, true, BM, BN, kWgcBK, false, true, 10, 256, WgradBf16cConfig<BM, BN>::LDS_BYTES, &launch_wgc<WgradBf16cConfig<BM, BN>>},
+    {NAME, true, BM, BN, kWgcBK, false, true, 10, WgradBf16cConfig<BM, BN>::THREADS, WgradBf16cConfig<BM, BN>::LDS_BYTES, &launch_wgc<WgradBf16cConfig<BM, BN>>},
 static const KernelInfo kRows[] = {IGC_WGC_LIST(IGC_WGC_ROW)};
 const KernelGroup kGroupWgradBF16Channels = {kRows, sizeof(kRows) / sizeof(kRows[0])};
 #endif
