@@ -8,8 +8,7 @@
 // 8 channels per load, 8 neighbouring lanes reading 128 contiguous bytes of one row.
 // Tile BM x BN x 64 channels, 2 x 2 wavefronts, v_mfma_f32_32x32x16_bf16; LDS rows of
 // 64 channels + 16 bytes (an odd number of 16-byte units: conflict-free 16-byte accesses);
-// global loads two steps ahead in two register sets, a loop without branches, one barrier
-// per step.  Persistent workgroups whose loads run on across the tile boundary.  The epilogue is the shared one (alpha/beta, bias,
+// global loads two steps ahead in two register sets, one barrier per step; moving and multiplying wavefronts apart.  Persistent workgroups whose loads run on across the tile boundary.  The epilogue is the shared one (alpha/beta, bias,
 // activation, either orientation of the output).
 #ifndef IGCONV_KERNEL_BF16_PW_HPP_
 #define IGCONV_KERNEL_BF16_PW_HPP_
@@ -25,14 +24,16 @@ template <int BM_, int BN_, bool SWAP_>
 struct Bf16PwConfig {
     static constexpr int BM = BM_, BN = BN_, BK = kPwBK;
     static constexpr bool SWAP = SWAP_;
-    static constexpr int THREADS = 256;
+    // eight wavefronts: four that load the tiles of the steps ahead and write them to LDS, four that read fragments and
+    // issue MFMAs (and store the finished tile); one barrier per step
+    static constexpr int THREADS = 512;
     static constexpr int STAGE_BYTES = (BM + BN) * kPwRowBytes;
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
     static_assert(BM % 64 == 0 && BN % 64 == 0, "2 x 2 wavefronts of whole 32 x 32 blocks");
 };
 
 template <class Cfg>
-__global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKernelParams p) {
+__global__ __launch_bounds__(Cfg::THREADS) void igconv_fwd_bf16_pw_kernel(const ConvKernelParams p) {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
     constexpr int MB = BM / 64, NB = BN / 64;
     constexpr int RB = kPwRowBytes;
@@ -40,8 +41,10 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     __shared__ __attribute__((aligned(16))) uint8_t lds[Cfg::LDS_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const bool mover = wave_all >= 4;            // wavefronts 4-7 move, 0-3 multiply; both kinds number themselves 0-3
+    const int wave = wave_all & 3, tid = (int)threadIdx.x & 255;
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, half = lane >> 5;
 
@@ -104,12 +107,35 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
     f32x16 acc[MB][NB];
     const int steps = (p.ksteps + 1) & ~1;   // per tile, an even number: the step added to an odd count reads zeros
 
-    // step s multiplies LDS stage `cur`, moves the loaded data of step s+1 to the other stage and requests step s+2 -
-    // of this tile, or step s+2-steps of the next one
-    auto body = [&](int s, int cur, u32x4_t (&a_new)[NA], u32x4_t (&b_new)[NBV], const u32x4_t (&a_next)[NA],
-                    const u32x4_t (&b_next)[NBV]) __attribute__((always_inline)) {
-        if (s + 2 < steps) fetch_from(s + 2, a_off, b_off, a_new, b_new);
-        else fetch_from(s + 2 - steps, a_nxt, b_nxt, a_new, b_new);
+    // In step s the multipliers compute from LDS stage `cur` while the movers put the loaded data of step s+1 into the
+    // other stage and request step s+2 - of this tile, or step s+2-steps of the next one; one barrier per step.
+    if (mover) {
+        auto move = [&](int s, int cur, u32x4_t (&a_new)[NA], u32x4_t (&b_new)[NBV], const u32x4_t (&a_next)[NA],
+                        const u32x4_t (&b_next)[NBV]) __attribute__((always_inline)) {
+            if (s + 2 < steps) fetch_from(s + 2, a_off, b_off, a_new, b_new);
+            else fetch_from(s + 2 - steps, a_nxt, b_nxt, a_new, b_new);
+            stage(cur ^ 1, a_next, b_next);
+            __syncthreads();
+        };
+        tile_offsets(tile, a_off, b_off);
+        fetch_from(0, a_off, b_off, a0, b0);
+        fetch_from(1, a_off, b_off, a1, b1);
+        stage(0, a0, b0);
+        __syncthreads();
+        for (; tile < range_end; tile += p.wgsPerXcd) {
+            tile_offsets(tile + p.wgsPerXcd, a_nxt, b_nxt);
+            for (int s = 0; s < steps; s += 2) {
+                move(s, 0, a0, b0, a1, b1);
+                move(s + 1, 1, a1, b1, a0, b0);
+            }
+#pragma unroll
+            for (int i = 0; i < NA; ++i) a_off[i] = a_nxt[i];
+#pragma unroll
+            for (int i = 0; i < NBV; ++i) b_off[i] = b_nxt[i];
+        }
+        return;
+    }
+    auto multiply = [&](int cur) __attribute__((always_inline)) {
         const uint8_t *a_base = lds + cur * Cfg::STAGE_BYTES + (wm * (BM / 2) + l32) * RB + half * 16;
         const uint8_t *b_base = lds + cur * Cfg::STAGE_BYTES + (BM + wn * (BN / 2) + l32) * RB + half * 16;
 #pragma unroll
@@ -129,17 +155,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
                 }
         }
-        stage(cur ^ 1, a_next, b_next);
         __syncthreads();
     };
-    tile_offsets(tile, a_off, b_off);
-    fetch_from(0, a_off, b_off, a0, b0);
-    fetch_from(1, a_off, b_off, a1, b1);
-    stage(0, a0, b0);
     __syncthreads();
     for (; tile < range_end; tile += p.wgsPerXcd) {
         const int m0 = (tile % p.tilesM) * BM, n0 = (tile / p.tilesM) * BN;
-        tile_offsets(tile + p.wgsPerXcd, a_nxt, b_nxt);
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -149,15 +169,11 @@ __global__ __launch_bounds__(256) void igconv_fwd_bf16_pw_kernel(const ConvKerne
         float bias[MB];
         load_bias<MB>(p, m0 + wm * (BM / 2), l32, bias);
         for (int s = 0; s < steps; s += 2) {
-            body(s, 0, a0, b0, a1, b1);
-            body(s + 1, 1, a1, b1, a0, b0);
+            multiply(0);
+            multiply(1);
         }
-        // (LDS stage 0 and the registers now hold the next tile's first two steps)
+        // (the movers are already on the next tile's first steps)
         store_tile<Cfg::SWAP, MB, NB>(p, ybuf, acc, bias, m0 + wm * (BM / 2), n0 + wn * (BN / 2), half, l32);
-#pragma unroll
-        for (int i = 0; i < NA; ++i) a_off[i] = a_nxt[i];
-#pragma unroll
-        for (int i = 0; i < NBV; ++i) b_off[i] = b_nxt[i];
     }
 }
 

@@ -21,7 +21,7 @@ IGC_PW_LIST(IGC_PW_INSTANTIATE)
 
 #if !defined(__HIP_DEVICE_COMPILE__)
 #define IGC_PW_ROW(NAME, BM, BN, SWAP) \
-    {NAME, true, BM, BN, kPwBK, SWAP, true, 12, 256, Bf16PwConfig<BM, BN, SWAP>::LDS_BYTES, &launch_pw<Bf16PwConfig<BM, BN, SWAP>>},
+    {NAME, true, BM, BN, kPwBK, SWAP, true, 12, Bf16PwConfig<BM, BN, SWAP>::THREADS, Bf16PwConfig<BM, BN, SWAP>::LDS_BYTES, &launch_pw<Bf16PwConfig<BM, BN, SWAP>>},
 static const KernelInfo kRows[] = {IGC_PW_LIST(IGC_PW_ROW)};
 const KernelGroup kGroupBF16Pointwise = {kRows, sizeof(kRows) / sizeof(kRows[0])};
 #endif
