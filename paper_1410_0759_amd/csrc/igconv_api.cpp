@@ -793,7 +793,7 @@ static void backward_filter_split(const igcContext *h, const BackwardFilterProbl
                                   int *steps_per_split) {
     const long long cus = h->computeUnits;
     const KernelInfo *ki = kernel_info(b.kernel_id);
-    const long long per_cu = ki && !ki->f64 && ki->gmode != 10 ? workgroups_per_cu(*ki) : 2;
+    const long long per_cu = ki && ki->f64 ? 4 : (ki && ki->gmode != 10 ? workgroups_per_cu(*ki) : 2);
     long long want = std::max<long long>(1, (per_cu * cus) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));

@@ -11,7 +11,7 @@ template <bool WGRAD, int NB>
 static int launch_f64(const ConvKernelParams &p, int grid, void *stream) {
     ConvKernelParams args = p;
     void *argv[] = {&args};
-    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_f64_kernel<WGRAD, NB>), dim3(grid), dim3(256), argv, 0,
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(&igconv_f64_kernel<WGRAD, NB>), dim3(grid), dim3(kF64Threads), argv, 0,
                                          static_cast<hipStream_t>(stream));
     if (e != hipSuccess && std::getenv("IGCONV_DEBUG"))
         std::fprintf(stderr, "igconv: launch of igconv_f64_kernel failed: %s\n", hipGetErrorString(e));
@@ -64,7 +64,7 @@ int launch_sum_parts_f64(const double *parts, double *out, uint32_t n, int count
 
 #if !defined(__HIP_DEVICE_COMPILE__)
 static KernelInfo f64_row(const char *name, int nb, int gmode, int (*launch)(const ConvKernelParams &, int, void *)) {
-    KernelInfo k{name, false, 32 * nb, 32 * nb, kF64BK, false, false, gmode, 256, f64_lds_bytes(nb), launch};
+    KernelInfo k{name, false, 32 * nb, 32 * nb, kF64BK, false, false, gmode, kF64Threads, f64_lds_bytes(nb), launch};
     k.f64 = true;
     return k;
 }
