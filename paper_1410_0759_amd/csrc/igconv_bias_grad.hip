@@ -121,29 +121,40 @@ __global__ __launch_bounds__(256) void bias_grad_packed_kernel(const BiasGradArg
     double acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
-#pragma unroll 8
-    for (uint32_t e = begin * (uint32_t)a.C + threadIdx.x * (uint32_t)V; e < e_end; e += 256u * V) {
-        const u32x4_t q = __builtin_amdgcn_raw_buffer_load_b128(buf, e * (uint32_t)sizeof(T), 0, 0);
-        // (the four dwords by name: indexed with the variable of an unrolled loop they were compiled as four copies of the first)
-        const uint32_t q0 = q.x, q1 = q.y, q2 = q.z, q3 = q.w;
-        if constexpr (V == 4) {
-            acc[0] += (double)__builtin_bit_cast(float, q0);
-            acc[1] += (double)__builtin_bit_cast(float, q1);
-            acc[2] += (double)__builtin_bit_cast(float, q2);
-            acc[3] += (double)__builtin_bit_cast(float, q3);
-        } else if constexpr (V == 8) {
-            acc[0] += (double)__builtin_bit_cast(float, q0 << 16);
-            acc[1] += (double)__builtin_bit_cast(float, q0 & 0xFFFF0000u);
-            acc[2] += (double)__builtin_bit_cast(float, q1 << 16);
-            acc[3] += (double)__builtin_bit_cast(float, q1 & 0xFFFF0000u);
-            acc[4] += (double)__builtin_bit_cast(float, q2 << 16);
-            acc[5] += (double)__builtin_bit_cast(float, q2 & 0xFFFF0000u);
-            acc[6] += (double)__builtin_bit_cast(float, q3 << 16);
-            acc[7] += (double)__builtin_bit_cast(float, q3 & 0xFFFF0000u);
-        } else {
-            typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-            acc[0] += __builtin_bit_cast(double, u32x2_t{q0, q1});
-            acc[1] += __builtin_bit_cast(double, u32x2_t{q2, q3});
+    // Eight loads requested, then added in their order (left to itself the compiler asked for one load at a time and
+    // waited for it); a load past the end of the range has its offset out of range and brings zeros.
+    constexpr uint32_t STRIDE = 256u * V;
+    for (uint32_t e = begin * (uint32_t)a.C + threadIdx.x * (uint32_t)V; e < e_end; e += 8u * STRIDE) {
+        u32x4_t q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t ei = e + (uint32_t)i * STRIDE;
+            q[i] = __builtin_amdgcn_raw_buffer_load_b128(buf, ei < e_end ? ei * (uint32_t)sizeof(T) : 0x80000000u, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // (the four dwords by name: indexed with the variable of an unrolled loop they were compiled as four copies of the first)
+            const uint32_t q0 = q[i].x, q1 = q[i].y, q2 = q[i].z, q3 = q[i].w;
+            if constexpr (V == 4) {
+                acc[0] += (double)__builtin_bit_cast(float, q0);
+                acc[1] += (double)__builtin_bit_cast(float, q1);
+                acc[2] += (double)__builtin_bit_cast(float, q2);
+                acc[3] += (double)__builtin_bit_cast(float, q3);
+            } else if constexpr (V == 8) {
+                acc[0] += (double)__builtin_bit_cast(float, q0 << 16);
+                acc[1] += (double)__builtin_bit_cast(float, q0 & 0xFFFF0000u);
+                acc[2] += (double)__builtin_bit_cast(float, q1 << 16);
+                acc[3] += (double)__builtin_bit_cast(float, q1 & 0xFFFF0000u);
+                acc[4] += (double)__builtin_bit_cast(float, q2 << 16);
+                acc[5] += (double)__builtin_bit_cast(float, q2 & 0xFFFF0000u);
+                acc[6] += (double)__builtin_bit_cast(float, q3 << 16);
+                acc[7] += (double)__builtin_bit_cast(float, q3 & 0xFFFF0000u);
+            } else {
+                typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+                acc[0] += __builtin_bit_cast(double, u32x2_t{q0, q1});
+                acc[1] += __builtin_bit_cast(double, u32x2_t{q2, q3});
+            }
         }
     }
 #pragma unroll
