@@ -787,8 +787,9 @@ static bool packed_phases(const BackwardDataProblem &b, PackedPhases *out) {
 }
 
 // How to cut the reduction: as many ranges as keep all (tile, range) workgroups resident at
-// once (two per compute unit, four of the small fp32 tiles) - one more would leave a second, nearly empty round -, ranges
-// of an even number of steps and not shorter than 8; at most max_parts ranges.
+// once (two per compute unit, four of the small fp32 tiles and of the double-precision kernel) - one more would leave
+// a second, nearly empty round -, ranges of an even number of steps and not shorter than 8; at most max_parts ranges.
+// (Double precision: possibly finer, see below.)
 static void backward_filter_split(const igcContext *h, const BackwardFilterProblem &b, long long max_parts, int *splits,
                                   int *steps_per_split) {
     const long long cus = h->computeUnits;
@@ -797,6 +798,26 @@ static void backward_filter_split(const igcContext *h, const BackwardFilterProbl
     long long want = std::max<long long>(1, (per_cu * cus) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));
+    if (ki && ki->f64) {
+        // The double-precision kernel runs one workgroup per (tile, range), handed to the compute units as they come
+        // free.  With few ranges per tile the rounding above leaves compute units short of a workgroup (216 tiles:
+        // 4 ranges, 864 workgroups, three or four per compute unit - the ones with four set the time).  Finer ranges
+        // even that out: the busiest compute unit does ceil(tiles * ranges / compute units) workgroups of
+        // steps / ranges + 3 steps (start-up), and every range adds its pass of the ordered sum (about one step per
+        // 1.5 MB).  Measured on those 216 tiles: 4 ranges 412 us, 7 ranges 358, 13 ranges 355, 28 ranges 372.
+        const long long hi = std::min({4 * want, std::max<long long>(1, b.ksteps / 8), std::max<long long>(1, max_parts)});
+        const double sum_steps = (double)b.out_elems * 8.0 / 1.5e6;
+        double best = 0.0;
+        long long pick = want;
+        for (long long s = want; s <= hi; ++s) {
+            const double cost = (double)((b.tiles * s + cus - 1) / cus) * ((double)b.ksteps / (double)s + 3.0) + (double)s * sum_steps;
+            if (s == want || cost < best * 0.98) {   // (a finer cut must pay: it also takes more workspace)
+                best = cost;
+                pick = s;
+            }
+        }
+        want = pick;
+    }
     long long per = (b.ksteps + want - 1) / want;
     per += per & 1;
     *steps_per_split = (int)per;
