@@ -28,8 +28,8 @@
 // wavefront and the double-precision MFMAs of another do not overlap (the movers alone take half of the
 // multipliers' time, and the times add), so what is left is the movers' instruction count - about 60 vector
 // instructions per step and thread.  Stepping the decoded index by additions instead of decoding it with
-// integer multiplications was measured: no fewer instructions, no faster.  A 128 x 128 tile (one stream) was
-// measured and is slower.  LDS holds both operands k-major ([k][row]) so that the 16 lanes sharing a k read
+// integer multiplications was measured: no fewer instructions, no faster.  Tiles of 64 x 128 and 128 x 64 (two
+// workgroups per compute unit) were measured too: no faster.  LDS holds both operands k-major ([k][row]) so that the 16 lanes sharing a k read
 // 16 consecutive doubles.  One workgroup per (tile, reduction range).
 #ifndef IGCONV_KERNEL_F64_HPP_
 #define IGCONV_KERNEL_F64_HPP_
