@@ -489,7 +489,7 @@ unsigned int igcMagicDivide(unsigned int n, unsigned int mul, unsigned int shift
  * use igcConvolutionBackwardFilter with a workspace then.  All calls on one GPU share that
  * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race; calls
  * on one stream are ordered and safe.  Nothing is kept in the array between calls. */
-#define IGC_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define IGC_NOALLOC_SCRATCH_BYTES (64u << 20)
 igcStatus igcConvolutionBackwardFilterNoAlloc(igcHandle_t handle, const void *alpha,
                                               igcTensorDescriptor_t xDesc, const void *x,
                                               igcTensorDescriptor_t dyDesc, const void *dy,

@@ -390,7 +390,7 @@ def convolution_backward_filter(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, con
         _vp(workspace_ptr), workspace_bytes, ctypes.byref(b), dwdesc.ptr, _vp(dw_ptr))
 
 
-NOALLOC_SCRATCH_BYTES = 32 << 20   # IGC_NOALLOC_SCRATCH_BYTES of include/igconv.h
+NOALLOC_SCRATCH_BYTES = 64 << 20   # IGC_NOALLOC_SCRATCH_BYTES of include/igconv.h
 
 
 def convolution_backward_filter_no_alloc(handle, alpha, xdesc, x_ptr, dydesc, dy_ptr, conv, beta, dwdesc, dw_ptr):

@@ -805,7 +805,8 @@ static void backward_filter_split(const igcContext *h, const BackwardFilterProbl
         // even that out: the busiest compute unit does ceil(tiles * ranges / compute units) workgroups of
         // steps / ranges + 3 steps (start-up), and every range adds its pass of the ordered sum (about one step per
         // 1.5 MB).  Measured on those 216 tiles: 4 ranges 412 us, 7 ranges 358, 13 ranges 355, 28 ranges 372.
-        const long long hi = std::min({4 * want, std::max<long long>(1, b.ksteps / 8), std::max<long long>(1, max_parts)});
+        // (At most twice the ranges: 2048 workgroups of at most 32 KB, within the scratch array of the allocation-free entry point.)
+        const long long hi = std::min({2 * want, std::max<long long>(1, b.ksteps / 8), std::max<long long>(1, max_parts)});
         const double sum_steps = (double)b.out_elems * 8.0 / 1.5e6;
         double best = 0.0;
         long long pick = want;

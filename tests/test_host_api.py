@@ -457,7 +457,8 @@ def test_double_precision_is_planned_and_mixed_types_are_rejected():
 def test_backward_filter_workspace_fits_the_no_alloc_scratch_array():
     """igcConvolutionBackwardFilterNoAlloc serves a problem when the workspace its ordinary form asks for fits the
     library's scratch array.  The ranges of a cut reduction are chosen so that all (tile, range) workgroups are
-    resident at once - at most 512 tiles of at most 64 KB -, so the sizes stay within the array; checked here over
+    resident at once - at most 512 tiles of at most 64 KB; in double precision at most 2048 workgroups of 32 KB -, so the
+    sizes stay within the array; checked here over
     layer shapes small and large, all three data types."""
     h = ig.Handle()
     worst = 0

@@ -53,18 +53,22 @@ def test_no_alloc_backward_filter_matches_on_two_calls_in_a_row():
         (4, 24, 13, 11, 40, 3, 3, (1, 1), (1, 1), "f32", "NCHW"),
         (8, 64, 14, 14, 64, 3, 3, (1, 1), (1, 1), "bf16", "NHWC"),
         (8, 3, 23, 23, 16, 5, 5, (0, 0), (2, 2), "f32", "NCHW"),
+        (8, 130, 20, 20, 200, 3, 3, (1, 1), (1, 1), "f64", "NCHW"),   # (double: more ranges than resident workgroups)
+        (4, 24, 13, 11, 40, 3, 3, (1, 1), (1, 1), "f64", "NCHW"),
     ]
     for (N, C, H, W, K, R, S, pad, stride, dtype, lay) in cases:
         print("no-alloc backward filter", N, C, H, W, K, R, S, pad, stride, dtype, lay, flush=True)
-        x, _ = wl.random_problem(300 + N, N, C, H, W, K, R, S, x_layout=lay, dtype=dtype)
+        x, _ = wl.random_problem(300 + N, N, C, H, W, K, R, S, x_layout=lay, dtype="f32" if dtype == "f64" else dtype)
         P, Q = oc.output_dim(H, R, stride[0], pad[0]), oc.output_dim(W, S, stride[1], pad[1])
         dy = rng.uniform(-1, 1, size=(N, K, P, Q)).astype(np.float32)
         if dtype == "bf16":
             dy = wl.round_to_bf16(dy)
         dy = wl.with_layout(dy, lay)
         old = rng.uniform(-1, 1, size=(K, C, R, S)).astype(np.float32)
+        # (double precision: the same float-valued inputs as doubles)
+        as_dev = (lambda a: None if a is None else a.astype(np.float64)) if dtype == "f64" else (lambda a: a)
         for alpha, beta, dw_old in ((1.0, 0.0, None), (0.5, -2.0, old)):
-            ref, got = _both(gu, x, dy, (R, S), pad, stride, dtype, alpha, beta, dw_old)
+            ref, got = _both(gu, as_dev(x), as_dev(dy), (R, S), pad, stride, dtype, alpha, beta, as_dev(dw_old))
             assert np.array_equal(ref, got), "not bit for bit the ordinary entry point's result"
             want = oc.conv_backward_filter(x, dy, (R, S), pad=pad, stride=stride, mode=1, alpha=alpha, beta=beta, dw_old=dw_old)
             assert gu.rel_err(got, want) <= gu.BOUND[dtype]
