@@ -798,21 +798,27 @@ static void backward_filter_split(const igcContext *h, const BackwardFilterProbl
     long long want = std::max<long long>(1, (per_cu * cus) / b.tiles);
     want = std::min(want, std::max<long long>(1, b.ksteps / 8));
     want = std::min(want, std::max<long long>(1, max_parts));
-    if (ki && ki->f64) {
-        // The double-precision kernel runs one workgroup per (tile, range), handed to the compute units as they come
-        // free.  With few ranges per tile the rounding above leaves compute units short of a workgroup (216 tiles:
+    if (ki && (ki->f64 || ki->gmode == 10)) {
+        // These kernels run one workgroup per (tile, range), handed to the compute units as they come free.  With few
+        // ranges per tile the rounding above leaves compute units short of a workgroup (double precision, 216 tiles:
         // 4 ranges, 864 workgroups, three or four per compute unit - the ones with four set the time).  Finer ranges
         // even that out: the busiest compute unit does ceil(tiles * ranges / compute units) workgroups of
-        // steps / ranges + 3 steps (start-up), and every range adds its pass of the ordered sum (about one step per
-        // 1.5 MB).  Measured on those 216 tiles: 4 ranges 412 us, 7 ranges 358, 13 ranges 355, 28 ranges 372.
-        // (At most twice the ranges: 2048 workgroups of at most 32 KB, within the scratch array of the allocation-free entry point.)
-        const long long hi = std::min({2 * want, std::max<long long>(1, b.ksteps / 8), std::max<long long>(1, max_parts)});
-        const double sum_steps = (double)b.out_elems * 8.0 / 1.5e6;
-        double best = 0.0;
+        // steps / ranges + 3 steps (start-up), and every range adds its pass of the ordered sum (in steps: a part's
+        // bytes by 1.5 MB in double precision, by 1.9 MB for the bf16 channel-vector kernels).  Measured, double precision
+        // on those 216 tiles: 4 ranges 412 us, 7 ranges 358, 13 ranges 355, 28 ranges 372; bf16, 144 tiles, mini-batch
+        // 256: 3 ranges 271 us, 5 264, 7 256, 10 273 (mini-batch 32: 3 ranges 48 us, more are slower - as the model says).
+        // The workspace stays within the scratch array of the allocation-free entry point.
+        const double part_bytes = (double)b.part_elems() * (ki->f64 ? 8.0 : 4.0);
+        const long long by_bytes = (long long)((double)IGC_NOALLOC_SCRATCH_BYTES / part_bytes);
+        const long long hi = std::min({std::max(want, std::min(4 * want, by_bytes)), std::max<long long>(1, b.ksteps / 8),
+                                       std::max<long long>(1, max_parts)});
+        const double sum_steps = part_bytes / (ki->f64 ? 1.5e6 : 1.9e6);
+        double base = 0.0, best = 0.0;
         long long pick = want;
         for (long long s = want; s <= hi; ++s) {
             const double cost = (double)((b.tiles * s + cus - 1) / cus) * ((double)b.ksteps / (double)s + 3.0) + (double)s * sum_steps;
-            if (s == want || cost < best * 0.98) {   // (a finer cut must pay: it also takes more workspace)
+            if (s == want) base = best = cost;
+            if (cost < best && cost < base * 0.98) {   // (a finer cut must pay: it also takes more workspace)
                 best = cost;
                 pick = s;
             }
