@@ -280,10 +280,46 @@ __global__ __launch_bounds__(256) void igconv_filter_exchange_kernel(const uint1
     }
 }
 
+// The same for whole blocks (K and C multiples of 16) and 4-byte aligned buffers, moved as dwords: a run of 16 pairs
+// is 8 * taps dwords on both sides; an output dword takes its two halves from LDS.  Half as many memory
+// instructions as the element-wise form.
+template <int taps>
+__global__ __launch_bounds__(256) void igconv_filter_exchange_dwords_kernel(const uint32_t *w, uint32_t *wt, int K, int C) {
+    constexpr int ROW = 8 * taps, TOTAL = 16 * ROW, PER = (TOTAL + 255) / 256;
+    __shared__ uint32_t blk32[TOTAL];
+    const int k0 = blockIdx.x * 16, c0 = blockIdx.y * 16;
+    uint32_t v[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = (int)threadIdx.x + 256 * i;
+        const int k = e / ROW, d = e - k * ROW;
+        v[i] = e < TOTAL ? w[(((size_t)(k0 + k) * C + c0) * taps) / 2 + d] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = (int)threadIdx.x + 256 * i;
+        if (e < TOTAL) blk32[e] = v[i];
+    }
+    __syncthreads();
+    const uint16_t *blk = reinterpret_cast<const uint16_t *>(blk32);   // [k][c][t]
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = (int)threadIdx.x + 256 * i;
+        if (e >= TOTAL) break;
+        const int c = e / ROW, d = e - c * ROW;   // halves 2 d and 2 d + 1 of the run (k_local, t) of channel c
+        const int ka = (2 * d) / taps, ta = 2 * d - ka * taps, kb = (2 * d + 1) / taps, tb = 2 * d + 1 - kb * taps;
+        const uint32_t lo = blk[(ka * 16 + c) * taps + ta], hi = blk[(kb * 16 + c) * taps + tb];
+        wt[(((size_t)(c0 + c) * K + k0) * taps) / 2 + d] = lo | (hi << 16);
+    }
+}
+
 int launch_filter_exchange(const void *w, void *wt, int K, int C, int taps, void *stream) {
     void *argv[] = {&w, &wt, &K, &C};
-    const void *kernel = taps == 9 ? reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<9>)
-                                   : reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<1>);
+    const bool dwords = K % 16 == 0 && C % 16 == 0 && (uintptr_t)w % 4 == 0 && (uintptr_t)wt % 4 == 0;
+    const void *kernel = taps == 9 ? (dwords ? reinterpret_cast<const void *>(&igconv_filter_exchange_dwords_kernel<9>)
+                                             : reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<9>))
+                                   : (dwords ? reinterpret_cast<const void *>(&igconv_filter_exchange_dwords_kernel<1>)
+                                             : reinterpret_cast<const void *>(&igconv_filter_exchange_kernel<1>));
     return static_cast<int>(hipLaunchKernel(kernel,
                                             dim3((K + 15) / 16, (C + 15) / 16), dim3(256), argv, 0,
                                             static_cast<hipStream_t>(stream)));
