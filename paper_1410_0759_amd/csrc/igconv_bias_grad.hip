@@ -102,10 +102,10 @@ __global__ __launch_bounds__(256) void bias_grad_channels_kernel(const BiasGradA
     if (wave == 0 && c < a.C) finish<OUT>(a, c, range, ((sums[0][lane] + sums[1][lane]) + sums[2][lane]) + sums[3][lane]);
 }
 
-// dy packed with the channels innermost (N,H,W,C without gaps) and C a divisor of the elements a workgroup loads per
-// round (256 threads x 16 bytes): the tensor is one run of positions * C elements, a thread loads 16 bytes at a time
-// and meets the same V = 4 (bfloat16: 8) feature maps every round; the threads that share feature maps are added in
-// thread order at the end.
+// dy packed with the channels innermost (N,H,W,C without gaps), C a whole number of 16-byte vectors, at most 256 of
+// them: the tensor is one run of positions * C elements, a thread loads 16 bytes at a time; the first S threads work,
+// S the largest multiple of C / V up to 256, and advance by S vectors per round, so a thread meets the same V = 4
+// (bfloat16: 8) feature maps every round; the threads that share feature maps are added in thread order at the end.
 template <class T> struct Pack;
 template <> struct Pack<float> { static constexpr int V = 4; };
 template <> struct Pack<uint16_t> { static constexpr int V = 8; };
@@ -125,8 +125,9 @@ __global__ __launch_bounds__(256) void bias_grad_packed_kernel(const BiasGradArg
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
     // Eight loads requested, then added in their order (left to itself the compiler asked for one load at a time and
     // waited for it); a load past the end of the range has its offset out of range and brings zeros.
-    constexpr uint32_t STRIDE = 256u * V;
-    for (uint32_t e = begin * (uint32_t)a.C + threadIdx.x * (uint32_t)V; e < e_end; e += 8u * STRIDE) {
+    const uint32_t vectors = (uint32_t)a.C / (uint32_t)V, active = (256u / vectors) * vectors;
+    const uint32_t STRIDE = active * V;
+    for (uint32_t e = threadIdx.x < active ? begin * (uint32_t)a.C + threadIdx.x * (uint32_t)V : e_end; e < e_end; e += 8u * STRIDE) {
         u32x4_t q[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -162,11 +163,10 @@ __global__ __launch_bounds__(256) void bias_grad_packed_kernel(const BiasGradArg
 #pragma unroll
     for (int v = 0; v < V; ++v) sums[threadIdx.x][v] = acc[v];
     __syncthreads();
-    const int c = (int)threadIdx.x;
-    if (c < a.C) {   // (the host offers the kernel for C <= 256: a thread per feature map here)
+    for (int c = (int)threadIdx.x; c < a.C; c += 256) {
         const int first = c / V, step = a.C / V;   // threads first, first + step, ... hold feature map c at slot c % V
         double sum = 0.0;
-        for (int t = first; t < 256; t += step) sum += sums[t][c % V];
+        for (int t = first; t < (int)active; t += step) sum += sums[t][c % V];
         finish<OUT>(a, c, range, sum);
     }
 }
@@ -310,7 +310,7 @@ igcStatus plan_bias_grad(const igcContext *h, igcTensorDescriptor_t dyDesc, igcT
     a.dbStride = (uint32_t)dbDesc->stride[1];
     pl->channels = a.C > 1 && dyDesc->stride[1] == 1;
     const int per16 = 16 / elem_size(dyDesc->dtype);
-    pl->packed = pl->channels && a.C <= 256 && a.C % per16 == 0 && (256 * per16) % a.C == 0 && dyDesc->stride[3] == a.C &&
+    pl->packed = pl->channels && a.C % per16 == 0 && a.C / per16 <= 256 && dyDesc->stride[3] == a.C &&
                  dyDesc->stride[2] == (long long)a.W * a.C && dyDesc->stride[0] == (long long)a.HW * a.C;
     pl->vectors = !pl->channels && dyDesc->stride[3] == 1 && dyDesc->stride[2] == a.W && a.HW % per16 == 0 &&
                   dyDesc->stride[0] % per16 == 0 && dyDesc->stride[1] % per16 == 0;
