@@ -207,14 +207,16 @@ int launch_pack_phase_filter(const float *w, float *f, int K, int C, int R, int 
 }
 
 // dx[n,c,h,w] = alpha * y'[n,(a,b,c),i,j] + beta * dx[n,c,h,w] (y' packed N, u*v*C, I, J; rows i >= I or columns
-// j >= J belong to input rows no window reaches: zero).  A thread per element of dx, w fastest.
+// j >= J belong to input rows no window reaches: zero).  A thread per column w of four consecutive rows of dx (lanes
+// along w): the decode of (n, c, first row, w) and of the column's phase serves the four elements, and their four
+// loads are requested together.
 struct PhaseScatterArgs {
     const float *y;
     float *dx;
-    uint32_t total;          // N*C*H*W
-    int C, H, W, I, J, u, v, pad_h, pad_w;
+    uint32_t total;          // N*C*ceil(H/4)*W
+    int C, H, W, HB, I, J, u, v, pad_h, pad_w;
     uint32_t dxs[4];         // strides of dx in elements
-    Magic mW, mH, mC, mu, mv;
+    Magic mW, mHB, mC, mu, mv;
     float alpha, beta;
 };
 
@@ -224,29 +226,59 @@ __global__ __launch_bounds__(256) void igconv_phase_scatter_kernel(const PhaseSc
     auto mdiv = [](uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; };
     uint32_t rest = mdiv(idx, a.mW);
     const uint32_t w = idx - rest * (uint32_t)a.W;
-    uint32_t q = mdiv(rest, a.mH);
-    const uint32_t h = rest - q * (uint32_t)a.H;
+    uint32_t q = mdiv(rest, a.mHB);
+    const uint32_t h0 = (rest - q * (uint32_t)a.HB) * 4u;
     const uint32_t n = mdiv(q, a.mC), c = q - n * (uint32_t)a.C;
-    const uint32_t gh = h + (uint32_t)a.pad_h, gw = w + (uint32_t)a.pad_w;
-    const uint32_t i = mdiv(gh, a.mu), pa = gh - i * (uint32_t)a.u;
+    const uint32_t gw = w + (uint32_t)a.pad_w;
     const uint32_t j = mdiv(gw, a.mv), pb = gw - j * (uint32_t)a.v;
-    float val = 0.f;
-    if (i < (uint32_t)a.I && j < (uint32_t)a.J) {
-        const uint32_t m = (pa * (uint32_t)a.v + pb) * (uint32_t)a.C + c;
-        const uint32_t maps = (uint32_t)(a.u * a.v * a.C);
-        val = a.y[(((size_t)n * maps + m) * a.I + i) * a.J + j];
+    const uint32_t maps = (uint32_t)(a.u * a.v * a.C);
+    float val[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t gh = h0 + (uint32_t)e + (uint32_t)a.pad_h;
+        const uint32_t i = mdiv(gh, a.mu), pa = gh - i * (uint32_t)a.u;
+        val[e] = 0.f;
+        if (h0 + (uint32_t)e < (uint32_t)a.H && i < (uint32_t)a.I && j < (uint32_t)a.J) {
+            const uint32_t m = (pa * (uint32_t)a.v + pb) * (uint32_t)a.C + c;
+            val[e] = a.y[(((size_t)n * maps + m) * a.I + i) * a.J + j];
+        }
     }
-    float *dst = a.dx + (size_t)n * a.dxs[0] + (size_t)c * a.dxs[1] + (size_t)h * a.dxs[2] + (size_t)w * a.dxs[3];
-    float r = a.alpha * val;
-    if (a.beta != 0.f) r += a.beta * *dst;
-    *dst = r;
+    float *dst = a.dx + (size_t)n * a.dxs[0] + (size_t)c * a.dxs[1] + (size_t)h0 * a.dxs[2] + (size_t)w * a.dxs[3];
+    float old[4] = {0.f, 0.f, 0.f, 0.f};
+    if (a.beta != 0.f) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (h0 + (uint32_t)e < (uint32_t)a.H) old[e] = dst[(size_t)e * a.dxs[2]];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (h0 + (uint32_t)e >= (uint32_t)a.H) break;
+        float r = a.alpha * val[e];
+        if (a.beta != 0.f) r += a.beta * old[e];
+        dst[(size_t)e * a.dxs[2]] = r;
+    }
+}
+
+// (multiply-and-shift form of a division by d, 1 <= d < 2^31, as the kernels evaluate it)
+static Magic scatter_magic(uint32_t d) {
+    uint32_t shift = 0;
+    while ((1ull << shift) < d) ++shift;
+    const unsigned __int128 one = 1;
+    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;
+    Magic m;
+    m.mul = (uint32_t)(q - (one << 32));
+    m.shift = shift;
+    return m;
 }
 
 int launch_phase_scatter(const float *y, float *dx, int N, int C, int H, int W, int I, int J, int u, int v, int pad_h, int pad_w,
                          const long long dxs[4], Magic mW, Magic mH, Magic mC, Magic mu, Magic mv, float alpha, float beta,
                          void *stream) {
-    PhaseScatterArgs a{y, dx, (uint32_t)((size_t)N * C * H * W), C, H, W, I, J, u, v, pad_h, pad_w,
-                       {(uint32_t)dxs[0], (uint32_t)dxs[1], (uint32_t)dxs[2], (uint32_t)dxs[3]}, mW, mH, mC, mu, mv, alpha, beta};
+    (void)mH;
+    const int HB = (H + 3) / 4;
+    PhaseScatterArgs a{y, dx, (uint32_t)((size_t)N * C * HB * W), C, H, W, HB, I, J, u, v, pad_h, pad_w,
+                       {(uint32_t)dxs[0], (uint32_t)dxs[1], (uint32_t)dxs[2], (uint32_t)dxs[3]}, mW, scatter_magic((uint32_t)HB), mC, mu, mv,
+                       alpha, beta};
     void *argv[] = {&a};
     return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_phase_scatter_kernel),
                                             dim3((a.total + 255u) / 256u), dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
