@@ -86,8 +86,57 @@ __global__ __launch_bounds__(256) void igconv_sum_parts_kernel(const float *part
     out[e] = r;
 }
 
+// The same sums - the same additions in the same order, so the same bits - for at most 16 parts of whole 16-byte
+// vectors: a thread takes four consecutive elements and requests all its loads before it adds.  (With few parts the
+// kernel above leaves most of its threads without a load: 9 parts of 3.5 MB took 14.8 us.)
+__global__ __launch_bounds__(256) void igconv_sum_few_parts_kernel(const float4 *parts, float4 *out, uint32_t n4, int count,
+                                                                   uint32_t stride4, float alpha, float beta) {
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+    if (e >= n4) return;
+    float4 v[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+        if (s < count) v[s] = parts[(size_t)s * stride4 + e];
+    // runs of one part (count <= 8) or of two: eight runs, each added from zero, then the runs added in order
+    float4 sum = {0.f, 0.f, 0.f, 0.f};
+    auto add = [](float4 &a, const float4 &b) {
+        a.x += b.x;
+        a.y += b.y;
+        a.z += b.z;
+        a.w += b.w;
+    };
+    const bool pairs = count > 8;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (pairs) {
+            if (2 * g < count) add(acc, v[2 * g]);
+            if (2 * g + 1 < count) add(acc, v[2 * g + 1]);
+        } else {
+            if (g < count) add(acc, v[g]);
+        }
+        if (g == 0) sum = acc;
+        else add(sum, acc);
+    }
+    float4 r = {alpha * sum.x, alpha * sum.y, alpha * sum.z, alpha * sum.w};
+    if (beta != 0.f) {
+        const float4 o = out[e];
+        r.x += beta * o.x;
+        r.y += beta * o.y;
+        r.z += beta * o.z;
+        r.w += beta * o.w;
+    }
+    out[e] = r;
+}
+
 int launch_sum_parts(const float *parts, float *out, uint32_t n, int count, uint32_t stride, float alpha, float beta,
                      void *stream) {
+    if (count <= 16 && n % 4 == 0 && stride % 4 == 0 && (uintptr_t)parts % 16 == 0 && (uintptr_t)out % 16 == 0) {
+        uint32_t n4 = n / 4, stride4 = stride / 4;
+        void *argv4[] = {&parts, &out, &n4, &count, &stride4, &alpha, &beta};
+        return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_few_parts_kernel), dim3((n4 + 255u) / 256u),
+                                                dim3(256), argv4, 0, static_cast<hipStream_t>(stream)));
+    }
     void *argv[] = {&parts, &out, &n, &count, &stride, &alpha, &beta};
     return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_sum_parts_kernel), dim3((n + 31u) / 32u),
                                             dim3(256), argv, 0, static_cast<hipStream_t>(stream)));
