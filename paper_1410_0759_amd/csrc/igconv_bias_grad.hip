@@ -45,6 +45,7 @@ struct BiasGradArgs {
     int C, W;
     uint32_t HW, positions;       // H*W, N*H*W
     Magic mHW, mW;
+    uint32_t runs;                // 1 when a feature map is one run of H*W elements (w-stride 1, h-stride W)
     uint32_t HWv;                 // H*W in 16-byte vectors (feature maps stored as runs: the vector form below)
     Magic mHWv;
     uint32_t sN, sC, sH, sW;      // element strides of dy
@@ -182,8 +183,12 @@ __global__ __launch_bounds__(256) void bias_grad_map_kernel(const BiasGradArgs a
 #pragma unroll 8
     for (uint32_t i = begin + threadIdx.x; i < end; i += 256u) {
         const uint32_t n = mdiv(i, a.mHW), rem = i - n * a.HW;
-        const uint32_t h = mdiv(rem, a.mW), w = rem - h * (uint32_t)a.W;
-        sum += load_as_double<T>(buf, n * a.sN + (uint32_t)c * a.sC + h * a.sH + w * a.sW);
+        if (a.runs) {   // (one division per element)
+            sum += load_as_double<T>(buf, n * a.sN + (uint32_t)c * a.sC + rem);
+        } else {
+            const uint32_t h = mdiv(rem, a.mW), w = rem - h * (uint32_t)a.W;
+            sum += load_as_double<T>(buf, n * a.sN + (uint32_t)c * a.sC + h * a.sH + w * a.sW);
+        }
     }
     sums[threadIdx.x] = sum;
     __syncthreads();
@@ -312,6 +317,7 @@ igcStatus plan_bias_grad(const igcContext *h, igcTensorDescriptor_t dyDesc, igcT
     const int per16 = 16 / elem_size(dyDesc->dtype);
     pl->packed = pl->channels && a.C % per16 == 0 && a.C / per16 <= 256 && dyDesc->stride[3] == a.C &&
                  dyDesc->stride[2] == (long long)a.W * a.C && dyDesc->stride[0] == (long long)a.HW * a.C;
+    a.runs = dyDesc->stride[3] == 1 && dyDesc->stride[2] == a.W ? 1u : 0u;
     pl->vectors = !pl->channels && dyDesc->stride[3] == 1 && dyDesc->stride[2] == a.W && a.HW % per16 == 0 &&
                   dyDesc->stride[0] % per16 == 0 && dyDesc->stride[1] % per16 == 0;
     if (pl->vectors) {
