@@ -45,18 +45,6 @@ const KernelInfo *kernel_info(int id) {
     return nullptr;
 }
 
-static bool magic_for(uint32_t d, Magic *m) {
-    if (d < 1u || d >= (1u << 31)) return false;
-    uint32_t shift = 0;
-    while ((1ull << shift) < d) ++shift;  // ceil(log2 d)
-    const unsigned __int128 one = 1;
-    const unsigned __int128 num = one << (32 + shift);
-    const unsigned __int128 q = (num + d - 1) / d;  // ceil(2^(32+shift) / d), in [2^32, 2^33)
-    m->mul = (uint32_t)(q - (one << 32));
-    m->shift = shift;
-    return true;
-}
-
 // eq. 1: ceil((H - R + 1 + 2 pad) / u); <= 0 when there is no output.
 static long long out_dim(long long H, long long R, long long u, long long pad) {
     const long long num = H - R + 1 + 2 * pad;

@@ -27,16 +27,6 @@ namespace {
 constexpr long long kMaxBytesBias = 1ll << 31;
 constexpr int kMaxRanges = 1024;
 
-bool magic_of(uint32_t d, Magic *m) {
-    if (d < 1u || d >= (1u << 31)) return false;
-    uint32_t shift = 0;
-    while ((1ull << shift) < d) ++shift;
-    const unsigned __int128 one = 1;
-    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;
-    m->mul = (uint32_t)(q - (one << 32));
-    m->shift = shift;
-    return true;
-}
 __device__ __forceinline__ uint32_t mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
 
 struct BiasGradArgs {
@@ -310,7 +300,7 @@ igcStatus plan_bias_grad(const igcContext *h, igcTensorDescriptor_t dyDesc, igcT
     a.W = dyDesc->dim[3];
     a.HW = (uint32_t)(dyDesc->dim[2] * dyDesc->dim[3]);
     a.positions = (uint32_t)positions;
-    if (!magic_of(a.HW, &a.mHW) || !magic_of((uint32_t)a.W, &a.mW)) return IGC_STATUS_NOT_SUPPORTED;
+    if (!magic_for(a.HW, &a.mHW) || !magic_for((uint32_t)a.W, &a.mW)) return IGC_STATUS_NOT_SUPPORTED;
     a.sN = (uint32_t)dyDesc->stride[0]; a.sC = (uint32_t)dyDesc->stride[1]; a.sH = (uint32_t)dyDesc->stride[2]; a.sW = (uint32_t)dyDesc->stride[3];
     a.dbStride = (uint32_t)dbDesc->stride[1];
     pl->channels = a.C > 1 && dyDesc->stride[1] == 1;
@@ -322,7 +312,7 @@ igcStatus plan_bias_grad(const igcContext *h, igcTensorDescriptor_t dyDesc, igcT
                   dyDesc->stride[0] % per16 == 0 && dyDesc->stride[1] % per16 == 0;
     if (pl->vectors) {
         a.HWv = a.HW / (uint32_t)per16;
-        if (!magic_of(a.HWv, &a.mHWv)) return IGC_STATUS_NOT_SUPPORTED;
+        if (!magic_for(a.HWv, &a.mHWv)) return IGC_STATUS_NOT_SUPPORTED;
     }
     pl->f64 = f64;
     pl->in = dyDesc->dtype;

@@ -308,25 +308,15 @@ __global__ __launch_bounds__(256) void igconv_phase_scatter_kernel(const PhaseSc
     }
 }
 
-// (multiply-and-shift form of a division by d, 1 <= d < 2^31, as the kernels evaluate it)
-static Magic scatter_magic(uint32_t d) {
-    uint32_t shift = 0;
-    while ((1ull << shift) < d) ++shift;
-    const unsigned __int128 one = 1;
-    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;
-    Magic m;
-    m.mul = (uint32_t)(q - (one << 32));
-    m.shift = shift;
-    return m;
-}
-
 int launch_phase_scatter(const float *y, float *dx, int N, int C, int H, int W, int I, int J, int u, int v, int pad_h, int pad_w,
                          const long long dxs[4], Magic mW, Magic mH, Magic mC, Magic mu, Magic mv, float alpha, float beta,
                          void *stream) {
     (void)mH;
     const int HB = (H + 3) / 4;
+    Magic mHB;
+    if (!magic_for((uint32_t)HB, &mHB)) return 1;
     PhaseScatterArgs a{y, dx, (uint32_t)((size_t)N * C * HB * W), C, H, W, HB, I, J, u, v, pad_h, pad_w,
-                       {(uint32_t)dxs[0], (uint32_t)dxs[1], (uint32_t)dxs[2], (uint32_t)dxs[3]}, mW, scatter_magic((uint32_t)HB), mC, mu, mv,
+                       {(uint32_t)dxs[0], (uint32_t)dxs[1], (uint32_t)dxs[2], (uint32_t)dxs[3]}, mW, mHB, mC, mu, mv,
                        alpha, beta};
     void *argv[] = {&a};
     return static_cast<int>(hipLaunchKernel(reinterpret_cast<const void *>(&igconv_phase_scatter_kernel),

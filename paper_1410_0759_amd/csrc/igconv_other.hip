@@ -27,17 +27,6 @@ namespace {
 
 constexpr long long kMaxBytesOther = 1ll << 31;
 
-bool magic_of(uint32_t d, Magic *m) {
-    if (d < 1u || d >= (1u << 31)) return false;
-    uint32_t shift = 0;
-    while ((1ull << shift) < d) ++shift;
-    const unsigned __int128 one = 1;
-    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;
-    m->mul = (uint32_t)(q - (one << 32));
-    m->shift = shift;
-    return true;
-}
-
 __device__ __forceinline__ uint32_t mdiv(uint32_t n, Magic m) { return (__umulhi(n, m.mul) + n) >> m.shift; }
 
 // Up to four dimensions, outermost first, with the element strides of up to four tensors
@@ -80,7 +69,7 @@ View make_view(const int dim[4], const long long (*stride)[4], int tensors, bool
         v.rank = 1;
         v.dim[0] = 1;
     }
-    for (int i = 0; i < v.rank; ++i) magic_of(v.dim[i], &v.mdim[i]);
+    for (int i = 0; i < v.rank; ++i) magic_for(v.dim[i], &v.mdim[i]);
     return v;
 }
 

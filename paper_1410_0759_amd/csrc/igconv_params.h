@@ -15,6 +15,18 @@ struct Magic {
     uint32_t shift;
 };
 
+// (mul, shift) for a divisor 1 <= d < 2^31; false outside that range.  Host code.
+inline bool magic_for(uint32_t d, Magic *m) {
+    if (d < 1u || d >= (1u << 31)) return false;
+    uint32_t shift = 0;
+    while ((1ull << shift) < d) ++shift;  // ceil(log2 d)
+    const unsigned __int128 one = 1;
+    const unsigned __int128 q = ((one << (32 + shift)) + d - 1) / d;  // ceil(2^(32+shift) / d), in [2^32, 2^33)
+    m->mul = (uint32_t)(q - (one << 32));
+    m->shift = shift;
+    return true;
+}
+
 // The kernels that feed the MFMAs straight from global memory (igconv_kernel_f32d.hpp): entries of their LDS table of
 // tap offsets (one per reduction index), and how many steps ahead their requests run (as many register sets).
 constexpr int kDirectTableEntries = 16384;
